@@ -1,0 +1,180 @@
+/* adapt_fxp.h - C ABI of the MI355X (gfx950) implementation of AdaPT's fixed-point hot path
+ * (Kummer et al., "Adaptive Precision Training (AdaPT)", arXiv 2107.13490).
+ *
+ * The calls follow the paper's own operations:
+ *   Quantize(L, <WL,FL>)             Alg. 1 (last loop), Alg. 3; format of Sec. 2.1 "Fixed-Point
+ *                                    Quantization", rounding rule SR of Sec. 3.2
+ *   ForwardPass / backward pass      Alg. 1, on quantized layers: integer GEMM and
+ *                                    convolution forward / data-gradient / weight-gradient
+ *   PushDown(L, WL, FL)              Sec. 3.3 "The PushDown Operation", Alg. 3: KL divergence
+ *                                    between the binned distributions of a tensor and of its
+ *                                    quantization, over candidate word lengths
+ *
+ * General rules (every entry point)
+ *   - Every tensor pointer and every result pointer is DEVICE memory owned by the caller,
+ *     16-byte aligned unless stated otherwise.  The library never frees or keeps caller
+ *     memory.  Its only allocations are the context and the context's workspace.
+ *   - All work is enqueued on the context's HIP stream and the call returns without
+ *     synchronising.  Results are valid in stream order.  Two calls on one context must not
+ *     overlap on different streams (they share the workspace).
+ *   - Return value: ADAPT_OK (0) or a negative adapt_status.  Nothing is printed, no
+ *     exceptions cross the boundary.  On error no kernel of that call has been launched.
+ *   - Storage of a tensor in format <wl,fl>: int8_t for wl <= 8 (sign-extended codes),
+ *     int16_t for 9 <= wl <= 16.  The represented value of code q is q * 2^-fl.
+ *   - Layouts: activations NHWC, filters KRSC (Cout, R, S, Cin), row-major, dense.
+ */
+#ifndef ADAPT_FXP_H
+#define ADAPT_FXP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ADAPT_OK = 0,
+    ADAPT_EINVAL = -1,       /* null / misaligned pointer, size, WL, FL, bins or range out of bounds */
+    ADAPT_EUNSUPPORTED = -2, /* valid request this build does not implement (WL > 16, dilation, groups) */
+    ADAPT_EBOUND = -3,       /* exact result does not fit the requested accumulator / output type */
+    ADAPT_EHIP = -4,         /* HIP runtime failure (see adapt_error_string / hipGetLastError) */
+    ADAPT_EWORKSPACE = -5    /* context workspace too small for this call */
+} adapt_status;
+
+typedef struct adapt_ctx adapt_ctx; /* opaque: stream, device, workspace */
+
+/* Fixed-point format <WL,FL> (Sec. 2.1, Sec. 3.2): signed, wl total bits, fl fractional bits.
+ * 2 <= wl <= 16, 0 <= fl <= 31 (fl need not be smaller than wl). */
+typedef struct { int wl, fl; } adapt_fmt;
+
+/* Rounding.  ADAPT_SR is the paper's stochastic rounding (Sec. 3.2): round down, or up with
+ * probability equal to the fractional distance, decided by 16 random bits per element.
+ * ADAPT_RN_HALF_UP (round to nearest, ties up) exists for deterministic tests.
+ * Random bits are counter based: element i of a tensor uses 16-bit lane (i mod 8), low half
+ * first, of the Philox-4x32-10 block with key (seed lo, seed hi) and counter
+ * (i/8 lo, i/8 hi, stream lo, stream hi).  The same (seed, stream) reproduces the same bits. */
+typedef enum { ADAPT_RN_HALF_UP = 0, ADAPT_SR = 1 } adapt_round;
+typedef struct { int mode; uint64_t seed, stream; } adapt_rng;
+
+/* Convolution geometry: input n x h x w x c, filters k x r x s x c, output n x p x q x k with
+ * p = (h + 2 pad - r)/stride + 1, q likewise.  Cross-correlation (no filter flip), zero
+ * padding, dilation 1, groups 1, stride >= 1. */
+typedef struct { int n, h, w, c, k, r, s, stride, pad; } adapt_conv_desc;
+
+/* What a contraction writes.
+ *  raw != 0 : the exact integer accumulator, int32_t if adapt_acc_bits(...) == 32 else int64_t.
+ *  raw == 0 : the accumulator converted to `fmt` (storage as for any tensor of that format):
+ *             with s = fl_a + fl_b - fmt.fl,
+ *               s <= 0      q = acc * 2^-s
+ *               1..16       q = (acc + (R16 >> (16-s))) >> s      (R16 = 2^15 for RN_HALF_UP)
+ *               s > 16      q = ((acc >> (s-16)) + R16) >> 16
+ *             then q = max(q,0) if relu, then saturation to fmt.wl bits.  R16 of output element
+ *             i (row-major index in the output tensor) comes from `rng` as described above. */
+typedef struct { int raw; adapt_fmt fmt; adapt_rng rng; int relu; } adapt_epilogue;
+
+/* ---- context ------------------------------------------------------------------------------ */
+
+/* Creates a context on the current HIP device.  `hip_stream` is a hipStream_t (NULL = the
+ * default stream).  `workspace_bytes` = 0 selects the default (64 MiB).  The workspace holds
+ * histograms, split-K partial sums and re-laid-out filters; ADAPT_EWORKSPACE is returned by
+ * a call that needs more.  Host pointers in, host pointer out. */
+int adapt_create(adapt_ctx **ctx, void *hip_stream, size_t workspace_bytes);
+int adapt_destroy(adapt_ctx *ctx);
+int adapt_set_stream(adapt_ctx *ctx, void *hip_stream);
+const char *adapt_error_string(int status);
+/* Library / ABI version (incremented on incompatible changes). */
+int adapt_version(void);
+
+/* ---- Quantize (Alg. 1 last loop; Sec. 3.2 SR; Sec. 2.1 format) ------------------------------ */
+
+/* q[i] = quantize(x[i]) for i < n:  y = x * 2^fl, saturated to [-2^(wl-1), 2^(wl-1)-1],
+ * t = floor(y * 2^16), q = min((t + R16) >> 16, 2^(wl-1)-1).  NaN gives 0, +-Inf saturate,
+ * denormals are not flushed.
+ *   x          device, fp32[n]
+ *   q          device, int8_t[n] (wl <= 8) or int16_t[n]
+ *   nnz        device uint64_t, may be NULL: number of non-zero codes (the paper's sp^l is
+ *              nnz / n, Sec. 3.4 "Inducing Sparsity")
+ *   saturated  device uint64_t, may be NULL: number of elements with x*2^fl outside the range
+ * n = 0 is valid (counters are set to 0). */
+int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng,
+                   void *q, uint64_t *nnz, uint64_t *saturated);
+
+/* One launch for a whole network (the per-layer loop of Alg. 1).  `items` is a HOST array of
+ * `count` descriptors (read before the call returns; the pointers inside are device
+ * pointers); each tensor is quantized exactly as by adapt_quantize with the item's own format
+ * and rng stream (mode and seed are shared).  nnz / saturated of item t are written to
+ * counters[2t], counters[2t+1] (device, uint64_t[2*count], may be NULL).  Descriptors travel
+ * as kernel arguments, 64 per launch. */
+typedef struct {
+    const float *x; void *q; uint64_t n; int32_t wl, fl; uint64_t stream;
+} adapt_quantize_item;
+int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item *items, int count,
+                           int mode, uint64_t seed, uint64_t *counters);
+
+/* ---- integer contractions (ForwardPass / backward pass of Alg. 1 on quantized tensors) ---- */
+
+/* 32 if K * 2^(wl_a-1) * 2^(wl_b-1) <= 2^31 - 1 (every possible sum fits int32), else 64. */
+int adapt_acc_bits(int64_t K, adapt_fmt a, adapt_fmt b);
+
+/* C[M,N] = op(A)[M,K] . op(B)[K,N], exact over the integers.  Row-major with leading
+ * dimensions in elements.  transA = 0: A is M x K (lda >= K); 1: A is stored K x M (lda >= M).
+ * transB likewise for B (K x N, ldb >= N; or N x K, ldb >= K).  C is M x N, ldc >= N,
+ * element type per `ep`.  The result has fa.fl + fb.fl fractional bits. */
+int adapt_fxp_gemm(adapt_ctx *ctx, int transA, int transB, int M, int N, int K,
+                   const void *A, adapt_fmt fa, int lda, const void *B, adapt_fmt fb, int ldb,
+                   void *C, int ldc, adapt_epilogue ep);
+
+/* y[n,p,q,k]  = sum_{r,s,c} x[n, p*stride+r-pad, q*stride+s-pad, c] * w[k,r,s,c] */
+int adapt_conv_fwd(adapt_ctx *ctx, adapt_conv_desc d, const void *x, adapt_fmt fx,
+                   const void *w, adapt_fmt fw, void *y, adapt_epilogue ep);
+/* dx[n,h,w,c] = sum over (k,r,s) and the (p,q) with h = p*stride+r-pad, w = q*stride+s-pad of
+ *               dy[n,p,q,k] * w[k,r,s,c] */
+int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy,
+                     const void *w, adapt_fmt fw, void *dx, adapt_epilogue ep);
+/* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride+r-pad, q*stride+s-pad, c] */
+int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy,
+                     const void *x, adapt_fmt fx, void *dw, adapt_epilogue ep);
+
+/* ---- PushDown: KL-divergence precision search (Sec. 3.3, Alg. 3) --------------------------- */
+
+/* For every candidate word length WL_c = wl_lo..wl_hi with FL_c = WL_c - il (il = integer bits
+ * including the sign, kept fixed so that lowering WL only drops fractional bits):
+ *   Q   = histogram of the finite elements of w on a grid of power-of-two bins: width 2^e,
+ *         edges at multiples of 2^e, e the smallest integer for which the range [min w, max w]
+ *         spans nb <= bins bins;
+ *   P_c = histogram of quantize(w, <WL_c,FL_c>) on the same bins (values outside go to the end
+ *         bins); every candidate uses the same random bits R16(seed, stream, i);
+ *   KL_c = sum_b P_c(b) log2(P_c(b) / Q(b)),  P_c(b) = (count + alpha)/(n_finite + alpha nb),
+ *         Q likewise.  alpha < 0 selects the default 1/nb; alpha = 0 is the unsmoothed
+ *         definition (0 log 0 = 0, +inf where P > 0 = Q).
+ * Selection: the smallest WL_c with KL_c < eps, wl_hi if there is none.
+ * If w has no finite element or min == max: every KL_c = 0 and wl_lo is selected.
+ *   w        device fp32[n]
+ *   kld      device double[wl_hi - wl_lo + 1]
+ *   sel      device int32_t[2]: selected WL, FL
+ *   hist     device uint32_t[(wl_hi - wl_lo + 2) * bins] or NULL: row 0 = counts of Q, row
+ *            1 + c = counts of P_c; entries nb..bins-1 of every row are zero
+ *   grid     device int64_t[3] or NULL: e, floor(min w / 2^e), nb  (0,0,0 in the degenerate case)
+ * Limits: 2 <= wl_lo <= wl_hi <= 16, 1 <= il, wl_lo - il >= 0, wl_hi - il <= 31,
+ * 2 <= bins <= 65536. */
+int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t n, int wl_lo, int wl_hi,
+                               int il, int bins, double eps, double alpha, adapt_rng rng,
+                               double *kld, int32_t *sel, uint32_t *hist, int64_t *grid);
+
+/* One call for all layers of a network (the loop of Alg. 2 over l in L): the same search on
+ * `count` tensors described by a HOST array (read before the call returns; `w` inside is a
+ * device pointer); tensor t writes kld[t*ncand ...] and
+ * sel[2t], sel[2t+1], with ncand = wl_hi - wl_lo + 1.  il, bins and the rng stream are per
+ * tensor; candidate range, eps, alpha, mode and seed are shared. */
+typedef struct {
+    const float *w; uint64_t n; int32_t il, bins; uint64_t stream;
+} adapt_kld_item;
+int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kld_item *items, int count,
+                                       int wl_lo, int wl_hi, double eps, double alpha, int mode,
+                                       uint64_t seed, double *kld, int32_t *sel);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAPT_FXP_H */

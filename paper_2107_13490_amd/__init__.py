@@ -1,0 +1,10 @@
+"""MI355X-native fixed-point hot path of AdaPT (arXiv 2107.13490).
+
+Thin ctypes binding over the C ABI declared in include/adapt_fxp.h.  Every step of the path
+runs in the HIP library (paper_2107_13490_amd/libadapt_fxp.so); PyTorch only provides device
+memory and streams.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+from .binding import (  # noqa: F401
+    RN_HALF_UP, SR, AdaptError, Context, ConvDesc, Epilogue, Fmt, Rng, acc_bits, library_path,
+    load_library,
+)

@@ -1,0 +1,251 @@
+"""ctypes binding of include/adapt_fxp.h: argument marshalling only.
+
+Tensors are torch CUDA (HIP) tensors; the binding passes their data pointers and the current
+torch stream to the library.  Names mirror the C entry points.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+RN_HALF_UP = 0
+SR = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libadapt_fxp.so")
+_lib = None
+
+
+class AdaptError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().adapt_error_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class Fmt(C.Structure):
+    _fields_ = [("wl", C.c_int), ("fl", C.c_int)]
+
+
+class Rng(C.Structure):
+    _fields_ = [("mode", C.c_int), ("seed", C.c_uint64), ("stream", C.c_uint64)]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(f, C.c_int) for f in ("n", "h", "w", "c", "k", "r", "s", "stride", "pad")]
+
+    @property
+    def p(self):
+        return (self.h + 2 * self.pad - self.r) // self.stride + 1
+
+    @property
+    def q(self):
+        return (self.w + 2 * self.pad - self.s) // self.stride + 1
+
+
+class Epilogue(C.Structure):
+    _fields_ = [("raw", C.c_int), ("fmt", Fmt), ("rng", Rng), ("relu", C.c_int)]
+
+    @staticmethod
+    def exact():
+        return Epilogue(1, Fmt(8, 0), Rng(RN_HALF_UP, 0, 0), 0)
+
+    @staticmethod
+    def requant(wl, fl, mode=SR, seed=0, stream=0, relu=False):
+        return Epilogue(0, Fmt(wl, fl), Rng(mode, seed, stream), int(relu))
+
+
+class QuantizeItem(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("q", C.c_void_p), ("n", C.c_uint64), ("wl", C.c_int32),
+                ("fl", C.c_int32), ("stream", C.c_uint64)]
+
+
+class KldItem(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("n", C.c_uint64), ("il", C.c_int32), ("bins", C.c_int32),
+                ("stream", C.c_uint64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Opens the HIP library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, sz, i, u64, i64, dbl = C.c_void_p, C.c_size_t, C.c_int, C.c_uint64, C.c_int64, C.c_double
+    lib.adapt_error_string.restype = C.c_char_p
+    lib.adapt_error_string.argtypes = [i]
+    lib.adapt_version.restype = i
+    lib.adapt_create.argtypes = [C.POINTER(vp), vp, sz]
+    lib.adapt_destroy.argtypes = [vp]
+    lib.adapt_set_stream.argtypes = [vp, vp]
+    lib.adapt_acc_bits.argtypes = [i64, Fmt, Fmt]
+    lib.adapt_quantize.argtypes = [vp, vp, sz, Fmt, Rng, vp, vp, vp]
+    lib.adapt_quantize_batched.argtypes = [vp, C.POINTER(QuantizeItem), i, i, u64, vp]
+    lib.adapt_fxp_gemm.argtypes = [vp, i, i, i, i, i, vp, Fmt, i, vp, Fmt, i, vp, i, Epilogue]
+    for f in (lib.adapt_conv_fwd, lib.adapt_conv_dgrad, lib.adapt_conv_wgrad):
+        f.argtypes = [vp, ConvDesc, vp, Fmt, vp, Fmt, vp, Epilogue]
+    lib.adapt_kld_precision_search.argtypes = [vp, vp, sz, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
+    lib.adapt_kld_precision_search_batched.argtypes = [vp, C.POINTER(KldItem), i, i, i, dbl, dbl, i, u64, vp, vp]
+    _lib = lib
+    return lib
+
+
+def acc_bits(k: int, fa: Fmt, fb: Fmt) -> int:
+    return load_library().adapt_acc_bits(k, fa, fb)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise AdaptError(status, where)
+
+
+class Context:
+    """Owns an adapt_ctx bound to the current torch device and stream."""
+
+    def __init__(self, workspace_bytes: int = 0, stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("paper_2107_13490_amd needs a HIP device; there is no CPU path")
+        self._lib = load_library()
+        self._torch = torch
+        s = stream if stream is not None else torch.cuda.current_stream()
+        self._stream = s
+        h = C.c_void_p()
+        _check(self._lib.adapt_create(C.byref(h), C.c_void_p(s.cuda_stream), workspace_bytes), "adapt_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.adapt_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    @staticmethod
+    def storage_dtype(wl: int):
+        import torch
+        return torch.int8 if wl <= 8 else torch.int16
+
+    # -- quantize -----------------------------------------------------------------------------
+    def quantize(self, x, wl, fl, mode=SR, seed=0, stream=0, out=None, counters=None):
+        """x: fp32 device tensor.  Returns (q, counters) with counters = uint64-as-int64[2] on the
+        device holding nnz and saturated."""
+        torch = self._torch
+        if out is None:
+            out = torch.empty(x.shape, dtype=self.storage_dtype(wl), device=x.device)
+        if counters is None:
+            counters = torch.empty(2, dtype=torch.int64, device=x.device)
+        _check(self._lib.adapt_quantize(self._h, _ptr(x), x.numel(), Fmt(wl, fl), Rng(mode, seed, stream), _ptr(out),
+                                        C.c_void_p(counters.data_ptr()), C.c_void_p(counters.data_ptr() + 8)),
+               "adapt_quantize")
+        return out, counters
+
+    def quantize_batched(self, xs, fmts, streams, mode=SR, seed=0, outs=None, counters=None):
+        torch = self._torch
+        n = len(xs)
+        if outs is None:
+            outs = [torch.empty(x.shape, dtype=self.storage_dtype(f[0]), device=x.device) for x, f in zip(xs, fmts)]
+        if counters is None:
+            counters = torch.empty(2 * max(n, 1), dtype=torch.int64, device=xs[0].device if n else "cuda")
+        items = (QuantizeItem * max(n, 1))()
+        for t in range(n):
+            items[t] = QuantizeItem(xs[t].data_ptr(), outs[t].data_ptr(), xs[t].numel(), fmts[t][0], fmts[t][1],
+                                    streams[t])
+        _check(self._lib.adapt_quantize_batched(self._h, items, n, mode, seed, _ptr(counters)),
+               "adapt_quantize_batched")
+        return outs, counters
+
+    # -- contractions -------------------------------------------------------------------------
+    def _out_dtype(self, k_total, fa, fb, ep):
+        torch = self._torch
+        if ep.raw:
+            return torch.int32 if self._lib.adapt_acc_bits(k_total, fa, fb) == 32 else torch.int64
+        return self.storage_dtype(ep.fmt.wl)
+
+    def fxp_gemm(self, a, fa, b, fb, ep, trans_a=False, trans_b=False, out=None):
+        torch = self._torch
+        m, k = (a.shape[1], a.shape[0]) if trans_a else a.shape
+        k2, n = (b.shape[1], b.shape[0]) if trans_b else b.shape
+        assert k == k2
+        fa, fb = Fmt(*fa), Fmt(*fb)
+        if out is None:
+            out = torch.empty((m, n), dtype=self._out_dtype(k, fa, fb, ep), device=a.device)
+        _check(self._lib.adapt_fxp_gemm(self._h, int(trans_a), int(trans_b), m, n, k, _ptr(a), fa, a.stride(0),
+                                        _ptr(b), fb, b.stride(0), _ptr(out), out.stride(0), ep), "adapt_fxp_gemm")
+        return out
+
+    def conv_fwd(self, d: ConvDesc, x, fx, w, fw, ep, out=None):
+        torch = self._torch
+        fx, fw = Fmt(*fx), Fmt(*fw)
+        if out is None:
+            out = torch.empty((d.n, d.p, d.q, d.k), dtype=self._out_dtype(d.r * d.s * d.c, fx, fw, ep), device=x.device)
+        _check(self._lib.adapt_conv_fwd(self._h, d, _ptr(x), fx, _ptr(w), fw, _ptr(out), ep), "adapt_conv_fwd")
+        return out
+
+    def conv_dgrad(self, d: ConvDesc, dy, fdy, w, fw, ep, out=None):
+        torch = self._torch
+        fdy, fw = Fmt(*fdy), Fmt(*fw)
+        if out is None:
+            out = torch.empty((d.n, d.h, d.w, d.c), dtype=self._out_dtype(d.r * d.s * d.k, fdy, fw, ep), device=dy.device)
+        _check(self._lib.adapt_conv_dgrad(self._h, d, _ptr(dy), fdy, _ptr(w), fw, _ptr(out), ep), "adapt_conv_dgrad")
+        return out
+
+    def conv_wgrad(self, d: ConvDesc, dy, fdy, x, fx, ep, out=None):
+        torch = self._torch
+        fdy, fx = Fmt(*fdy), Fmt(*fx)
+        if out is None:
+            out = torch.empty((d.k, d.r, d.s, d.c), dtype=self._out_dtype(d.n * d.p * d.q, fdy, fx, ep), device=dy.device)
+        _check(self._lib.adapt_conv_wgrad(self._h, d, _ptr(dy), fdy, _ptr(x), fx, _ptr(out), ep), "adapt_conv_wgrad")
+        return out
+
+    # -- KLD precision search -----------------------------------------------------------------
+    def kld_precision_search(self, w, wl_lo, wl_hi, il, bins, eps, alpha=-1.0, mode=SR, seed=0, stream=0,
+                             want_hist=False):
+        """Returns dict(kld=f64[ncand], sel=int32[2], hist=uint32-as-int32[(ncand+1), bins] or None,
+        grid=int64[3]) of device tensors."""
+        torch = self._torch
+        ncand = wl_hi - wl_lo + 1
+        dev = w.device
+        kld = torch.empty(max(ncand, 1), dtype=torch.float64, device=dev)
+        sel = torch.empty(2, dtype=torch.int32, device=dev)
+        grid = torch.empty(3, dtype=torch.int64, device=dev)
+        hist = torch.empty((max(ncand, 0) + 1, bins), dtype=torch.int32, device=dev) if want_hist else None
+        _check(self._lib.adapt_kld_precision_search(self._h, _ptr(w), w.numel(), wl_lo, wl_hi, il, bins, eps, alpha,
+                                                    Rng(mode, seed, stream), _ptr(kld), _ptr(sel), _ptr(hist),
+                                                    _ptr(grid)), "adapt_kld_precision_search")
+        return dict(kld=kld, sel=sel, hist=hist, grid=grid)
+
+    def kld_precision_search_batched(self, ws, ils, bins, streams, wl_lo, wl_hi, eps, alpha=-1.0, mode=SR, seed=0,
+                                     kld=None, sel=None):
+        torch = self._torch
+        n = len(ws)
+        ncand = wl_hi - wl_lo + 1
+        dev = ws[0].device if n else "cuda"
+        if kld is None:
+            kld = torch.empty((max(n, 1), ncand), dtype=torch.float64, device=dev)
+        if sel is None:
+            sel = torch.empty((max(n, 1), 2), dtype=torch.int32, device=dev)
+        items = (KldItem * max(n, 1))()
+        for t in range(n):
+            items[t] = KldItem(ws[t].data_ptr(), ws[t].numel(), ils[t], bins[t], streams[t])
+        _check(self._lib.adapt_kld_precision_search_batched(self._h, items, n, wl_lo, wl_hi, eps, alpha, mode, seed,
+                                                            _ptr(kld), _ptr(sel)), "adapt_kld_precision_search_batched")
+        return kld, sel

@@ -1,0 +1,115 @@
+// Shared device / host helpers of the gfx950 fixed-point library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adapt_fxp.h"
+
+namespace adapt {
+
+constexpr int kWave = 64;
+
+struct adapt_ctx_impl;
+
+// ---------------------------------------------------------------------------------------------
+// Philox-4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1).  One call yields the
+// 16 rounding bits of 8 consecutive elements.  The key schedule depends only on the seed, so
+// the compiler keeps it in scalar registers.
+// ---------------------------------------------------------------------------------------------
+struct u32x4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)M0 * c0;
+        const uint64_t p1 = (uint64_t)M1 * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += W0;
+        k1 += W1;
+    }
+    return {c0, c1, c2, c3};
+}
+
+// Rounding bits of the 8 elements 8*j .. 8*j+7 of a tensor: lane l is (w[l/2] >> 16*(l%2)) & 0xffff.
+__device__ __forceinline__ u32x4 rounding_block(uint64_t seed, uint64_t stream, uint64_t j)
+{
+    return philox4x32_10((uint32_t)j, (uint32_t)(j >> 32), (uint32_t)stream, (uint32_t)(stream >> 32),
+                         (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+__device__ __forceinline__ uint32_t lane16(const u32x4 &b, int lane)
+{
+    const uint32_t w = (lane >> 1) == 0 ? b.x : (lane >> 1) == 1 ? b.y : (lane >> 1) == 2 ? b.z : b.w;
+    return (lane & 1) ? (w >> 16) : (w & 0xffffu);
+}
+
+// 16 rounding bits of one element (used where elements are not handled 8 at a time)
+__device__ __forceinline__ uint32_t rounding_bits_of(uint64_t seed, uint64_t stream, uint64_t i, int mode)
+{
+    if (mode != ADAPT_SR) return 0x8000u;
+    return lane16(rounding_block(seed, stream, i >> 3), (int)(i & 7));
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 -> fixed-point code (Sec. 3.2 SR rule with 16 guard bits, two's-complement saturation)
+// ---------------------------------------------------------------------------------------------
+struct QuantParams {
+    float scale;     // 2^fl
+    float qminf, qmaxf;
+    int qmax;
+};
+
+__host__ __device__ inline QuantParams make_quant_params(int wl, int fl)
+{
+    QuantParams p;
+    p.scale = (float)(1ull << fl);
+    p.qmaxf = (float)((1 << (wl - 1)) - 1);
+    p.qminf = -(float)(1 << (wl - 1));
+    p.qmax = (1 << (wl - 1)) - 1;
+    return p;
+}
+
+// returns the code; sat is set to 1 when x*2^fl lies outside the representable range
+__device__ __forceinline__ int quantize_one(float x, uint32_t r16, const QuantParams &p, int &sat)
+{
+    const float y = x * p.scale;                       // exact (power of two), may become +-inf
+    sat = (y < p.qminf) | (y > p.qmaxf);               // false for NaN
+    const float yc = fminf(fmaxf(y, p.qminf), p.qmaxf);
+    const int t = (int)floorf(yc * 65536.0f);          // exact, |t| <= 2^31 - 2^16 ... -2^31
+    int q = (t + (int)r16) >> 16;
+    q = min(q, p.qmax);
+    return (x != x) ? 0 : q;
+}
+
+// ---------------------------------------------------------------------------------------------
+// wavefront reductions (64 lanes)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_min_f32(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_max_f32(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+}  // namespace adapt

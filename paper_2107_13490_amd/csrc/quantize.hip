@@ -1,0 +1,258 @@
+// Quantize(L, <WL,FL>) of Alg. 1 / Alg. 3 (rounding rule SR of Sec. 3.2) for gfx950.
+//
+// HBM-bound streaming kernel: every thread converts groups of 8 consecutive elements
+// (two 16-byte loads, one 8- or 16-byte store) with one Philox block per group.
+// nnz / saturated are reduced per wavefront, then per block, and the last block to finish
+// sums the block partials (no zero-fill launch, no floating point, order-independent).
+#include "common.hpp"
+#include "context.hpp"
+
+namespace adapt {
+
+constexpr int kQThreads = 256;
+
+template <typename OutT>
+__device__ __forceinline__ void store8(OutT *q, const int (&v)[8]);
+
+template <>
+__device__ __forceinline__ void store8<int8_t>(int8_t *q, const int (&v)[8])
+{
+    uint2 o;
+    o.x = (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) |
+          ((uint32_t)(v[3] & 0xff) << 24);
+    o.y = (uint32_t)(v[4] & 0xff) | ((uint32_t)(v[5] & 0xff) << 8) | ((uint32_t)(v[6] & 0xff) << 16) |
+          ((uint32_t)(v[7] & 0xff) << 24);
+    *reinterpret_cast<uint2 *>(q) = o;
+}
+template <>
+__device__ __forceinline__ void store8<int16_t>(int16_t *q, const int (&v)[8])
+{
+    uint4 o;
+    o.x = (uint32_t)(v[0] & 0xffff) | ((uint32_t)v[1] << 16);
+    o.y = (uint32_t)(v[2] & 0xffff) | ((uint32_t)v[3] << 16);
+    o.z = (uint32_t)(v[4] & 0xffff) | ((uint32_t)v[5] << 16);
+    o.w = (uint32_t)(v[6] & 0xffff) | ((uint32_t)v[7] << 16);
+    *reinterpret_cast<uint4 *>(q) = o;
+}
+
+// Converts the elements [0, n) of one tensor; this block handles the groups
+// first_group, first_group + group_stride, ...  Returns the thread's (nnz, sat) counts.
+template <typename OutT>
+__device__ __forceinline__ void quantize_span(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n,
+                                              const QuantParams p, int mode, uint64_t seed, uint64_t stream,
+                                              uint64_t first_group, uint64_t group_stride, uint32_t &nnz,
+                                              uint32_t &nsat)
+{
+    const uint64_t full_groups = n >> 3;
+    for (uint64_t g = first_group; g < full_groups; g += group_stride) {
+        const float4 a = reinterpret_cast<const float4 *>(x)[2 * g];
+        const float4 b = reinterpret_cast<const float4 *>(x)[2 * g + 1];
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        uint32_t r[8];
+        if (mode == ADAPT_SR) {
+            const u32x4 blk = rounding_block(seed, stream, g);
+            r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
+            r[4] = blk.z & 0xffffu; r[5] = blk.z >> 16; r[6] = blk.w & 0xffffu; r[7] = blk.w >> 16;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = 0x8000u;
+        }
+        int c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int s;
+            c[e] = quantize_one(v[e], r[e], p, s);
+            nnz += (c[e] != 0);
+            nsat += s;
+        }
+        store8<OutT>(q + 8 * g, c);
+    }
+    // ragged tail (< 8 elements): the thread that would own group `full_groups`
+    if ((n & 7) && first_group <= full_groups && (full_groups - first_group) % group_stride == 0) {
+        for (uint64_t i = full_groups << 3; i < n; ++i) {
+            int s;
+            const int c = quantize_one(x[i], rounding_bits_of(seed, stream, i, mode), p, s);
+            q[i] = (OutT)c;
+            nnz += (c != 0);
+            nsat += s;
+        }
+    }
+}
+
+__device__ __forceinline__ void block_sum2(uint32_t a, uint32_t b, uint64_t &sa, uint64_t &sb)
+{
+    __shared__ uint32_t part[2][kQThreads / kWave];
+    a = wave_sum_u32(a);
+    b = wave_sum_u32(b);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) { part[0][wave] = a; part[1][wave] = b; }
+    __syncthreads();
+    sa = 0; sb = 0;
+#pragma unroll
+    for (int w = 0; w < kQThreads / kWave; ++w) { sa += part[0][w]; sb += part[1][w]; }
+    __syncthreads();
+}
+
+template <typename OutT>
+__global__ void __launch_bounds__(kQThreads)
+quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, int wl, int fl, int mode,
+                uint64_t seed, uint64_t stream, uint64_t *nnz_out, uint64_t *sat_out,
+                uint64_t *partial /* [2*gridDim.x] */, uint32_t *ticket)
+{
+    const QuantParams p = make_quant_params(wl, fl);
+    uint32_t nnz = 0, nsat = 0;
+    // a thread converts at most n/8/stride + 8 < 2^32 elements for any n < 2^61
+    quantize_span<OutT>(x, q, n, p, mode, seed, stream, (uint64_t)blockIdx.x * kQThreads + threadIdx.x,
+                        (uint64_t)gridDim.x * kQThreads, nnz, nsat);
+    if (nnz_out == nullptr && sat_out == nullptr) return;
+    uint64_t bn, bs;
+    block_sum2(nnz, nsat, bn, bs);
+    __shared__ bool last;
+    if (threadIdx.x == 0) {
+        partial[2 * blockIdx.x] = bn;
+        partial[2 * blockIdx.x + 1] = bs;
+        __threadfence();
+        last = (atomicAdd(ticket, 1u) == gridDim.x - 1);
+    }
+    __syncthreads();
+    if (!last) return;
+    __threadfence();
+    uint64_t tn = 0, ts = 0;
+    for (uint32_t b = threadIdx.x; b < gridDim.x; b += kQThreads) {
+        tn += __hip_atomic_load(partial + 2 * b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ts += __hip_atomic_load(partial + 2 * b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // 64-bit block reduction through LDS
+    __shared__ uint64_t red[2][kQThreads];
+    red[0][threadIdx.x] = tn;
+    red[1][threadIdx.x] = ts;
+    __syncthreads();
+    for (int off = kQThreads / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + off];
+            red[1][threadIdx.x] += red[1][threadIdx.x + off];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (nnz_out) *nnz_out = red[0][0];
+        if (sat_out) *sat_out = red[1][0];
+        *ticket = 0;   // ready for the next call on this context
+    }
+}
+
+// ---- batched form: up to kMaxItems tensors per launch, descriptors in the kernel arguments ----
+constexpr int kMaxItems = 64;
+struct QuantBatch {
+    adapt_quantize_item item[kMaxItems];
+    int count;
+};
+
+__global__ void zero_u64_kernel(uint64_t *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+__global__ void __launch_bounds__(kQThreads)
+quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint64_t *counters)
+{
+    // Blocks are dealt to tensors round-robin: tensor t starts at block `rot` so that small
+    // tensors do not all land on block 0.
+    uint32_t rot = 0;
+    for (int t = 0; t < batch.count; ++t) {
+        const adapt_quantize_item it = batch.item[t];
+        const uint64_t groups = (it.n + 7) >> 3;
+        const uint32_t blocks_needed = (uint32_t)min((uint64_t)gridDim.x, (groups + kQThreads - 1) / kQThreads);
+        const uint32_t slot = (blockIdx.x + gridDim.x - rot % gridDim.x) % gridDim.x;
+        rot += blocks_needed;
+        if (blocks_needed == 0) continue;
+        uint32_t nnz = 0, nsat = 0;
+        if (slot < blocks_needed) {
+            const QuantParams p = make_quant_params(it.wl, it.fl);
+            const uint64_t first = (uint64_t)slot * kQThreads + threadIdx.x;
+            const uint64_t stride = (uint64_t)blocks_needed * kQThreads;
+            if (it.wl <= 8)
+                quantize_span<int8_t>(it.x, (int8_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat);
+            else
+                quantize_span<int16_t>(it.x, (int16_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat);
+        }
+        if (counters != nullptr && slot < blocks_needed) {
+            nnz = wave_sum_u32(nnz);
+            nsat = wave_sum_u32(nsat);
+            if ((threadIdx.x & (kWave - 1)) == 0) {
+                if (nnz) atomicAdd((unsigned long long *)&counters[2 * t], (unsigned long long)nnz);
+                if (nsat) atomicAdd((unsigned long long *)&counters[2 * t + 1], (unsigned long long)nsat);
+            }
+        }
+    }
+}
+
+static int grid_for(const adapt_ctx *ctx, uint64_t n)
+{
+    const uint64_t groups = (n + 7) >> 3;
+    uint64_t blocks = (groups + kQThreads - 1) / kQThreads;
+    const uint64_t cap = (uint64_t)ctx->num_cu * 8;
+    if (blocks > cap) blocks = cap;
+    if (blocks == 0) blocks = 1;
+    return (int)blocks;
+}
+
+}  // namespace adapt
+
+using namespace adapt;
+
+extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng, void *q,
+                              uint64_t *nnz, uint64_t *saturated)
+{
+    if (!ctx || !fmt_ok(fmt) || (rng.mode != ADAPT_SR && rng.mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
+    if (n > 0 && (!x || !q || !aligned16(x) || !aligned16(q))) return ADAPT_EINVAL;
+    if (n >= ((uint64_t)1 << 60)) return ADAPT_EINVAL;
+    if ((nnz && ((uintptr_t)nnz & 7)) || (saturated && ((uintptr_t)saturated & 7))) return ADAPT_EINVAL;
+    const int grid = grid_for(ctx, n);
+    uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
+    if ((size_t)grid * 16 > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    if (fmt.wl <= 8)
+        hipLaunchKernelGGL(quantize_kernel<int8_t>, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int8_t *)q,
+                           (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, nnz, saturated, partial,
+                           ticket(ctx, 0));
+    else
+        hipLaunchKernelGGL(quantize_kernel<int16_t>, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int16_t *)q,
+                           (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, nnz, saturated, partial,
+                           ticket(ctx, 0));
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item *items, int count, int mode,
+                                      uint64_t seed, uint64_t *counters)
+{
+    if (!ctx || count < 0 || (count > 0 && !items)) return ADAPT_EINVAL;
+    if (mode != ADAPT_SR && mode != ADAPT_RN_HALF_UP) return ADAPT_EINVAL;
+    if (counters && ((uintptr_t)counters & 7)) return ADAPT_EINVAL;
+    for (int t = 0; t < count; ++t) {
+        const adapt_quantize_item &it = items[t];
+        if (!fmt_ok(adapt_fmt{it.wl, it.fl}) || it.n >= ((uint64_t)1 << 60)) return ADAPT_EINVAL;
+        if (it.n > 0 && (!it.x || !it.q || !aligned16(it.x) || !aligned16(it.q))) return ADAPT_EINVAL;
+    }
+    if (count == 0) return ADAPT_OK;
+    if (counters) {
+        hipLaunchKernelGGL(zero_u64_kernel, dim3((2 * count + 255) / 256), dim3(256), 0, ctx->stream, counters,
+                           2 * count);
+    }
+    for (int base = 0; base < count; base += kMaxItems) {
+        QuantBatch batch;
+        batch.count = count - base < kMaxItems ? count - base : kMaxItems;
+        uint64_t total_blocks = 0;
+        for (int t = 0; t < batch.count; ++t) {
+            batch.item[t] = items[base + t];
+            total_blocks += (((items[base + t].n + 7) >> 3) + kQThreads - 1) / kQThreads;
+        }
+        uint64_t grid = total_blocks;
+        const uint64_t cap = (uint64_t)ctx->num_cu * 8;
+        if (grid > cap) grid = cap;
+        if (grid == 0) continue;
+        hipLaunchKernelGGL(quantize_batched_kernel, dim3((unsigned)grid), dim3(kQThreads), 0, ctx->stream, batch, mode,
+                           seed, counters ? counters + 2 * base : nullptr);
+    }
+    return hip_status(ctx, hipGetLastError());
+}

@@ -1,0 +1,57 @@
+"""The C-ABI library loads and exports every entry point include/adapt_fxp.h declares (CPU only:
+no compute call is made)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "adapt_fxp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adapt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_documented_entry_points():
+    names = _declared()
+    for must in ("adapt_create", "adapt_destroy", "adapt_quantize", "adapt_quantize_batched", "adapt_fxp_gemm",
+                 "adapt_conv_fwd", "adapt_conv_dgrad", "adapt_conv_wgrad", "adapt_kld_precision_search",
+                 "adapt_kld_precision_search_batched", "adapt_acc_bits", "adapt_error_string"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2107_13490_amd as pkg
+    path = pkg.library_path()
+    if not os.path.exists(path):
+        import __graft_entry__
+        __graft_entry__.build()
+    lib = ctypes.CDLL(path)
+    for name in _declared():
+        assert hasattr(lib, name), name
+    lib.adapt_error_string.restype = ctypes.c_char_p
+    assert lib.adapt_error_string(0) == b"ok"
+    assert lib.adapt_version() >= 1
+
+
+def test_acc_bits_rule():
+    import paper_2107_13490_amd as pkg
+    from paper_2107_13490_amd import Fmt
+    assert pkg.acc_bits(256, Fmt(8, 6), Fmt(8, 6)) == 32
+    assert pkg.acc_bits((1 << 17) - 1, Fmt(8, 0), Fmt(8, 0)) == 32        # (2^17-1) * 2^14 < 2^31
+    assert pkg.acc_bits(1 << 17, Fmt(8, 0), Fmt(8, 0)) == 64
+    assert pkg.acc_bits(1, Fmt(16, 0), Fmt(16, 0)) == 32                  # 2^30
+    assert pkg.acc_bits(2, Fmt(16, 0), Fmt(16, 0)) == 64
+    assert pkg.acc_bits(1152, Fmt(12, 9), Fmt(12, 9)) == 64
+
+
+def test_no_cpu_fallback():
+    import torch
+    import paper_2107_13490_amd as pkg
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        pkg.Context()

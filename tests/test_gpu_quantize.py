@@ -1,0 +1,116 @@
+"""GPU parity: adapt_quantize / adapt_quantize_batched against the CPU oracle, bit for bit
+(Sec. 3.2 SR rule; Alg. 1 per-layer Quantize)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2107_13490_amd as pkg
+import workloads as wk
+from oracle import fxp_oracle as orc
+
+from gpu_util import ctx, dev, host, u64
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(x, wl, fl, mode, seed, stream):
+    q, cnt = ctx().quantize(dev(x), wl, fl, mode, seed, stream)
+    want, nnz, sat = orc.quantize(x, wl, fl, mode, seed, stream)
+    got = host(q)
+    assert got.dtype == (np.int8 if wl <= 8 else np.int16)
+    assert np.array_equal(got.astype(np.int64), want)
+    assert u64(cnt).tolist() == [nnz, sat]
+
+
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 63, 1000, 2048 * 8 + 5, (1 << 20) + 3])
+@pytest.mark.parametrize("wl,fl", [(8, 5), (12, 9), (4, 1), (16, 13), (2, 0)])
+def test_sizes_and_formats(n, wl, fl):
+    x = (np.random.default_rng(n + wl).standard_normal(n) * 2.0 ** (wl - 2 - fl)).astype(np.float32)
+    _check(x, wl, fl, pkg.SR, seed=3, stream=n)
+
+
+@pytest.mark.parametrize("wl,fl", [(8, 4), (16, 8), (8, 12), (3, 31), (16, 0)])
+@pytest.mark.parametrize("mode", [pkg.SR, pkg.RN_HALF_UP])
+def test_modes_seeds_streams(wl, fl, mode):
+    x = (np.random.default_rng(7).standard_normal(40001) * 2.0 ** (wl - 1 - fl) * 0.6).astype(np.float32)
+    _check(x, wl, fl, mode, seed=(5 << 40) + 17, stream=(9 << 35) + 2)
+    _check(x, wl, fl, mode, seed=0, stream=0)
+
+
+def test_special_values_and_denormals():
+    den = np.float32(1e-45)
+    base = np.array([np.nan, np.inf, -np.inf, -0.0, 0.0, den, -den, 3.4e38, -3.4e38, 1e-39, -1e-39,
+                     7.9999, -8.0, -8.0001, 0.03125, -0.03125], dtype=np.float32)
+    x = np.tile(base, 37)[:-3]
+    for wl, fl in ((8, 4), (16, 12)):
+        for seed in range(4):
+            _check(x, wl, fl, pkg.SR, seed, 1)
+        _check(x, wl, fl, pkg.RN_HALF_UP, 0, 0)
+
+
+def test_grid_points_unchanged_for_any_seed():
+    codes = np.arange(-128, 128).repeat(9)
+    x = (codes * 2.0 ** -5).astype(np.float32)
+    for seed in range(3):
+        q, _ = ctx().quantize(dev(x), 8, 5, pkg.SR, seed, 4)
+        assert np.array_equal(host(q).astype(np.int64), codes)
+
+
+def test_empty_tensor():
+    x = torch.empty(0, dtype=torch.float32, device="cuda")
+    q, cnt = ctx().quantize(x, 8, 4)
+    assert u64(cnt).tolist() == [0, 0] and q.numel() == 0
+
+
+def test_config2_full_size_tensors():
+    L = wk.config2()
+    for stream, t in enumerate((L.x, L.w, L.dy)):
+        _check(t.ravel(), L.wl, L.fl, pkg.SR, seed=0, stream=stream + 1)
+
+
+def test_config3_weights_keep_exact_zeros():
+    L = wk.config3(batch=2)
+    q, cnt = ctx().quantize(dev(L.w.ravel()), L.wl, L.fl, pkg.SR, 0, 2)
+    got = host(q)
+    assert (got[L.w.ravel() == 0] == 0).all()
+    want, nnz, sat = orc.quantize(L.w.ravel(), L.wl, L.fl, pkg.SR, 0, 2)
+    assert np.array_equal(got.astype(np.int64), want) and u64(cnt).tolist() == [nnz, sat]
+
+
+def test_batched_matches_oracle():
+    g = np.random.default_rng(1)
+    sizes = [1, 5, 4096, 100003, 0, 17, 300000, 8]
+    fmts = [(8, 4), (12, 9), (4, 2), (16, 10), (8, 4), (6, 3), (8, 5), (9, 4)]
+    xs = [(g.standard_normal(n) * 2.0 ** (f[0] - 2 - f[1])).astype(np.float32) for n, f in zip(sizes, fmts)]
+    streams = list(range(10, 10 + len(xs)))
+    outs, cnt = ctx().quantize_batched([dev(x) for x in xs], fmts, streams, pkg.SR, seed=77)
+    c = u64(cnt)
+    for t, (x, f) in enumerate(zip(xs, fmts)):
+        want, nnz, sat = orc.quantize(x, f[0], f[1], pkg.SR, 77, streams[t])
+        assert np.array_equal(host(outs[t]).astype(np.int64), want)
+        assert c[2 * t:2 * t + 2].tolist() == [nnz, sat]
+
+
+def test_batched_many_items():
+    g = np.random.default_rng(2)
+    xs = [(g.standard_normal(100 + 37 * t)).astype(np.float32) for t in range(150)]
+    fmts = [(8, 4) if t % 2 else (12, 8) for t in range(150)]
+    outs, cnt = ctx().quantize_batched([dev(x) for x in xs], fmts, list(range(150)), pkg.SR, seed=1)
+    c = u64(cnt)
+    for t in (0, 1, 63, 64, 65, 127, 128, 149):
+        want, nnz, sat = orc.quantize(xs[t], fmts[t][0], fmts[t][1], pkg.SR, 1, t)
+        assert np.array_equal(host(outs[t]).astype(np.int64), want)
+        assert c[2 * t:2 * t + 2].tolist() == [nnz, sat]
+
+
+def test_invalid_arguments_are_rejected():
+    x = torch.zeros(64, dtype=torch.float32, device="cuda")
+    with pytest.raises(pkg.AdaptError) as e:
+        ctx().quantize(x, 17, 4)
+    assert e.value.status == -1
+    with pytest.raises(pkg.AdaptError):
+        ctx().quantize(x, 8, 32)
+    with pytest.raises(pkg.AdaptError):
+        ctx().quantize(x[1:], 8, 4)          # misaligned
+    with pytest.raises(pkg.AdaptError):
+        ctx().quantize(x, 8, 4, mode=5)
