@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the fixed-point hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch of the AlexNet-CIFAR-style
+conv layer (batch 128, 64ch 16x16 -> 192ch 3x3, all tensors <8,5>):
+
+    quantize(X, W, dY)  ->  conv fwd (+ReLU)  ->  dgrad  ->  wgrad   (outputs requantized, SR)
+    ->  KL-divergence precision search on W (WL 4..16, 2048 bins)
+
+All inputs are resident in HBM before the timed region.  `value` is useful conv/GEMM
+tera-ops (2*M*N*K per contraction, three contractions) divided by the whole step time.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, 256 CU x 8192 op/clk x 2.4 GHz
+PEAK_HBM_GBPS = 8000.0
+
+
+def cpu_baseline(batch: int):
+    """The oracle, as it stands, on a bounded sample (reduced batch) of the same layer."""
+    import numpy as np
+    import workloads as wk
+    from oracle import conv_oracle as co
+    from oracle import fxp_oracle as orc
+
+    L = wk.config2(batch=batch)
+    s = L.shape
+    co.load()
+    t0 = time.perf_counter()
+    qx, _, _ = orc.quantize(L.x, L.wl, L.fl, orc.SR, 0, 1)
+    qw, _, _ = orc.quantize(L.w, L.wl, L.fl, orc.SR, 0, 2)
+    qdy, _, _ = orc.quantize(L.dy, L.wl, L.fl, orc.SR, 0, 3)
+    y = co.conv_fwd(qx, qw, s.stride, s.pad)
+    dx = co.conv_dgrad(qdy, qw, s.h, s.w, s.stride, s.pad)
+    dw = co.conv_wgrad(qdy, qx, s.r, s.s, s.stride, s.pad)
+    orc.requantize(y, L.fl, L.wl, orc.SR, 0, 10, True)
+    orc.requantize(dx, L.fl, L.wl, orc.SR, 0, 11)
+    orc.requantize(dw, L.fl, L.wl, orc.SR, 0, 12)
+    orc.kld_precision_search(L.w.ravel(), 4, 16, 3, 2048, 1e-2, None, orc.SR, 0, 2)
+    dt = time.perf_counter() - t0
+    ops = 3 * 2.0 * s.macs
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": co.num_threads(), "kind": "oracle",
+            "sample": f"same layer at batch {batch} (of 128): quantize + fwd + dgrad + wgrad + requantize + KLD, "
+                      f"{dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batch", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2107_13490_amd as pkg
+    import workloads as wk
+    from paper_2107_13490_amd import ConvDesc, Epilogue
+
+    torch.cuda.set_device(0)
+    ctx = pkg.Context()
+    L = wk.config2()
+    s = L.shape
+    d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+    f = (L.wl, L.fl)
+    x, w, dy = (torch.from_numpy(t).cuda() for t in (L.x, L.w, L.dy))
+    qx = torch.empty(x.shape, dtype=torch.int8, device="cuda")
+    qw = torch.empty(w.shape, dtype=torch.int8, device="cuda")
+    qdy = torch.empty(dy.shape, dtype=torch.int8, device="cuda")
+    y = torch.empty((s.n, s.p, s.q, s.k), dtype=torch.int8, device="cuda")
+    dx = torch.empty(x.shape, dtype=torch.int8, device="cuda")
+    dw = torch.empty(w.shape, dtype=torch.int8, device="cuda")
+    counters = torch.empty(6, dtype=torch.int64, device="cuda")
+    kld = torch.empty((1, 13), dtype=torch.float64, device="cuda")
+    sel = torch.empty((1, 2), dtype=torch.int32, device="cuda")
+    ep_y = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10, relu=True)
+    ep_dx = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 11)
+    ep_dw = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 12)
+
+    names = ["quantize", "conv_fwd", "conv_dgrad", "conv_wgrad", "kld_search"]
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        ctx.quantize_batched([x, w, dy], [f, f, f], [1, 2, 3], pkg.SR, 0, outs=[qx, qw, qdy], counters=counters)
+        mark(1)
+        ctx.conv_fwd(d, qx, f, qw, f, ep_y, out=y)
+        mark(2)
+        ctx.conv_dgrad(d, qdy, f, qw, f, ep_dx, out=dx)
+        mark(3)
+        ctx.conv_wgrad(d, qdy, f, qx, f, ep_dw, out=dw)
+        mark(4)
+        ctx.kld_precision_search_batched([w.view(-1)], [3], [2048], [2], 4, 16, 1e-2, kld=kld, sel=sel)
+        mark(5)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # per-call device times come from events recorded on the launch stream inside the timed region
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_step = dt / args.steps * 1e3
+    call_ms = [sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps for i in range(5)]
+    conv_ops = 2.0 * s.macs
+    value = 3 * conv_ops / (ms_step * 1e-3) / 1e12
+    # dominant kernel: the forward convolution is one launch of the MFMA contraction kernel
+    fwd_tops = conv_ops / (call_ms[1] * 1e-3) / 1e12
+    q_bytes = 5.0 * (x.numel() + w.numel() + dy.numel())
+    kld_bytes = 8.0 * w.numel()
+    out = {
+        "metric": "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s",
+        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "configs[1]: AlexNet-CIFAR conv 64->192 3x3 @16x16, batch 128, <8,5>; quantize(X,W,dY) "
+                               "+ fwd + dgrad + wgrad (requantized, SR) + KLD search on W (WL 4..16, 2048 bins)",
+                   "useful_ops_per_step": 3 * conv_ops},
+        "roofline": {"bound": "mfma", "kernel": "contract_kernel<fwd> (conv_fwd call)", "achieved": fwd_tops,
+                     "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": fwd_tops / PEAK_INT8_TOPS, "traffic": None},
+        "calls_ms": dict(zip(names, call_ms)),
+        "conv_TOPS": {n: conv_ops / (call_ms[i] * 1e-3) / 1e12 for i, n in ((1, "fwd"), (2, "dgrad"), (3, "wgrad"))},
+        "quantize_GBps": q_bytes / (call_ms[0] * 1e-3) / 1e9,
+        "quantize_frac_hbm": q_bytes / (call_ms[0] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "kld_GBps": kld_bytes / (call_ms[4] * 1e-3) / 1e9,
+        "kld_frac_hbm": kld_bytes / (call_ms[4] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_batch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

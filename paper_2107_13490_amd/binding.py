@@ -188,8 +188,10 @@ class Context:
         fa, fb = Fmt(*fa), Fmt(*fb)
         if out is None:
             out = torch.empty((m, n), dtype=self._out_dtype(k, fa, fb, ep), device=a.device)
-        _check(self._lib.adapt_fxp_gemm(self._h, int(trans_a), int(trans_b), m, n, k, _ptr(a), fa, a.stride(0),
-                                        _ptr(b), fb, b.stride(0), _ptr(out), out.stride(0), ep), "adapt_fxp_gemm")
+        lda = a.stride(0) if a.numel() else max(a.shape[1], 1)      # empty tensors report stride 0
+        ldb = b.stride(0) if b.numel() else max(b.shape[1], 1)
+        _check(self._lib.adapt_fxp_gemm(self._h, int(trans_a), int(trans_b), m, n, k, _ptr(a), fa, lda,
+                                        _ptr(b), fb, ldb, _ptr(out), out.stride(0), ep), "adapt_fxp_gemm")
         return out
 
     def conv_fwd(self, d: ConvDesc, x, fx, w, fw, ep, out=None):

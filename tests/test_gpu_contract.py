@@ -1,0 +1,260 @@
+"""GPU parity: integer GEMM and convolution forward / data gradient / weight gradient against
+the CPU oracle, bit for bit (exact accumulators and requantized outputs).  The contractions are
+the quantized layer compute of Alg. 1; requantization applies the SR rule of Sec. 3.2 to the
+accumulator."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2107_13490_amd as pkg
+import workloads as wk
+from oracle import conv_oracle as co
+from oracle import fxp_oracle as orc
+from paper_2107_13490_amd import ConvDesc, Epilogue
+
+from gpu_util import ctx, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def codes(shape, wl, seed, extreme=False):
+    g = np.random.default_rng(seed)
+    lo, hi = -(1 << (wl - 1)), (1 << (wl - 1)) - 1
+    if extreme:
+        a = g.choice(np.array([lo, hi, lo + 1, hi - 1, 0, -1, 1, 127, 128, -128, -129, 255, 256, 32639, 32640]).clip(lo, hi), shape)
+    else:
+        a = g.integers(lo, hi + 1, shape)
+    return a.astype(np.int8 if wl <= 8 else np.int16)
+
+
+def to_dev(a):
+    return dev(a)
+
+
+# ------------------------------------------------------------------------------------ GEMM
+
+def test_config1_gemm():
+    a, b = wk.config1_gemm()
+    qa, _, _ = orc.quantize(a, 8, 6, orc.SR, 0, 1)
+    qb, _, _ = orc.quantize(b, 8, 6, orc.SR, 0, 2)
+    c = ctx().fxp_gemm(to_dev(qa.astype(np.int8)), (8, 6), to_dev(qb.astype(np.int8)), (8, 6), Epilogue.exact())
+    got = host(c)
+    assert got.dtype == np.int32
+    assert np.array_equal(got.astype(np.int64), co.gemm(qa, qb))
+    # the whole path: quantize on the GPU, then multiply
+    da, _ = ctx().quantize(dev(a), 8, 6, pkg.SR, 0, 1)
+    db, _ = ctx().quantize(dev(b), 8, 6, pkg.SR, 0, 2)
+    c2 = ctx().fxp_gemm(da, (8, 6), db, (8, 6), Epilogue.exact())
+    assert np.array_equal(host(c2), got)
+
+
+GEMM_SHAPES = [(1, 1, 1), (5, 3, 7), (77, 45, 33), (128, 64, 64), (129, 65, 65), (256, 192, 576), (300, 130, 1000),
+               (64, 256, 16), (33, 500, 48), (16, 16, 0)]
+
+
+@pytest.mark.parametrize("m,n,k", GEMM_SHAPES)
+@pytest.mark.parametrize("wla,wlb", [(8, 8), (12, 12), (16, 16), (8, 16), (13, 4)])
+def test_gemm_shapes_and_word_lengths(m, n, k, wla, wlb):
+    a = codes((m, k), wla, m + k, extreme=(m % 2 == 1))
+    b = codes((k, n), wlb, n + k + 1, extreme=(n % 2 == 1))
+    want = orc.gemm(a, b)
+    c = ctx().fxp_gemm(to_dev(a), (wla, 3), to_dev(b), (wlb, 2), Epilogue.exact())
+    got = host(c)
+    bits = 32 if k * 2 ** (wla + wlb - 2) <= 2 ** 31 - 1 else 64
+    assert got.dtype == (np.int32 if bits == 32 else np.int64)
+    assert np.array_equal(got.astype(np.int64), want)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("m,n,k,wl", [(64, 64, 64, 8), (100, 36, 52, 8), (37, 29, 19, 8), (96, 160, 48, 14)])
+def test_gemm_transposes(ta, tb, m, n, k, wl):
+    a = codes((m, k), wl, 1)
+    b = codes((k, n), wl, 2)
+    want = orc.gemm(a, b)
+    da = to_dev(a.T.copy() if ta else a)
+    db = to_dev(b.T.copy() if tb else b)
+    c = ctx().fxp_gemm(da, (wl, 0), db, (wl, 0), Epilogue.exact(), trans_a=bool(ta), trans_b=bool(tb))
+    assert np.array_equal(host(c).astype(np.int64), want)
+
+
+def test_gemm_leading_dimensions():
+    a = codes((70, 128), 8, 3)
+    b = codes((96, 80), 8, 4)
+    da, db = to_dev(a)[:, :96], to_dev(b)[:, :48]        # lda = 128, ldb = 80
+    out = torch.full((70, 64), 7, dtype=torch.int32, device="cuda")
+    c = ctx().fxp_gemm(da, (8, 0), db, (8, 0), Epilogue.exact(), out=out[:, :48])
+    want = orc.gemm(a[:, :96], b[:, :48])
+    got = host(out)
+    assert np.array_equal(got[:, :48].astype(np.int64), want) and (got[:, 48:] == 7).all()
+
+
+def test_gemm_worst_case_accumulation():
+    # every product is +2^14 (or 2^30 for 16 bit): the int32 accumulators run at their bound
+    k = 4096
+    a = np.full((64, k), -128, dtype=np.int8)
+    b = np.full((k, 64), -128, dtype=np.int8)
+    c = ctx().fxp_gemm(to_dev(a), (8, 0), to_dev(b), (8, 0), Epilogue.exact())
+    assert (host(c) == k * 16384).all()
+    a16 = np.full((64, k), -32768, dtype=np.int16)
+    b16 = np.full((k, 64), -32768, dtype=np.int16)
+    c = ctx().fxp_gemm(to_dev(a16), (16, 0), to_dev(b16), (16, 0), Epilogue.exact())
+    assert host(c).dtype == np.int64 and (host(c) == k * (1 << 30)).all()
+    b16[:] = 32767
+    c = ctx().fxp_gemm(to_dev(a16), (16, 0), to_dev(b16), (16, 0), Epilogue.exact())
+    assert (host(c) == k * (-32768 * 32767)).all()
+
+
+def test_gemm_long_k_is_split():
+    k = 200000
+    a = codes((32, k), 8, 5)
+    b = codes((k, 48), 8, 6)
+    c = ctx().fxp_gemm(to_dev(a), (8, 0), to_dev(b), (8, 0), Epilogue.exact())
+    assert host(c).dtype == np.int64
+    assert np.array_equal(host(c), orc.gemm(a, b))
+
+
+@pytest.mark.parametrize("wl_o,fl_o,mode,relu", [(8, 4, pkg.SR, False), (8, 6, pkg.RN_HALF_UP, True), (16, 10, pkg.SR, True),
+                                                 (12, 12, pkg.SR, False), (8, 0, pkg.SR, False), (16, 14, pkg.SR, False),
+                                                 (4, 1, pkg.SR, False)])
+@pytest.mark.parametrize("m,n,k,wl", [(130, 192, 96, 8), (64, 40, 33, 8), (100, 64, 128, 12)])
+def test_gemm_requantize_epilogue(wl_o, fl_o, mode, relu, m, n, k, wl):
+    fa, fb = 6, 6
+    a = codes((m, k), wl, 11)
+    b = codes((k, n), wl, 12)
+    ep = Epilogue.requant(wl_o, fl_o, mode, seed=21, stream=5, relu=relu)
+    c = ctx().fxp_gemm(to_dev(a), (wl, fa), to_dev(b), (wl, fb), ep)
+    want = orc.requantize(orc.gemm(a, b), fa + fb - fl_o, wl_o, mode, 21, 5, relu)
+    got = host(c)
+    assert got.dtype == (np.int8 if wl_o <= 8 else np.int16)
+    assert np.array_equal(got.astype(np.int64), want)
+
+
+def test_requantize_wide_shift():
+    a = codes((64, 256), 16, 13)
+    b = codes((256, 64), 16, 14)
+    ep = Epilogue.requant(16, 2, pkg.SR, seed=1, stream=1)
+    c = ctx().fxp_gemm(to_dev(a), (16, 12), to_dev(b), (16, 12), ep)           # shift 22
+    want = orc.requantize(orc.gemm(a, b), 22, 16, orc.SR, 1, 1)
+    assert np.array_equal(host(c).astype(np.int64), want)
+
+
+# ------------------------------------------------------------------------------------ convolutions
+
+CONV_CASES = [
+    # n, h, w, c, k, r, s, stride, pad
+    (2, 8, 8, 16, 32, 3, 3, 1, 1),
+    (3, 7, 5, 32, 16, 3, 3, 1, 1),
+    (2, 9, 9, 16, 48, 3, 3, 2, 1),
+    (2, 6, 6, 64, 64, 1, 1, 1, 0),
+    (1, 8, 8, 32, 32, 1, 1, 2, 0),
+    (2, 10, 10, 16, 16, 5, 5, 1, 2),
+    (2, 8, 8, 3, 8, 3, 3, 1, 1),          # Cin = 3: element-wise gather path
+    (2, 5, 6, 20, 12, 3, 3, 1, 0),        # C multiple of 4 only
+    (1, 4, 4, 7, 5, 2, 2, 1, 1),          # nothing aligned
+    (9, 1, 1, 256, 100, 1, 1, 1, 0),      # fully connected layer
+]
+
+
+def _conv_all(case, wlx, wlw, wldy, extreme=False):
+    n, h, w, c, k, r, s, st, pad = case
+    d = ConvDesc(n, h, w, c, k, r, s, st, pad)
+    x = codes((n, h, w, c), wlx, 1, extreme)
+    wt = codes((k, r, s, c), wlw, 2, extreme)
+    dy = codes((n, d.p, d.q, k), wldy, 3, extreme)
+    y = ctx().conv_fwd(d, to_dev(x), (wlx, 4), to_dev(wt), (wlw, 5), Epilogue.exact())
+    assert np.array_equal(host(y).astype(np.int64), co.conv_fwd(x, wt, st, pad))
+    dx = ctx().conv_dgrad(d, to_dev(dy), (wldy, 4), to_dev(wt), (wlw, 5), Epilogue.exact())
+    assert np.array_equal(host(dx).astype(np.int64), co.conv_dgrad(dy, wt, h, w, st, pad))
+    dw = ctx().conv_wgrad(d, to_dev(dy), (wldy, 4), to_dev(x), (wlx, 4), Epilogue.exact())
+    assert np.array_equal(host(dw).astype(np.int64), co.conv_wgrad(dy, x, r, s, st, pad))
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_one_limb(case):
+    _conv_all(case, 8, 8, 8)
+    _conv_all(case, 4, 6, 8, extreme=True)
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_two_limb(case):
+    _conv_all(case, 12, 12, 12)
+    _conv_all(case, 16, 16, 16, extreme=True)
+
+
+@pytest.mark.parametrize("case", CONV_CASES[:4])
+def test_conv_mixed_word_lengths(case):
+    _conv_all(case, 8, 12, 16)
+    _conv_all(case, 16, 8, 9)
+
+
+def _layer_codes(L):
+    qx, _, _ = orc.quantize(L.x, L.wl, L.fl, orc.SR, 0, 1)
+    qw, _, _ = orc.quantize(L.w, L.wl, L.fl, orc.SR, 0, 2)
+    qdy, _, _ = orc.quantize(L.dy, L.wl, L.fl, orc.SR, 0, 3)
+    t = np.int8 if L.wl <= 8 else np.int16
+    return qx.astype(t), qw.astype(t), qdy.astype(t)
+
+
+def _layer_check(L, requant):
+    s = L.shape
+    d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+    qx, qw, qdy = _layer_codes(L)
+    f = (L.wl, L.fl)
+    dx_, dw_, ddy_ = to_dev(qx), to_dev(qw), to_dev(qdy)
+    y_ref = co.conv_fwd(qx, qw, s.stride, s.pad)
+    dx_ref = co.conv_dgrad(qdy, qw, s.h, s.w, s.stride, s.pad)
+    dw_ref = co.conv_wgrad(qdy, qx, s.r, s.s, s.stride, s.pad)
+    y = ctx().conv_fwd(d, dx_, f, dw_, f, Epilogue.exact())
+    dx = ctx().conv_dgrad(d, ddy_, f, dw_, f, Epilogue.exact())
+    dw = ctx().conv_wgrad(d, ddy_, f, dx_, f, Epilogue.exact())
+    assert np.array_equal(host(y).astype(np.int64), y_ref)
+    assert np.array_equal(host(dx).astype(np.int64), dx_ref)
+    assert np.array_equal(host(dw).astype(np.int64), dw_ref)
+    if requant:
+        # the configuration the benchmark times: outputs requantized to the layer format
+        for stream, (fn, args, ref, relu) in enumerate((
+                (ctx().conv_fwd, (dx_, f, dw_, f), y_ref, True),
+                (ctx().conv_dgrad, (ddy_, f, dw_, f), dx_ref, False),
+                (ctx().conv_wgrad, (ddy_, f, dx_, f), dw_ref, False))):
+            ep = Epilogue.requant(L.wl, L.fl, pkg.SR, seed=0, stream=10 + stream, relu=relu)
+            got = host(fn(d, *args, ep)).astype(np.int64)
+            want = orc.requantize(ref, L.fl, L.wl, orc.SR, 0, 10 + stream, relu)
+            assert np.array_equal(got, want)
+
+
+def test_config2_full_size():
+    _layer_check(wk.config2(), requant=True)
+
+
+def test_config3_reduced_batch():
+    _layer_check(wk.config3(batch=16), requant=True)
+
+
+def test_config3_full_size_sampled():
+    """Full batch 256 in the launch configuration the benchmark uses.  fwd and dgrad are
+    independent per image: the oracle computes a sample of images one by one; wgrad sums over
+    the whole batch and is compared in full."""
+    L = wk.config3()
+    s = L.shape
+    d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+    qx, qw, qdy = _layer_codes(L)
+    f = (L.wl, L.fl)
+    dx_, dw_, ddy_ = to_dev(qx), to_dev(qw), to_dev(qdy)
+    y = host(ctx().conv_fwd(d, dx_, f, dw_, f, Epilogue.exact()))
+    dx = host(ctx().conv_dgrad(d, ddy_, f, dw_, f, Epilogue.exact()))
+    dw = host(ctx().conv_wgrad(d, ddy_, f, dx_, f, Epilogue.exact()))
+    for img in (0, 1, 100, 254, 255):
+        assert np.array_equal(y[img:img + 1].astype(np.int64), co.conv_fwd(qx[img:img + 1], qw, 1, 1))
+        assert np.array_equal(dx[img:img + 1].astype(np.int64), co.conv_dgrad(qdy[img:img + 1], qw, s.h, s.w, 1, 1))
+    assert np.array_equal(dw.astype(np.int64), co.conv_wgrad(qdy, qx, 3, 3, 1, 1))
+
+
+def test_invalid_arguments():
+    a = torch.zeros((16, 16), dtype=torch.int8, device="cuda")
+    with pytest.raises(pkg.AdaptError):
+        ctx().fxp_gemm(a, (17, 0), a, (8, 0), Epilogue.exact())
+    with pytest.raises(pkg.AdaptError):
+        ctx().fxp_gemm(a, (8, 0), a, (8, 0), Epilogue.requant(20, 0))
+    d = ConvDesc(1, 2, 2, 16, 16, 5, 5, 1, 0)        # filter larger than the padded input
+    with pytest.raises(pkg.AdaptError):
+        ctx().conv_fwd(d, a, (8, 0), a, (8, 0), Epilogue.exact(), out=a)
