@@ -12,7 +12,8 @@ RN_HALF_UP = 0
 SR = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libadapt_fxp.so")
+# ADAPT_FXP_LIB selects another build of the same library (e.g. an instrumented one)
+_LIB_PATH = os.environ.get("ADAPT_FXP_LIB") or os.path.join(_HERE, "libadapt_fxp.so")
 _lib = None
 
 

@@ -67,3 +67,4 @@ extern "C" int adapt_acc_bits(int64_t K, adapt_fmt a, adapt_fmt b)
     const int64_t lim = ((int64_t)1 << 31) - 1;
     return (K <= (lim >> sh)) ? 32 : 64;
 }
+

@@ -6,6 +6,17 @@
 
 #include "adapt_fxp.h"
 
+#ifdef ADAPT_PROF
+// development builds only: phase timestamps of block 0 (s_memtime ticks), one array per source file
+static __device__ unsigned long long g_adapt_prof[64];
+#define ADAPT_STAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_adapt_prof[i] = clock64(); } while (0)
+#define ADAPT_PROF_GETTER(name) extern "C" int name(unsigned long long *host_out) { \
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_adapt_prof), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -4; }
+#else
+#define ADAPT_STAMP(i) do { } while (0)
+#define ADAPT_PROF_GETTER(name)
+#endif
+
 namespace adapt {
 
 constexpr int kWave = 64;

@@ -1,0 +1,28 @@
+// C entry point of the gemm contraction; the kernel template lives in contract_kernel.hpp
+#include "contract_kernel.hpp"
+
+using namespace adapt;
+
+extern "C" int adapt_fxp_gemm(adapt_ctx *ctx, int transA, int transB, int M, int N, int K, const void *A, adapt_fmt fa,
+                              int lda, const void *B, adapt_fmt fb, int ldb, void *C, int ldc, adapt_epilogue ep)
+{
+    if (!ctx || !fmt_ok(fa) || !fmt_ok(fb) || M < 0 || N < 0 || K < 0) return ADAPT_EINVAL;
+    if (M == 0 || N == 0) return ADAPT_OK;
+    if (!C || !aligned16(C) || ldc < N) return ADAPT_EINVAL;
+    if (K > 0 && (!A || !B || !aligned16(A) || !aligned16(B))) return ADAPT_EINVAL;
+    if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return ADAPT_EINVAL;
+    ContractArgs a = {};
+    a.act = A; a.wgt = B; a.out = C;
+    a.M = M; a.N = N; a.K = K;
+    a.act_es = storage_bytes(fa); a.wgt_es = storage_bytes(fb);
+    a.act_rs = transA ? 1 : lda; a.act_ks = transA ? lda : 1;
+    a.wgt_rs = transB ? ldb : 1; a.wgt_ks = transB ? 1 : ldb;
+    // vector paths need whole 16-element (k) or 4-element (row) groups inside the matrix and aligned starts
+    a.act_load = !transA ? ((K % 16 == 0 && lda % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
+                         : ((M % 4 == 0 && lda % 4 == 0 && K % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR);
+    a.wgt_load = transB ? ((K % 16 == 0 && ldb % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
+                        : ((N % 4 == 0 && ldb % 4 == 0 && K % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR);
+    a.ldc = ldc;
+    return run_contraction<OP_GEMM>(ctx, a, fa, fb, ep, 0);
+}
+

@@ -22,6 +22,7 @@
 // The four limb products accumulate in three int32 accumulators (hi*hi, cross, lo*lo); the
 // "+128" offsets are undone in the epilogue from the row sums of both operands:
 //   sum a*b = sum a'b' + 128 (sum a' + sum b') + 16384 * K,   a' = a - 128.
+#pragma once
 #include <algorithm>
 
 #include "common.hpp"
@@ -34,7 +35,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 enum { OP_GEMM = 0, OP_FWD = 1, OP_DGRAD = 2, OP_WGRAD = 3 };
 enum { LOAD_SCALAR = 0, LOAD_VEC = 1, LOAD_TRANS = 2 };
-enum { OUT_RAW32 = 0, OUT_RAW64 = 1, OUT_Q8 = 2, OUT_Q16 = 3, OUT_ATOMIC32 = 4, OUT_ATOMIC64 = 5 };
+enum { OUT_RAW32 = 0, OUT_RAW64 = 1, OUT_Q8 = 2, OUT_Q16 = 3 };
 
 constexpr int BK = 64;           // k bytes per LDS tile row
 constexpr int LDS_ROW = BK + 16; // padded row: 80 B keeps 16-byte fragment reads conflict-free
@@ -72,6 +73,7 @@ struct ContractArgs {
     int n, h, w, c, k, r, s, stride, pad, p, q;
     FastDiv div_c, div_s, div_q, div_p, div_k, div_w, div_h, div_stride;
     int k_per_split;             // multiple of BK
+    long long slab_bytes;        // split-K: split y writes its exact partial sums to out + y*slab_bytes
     long long ldc;               // output row stride in elements
     int out_mode;
     int shift, wl_o, relu, rmode;
@@ -165,6 +167,11 @@ __device__ __forceinline__ void transpose4x4(const uint32_t (&d)[4], uint32_t (&
 // tile staging: global -> registers (prefetch) -> LDS
 // A tile is ROWS x BK codes per limb plane, row stride LDS_ROW bytes.  Zero elements are stored
 // as code 0, i.e. limbs (hi = 0, lo = 0x80) in two-limb mode.
+//
+// Work is dealt in units of 16 elements.  LOAD_VEC / LOAD_SCALAR: unit = one row x 16 consecutive
+// k.  LOAD_TRANS: unit = 4 consecutive rows x 4 consecutive k (rows contiguous in memory), byte-
+// transposed in registers.  Everything that depends only on the unit's row is computed once
+// (Loader::init); per k step only the k-dependent part of the address remains.
 // ---------------------------------------------------------------------------------------------
 template <int ROWS, int LIMBS>
 struct Staged {
@@ -173,120 +180,202 @@ struct Staged {
     uint32_t lo[UNITS][4];   // two-limb only
 };
 
-template <int OP, bool ACT, int ROWS, int LIMBS>
-__device__ __forceinline__ void stage_load(const ContractArgs &a, int row0, int k0, Staged<ROWS, LIMBS> &st)
+__device__ __forceinline__ void zero_unit(uint32_t (&hi)[4], uint32_t (&lo)[4])
 {
-    const void *base = ACT ? a.act : a.wgt;
-    const int es = ACT ? a.act_es : a.wgt_es;
-    const int mode = ACT ? a.act_load : a.wgt_load;
-    constexpr int UNITS = Staged<ROWS, LIMBS>::UNITS;
 #pragma unroll
-    for (int u = 0; u < UNITS; ++u) {
-        const int id = threadIdx.x + u * kThreads;
-        uint32_t raw[8];     // up to 16 int16
-        if (mode == LOAD_VEC) {
-            // unit = one row, 16 consecutive k
-            const int row = row0 + (id >> 2), k = k0 + (id & 3) * 16;
-            const long long off = operand_offset<OP, ACT>(a, row, k);
-            if (off < 0) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) raw[i] = 0;
-            } else if (es == 1) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const int8_t *>(base) + off);
-                raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
-            } else {
-                const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const int16_t *>(base) + off);
-                const uint4 v0 = p[0], v1 = p[1];
-                raw[0] = v0.x; raw[1] = v0.y; raw[2] = v0.z; raw[3] = v0.w;
-                raw[4] = v1.x; raw[5] = v1.y; raw[6] = v1.z; raw[7] = v1.w;
-            }
-            if (es == 1) {
-                if (LIMBS == 1) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) st.hi[u][i] = raw[i];
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) split8(raw[i], st.hi[u][i], st.lo[u][i]);
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) split16(raw[2 * i], raw[2 * i + 1], st.hi[u][i], st.lo[u][i]);
-            }
-        } else if (mode == LOAD_TRANS) {
-            // unit = 4 rows x 4 k; rows are contiguous in memory.  Lane order: 4 k-quads fastest,
-            // then row quads.
-            const int kq = (id & 3) + 4 * (id / (4 * (ROWS / 4))), rq = (id >> 2) % (ROWS / 4);
-            const int row = row0 + rq * 4, k = k0 + kq * 4;
-            uint32_t dh[4], dl[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const long long off = operand_offset<OP, ACT>(a, row, k + j);
-                if (off < 0) {
-                    dh[j] = 0; dl[j] = 0x80808080u;
-                } else if (es == 1) {
-                    const uint32_t v = *reinterpret_cast<const uint32_t *>(static_cast<const int8_t *>(base) + off);
-                    if (LIMBS == 1) dh[j] = v; else split8(v, dh[j], dl[j]);
-                } else {
-                    const uint2 v = *reinterpret_cast<const uint2 *>(static_cast<const int16_t *>(base) + off);
-                    split16(v.x, v.y, dh[j], dl[j]);
-                }
-            }
-            transpose4x4(dh, st.hi[u]);
-            if (LIMBS == 2) transpose4x4(dl, st.lo[u]);
-        } else {
-            // element-wise gather: any shape, any alignment
-            const int row = row0 + (id >> 2), k = k0 + (id & 3) * 16;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint32_t h = 0, l = 0;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const long long off = operand_offset<OP, ACT>(a, row, k + 4 * i + b);
-                    int v = 0;
-                    if (off >= 0)
-                        v = es == 1 ? (int)static_cast<const int8_t *>(base)[off] : (int)static_cast<const int16_t *>(base)[off];
-                    if (LIMBS == 1) {
-                        h |= (uint32_t)(v & 0xff) << (8 * b);
-                    } else {
-                        h |= (uint32_t)((v >> 8) & 0xff) << (8 * b);
-                        l |= (uint32_t)((v & 0xff) ^ 0x80) << (8 * b);
-                    }
-                }
-                st.hi[u][i] = h;
-                st.lo[u][i] = l;
-            }
-        }
-        if (LIMBS == 2 && mode == LOAD_VEC) {
-            // (already split above)
-        }
-    }
+    for (int i = 0; i < 4; ++i) { hi[i] = 0; lo[i] = 0x80808080u; }
 }
 
-template <bool ACT, int ROWS, int LIMBS>
-__device__ __forceinline__ void stage_store(const ContractArgs &a, const Staged<ROWS, LIMBS> &st, char *tile_hi,
-                                            char *tile_lo)
-{
-    const int mode = ACT ? a.act_load : a.wgt_load;
-    constexpr int UNITS = Staged<ROWS, LIMBS>::UNITS;
+template <int OP, bool ACT, int MODE, int ROWS, int LIMBS>
+struct Loader {
+    static constexpr int UNITS = Staged<ROWS, LIMBS>::UNITS;
+    long long base[UNITS];   // row part of the element offset
+    int a0[UNITS], a1[UNITS];
+    bool valid[UNITS];
+
+    __device__ __forceinline__ static int unit_row(int id)
+    {
+        return MODE == LOAD_TRANS ? ((id >> 2) % (ROWS / 4)) * 4 : (id >> 2);
+    }
+    __device__ __forceinline__ static int unit_k(int id)
+    {
+        return MODE == LOAD_TRANS ? ((id & 3) + 4 * (id / ROWS)) * 4 : (id & 3) * 16;
+    }
+
+    __device__ __forceinline__ void init(const ContractArgs &a, int row0)
+    {
 #pragma unroll
-    for (int u = 0; u < UNITS; ++u) {
-        const int id = threadIdx.x + u * kThreads;
-        if (mode == LOAD_TRANS) {
-            const int kq = (id & 3) + 4 * (id / (4 * (ROWS / 4))), rq = (id >> 2) % (ROWS / 4);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int o = (rq * 4 + i) * LDS_ROW + kq * 4;
-                *reinterpret_cast<uint32_t *>(tile_hi + o) = st.hi[u][i];
-                if (LIMBS == 2) *reinterpret_cast<uint32_t *>(tile_lo + o) = st.lo[u][i];
+        for (int u = 0; u < UNITS; ++u) {
+            const int row = row0 + unit_row(threadIdx.x + u * kThreads);
+            valid[u] = row < (ACT ? a.M : a.N);
+            a0[u] = 0; a1[u] = 0; base[u] = 0;
+            if (MODE == LOAD_SCALAR || !valid[u]) continue;
+            if (OP == OP_GEMM) {
+                base[u] = (long long)row * (ACT ? a.act_rs : a.wgt_rs);
+            } else if (ACT && OP == OP_FWD) {
+                const uint32_t pq = fdiv(row, a.div_q), q = row - pq * a.q;
+                const uint32_t n = fdiv(pq, a.div_p), p = pq - n * a.p;
+                a0[u] = (int)p * a.stride - a.pad;
+                a1[u] = (int)q * a.stride - a.pad;
+                base[u] = (((long long)n * a.h + a0[u]) * a.w + a1[u]) * a.c;
+            } else if (ACT && OP == OP_DGRAD) {
+                const uint32_t nh = fdiv(row, a.div_w), w = row - nh * a.w;
+                const uint32_t n = fdiv(nh, a.div_h), h = nh - n * a.h;
+                a0[u] = (int)h + a.pad;
+                a1[u] = (int)w + a.pad;
+                base[u] = (long long)n * a.p * a.q * a.k;
+            } else if (ACT && OP == OP_WGRAD) {
+                base[u] = row;
+            } else if (!ACT && OP == OP_WGRAD) {
+                const uint32_t tap = fdiv(row, a.div_c), c = row - tap * a.c;
+                const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
+                a0[u] = (int)r - a.pad;
+                a1[u] = (int)s - a.pad;
+                base[u] = c;
+            } else {
+                base[u] = (long long)row * a.K;      // filters: [row][k]
             }
-        } else {
-            const int o = (id >> 2) * LDS_ROW + (id & 3) * 16;
-            *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(st.hi[u][0], st.hi[u][1], st.hi[u][2], st.hi[u][3]);
-            if (LIMBS == 2)
-                *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(st.lo[u][0], st.lo[u][1], st.lo[u][2], st.lo[u][3]);
         }
     }
-}
+
+    // element offset of (unit row, k) for the K-contiguous operands, -1 for zeros
+    __device__ __forceinline__ long long vec_offset(const ContractArgs &a, int u, int k) const
+    {
+        if (!valid[u] || k >= a.K) return -1;
+        if (ACT && OP == OP_FWD) {
+            const uint32_t tap = fdiv(k, a.div_c), c = k - tap * a.c;
+            const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
+            if ((unsigned)(a0[u] + (int)r) >= (unsigned)a.h || (unsigned)(a1[u] + (int)s) >= (unsigned)a.w) return -1;
+            return base[u] + ((long long)r * a.w + s) * a.c + c;
+        }
+        if (ACT && OP == OP_DGRAD) {
+            const uint32_t tap = fdiv(k, a.div_k), ko = k - tap * a.k;
+            const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
+            const int hp = a0[u] - (int)r, wp = a1[u] - (int)s;
+            if (hp < 0 || wp < 0) return -1;
+            uint32_t p = hp, q = wp;
+            if (a.stride != 1) {
+                p = fdiv(hp, a.div_stride); q = fdiv(wp, a.div_stride);
+                if ((int)(p * a.stride) != hp || (int)(q * a.stride) != wp) return -1;
+            }
+            if ((int)p >= a.p || (int)q >= a.q) return -1;
+            return base[u] + ((long long)p * a.q + q) * a.k + ko;
+        }
+        return base[u] + k;
+    }
+
+    __device__ __forceinline__ void load(const ContractArgs &a, int row0, int k0, Staged<ROWS, LIMBS> &st) const
+    {
+        const void *ptr = ACT ? a.act : a.wgt;
+        const int es = ACT ? a.act_es : a.wgt_es;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int id = threadIdx.x + u * kThreads;
+            const int k = k0 + unit_k(id);
+            if (MODE == LOAD_VEC) {
+                const long long off = vec_offset(a, u, k);
+                if (off < 0) {
+                    zero_unit(st.hi[u], st.lo[u]);
+                } else if (es == 1) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const int8_t *>(ptr) + off);
+                    const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (LIMBS == 1) st.hi[u][i] = raw[i]; else split8(raw[i], st.hi[u][i], st.lo[u][i]);
+                    }
+                } else {
+                    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const int16_t *>(ptr) + off);
+                    const uint4 v0 = p[0], v1 = p[1];
+                    split16(v0.x, v0.y, st.hi[u][0], st.lo[u][0]);
+                    split16(v0.z, v0.w, st.hi[u][1], st.lo[u][1]);
+                    split16(v1.x, v1.y, st.hi[u][2], st.lo[u][2]);
+                    split16(v1.z, v1.w, st.hi[u][3], st.lo[u][3]);
+                }
+            } else if (MODE == LOAD_TRANS) {
+                uint32_t dh[4], dl[4];
+                uint32_t n = 0, p = 0, q = 0;
+                if (!ACT && OP == OP_WGRAD) {
+                    const uint32_t np = fdiv(k, a.div_q);
+                    q = k - np * a.q;
+                    n = fdiv(np, a.div_p);
+                    p = np - n * a.p;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    long long off = -1;
+                    if (valid[u] && k + j < a.K) {
+                        if (OP == OP_GEMM) {
+                            off = base[u] + (long long)(k + j) * (ACT ? a.act_ks : a.wgt_ks);
+                        } else if (ACT) {                  // wgrad: dy[(n,p,q)][kout]
+                            off = base[u] + (long long)(k + j) * a.k;
+                        } else {                           // wgrad: x[n, p*st+r-pad, q*st+s-pad, c]
+                            const int hh = (int)p * a.stride + a0[u], ww = (int)q * a.stride + a1[u];
+                            if ((unsigned)hh < (unsigned)a.h && (unsigned)ww < (unsigned)a.w)
+                                off = (((long long)n * a.h + hh) * a.w + ww) * a.c + base[u];
+                        }
+                    }
+                    if (!ACT && OP == OP_WGRAD) {
+                        if (++q == (uint32_t)a.q) { q = 0; if (++p == (uint32_t)a.p) { p = 0; ++n; } }
+                    }
+                    if (off < 0) {
+                        dh[j] = 0; dl[j] = 0x80808080u;
+                    } else if (es == 1) {
+                        const uint32_t v = *reinterpret_cast<const uint32_t *>(static_cast<const int8_t *>(ptr) + off);
+                        if (LIMBS == 1) dh[j] = v; else split8(v, dh[j], dl[j]);
+                    } else {
+                        const uint2 v = *reinterpret_cast<const uint2 *>(static_cast<const int16_t *>(ptr) + off);
+                        split16(v.x, v.y, dh[j], dl[j]);
+                    }
+                }
+                transpose4x4(dh, st.hi[u]);
+                if (LIMBS == 2) transpose4x4(dl, st.lo[u]);
+            } else {
+                // element-wise gather: any shape, any alignment
+                const int row = row0 + unit_row(id);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint32_t h = 0, l = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const long long off = operand_offset<OP, ACT>(a, row, k + 4 * i + b);
+                        int v = 0;
+                        if (off >= 0)
+                            v = es == 1 ? (int)static_cast<const int8_t *>(ptr)[off] : (int)static_cast<const int16_t *>(ptr)[off];
+                        if (LIMBS == 1) {
+                            h |= (uint32_t)(v & 0xff) << (8 * b);
+                        } else {
+                            h |= (uint32_t)((v >> 8) & 0xff) << (8 * b);
+                            l |= (uint32_t)((v & 0xff) ^ 0x80) << (8 * b);
+                        }
+                    }
+                    st.hi[u][i] = h;
+                    st.lo[u][i] = l;
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ static void store(const Staged<ROWS, LIMBS> &st, char *tile_hi, char *tile_lo)
+    {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int id = threadIdx.x + u * kThreads;
+            if (MODE == LOAD_TRANS) {
+                const int o0 = unit_row(id) * LDS_ROW + unit_k(id);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    *reinterpret_cast<uint32_t *>(tile_hi + o0 + i * LDS_ROW) = st.hi[u][i];
+                    if (LIMBS == 2) *reinterpret_cast<uint32_t *>(tile_lo + o0 + i * LDS_ROW) = st.lo[u][i];
+                }
+            } else {
+                const int o = unit_row(id) * LDS_ROW + unit_k(id);
+                *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(st.hi[u][0], st.hi[u][1], st.hi[u][2], st.hi[u][3]);
+                if (LIMBS == 2)
+                    *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(st.lo[u][0], st.lo[u][1], st.lo[u][2], st.lo[u][3]);
+            }
+        }
+    }
+};
 
 // ---------------------------------------------------------------------------------------------
 // accumulator -> output format (the SR rule applied to the accumulator's low bits)
@@ -309,14 +398,14 @@ __device__ __forceinline__ int requantize_one(long long acc, int shift, int wl, 
 }
 
 // Writes 16 consecutive outputs (m, n0..n0+15) held by one lane.
-__device__ __forceinline__ void emit16(const ContractArgs &a, int m, int n0, const long long (&v)[16])
+__device__ __forceinline__ void emit16(const ContractArgs &a, void *out, int m, int n0, const long long (&v)[16])
 {
     if (m >= a.M || n0 >= a.N) return;
     const int cnt = min(16, a.N - n0);
     const long long row = (long long)m * a.ldc + n0;
     switch (a.out_mode) {
         case OUT_RAW32: {
-            int32_t *o = static_cast<int32_t *>(a.out) + row;
+            int32_t *o = static_cast<int32_t *>(out) + row;
             if (cnt == 16 && ((a.ldc | n0) & 3) == 0) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
@@ -327,18 +416,8 @@ __device__ __forceinline__ void emit16(const ContractArgs &a, int m, int n0, con
             break;
         }
         case OUT_RAW64: {
-            long long *o = static_cast<long long *>(a.out) + row;
+            long long *o = static_cast<long long *>(out) + row;
             for (int i = 0; i < cnt; ++i) o[i] = v[i];
-            break;
-        }
-        case OUT_ATOMIC32: {
-            int *o = static_cast<int *>(a.out) + row;
-            for (int i = 0; i < cnt; ++i) atomicAdd(o + i, (int)v[i]);
-            break;
-        }
-        case OUT_ATOMIC64: {
-            unsigned long long *o = static_cast<unsigned long long *>(a.out) + row;
-            for (int i = 0; i < cnt; ++i) atomicAdd(o + i, (unsigned long long)v[i]);
             break;
         }
         default: {
@@ -362,7 +441,7 @@ __device__ __forceinline__ void emit16(const ContractArgs &a, int m, int n0, con
 #pragma unroll
             for (int i = 0; i < 16; ++i) q[i] = requantize_one(v[i], a.shift, a.wl_o, a.relu, r[i]);
             if (a.out_mode == OUT_Q8) {
-                int8_t *o = static_cast<int8_t *>(a.out) + row;
+                int8_t *o = static_cast<int8_t *>(out) + row;
                 if (cnt == 16 && ((a.ldc | n0) & 15) == 0) {
                     uint32_t w[4];
 #pragma unroll
@@ -374,7 +453,7 @@ __device__ __forceinline__ void emit16(const ContractArgs &a, int m, int n0, con
                     for (int i = 0; i < cnt; ++i) o[i] = (int8_t)q[i];
                 }
             } else {
-                int16_t *o = static_cast<int16_t *>(a.out) + row;
+                int16_t *o = static_cast<int16_t *>(out) + row;
                 if (cnt == 16 && ((a.ldc | n0) & 7) == 0) {
                     uint32_t w[8];
 #pragma unroll
@@ -395,7 +474,7 @@ __device__ __forceinline__ void emit16(const ContractArgs &a, int m, int n0, con
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
 
-template <int OP, int LIMBS, int BM, int BN, int WGM, int WGN>
+template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN>
 __global__ void __launch_bounds__(kThreads)
 contract_kernel(const ContractArgs a)
 {
@@ -435,6 +514,12 @@ contract_kernel(const ContractArgs a)
 
     Staged<BM, LIMBS> sa;
     Staged<BN, LIMBS> sb;
+    Loader<OP, true, AMODE, BM, LIMBS> la;
+    Loader<OP, false, WMODE, BN, LIMBS> lb;
+    ADAPT_STAMP(0);
+    la.init(a, m0);
+    lb.init(a, n0);
+    ADAPT_STAMP(1);
     auto tiles = [&](int buf, char *&a_hi, char *&a_lo, char *&b_hi, char *&b_lo) {
         char *base = smem + buf * STAGE;
         a_hi = base; a_lo = base + TILE_A;
@@ -442,20 +527,21 @@ contract_kernel(const ContractArgs a)
     };
 
     if (ksteps > 0) {
-        stage_load<OP, true, BM, LIMBS>(a, m0, kbeg, sa);
-        stage_load<OP, false, BN, LIMBS>(a, n0, kbeg, sb);
+        la.load(a, m0, kbeg, sa);
+        lb.load(a, n0, kbeg, sb);
         char *ah, *al, *bh, *bl;
         tiles(0, ah, al, bh, bl);
-        stage_store<true, BM, LIMBS>(a, sa, ah, al);
-        stage_store<false, BN, LIMBS>(a, sb, bh, bl);
+        la.store(sa, ah, al);
+        lb.store(sb, bh, bl);
     }
     __syncthreads();
+    ADAPT_STAMP(2);
 
     for (int kt = 0; kt < ksteps; ++kt) {
         const bool more = kt + 1 < ksteps;
         if (more) {
-            stage_load<OP, true, BM, LIMBS>(a, m0, kbeg + (kt + 1) * BK, sa);
-            stage_load<OP, false, BN, LIMBS>(a, n0, kbeg + (kt + 1) * BK, sb);
+            la.load(a, m0, kbeg + (kt + 1) * BK, sa);
+            lb.load(a, n0, kbeg + (kt + 1) * BK, sb);
         }
         char *ah, *al, *bh, *bl;
         tiles(kt & 1, ah, al, bh, bl);
@@ -501,12 +587,13 @@ contract_kernel(const ContractArgs a)
         }
         if (more) {
             tiles((kt + 1) & 1, ah, al, bh, bl);
-            stage_store<true, BM, LIMBS>(a, sa, ah, al);
-            stage_store<false, BN, LIMBS>(a, sb, bh, bl);
+            la.store(sa, ah, al);
+            lb.store(sb, bh, bl);
         }
         __syncthreads();
     }
 
+    ADAPT_STAMP(3);
     // ---- epilogue -----------------------------------------------------------------------------
     // lane holds, for block (i,j): m = m0 + wm*WM + j*32 + l32, n = n0 + wn*WN + i*32 + 16*g + r
     long long corr_m[MB];
@@ -522,6 +609,7 @@ contract_kernel(const ContractArgs a)
         __syncthreads();
     }
     const long long kpad = (long long)ksteps * BK;
+    void *out = static_cast<char *>(a.out) + (long long)blockIdx.y * a.slab_bytes;
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -537,17 +625,12 @@ contract_kernel(const ContractArgs a)
                            128 * (corr_m[j] + s_n) + 16384 * kpad;
                 }
             }
-            if (ksteps > 0 || a.out_mode < OUT_ATOMIC32)
-                emit16(a, m0 + wm * WM + j * 32 + l32, n0 + wn * WN + i * 32 + 16 * g, v);
+            emit16(a, out, m0 + wm * WM + j * 32 + l32, n0 + wn * WN + i * 32 + 16 * g, v);
         }
+    ADAPT_STAMP(4);
 }
 
-// ---- helpers: zero fill, filter re-layout for dgrad, split-K finish ------------------------------
-__global__ void zero_words_kernel(uint32_t *p, size_t n)
-{
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
-}
-
+// ---- helpers: filter re-layout for dgrad, split-K finish --------------------------------------------
 // w[k][rs][c] -> wt[c][rs][k]
 template <typename T>
 __global__ void relayout_filter_kernel(const T *__restrict__ w, T *__restrict__ wt, int K, int RS, int C)
@@ -561,15 +644,16 @@ __global__ void relayout_filter_kernel(const T *__restrict__ w, T *__restrict__ 
     }
 }
 
-// split-K partial sums (int32 or int64, dense M x N) -> final output
+// split-K: sums the `splits` slabs of exact partial sums (dense M x N each) and converts
 template <typename AccT>
 __global__ void __launch_bounds__(256)
-finish_kernel(const AccT *__restrict__ ws, ContractArgs a)
+finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 {
     const size_t total = (size_t)a.M * a.N;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        long long v = 0;
+        for (int y = 0; y < splits; ++y) v += (long long)ws[(size_t)y * total + i];
         const size_t m = i / a.N, n = i % a.N;
-        const long long v = (long long)ws[i];
         const size_t o = m * (size_t)a.ldc + n;
         switch (a.out_mode) {
             case OUT_RAW32: static_cast<int32_t *>(a.out)[o] = (int32_t)v; break;
@@ -584,12 +668,14 @@ finish_kernel(const AccT *__restrict__ ws, ContractArgs a)
 }
 
 // ---- host side ---------------------------------------------------------------------------------
-template <int OP, int LIMBS, int BM, int BN, int WGM, int WGN>
+struct TileShape { int bm, bn; };
+
+template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN>
 static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const size_t lds = (size_t)2 * (BM + BN) * LDS_ROW * LIMBS;
-    auto kern = contract_kernel<OP, LIMBS, BM, BN, WGM, WGN>;
+    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, BM, BN, WGM, WGN>;
     static bool attr_done = false;
     if (!attr_done && lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -600,20 +686,46 @@ static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int spli
     return hipGetLastError();
 }
 
-template <int OP, int LIMBS>
-static hipError_t launch_op(adapt_ctx *ctx, const ContractArgs &a, int splits, int bn)
+template <int OP, int LIMBS, int AMODE, int WMODE>
+static hipError_t launch_tile(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
 {
-    if (bn == 64) return launch_variant<OP, LIMBS, 128, 64, 2, 2>(ctx, a, splits);
-    return launch_variant<OP, LIMBS, 128, 128, 2, 2>(ctx, a, splits);
+    if (AMODE == LOAD_SCALAR) return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 64, 2, 2>(ctx, a, splits);
+    if (t.bn == 64) return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 64, 2, 2>(ctx, a, splits);
+    if (t.bn == 192) return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 192, 2, 2>(ctx, a, splits);
+    return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 128, 2, 2>(ctx, a, splits);
 }
 
-struct OperandDesc {
-    const void *ptr;
-    adapt_fmt fmt;
-};
+// Instantiated load-mode pairs: the vector paths that each op can use, and one element-wise
+// fallback per op for shapes that are not multiples of the vector width.
+template <int OP, int LIMBS>
+static hipError_t launch_modes(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
+{
+    const bool scalar = a.act_load == LOAD_SCALAR || a.wgt_load == LOAD_SCALAR;
+    if (scalar) return launch_tile<OP, LIMBS, LOAD_SCALAR, LOAD_SCALAR>(ctx, a, splits, t);
+    if (OP == OP_WGRAD) return launch_tile<OP, LIMBS, LOAD_TRANS, LOAD_TRANS>(ctx, a, splits, t);
+    if (OP == OP_GEMM) {
+        if (a.act_load == LOAD_VEC && a.wgt_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_VEC>(ctx, a, splits, t);
+        if (a.act_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_TRANS>(ctx, a, splits, t);
+        if (a.wgt_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_TRANS, LOAD_VEC>(ctx, a, splits, t);
+        return launch_tile<OP, LIMBS, LOAD_TRANS, LOAD_TRANS>(ctx, a, splits, t);
+    }
+    return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_VEC>(ctx, a, splits, t);
+}
 
-// Fills the parts of ContractArgs common to all ops and runs the kernel (with split-K through the
-// workspace when K is long or the output has too few tiles to fill the GPU).
+static TileShape pick_tile(const ContractArgs &a)
+{
+    TileShape t;
+    t.bm = 128;
+    if (a.N <= 64) t.bn = 64;
+    else if (a.N % 192 == 0 || (a.N > 128 && a.N <= 192)) t.bn = 192;
+    else if ((a.N + 127) / 128 * 128 - a.N >= 64) t.bn = 64;
+    else t.bn = 128;
+    return t;
+}
+
+// Fills the parts of ContractArgs common to all ops and runs the kernel.  K is split across
+// blocks (exact partial sums in workspace slabs, summed by finish_kernel) when a single block
+// could overflow its int32 accumulators or when the output has too few tiles to fill the GPU.
 template <int OP>
 static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_fmt fb, adapt_epilogue ep,
                            size_t ws_offset /* bytes of scratch already in use */)
@@ -635,15 +747,14 @@ static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_f
     }
     if (a.M == 0 || a.N == 0) return ADAPT_OK;
 
-    const int bn = a.N <= 64 ? 64 : ((a.N + 127) / 128 * 128 - a.N >= 64 ? 64 : 128);
-    const int bm = 128;
-    const long long tiles = (long long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
+    const TileShape t = pick_tile(a);
+    const long long tiles = (long long)((a.M + t.bm - 1) / t.bm) * ((a.N + t.bn - 1) / t.bn);
     // int32 accumulators: |product| <= 2^14 per limb pair, the cross accumulator holds two per k
     const int k_cap = limbs == 1 ? 65536 : 32768;
     int splits = (a.K + k_cap - 1) / k_cap;
-    if (tiles < ctx->num_cu && a.K >= 4 * BK) {
-        const long long want = (2ll * ctx->num_cu + tiles - 1) / tiles;
-        const long long max_by_k = a.K / (2 * BK);
+    if (tiles < ctx->num_cu && a.K >= 8 * BK) {
+        const long long want = (ctx->num_cu + tiles - 1) / tiles;
+        const long long max_by_k = a.K / (4 * BK);
         splits = (int)std::max<long long>(splits, std::min(want, std::max(1ll, max_by_k)));
     }
     if (splits < 1) splits = 1;
@@ -651,34 +762,34 @@ static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_f
     if (k_per == 0) k_per = BK;
     splits = a.K == 0 ? 1 : (a.K + k_per - 1) / k_per;
     a.k_per_split = k_per;
+    a.slab_bytes = 0;
 
     hipError_t e;
     if (splits == 1) {
         a.out_mode = final_mode;
-        e = limbs == 1 ? launch_op<OP, 1>(ctx, a, 1, bn) : launch_op<OP, 2>(ctx, a, 1, bn);
+        e = limbs == 1 ? launch_modes<OP, 1>(ctx, a, 1, t) : launch_modes<OP, 2>(ctx, a, 1, t);
         return hip_status(ctx, e);
     }
-    // split-K: exact integer partial sums are added into the workspace, then converted
+    // a partial sum is bounded like the total, so the slabs use the total's accumulator type
     const size_t acc_bytes = bits == 32 ? 4 : 8;
-    const size_t need = ((ws_offset + 255) & ~(size_t)255) + (size_t)a.M * a.N * acc_bytes;
-    if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
-    char *acc = scratch(ctx) + ((ws_offset + 255) & ~(size_t)255);
-    const size_t words = (size_t)a.M * a.N * acc_bytes / 4;
-    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 4096)), dim3(256), 0, ctx->stream,
-                       reinterpret_cast<uint32_t *>(acc), words);
+    const size_t slab = (size_t)a.M * a.N * acc_bytes;
+    const size_t off = (ws_offset + 255) & ~(size_t)255;
+    if (off + slab * splits > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    char *acc = scratch(ctx) + off;
     ContractArgs part = a;
     part.out = acc;
     part.ldc = a.N;
-    part.out_mode = bits == 32 ? OUT_ATOMIC32 : OUT_ATOMIC64;
-    e = limbs == 1 ? launch_op<OP, 1>(ctx, part, splits, bn) : launch_op<OP, 2>(ctx, part, splits, bn);
+    part.slab_bytes = (long long)slab;
+    part.out_mode = bits == 32 ? OUT_RAW32 : OUT_RAW64;
+    e = limbs == 1 ? launch_modes<OP, 1>(ctx, part, splits, t) : launch_modes<OP, 2>(ctx, part, splits, t);
     if (e != hipSuccess) return hip_status(ctx, e);
     ContractArgs fin = a;
     fin.out_mode = final_mode;
     const unsigned fgrid = (unsigned)std::min<size_t>(((size_t)a.M * a.N + 255) / 256, (size_t)ctx->num_cu * 8);
     if (bits == 32)
-        hipLaunchKernelGGL(finish_kernel<int32_t>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const int32_t *>(acc), fin);
+        hipLaunchKernelGGL(finish_kernel<int32_t>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const int32_t *>(acc), splits, fin);
     else
-        hipLaunchKernelGGL(finish_kernel<long long>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const long long *>(acc), fin);
+        hipLaunchKernelGGL(finish_kernel<long long>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const long long *>(acc), splits, fin);
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -708,90 +819,3 @@ static bool check_ptrs(const void *x, const void *y, const void *z) { return x &
 
 }  // namespace adapt
 
-using namespace adapt;
-
-extern "C" int adapt_fxp_gemm(adapt_ctx *ctx, int transA, int transB, int M, int N, int K, const void *A, adapt_fmt fa,
-                              int lda, const void *B, adapt_fmt fb, int ldb, void *C, int ldc, adapt_epilogue ep)
-{
-    if (!ctx || !fmt_ok(fa) || !fmt_ok(fb) || M < 0 || N < 0 || K < 0) return ADAPT_EINVAL;
-    if (M == 0 || N == 0) return ADAPT_OK;
-    if (!C || !aligned16(C) || ldc < N) return ADAPT_EINVAL;
-    if (K > 0 && (!A || !B || !aligned16(A) || !aligned16(B))) return ADAPT_EINVAL;
-    if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return ADAPT_EINVAL;
-    ContractArgs a = {};
-    a.act = A; a.wgt = B; a.out = C;
-    a.M = M; a.N = N; a.K = K;
-    a.act_es = storage_bytes(fa); a.wgt_es = storage_bytes(fb);
-    a.act_rs = transA ? 1 : lda; a.act_ks = transA ? lda : 1;
-    a.wgt_rs = transB ? ldb : 1; a.wgt_ks = transB ? 1 : ldb;
-    // vector paths need whole 16-element (k) or 4-element (row) groups inside the matrix and aligned starts
-    a.act_load = !transA ? ((K % 16 == 0 && lda % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
-                         : ((M % 4 == 0 && lda % 4 == 0 && K % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR);
-    a.wgt_load = transB ? ((K % 16 == 0 && ldb % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
-                        : ((N % 4 == 0 && ldb % 4 == 0 && K % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR);
-    a.ldc = ldc;
-    return run_contraction<OP_GEMM>(ctx, a, fa, fb, ep, 0);
-}
-
-extern "C" int adapt_conv_fwd(adapt_ctx *ctx, adapt_conv_desc d, const void *x, adapt_fmt fx, const void *w, adapt_fmt fw,
-                              void *y, adapt_epilogue ep)
-{
-    if (!ctx || !fmt_ok(fx) || !fmt_ok(fw) || !conv_ok(d)) return ADAPT_EINVAL;
-    if (d.n == 0) return ADAPT_OK;
-    if (!check_ptrs(x, w, y)) return ADAPT_EINVAL;
-    ContractArgs a = {};
-    if (int s = fill_conv(a, d)) return s;
-    a.act = x; a.wgt = w; a.out = y;
-    a.M = d.n * a.p * a.q; a.N = d.k; a.K = d.r * d.s * d.c;
-    a.act_es = storage_bytes(fx); a.wgt_es = storage_bytes(fw);
-    a.act_load = d.c % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
-    a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
-    a.ldc = d.k;
-    return run_contraction<OP_FWD>(ctx, a, fx, fw, ep, 0);
-}
-
-extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *w,
-                                adapt_fmt fw, void *dx, adapt_epilogue ep)
-{
-    if (!ctx || !fmt_ok(fdy) || !fmt_ok(fw) || !conv_ok(d)) return ADAPT_EINVAL;
-    if (d.n == 0) return ADAPT_OK;
-    if (!check_ptrs(dy, w, dx)) return ADAPT_EINVAL;
-    ContractArgs a = {};
-    if (int s = fill_conv(a, d)) return s;
-    // filters re-laid-out as [c][r][s][kout] so that the reduction index is contiguous
-    const size_t wbytes = (size_t)d.k * d.r * d.s * d.c * storage_bytes(fw);
-    if (wbytes > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
-    void *wt = scratch(ctx);
-    const unsigned grid = (unsigned)std::min<size_t>(((size_t)d.k * d.r * d.s * d.c + 255) / 256, (size_t)ctx->num_cu * 8);
-    if (storage_bytes(fw) == 1)
-        hipLaunchKernelGGL(relayout_filter_kernel<int8_t>, dim3(grid), dim3(256), 0, ctx->stream, static_cast<const int8_t *>(w),
-                           static_cast<int8_t *>(wt), d.k, d.r * d.s, d.c);
-    else
-        hipLaunchKernelGGL(relayout_filter_kernel<int16_t>, dim3(grid), dim3(256), 0, ctx->stream, static_cast<const int16_t *>(w),
-                           static_cast<int16_t *>(wt), d.k, d.r * d.s, d.c);
-    a.act = dy; a.wgt = wt; a.out = dx;
-    a.M = d.n * d.h * d.w; a.N = d.c; a.K = d.r * d.s * d.k;
-    a.act_es = storage_bytes(fdy); a.wgt_es = storage_bytes(fw);
-    a.act_load = d.k % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
-    a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
-    a.ldc = d.c;
-    return run_contraction<OP_DGRAD>(ctx, a, fdy, fw, ep, wbytes);
-}
-
-extern "C" int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *x,
-                                adapt_fmt fx, void *dw, adapt_epilogue ep)
-{
-    if (!ctx || !fmt_ok(fdy) || !fmt_ok(fx) || !conv_ok(d)) return ADAPT_EINVAL;
-    if (!dw || !aligned16(dw)) return ADAPT_EINVAL;
-    if (d.n > 0 && !check_ptrs(dy, x, dw)) return ADAPT_EINVAL;
-    ContractArgs a = {};
-    if (int s = fill_conv(a, d)) return s;
-    a.act = dy; a.wgt = x; a.out = dw;
-    a.M = d.k; a.N = d.r * d.s * d.c; a.K = d.n * a.p * a.q;
-    a.act_es = storage_bytes(fdy); a.wgt_es = storage_bytes(fx);
-    // rows (kout / c) are the contiguous direction of both operands
-    a.act_load = (d.k % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR;
-    a.wgt_load = (d.c % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR;
-    a.ldc = a.N;
-    return run_contraction<OP_WGRAD>(ctx, a, fdy, fx, ep, 0);
-}

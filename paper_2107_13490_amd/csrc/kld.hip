@@ -2,14 +2,18 @@
 // distribution of a tensor and of its <WL_c, FL_c> quantizations, for all candidate word
 // lengths in one pass over the tensor.
 //
-// Three kernels per search, all on the context's stream, no host round trip:
-//   range   min / max of the finite elements; the last block to finish derives the bin grid
-//           (power-of-two width) and the per-candidate integer bin parameters ("plan");
-//           it also clears the global histograms.
-//   hist    one read of the tensor: reference bin + one bin per candidate for every element,
-//           counted in LDS-private histograms (per wavefront replicas when they fit), then
-//           flushed to global memory with integer atomics (order-independent, exact).
-//   kld     fp64 KL sums over the bins, selection of the lowest WL with KL < eps.
+// Four launches per search, all on the context's stream, no host round trip and no device-wide
+// fences (kernel boundaries order the phases):
+//   range    per-block min / max of the finite elements.
+//   hist     every block first reduces the range partials and derives the bin grid (power-of-two
+//            width) and the per-candidate integer bin parameters (the "plan"; block 0 also stores
+//            it for the later kernels), then reads its share of the tensor once: reference bin +
+//            one bin per candidate for every element, counted in LDS histograms (one replica per
+//            wavefront when they fit), and written to the block's own slab with plain stores.
+//   final    one block per candidate: adds the slabs of the reference row and of its own row,
+//            KL sum in fp64.
+//   select   lowest WL with KL < eps.
+// All counts are integers, so the result does not depend on the order of accumulation.
 #include <algorithm>
 
 #include "common.hpp"
@@ -18,17 +22,18 @@
 namespace adapt {
 
 constexpr int kMaxCand = 15;
-constexpr int kHistThreads = 1024;
+constexpr int kHistMaxThreads = 1024;
 constexpr int kRangeThreads = 256;
+constexpr int kFinalThreads = 256;
 constexpr size_t kLdsBudget = 144 * 1024;
 
 struct KldCand {
     int d;        // T >> d gives floor(x * 2^(FL_c + 16))
     int kind;     // 0: bin = (q >> s) - base   1: bin = (q << s) - base (32-bit)   2: 64-bit left shift
-    int s;        // shift amount (kind 0: already includes the 16 guard bits, capped at 31)
-    int base32;   // bin origin, saturated to +-2^30
-    int bmax;     // bin of the largest code of the candidate, clamped to [0, nb-1]
-    int pad;
+    int s;        // shift amount (kind 0: includes the 16 guard bits, capped at 31)
+    int lo;       // bin origin, saturated to +-2^30 ("base32")
+    int hi;       // lo + bin of the largest code of the candidate (already clamped to [0, nb-1])
+    int bmax;
     long long base64;
 };
 
@@ -39,77 +44,76 @@ struct KldPlan {
     int ncand;
     float lo, hi;
     float base_f;     // floor(lo * 2^-e), exactly representable
-    float tscale;     // 2^FLmax
-    float tmin, tmax; // code range of the widest candidate
+    float tscale;     // 2^(FLmax + 16)
+    float tmin, tmax; // code range of the widest candidate, times 2^16
     long long base;
     KldCand cand[kMaxCand];
 };
 
 __device__ inline double floor_scaled(double v, int e) { return floor(ldexp(v, -e)); }
 
-// Runs in one thread.  lo < hi are finite fp32 values.
-__device__ void make_plan(KldPlan *plan, float lo, float hi, int wl_lo, int wl_hi, int il, int bins)
+// Bin grid from the range: runs in one thread.  lo < hi are finite fp32 values.
+__device__ void make_grid(KldPlan *plan, float lo, float hi, int wl_hi, int il, int bins)
 {
-    plan->lo = lo;
-    plan->hi = hi;
-    plan->ncand = wl_hi - wl_lo + 1;
     const double dlo = lo, dhi = hi;
     // smallest e with floor(hi/2^e) - floor(lo/2^e) + 1 <= bins; the count is non-increasing in e
     int e = ilogb(dhi - dlo) - ilogb((double)bins) - 2;
     while (floor_scaled(dhi, e) - floor_scaled(dlo, e) + 1.0 > (double)bins) ++e;
     while (floor_scaled(dhi, e - 1) - floor_scaled(dlo, e - 1) + 1.0 <= (double)bins) --e;
     const double fbase = floor_scaled(dlo, e);
-    const long long base = (long long)fbase;
-    const int nb = (int)(floor_scaled(dhi, e) - fbase + 1.0);
     plan->e = e;
-    plan->nb = nb;
-    plan->base = base;
+    plan->nb = (int)(floor_scaled(dhi, e) - fbase + 1.0);
+    plan->base = (long long)fbase;
     plan->base_f = (float)fbase;
+    plan->lo = lo;
+    plan->hi = hi;
     const int flmax = wl_hi - il;
-    plan->tscale = ldexpf(1.0f, flmax);
-    plan->tmin = -ldexpf(1.0f, wl_hi - 1);
-    plan->tmax = ldexpf(1.0f, wl_hi - 1) - 1.0f;
-    const long long lim = 1ll << 30;
-    for (int c = 0; c < plan->ncand; ++c) {
-        KldCand k;
-        const int wl = wl_lo + c, fl = wl - il;
-        const long long qmax = (1ll << (wl - 1)) - 1;
-        const int sh = fl + e;
-        k.d = wl_hi - wl;
-        k.base64 = base;
-        k.base32 = (int)(base > lim ? lim : base < -lim ? -lim : base);
-        k.pad = 0;
-        long long braw;
-        if (sh >= 0) {
-            k.kind = 0;
-            k.s = 16 + sh > 31 ? 31 : 16 + sh;
-            braw = (qmax >> (sh > 62 ? 62 : sh)) - base;
-        } else {
-            const int L = -sh;
-            if (L <= 14 && base >= -lim && base <= lim) {
-                k.kind = 1;
-                k.s = L;
-            } else {
-                k.kind = 2;
-                k.s = L > 42 ? 42 : L;   // 2^42 exceeds |base| + nb, so the sign of q decides
-            }
-            braw = (long long)((unsigned long long)qmax << k.s) - base;
-        }
-        k.bmax = (int)(braw < 0 ? 0 : braw > nb - 1 ? nb - 1 : braw);
-        plan->cand[c] = k;
-    }
+    plan->tscale = ldexpf(1.0f, flmax + 16);
+    plan->tmin = -ldexpf(1.0f, wl_hi - 1 + 16);
+    plan->tmax = (ldexpf(1.0f, wl_hi - 1) - 1.0f) * 65536.0f;
     plan->degenerate = 0;
 }
 
-// ---- kernel 1: range + plan + clearing of the global histograms --------------------------------
+// Parameters of candidate c: runs in one thread per candidate after make_grid.
+__device__ void make_candidate(KldPlan *plan, int c, int wl_lo, int wl_hi, int il)
+{
+    KldCand k;
+    const int e = plan->e, nb = plan->nb;
+    const long long base = plan->base;
+    const int wl = wl_lo + c, fl = wl - il;
+    const long long qmax = (1ll << (wl - 1)) - 1;
+    const int sh = fl + e;
+    const long long lim = 1ll << 30;
+    k.d = wl_hi - wl;
+    k.base64 = base;
+    k.lo = (int)(base > lim ? lim : base < -lim ? -lim : base);
+    long long braw;
+    if (sh >= 0) {
+        k.kind = 0;
+        k.s = 16 + sh > 31 ? 31 : 16 + sh;
+        braw = (qmax >> (sh > 62 ? 62 : sh)) - base;
+    } else {
+        const int L = -sh;
+        if (L <= 14 && base >= -lim && base <= lim) {
+            k.kind = 1;
+            k.s = L;
+        } else {
+            k.kind = 2;
+            k.s = L > 42 ? 42 : L;   // 2^42 exceeds |base| + nb, so the sign of q decides
+        }
+        braw = (long long)((unsigned long long)qmax << k.s) - base;
+    }
+    k.bmax = (int)(braw < 0 ? 0 : braw > nb - 1 ? nb - 1 : braw);
+    k.hi = k.lo + k.bmax;
+    plan->cand[c] = k;
+}
+
+// ---- kernel 1: per-block range of the finite elements -----------------------------------------------
 __global__ void __launch_bounds__(kRangeThreads)
-kld_range_kernel(const float *__restrict__ w, uint64_t n, int wl_lo, int wl_hi, int il, int bins, KldPlan *plan,
-                 float *partial /* [2*gridDim.x] */, uint32_t *ticket, uint32_t *ghist, uint64_t ghist_words)
+kld_range_kernel(const float *__restrict__ w, uint64_t n, float *partial /* [2*gridDim.x] */)
 {
     const uint64_t tid = (uint64_t)blockIdx.x * kRangeThreads + threadIdx.x;
     const uint64_t nthreads = (uint64_t)gridDim.x * kRangeThreads;
-    for (uint64_t i = tid; i < ghist_words; i += nthreads) ghist[i] = 0;
-
     float lo = INFINITY, hi = -INFINITY;
     const uint64_t n4 = n >> 2;
     for (uint64_t i = tid; i < n4; i += nthreads) {
@@ -125,42 +129,16 @@ kld_range_kernel(const float *__restrict__ w, uint64_t n, int wl_lo, int wl_hi, 
     lo = wave_min_f32(lo);
     hi = wave_max_f32(hi);
     __shared__ float slo[kRangeThreads / kWave], shi[kRangeThreads / kWave];
-    __shared__ bool last;
     if ((threadIdx.x & (kWave - 1)) == 0) { slo[threadIdx.x / kWave] = lo; shi[threadIdx.x / kWave] = hi; }
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 1; i < kRangeThreads / kWave; ++i) { lo = fminf(lo, slo[i]); hi = fmaxf(hi, shi[i]); }
         partial[2 * blockIdx.x] = lo;
         partial[2 * blockIdx.x + 1] = hi;
-        __threadfence();
-        last = (atomicAdd(ticket, 1u) == gridDim.x - 1);
-    }
-    __syncthreads();
-    if (!last) return;
-    __threadfence();
-    lo = INFINITY; hi = -INFINITY;
-    for (uint32_t b = threadIdx.x; b < gridDim.x; b += kRangeThreads) {
-        lo = fminf(lo, __hip_atomic_load(partial + 2 * b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        hi = fmaxf(hi, __hip_atomic_load(partial + 2 * b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    }
-    lo = wave_min_f32(lo);
-    hi = wave_max_f32(hi);
-    if ((threadIdx.x & (kWave - 1)) == 0) { slo[threadIdx.x / kWave] = lo; shi[threadIdx.x / kWave] = hi; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int i = 1; i < kRangeThreads / kWave; ++i) { lo = fminf(lo, slo[i]); hi = fmaxf(hi, shi[i]); }
-        if (!(lo < hi)) {      // nothing finite (lo = +inf) or a single value
-            plan->degenerate = 1;
-            plan->ncand = wl_hi - wl_lo + 1;
-            plan->e = 0; plan->nb = 0; plan->base = 0; plan->lo = lo; plan->hi = hi;
-        } else {
-            make_plan(plan, lo, hi, wl_lo, wl_hi, il, bins);
-        }
-        *ticket = 0;
     }
 }
 
-// ---- kernel 2: histograms -----------------------------------------------------------------------
+// ---- kernel 2: plan + histograms ------------------------------------------------------------------------
 
 // Bin of an fp32 value: floor(v * 2^-e) - base.  Scaling by a power of two and the difference
 // of the two floored values are exact; only a complete underflow to zero loses the sign.
@@ -172,36 +150,79 @@ __device__ __forceinline__ int value_bin(float v, int e, float base_f)
     return (int)(f - base_f);
 }
 
-__device__ __forceinline__ int cand_bin(const KldCand &k, int T, int r, int nbm1)
+// bin (plus k.lo) of the candidate's code for an element with scaled value T and rounding bits r
+__device__ __forceinline__ int cand_bin_biased(const KldCand &k, int T, int r)
 {
     const int tr = (T >> k.d) + r;
-    int b;
+    int x;
     if (k.kind == 0) {
-        b = (tr >> k.s) - k.base32;
+        x = tr >> k.s;
     } else if (k.kind == 1) {
-        b = (int)((unsigned)(tr >> 16) << k.s) - k.base32;
+        x = (int)((unsigned)(tr >> 16) << k.s);
     } else {
         const long long q = (long long)(tr >> 16);
         const long long b64 = (long long)((unsigned long long)q << k.s) - k.base64;
-        b = (int)(b64 < 0 ? 0 : b64 > (long long)nbm1 ? (long long)nbm1 : b64);
+        x = (int)(b64 < 0 ? 0 : b64 > (long long)k.bmax ? (long long)k.bmax : b64) + k.lo;
     }
-    return min(max(b, 0), k.bmax);
+    return min(max(x, k.lo), k.hi);
+}
+
+__global__ void zero_words_kernel(uint32_t *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
 // LDS layout: replica-major, then row (0 = reference, 1 + c = candidate c) over [row0, row0+rows),
-// `nb` counters per row.  USE_LDS = false counts straight into global memory (bins too large).
+// `nb` counters per row.  Every block writes its counts (zeros included) to its own slab
+// slabs[block][row][bins] with plain stores: device-wide atomics on shared counters are far
+// slower than that on this GPU.  USE_LDS = false (bins too large for LDS) counts with atomics
+// straight into the block's slab, which the host has cleared.
 template <bool USE_LDS>
-__global__ void __launch_bounds__(kHistThreads)
-kld_hist_kernel(const float *__restrict__ w, uint64_t n, const KldPlan *__restrict__ plan_g, uint32_t *ghist,
-                int bins, int row0, int rows, int replicas, int mode, uint64_t seed, uint64_t stream)
+__global__ void __launch_bounds__(kHistMaxThreads)
+kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial, int range_blocks,
+                int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *slabs, int total_rows, int row0,
+                int rows, int replicas, int mode, uint64_t seed, uint64_t stream)
 {
     extern __shared__ uint32_t lds[];
     __shared__ KldPlan plan;
-    for (int i = threadIdx.x; i < (int)(sizeof(KldPlan) / 4); i += kHistThreads)
-        reinterpret_cast<uint32_t *>(&plan)[i] = reinterpret_cast<const uint32_t *>(plan_g)[i];
-    __syncthreads();
+    __shared__ float slo[kHistMaxThreads / kWave], shi[kHistMaxThreads / kWave];
+    __shared__ int row_off[kMaxCand];          // word offset of the candidate's row minus its bin origin
+    const int nthreads = blockDim.x, nwaves = nthreads / kWave;
+    const int ncand = wl_hi - wl_lo + 1;
+
+    ADAPT_STAMP(0);
+    // ---- plan (identical in every block) ----
+    {
+        float lo = INFINITY, hi = -INFINITY;
+        for (int b = threadIdx.x; b < range_blocks; b += nthreads) {
+            lo = fminf(lo, range_partial[2 * b]);
+            hi = fmaxf(hi, range_partial[2 * b + 1]);
+        }
+        lo = wave_min_f32(lo);
+        hi = wave_max_f32(hi);
+        if ((threadIdx.x & (kWave - 1)) == 0) { slo[threadIdx.x / kWave] = lo; shi[threadIdx.x / kWave] = hi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int i = 1; i < nwaves; ++i) { lo = fminf(lo, slo[i]); hi = fmaxf(hi, shi[i]); }
+            plan.ncand = ncand;
+            if (!(lo < hi)) {      // nothing finite (lo = +inf) or a single value
+                plan.degenerate = 1;
+                plan.e = 0; plan.nb = 0; plan.base = 0; plan.lo = lo; plan.hi = hi;
+            } else {
+                make_grid(&plan, lo, hi, wl_hi, il, bins);
+            }
+        }
+        __syncthreads();
+        if (!plan.degenerate && (int)threadIdx.x < ncand) make_candidate(&plan, threadIdx.x, wl_lo, wl_hi, il);
+        __syncthreads();
+        if (blockIdx.x == 0 && row0 == 0)
+            for (int i = threadIdx.x; i < (int)(sizeof(KldPlan) / 4); i += nthreads)
+                reinterpret_cast<uint32_t *>(plan_out)[i] = reinterpret_cast<const uint32_t *>(&plan)[i];
+    }
     if (plan.degenerate) return;
-    const int nb = plan.nb, nbm1 = nb - 1, e = plan.e;
+    ADAPT_STAMP(1);
+
+    const int nb = plan.nb, e = plan.e;
     const float base_f = plan.base_f, tscale = plan.tscale, tmin = plan.tmin, tmax = plan.tmax;
     const int c_begin = max(row0 - 1, 0), c_end = row0 + rows - 1;   // candidate range of this pass
     const bool do_ref = (row0 == 0);
@@ -209,30 +230,44 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const KldPlan *__restri
     int row_stride;
     if (USE_LDS) {
         const int words = rows * nb;
-        for (int i = threadIdx.x; i < words * replicas; i += kHistThreads) lds[i] = 0;
-        __syncthreads();
+        for (int i = threadIdx.x; i < words * replicas; i += nthreads) lds[i] = 0;
         hist = lds + ((threadIdx.x / kWave) % replicas) * words;
         row_stride = nb;
     } else {
-        hist = ghist + (size_t)row0 * bins;
+        hist = slabs + ((size_t)blockIdx.x * total_rows + row0) * bins;
         row_stride = bins;
     }
+    if ((int)threadIdx.x >= c_begin && (int)threadIdx.x < c_end)
+        row_off[threadIdx.x] = (threadIdx.x + 1 - row0) * row_stride - plan.cand[threadIdx.x].lo;
+    __syncthreads();
+    ADAPT_STAMP(2);
 
-    auto count = [&](float v, int r) {
-        if (!(fabsf(v) < INFINITY)) return;
-        if (do_ref) atomicAdd(&hist[value_bin(v, e, base_f)], 1u);
-        const float yc = fminf(fmaxf(v * tscale, tmin), tmax);
-        const int T = (int)floorf(yc * 65536.0f);
-        for (int c = c_begin; c < c_end; ++c)
-            atomicAdd(&hist[(c + 1 - row0) * row_stride + cand_bin(plan.cand[c], T, r, nbm1)], 1u);
+    // one group = 8 consecutive elements of one thread (one Philox block)
+    auto count_group = [&](const float (&v)[8], const int (&r)[8], int cnt) {
+        int T[8];
+        bool fin[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            fin[j] = j < cnt && fabsf(v[j]) < INFINITY;
+            T[j] = (int)floorf(fminf(fmaxf(v[j] * tscale, tmin), tmax));
+            if (do_ref && fin[j]) atomicAdd(&hist[value_bin(v[j], e, base_f)], 1u);
+        }
+        for (int c = c_begin; c < c_end; ++c) {
+            const KldCand k = plan.cand[c];
+            uint32_t *row = hist + row_off[c];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (fin[j]) atomicAdd(&row[cand_bin_biased(k, T[j], r[j])], 1u);
+        }
     };
 
     const uint64_t full_groups = n >> 3;
-    const uint64_t first = (uint64_t)blockIdx.x * kHistThreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * kHistThreads;
+    const uint64_t first = (uint64_t)blockIdx.x * nthreads + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * nthreads;
     for (uint64_t g = first; g < full_groups; g += stride) {
         const float4 a = reinterpret_cast<const float4 *>(w)[2 * g];
         const float4 b = reinterpret_cast<const float4 *>(w)[2 * g + 1];
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
         int r[8];
         if (mode == ADAPT_SR) {
             const u32x4 blk = rounding_block(seed, stream, g);
@@ -242,29 +277,44 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const KldPlan *__restri
 #pragma unroll
             for (int j = 0; j < 8; ++j) r[j] = 0x8000;
         }
-        count(a.x, r[0]); count(a.y, r[1]); count(a.z, r[2]); count(a.w, r[3]);
-        count(b.x, r[4]); count(b.y, r[5]); count(b.z, r[6]); count(b.w, r[7]);
+        count_group(v, r, 8);
     }
-    if ((n & 7) && first == 0)
-        for (uint64_t i = full_groups << 3; i < n; ++i) count(w[i], (int)rounding_bits_of(seed, stream, i, mode));
+    if ((n & 7) && first == 0) {
+        float v[8];
+        int r[8];
+        const int cnt = (int)(n & 7);
+        for (int j = 0; j < 8; ++j) {
+            const uint64_t i = (full_groups << 3) + j;
+            v[j] = j < cnt ? w[i] : 0.0f;
+            r[j] = (int)rounding_bits_of(seed, stream, i, mode);
+        }
+        count_group(v, r, cnt);
+    }
 
+    ADAPT_STAMP(3);
     if (USE_LDS) {
         __syncthreads();
+        ADAPT_STAMP(4);
         const int words = rows * nb;
-        for (int i = threadIdx.x; i < words; i += kHistThreads) {
-            uint32_t v = 0;
-            for (int rep = 0; rep < replicas; ++rep) v += lds[rep * words + i];
-            if (v) atomicAdd(&ghist[(size_t)(row0 + i / nb) * bins + (i % nb)], v);
-        }
+        for (int row = 0; row < rows; ++row)
+            for (int b = threadIdx.x; b < nb; b += nthreads) {
+                uint32_t v = 0;
+                for (int rep = 0; rep < replicas; ++rep) v += lds[rep * words + row * nb + b];
+                slabs[((size_t)blockIdx.x * total_rows + row0 + row) * bins + b] = v;
+            }
     }
+    ADAPT_STAMP(5);
 }
 
-// ---- kernel 3: KL sums and selection --------------------------------------------------------------
+// ---- kernel 3: slab sums and KL per candidate -------------------------------------------------------------
+// With the same smoothing and the same total on both sides,
+//   KL = sum_b P(b) log2(P(b)/Q(b)) = (1/D) sum_b (cp_b + alpha) log2((cp_b + alpha)/(cq_b + alpha)),
+// D = n_finite + alpha nb, so bins with cp_b == cq_b contribute nothing and need no logarithm.
 __device__ __forceinline__ double block_sum_f64(double v, double *red)
 {
     red[threadIdx.x] = v;
     __syncthreads();
-    for (int off = kHistThreads / 2; off > 0; off >>= 1) {
+    for (int off = kFinalThreads / 2; off > 0; off >>= 1) {
         if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
         __syncthreads();
     }
@@ -273,46 +323,65 @@ __device__ __forceinline__ double block_sum_f64(double v, double *red)
     return r;
 }
 
-__global__ void __launch_bounds__(kHistThreads)
-kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ ghist, int bins, int wl_lo, int il,
-                 double eps, double alpha_in, double *kld, int32_t *sel, long long *grid_out)
+__device__ __forceinline__ uint32_t slab_sum(const uint32_t *__restrict__ slabs, int nslabs, size_t slab_words, size_t idx)
 {
-    __shared__ double red[kHistThreads];
-    __shared__ double kl_s[kMaxCand];
-    const int ncand = plan->ncand;
-    const int nb = plan->nb;
-    if (plan->degenerate) {
-        if ((int)threadIdx.x < ncand) kld[threadIdx.x] = 0.0;
-        if (threadIdx.x == 0) {
-            sel[0] = wl_lo; sel[1] = wl_lo - il;
-            if (grid_out) { grid_out[0] = 0; grid_out[1] = 0; grid_out[2] = 0; }
-        }
-        return;
+    uint32_t v = 0;
+    int s = 0;
+    for (; s + 4 <= nslabs; s += 4) {
+        const uint32_t a = slabs[(size_t)s * slab_words + idx], b = slabs[(size_t)(s + 1) * slab_words + idx];
+        const uint32_t c = slabs[(size_t)(s + 2) * slab_words + idx], d = slabs[(size_t)(s + 3) * slab_words + idx];
+        v += a + b + c + d;
     }
-    double cnt = 0.0;
-    for (int b = threadIdx.x; b < nb; b += kHistThreads) cnt += (double)ghist[b];
+    for (; s < nslabs; ++s) v += slabs[(size_t)s * slab_words + idx];
+    return v;
+}
+
+__global__ void __launch_bounds__(kFinalThreads)
+kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs, int rows, int bins,
+                 double alpha_in, double *kld, uint32_t *hist_out)
+{
+    __shared__ double red[kFinalThreads];
+    const int c = blockIdx.x;
+    const int nb = plan->degenerate ? 0 : plan->nb;
+    const size_t slab_words = (size_t)rows * bins;
+    const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
+    double cnt = 0.0, acc = 0.0;
+    for (int b = threadIdx.x; b < bins; b += kFinalThreads) {
+        uint32_t uq = 0, up = 0;
+        if (b < nb) {
+            uq = slab_sum(slabs, nslabs, slab_words, b);
+            up = slab_sum(slabs, nslabs, slab_words, (size_t)(c + 1) * bins + b);
+            cnt += (double)uq;
+            if (up != uq) {
+                const double p = (double)up + alpha, q = (double)uq + alpha;
+                if (p > 0.0) acc += (q > 0.0) ? p * log2(p / q) : (double)INFINITY;
+            }
+        }
+        if (hist_out) {
+            hist_out[(size_t)(c + 1) * bins + b] = up;
+            if (c == 0) hist_out[b] = uq;
+        }
+    }
     const double nfin = block_sum_f64(cnt, red);          // exact: integers below 2^53
-    const double alpha = alpha_in < 0.0 ? 1.0 / (double)nb : alpha_in;
-    const double denom = nfin + alpha * (double)nb;
-    for (int c = 0; c < ncand; ++c) {
-        double acc = 0.0;
-        const uint32_t *cp = ghist + (size_t)(c + 1) * bins;
-        for (int b = threadIdx.x; b < nb; b += kHistThreads) {
-            const double p = ((double)cp[b] + alpha) / denom;
-            const double q = ((double)ghist[b] + alpha) / denom;
-            if (p > 0.0) acc += (q > 0.0) ? p * log2(p / q) : (double)INFINITY;
-        }
-        const double kl = block_sum_f64(acc, red);
-        if (threadIdx.x == 0) { kld[c] = kl; kl_s[c] = kl; }
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int pick = ncand - 1;
-        for (int c = 0; c < ncand; ++c)
-            if (kl_s[c] < eps) { pick = c; break; }
-        sel[0] = wl_lo + pick;
-        sel[1] = wl_lo + pick - il;
-        if (grid_out) { grid_out[0] = plan->e; grid_out[1] = plan->base; grid_out[2] = nb; }
+    const double total = block_sum_f64(acc, red);
+    if (threadIdx.x == 0) kld[c] = nb > 0 ? total / (nfin + alpha * (double)nb) : 0.0;
+}
+
+__global__ void kld_select_kernel(const KldPlan *__restrict__ plan, const double *__restrict__ kld, int wl_lo, int il,
+                                  double eps, int32_t *sel, long long *grid_out)
+{
+    if (threadIdx.x != 0) return;
+    const int ncand = plan->ncand;
+    int pick = plan->degenerate ? 0 : ncand - 1;
+    if (!plan->degenerate)
+        for (int i = 0; i < ncand; ++i)
+            if (kld[i] < eps) { pick = i; break; }
+    sel[0] = wl_lo + pick;
+    sel[1] = wl_lo + pick - il;
+    if (grid_out) {
+        grid_out[0] = plan->degenerate ? 0 : plan->e;
+        grid_out[1] = plan->degenerate ? 0 : plan->base;
+        grid_out[2] = plan->degenerate ? 0 : plan->nb;
     }
 }
 
@@ -322,42 +391,46 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
 {
     const int ncand = wl_hi - wl_lo + 1;
     const int rows = ncand + 1;
-    // workspace: plan | range partials | histograms (unless the caller supplied them)
+    // small tensors: many small blocks; large tensors: one big block per CU (more wavefronts share
+    // one set of LDS histograms)
+    const int threads = n >= ((uint64_t)1 << 20) ? 1024 : 256;
+    const uint64_t per_block = (uint64_t)threads * 8;
+    const int hist_grid = (int)std::min<uint64_t>((uint64_t)ctx->num_cu, std::max<uint64_t>(1, (n + per_block - 1) / per_block));
+    // workspace: plan | range partials | slabs
     char *ws = scratch(ctx);
     const size_t plan_bytes = (sizeof(KldPlan) + 255) & ~(size_t)255;
     const int range_grid = (int)std::min<uint64_t>((uint64_t)ctx->num_cu * 4, std::max<uint64_t>(1, (n / 4 + kRangeThreads - 1) / kRangeThreads));
     const size_t partial_bytes = ((size_t)range_grid * 8 + 255) & ~(size_t)255;
     const size_t hist_words = (size_t)rows * bins;
-    size_t need = plan_bytes + partial_bytes + (hist ? 0 : hist_words * 4);
+    const size_t need = plan_bytes + partial_bytes + (size_t)hist_grid * hist_words * 4;
     if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     KldPlan *plan = reinterpret_cast<KldPlan *>(ws);
     float *partial = reinterpret_cast<float *>(ws + plan_bytes);
-    uint32_t *ghist = hist ? hist : reinterpret_cast<uint32_t *>(ws + plan_bytes + partial_bytes);
+    uint32_t *slabs = reinterpret_cast<uint32_t *>(ws + plan_bytes + partial_bytes);
 
-    hipLaunchKernelGGL(kld_range_kernel, dim3(range_grid), dim3(kRangeThreads), 0, ctx->stream, w, n, wl_lo, wl_hi, il,
-                       bins, plan, partial, ticket(ctx, 1), ghist, (uint64_t)hist_words);
+    hipLaunchKernelGGL(kld_range_kernel, dim3(range_grid), dim3(kRangeThreads), 0, ctx->stream, w, n, partial);
 
-    if (n > 0) {
-        // enough elements per block to amortise the flush of the block's histograms
-        const uint64_t per_block = 16384;
-        const int hist_grid = (int)std::min<uint64_t>((uint64_t)ctx->num_cu, std::max<uint64_t>(1, (n + per_block - 1) / per_block));
-        const size_t row_bytes = (size_t)bins * 4;
-        if (row_bytes <= kLdsBudget) {
-            const int rows_per_pass = (int)std::min<size_t>(rows, kLdsBudget / row_bytes);
-            for (int row0 = 0; row0 < rows; row0 += rows_per_pass) {
-                const int r = std::min(rows_per_pass, rows - row0);
-                const int replicas = (int)std::min<size_t>(kHistThreads / kWave, kLdsBudget / (r * row_bytes));
-                const size_t lds = (size_t)replicas * r * row_bytes;
-                hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid), dim3(kHistThreads), lds, ctx->stream, w, n,
-                                   plan, ghist, bins, row0, r, replicas, mode, seed, stream);
-            }
-        } else {
-            hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid), dim3(kHistThreads), 0, ctx->stream, w, n, plan,
-                               ghist, bins, 0, rows, 1, mode, seed, stream);
+    const size_t row_bytes = (size_t)bins * 4;
+    if (row_bytes <= kLdsBudget) {
+        const int rows_per_pass = (int)std::min<size_t>(rows, kLdsBudget / row_bytes);
+        for (int row0 = 0; row0 < rows; row0 += rows_per_pass) {
+            const int r = std::min(rows_per_pass, rows - row0);
+            const int replicas = (int)std::min<size_t>(threads / kWave, kLdsBudget / (r * row_bytes));
+            const size_t lds = (size_t)replicas * r * row_bytes;
+            hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid), dim3(threads), lds, ctx->stream, w, n, partial,
+                               range_grid, wl_lo, wl_hi, il, bins, plan, slabs, rows, row0, r, replicas, mode, seed, stream);
         }
+    } else {
+        const size_t zw = (size_t)hist_grid * hist_words;
+        hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)std::min<size_t>((zw + 255) / 256, (size_t)ctx->num_cu * 8)),
+                           dim3(256), 0, ctx->stream, slabs, zw);
+        hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid), dim3(threads), 0, ctx->stream, w, n, partial, range_grid,
+                           wl_lo, wl_hi, il, bins, plan, slabs, rows, 0, rows, 1, mode, seed, stream);
     }
-    hipLaunchKernelGGL(kld_final_kernel, dim3(1), dim3(kHistThreads), 0, ctx->stream, plan, ghist, bins, wl_lo, il, eps,
-                       alpha, kld, sel, reinterpret_cast<long long *>(grid));
+    hipLaunchKernelGGL(kld_final_kernel, dim3(ncand), dim3(kFinalThreads), 0, ctx->stream, plan, slabs, hist_grid, rows, bins,
+                       alpha, kld, hist);
+    hipLaunchKernelGGL(kld_select_kernel, dim3(1), dim3(64), 0, ctx->stream, plan, kld, wl_lo, il, eps, sel,
+                       reinterpret_cast<long long *>(grid));
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -382,6 +455,8 @@ static hipError_t allow_big_lds()
 
 using namespace adapt;
 
+ADAPT_PROF_GETTER(adapt_debug_prof_kld)
+
 extern "C" int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t n, int wl_lo, int wl_hi, int il,
                                           int bins, double eps, double alpha, adapt_rng rng, double *kld, int32_t *sel,
                                           uint32_t *hist, int64_t *grid)
@@ -389,7 +464,7 @@ extern "C" int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t
     if (!ctx || !kld || !sel) return ADAPT_EINVAL;
     if (int s = check_search_args(wl_lo, wl_hi, il, bins, eps, alpha, rng.mode)) return s;
     if (n > 0 && (!w || !aligned16(w))) return ADAPT_EINVAL;
-    if (n >= ((uint64_t)1 << 60)) return ADAPT_EINVAL;
+    if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if (((uintptr_t)kld & 7) || ((uintptr_t)sel & 3) || ((uintptr_t)hist & 3) || ((uintptr_t)grid & 7)) return ADAPT_EINVAL;
     if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
     return search_one(ctx, w, n, wl_lo, wl_hi, il, bins, eps, alpha, rng.mode, rng.seed, rng.stream, kld, sel, hist, grid);
@@ -404,7 +479,7 @@ extern "C" int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kl
     for (int t = 0; t < count; ++t) {
         if (int s = check_search_args(wl_lo, wl_hi, items[t].il, items[t].bins, eps, alpha, mode)) return s;
         if (items[t].n > 0 && (!items[t].w || !aligned16(items[t].w))) return ADAPT_EINVAL;
-        if (items[t].n >= ((uint64_t)1 << 60)) return ADAPT_EINVAL;
+        if (items[t].n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     }
     if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
     const int ncand = wl_hi - wl_lo + 1;

@@ -2,8 +2,8 @@
 //
 // HBM-bound streaming kernel: every thread converts groups of 8 consecutive elements
 // (two 16-byte loads, one 8- or 16-byte store) with one Philox block per group.
-// nnz / saturated are reduced per wavefront, then per block, and the last block to finish
-// sums the block partials (no zero-fill launch, no floating point, order-independent).
+// nnz / saturated are reduced per wavefront, then per block; a one-block follow-up kernel sums
+// the block partials (integer, order-independent).
 #include "common.hpp"
 #include "context.hpp"
 
@@ -96,48 +96,40 @@ __device__ __forceinline__ void block_sum2(uint32_t a, uint32_t b, uint64_t &sa,
 template <typename OutT>
 __global__ void __launch_bounds__(kQThreads)
 quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, int wl, int fl, int mode,
-                uint64_t seed, uint64_t stream, uint64_t *nnz_out, uint64_t *sat_out,
-                uint64_t *partial /* [2*gridDim.x] */, uint32_t *ticket)
+                uint64_t seed, uint64_t stream, uint32_t *partial /* [gridDim.x][2] or null */)
 {
     const QuantParams p = make_quant_params(wl, fl);
     uint32_t nnz = 0, nsat = 0;
-    // a thread converts at most n/8/stride + 8 < 2^32 elements for any n < 2^61
+    // n <= 2^40 (checked by the host): per-thread and per-block counts stay below 2^32
     quantize_span<OutT>(x, q, n, p, mode, seed, stream, (uint64_t)blockIdx.x * kQThreads + threadIdx.x,
                         (uint64_t)gridDim.x * kQThreads, nnz, nsat);
-    if (nnz_out == nullptr && sat_out == nullptr) return;
+    if (partial == nullptr) return;
     uint64_t bn, bs;
     block_sum2(nnz, nsat, bn, bs);
-    __shared__ bool last;
     if (threadIdx.x == 0) {
-        partial[2 * blockIdx.x] = bn;
-        partial[2 * blockIdx.x + 1] = bs;
-        __threadfence();
-        last = (atomicAdd(ticket, 1u) == gridDim.x - 1);
+        partial[2 * blockIdx.x] = (uint32_t)bn;
+        partial[2 * blockIdx.x + 1] = (uint32_t)bs;
     }
-    __syncthreads();
-    if (!last) return;
-    __threadfence();
-    uint64_t tn = 0, ts = 0;
-    for (uint32_t b = threadIdx.x; b < gridDim.x; b += kQThreads) {
-        tn += __hip_atomic_load(partial + 2 * b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ts += __hip_atomic_load(partial + 2 * b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    // 64-bit block reduction through LDS
-    __shared__ uint64_t red[2][kQThreads];
-    red[0][threadIdx.x] = tn;
-    red[1][threadIdx.x] = ts;
-    __syncthreads();
-    for (int off = kQThreads / 2; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) {
-            red[0][threadIdx.x] += red[0][threadIdx.x + off];
-            red[1][threadIdx.x] += red[1][threadIdx.x + off];
+}
+
+// Sums the per-block partial counts (partial[block][cols]) into out[col], one wavefront per
+// column.  A separate launch: the kernel boundary makes the partials visible without fences
+// that would force the L2 to write back the freshly quantized tensor.
+__global__ void __launch_bounds__(kQThreads)
+sum_partials_kernel(const uint32_t *__restrict__ partial, int nblocks, int cols, uint64_t *out0, uint64_t *out1)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (int j = wave; j < cols; j += kQThreads / kWave) {
+        uint64_t sum = 0;
+#pragma unroll 4
+        for (int b = lane; b < nblocks; b += kWave) sum += partial[(size_t)b * cols + j];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if (lane == 0) {
+            // out0 / out1: separate destinations of columns 0 and 1 (single tensor), or out0 = array
+            uint64_t *dst = out1 == nullptr ? out0 + j : (j == 0 ? out0 : out1);
+            if (dst) *dst = sum;
         }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        if (nnz_out) *nnz_out = red[0][0];
-        if (sat_out) *sat_out = red[1][0];
-        *ticket = 0;   // ready for the next call on this context
     }
 }
 
@@ -148,15 +140,13 @@ struct QuantBatch {
     int count;
 };
 
-__global__ void zero_u64_kernel(uint64_t *p, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
-
+// nnz / saturated of every tensor: per-block partial counts in `partial[block][2*count]`, summed
+// by sum_partials_kernel (no same-address atomics, no zero-fill launch).
 __global__ void __launch_bounds__(kQThreads)
-quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint64_t *counters)
+quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint32_t *partial /* or null */)
 {
+    __shared__ uint32_t wave_part[2][kQThreads / kWave];
+    const int wave = threadIdx.x / kWave;
     // Blocks are dealt to tensors round-robin: tensor t starts at block `rot` so that small
     // tensors do not all land on block 0.
     uint32_t rot = 0;
@@ -166,7 +156,6 @@ quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint64_
         const uint32_t blocks_needed = (uint32_t)min((uint64_t)gridDim.x, (groups + kQThreads - 1) / kQThreads);
         const uint32_t slot = (blockIdx.x + gridDim.x - rot % gridDim.x) % gridDim.x;
         rot += blocks_needed;
-        if (blocks_needed == 0) continue;
         uint32_t nnz = 0, nsat = 0;
         if (slot < blocks_needed) {
             const QuantParams p = make_quant_params(it.wl, it.fl);
@@ -177,13 +166,17 @@ quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint64_
             else
                 quantize_span<int16_t>(it.x, (int16_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat);
         }
-        if (counters != nullptr && slot < blocks_needed) {
+        if (partial != nullptr) {
             nnz = wave_sum_u32(nnz);
             nsat = wave_sum_u32(nsat);
-            if ((threadIdx.x & (kWave - 1)) == 0) {
-                if (nnz) atomicAdd((unsigned long long *)&counters[2 * t], (unsigned long long)nnz);
-                if (nsat) atomicAdd((unsigned long long *)&counters[2 * t + 1], (unsigned long long)nsat);
+            if ((threadIdx.x & (kWave - 1)) == 0) { wave_part[0][wave] = nnz; wave_part[1][wave] = nsat; }
+            __syncthreads();
+            if (threadIdx.x < 2) {
+                uint32_t v = 0;
+                for (int w = 0; w < kQThreads / kWave; ++w) v += wave_part[threadIdx.x][w];
+                partial[(size_t)blockIdx.x * 2 * batch.count + 2 * t + threadIdx.x] = v;
             }
+            __syncthreads();
         }
     }
 }
@@ -207,19 +200,24 @@ extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fm
 {
     if (!ctx || !fmt_ok(fmt) || (rng.mode != ADAPT_SR && rng.mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
     if (n > 0 && (!x || !q || !aligned16(x) || !aligned16(q))) return ADAPT_EINVAL;
-    if (n >= ((uint64_t)1 << 60)) return ADAPT_EINVAL;
+    if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if ((nnz && ((uintptr_t)nnz & 7)) || (saturated && ((uintptr_t)saturated & 7))) return ADAPT_EINVAL;
     const int grid = grid_for(ctx, n);
-    uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
-    if ((size_t)grid * 16 > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    const bool count = nnz || saturated;
+    uint32_t *partial = count ? reinterpret_cast<uint32_t *>(scratch(ctx)) : nullptr;
+    if ((size_t)grid * 8 > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     if (fmt.wl <= 8)
         hipLaunchKernelGGL(quantize_kernel<int8_t>, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int8_t *)q,
-                           (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, nnz, saturated, partial,
-                           ticket(ctx, 0));
+                           (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, partial);
     else
         hipLaunchKernelGGL(quantize_kernel<int16_t>, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int16_t *)q,
-                           (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, nnz, saturated, partial,
-                           ticket(ctx, 0));
+                           (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, partial);
+    if (count) {
+        // out1 != null selects the two-destination form; a null nnz is redirected to a dummy slot
+        uint64_t *dummy = reinterpret_cast<uint64_t *>(scratch(ctx) + (((size_t)grid * 8 + 255) & ~(size_t)255));
+        hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kQThreads), 0, ctx->stream, partial, grid, 2,
+                           nnz ? nnz : dummy, saturated ? saturated : dummy + 1);
+    }
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -231,14 +229,10 @@ extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item 
     if (counters && ((uintptr_t)counters & 7)) return ADAPT_EINVAL;
     for (int t = 0; t < count; ++t) {
         const adapt_quantize_item &it = items[t];
-        if (!fmt_ok(adapt_fmt{it.wl, it.fl}) || it.n >= ((uint64_t)1 << 60)) return ADAPT_EINVAL;
+        if (!fmt_ok(adapt_fmt{it.wl, it.fl}) || it.n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
         if (it.n > 0 && (!it.x || !it.q || !aligned16(it.x) || !aligned16(it.q))) return ADAPT_EINVAL;
     }
     if (count == 0) return ADAPT_OK;
-    if (counters) {
-        hipLaunchKernelGGL(zero_u64_kernel, dim3((2 * count + 255) / 256), dim3(256), 0, ctx->stream, counters,
-                           2 * count);
-    }
     for (int base = 0; base < count; base += kMaxItems) {
         QuantBatch batch;
         batch.count = count - base < kMaxItems ? count - base : kMaxItems;
@@ -248,11 +242,16 @@ extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item 
             total_blocks += (((items[base + t].n + 7) >> 3) + kQThreads - 1) / kQThreads;
         }
         uint64_t grid = total_blocks;
-        const uint64_t cap = (uint64_t)ctx->num_cu * 8;
+        const uint64_t cap = (uint64_t)ctx->num_cu * 4;
         if (grid > cap) grid = cap;
-        if (grid == 0) continue;
+        if (grid == 0) grid = 1;     // still writes the (zero) counters
+        uint32_t *partial = counters ? reinterpret_cast<uint32_t *>(scratch(ctx)) : nullptr;
+        if (grid * 2 * batch.count * sizeof(uint32_t) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
         hipLaunchKernelGGL(quantize_batched_kernel, dim3((unsigned)grid), dim3(kQThreads), 0, ctx->stream, batch, mode,
-                           seed, counters ? counters + 2 * base : nullptr);
+                           seed, partial);
+        if (counters)
+            hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kQThreads), 0, ctx->stream, partial, (int)grid,
+                               2 * batch.count, counters + 2 * base, (uint64_t *)nullptr);
     }
     return hip_status(ctx, hipGetLastError());
 }
