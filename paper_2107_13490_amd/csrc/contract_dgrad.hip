@@ -30,6 +30,7 @@ extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *d
     a.act_load = d.k % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.ldc = d.c;
+    a.uniform_tap = d.k % 64 == 0;
     return run_contraction<OP_DGRAD>(ctx, a, fdy, fw, ep, wbytes);
 }
 

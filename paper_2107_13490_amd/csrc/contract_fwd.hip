@@ -19,6 +19,7 @@ extern "C" int adapt_conv_fwd(adapt_ctx *ctx, adapt_conv_desc d, const void *x, 
     a.act_load = d.c % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.ldc = d.k;
+    a.uniform_tap = d.c % 64 == 0;
     return run_contraction<OP_FWD>(ctx, a, fx, fw, ep, 0);
 }
 

@@ -17,11 +17,11 @@ extern "C" int adapt_fxp_gemm(adapt_ctx *ctx, int transA, int transB, int M, int
     a.act_es = storage_bytes(fa); a.wgt_es = storage_bytes(fb);
     a.act_rs = transA ? 1 : lda; a.act_ks = transA ? lda : 1;
     a.wgt_rs = transB ? ldb : 1; a.wgt_ks = transB ? 1 : ldb;
-    // vector paths need whole 16-element (k) or 4-element (row) groups inside the matrix and aligned starts
+    // vector paths need whole 16-element groups (along k, or along rows) inside the matrix and aligned starts
     a.act_load = !transA ? ((K % 16 == 0 && lda % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
-                         : ((M % 4 == 0 && lda % 4 == 0 && K % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR);
+                         : ((M % 16 == 0 && lda % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR);
     a.wgt_load = transB ? ((K % 16 == 0 && ldb % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
-                        : ((N % 4 == 0 && ldb % 4 == 0 && K % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR);
+                        : ((N % 16 == 0 && ldb % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR);
     a.ldc = ldc;
     return run_contraction<OP_GEMM>(ctx, a, fa, fb, ep, 0);
 }

@@ -12,10 +12,9 @@
 //   dgrad   (n,h,w)      c          (r,s,kout)   dy[n,(h+pad-r)/st,(w+pad-s)/st,kout]   wt[c,r,s,kout]
 //   wgrad   kout         (r,s,c)    (n,p,q)      dy[n,p,q,kout]                 x[n,p*st+r-pad,q*st+s-pad,c]
 //
-// Tiles of ACT and WGT are staged in LDS with k contiguous, and fed to
-// v_mfma_i32_32x32x32_i8 with WGT as the row operand, so that a lane ends up holding 16
-// consecutive n for one m: the requantizing epilogue then needs one Philox block per 8
-// outputs and issues 16-byte stores.
+// Tiles of ACT and WGT are staged in LDS and fed to v_mfma_i32_32x32x32_i8 with WGT as the row
+// operand, so that a lane ends up holding 16 consecutive n for one m: the requantizing
+// epilogue then needs one Philox block per 8 outputs and issues 16-byte stores.
 //
 // 9..16-bit operands are split on load into two int8 limbs, a = 256*hi + (lo - 128) + 128
 // with hi = a >> 8 and lo - 128 = (a & 255) ^ 0x80, both in [-128,127] for every int16 a.
@@ -30,15 +29,14 @@
 
 namespace adapt {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 enum { OP_GEMM = 0, OP_FWD = 1, OP_DGRAD = 2, OP_WGRAD = 3 };
-enum { LOAD_SCALAR = 0, LOAD_VEC = 1, LOAD_TRANS = 2 };
+enum { LOAD_SCALAR = 0, LOAD_VEC = 1, LOAD_ROWS = 2 };
 enum { OUT_RAW32 = 0, OUT_RAW64 = 1, OUT_Q8 = 2, OUT_Q16 = 3 };
 
-constexpr int BK = 64;           // k bytes per LDS tile row
-constexpr int LDS_ROW = BK + 16; // padded row: 80 B keeps 16-byte fragment reads conflict-free
 constexpr int kThreads = 256;
 
 // unsigned division by a run-time constant (Granlund-Montgomery round-up method), n < 2^31
@@ -72,7 +70,8 @@ struct ContractArgs {
     // conv geometry
     int n, h, w, c, k, r, s, stride, pad, p, q;
     FastDiv div_c, div_s, div_q, div_p, div_k, div_w, div_h, div_stride;
-    int k_per_split;             // multiple of BK
+    int uniform_tap;             // 64 consecutive, 64-aligned k always lie in one filter tap
+    int k_per_split;             // multiple of the kernel's stage depth
     long long slab_bytes;        // split-K: split y writes its exact partial sums to out + y*slab_bytes
     long long ldc;               // output row stride in elements
     int out_mode;
@@ -150,108 +149,104 @@ __device__ __forceinline__ void split8(uint32_t d, uint32_t &hi, uint32_t &lo)
     hi = ((d >> 7) & 0x01010101u) * 0xffu;
     lo = d ^ 0x80808080u;
 }
-// 4x4 byte transpose: in d[k] = bytes of rows 0..3 at k; out o[row] = bytes of k 0..3
-__device__ __forceinline__ void transpose4x4(const uint32_t (&d)[4], uint32_t (&o)[4])
-{
-    const uint32_t t0 = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);
-    const uint32_t t1 = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);
-    const uint32_t t2 = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
-    const uint32_t t3 = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
-    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
-    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
-    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
-    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
-}
-
 // ---------------------------------------------------------------------------------------------
 // tile staging: global -> registers (prefetch) -> LDS
-// A tile is ROWS x BK codes per limb plane, row stride LDS_ROW bytes.  Zero elements are stored
-// as code 0, i.e. limbs (hi = 0, lo = 0x80) in two-limb mode.
 //
-// Work is dealt in units of 16 elements.  LOAD_VEC / LOAD_SCALAR: unit = one row x 16 consecutive
-// k.  LOAD_TRANS: unit = 4 consecutive rows x 4 consecutive k (rows contiguous in memory), byte-
-// transposed in registers.  Everything that depends only on the unit's row is computed once
-// (Loader::init); per k step only the k-dependent part of the address remains.
+// A stage holds BKT reduction indices of both operands.  Two LDS layouts:
+//   K-major  [row][BKT + 16 bytes]: k contiguous; fragments are read with one 16-byte LDS load.
+//            Used when k is the contiguous direction in memory (LOAD_VEC, 16-byte global loads)
+//            and by the element-wise fallback (LOAD_SCALAR).
+//   R-major  [k][ROWS + 16 bytes]: rows contiguous, the operand's natural layout when the
+//            reduction index is the slow direction in memory (weight gradient, transposed GEMM
+//            operands).  Global 16-byte loads go to LDS untouched and fragments are read with
+//            ds_read_b64_tr_b8, which hands each lane the 8 k-values of its row out of an
+//            8 (k) x 16 (rows) byte block: no shuffling in registers.
+// Zero elements are stored as code 0, i.e. limbs (hi = 0, lo = 0x80) in two-limb mode.
+// Everything that depends only on the thread's rows is computed once (init); per stage only
+// the k-dependent part of the address remains, and when 64 consecutive k share one filter tap
+// (a.uniform_tap) that part is the same for the whole block and lives in scalar registers.
 // ---------------------------------------------------------------------------------------------
-template <int ROWS, int LIMBS>
-struct Staged {
-    static constexpr int UNITS = ROWS * (BK / 16) / kThreads;   // 16-element units per thread
-    uint32_t hi[UNITS][4];   // one-limb: the codes themselves
-    uint32_t lo[UNITS][4];   // two-limb only
-};
-
 __device__ __forceinline__ void zero_unit(uint32_t (&hi)[4], uint32_t (&lo)[4])
 {
 #pragma unroll
     for (int i = 0; i < 4; ++i) { hi[i] = 0; lo[i] = 0x80808080u; }
 }
 
-template <int OP, bool ACT, int MODE, int ROWS, int LIMBS>
-struct Loader {
-    static constexpr int UNITS = Staged<ROWS, LIMBS>::UNITS;
-    long long base[UNITS];   // row part of the element offset
-    int a0[UNITS], a1[UNITS];
-    bool valid[UNITS];
+// Converts 16 codes (es = 1: one uint4, es = 2: two) into limb words.
+template <int LIMBS>
+__device__ __forceinline__ void load_unit(const void *ptr, long long off, int es, uint32_t (&hi)[4], uint32_t (&lo)[4])
+{
+    if (es == 1) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const int8_t *>(ptr) + off);
+        const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (LIMBS == 1) hi[i] = raw[i]; else split8(raw[i], hi[i], lo[i]);
+        }
+    } else {
+        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const int16_t *>(ptr) + off);
+        const uint4 v0 = p[0], v1 = p[1];
+        split16(v0.x, v0.y, hi[0], lo[0]);
+        split16(v0.z, v0.w, hi[1], lo[1]);
+        split16(v1.x, v1.y, hi[2], lo[2]);
+        split16(v1.z, v1.w, hi[3], lo[3]);
+    }
+}
 
-    __device__ __forceinline__ static int unit_row(int id)
-    {
-        return MODE == LOAD_TRANS ? ((id >> 2) % (ROWS / 4)) * 4 : (id >> 2);
-    }
-    __device__ __forceinline__ static int unit_k(int id)
-    {
-        return MODE == LOAD_TRANS ? ((id & 3) + 4 * (id / ROWS)) * 4 : (id & 3) * 16;
-    }
+// ---- K-major operand: thread t owns rows (t/4) + 64*i and the 16-byte column (t%4) of every
+//      64-k sub-chunk of the stage
+template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT>
+struct LoaderK {
+    static constexpr int RPT = ROWS / 64, SUB = BKT / 64, UNITS = RPT * SUB;
+    static constexpr int ROW_BYTES = BKT + 16;
+    static constexpr int TILE_BYTES = ROWS * ROW_BYTES;
+    struct Regs { uint32_t hi[UNITS][4], lo[UNITS][4]; };   // one stage in flight
+    long long base[RPT];
+    int ra[RPT], rb[RPT];
+    bool valid[RPT];
 
     __device__ __forceinline__ void init(const ContractArgs &a, int row0)
     {
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const int row = row0 + unit_row(threadIdx.x + u * kThreads);
-            valid[u] = row < (ACT ? a.M : a.N);
-            a0[u] = 0; a1[u] = 0; base[u] = 0;
-            if (MODE == LOAD_SCALAR || !valid[u]) continue;
+        for (int i = 0; i < RPT; ++i) {
+            const int row = row0 + (threadIdx.x >> 2) + 64 * i;
+            valid[i] = row < (ACT ? a.M : a.N);
+            ra[i] = 0; rb[i] = 0; base[i] = 0;
+            if (MODE == LOAD_SCALAR || !valid[i]) continue;
             if (OP == OP_GEMM) {
-                base[u] = (long long)row * (ACT ? a.act_rs : a.wgt_rs);
+                base[i] = (long long)row * (ACT ? a.act_rs : a.wgt_rs);
             } else if (ACT && OP == OP_FWD) {
                 const uint32_t pq = fdiv(row, a.div_q), q = row - pq * a.q;
                 const uint32_t n = fdiv(pq, a.div_p), p = pq - n * a.p;
-                a0[u] = (int)p * a.stride - a.pad;
-                a1[u] = (int)q * a.stride - a.pad;
-                base[u] = (((long long)n * a.h + a0[u]) * a.w + a1[u]) * a.c;
+                ra[i] = (int)p * a.stride - a.pad;
+                rb[i] = (int)q * a.stride - a.pad;
+                base[i] = (((long long)n * a.h + ra[i]) * a.w + rb[i]) * a.c;
             } else if (ACT && OP == OP_DGRAD) {
                 const uint32_t nh = fdiv(row, a.div_w), w = row - nh * a.w;
                 const uint32_t n = fdiv(nh, a.div_h), h = nh - n * a.h;
-                a0[u] = (int)h + a.pad;
-                a1[u] = (int)w + a.pad;
-                base[u] = (long long)n * a.p * a.q * a.k;
-            } else if (ACT && OP == OP_WGRAD) {
-                base[u] = row;
-            } else if (!ACT && OP == OP_WGRAD) {
-                const uint32_t tap = fdiv(row, a.div_c), c = row - tap * a.c;
-                const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
-                a0[u] = (int)r - a.pad;
-                a1[u] = (int)s - a.pad;
-                base[u] = c;
+                ra[i] = (int)h + a.pad;
+                rb[i] = (int)w + a.pad;
+                base[i] = (long long)n * a.p * a.q * a.k;
             } else {
-                base[u] = (long long)row * a.K;      // filters: [row][k]
+                base[i] = (long long)row * a.K;      // filters: [row][k]
             }
         }
     }
 
-    // element offset of (unit row, k) for the K-contiguous operands, -1 for zeros
-    __device__ __forceinline__ long long vec_offset(const ContractArgs &a, int u, int k) const
+    // element offset of (row i, k); k64 = first k of the 64-k sub-chunk.  -1 for zeros.
+    __device__ __forceinline__ long long offset(const ContractArgs &a, int i, int k, int k64) const
     {
-        if (!valid[u] || k >= a.K) return -1;
+        if (!valid[i] || k >= a.K) return -1;
         if (ACT && OP == OP_FWD) {
-            const uint32_t tap = fdiv(k, a.div_c), c = k - tap * a.c;
+            const uint32_t tap = fdiv(a.uniform_tap ? k64 : k, a.div_c), c = k - tap * a.c;
             const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
-            if ((unsigned)(a0[u] + (int)r) >= (unsigned)a.h || (unsigned)(a1[u] + (int)s) >= (unsigned)a.w) return -1;
-            return base[u] + ((long long)r * a.w + s) * a.c + c;
+            if ((unsigned)(ra[i] + (int)r) >= (unsigned)a.h || (unsigned)(rb[i] + (int)s) >= (unsigned)a.w) return -1;
+            return base[i] + (long long)((r * a.w + s) * a.c + c);
         }
         if (ACT && OP == OP_DGRAD) {
-            const uint32_t tap = fdiv(k, a.div_k), ko = k - tap * a.k;
+            const uint32_t tap = fdiv(a.uniform_tap ? k64 : k, a.div_k), ko = k - tap * a.k;
             const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
-            const int hp = a0[u] - (int)r, wp = a1[u] - (int)s;
+            const int hp = ra[i] - (int)r, wp = rb[i] - (int)s;
             if (hp < 0 || wp < 0) return -1;
             uint32_t p = hp, q = wp;
             if (a.stride != 1) {
@@ -259,123 +254,167 @@ struct Loader {
                 if ((int)(p * a.stride) != hp || (int)(q * a.stride) != wp) return -1;
             }
             if ((int)p >= a.p || (int)q >= a.q) return -1;
-            return base[u] + ((long long)p * a.q + q) * a.k + ko;
+            return base[i] + (long long)((p * a.q + q) * a.k + ko);
         }
-        return base[u] + k;
+        return base[i] + k;
     }
 
-    __device__ __forceinline__ void load(const ContractArgs &a, int row0, int k0, Staged<ROWS, LIMBS> &st) const
+    __device__ __forceinline__ void load(const ContractArgs &a, int row0, int k0, Regs &rg) const
     {
         const void *ptr = ACT ? a.act : a.wgt;
         const int es = ACT ? a.act_es : a.wgt_es;
+        uint32_t (&hi)[UNITS][4] = rg.hi;
+        uint32_t (&lo)[UNITS][4] = rg.lo;
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const int id = threadIdx.x + u * kThreads;
-            const int k = k0 + unit_k(id);
-            if (MODE == LOAD_VEC) {
-                const long long off = vec_offset(a, u, k);
-                if (off < 0) {
-                    zero_unit(st.hi[u], st.lo[u]);
-                } else if (es == 1) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const int8_t *>(ptr) + off);
-                    const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
+        for (int sc = 0; sc < SUB; ++sc)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if (LIMBS == 1) st.hi[u][i] = raw[i]; else split8(raw[i], st.hi[u][i], st.lo[u][i]);
-                    }
+            for (int i = 0; i < RPT; ++i) {
+                const int u = sc * RPT + i;
+                const int k64 = k0 + sc * 64, k = k64 + (threadIdx.x & 3) * 16;
+                if (MODE == LOAD_VEC) {
+                    const long long off = offset(a, i, k, k64);
+                    if (off < 0) zero_unit(hi[u], lo[u]); else load_unit<LIMBS>(ptr, off, es, hi[u], lo[u]);
                 } else {
-                    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const int16_t *>(ptr) + off);
-                    const uint4 v0 = p[0], v1 = p[1];
-                    split16(v0.x, v0.y, st.hi[u][0], st.lo[u][0]);
-                    split16(v0.z, v0.w, st.hi[u][1], st.lo[u][1]);
-                    split16(v1.x, v1.y, st.hi[u][2], st.lo[u][2]);
-                    split16(v1.z, v1.w, st.hi[u][3], st.lo[u][3]);
-                }
-            } else if (MODE == LOAD_TRANS) {
-                uint32_t dh[4], dl[4];
-                uint32_t n = 0, p = 0, q = 0;
-                if (!ACT && OP == OP_WGRAD) {
-                    const uint32_t np = fdiv(k, a.div_q);
-                    q = k - np * a.q;
-                    n = fdiv(np, a.div_p);
-                    p = np - n * a.p;
-                }
+                    // element-wise gather: any shape, any alignment
+                    const int row = row0 + (threadIdx.x >> 2) + 64 * i;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    long long off = -1;
-                    if (valid[u] && k + j < a.K) {
-                        if (OP == OP_GEMM) {
-                            off = base[u] + (long long)(k + j) * (ACT ? a.act_ks : a.wgt_ks);
-                        } else if (ACT) {                  // wgrad: dy[(n,p,q)][kout]
-                            off = base[u] + (long long)(k + j) * a.k;
-                        } else {                           // wgrad: x[n, p*st+r-pad, q*st+s-pad, c]
-                            const int hh = (int)p * a.stride + a0[u], ww = (int)q * a.stride + a1[u];
-                            if ((unsigned)hh < (unsigned)a.h && (unsigned)ww < (unsigned)a.w)
-                                off = (((long long)n * a.h + hh) * a.w + ww) * a.c + base[u];
+                    for (int w = 0; w < 4; ++w) {
+                        uint32_t h = 0, l = 0;
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const long long off = operand_offset<OP, ACT>(a, row, k + 4 * w + b);
+                            int v = 0;
+                            if (off >= 0)
+                                v = es == 1 ? (int)static_cast<const int8_t *>(ptr)[off] : (int)static_cast<const int16_t *>(ptr)[off];
+                            if (LIMBS == 1) {
+                                h |= (uint32_t)(v & 0xff) << (8 * b);
+                            } else {
+                                h |= (uint32_t)((v >> 8) & 0xff) << (8 * b);
+                                l |= (uint32_t)((v & 0xff) ^ 0x80) << (8 * b);
+                            }
                         }
+                        hi[u][w] = h;
+                        lo[u][w] = l;
                     }
-                    if (!ACT && OP == OP_WGRAD) {
-                        if (++q == (uint32_t)a.q) { q = 0; if (++p == (uint32_t)a.p) { p = 0; ++n; } }
-                    }
-                    if (off < 0) {
-                        dh[j] = 0; dl[j] = 0x80808080u;
-                    } else if (es == 1) {
-                        const uint32_t v = *reinterpret_cast<const uint32_t *>(static_cast<const int8_t *>(ptr) + off);
-                        if (LIMBS == 1) dh[j] = v; else split8(v, dh[j], dl[j]);
-                    } else {
-                        const uint2 v = *reinterpret_cast<const uint2 *>(static_cast<const int16_t *>(ptr) + off);
-                        split16(v.x, v.y, dh[j], dl[j]);
-                    }
-                }
-                transpose4x4(dh, st.hi[u]);
-                if (LIMBS == 2) transpose4x4(dl, st.lo[u]);
-            } else {
-                // element-wise gather: any shape, any alignment
-                const int row = row0 + unit_row(id);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    uint32_t h = 0, l = 0;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const long long off = operand_offset<OP, ACT>(a, row, k + 4 * i + b);
-                        int v = 0;
-                        if (off >= 0)
-                            v = es == 1 ? (int)static_cast<const int8_t *>(ptr)[off] : (int)static_cast<const int16_t *>(ptr)[off];
-                        if (LIMBS == 1) {
-                            h |= (uint32_t)(v & 0xff) << (8 * b);
-                        } else {
-                            h |= (uint32_t)((v >> 8) & 0xff) << (8 * b);
-                            l |= (uint32_t)((v & 0xff) ^ 0x80) << (8 * b);
-                        }
-                    }
-                    st.hi[u][i] = h;
-                    st.lo[u][i] = l;
                 }
             }
-        }
     }
 
-    __device__ __forceinline__ static void store(const Staged<ROWS, LIMBS> &st, char *tile_hi, char *tile_lo)
+    __device__ __forceinline__ static void store(const Regs &rg, char *tile_hi, char *tile_lo)
+    {
+        const uint32_t (&hi)[UNITS][4] = rg.hi;
+        const uint32_t (&lo)[UNITS][4] = rg.lo;
+#pragma unroll
+        for (int sc = 0; sc < SUB; ++sc)
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const int u = sc * RPT + i;
+                const int o = ((threadIdx.x >> 2) + 64 * i) * ROW_BYTES + sc * 64 + (threadIdx.x & 3) * 16;
+                *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(hi[u][0], hi[u][1], hi[u][2], hi[u][3]);
+                if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(lo[u][0], lo[u][1], lo[u][2], lo[u][3]);
+            }
+    }
+
+    // MFMA fragment: the 16 k-values [32*ks + 16*g, +16) of tile row `row`
+    __device__ __forceinline__ static v4i frag(const char *tile, int row, int ks, int g)
+    {
+        return *reinterpret_cast<const v4i *>(tile + row * ROW_BYTES + ks * 32 + g * 16);
+    }
+};
+
+// ---- R-major operand: a unit is 16 consecutive rows of one k
+template <int OP, bool ACT, int ROWS, int LIMBS, int BKT>
+struct LoaderR {
+    static constexpr int CPL = ROWS / 16;                 // 16-row chunks per k line
+    static constexpr int UNITS = BKT * CPL / kThreads;
+    static constexpr int ROW_BYTES = ROWS + 16;           // bytes per k line
+    static constexpr int TILE_BYTES = BKT * ROW_BYTES;
+    struct Regs { uint32_t hi[UNITS][4], lo[UNITS][4]; };   // one stage in flight
+    long long coff[UNITS];
+    int ra[UNITS], rb[UNITS];
+    bool valid[UNITS];
+
+    __device__ __forceinline__ void init(const ContractArgs &a, int row0)
     {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             const int id = threadIdx.x + u * kThreads;
-            if (MODE == LOAD_TRANS) {
-                const int o0 = unit_row(id) * LDS_ROW + unit_k(id);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    *reinterpret_cast<uint32_t *>(tile_hi + o0 + i * LDS_ROW) = st.hi[u][i];
-                    if (LIMBS == 2) *reinterpret_cast<uint32_t *>(tile_lo + o0 + i * LDS_ROW) = st.lo[u][i];
-                }
-            } else {
-                const int o = unit_row(id) * LDS_ROW + unit_k(id);
-                *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(st.hi[u][0], st.hi[u][1], st.hi[u][2], st.hi[u][3]);
-                if (LIMBS == 2)
-                    *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(st.lo[u][0], st.lo[u][1], st.lo[u][2], st.lo[u][3]);
+            const int row = row0 + (id % CPL) * 16;
+            valid[u] = row < (ACT ? a.M : a.N);
+            ra[u] = 0; rb[u] = 0; coff[u] = row;
+            if (!ACT && OP == OP_WGRAD && valid[u]) {
+                const uint32_t tap = fdiv(row, a.div_c), c = row - tap * a.c;
+                const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
+                ra[u] = (int)r - a.pad;
+                rb[u] = (int)s - a.pad;
+                coff[u] = c;
             }
         }
     }
+
+    __device__ __forceinline__ void load(const ContractArgs &a, int row0, int k0, Regs &rg) const
+    {
+        const void *ptr = ACT ? a.act : a.wgt;
+        const int es = ACT ? a.act_es : a.wgt_es;
+        uint32_t (&hi)[UNITS][4] = rg.hi;
+        uint32_t (&lo)[UNITS][4] = rg.lo;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int id = threadIdx.x + u * kThreads;
+            const int kk = k0 + id / CPL;
+            long long off = -1;
+            if (valid[u] && kk < a.K) {
+                if (OP == OP_GEMM) {
+                    off = coff[u] + (long long)kk * (ACT ? a.act_ks : a.wgt_ks);
+                } else if (ACT) {                      // wgrad: dy[(n,p,q)][kout]
+                    off = coff[u] + (long long)kk * a.k;
+                } else {                               // wgrad: x[n, p*st+r-pad, q*st+s-pad, c]
+                    const uint32_t np = fdiv(kk, a.div_q), q = kk - np * a.q;
+                    const uint32_t n = fdiv(np, a.div_p), p = np - n * a.p;
+                    const int hh = (int)p * a.stride + ra[u], ww = (int)q * a.stride + rb[u];
+                    if ((unsigned)hh < (unsigned)a.h && (unsigned)ww < (unsigned)a.w)
+                        off = (((long long)n * a.h + hh) * a.w + ww) * a.c + coff[u];
+                }
+            }
+            if (off < 0) zero_unit(hi[u], lo[u]); else load_unit<LIMBS>(ptr, off, es, hi[u], lo[u]);
+        }
+    }
+
+    __device__ __forceinline__ static void store(const Regs &rg, char *tile_hi, char *tile_lo)
+    {
+        const uint32_t (&hi)[UNITS][4] = rg.hi;
+        const uint32_t (&lo)[UNITS][4] = rg.lo;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int id = threadIdx.x + u * kThreads;
+            const int o = (id / CPL) * ROW_BYTES + (id % CPL) * 16;
+            *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(hi[u][0], hi[u][1], hi[u][2], hi[u][3]);
+            if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(lo[u][0], lo[u][1], lo[u][2], lo[u][3]);
+        }
+    }
+
+    // MFMA fragment for the 32 rows starting at row32: lane l gets row row32 + l%32, k-values
+    // [32*ks + 16*(l/32), +16).  Within a group of 16 lanes, ds_read_b64_tr_b8 gives lane i byte j
+    // = byte (i%8) of the 8 bytes addressed by lane 2j + i/8; so lane 2j + h of the group points at
+    // rows [8h, 8h+8) of k line j.
+    __device__ __forceinline__ static v4i frag(const char *tile, int row32, int ks, int lane)
+    {
+        const int grp = lane >> 4, a = lane & 15;
+        const int k = ks * 32 + 16 * (grp >> 1) + (a >> 1);
+        const char *p = tile + k * ROW_BYTES + row32 + 16 * (grp & 1) + 8 * (a & 1);
+        typedef v2i __attribute__((address_space(3))) * lds_v2i;
+        const v2i x = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(p));
+        const v2i y = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(p + 8 * ROW_BYTES));
+        v4i f;
+        f[0] = x[0]; f[1] = x[1]; f[2] = y[0]; f[3] = y[1];
+        return f;
+    }
 };
+
+template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT>
+struct LoaderSelect { typedef LoaderK<OP, ACT, MODE, ROWS, LIMBS, BKT> type; };
+template <int OP, bool ACT, int ROWS, int LIMBS, int BKT>
+struct LoaderSelect<OP, ACT, LOAD_ROWS, ROWS, LIMBS, BKT> { typedef LoaderR<OP, ACT, ROWS, LIMBS, BKT> type; };
 
 // ---------------------------------------------------------------------------------------------
 // accumulator -> output format (the SR rule applied to the accumulator's low bits)
@@ -397,18 +436,28 @@ __device__ __forceinline__ int requantize_one(long long acc, int shift, int wl, 
     return (int)(q > qmax ? qmax : q < qmin ? qmin : q);
 }
 
-// Writes 16 consecutive outputs (m, n0..n0+15) held by one lane.
-__device__ __forceinline__ void emit16(const ContractArgs &a, void *out, int m, int n0, const long long (&v)[16])
+// one-limb accumulators fit 32 bits with room for the rounding bits (|acc| <= 2^30)
+__device__ __forceinline__ int requantize_i32(int acc, int shift, int qmin, int qmax, int relu, uint32_t r16)
+{
+    int q = shift <= 16 ? (acc + (int)(r16 >> (16 - shift))) >> shift : ((acc >> (shift - 16)) + (int)r16) >> 16;
+    if (relu) q = max(q, 0);
+    return min(max(q, qmin), qmax);
+}
+
+// Writes RUN (4 or 16) consecutive outputs (m, n0 .. n0+RUN-1) held by one lane.  FITS32: the
+// values are int32 accumulators of the one-limb path.
+template <int RUN, bool FITS32>
+__device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m, int n0, const long long (&v)[RUN])
 {
     if (m >= a.M || n0 >= a.N) return;
-    const int cnt = min(16, a.N - n0);
+    const int cnt = min(RUN, a.N - n0);
     const long long row = (long long)m * a.ldc + n0;
     switch (a.out_mode) {
         case OUT_RAW32: {
             int32_t *o = static_cast<int32_t *>(out) + row;
-            if (cnt == 16 && ((a.ldc | n0) & 3) == 0) {
+            if (cnt == RUN && ((a.ldc | n0) & 3) == 0) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < RUN / 4; ++i)
                     reinterpret_cast<int4 *>(o)[i] = make_int4((int)v[4 * i], (int)v[4 * i + 1], (int)v[4 * i + 2], (int)v[4 * i + 3]);
             } else {
                 for (int i = 0; i < cnt; ++i) o[i] = (int32_t)v[i];
@@ -417,49 +466,69 @@ __device__ __forceinline__ void emit16(const ContractArgs &a, void *out, int m, 
         }
         case OUT_RAW64: {
             long long *o = static_cast<long long *>(out) + row;
-            for (int i = 0; i < cnt; ++i) o[i] = v[i];
+            if (cnt == RUN && ((a.ldc | n0) & 1) == 0) {
+#pragma unroll
+                for (int i = 0; i < RUN / 2; ++i) reinterpret_cast<longlong2 *>(o)[i] = make_longlong2(v[2 * i], v[2 * i + 1]);
+            } else {
+                for (int i = 0; i < cnt; ++i) o[i] = v[i];
+            }
             break;
         }
         default: {
             // requantize: output element index = m * N + n (row-major over the logical tensor)
             const uint64_t idx0 = (uint64_t)m * (uint64_t)a.N + (uint64_t)n0;
-            uint32_t r[16];
+            uint32_t r[RUN];
             if (a.rmode != ADAPT_SR) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) r[i] = 0x8000u;
-            } else if ((idx0 & 7) == 0) {
+                for (int i = 0; i < RUN; ++i) r[i] = 0x8000u;
+            } else if (RUN == 16 && (idx0 & 7) == 0) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
+                for (int h = 0; h < RUN / 8; ++h) {
                     const u32x4 b = rounding_block(a.seed, a.stream, (idx0 >> 3) + h);
                     r[8 * h + 0] = b.x & 0xffffu; r[8 * h + 1] = b.x >> 16; r[8 * h + 2] = b.y & 0xffffu; r[8 * h + 3] = b.y >> 16;
                     r[8 * h + 4] = b.z & 0xffffu; r[8 * h + 5] = b.z >> 16; r[8 * h + 6] = b.w & 0xffffu; r[8 * h + 7] = b.w >> 16;
                 }
+            } else if (RUN == 4 && (idx0 & 3) == 0) {
+                const u32x4 b = rounding_block(a.seed, a.stream, idx0 >> 3);
+                const uint32_t w0 = (idx0 & 4) ? b.z : b.x, w1 = (idx0 & 4) ? b.w : b.y;
+                r[0] = w0 & 0xffffu; r[1] = w0 >> 16; r[2] = w1 & 0xffffu; r[3] = w1 >> 16;
             } else {
-                for (int i = 0; i < 16; ++i) r[i] = rounding_bits_of(a.seed, a.stream, idx0 + i, ADAPT_SR);
+                for (int i = 0; i < RUN; ++i) r[i] = rounding_bits_of(a.seed, a.stream, idx0 + i, ADAPT_SR);
             }
-            int q[16];
+            int q[RUN];
+            if (FITS32 && a.shift >= 1) {
+                const int qmax = (1 << (a.wl_o - 1)) - 1, qmin = -(1 << (a.wl_o - 1));
 #pragma unroll
-            for (int i = 0; i < 16; ++i) q[i] = requantize_one(v[i], a.shift, a.wl_o, a.relu, r[i]);
+                for (int i = 0; i < RUN; ++i) q[i] = requantize_i32((int)v[i], a.shift, qmin, qmax, a.relu, r[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < RUN; ++i) q[i] = requantize_one(v[i], a.shift, a.wl_o, a.relu, r[i]);
+            }
             if (a.out_mode == OUT_Q8) {
                 int8_t *o = static_cast<int8_t *>(out) + row;
-                if (cnt == 16 && ((a.ldc | n0) & 15) == 0) {
-                    uint32_t w[4];
+                if (cnt == RUN && ((a.ldc | n0) & (RUN - 1)) == 0) {
+                    uint32_t w[RUN / 4];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < RUN / 4; ++i)
                         w[i] = (uint32_t)(q[4 * i] & 0xff) | ((uint32_t)(q[4 * i + 1] & 0xff) << 8) |
                                ((uint32_t)(q[4 * i + 2] & 0xff) << 16) | ((uint32_t)(q[4 * i + 3] & 0xff) << 24);
-                    *reinterpret_cast<uint4 *>(o) = make_uint4(w[0], w[1], w[2], w[3]);
+                    if (RUN == 16) *reinterpret_cast<uint4 *>(o) = make_uint4(w[0], w[RUN / 4 > 1 ? 1 : 0], w[RUN / 4 > 2 ? 2 : 0], w[RUN / 4 > 3 ? 3 : 0]);
+                    else *reinterpret_cast<uint32_t *>(o) = w[0];
                 } else {
                     for (int i = 0; i < cnt; ++i) o[i] = (int8_t)q[i];
                 }
             } else {
                 int16_t *o = static_cast<int16_t *>(out) + row;
-                if (cnt == 16 && ((a.ldc | n0) & 7) == 0) {
-                    uint32_t w[8];
+                if (cnt == RUN && ((a.ldc | n0) & (RUN == 16 ? 7 : 3)) == 0) {
+                    uint32_t w[RUN / 2];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) w[i] = (uint32_t)(q[2 * i] & 0xffff) | ((uint32_t)q[2 * i + 1] << 16);
-                    reinterpret_cast<uint4 *>(o)[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                    reinterpret_cast<uint4 *>(o)[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                    for (int i = 0; i < RUN / 2; ++i) w[i] = (uint32_t)(q[2 * i] & 0xffff) | ((uint32_t)q[2 * i + 1] << 16);
+                    if (RUN == 16) {
+                        reinterpret_cast<uint4 *>(o)[0] = make_uint4(w[0], w[1], w[RUN / 2 > 2 ? 2 : 0], w[RUN / 2 > 3 ? 3 : 0]);
+                        reinterpret_cast<uint4 *>(o)[1] = make_uint4(w[RUN / 2 > 4 ? 4 : 0], w[RUN / 2 > 5 ? 5 : 0], w[RUN / 2 > 6 ? 6 : 0], w[RUN / 2 > 7 ? 7 : 0]);
+                    } else {
+                        *reinterpret_cast<uint2 *>(o) = make_uint2(w[0], w[1]);
+                    }
                 } else {
                     for (int i = 0; i < cnt; ++i) o[i] = (int16_t)q[i];
                 }
@@ -470,34 +539,43 @@ __device__ __forceinline__ void emit16(const ContractArgs &a, void *out, int m, 
 
 // ---------------------------------------------------------------------------------------------
 // the kernel: block tile BM x BN, 4 wavefronts in a WGM x WGN grid, wave tile (BM/WGM) x (BN/WGN)
-// built from 32x32 MFMA blocks.
+// built from 32x32 MFMA blocks; BKT reduction indices per stage.  One LDS stage: the next
+// stage's global loads are in flight (in registers) while the MFMAs of the current one run;
+// several blocks per CU cover the rest of the load latency and each other's epilogues.
+// (A 4-deep register pipeline with 64-wide stages was measured slower: the extra registers cost
+// the second resident block and the per-stage barrier and store overhead tripled.)
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN>
+template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN, int BKT>
 __global__ void __launch_bounds__(kThreads)
 contract_kernel(const ContractArgs a)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per block");
+    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT>::type LB;
+    constexpr bool A_R = AMODE == LOAD_ROWS, W_R = WMODE == LOAD_ROWS;
     constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
     constexpr int MB = WM / 32, NB = WN / 32;       // 32x32 blocks per wave
-    constexpr int TILE_A = BM * LDS_ROW, TILE_B = BN * LDS_ROW;
-    constexpr int STAGE = (TILE_A + TILE_B) * LIMBS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *const a_hi = smem, *const a_lo = smem + LA::TILE_BYTES;
+    char *const b_hi = smem + LA::TILE_BYTES * LIMBS, *const b_lo = b_hi + LB::TILE_BYTES;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, g = lane >> 5;
-    // MFMA row i of the WGT operand carries n_local = perm(i), so that accumulator register r of
-    // a lane is n_local = 16*g + r
+    // K-major WGT operand: MFMA row i carries n_local = nperm(i), so that accumulator register r
+    // of a lane is n_local = 16*g + r (16 consecutive outputs per lane).  R-major WGT operand:
+    // rows arrive in order, register r is n_local = 8*(r/4) + 4*g + r%4 (runs of 4).
     const int nperm = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
+    const int wrow = W_R ? l32 : nperm;
 
     const int tiles_n = (a.N + BN - 1) / BN;
     const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int kbeg = blockIdx.y * a.k_per_split;
     const int kend = min(a.K, kbeg + a.k_per_split);
-    const int ksteps = (kend - kbeg + BK - 1) / BK;
+    const int ksteps = (kend - kbeg + BKT - 1) / BKT;
 
     v16i acc_hh[NB][MB], acc_x[NB][MB], acc_ll[NB][MB];
 #pragma unroll
@@ -512,103 +590,97 @@ contract_kernel(const ContractArgs a)
 #pragma unroll
     for (int i = 0; i < NB; ++i) sum_n[i] = 0;
 
-    Staged<BM, LIMBS> sa;
-    Staged<BN, LIMBS> sb;
-    Loader<OP, true, AMODE, BM, LIMBS> la;
-    Loader<OP, false, WMODE, BN, LIMBS> lb;
     ADAPT_STAMP(0);
+    LA la;
+    LB lb;
     la.init(a, m0);
     lb.init(a, n0);
     ADAPT_STAMP(1);
-    auto tiles = [&](int buf, char *&a_hi, char *&a_lo, char *&b_hi, char *&b_lo) {
-        char *base = smem + buf * STAGE;
-        a_hi = base; a_lo = base + TILE_A;
-        b_hi = base + TILE_A * LIMBS; b_lo = b_hi + TILE_B;
-    };
-
+    typename LA::Regs ra;
+    typename LB::Regs rb;
     if (ksteps > 0) {
-        la.load(a, m0, kbeg, sa);
-        lb.load(a, n0, kbeg, sb);
-        char *ah, *al, *bh, *bl;
-        tiles(0, ah, al, bh, bl);
-        la.store(sa, ah, al);
-        lb.store(sb, bh, bl);
+        la.load(a, m0, kbeg, ra);
+        lb.load(a, n0, kbeg, rb);
     }
-    __syncthreads();
     ADAPT_STAMP(2);
 
     for (int kt = 0; kt < ksteps; ++kt) {
-        const bool more = kt + 1 < ksteps;
-        if (more) {
-            la.load(a, m0, kbeg + (kt + 1) * BK, sa);
-            lb.load(a, n0, kbeg + (kt + 1) * BK, sb);
-        }
-        char *ah, *al, *bh, *bl;
-        tiles(kt & 1, ah, al, bh, bl);
-#pragma unroll
-        for (int ks = 0; ks < BK / 32; ++ks) {
-            const int koff = ks * 32 + g * 16;
-            v4i fa_h[MB], fa_l[MB], fb_h[NB], fb_l[NB];
-#pragma unroll
-            for (int j = 0; j < MB; ++j) {
-                const int o = (wm * WM + j * 32 + l32) * LDS_ROW + koff;
-                fa_h[j] = *reinterpret_cast<const v4i *>(ah + o);
-                if (LIMBS == 2) fa_l[j] = *reinterpret_cast<const v4i *>(al + o);
+        {
+            __syncthreads();                 // every wavefront is done with the previous stage
+            LA::store(ra, a_hi, a_lo);
+            LB::store(rb, b_hi, b_lo);
+            __syncthreads();
+            if (kt + 1 < ksteps) {
+                la.load(a, m0, kbeg + (kt + 1) * BKT, ra);
+                lb.load(a, n0, kbeg + (kt + 1) * BKT, rb);
             }
 #pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const int o = (wn * WN + i * 32 + nperm) * LDS_ROW + koff;
-                fb_h[i] = *reinterpret_cast<const v4i *>(bh + o);
-                if (LIMBS == 2) fb_l[i] = *reinterpret_cast<const v4i *>(bl + o);
-            }
-#pragma unroll
-            for (int i = 0; i < NB; ++i)
+            for (int ks = 0; ks < BKT / 32; ++ks) {
+                v4i fa_h[MB], fa_l[MB], fb_h[NB], fb_l[NB];
 #pragma unroll
                 for (int j = 0; j < MB; ++j) {
-                    acc_hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_h[j], acc_hh[i][j], 0, 0, 0);
-                    if (LIMBS == 2) {
-                        acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_l[j], acc_x[i][j], 0, 0, 0);
-                        acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_h[j], acc_x[i][j], 0, 0, 0);
-                        acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_l[j], acc_ll[i][j], 0, 0, 0);
+                    if constexpr (A_R) {
+                        fa_h[j] = LA::frag(a_hi, wm * WM + j * 32, ks, lane);
+                        if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32, ks, lane);
+                    } else {
+                        fa_h[j] = LA::frag(a_hi, wm * WM + j * 32 + l32, ks, g);
+                        if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32 + l32, ks, g);
                     }
                 }
-            if (LIMBS == 2) {
 #pragma unroll
-                for (int j = 0; j < MB; ++j)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        sum_m[j] += 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e]);
+                for (int i = 0; i < NB; ++i) {
+                    if constexpr (W_R) {
+                        fb_h[i] = LB::frag(b_hi, wn * WN + i * 32, ks, lane);
+                        if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32, ks, lane);
+                    } else {
+                        fb_h[i] = LB::frag(b_hi, wn * WN + i * 32 + nperm, ks, g);
+                        if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32 + nperm, ks, g);
+                    }
+                }
 #pragma unroll
                 for (int i = 0; i < NB; ++i)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        sum_n[i] += 256 * dot4_ones((uint32_t)fb_h[i][e]) + dot4_ones((uint32_t)fb_l[i][e]);
+                    for (int j = 0; j < MB; ++j) {
+                        acc_hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_h[j], acc_hh[i][j], 0, 0, 0);
+                        if (LIMBS == 2) {
+                            acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_l[j], acc_x[i][j], 0, 0, 0);
+                            acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_h[j], acc_x[i][j], 0, 0, 0);
+                            acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_l[j], acc_ll[i][j], 0, 0, 0);
+                        }
+                    }
+                if (LIMBS == 2) {
+#pragma unroll
+                    for (int j = 0; j < MB; ++j)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            sum_m[j] += 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e]);
+#pragma unroll
+                    for (int i = 0; i < NB; ++i)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            sum_n[i] += 256 * dot4_ones((uint32_t)fb_h[i][e]) + dot4_ones((uint32_t)fb_l[i][e]);
+                }
             }
         }
-        if (more) {
-            tiles((kt + 1) & 1, ah, al, bh, bl);
-            la.store(sa, ah, al);
-            lb.store(sb, bh, bl);
-        }
-        __syncthreads();
     }
 
     ADAPT_STAMP(3);
     // ---- epilogue -----------------------------------------------------------------------------
-    // lane holds, for block (i,j): m = m0 + wm*WM + j*32 + l32, n = n0 + wn*WN + i*32 + 16*g + r
+    // lane holds, for block (i,j): m = m0 + wm*WM + j*32 + l32 and 16 values of n (see above)
     long long corr_m[MB];
     int *sn = reinterpret_cast<int *>(smem);          // [4 waves][NB][32] n-side sums
     if (LIMBS == 2) {
+        __syncthreads();                              // the tiles are no longer read
 #pragma unroll
         for (int j = 0; j < MB; ++j) corr_m[j] = (long long)(sum_m[j] + __shfl_xor(sum_m[j], 32, 64));
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int t = sum_n[i] + __shfl_xor(sum_n[i], 32, 64);
-            if (g == 0) sn[(wave * NB + i) * 32 + nperm] = t;
+            if (g == 0) sn[(wave * NB + i) * 32 + wrow] = t;
         }
         __syncthreads();
     }
-    const long long kpad = (long long)ksteps * BK;
+    const long long kpad = (long long)ksteps * BKT;
     void *out = static_cast<char *>(a.out) + (long long)blockIdx.y * a.slab_bytes;
 #pragma unroll
     for (int i = 0; i < NB; ++i)
@@ -620,12 +692,36 @@ contract_kernel(const ContractArgs a)
                 if (LIMBS == 1) {
                     v[r] = acc_hh[i][j][r];
                 } else {
-                    const long long s_n = sn[(wave * NB + i) * 32 + 16 * g + r];
+                    const int nl = W_R ? 8 * (r >> 2) + 4 * g + (r & 3) : 16 * g + r;
+                    const long long s_n = sn[(wave * NB + i) * 32 + nl];
                     v[r] = ((long long)acc_hh[i][j][r] << 16) + ((long long)acc_x[i][j][r] << 8) + (long long)acc_ll[i][j][r] +
                            128 * (corr_m[j] + s_n) + 16384 * kpad;
                 }
             }
-            emit16(a, out, m0 + wm * WM + j * 32 + l32, n0 + wn * WN + i * 32 + 16 * g, v);
+            const int m = m0 + wm * WM + j * 32 + l32, nb0 = n0 + wn * WN + i * 32;
+            if constexpr (W_R) {
+                // lanes l and l^32 hold interleaved runs of 4 of the same output row: swap halves
+                // so that each ends up with 16 consecutive n (lane/32 = 0: n 0..15, 1: n 16..31)
+                long long recv[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const long long send = g == 0 ? v[8 + t] : v[t];
+                    const int lo = __shfl_xor((int)(uint32_t)send, 32, 64);
+                    const int hi = LIMBS == 1 ? (lo >> 31) : __shfl_xor((int)(send >> 32), 32, 64);
+                    recv[t] = ((long long)hi << 32) | (uint32_t)lo;
+                }
+                long long w[16];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    w[t] = g == 0 ? v[t] : recv[t];
+                    w[4 + t] = g == 0 ? recv[t] : v[8 + t];
+                    w[8 + t] = g == 0 ? v[4 + t] : recv[4 + t];
+                    w[12 + t] = g == 0 ? recv[4 + t] : v[12 + t];
+                }
+                emit_run<16, LIMBS == 1>(a, out, m, nb0 + 16 * g, w);
+            } else {
+                emit_run<16, LIMBS == 1>(a, out, m, nb0 + 16 * g, v);
+            }
         }
     ADAPT_STAMP(4);
 }
@@ -652,7 +748,15 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
     const size_t total = (size_t)a.M * a.N;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         long long v = 0;
-        for (int y = 0; y < splits; ++y) v += (long long)ws[(size_t)y * total + i];
+        int y = 0;
+        for (; y + 8 <= splits; y += 8) {      // eight independent loads in flight
+            AccT t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = ws[(size_t)(y + u) * total + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v += (long long)t[u];
+        }
+        for (; y < splits; ++y) v += (long long)ws[(size_t)y * total + i];
         const size_t m = i / a.N, n = i % a.N;
         const size_t o = m * (size_t)a.ldc + n;
         switch (a.out_mode) {
@@ -668,14 +772,16 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 }
 
 // ---- host side ---------------------------------------------------------------------------------
-struct TileShape { int bm, bn; };
+struct TileShape { int bm, bn, bkt; };
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN>
+template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN, int BKT>
 static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
+    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    const size_t lds = (size_t)2 * (BM + BN) * LDS_ROW * LIMBS;
-    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, BM, BN, WGM, WGN>;
+    const size_t lds = (size_t)(LA::TILE_BYTES + LB::TILE_BYTES) * LIMBS;
+    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, BM, BN, WGM, WGN, BKT>;
     static bool attr_done = false;
     if (!attr_done && lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -686,13 +792,33 @@ static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int spli
     return hipGetLastError();
 }
 
+// Tile shapes: BM in {64, 128}, BN in {64, 128} and (one-limb convolutions only) 192; stage depth
+// 64, or 192 for the vector paths of the convolutions.
+template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BKT>
+static hipError_t launch_bn(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
+{
+    if (t.bn == 64) return launch_variant<OP, LIMBS, AMODE, WMODE, BM, 64, 2, 2, BKT>(ctx, a, splits);
+    if constexpr (LIMBS == 1 && OP != OP_GEMM)
+        if (t.bn == 192) return launch_variant<OP, LIMBS, AMODE, WMODE, BM, 192, 2, 2, BKT>(ctx, a, splits);
+    return launch_variant<OP, LIMBS, AMODE, WMODE, BM, 128, 2, 2, BKT>(ctx, a, splits);
+}
+
 template <int OP, int LIMBS, int AMODE, int WMODE>
 static hipError_t launch_tile(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
 {
-    if (AMODE == LOAD_SCALAR) return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 64, 2, 2>(ctx, a, splits);
-    if (t.bn == 64) return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 64, 2, 2>(ctx, a, splits);
-    if (t.bn == 192) return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 192, 2, 2>(ctx, a, splits);
-    return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 128, 2, 2>(ctx, a, splits);
+    if constexpr (AMODE == LOAD_SCALAR) {
+        return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 64, 2, 2, 64>(ctx, a, splits);
+    } else if constexpr (OP == OP_GEMM) {
+        if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 64>(ctx, a, splits, t);
+        return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 64>(ctx, a, splits, t);
+    } else {
+        if (t.bkt == 192) {
+            if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 192>(ctx, a, splits, t);
+            return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 192>(ctx, a, splits, t);
+        }
+        if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 64>(ctx, a, splits, t);
+        return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 64>(ctx, a, splits, t);
+    }
 }
 
 // Instantiated load-mode pairs: the vector paths that each op can use, and one element-wise
@@ -702,24 +828,35 @@ static hipError_t launch_modes(adapt_ctx *ctx, const ContractArgs &a, int splits
 {
     const bool scalar = a.act_load == LOAD_SCALAR || a.wgt_load == LOAD_SCALAR;
     if (scalar) return launch_tile<OP, LIMBS, LOAD_SCALAR, LOAD_SCALAR>(ctx, a, splits, t);
-    if (OP == OP_WGRAD) return launch_tile<OP, LIMBS, LOAD_TRANS, LOAD_TRANS>(ctx, a, splits, t);
-    if (OP == OP_GEMM) {
+    if constexpr (OP == OP_WGRAD) {
+        return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_ROWS>(ctx, a, splits, t);
+    } else if constexpr (OP == OP_GEMM) {
         if (a.act_load == LOAD_VEC && a.wgt_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_VEC>(ctx, a, splits, t);
-        if (a.act_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_TRANS>(ctx, a, splits, t);
-        if (a.wgt_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_TRANS, LOAD_VEC>(ctx, a, splits, t);
-        return launch_tile<OP, LIMBS, LOAD_TRANS, LOAD_TRANS>(ctx, a, splits, t);
+        if (a.act_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_ROWS>(ctx, a, splits, t);
+        if (a.wgt_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_VEC>(ctx, a, splits, t);
+        return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_ROWS>(ctx, a, splits, t);
+    } else {
+        return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_VEC>(ctx, a, splits, t);
     }
-    return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_VEC>(ctx, a, splits, t);
 }
 
-static TileShape pick_tile(const ContractArgs &a)
+template <int OP>
+static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
 {
     TileShape t;
-    t.bm = 128;
-    if (a.N <= 64) t.bn = 64;
-    else if (a.N % 192 == 0 || (a.N > 128 && a.N <= 192)) t.bn = 192;
+    const bool scalar = a.act_load == LOAD_SCALAR || a.wgt_load == LOAD_SCALAR;
+    if (a.N <= 64 || scalar) t.bn = 64;
+    else if (OP != OP_GEMM && limbs == 1 && (a.N % 192 == 0 || (a.N > 128 && a.N <= 192))) t.bn = 192;   // 3 x 96 accumulators do not fit
+                                                                                                           // the register file
     else if ((a.N + 127) / 128 * 128 - a.N >= 64) t.bn = 64;
     else t.bn = 128;
+    // deeper stages cut the number of exposed load latencies; zero padding of the last stage must stay small
+    t.bkt = (OP != OP_GEMM && !scalar && (a.K % 192 == 0 || a.K >= 3072)) ? 192 : 64;
+    // Small problems: several resident blocks per CU hide each other's load latency and epilogue,
+    // so halve the tile when 128-row tiles would leave fewer than two blocks per CU.  (Split-K
+    // contractions get their parallelism from the splits instead.)
+    const long long tiles128 = (long long)((a.M + 127) / 128) * ((a.N + t.bn - 1) / t.bn);
+    t.bm = (!scalar && OP != OP_WGRAD && tiles128 < 2 * num_cu && a.M > 64) ? 64 : 128;
     return t;
 }
 
@@ -747,19 +884,19 @@ static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_f
     }
     if (a.M == 0 || a.N == 0) return ADAPT_OK;
 
-    const TileShape t = pick_tile(a);
+    const TileShape t = pick_tile<OP>(a, limbs, ctx->num_cu);
     const long long tiles = (long long)((a.M + t.bm - 1) / t.bm) * ((a.N + t.bn - 1) / t.bn);
     // int32 accumulators: |product| <= 2^14 per limb pair, the cross accumulator holds two per k
     const int k_cap = limbs == 1 ? 65536 : 32768;
     int splits = (a.K + k_cap - 1) / k_cap;
-    if (tiles < ctx->num_cu && a.K >= 8 * BK) {
+    if (tiles < ctx->num_cu && a.K >= 8 * t.bkt) {
         const long long want = (ctx->num_cu + tiles - 1) / tiles;
-        const long long max_by_k = a.K / (4 * BK);
+        const long long max_by_k = a.K / (4 * t.bkt);
         splits = (int)std::max<long long>(splits, std::min(want, std::max(1ll, max_by_k)));
     }
     if (splits < 1) splits = 1;
-    int k_per = ((a.K + splits - 1) / splits + BK - 1) / BK * BK;
-    if (k_per == 0) k_per = BK;
+    int k_per = ((a.K + splits - 1) / splits + t.bkt - 1) / t.bkt * t.bkt;
+    if (k_per == 0) k_per = t.bkt;
     splits = a.K == 0 ? 1 : (a.K + k_per - 1) / k_per;
     a.k_per_split = k_per;
     a.slab_bytes = 0;

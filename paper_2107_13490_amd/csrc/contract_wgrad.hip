@@ -17,8 +17,8 @@ extern "C" int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *d
     a.M = d.k; a.N = d.r * d.s * d.c; a.K = d.n * a.p * a.q;
     a.act_es = storage_bytes(fdy); a.wgt_es = storage_bytes(fx);
     // rows (kout / c) are the contiguous direction of both operands
-    a.act_load = (d.k % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR;
-    a.wgt_load = (d.c % 4 == 0) ? LOAD_TRANS : LOAD_SCALAR;
+    a.act_load = (d.k % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR;
+    a.wgt_load = (d.c % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR;
     a.ldc = a.N;
     return run_contraction<OP_WGRAD>(ctx, a, fdy, fx, ep, 0);
 }

@@ -10,9 +10,9 @@
 //            it for the later kernels), then reads its share of the tensor once: reference bin +
 //            one bin per candidate for every element, counted in LDS histograms (one replica per
 //            wavefront when they fit), and written to the block's own slab with plain stores.
-//   final    one block per candidate: adds the slabs of the reference row and of its own row,
-//            KL sum in fp64.
-//   select   lowest WL with KL < eps.
+//   final    blocks of (256 bins, candidate): add the slabs of the reference row and of the
+//            candidate's row, partial KL sums in fp64.
+//   select   adds the partial sums in a fixed order, lowest WL with KL < eps.
 // All counts are integers, so the result does not depend on the order of accumulation.
 #include <algorithm>
 
@@ -24,7 +24,6 @@ namespace adapt {
 constexpr int kMaxCand = 15;
 constexpr int kHistMaxThreads = 1024;
 constexpr int kRangeThreads = 256;
-constexpr int kFinalThreads = 256;
 constexpr size_t kLdsBudget = 144 * 1024;
 
 struct KldCand {
@@ -150,21 +149,34 @@ __device__ __forceinline__ int value_bin(float v, int e, float base_f)
     return (int)(f - base_f);
 }
 
-// bin (plus k.lo) of the candidate's code for an element with scaled value T and rounding bits r
-__device__ __forceinline__ int cand_bin_biased(const KldCand &k, int T, int r)
+// Adds the 8 elements of a group to candidate k's row.  x = bin + k.lo of the candidate's code for
+// an element with scaled value T and rounding bits r; `inc` is 0 for non-finite elements (their
+// clamped bin is a valid address).  The branch on the candidate's kind is uniform and outside
+// the element loop, so the loop bodies are straight-line code.
+__device__ __forceinline__ void count_candidate(const KldCand &k, uint32_t *row, const int (&T)[8], const int (&r)[8],
+                                                const uint32_t (&inc)[8])
 {
-    const int tr = (T >> k.d) + r;
-    int x;
     if (k.kind == 0) {
-        x = tr >> k.s;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int x = ((T[j] >> k.d) + r[j]) >> k.s;
+            atomicAdd(&row[min(max(x, k.lo), k.hi)], inc[j]);
+        }
     } else if (k.kind == 1) {
-        x = (int)((unsigned)(tr >> 16) << k.s);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int x = (int)((unsigned)(((T[j] >> k.d) + r[j]) >> 16) << k.s);
+            atomicAdd(&row[min(max(x, k.lo), k.hi)], inc[j]);
+        }
     } else {
-        const long long q = (long long)(tr >> 16);
-        const long long b64 = (long long)((unsigned long long)q << k.s) - k.base64;
-        x = (int)(b64 < 0 ? 0 : b64 > (long long)k.bmax ? (long long)k.bmax : b64) + k.lo;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const long long q = (long long)(((T[j] >> k.d) + r[j]) >> 16);
+            const long long b64 = (long long)((unsigned long long)q << k.s) - k.base64;
+            const int x = (int)(b64 < 0 ? 0 : b64 > (long long)k.bmax ? (long long)k.bmax : b64) + k.lo;
+            atomicAdd(&row[x], inc[j]);
+        }
     }
-    return min(max(x, k.lo), k.hi);
 }
 
 __global__ void zero_words_kernel(uint32_t *p, size_t n)
@@ -230,7 +242,9 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     int row_stride;
     if (USE_LDS) {
         const int words = rows * nb;
-        for (int i = threadIdx.x; i < words * replicas; i += nthreads) lds[i] = 0;
+        const int total = words * replicas;
+        for (int i = threadIdx.x; i < total / 4; i += nthreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
+        if ((int)threadIdx.x < (total & 3)) lds[(total & ~3) + threadIdx.x] = 0;
         hist = lds + ((threadIdx.x / kWave) % replicas) * words;
         row_stride = nb;
     } else {
@@ -245,20 +259,15 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     // one group = 8 consecutive elements of one thread (one Philox block)
     auto count_group = [&](const float (&v)[8], const int (&r)[8], int cnt) {
         int T[8];
-        bool fin[8];
+        uint32_t inc[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            fin[j] = j < cnt && fabsf(v[j]) < INFINITY;
-            T[j] = (int)floorf(fminf(fmaxf(v[j] * tscale, tmin), tmax));
-            if (do_ref && fin[j]) atomicAdd(&hist[value_bin(v[j], e, base_f)], 1u);
+            const bool fin = j < cnt && fabsf(v[j]) < INFINITY;
+            inc[j] = fin ? 1u : 0u;
+            T[j] = (int)floorf(fminf(fmaxf(v[j] * tscale, tmin), tmax));      // NaN -> tmin
+            if (do_ref) atomicAdd(&hist[fin ? value_bin(v[j], e, base_f) : 0], inc[j]);
         }
-        for (int c = c_begin; c < c_end; ++c) {
-            const KldCand k = plan.cand[c];
-            uint32_t *row = hist + row_off[c];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (fin[j]) atomicAdd(&row[cand_bin_biased(k, T[j], r[j])], 1u);
-        }
+        for (int c = c_begin; c < c_end; ++c) count_candidate(plan.cand[c], hist + row_off[c], T, r, inc);
     };
 
     const uint64_t full_groups = n >> 3;
@@ -296,86 +305,123 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
         __syncthreads();
         ADAPT_STAMP(4);
         const int words = rows * nb;
-        for (int row = 0; row < rows; ++row)
-            for (int b = threadIdx.x; b < nb; b += nthreads) {
+        // slab rows are 16-byte aligned (bins % 4 == 0 is not required: the tail is written singly)
+        const int nb4 = (bins % 4 == 0) ? nb / 4 : 0;
+        for (int row = 0; row < rows; ++row) {
+            uint32_t *dst = slabs + ((size_t)blockIdx.x * total_rows + row0 + row) * bins;
+            for (int q = threadIdx.x; q < nb4; q += nthreads) {
+                uint32_t v[4] = {0, 0, 0, 0};
+                for (int rep = 0; rep < replicas; ++rep)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] += lds[rep * words + row * nb + 4 * q + j];
+                reinterpret_cast<uint4 *>(dst)[q] = make_uint4(v[0], v[1], v[2], v[3]);
+            }
+            for (int b = 4 * nb4 + threadIdx.x; b < nb; b += nthreads) {
                 uint32_t v = 0;
                 for (int rep = 0; rep < replicas; ++rep) v += lds[rep * words + row * nb + b];
-                slabs[((size_t)blockIdx.x * total_rows + row0 + row) * bins + b] = v;
+                dst[b] = v;
             }
+        }
     }
     ADAPT_STAMP(5);
 }
 
-// ---- kernel 3: slab sums and KL per candidate -------------------------------------------------------------
+// ---- kernel 3: slab sums and partial KL sums ------------------------------------------------------------------
 // With the same smoothing and the same total on both sides,
 //   KL = sum_b P(b) log2(P(b)/Q(b)) = (1/D) sum_b (cp_b + alpha) log2((cp_b + alpha)/(cq_b + alpha)),
 // D = n_finite + alpha nb, so bins with cp_b == cq_b contribute nothing and need no logarithm.
-__device__ __forceinline__ double block_sum_f64(double v, double *red)
-{
-    red[threadIdx.x] = v;
-    __syncthreads();
-    for (int off = kFinalThreads / 2; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
-        __syncthreads();
-    }
-    const double r = red[0];
-    __syncthreads();
-    return r;
-}
+// Block (x, c) handles bins [x*kChunk, (x+1)*kChunk) of candidate c: its 1024 threads are 4 groups
+// of 256; group s adds every 4th slab (all loads independent), LDS combines the groups.  The
+// partial sums go to part[c][x] = (sum of terms, sum of reference counts); kld_select_kernel adds
+// them in a fixed order.
+constexpr int kChunk = 256;
+constexpr int kFinalGroups = 4;
 
-__device__ __forceinline__ uint32_t slab_sum(const uint32_t *__restrict__ slabs, int nslabs, size_t slab_words, size_t idx)
-{
-    uint32_t v = 0;
-    int s = 0;
-    for (; s + 4 <= nslabs; s += 4) {
-        const uint32_t a = slabs[(size_t)s * slab_words + idx], b = slabs[(size_t)(s + 1) * slab_words + idx];
-        const uint32_t c = slabs[(size_t)(s + 2) * slab_words + idx], d = slabs[(size_t)(s + 3) * slab_words + idx];
-        v += a + b + c + d;
-    }
-    for (; s < nslabs; ++s) v += slabs[(size_t)s * slab_words + idx];
-    return v;
-}
-
-__global__ void __launch_bounds__(kFinalThreads)
+__global__ void __launch_bounds__(kChunk * kFinalGroups)
 kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs, int rows, int bins,
-                 double alpha_in, double *kld, uint32_t *hist_out)
+                 double alpha_in, double *part, uint32_t *hist_out)
 {
-    __shared__ double red[kFinalThreads];
-    const int c = blockIdx.x;
+    __shared__ uint32_t cq_s[kFinalGroups][kChunk], cp_s[kFinalGroups][kChunk];
+    __shared__ double red[2][kChunk];
+    const int c = blockIdx.y, nchunks = gridDim.x;
+    const int lane = threadIdx.x % kChunk, grp = threadIdx.x / kChunk;
+    const int b = blockIdx.x * kChunk + lane;
     const int nb = plan->degenerate ? 0 : plan->nb;
     const size_t slab_words = (size_t)rows * bins;
-    const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
-    double cnt = 0.0, acc = 0.0;
-    for (int b = threadIdx.x; b < bins; b += kFinalThreads) {
-        uint32_t uq = 0, up = 0;
-        if (b < nb) {
-            uq = slab_sum(slabs, nslabs, slab_words, b);
-            up = slab_sum(slabs, nslabs, slab_words, (size_t)(c + 1) * bins + b);
-            cnt += (double)uq;
-            if (up != uq) {
-                const double p = (double)up + alpha, q = (double)uq + alpha;
-                if (p > 0.0) acc += (q > 0.0) ? p * log2(p / q) : (double)INFINITY;
+    uint32_t uq = 0, up = 0;
+    if (b < nb) {
+        const uint32_t *pq = slabs + b, *pp = slabs + (size_t)(c + 1) * bins + b;
+        int sidx = grp;
+        for (; sidx + 3 * kFinalGroups < nslabs; sidx += 4 * kFinalGroups) {
+            uint32_t tq[4], tp[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                tq[u] = pq[(size_t)(sidx + u * kFinalGroups) * slab_words];
+                tp[u] = pp[(size_t)(sidx + u * kFinalGroups) * slab_words];
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { uq += tq[u]; up += tp[u]; }
         }
-        if (hist_out) {
+        for (; sidx < nslabs; sidx += kFinalGroups) {
+            uq += pq[(size_t)sidx * slab_words];
+            up += pp[(size_t)sidx * slab_words];
+        }
+    }
+    cq_s[grp][lane] = uq;
+    cp_s[grp][lane] = up;
+    __syncthreads();
+    const bool lead = grp == 0;          // group 0 finishes; the others only keep the barriers company
+    double term = 0.0;
+    if (lead) {
+#pragma unroll
+        for (int s = 1; s < kFinalGroups; ++s) { uq += cq_s[s][lane]; up += cp_s[s][lane]; }
+        if (hist_out && b < bins) {
             hist_out[(size_t)(c + 1) * bins + b] = up;
             if (c == 0) hist_out[b] = uq;
         }
+        const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
+        if (b < nb && up != uq) {
+            const double p = (double)up + alpha, q = (double)uq + alpha;
+            if (p > 0.0) term = (q > 0.0) ? p * log2(p / q) : (double)INFINITY;
+        }
+        red[0][lane] = term;
+        red[1][lane] = (double)uq;
     }
-    const double nfin = block_sum_f64(cnt, red);          // exact: integers below 2^53
-    const double total = block_sum_f64(acc, red);
-    if (threadIdx.x == 0) kld[c] = nb > 0 ? total / (nfin + alpha * (double)nb) : 0.0;
+    for (int off = kChunk / 2; off > 0; off >>= 1) {
+        __syncthreads();
+        if (lead && lane < off) { red[0][lane] += red[0][lane + off]; red[1][lane] += red[1][lane + off]; }
+    }
+    if (lead && lane == 0) {
+        part[2 * ((size_t)c * nchunks + blockIdx.x)] = red[0][0];
+        part[2 * ((size_t)c * nchunks + blockIdx.x) + 1] = red[1][0];
+    }
 }
 
-__global__ void kld_select_kernel(const KldPlan *__restrict__ plan, const double *__restrict__ kld, int wl_lo, int il,
-                                  double eps, int32_t *sel, long long *grid_out)
+__global__ void kld_select_kernel(const KldPlan *__restrict__ plan, const double *__restrict__ part, int nchunks,
+                                  int wl_lo, int il, double eps, double alpha_in, double *kld, int32_t *sel,
+                                  long long *grid_out)
 {
-    if (threadIdx.x != 0) return;
+    __shared__ double kl_s[kMaxCand];
     const int ncand = plan->ncand;
+    const int nb = plan->degenerate ? 0 : plan->nb;
+    const int c = threadIdx.x;
+    if (c < ncand) {
+        double total = 0.0, nfin = 0.0;
+        for (int x = 0; x < nchunks; ++x) {
+            total += part[2 * ((size_t)c * nchunks + x)];
+            nfin += part[2 * ((size_t)c * nchunks + x) + 1];     // exact: integers below 2^53
+        }
+        const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
+        const double kl = nb > 0 ? total / (nfin + alpha * (double)nb) : 0.0;
+        kld[c] = kl;
+        kl_s[c] = kl;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
     int pick = plan->degenerate ? 0 : ncand - 1;
     if (!plan->degenerate)
         for (int i = 0; i < ncand; ++i)
-            if (kld[i] < eps) { pick = i; break; }
+            if (kl_s[i] < eps) { pick = i; break; }
     sel[0] = wl_lo + pick;
     sel[1] = wl_lo + pick - il;
     if (grid_out) {
@@ -393,20 +439,23 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
     const int rows = ncand + 1;
     // small tensors: many small blocks; large tensors: one big block per CU (more wavefronts share
     // one set of LDS histograms)
-    const int threads = n >= ((uint64_t)1 << 20) ? 1024 : 256;
+    const int threads = n >= ((uint64_t)1 << 20) ? 1024 : n >= ((uint64_t)1 << 16) ? 512 : 256;
     const uint64_t per_block = (uint64_t)threads * 8;
     const int hist_grid = (int)std::min<uint64_t>((uint64_t)ctx->num_cu, std::max<uint64_t>(1, (n + per_block - 1) / per_block));
-    // workspace: plan | range partials | slabs
+    // workspace: plan | range partials | KL partials | slabs
     char *ws = scratch(ctx);
+    const int nchunks = (bins + kChunk - 1) / kChunk;
+    const size_t klpart_bytes = ((size_t)ncand * nchunks * 16 + 255) & ~(size_t)255;
     const size_t plan_bytes = (sizeof(KldPlan) + 255) & ~(size_t)255;
     const int range_grid = (int)std::min<uint64_t>((uint64_t)ctx->num_cu * 4, std::max<uint64_t>(1, (n / 4 + kRangeThreads - 1) / kRangeThreads));
     const size_t partial_bytes = ((size_t)range_grid * 8 + 255) & ~(size_t)255;
     const size_t hist_words = (size_t)rows * bins;
-    const size_t need = plan_bytes + partial_bytes + (size_t)hist_grid * hist_words * 4;
+    const size_t need = plan_bytes + partial_bytes + klpart_bytes + (size_t)hist_grid * hist_words * 4;
     if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     KldPlan *plan = reinterpret_cast<KldPlan *>(ws);
     float *partial = reinterpret_cast<float *>(ws + plan_bytes);
-    uint32_t *slabs = reinterpret_cast<uint32_t *>(ws + plan_bytes + partial_bytes);
+    double *klpart = reinterpret_cast<double *>(ws + plan_bytes + partial_bytes);
+    uint32_t *slabs = reinterpret_cast<uint32_t *>(ws + plan_bytes + partial_bytes + klpart_bytes);
 
     hipLaunchKernelGGL(kld_range_kernel, dim3(range_grid), dim3(kRangeThreads), 0, ctx->stream, w, n, partial);
 
@@ -427,10 +476,10 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
         hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid), dim3(threads), 0, ctx->stream, w, n, partial, range_grid,
                            wl_lo, wl_hi, il, bins, plan, slabs, rows, 0, rows, 1, mode, seed, stream);
     }
-    hipLaunchKernelGGL(kld_final_kernel, dim3(ncand), dim3(kFinalThreads), 0, ctx->stream, plan, slabs, hist_grid, rows, bins,
-                       alpha, kld, hist);
-    hipLaunchKernelGGL(kld_select_kernel, dim3(1), dim3(64), 0, ctx->stream, plan, kld, wl_lo, il, eps, sel,
-                       reinterpret_cast<long long *>(grid));
+    hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks, ncand), dim3(kChunk * kFinalGroups), 0, ctx->stream, plan, slabs,
+                       hist_grid, rows, bins, alpha, klpart, hist);
+    hipLaunchKernelGGL(kld_select_kernel, dim3(1), dim3(64), 0, ctx->stream, plan, klpart, nchunks, wl_lo, il, eps, alpha,
+                       kld, sel, reinterpret_cast<long long *>(grid));
     return hip_status(ctx, hipGetLastError());
 }
 
