@@ -12,7 +12,9 @@ SOURCES = ["api.hip", "quantize.hip", "kld.hip", "contract_gemm.hip", "contract_
            "contract_dgrad.hip", "contract_wgrad.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-fno-gpu-flush-denormals-to-zero", "-Wall", "-Wno-unused-function"]
+         "-fno-gpu-flush-denormals-to-zero", "-Wall", "-Wno-unused-function",
+         # the accumulator loops of the contraction epilogue must be fully unrolled (register arrays)
+         "-mllvm", "-pragma-unroll-threshold=262144"]
 OBJDIR = os.path.join(HERE, "_build")
 
 

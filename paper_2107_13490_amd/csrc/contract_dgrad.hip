@@ -27,6 +27,8 @@ extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *d
     a.act = dy; a.wgt = wt; a.out = dx;
     a.M = d.n * d.h * d.w; a.N = d.c; a.K = d.r * d.s * d.k;
     a.act_es = storage_bytes(fdy); a.wgt_es = storage_bytes(fw);
+    a.act_bytes = (uint32_t)((long long)d.n * a.p * a.q * d.k * a.act_es);
+    a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);
     a.act_load = d.k % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.ldc = d.c;

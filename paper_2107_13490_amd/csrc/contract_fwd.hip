@@ -16,6 +16,8 @@ extern "C" int adapt_conv_fwd(adapt_ctx *ctx, adapt_conv_desc d, const void *x, 
     a.act = x; a.wgt = w; a.out = y;
     a.M = d.n * a.p * a.q; a.N = d.k; a.K = d.r * d.s * d.c;
     a.act_es = storage_bytes(fx); a.wgt_es = storage_bytes(fw);
+    a.act_bytes = (uint32_t)((long long)d.n * d.h * d.w * d.c * a.act_es);
+    a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);
     a.act_load = d.c % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.ldc = d.k;

@@ -64,6 +64,7 @@ struct ContractArgs {
     void *out;
     int M, N, K;
     int act_es, wgt_es;          // element size in bytes (1: int8, 2: int16)
+    uint32_t act_bytes, wgt_bytes;   // operand extents (the vector paths read through bounds-checked buffer loads)
     int act_load, wgt_load;      // LOAD_*
     // gemm: element (row,k) at row*rs + k*ks
     long long act_rs, act_ks, wgt_rs, wgt_ks;
@@ -172,146 +173,171 @@ __device__ __forceinline__ void zero_unit(uint32_t (&hi)[4], uint32_t (&lo)[4])
     for (int i = 0; i < 4; ++i) { hi[i] = 0; lo[i] = 0x80808080u; }
 }
 
-// Converts 16 codes (es = 1: one uint4, es = 2: two) into limb words.
-template <int LIMBS>
-__device__ __forceinline__ void load_unit(const void *ptr, long long off, int es, uint32_t (&hi)[4], uint32_t (&lo)[4])
+// Loads 16 codes (ES = 1: one 16-byte load, ES = 2: two) at element offset `off` and converts them
+// into limb words.  Branch-free: the operand is read through a raw buffer descriptor whose range
+// check returns zeros for out-of-range offsets, so an invalid unit just uses an offset beyond
+// the tensor; zeros split into the limbs of code 0.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
 {
-    if (es == 1) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const int8_t *>(ptr) + off);
-        const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
+    // dword 3 of the descriptor: 32-bit data format, raw (unstrided) addressing
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <int LIMBS, int ES>
+__device__ __forceinline__ void load_unit(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, bool ok, uint32_t (&hi)[4], uint32_t (&lo)[4])
+{
+    const uint32_t byte_off = ok ? off * ES : 0xfffffff0u;
+    if (ES == 1) {
+        const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (LIMBS == 1) hi[i] = raw[i]; else split8(raw[i], hi[i], lo[i]);
+            if (LIMBS == 1) hi[i] = v[i]; else split8(v[i], hi[i], lo[i]);
         }
     } else {
-        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const int16_t *>(ptr) + off);
-        const uint4 v0 = p[0], v1 = p[1];
-        split16(v0.x, v0.y, hi[0], lo[0]);
-        split16(v0.z, v0.w, hi[1], lo[1]);
-        split16(v1.x, v1.y, hi[2], lo[2]);
-        split16(v1.z, v1.w, hi[3], lo[3]);
+        const v4u v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
+        const v4u v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 16, 0);
+        split16(v0[0], v0[1], hi[0], lo[0]);
+        split16(v0[2], v0[3], hi[1], lo[1]);
+        split16(v1[0], v1[1], hi[2], lo[2]);
+        split16(v1[2], v1[3], hi[3], lo[3]);
     }
 }
 
 // ---- K-major operand: thread t owns rows (t/4) + 64*i and the 16-byte column (t%4) of every
-//      64-k sub-chunk of the stage
-template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT>
+//      64-k sub-chunk of the stage.  Element offsets are 32-bit (operands below 2^32 elements,
+//      checked by the host); intermediate values may wrap, valid results do not.
+template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT, int ES>
 struct LoaderK {
     static constexpr int RPT = ROWS / 64, SUB = BKT / 64, UNITS = RPT * SUB;
     static constexpr int ROW_BYTES = BKT + 16;
     static constexpr int TILE_BYTES = ROWS * ROW_BYTES;
     struct Regs { uint32_t hi[UNITS][4], lo[UNITS][4]; };   // one stage in flight
-    long long base[RPT];
+    uint32_t base[RPT];       // row part of the element offset, plus the thread's 16-element column
     int ra[RPT], rb[RPT];
     bool valid[RPT];
+    __amdgpu_buffer_rsrc_t rsrc;
 
     __device__ __forceinline__ void init(const ContractArgs &a, int row0)
     {
+        rsrc = make_rsrc(ACT ? a.act : a.wgt, ACT ? a.act_bytes : a.wgt_bytes);
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
             const int row = row0 + (threadIdx.x >> 2) + 64 * i;
             valid[i] = row < (ACT ? a.M : a.N);
             ra[i] = 0; rb[i] = 0; base[i] = 0;
-            if (MODE == LOAD_SCALAR || !valid[i]) continue;
+            if (MODE == LOAD_SCALAR) continue;
             if (OP == OP_GEMM) {
-                base[i] = (long long)row * (ACT ? a.act_rs : a.wgt_rs);
+                base[i] = (uint32_t)row * (uint32_t)(ACT ? a.act_rs : a.wgt_rs);
             } else if (ACT && OP == OP_FWD) {
                 const uint32_t pq = fdiv(row, a.div_q), q = row - pq * a.q;
                 const uint32_t n = fdiv(pq, a.div_p), p = pq - n * a.p;
                 ra[i] = (int)p * a.stride - a.pad;
                 rb[i] = (int)q * a.stride - a.pad;
-                base[i] = (((long long)n * a.h + ra[i]) * a.w + rb[i]) * a.c;
+                base[i] = ((n * (uint32_t)a.h + (uint32_t)ra[i]) * (uint32_t)a.w + (uint32_t)rb[i]) * (uint32_t)a.c;
             } else if (ACT && OP == OP_DGRAD) {
                 const uint32_t nh = fdiv(row, a.div_w), w = row - nh * a.w;
                 const uint32_t n = fdiv(nh, a.div_h), h = nh - n * a.h;
                 ra[i] = (int)h + a.pad;
                 rb[i] = (int)w + a.pad;
-                base[i] = (long long)n * a.p * a.q * a.k;
+                base[i] = n * (uint32_t)(a.p * a.q) * (uint32_t)a.k;
             } else {
-                base[i] = (long long)row * a.K;      // filters: [row][k]
+                base[i] = (uint32_t)row * (uint32_t)a.K;      // filters: [row][k]
             }
+            base[i] += (threadIdx.x & 3) * 16;
         }
     }
 
-    // element offset of (row i, k); k64 = first k of the 64-k sub-chunk.  -1 for zeros.
-    __device__ __forceinline__ long long offset(const ContractArgs &a, int i, int k, int k64) const
+    // One 64-k sub-chunk of all the thread's rows.  kq decides the filter tap: the sub-chunk's first k
+    // when 64 aligned k share a tap (a uniform value: the tap arithmetic runs on the scalar unit),
+    // else the thread's own k.
+    template <typename KQ>
+    __device__ __forceinline__ void load_sub(const ContractArgs &a, int sc, int k, int k64, KQ kq, Regs &rg) const
     {
-        if (!valid[i] || k >= a.K) return -1;
+        const __amdgpu_buffer_rsrc_t ptr = rsrc;
+        const bool kin = k < a.K;
         if (ACT && OP == OP_FWD) {
-            const uint32_t tap = fdiv(a.uniform_tap ? k64 : k, a.div_c), c = k - tap * a.c;
+            const uint32_t tap = fdiv(kq, a.div_c);
             const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
-            if ((unsigned)(ra[i] + (int)r) >= (unsigned)a.h || (unsigned)(rb[i] + (int)s) >= (unsigned)a.w) return -1;
-            return base[i] + (long long)((r * a.w + s) * a.c + c);
-        }
-        if (ACT && OP == OP_DGRAD) {
-            const uint32_t tap = fdiv(a.uniform_tap ? k64 : k, a.div_k), ko = k - tap * a.k;
-            const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
-            const int hp = ra[i] - (int)r, wp = rb[i] - (int)s;
-            if (hp < 0 || wp < 0) return -1;
-            uint32_t p = hp, q = wp;
-            if (a.stride != 1) {
-                p = fdiv(hp, a.div_stride); q = fdiv(wp, a.div_stride);
-                if ((int)(p * a.stride) != hp || (int)(q * a.stride) != wp) return -1;
+            const uint32_t koff = (r * a.w + s) * a.c + ((uint32_t)k64 - tap * a.c);
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const bool ok = valid[i] && kin && (unsigned)(ra[i] + (int)r) < (unsigned)a.h &&
+                                (unsigned)(rb[i] + (int)s) < (unsigned)a.w;
+                load_unit<LIMBS, ES>(ptr, base[i] + koff, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
             }
-            if ((int)p >= a.p || (int)q >= a.q) return -1;
-            return base[i] + (long long)((p * a.q + q) * a.k + ko);
+        } else if (ACT && OP == OP_DGRAD) {
+            const uint32_t tap = fdiv(kq, a.div_k), ko = (uint32_t)k64 - tap * a.k;
+            const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const int hp = ra[i] - (int)r, wp = rb[i] - (int)s;
+                uint32_t p = hp, q = wp;
+                bool ok = valid[i] && kin && hp >= 0 && wp >= 0;
+                if (a.stride != 1) {
+                    p = fdiv(ok ? hp : 0, a.div_stride); q = fdiv(ok ? wp : 0, a.div_stride);
+                    ok = ok && (int)(p * a.stride) == hp && (int)(q * a.stride) == wp;
+                }
+                ok = ok && (int)p < a.p && (int)q < a.q;
+                load_unit<LIMBS, ES>(ptr, base[i] + (p * a.q + q) * a.k + ko, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < RPT; ++i)
+                load_unit<LIMBS, ES>(ptr, base[i] + (uint32_t)k64, valid[i] && kin, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
         }
-        return base[i] + k;
     }
 
     __device__ __forceinline__ void load(const ContractArgs &a, int row0, int k0, Regs &rg) const
     {
-        const void *ptr = ACT ? a.act : a.wgt;
-        const int es = ACT ? a.act_es : a.wgt_es;
-        uint32_t (&hi)[UNITS][4] = rg.hi;
-        uint32_t (&lo)[UNITS][4] = rg.lo;
+        if (MODE == LOAD_VEC) {
 #pragma unroll
-        for (int sc = 0; sc < SUB; ++sc)
+            for (int sc = 0; sc < SUB; ++sc) {
+                const int k64 = k0 + sc * 64, k = k64 + (threadIdx.x & 3) * 16;
+                if (a.uniform_tap) load_sub(a, sc, k, k64, (uint32_t)__builtin_amdgcn_readfirstlane(k64), rg);
+                else load_sub(a, sc, k, k64, (uint32_t)k, rg);
+            }
+        } else {
+            // element-wise gather: any shape, any alignment
+            const void *ptr = ACT ? a.act : a.wgt;
 #pragma unroll
             for (int i = 0; i < RPT; ++i) {
-                const int u = sc * RPT + i;
-                const int k64 = k0 + sc * 64, k = k64 + (threadIdx.x & 3) * 16;
-                if (MODE == LOAD_VEC) {
-                    const long long off = offset(a, i, k, k64);
-                    if (off < 0) zero_unit(hi[u], lo[u]); else load_unit<LIMBS>(ptr, off, es, hi[u], lo[u]);
-                } else {
-                    // element-wise gather: any shape, any alignment
-                    const int row = row0 + (threadIdx.x >> 2) + 64 * i;
+                const int row = row0 + (threadIdx.x >> 2) + 64 * i;
+                const int k = k0 + (threadIdx.x & 3) * 16;
 #pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        uint32_t h = 0, l = 0;
+                for (int w = 0; w < 4; ++w) {
+                    uint32_t h = 0, l = 0;
 #pragma unroll
-                        for (int b = 0; b < 4; ++b) {
-                            const long long off = operand_offset<OP, ACT>(a, row, k + 4 * w + b);
-                            int v = 0;
-                            if (off >= 0)
-                                v = es == 1 ? (int)static_cast<const int8_t *>(ptr)[off] : (int)static_cast<const int16_t *>(ptr)[off];
-                            if (LIMBS == 1) {
-                                h |= (uint32_t)(v & 0xff) << (8 * b);
-                            } else {
-                                h |= (uint32_t)((v >> 8) & 0xff) << (8 * b);
-                                l |= (uint32_t)((v & 0xff) ^ 0x80) << (8 * b);
-                            }
+                    for (int b = 0; b < 4; ++b) {
+                        const long long off = operand_offset<OP, ACT>(a, row, k + 4 * w + b);
+                        int v = 0;
+                        if (off >= 0)
+                            v = ES == 1 ? (int)static_cast<const int8_t *>(ptr)[off] : (int)static_cast<const int16_t *>(ptr)[off];
+                        if (LIMBS == 1) {
+                            h |= (uint32_t)(v & 0xff) << (8 * b);
+                        } else {
+                            h |= (uint32_t)((v >> 8) & 0xff) << (8 * b);
+                            l |= (uint32_t)((v & 0xff) ^ 0x80) << (8 * b);
                         }
-                        hi[u][w] = h;
-                        lo[u][w] = l;
                     }
+                    rg.hi[i][w] = h;
+                    rg.lo[i][w] = l;
                 }
             }
+        }
     }
 
     __device__ __forceinline__ static void store(const Regs &rg, char *tile_hi, char *tile_lo)
     {
-        const uint32_t (&hi)[UNITS][4] = rg.hi;
-        const uint32_t (&lo)[UNITS][4] = rg.lo;
 #pragma unroll
         for (int sc = 0; sc < SUB; ++sc)
 #pragma unroll
             for (int i = 0; i < RPT; ++i) {
                 const int u = sc * RPT + i;
                 const int o = ((threadIdx.x >> 2) + 64 * i) * ROW_BYTES + sc * 64 + (threadIdx.x & 3) * 16;
-                *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(hi[u][0], hi[u][1], hi[u][2], hi[u][3]);
-                if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(lo[u][0], lo[u][1], lo[u][2], lo[u][3]);
+                *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(rg.hi[u][0], rg.hi[u][1], rg.hi[u][2], rg.hi[u][3]);
+                if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(rg.lo[u][0], rg.lo[u][1], rg.lo[u][2], rg.lo[u][3]);
             }
     }
 
@@ -323,27 +349,29 @@ struct LoaderK {
 };
 
 // ---- R-major operand: a unit is 16 consecutive rows of one k
-template <int OP, bool ACT, int ROWS, int LIMBS, int BKT>
+template <int OP, bool ACT, int ROWS, int LIMBS, int BKT, int ES>
 struct LoaderR {
     static constexpr int CPL = ROWS / 16;                 // 16-row chunks per k line
     static constexpr int UNITS = BKT * CPL / kThreads;
     static constexpr int ROW_BYTES = ROWS + 16;           // bytes per k line
     static constexpr int TILE_BYTES = BKT * ROW_BYTES;
     struct Regs { uint32_t hi[UNITS][4], lo[UNITS][4]; };   // one stage in flight
-    long long coff[UNITS];
+    uint32_t coff[UNITS];
     int ra[UNITS], rb[UNITS];
     bool valid[UNITS];
+    __amdgpu_buffer_rsrc_t rsrc;
 
     __device__ __forceinline__ void init(const ContractArgs &a, int row0)
     {
+        rsrc = make_rsrc(ACT ? a.act : a.wgt, ACT ? a.act_bytes : a.wgt_bytes);
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             const int id = threadIdx.x + u * kThreads;
             const int row = row0 + (id % CPL) * 16;
             valid[u] = row < (ACT ? a.M : a.N);
             ra[u] = 0; rb[u] = 0; coff[u] = row;
-            if (!ACT && OP == OP_WGRAD && valid[u]) {
-                const uint32_t tap = fdiv(row, a.div_c), c = row - tap * a.c;
+            if (!ACT && OP == OP_WGRAD) {
+                const uint32_t tap = fdiv(valid[u] ? row : 0, a.div_c), c = row - tap * a.c;
                 const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
                 ra[u] = (int)r - a.pad;
                 rb[u] = (int)s - a.pad;
@@ -354,42 +382,36 @@ struct LoaderR {
 
     __device__ __forceinline__ void load(const ContractArgs &a, int row0, int k0, Regs &rg) const
     {
-        const void *ptr = ACT ? a.act : a.wgt;
-        const int es = ACT ? a.act_es : a.wgt_es;
-        uint32_t (&hi)[UNITS][4] = rg.hi;
-        uint32_t (&lo)[UNITS][4] = rg.lo;
+        const __amdgpu_buffer_rsrc_t ptr = rsrc;
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             const int id = threadIdx.x + u * kThreads;
             const int kk = k0 + id / CPL;
-            long long off = -1;
-            if (valid[u] && kk < a.K) {
-                if (OP == OP_GEMM) {
-                    off = coff[u] + (long long)kk * (ACT ? a.act_ks : a.wgt_ks);
-                } else if (ACT) {                      // wgrad: dy[(n,p,q)][kout]
-                    off = coff[u] + (long long)kk * a.k;
-                } else {                               // wgrad: x[n, p*st+r-pad, q*st+s-pad, c]
-                    const uint32_t np = fdiv(kk, a.div_q), q = kk - np * a.q;
-                    const uint32_t n = fdiv(np, a.div_p), p = np - n * a.p;
-                    const int hh = (int)p * a.stride + ra[u], ww = (int)q * a.stride + rb[u];
-                    if ((unsigned)hh < (unsigned)a.h && (unsigned)ww < (unsigned)a.w)
-                        off = (((long long)n * a.h + hh) * a.w + ww) * a.c + coff[u];
-                }
+            bool ok = valid[u] && kk < a.K;
+            uint32_t off;
+            if (OP == OP_GEMM) {
+                off = coff[u] + (uint32_t)kk * (uint32_t)(ACT ? a.act_ks : a.wgt_ks);
+            } else if (ACT) {                      // wgrad: dy[(n,p,q)][kout]
+                off = coff[u] + (uint32_t)kk * (uint32_t)a.k;
+            } else {                               // wgrad: x[n, p*st+r-pad, q*st+s-pad, c]
+                const uint32_t np = fdiv(ok ? kk : 0, a.div_q), q = kk - np * a.q;
+                const uint32_t n = fdiv(np, a.div_p), p = np - n * a.p;
+                const int hh = (int)p * a.stride + ra[u], ww = (int)q * a.stride + rb[u];
+                ok = ok && (unsigned)hh < (unsigned)a.h && (unsigned)ww < (unsigned)a.w;
+                off = ((n * (uint32_t)a.h + (uint32_t)hh) * (uint32_t)a.w + (uint32_t)ww) * (uint32_t)a.c + coff[u];
             }
-            if (off < 0) zero_unit(hi[u], lo[u]); else load_unit<LIMBS>(ptr, off, es, hi[u], lo[u]);
+            load_unit<LIMBS, ES>(ptr, off, ok, rg.hi[u], rg.lo[u]);
         }
     }
 
     __device__ __forceinline__ static void store(const Regs &rg, char *tile_hi, char *tile_lo)
     {
-        const uint32_t (&hi)[UNITS][4] = rg.hi;
-        const uint32_t (&lo)[UNITS][4] = rg.lo;
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             const int id = threadIdx.x + u * kThreads;
             const int o = (id / CPL) * ROW_BYTES + (id % CPL) * 16;
-            *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(hi[u][0], hi[u][1], hi[u][2], hi[u][3]);
-            if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(lo[u][0], lo[u][1], lo[u][2], lo[u][3]);
+            *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(rg.hi[u][0], rg.hi[u][1], rg.hi[u][2], rg.hi[u][3]);
+            if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(rg.lo[u][0], rg.lo[u][1], rg.lo[u][2], rg.lo[u][3]);
         }
     }
 
@@ -411,10 +433,10 @@ struct LoaderR {
     }
 };
 
-template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT>
-struct LoaderSelect { typedef LoaderK<OP, ACT, MODE, ROWS, LIMBS, BKT> type; };
-template <int OP, bool ACT, int ROWS, int LIMBS, int BKT>
-struct LoaderSelect<OP, ACT, LOAD_ROWS, ROWS, LIMBS, BKT> { typedef LoaderR<OP, ACT, ROWS, LIMBS, BKT> type; };
+template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT, int ES>
+struct LoaderSelect { typedef LoaderK<OP, ACT, MODE, ROWS, LIMBS, BKT, ES> type; };
+template <int OP, bool ACT, int ROWS, int LIMBS, int BKT, int ES>
+struct LoaderSelect<OP, ACT, LOAD_ROWS, ROWS, LIMBS, BKT, ES> { typedef LoaderR<OP, ACT, ROWS, LIMBS, BKT, ES> type; };
 
 // ---------------------------------------------------------------------------------------------
 // accumulator -> output format (the SR rule applied to the accumulator's low bits)
@@ -436,103 +458,107 @@ __device__ __forceinline__ int requantize_one(long long acc, int shift, int wl, 
     return (int)(q > qmax ? qmax : q < qmin ? qmin : q);
 }
 
-// one-limb accumulators fit 32 bits with room for the rounding bits (|acc| <= 2^30)
-__device__ __forceinline__ int requantize_i32(int acc, int shift, int qmin, int qmax, int relu, uint32_t r16)
+// one-limb accumulators fit 32 bits with room for the rounding bits (|acc| <= 2^30).  `w` holds the
+// rounding bits of two neighbouring outputs (low / high half); shift >= 1.
+__device__ __forceinline__ int requantize_i32(int acc, int shift, int qlo, int qhi, uint32_t w, int half)
 {
-    int q = shift <= 16 ? (acc + (int)(r16 >> (16 - shift))) >> shift : ((acc >> (shift - 16)) + (int)r16) >> 16;
-    if (relu) q = max(q, 0);
-    return min(max(q, qmin), qmax);
+    int q;
+    if (shift <= 16) q = (acc + (int)__builtin_amdgcn_ubfe(w, 16 * half + 16 - shift, shift)) >> shift;
+    else q = ((acc >> (shift - 16)) + (int)__builtin_amdgcn_ubfe(w, 16 * half, 16)) >> 16;
+    return min(max(q, qlo), qhi);      // one v_med3_i32
 }
 
-// Writes RUN (4 or 16) consecutive outputs (m, n0 .. n0+RUN-1) held by one lane.  FITS32: the
-// values are int32 accumulators of the one-limb path.
+__device__ __forceinline__ uint32_t pack4_i8(int q0, int q1, int q2, int q3)
+{
+    // byte selectors: 0-3 second operand, 4-7 first operand, 0x0c constant zero
+    return __builtin_amdgcn_perm((uint32_t)q1, (uint32_t)q0, 0x0c0c0400u) | __builtin_amdgcn_perm((uint32_t)q3, (uint32_t)q2, 0x04000c0cu);
+}
+
+// Writes 16 consecutive outputs (m, n0 .. n0+15) held by one lane.  FITS32: the values are int32
+// accumulators of the one-limb path.
 template <int RUN, bool FITS32>
 __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m, int n0, const long long (&v)[RUN])
 {
+    static_assert(RUN == 16, "a lane holds runs of 16 outputs");
     if (m >= a.M || n0 >= a.N) return;
     const int cnt = min(RUN, a.N - n0);
     const long long row = (long long)m * a.ldc + n0;
-    switch (a.out_mode) {
-        case OUT_RAW32: {
-            int32_t *o = static_cast<int32_t *>(out) + row;
-            if (cnt == RUN && ((a.ldc | n0) & 3) == 0) {
+    if (a.out_mode == OUT_RAW32) {
+        int32_t *o = static_cast<int32_t *>(out) + row;
+        if (cnt == RUN && ((a.ldc | n0) & 3) == 0) {
 #pragma unroll
-                for (int i = 0; i < RUN / 4; ++i)
-                    reinterpret_cast<int4 *>(o)[i] = make_int4((int)v[4 * i], (int)v[4 * i + 1], (int)v[4 * i + 2], (int)v[4 * i + 3]);
-            } else {
-                for (int i = 0; i < cnt; ++i) o[i] = (int32_t)v[i];
-            }
-            break;
+            for (int i = 0; i < RUN / 4; ++i)
+                reinterpret_cast<int4 *>(o)[i] = make_int4((int)v[4 * i], (int)v[4 * i + 1], (int)v[4 * i + 2], (int)v[4 * i + 3]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < RUN; ++i)
+                if (i < cnt) o[i] = (int32_t)v[i];
         }
-        case OUT_RAW64: {
-            long long *o = static_cast<long long *>(out) + row;
-            if (cnt == RUN && ((a.ldc | n0) & 1) == 0) {
+        return;
+    }
+    if (a.out_mode == OUT_RAW64) {
+        long long *o = static_cast<long long *>(out) + row;
+        if (cnt == RUN && ((a.ldc | n0) & 1) == 0) {
 #pragma unroll
-                for (int i = 0; i < RUN / 2; ++i) reinterpret_cast<longlong2 *>(o)[i] = make_longlong2(v[2 * i], v[2 * i + 1]);
-            } else {
-                for (int i = 0; i < cnt; ++i) o[i] = v[i];
-            }
-            break;
+            for (int i = 0; i < RUN / 2; ++i) reinterpret_cast<longlong2 *>(o)[i] = make_longlong2(v[2 * i], v[2 * i + 1]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < RUN; ++i)
+                if (i < cnt) o[i] = v[i];
         }
-        default: {
-            // requantize: output element index = m * N + n (row-major over the logical tensor)
-            const uint64_t idx0 = (uint64_t)m * (uint64_t)a.N + (uint64_t)n0;
-            uint32_t r[RUN];
-            if (a.rmode != ADAPT_SR) {
+        return;
+    }
+    // requantize: output element index = m * N + n (row-major over the logical tensor); rw[i/2] holds
+    // the rounding bits of outputs i (low half) and i+1 (high half)
+    const uint64_t idx0 = (uint64_t)m * (uint64_t)a.N + (uint64_t)n0;
+    uint32_t rw[RUN / 2];
+    if (a.rmode != ADAPT_SR) {
 #pragma unroll
-                for (int i = 0; i < RUN; ++i) r[i] = 0x8000u;
-            } else if (RUN == 16 && (idx0 & 7) == 0) {
+        for (int i = 0; i < RUN / 2; ++i) rw[i] = 0x80008000u;
+    } else if ((idx0 & 7) == 0) {
 #pragma unroll
-                for (int h = 0; h < RUN / 8; ++h) {
-                    const u32x4 b = rounding_block(a.seed, a.stream, (idx0 >> 3) + h);
-                    r[8 * h + 0] = b.x & 0xffffu; r[8 * h + 1] = b.x >> 16; r[8 * h + 2] = b.y & 0xffffu; r[8 * h + 3] = b.y >> 16;
-                    r[8 * h + 4] = b.z & 0xffffu; r[8 * h + 5] = b.z >> 16; r[8 * h + 6] = b.w & 0xffffu; r[8 * h + 7] = b.w >> 16;
-                }
-            } else if (RUN == 4 && (idx0 & 3) == 0) {
-                const u32x4 b = rounding_block(a.seed, a.stream, idx0 >> 3);
-                const uint32_t w0 = (idx0 & 4) ? b.z : b.x, w1 = (idx0 & 4) ? b.w : b.y;
-                r[0] = w0 & 0xffffu; r[1] = w0 >> 16; r[2] = w1 & 0xffffu; r[3] = w1 >> 16;
-            } else {
-                for (int i = 0; i < RUN; ++i) r[i] = rounding_bits_of(a.seed, a.stream, idx0 + i, ADAPT_SR);
-            }
-            int q[RUN];
-            if (FITS32 && a.shift >= 1) {
-                const int qmax = (1 << (a.wl_o - 1)) - 1, qmin = -(1 << (a.wl_o - 1));
+        for (int h = 0; h < RUN / 8; ++h) {
+            const u32x4 b = rounding_block(a.seed, a.stream, (idx0 >> 3) + h);
+            rw[4 * h] = b.x; rw[4 * h + 1] = b.y; rw[4 * h + 2] = b.z; rw[4 * h + 3] = b.w;
+        }
+    } else {
 #pragma unroll
-                for (int i = 0; i < RUN; ++i) q[i] = requantize_i32((int)v[i], a.shift, qmin, qmax, a.relu, r[i]);
-            } else {
+        for (int i = 0; i < RUN / 2; ++i)
+            rw[i] = rounding_bits_of(a.seed, a.stream, idx0 + 2 * i, ADAPT_SR) |
+                    (rounding_bits_of(a.seed, a.stream, idx0 + 2 * i + 1, ADAPT_SR) << 16);
+    }
+    int q[RUN];
+    if (FITS32 && a.shift >= 1) {
+        const int qhi = (1 << (a.wl_o - 1)) - 1, qlo = a.relu ? 0 : -(1 << (a.wl_o - 1));
 #pragma unroll
-                for (int i = 0; i < RUN; ++i) q[i] = requantize_one(v[i], a.shift, a.wl_o, a.relu, r[i]);
-            }
-            if (a.out_mode == OUT_Q8) {
-                int8_t *o = static_cast<int8_t *>(out) + row;
-                if (cnt == RUN && ((a.ldc | n0) & (RUN - 1)) == 0) {
-                    uint32_t w[RUN / 4];
+        for (int i = 0; i < RUN; ++i) q[i] = requantize_i32((int)v[i], a.shift, qlo, qhi, rw[i >> 1], i & 1);
+    } else {
 #pragma unroll
-                    for (int i = 0; i < RUN / 4; ++i)
-                        w[i] = (uint32_t)(q[4 * i] & 0xff) | ((uint32_t)(q[4 * i + 1] & 0xff) << 8) |
-                               ((uint32_t)(q[4 * i + 2] & 0xff) << 16) | ((uint32_t)(q[4 * i + 3] & 0xff) << 24);
-                    if (RUN == 16) *reinterpret_cast<uint4 *>(o) = make_uint4(w[0], w[RUN / 4 > 1 ? 1 : 0], w[RUN / 4 > 2 ? 2 : 0], w[RUN / 4 > 3 ? 3 : 0]);
-                    else *reinterpret_cast<uint32_t *>(o) = w[0];
-                } else {
-                    for (int i = 0; i < cnt; ++i) o[i] = (int8_t)q[i];
-                }
-            } else {
-                int16_t *o = static_cast<int16_t *>(out) + row;
-                if (cnt == RUN && ((a.ldc | n0) & (RUN == 16 ? 7 : 3)) == 0) {
-                    uint32_t w[RUN / 2];
+        for (int i = 0; i < RUN; ++i)
+            q[i] = requantize_one(v[i], a.shift, a.wl_o, a.relu, (rw[i >> 1] >> (16 * (i & 1))) & 0xffffu);
+    }
+    if (a.out_mode == OUT_Q8) {
+        int8_t *o = static_cast<int8_t *>(out) + row;
+        if (cnt == RUN && ((a.ldc | n0) & 15) == 0) {
+            *reinterpret_cast<uint4 *>(o) = make_uint4(pack4_i8(q[0], q[1], q[2], q[3]), pack4_i8(q[4], q[5], q[6], q[7]),
+                                                       pack4_i8(q[8], q[9], q[10], q[11]), pack4_i8(q[12], q[13], q[14], q[15]));
+        } else {
 #pragma unroll
-                    for (int i = 0; i < RUN / 2; ++i) w[i] = (uint32_t)(q[2 * i] & 0xffff) | ((uint32_t)q[2 * i + 1] << 16);
-                    if (RUN == 16) {
-                        reinterpret_cast<uint4 *>(o)[0] = make_uint4(w[0], w[1], w[RUN / 2 > 2 ? 2 : 0], w[RUN / 2 > 3 ? 3 : 0]);
-                        reinterpret_cast<uint4 *>(o)[1] = make_uint4(w[RUN / 2 > 4 ? 4 : 0], w[RUN / 2 > 5 ? 5 : 0], w[RUN / 2 > 6 ? 6 : 0], w[RUN / 2 > 7 ? 7 : 0]);
-                    } else {
-                        *reinterpret_cast<uint2 *>(o) = make_uint2(w[0], w[1]);
-                    }
-                } else {
-                    for (int i = 0; i < cnt; ++i) o[i] = (int16_t)q[i];
-                }
-            }
+            for (int i = 0; i < RUN; ++i)
+                if (i < cnt) o[i] = (int8_t)q[i];
+        }
+    } else {
+        int16_t *o = static_cast<int16_t *>(out) + row;
+        if (cnt == RUN && ((a.ldc | n0) & 7) == 0) {
+            uint32_t w[RUN / 2];
+#pragma unroll
+            for (int i = 0; i < RUN / 2; ++i) w[i] = (uint32_t)(q[2 * i] & 0xffff) | ((uint32_t)q[2 * i + 1] << 16);
+            reinterpret_cast<uint4 *>(o)[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            reinterpret_cast<uint4 *>(o)[1] = make_uint4(w[4], w[5], w[6], w[7]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < RUN; ++i)
+                if (i < cnt) o[i] = (int16_t)q[i];
         }
     }
 }
@@ -547,13 +573,13 @@ __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN, int BKT>
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
 __global__ void __launch_bounds__(kThreads)
 contract_kernel(const ContractArgs a)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per block");
-    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT>::type LA;
-    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT>::type LB;
+    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT, AES>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT, WES>::type LB;
     constexpr bool A_R = AMODE == LOAD_ROWS, W_R = WMODE == LOAD_ROWS;
     constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
     constexpr int MB = WM / 32, NB = WN / 32;       // 32x32 blocks per wave
@@ -774,14 +800,14 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 // ---- host side ---------------------------------------------------------------------------------
 struct TileShape { int bm, bn, bkt; };
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN, int BKT>
-static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int splits)
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
+static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
-    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT>::type LA;
-    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT>::type LB;
+    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT, AES>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT, WES>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const size_t lds = (size_t)(LA::TILE_BYTES + LB::TILE_BYTES) * LIMBS;
-    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, BM, BN, WGM, WGN, BKT>;
+    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT>;
     static bool attr_done = false;
     if (!attr_done && lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -790,6 +816,19 @@ static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int spli
     }
     hipLaunchKernelGGL(kern, dim3(tiles, splits), dim3(kThreads), lds, ctx->stream, a);
     return hipGetLastError();
+}
+
+// storage types of the two operands: one limb means both int8
+template <int OP, int LIMBS, int AMODE, int WMODE, int BM, int BN, int WGM, int WGN, int BKT>
+static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int splits)
+{
+    if constexpr (LIMBS == 1) {
+        return launch_es<OP, 1, AMODE, WMODE, 1, 1, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+    } else {
+        if (a.act_es == 2 && a.wgt_es == 2) return launch_es<OP, 2, AMODE, WMODE, 2, 2, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+        if (a.act_es == 2) return launch_es<OP, 2, AMODE, WMODE, 2, 1, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+        return launch_es<OP, 2, AMODE, WMODE, 1, 2, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+    }
 }
 
 // Tile shapes: BM in {64, 128}, BN in {64, 128} and (one-limb convolutions only) 192; stage depth
@@ -812,10 +851,11 @@ static hipError_t launch_tile(adapt_ctx *ctx, const ContractArgs &a, int splits,
         if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 64>(ctx, a, splits, t);
         return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 64>(ctx, a, splits, t);
     } else {
-        if (t.bkt == 192) {
-            if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 192>(ctx, a, splits, t);
-            return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 192>(ctx, a, splits, t);
-        }
+        if constexpr (LIMBS == 1)
+            if (t.bkt == 192) {
+                if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 192>(ctx, a, splits, t);
+                return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 192>(ctx, a, splits, t);
+            }
         if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 64>(ctx, a, splits, t);
         return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 64>(ctx, a, splits, t);
     }
@@ -851,7 +891,8 @@ static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
     else if ((a.N + 127) / 128 * 128 - a.N >= 64) t.bn = 64;
     else t.bn = 128;
     // deeper stages cut the number of exposed load latencies; zero padding of the last stage must stay small
-    t.bkt = (OP != OP_GEMM && !scalar && (a.K % 192 == 0 || a.K >= 3072)) ? 192 : 64;
+    // (two limbs: four times the MFMA work per stage already, and the staging registers are needed for accumulators)
+    t.bkt = (OP != OP_GEMM && !scalar && limbs == 1 && (a.K % 192 == 0 || a.K >= 3072)) ? 192 : 64;
     // Small problems: several resident blocks per CU hide each other's load latency and epilogue,
     // so halve the tile when 128-row tiles would leave fewer than two blocks per CU.  (Split-K
     // contractions get their parallelism from the splits instead.)
@@ -945,6 +986,11 @@ static int fill_conv(ContractArgs &a, const adapt_conv_desc &d)
     const long long lim = (1ll << 31) - 1;
     if ((long long)d.n * d.h * d.w >= lim || (long long)d.n * a.p * a.q >= lim || (long long)d.r * d.s * d.c >= lim ||
         (long long)d.r * d.s * d.k >= lim)
+        return ADAPT_EUNSUPPORTED;
+    // the kernels index every tensor with 32-bit byte offsets (int16 storage assumed)
+    const long long lim32 = 1ll << 32;
+    if ((long long)d.n * d.h * d.w * d.c * 2 >= lim32 || (long long)d.n * a.p * a.q * d.k * 2 >= lim32 ||
+        (long long)d.k * d.r * d.s * d.c * 2 >= lim32)
         return ADAPT_EUNSUPPORTED;
     a.div_c = make_fastdiv(d.c); a.div_s = make_fastdiv(d.s); a.div_q = make_fastdiv(a.q); a.div_p = make_fastdiv(a.p);
     a.div_k = make_fastdiv(d.k); a.div_w = make_fastdiv(d.w); a.div_h = make_fastdiv(d.h);
