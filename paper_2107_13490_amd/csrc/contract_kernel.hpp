@@ -9,7 +9,7 @@
 //   op      m            n          k            ACT[m][k]                      WGT[n][k]
 //   gemm    row of C     col of C   K            A                              B
 //   fwd     (n,p,q)      kout       (r,s,c)      x[n,p*st+r-pad,q*st+s-pad,c]   w[kout,r,s,c]
-//   dgrad   (n,h,w)      c          (r,s,kout)   dy[n,(h+pad-r)/st,(w+pad-s)/st,kout]   wt[c,r,s,kout]
+//   dgrad   (n,h,w)      c          (r,s,kout)   dy[n,(h+pad-r)/st,(w+pad-s)/st,kout]   w[kout,r,s,c]
 //   wgrad   kout         (r,s,c)    (n,p,q)      dy[n,p,q,kout]                 x[n,p*st+r-pad,q*st+s-pad,c]
 //
 // Tiles of ACT and WGT are staged in LDS and fed to v_mfma_i32_32x32x32_i8 with WGT as the row
@@ -118,7 +118,10 @@ __device__ __forceinline__ long long wgt_offset(const ContractArgs &a, int row, 
     if (row >= a.N || k >= a.K) return -1;
     if (OP == OP_GEMM) return (long long)row * a.wgt_rs + (long long)k * a.wgt_ks;
     if (OP == OP_FWD) return (long long)row * a.K + k;
-    if (OP == OP_DGRAD) return (long long)row * a.K + k;       // filters re-laid-out as [c][r][s][kout]
+    if (OP == OP_DGRAD) {                                       // row = c, k = (r,s,kout): w[kout][r][s][c]
+        const uint32_t tap = fdiv(k, a.div_k), ko = k - tap * a.k;
+        return ((long long)ko * (a.r * a.s) + tap) * a.c + row;
+    }
     // OP_WGRAD: row = (r,s,c), k = (n,p,q)
     const uint32_t tap = fdiv(row, a.div_c), c = row - tap * a.c;
     const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
@@ -393,6 +396,9 @@ struct LoaderR {
                 off = coff[u] + (uint32_t)kk * (uint32_t)(ACT ? a.act_ks : a.wgt_ks);
             } else if (ACT) {                      // wgrad: dy[(n,p,q)][kout]
                 off = coff[u] + (uint32_t)kk * (uint32_t)a.k;
+            } else if (OP == OP_DGRAD) {           // filters w[kout][r][s][c], k line = (r,s,kout)
+                const uint32_t tap = fdiv(ok ? kk : 0, a.div_k), ko = kk - tap * a.k;
+                off = (ko * (uint32_t)(a.r * a.s) + tap) * (uint32_t)a.c + coff[u];
             } else {                               // wgrad: x[n, p*st+r-pad, q*st+s-pad, c]
                 const uint32_t np = fdiv(ok ? kk : 0, a.div_q), q = kk - np * a.q;
                 const uint32_t n = fdiv(np, a.div_p), p = np - n * a.p;
@@ -752,20 +758,7 @@ contract_kernel(const ContractArgs a)
     ADAPT_STAMP(4);
 }
 
-// ---- helpers: filter re-layout for dgrad, split-K finish --------------------------------------------
-// w[k][rs][c] -> wt[c][rs][k]
-template <typename T>
-__global__ void relayout_filter_kernel(const T *__restrict__ w, T *__restrict__ wt, int K, int RS, int C)
-{
-    const size_t total = (size_t)K * RS * C;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int k = (int)(i % K);
-        const size_t t = i / K;
-        const int rs = (int)(t % RS), c = (int)(t / RS);
-        wt[i] = w[((size_t)k * RS + rs) * C + c];
-    }
-}
-
+// ---- helper: split-K finish ---------------------------------------------------------------------------
 // split-K: sums the `splits` slabs of exact partial sums (dense M x N each) and converts
 template <typename AccT>
 __global__ void __launch_bounds__(256)
@@ -875,6 +868,8 @@ static hipError_t launch_modes(adapt_ctx *ctx, const ContractArgs &a, int splits
         if (a.act_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_ROWS>(ctx, a, splits, t);
         if (a.wgt_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_VEC>(ctx, a, splits, t);
         return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_ROWS>(ctx, a, splits, t);
+    } else if constexpr (OP == OP_DGRAD) {
+        return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_ROWS>(ctx, a, splits, t);
     } else {
         return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_VEC>(ctx, a, splits, t);
     }

@@ -258,3 +258,41 @@ def test_invalid_arguments():
     d = ConvDesc(1, 2, 2, 16, 16, 5, 5, 1, 0)        # filter larger than the padded input
     with pytest.raises(pkg.AdaptError):
         ctx().conv_fwd(d, a, (8, 0), a, (8, 0), Epilogue.exact(), out=a)
+
+
+# ------------------------------------------------------------------------------------ layer sweeps (configs 4 and 5)
+
+def _sweep(specs, batch, seed):
+    """Every layer of the network shape at reduced batch: quantize on the GPU with the layer's own
+    <WL,FL>, then fwd / dgrad / wgrad, all against the oracle."""
+    import dataclasses
+    for li, spec in enumerate(specs):
+        shp = dataclasses.replace(spec.shape, n=batch)
+        L = wk.conv_layer(shp, spec.wl, spec.fl, seed + li, spec.zero_frac, spec.name)
+        s = L.shape
+        d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+        f = (L.wl, L.fl)
+        (qx, qw, qdy), _ = ctx().quantize_batched([dev(L.x), dev(L.w), dev(L.dy)], [f, f, f], [1, 2, 3], pkg.SR, seed=0)
+        hx, hw, hdy = host(qx), host(qw), host(qdy)
+        for t, ref_in, stream in ((hx, L.x, 1), (hw, L.w, 2), (hdy, L.dy, 3)):
+            want, _, _ = orc.quantize(ref_in, L.wl, L.fl, orc.SR, 0, stream)
+            assert np.array_equal(t.astype(np.int64), want), spec.name
+        y = ctx().conv_fwd(d, qx, f, qw, f, Epilogue.exact())
+        dx = ctx().conv_dgrad(d, qdy, f, qw, f, Epilogue.exact())
+        dw = ctx().conv_wgrad(d, qdy, f, qx, f, Epilogue.exact())
+        assert np.array_equal(host(y).astype(np.int64), co.conv_fwd(hx, hw, s.stride, s.pad)), spec.name
+        assert np.array_equal(host(dx).astype(np.int64), co.conv_dgrad(hdy, hw, s.h, s.w, s.stride, s.pad)), spec.name
+        assert np.array_equal(host(dw).astype(np.int64), co.conv_wgrad(hdy, hx, s.r, s.s, s.stride, s.pad)), spec.name
+        # requantized forward output in the layer's own format
+        ep = Epilogue.requant(L.wl, L.fl, pkg.SR, seed=0, stream=20 + li, relu=True)
+        yq = host(ctx().conv_fwd(d, qx, f, qw, f, ep)).astype(np.int64)
+        want = orc.requantize(co.conv_fwd(hx, hw, s.stride, s.pad), L.fl, L.wl, orc.SR, 0, 20 + li, True)
+        assert np.array_equal(yq, want), spec.name
+
+
+def test_config4_alexnet_layer_sweep_reduced_batch():
+    _sweep(wk.alexnet_cifar_layers(), batch=4, seed=40)
+
+
+def test_config5_resnet18_layer_sweep_reduced_batch():
+    _sweep(wk.resnet18_cifar_layers(), batch=2, seed=50)
