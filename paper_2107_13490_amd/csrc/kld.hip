@@ -2,8 +2,8 @@
 // distribution of a tensor and of its <WL_c, FL_c> quantizations, for all candidate word
 // lengths in one pass over the tensor.
 //
-// Four launches per search, all on the context's stream, no host round trip and no device-wide
-// fences (kernel boundaries order the phases):
+// Three launches per search, all on the context's stream, no host round trip (kernel boundaries
+// order the phases; only the tiny final kernel uses a device-wide fence):
 //   range    per-block min / max of the finite elements.
 //   hist     every block first reduces the range partials and derives the bin grid (power-of-two
 //            width) and the per-candidate integer bin parameters (the "plan"; block 0 also stores
@@ -11,8 +11,8 @@
 //            one bin per candidate for every element, counted in LDS histograms (one replica per
 //            wavefront when they fit), and written to the block's own slab with plain stores.
 //   final    blocks of (256 bins, candidate): add the slabs of the reference row and of the
-//            candidate's row, partial KL sums in fp64.
-//   select   adds the partial sums in a fixed order, lowest WL with KL < eps.
+//            candidate's row, partial KL sums in fp64; the last block to finish adds the partial
+//            sums in a fixed order and picks the lowest WL with KL < eps.
 // All counts are integers, so the result does not depend on the order of accumulation.
 #include <algorithm>
 
@@ -192,9 +192,13 @@ __global__ void zero_words_kernel(uint32_t *p, size_t n)
 template <bool USE_LDS>
 __global__ void __launch_bounds__(kHistMaxThreads)
 kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial, int range_blocks,
-                int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *slabs, int total_rows, int row0,
-                int rows, int replicas, int mode, uint64_t seed, uint64_t stream)
+                int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *slabs, int total_rows,
+                int rows_per_group, int replicas, int mode, uint64_t seed, uint64_t stream)
 {
+    // blockIdx.y selects a group of histogram rows: small tensors are spread over more CUs by
+    // letting several blocks count different candidates of the same elements
+    const int row0 = blockIdx.y * rows_per_group;
+    const int rows = min(rows_per_group, total_rows - row0);
     extern __shared__ uint32_t lds[];
     __shared__ KldPlan plan;
     __shared__ float slo[kHistMaxThreads / kWave], shi[kHistMaxThreads / kWave];
@@ -227,7 +231,7 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
         __syncthreads();
         if (!plan.degenerate && (int)threadIdx.x < ncand) make_candidate(&plan, threadIdx.x, wl_lo, wl_hi, il);
         __syncthreads();
-        if (blockIdx.x == 0 && row0 == 0)
+        if (blockIdx.x == 0 && blockIdx.y == 0)
             for (int i = threadIdx.x; i < (int)(sizeof(KldPlan) / 4); i += nthreads)
                 reinterpret_cast<uint32_t *>(plan_out)[i] = reinterpret_cast<const uint32_t *>(&plan)[i];
     }
@@ -332,14 +336,15 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
 // D = n_finite + alpha nb, so bins with cp_b == cq_b contribute nothing and need no logarithm.
 // Block (x, c) handles bins [x*kChunk, (x+1)*kChunk) of candidate c: its 1024 threads are 4 groups
 // of 256; group s adds every 4th slab (all loads independent), LDS combines the groups.  The
-// partial sums go to part[c][x] = (sum of terms, sum of reference counts); kld_select_kernel adds
-// them in a fixed order.
+// partial sums go to part[c][x] = (sum of terms, sum of reference counts); the last block to finish
+// adds them in a fixed order and selects.
 constexpr int kChunk = 256;
 constexpr int kFinalGroups = 4;
 
 __global__ void __launch_bounds__(kChunk * kFinalGroups)
 kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs, int rows, int bins,
-                 double alpha_in, double *part, uint32_t *hist_out)
+                 double alpha_in, double *part, uint32_t *hist_out, int wl_lo, int il, double eps, double *kld, int32_t *sel,
+                 long long *grid_out, uint32_t *ticket)
 {
     __shared__ uint32_t cq_s[kFinalGroups][kChunk], cp_s[kFinalGroups][kChunk];
     __shared__ double red[2][kChunk];
@@ -395,26 +400,28 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
         part[2 * ((size_t)c * nchunks + blockIdx.x)] = red[0][0];
         part[2 * ((size_t)c * nchunks + blockIdx.x) + 1] = red[1][0];
     }
-}
-
-__global__ void kld_select_kernel(const KldPlan *__restrict__ plan, const double *__restrict__ part, int nchunks,
-                                  int wl_lo, int il, double eps, double alpha_in, double *kld, int32_t *sel,
-                                  long long *grid_out)
-{
+    // the last block to finish adds the partial sums in a fixed order and selects
+    __shared__ bool last;
+    if (threadIdx.x == 0) {
+        __threadfence();
+        last = atomicAdd(ticket, 1u) == gridDim.x * gridDim.y - 1;
+    }
+    __syncthreads();
+    if (!last) return;
+    __threadfence();
     __shared__ double kl_s[kMaxCand];
-    const int ncand = plan->ncand;
-    const int nb = plan->degenerate ? 0 : plan->nb;
-    const int c = threadIdx.x;
-    if (c < ncand) {
+    const int ncand = gridDim.y;
+    if ((int)threadIdx.x < ncand) {
+        const int cc = threadIdx.x;
         double total = 0.0, nfin = 0.0;
         for (int x = 0; x < nchunks; ++x) {
-            total += part[2 * ((size_t)c * nchunks + x)];
-            nfin += part[2 * ((size_t)c * nchunks + x) + 1];     // exact: integers below 2^53
+            total += __hip_atomic_load(part + 2 * ((size_t)cc * nchunks + x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            nfin += __hip_atomic_load(part + 2 * ((size_t)cc * nchunks + x) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // exact
         }
         const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
         const double kl = nb > 0 ? total / (nfin + alpha * (double)nb) : 0.0;
-        kld[c] = kl;
-        kl_s[c] = kl;
+        kld[cc] = kl;
+        kl_s[cc] = kl;
     }
     __syncthreads();
     if (threadIdx.x != 0) return;
@@ -429,6 +436,7 @@ __global__ void kld_select_kernel(const KldPlan *__restrict__ plan, const double
         grid_out[1] = plan->degenerate ? 0 : plan->base;
         grid_out[2] = plan->degenerate ? 0 : plan->nb;
     }
+    *ticket = 0;      // ready for the next search on this context
 }
 
 static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int wl_hi, int il, int bins, double eps,
@@ -461,25 +469,25 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
 
     const size_t row_bytes = (size_t)bins * 4;
     if (row_bytes <= kLdsBudget) {
-        const int rows_per_pass = (int)std::min<size_t>(rows, kLdsBudget / row_bytes);
-        for (int row0 = 0; row0 < rows; row0 += rows_per_pass) {
-            const int r = std::min(rows_per_pass, rows - row0);
-            const int replicas = (int)std::min<size_t>(threads / kWave, kLdsBudget / (r * row_bytes));
-            const size_t lds = (size_t)replicas * r * row_bytes;
-            hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid), dim3(threads), lds, ctx->stream, w, n, partial,
-                               range_grid, wl_lo, wl_hi, il, bins, plan, slabs, rows, row0, r, replicas, mode, seed, stream);
-        }
+        // rows per block: as many as LDS holds, fewer when the tensor alone cannot fill the GPU
+        int rows_per_group = (int)std::min<size_t>(rows, kLdsBudget / row_bytes);
+        const int want_groups = std::max(1, (2 * ctx->num_cu + hist_grid - 1) / hist_grid);
+        rows_per_group = std::max(1, std::min(rows_per_group, (rows + want_groups - 1) / want_groups));
+        const int groups = (rows + rows_per_group - 1) / rows_per_group;
+        const int replicas = (int)std::min<size_t>(threads / kWave, kLdsBudget / (rows_per_group * row_bytes));
+        const size_t lds = (size_t)replicas * rows_per_group * row_bytes;
+        hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, partial,
+                           range_grid, wl_lo, wl_hi, il, bins, plan, slabs, rows, rows_per_group, replicas, mode, seed, stream);
     } else {
         const size_t zw = (size_t)hist_grid * hist_words;
         hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)std::min<size_t>((zw + 255) / 256, (size_t)ctx->num_cu * 8)),
                            dim3(256), 0, ctx->stream, slabs, zw);
-        hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid), dim3(threads), 0, ctx->stream, w, n, partial, range_grid,
-                           wl_lo, wl_hi, il, bins, plan, slabs, rows, 0, rows, 1, mode, seed, stream);
+        hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, partial, range_grid,
+                           wl_lo, wl_hi, il, bins, plan, slabs, rows, rows, 1, mode, seed, stream);
     }
     hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks, ncand), dim3(kChunk * kFinalGroups), 0, ctx->stream, plan, slabs,
-                       hist_grid, rows, bins, alpha, klpart, hist);
-    hipLaunchKernelGGL(kld_select_kernel, dim3(1), dim3(64), 0, ctx->stream, plan, klpart, nchunks, wl_lo, il, eps, alpha,
-                       kld, sel, reinterpret_cast<long long *>(grid));
+                       hist_grid, rows, bins, alpha, klpart, hist, wl_lo, il, eps, kld, sel, reinterpret_cast<long long *>(grid),
+                       ticket(ctx, 2));
     return hip_status(ctx, hipGetLastError());
 }
 
