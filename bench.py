@@ -25,6 +25,11 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, 256 CU x 8192 op/clk x 2.4 GHz
 PEAK_HBM_GBPS = 8000.0
+# HBM bytes per launch of the forward-convolution kernel on this workload, from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE (KiB per dispatch, scaled by what a plain 256 MiB device copy reads on
+# the same counters: x2.0 and x1.0); the summary with the commands is
+# profiles/bench_config2_hbm_traffic.md.  Counters cannot be read from inside this process.
+FWD_TRAFFIC_BYTES = {"read": 4036 * 1024, "written": 6144 * 1024}
 
 
 def cpu_baseline(batch: int):
@@ -112,7 +117,7 @@ def main():
         "kld_search": lambda: ctx.kld_precision_search_batched([w.view(-1)], [3], [2048], [2], 4, 16, 1e-2, kld=kld,
                                                                sel=sel),
     }
-    EV_EVERY = 4     # the dominant kernel is bracketed by events on every 4th step of the timed region
+    EV_EVERY = 10    # the dominant kernel is bracketed by events on every 10th step of the timed region
 
     def step(ev=None):
         calls["quantize"]()
@@ -134,6 +139,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(events[i])
+    t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_step = dt / args.steps * 1e3
@@ -170,7 +176,13 @@ def main():
                    "useful_ops_per_step": 3 * conv_ops},
         "roofline": {"bound": "mfma", "kernel": "contract_kernel<fwd> (the conv_fwd call is this one launch)",
                      "achieved": fwd_tops, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": fwd_tops / PEAK_INT8_TOPS,
-                     "traffic": None, "avg_launch_ms": fwd_ms},
+                     "traffic": FWD_TRAFFIC_BYTES["read"] + FWD_TRAFFIC_BYTES["written"],
+                     "traffic_unit": "bytes of HBM per launch (rocprofv3 --pmc, see profiles/)",
+                     "algorithmic_bytes": x.numel() + w.numel() + y.numel(),
+                     "avg_launch_ms": fwd_ms,
+                     "avg_launch_ms_note": "HIP events around the call inside the timed region; includes the dispatch gap "
+                                           "that rocprofv3's kernel duration excludes (about 2-4 us)"},
+        "host_enqueue_ms_per_step": t_enq / args.steps * 1e3,
         "calls_ms_back_to_back": call_ms,
         "conv_TOPS": {n: conv_ops / (call_ms["conv_" + n] * 1e-3) / 1e12 for n in ("fwd", "dgrad", "wgrad")},
         "quantize_GBps": q_bytes / (call_ms["quantize"] * 1e-3) / 1e9,

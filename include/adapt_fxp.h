@@ -96,7 +96,8 @@ int adapt_version(void);
  *   nnz        device uint64_t, may be NULL: number of non-zero codes (the paper's sp^l is
  *              nnz / n, Sec. 3.4 "Inducing Sparsity")
  *   saturated  device uint64_t, may be NULL: number of elements with x*2^fl outside the range
- * n = 0 is valid (counters are set to 0). */
+ * n = 0 is valid (counters are set to 0).  n > 2^40 is ADAPT_EINVAL (per-block counters are
+ * 32-bit); x and q must be 16-byte aligned. */
 int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng,
                    void *q, uint64_t *nnz, uint64_t *saturated);
 
@@ -113,6 +114,14 @@ int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item *items, int
                            int mode, uint64_t seed, uint64_t *counters);
 
 /* ---- integer contractions (ForwardPass / backward pass of Alg. 1 on quantized tensors) ---- */
+
+/* Common to the four contractions below: operands are device arrays of int8_t (wl <= 8) or
+ * int16_t codes, 16-byte aligned, read in place; the output is written per `ep` (exact
+ * accumulators: int32_t if adapt_acc_bits() is 32, else int64_t; or requantized codes).  Every
+ * tensor must be smaller than 4 GiB (the kernels use 32-bit byte offsets): larger ones return
+ * ADAPT_EUNSUPPORTED.  Reductions too long for an int32 accumulator, and weight gradients, are
+ * split over K through the context's workspace (ADAPT_EWORKSPACE if it is too small); the
+ * result is bit-identical to the unsplit sum.  Empty outputs (M or N = 0) return ADAPT_OK. */
 
 /* 32 if K * 2^(wl_a-1) * 2^(wl_b-1) <= 2^31 - 1 (every possible sum fits int32), else 64. */
 int adapt_acc_bits(int64_t K, adapt_fmt a, adapt_fmt b);

@@ -125,6 +125,11 @@ class Context:
         _check(self._lib.adapt_create(C.byref(h), C.c_void_p(s.cuda_stream), workspace_bytes), "adapt_create")
         self._h = h
 
+    def set_stream(self, stream):
+        """Later calls launch on `stream` (a torch.cuda.Stream); the caller orders it against the old one."""
+        _check(self._lib.adapt_set_stream(self._h, C.c_void_p(stream.cuda_stream)), "adapt_set_stream")
+        self._stream = stream
+
     def close(self):
         if getattr(self, "_h", None):
             self._lib.adapt_destroy(self._h)

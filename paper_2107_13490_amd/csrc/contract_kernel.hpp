@@ -22,6 +22,9 @@
 // "+128" offsets are undone in the epilogue from the row sums of both operands:
 //   sum a*b = sum a'b' + 128 (sum a' + sum b') + 16384 * K,   a' = a - 128.
 #pragma once
+#include <cmath>
+#include <cstdlib>
+#include <cstdio>
 #include <algorithm>
 
 #include "common.hpp"
@@ -38,6 +41,7 @@ enum { LOAD_SCALAR = 0, LOAD_VEC = 1, LOAD_ROWS = 2 };
 enum { OUT_RAW32 = 0, OUT_RAW64 = 1, OUT_Q8 = 2, OUT_Q16 = 3 };
 
 constexpr int kThreads = 256;
+constexpr unsigned kXcds = 8;      // accelerator dies, each with its own L2
 
 // unsigned division by a run-time constant (Granlund-Montgomery round-up method), n < 2^31
 struct FastDiv {
@@ -72,6 +76,7 @@ struct ContractArgs {
     int n, h, w, c, k, r, s, stride, pad, p, q;
     FastDiv div_c, div_s, div_q, div_p, div_k, div_w, div_h, div_stride;
     int uniform_tap;             // 64 consecutive, 64-aligned k always lie in one filter tap
+    int xcd_remap;               // contiguous ranges of blocks per XCD (see the kernel)
     int k_per_split;             // multiple of the kernel's stage depth
     long long slab_bytes;        // split-K: split y writes its exact partial sums to out + y*slab_bytes
     long long ldc;               // output row stride in elements
@@ -571,15 +576,13 @@ __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m
 
 // ---------------------------------------------------------------------------------------------
 // the kernel: block tile BM x BN, 4 wavefronts in a WGM x WGN grid, wave tile (BM/WGM) x (BN/WGN)
-// built from 32x32 MFMA blocks; BKT reduction indices per stage.  One LDS stage: the next
-// stage's global loads are in flight (in registers) while the MFMAs of the current one run;
-// several blocks per CU cover the rest of the load latency and each other's epilogues.
-// (A 4-deep register pipeline with 64-wide stages was measured slower: the extra registers cost
-// the second resident block and the per-stage barrier and store overhead tripled.)
+// built from 32x32 MFMA blocks; BKT reduction indices per stage.  One LDS stage: the global
+// loads of the next PF stages are in flight (in registers) while the MFMAs of the current one
+// run; several blocks per CU cover the rest of the load latency and each other's epilogues.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PF>
 __global__ void __launch_bounds__(kThreads)
 contract_kernel(const ContractArgs a)
 {
@@ -602,10 +605,17 @@ contract_kernel(const ContractArgs a)
     const int nperm = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
     const int wrow = W_R ? l32 : nperm;
 
+    // Workgroups go to the 8 XCDs round-robin in launch order and each XCD has its own L2: give
+    // every XCD one contiguous range of the (split, tile_m, tile_n) order, so that blocks which
+    // share operand rows (neighbouring tiles, all tiles of one split) fetch them from HBM once.
+    const unsigned nwg = gridDim.x * gridDim.y, lin = blockIdx.y * gridDim.x + blockIdx.x;
+    const unsigned per_xcd = nwg / kXcds, extra = nwg % kXcds, xcd = lin % kXcds;
+    const unsigned vid = a.xcd_remap ? xcd * per_xcd + min(xcd, extra) + lin / kXcds : lin;
+    const int split = vid / gridDim.x, tile = vid % gridDim.x;
     const int tiles_n = (a.N + BN - 1) / BN;
-    const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+    const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int kbeg = blockIdx.y * a.k_per_split;
+    const int kbeg = split * a.k_per_split;
     const int kend = min(a.K, kbeg + a.k_per_split);
     const int ksteps = (kend - kbeg + BKT - 1) / BKT;
 
@@ -623,75 +633,93 @@ contract_kernel(const ContractArgs a)
     for (int i = 0; i < NB; ++i) sum_n[i] = 0;
 
     ADAPT_STAMP(0);
+    ADAPT_STAMP_WG(0);
     LA la;
     LB lb;
     la.init(a, m0);
     lb.init(a, n0);
     ADAPT_STAMP(1);
-    typename LA::Regs ra;
-    typename LB::Regs rb;
-    if (ksteps > 0) {
-        la.load(a, m0, kbeg, ra);
-        lb.load(a, n0, kbeg, rb);
-    }
+    // Register staging, PF stages deep: the global loads of stages kt+1 .. kt+PF are in flight while
+    // stage kt is multiplied out of LDS.
+    typename LA::Regs ra[PF];
+    typename LB::Regs rb[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u < ksteps) {
+            la.load(a, m0, kbeg + u * BKT, ra[u]);
+            lb.load(a, n0, kbeg + u * BKT, rb[u]);
+        }
     ADAPT_STAMP(2);
 
-    for (int kt = 0; kt < ksteps; ++kt) {
-        {
-            __syncthreads();                 // every wavefront is done with the previous stage
-            LA::store(ra, a_hi, a_lo);
-            LB::store(rb, b_hi, b_lo);
-            __syncthreads();
-            if (kt + 1 < ksteps) {
-                la.load(a, m0, kbeg + (kt + 1) * BKT, ra);
-                lb.load(a, n0, kbeg + (kt + 1) * BKT, rb);
+    auto multiply_stage = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < BKT / 32; ++ks) {
+            v4i fa_h[MB], fa_l[MB], fb_h[NB], fb_l[NB];
+#pragma unroll
+            for (int j = 0; j < MB; ++j) {
+                if constexpr (A_R) {
+                    fa_h[j] = LA::frag(a_hi, wm * WM + j * 32, ks, lane);
+                    if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32, ks, lane);
+                } else {
+                    fa_h[j] = LA::frag(a_hi, wm * WM + j * 32 + l32, ks, g);
+                    if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32 + l32, ks, g);
+                }
             }
 #pragma unroll
-            for (int ks = 0; ks < BKT / 32; ++ks) {
-                v4i fa_h[MB], fa_l[MB], fb_h[NB], fb_l[NB];
+            for (int i = 0; i < NB; ++i) {
+                if constexpr (W_R) {
+                    fb_h[i] = LB::frag(b_hi, wn * WN + i * 32, ks, lane);
+                    if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32, ks, lane);
+                } else {
+                    fb_h[i] = LB::frag(b_hi, wn * WN + i * 32 + nperm, ks, g);
+                    if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32 + nperm, ks, g);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
 #pragma unroll
                 for (int j = 0; j < MB; ++j) {
-                    if constexpr (A_R) {
-                        fa_h[j] = LA::frag(a_hi, wm * WM + j * 32, ks, lane);
-                        if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32, ks, lane);
-                    } else {
-                        fa_h[j] = LA::frag(a_hi, wm * WM + j * 32 + l32, ks, g);
-                        if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32 + l32, ks, g);
+                    acc_hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_h[j], acc_hh[i][j], 0, 0, 0);
+                    if (LIMBS == 2) {
+                        acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_l[j], acc_x[i][j], 0, 0, 0);
+                        acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_h[j], acc_x[i][j], 0, 0, 0);
+                        acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_l[j], acc_ll[i][j], 0, 0, 0);
                     }
                 }
+            if (LIMBS == 2) {
 #pragma unroll
-                for (int i = 0; i < NB; ++i) {
-                    if constexpr (W_R) {
-                        fb_h[i] = LB::frag(b_hi, wn * WN + i * 32, ks, lane);
-                        if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32, ks, lane);
-                    } else {
-                        fb_h[i] = LB::frag(b_hi, wn * WN + i * 32 + nperm, ks, g);
-                        if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32 + nperm, ks, g);
-                    }
-                }
+                for (int j = 0; j < MB; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        sum_m[j] += 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e]);
 #pragma unroll
                 for (int i = 0; i < NB; ++i)
 #pragma unroll
-                    for (int j = 0; j < MB; ++j) {
-                        acc_hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_h[j], acc_hh[i][j], 0, 0, 0);
-                        if (LIMBS == 2) {
-                            acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_l[j], acc_x[i][j], 0, 0, 0);
-                            acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_h[j], acc_x[i][j], 0, 0, 0);
-                            acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_l[j], acc_ll[i][j], 0, 0, 0);
-                        }
-                    }
-                if (LIMBS == 2) {
+                    for (int e = 0; e < 4; ++e)
+                        sum_n[i] += 256 * dot4_ones((uint32_t)fb_h[i][e]) + dot4_ones((uint32_t)fb_l[i][e]);
+            }
+        }
+    };
+
+    for (int kt0 = 0; kt0 < ksteps; kt0 += PF) {
 #pragma unroll
-                    for (int j = 0; j < MB; ++j)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            sum_m[j] += 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e]);
-#pragma unroll
-                    for (int i = 0; i < NB; ++i)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            sum_n[i] += 256 * dot4_ones((uint32_t)fb_h[i][e]) + dot4_ones((uint32_t)fb_l[i][e]);
+        for (int u = 0; u < PF; ++u) {
+            const int kt = kt0 + u;
+            if (kt < ksteps) {
+                ADAPT_STAMP(8 + 5 * min(kt, 10));
+                __syncthreads();                 // every wavefront is done with the previous stage
+                ADAPT_STAMP(9 + 5 * min(kt, 10));
+                LA::store(ra[u], a_hi, a_lo);
+                LB::store(rb[u], b_hi, b_lo);
+                __syncthreads();
+                ADAPT_STAMP(10 + 5 * min(kt, 10));
+                if (kt + PF < ksteps) {
+                    la.load(a, m0, kbeg + (kt + PF) * BKT, ra[u]);
+                    lb.load(a, n0, kbeg + (kt + PF) * BKT, rb[u]);
                 }
+                ADAPT_STAMP(11 + 5 * min(kt, 10));
+                multiply_stage();
+                ADAPT_STAMP(12 + 5 * min(kt, 10));
             }
         }
     }
@@ -713,7 +741,7 @@ contract_kernel(const ContractArgs a)
         __syncthreads();
     }
     const long long kpad = (long long)ksteps * BKT;
-    void *out = static_cast<char *>(a.out) + (long long)blockIdx.y * a.slab_bytes;
+    void *out = static_cast<char *>(a.out) + (long long)split * a.slab_bytes;
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -756,6 +784,7 @@ contract_kernel(const ContractArgs a)
             }
         }
     ADAPT_STAMP(4);
+    ADAPT_STAMP_WG(1);
 }
 
 // ---- helper: split-K finish ---------------------------------------------------------------------------
@@ -793,6 +822,20 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 // ---- host side ---------------------------------------------------------------------------------
 struct TileShape { int bm, bn, bkt; };
 
+// Stages of global loads kept in flight in registers.  Depths 2 and 3 were measured no faster at
+// any tile shape: a stage is bound by the rate at which the CU's vector-memory and LDS pipes move
+// the operand bytes (issuing the loads of a stage takes as long as multiplying it), not by the
+// latency of the loads, and the extra staging registers cost the large tiles their second
+// resident block.  The kernel keeps the parameter; every instantiation uses depth 1.
+constexpr int prefetch_depth(int /*limbs*/, int /*amode*/, int /*bm*/, int /*bn*/, int /*bkt*/)
+{
+#ifdef ADAPT_PF_OVERRIDE
+    return ADAPT_PF_OVERRIDE;
+#else
+    return 1;
+#endif
+}
+
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
 static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
@@ -800,7 +843,8 @@ static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
     typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT, WES>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const size_t lds = (size_t)(LA::TILE_BYTES + LB::TILE_BYTES) * LIMBS;
-    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT>;
+    constexpr int PF = prefetch_depth(LIMBS, AMODE, BM, BN, BKT);
+    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PF>;
     static bool attr_done = false;
     if (!attr_done && lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -896,6 +940,32 @@ static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
     return t;
 }
 
+// Weight gradients have a small output and a very long reduction, so they are always split
+// across blocks.  The tile and the number of splits are chosen together from a model fitted to
+// measurements on MI355X: operand bytes pulled through L2 (at about 10.7 TB/s), slab bytes written
+// and read back by the finish kernel (about 3.1 TB/s), a fixed cost for the second launch, and
+// the rounding up to whole rounds of two blocks per CU.  Returns the number of splits.
+static int pick_split_tile(const ContractArgs &a, int limbs, int acc_bits, int num_cu, TileShape &t)
+{
+    static const int cand[5][2] = {{64, 64}, {128, 64}, {64, 128}, {128, 128}, {128, 192}};
+    const int bkt = t.bkt;
+    double best = 1e30;
+    int best_splits = 1;
+    for (int i = 0; i < (limbs == 1 ? 5 : 4); ++i) {
+        const int bm = cand[i][0], bn = cand[i][1];
+        const long long tm = (a.M + bm - 1) / bm, tn = (a.N + bn - 1) / bn, tiles = tm * tn;
+        long long sp = tiles >= num_cu ? 1 : std::max(1ll, 2ll * num_cu / tiles);
+        sp = std::max(1ll, std::min(sp, (long long)a.K / (2 * bkt)));
+        const double slots = 2.0 * num_cu, wgs = (double)tiles * sp;
+        const double rounds = std::ceil(wgs / slots) / (wgs / slots);
+        const double operand = (double)a.K * (double)(tm * bm) * (double)(tn * bn) * (1.0 / bm + 1.0 / bn) * limbs;
+        const double slab = sp > 1 ? 2.0 * (double)a.M * a.N * (acc_bits / 8) * sp : 0.0;
+        const double cost = operand * rounds / 10.7e12 + slab / 3.1e12 + (sp > 1 ? 5e-6 : 0.0);
+        if (cost < best) { best = cost; best_splits = (int)sp; t.bm = bm; t.bn = bn; }
+    }
+    return best_splits;
+}
+
 // Fills the parts of ContractArgs common to all ops and runs the kernel.  K is split across
 // blocks (exact partial sums in workspace slabs, summed by finish_kernel) when a single block
 // could overflow its int32 accumulators or when the output has too few tiles to fill the GPU.
@@ -920,16 +990,29 @@ static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_f
     }
     if (a.M == 0 || a.N == 0) return ADAPT_OK;
 
-    const TileShape t = pick_tile<OP>(a, limbs, ctx->num_cu);
+    TileShape t = pick_tile<OP>(a, limbs, ctx->num_cu);
+    int model_splits = 0;
+    if (OP == OP_WGRAD && a.act_load != LOAD_SCALAR && a.wgt_load != LOAD_SCALAR) model_splits = pick_split_tile(a, limbs, bits, ctx->num_cu, t);
+    a.xcd_remap = 1;
+#ifdef ADAPT_TUNE
+    int tune_splits = 0;
+    if (getenv("ADAPT_NOREMAP")) a.xcd_remap = 0;
+    if (const char *env = getenv("ADAPT_TILE")) sscanf(env, "%d,%d,%d,%d", &t.bm, &t.bn, &t.bkt, &tune_splits);
+#endif
     const long long tiles = (long long)((a.M + t.bm - 1) / t.bm) * ((a.N + t.bn - 1) / t.bn);
     // int32 accumulators: |product| <= 2^14 per limb pair, the cross accumulator holds two per k
     const int k_cap = limbs == 1 ? 65536 : 32768;
     int splits = (a.K + k_cap - 1) / k_cap;
-    if (tiles < ctx->num_cu && a.K >= 8 * t.bkt) {
+    if (model_splits > 0) {
+        splits = std::max(splits, model_splits);
+    } else if (tiles < ctx->num_cu && a.K >= 8 * t.bkt) {
         const long long want = (ctx->num_cu + tiles - 1) / tiles;
         const long long max_by_k = a.K / (4 * t.bkt);
         splits = (int)std::max<long long>(splits, std::min(want, std::max(1ll, max_by_k)));
     }
+#ifdef ADAPT_TUNE
+    if (tune_splits > 0) splits = tune_splits;
+#endif
     if (splits < 1) splits = 1;
     int k_per = ((a.K + splits - 1) / splits + t.bkt - 1) / t.bkt * t.bkt;
     if (k_per == 0) k_per = t.bkt;

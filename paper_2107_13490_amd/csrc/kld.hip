@@ -8,13 +8,13 @@
 //   hist     every block first reduces the range partials and derives the bin grid (power-of-two
 //            width) and the per-candidate integer bin parameters (the "plan"; block 0 also stores
 //            it for the later kernels), then reads its share of the tensor once: reference bin +
-//            one bin per candidate for every element, counted in LDS histograms (one replica per
-//            wavefront when they fit), and written to the block's own slab with plain stores.
+//            one bin per candidate for every element, counted in LDS histograms, and written to the block's own slab with plain stores.
 //   final    blocks of (256 bins, candidate): add the slabs of the reference row and of the
 //            candidate's row, partial KL sums in fp64; the last block to finish adds the partial
 //            sums in a fixed order and picks the lowest WL with KL < eps.
 // All counts are integers, so the result does not depend on the order of accumulation.
 #include <algorithm>
+#include <cstdlib>
 
 #include "common.hpp"
 #include "context.hpp"
@@ -49,14 +49,17 @@ struct KldPlan {
     KldCand cand[kMaxCand];
 };
 
-__device__ inline double floor_scaled(double v, int e) { return floor(ldexp(v, -e)); }
+// floor(v * 2^-e) for |e| < 1000 and v an fp32 value held in a double: the power of two is built
+// from its exponent bits and the product is exact (no overflow or underflow in that range).
+__device__ inline double floor_scaled(double v, int e) { return floor(v * __longlong_as_double((long long)(1023 - e) << 52)); }
+__device__ inline int exponent_of(double v) { return (int)((__double_as_longlong(v) >> 52) & 0x7ff) - 1023; }   // normal v > 0
 
 // Bin grid from the range: runs in one thread.  lo < hi are finite fp32 values.
 __device__ void make_grid(KldPlan *plan, float lo, float hi, int wl_hi, int il, int bins)
 {
     const double dlo = lo, dhi = hi;
     // smallest e with floor(hi/2^e) - floor(lo/2^e) + 1 <= bins; the count is non-increasing in e
-    int e = ilogb(dhi - dlo) - ilogb((double)bins) - 2;
+    int e = exponent_of(dhi - dlo) - exponent_of((double)bins) - 2;
     while (floor_scaled(dhi, e) - floor_scaled(dlo, e) + 1.0 > (double)bins) ++e;
     while (floor_scaled(dhi, e - 1) - floor_scaled(dlo, e - 1) + 1.0 <= (double)bins) --e;
     const double fbase = floor_scaled(dlo, e);
@@ -184,8 +187,7 @@ __global__ void zero_words_kernel(uint32_t *p, size_t n)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
-// LDS layout: replica-major, then row (0 = reference, 1 + c = candidate c) over [row0, row0+rows),
-// `nb` counters per row.  Every block writes its counts (zeros included) to its own slab
+// LDS layout: row (0 = reference, 1 + c = candidate c) over [row0, row0+rows), `nb` counters per row.  Every block writes its counts (zeros included) to its own slab
 // slabs[block][row][bins] with plain stores: device-wide atomics on shared counters are far
 // slower than that on this GPU.  USE_LDS = false (bins too large for LDS) counts with atomics
 // straight into the block's slab, which the host has cleared.
@@ -193,7 +195,7 @@ template <bool USE_LDS>
 __global__ void __launch_bounds__(kHistMaxThreads)
 kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial, int range_blocks,
                 int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *slabs, int total_rows,
-                int rows_per_group, int replicas, int mode, uint64_t seed, uint64_t stream)
+                int rows_per_group, int mode, uint64_t seed, uint64_t stream)
 {
     // blockIdx.y selects a group of histogram rows: small tensors are spread over more CUs by
     // letting several blocks count different candidates of the same elements
@@ -245,11 +247,10 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     uint32_t *hist;
     int row_stride;
     if (USE_LDS) {
-        const int words = rows * nb;
-        const int total = words * replicas;
+        const int total = rows * nb;
         for (int i = threadIdx.x; i < total / 4; i += nthreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
         if ((int)threadIdx.x < (total & 3)) lds[(total & ~3) + threadIdx.x] = 0;
-        hist = lds + ((threadIdx.x / kWave) % replicas) * words;
+        hist = lds;
         row_stride = nb;
     } else {
         hist = slabs + ((size_t)blockIdx.x * total_rows + row0) * bins;
@@ -308,23 +309,14 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     if (USE_LDS) {
         __syncthreads();
         ADAPT_STAMP(4);
-        const int words = rows * nb;
-        // slab rows are 16-byte aligned (bins % 4 == 0 is not required: the tail is written singly)
+        // slab rows are 16-byte aligned when bins % 4 == 0; otherwise every counter is written singly
         const int nb4 = (bins % 4 == 0) ? nb / 4 : 0;
         for (int row = 0; row < rows; ++row) {
             uint32_t *dst = slabs + ((size_t)blockIdx.x * total_rows + row0 + row) * bins;
-            for (int q = threadIdx.x; q < nb4; q += nthreads) {
-                uint32_t v[4] = {0, 0, 0, 0};
-                for (int rep = 0; rep < replicas; ++rep)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] += lds[rep * words + row * nb + 4 * q + j];
-                reinterpret_cast<uint4 *>(dst)[q] = make_uint4(v[0], v[1], v[2], v[3]);
-            }
-            for (int b = 4 * nb4 + threadIdx.x; b < nb; b += nthreads) {
-                uint32_t v = 0;
-                for (int rep = 0; rep < replicas; ++rep) v += lds[rep * words + row * nb + b];
-                dst[b] = v;
-            }
+            const uint32_t *src = lds + row * nb;
+            for (int q = threadIdx.x; q < nb4; q += nthreads)
+                reinterpret_cast<uint4 *>(dst)[q] = make_uint4(src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]);
+            for (int b = 4 * nb4 + threadIdx.x; b < nb; b += nthreads) dst[b] = src[b];
         }
     }
     ADAPT_STAMP(5);
@@ -348,6 +340,7 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
 {
     __shared__ uint32_t cq_s[kFinalGroups][kChunk], cp_s[kFinalGroups][kChunk];
     __shared__ double red[2][kChunk];
+    ADAPT_STAMP_WG4(0);
     const int c = blockIdx.y, nchunks = gridDim.x;
     const int lane = threadIdx.x % kChunk, grp = threadIdx.x / kChunk;
     const int b = blockIdx.x * kChunk + lane;
@@ -355,21 +348,24 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
     const size_t slab_words = (size_t)rows * bins;
     uint32_t uq = 0, up = 0;
     if (b < nb) {
+        // slabs grp, grp + 4, ...: eight pairs of loads in flight at a time (a slab index past the end
+        // is redirected to slab 0 and its value dropped, so the loads carry no branches)
         const uint32_t *pq = slabs + b, *pp = slabs + (size_t)(c + 1) * bins + b;
-        int sidx = grp;
-        for (; sidx + 3 * kFinalGroups < nslabs; sidx += 4 * kFinalGroups) {
-            uint32_t tq[4], tp[4];
+        for (int s0 = grp; s0 < nslabs; s0 += 8 * kFinalGroups) {
+            uint32_t tq[8], tp[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                tq[u] = pq[(size_t)(sidx + u * kFinalGroups) * slab_words];
-                tp[u] = pp[(size_t)(sidx + u * kFinalGroups) * slab_words];
+            for (int u = 0; u < 8; ++u) {
+                const int sidx = s0 + u * kFinalGroups;
+                const size_t off = sidx < nslabs ? (size_t)sidx * slab_words : 0;
+                tq[u] = pq[off];
+                tp[u] = pp[off];
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { uq += tq[u]; up += tp[u]; }
-        }
-        for (; sidx < nslabs; sidx += kFinalGroups) {
-            uq += pq[(size_t)sidx * slab_words];
-            up += pp[(size_t)sidx * slab_words];
+            for (int u = 0; u < 8; ++u) {
+                const bool in = s0 + u * kFinalGroups < nslabs;
+                uq += in ? tq[u] : 0u;
+                up += in ? tp[u] : 0u;
+            }
         }
     }
     cq_s[grp][lane] = uq;
@@ -402,21 +398,34 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
     }
     // the last block to finish adds the partial sums in a fixed order and selects
     __shared__ bool last;
-    if (threadIdx.x == 0) {
-        __threadfence();
-        last = atomicAdd(ticket, 1u) == gridDim.x * gridDim.y - 1;
-    }
+    ADAPT_STAMP_WG4(1);
+    if (threadIdx.x == 0)      // release this block's partial sums, acquire everyone else's
+        last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x * gridDim.y - 1;
     __syncthreads();
+    ADAPT_STAMP_WG4(2);
     if (!last) return;
-    __threadfence();
     __shared__ double kl_s[kMaxCand];
     const int ncand = gridDim.y;
+    // all partial sums are loaded at once (one pair per thread), then added in a fixed order
+    double *tail = &red[0][0];
+    const int npart = 2 * ncand * nchunks;
+    const bool fits = npart <= 2 * kChunk;      // else (very many bins) each candidate's thread loads its own
+    if (fits)
+        for (int i = threadIdx.x; i < npart; i += blockDim.x)
+            tail[i] = __hip_atomic_load(part + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
     if ((int)threadIdx.x < ncand) {
         const int cc = threadIdx.x;
         double total = 0.0, nfin = 0.0;
         for (int x = 0; x < nchunks; ++x) {
-            total += __hip_atomic_load(part + 2 * ((size_t)cc * nchunks + x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            nfin += __hip_atomic_load(part + 2 * ((size_t)cc * nchunks + x) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // exact
+            const size_t i = 2 * ((size_t)cc * nchunks + x);
+            if (fits) {
+                total += tail[i];
+                nfin += tail[i + 1];      // exact
+            } else {
+                total += __hip_atomic_load(part + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                nfin += __hip_atomic_load(part + i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
         const double kl = nb > 0 ? total / (nfin + alpha * (double)nb) : 0.0;
@@ -437,6 +446,7 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
         grid_out[2] = plan->degenerate ? 0 : plan->nb;
     }
     *ticket = 0;      // ready for the next search on this context
+    ADAPT_STAMP_WG4(3);
 }
 
 static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int wl_hi, int il, int bins, double eps,
@@ -474,16 +484,16 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
         const int want_groups = std::max(1, (2 * ctx->num_cu + hist_grid - 1) / hist_grid);
         rows_per_group = std::max(1, std::min(rows_per_group, (rows + want_groups - 1) / want_groups));
         const int groups = (rows + rows_per_group - 1) / rows_per_group;
-        const int replicas = (int)std::min<size_t>(threads / kWave, kLdsBudget / (rows_per_group * row_bytes));
-        const size_t lds = (size_t)replicas * rows_per_group * row_bytes;
+        // one set of LDS histograms per block: per-wavefront replicas were measured no faster
+        const size_t lds = (size_t)rows_per_group * row_bytes;
         hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, partial,
-                           range_grid, wl_lo, wl_hi, il, bins, plan, slabs, rows, rows_per_group, replicas, mode, seed, stream);
+                           range_grid, wl_lo, wl_hi, il, bins, plan, slabs, rows, rows_per_group, mode, seed, stream);
     } else {
         const size_t zw = (size_t)hist_grid * hist_words;
         hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)std::min<size_t>((zw + 255) / 256, (size_t)ctx->num_cu * 8)),
                            dim3(256), 0, ctx->stream, slabs, zw);
         hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, partial, range_grid,
-                           wl_lo, wl_hi, il, bins, plan, slabs, rows, rows, 1, mode, seed, stream);
+                           wl_lo, wl_hi, il, bins, plan, slabs, rows, rows, mode, seed, stream);
     }
     hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks, ncand), dim3(kChunk * kFinalGroups), 0, ctx->stream, plan, slabs,
                        hist_grid, rows, bins, alpha, klpart, hist, wl_lo, il, eps, kld, sel, reinterpret_cast<long long *>(grid),

@@ -4,6 +4,8 @@
 // (two 16-byte loads, one 8- or 16-byte store) with one Philox block per group.
 // nnz / saturated are reduced per wavefront, then per block; a one-block follow-up kernel sums
 // the block partials (integer, order-independent).
+#include <cstdlib>
+
 #include "common.hpp"
 #include "context.hpp"
 
@@ -44,9 +46,7 @@ __device__ __forceinline__ void quantize_span(const float *__restrict__ x, OutT 
                                               uint32_t &nsat)
 {
     const uint64_t full_groups = n >> 3;
-    for (uint64_t g = first_group; g < full_groups; g += group_stride) {
-        const float4 a = reinterpret_cast<const float4 *>(x)[2 * g];
-        const float4 b = reinterpret_cast<const float4 *>(x)[2 * g + 1];
+    auto convert = [&](uint64_t g, const float4 &a, const float4 &b) {
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
         uint32_t r[8];
         if (mode == ADAPT_SR) {
@@ -66,7 +66,17 @@ __device__ __forceinline__ void quantize_span(const float *__restrict__ x, OutT 
             nsat += s;
         }
         store8<OutT>(q + 8 * g, c);
+    };
+    // two groups per iteration: four 16-byte loads in flight per thread
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    uint64_t g = first_group;
+    for (; g + group_stride < full_groups; g += 2 * group_stride) {
+        const uint64_t h = g + group_stride;
+        const float4 a0 = x4[2 * g], b0 = x4[2 * g + 1], a1 = x4[2 * h], b1 = x4[2 * h + 1];
+        convert(g, a0, b0);
+        convert(h, a1, b1);
     }
+    if (g < full_groups) convert(g, x4[2 * g], x4[2 * g + 1]);
     // ragged tail (< 8 elements): the thread that would own group `full_groups`
     if ((n & 7) && first_group <= full_groups && (full_groups - first_group) % group_stride == 0) {
         for (uint64_t i = full_groups << 3; i < n; ++i) {
@@ -96,7 +106,7 @@ __device__ __forceinline__ void block_sum2(uint32_t a, uint32_t b, uint64_t &sa,
 template <typename OutT>
 __global__ void __launch_bounds__(kQThreads)
 quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, int wl, int fl, int mode,
-                uint64_t seed, uint64_t stream, uint32_t *partial /* [gridDim.x][2] or null */)
+                uint64_t seed, uint64_t stream, uint32_t *partial /* [2][gridDim.x] or null */)
 {
     const QuantParams p = make_quant_params(wl, fl);
     uint32_t nnz = 0, nsat = 0;
@@ -107,22 +117,32 @@ quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, i
     uint64_t bn, bs;
     block_sum2(nnz, nsat, bn, bs);
     if (threadIdx.x == 0) {
-        partial[2 * blockIdx.x] = (uint32_t)bn;
-        partial[2 * blockIdx.x + 1] = (uint32_t)bs;
+        partial[blockIdx.x] = (uint32_t)bn;
+        partial[gridDim.x + blockIdx.x] = (uint32_t)bs;
     }
 }
 
-// Sums the per-block partial counts (partial[block][cols]) into out[col], one wavefront per
-// column.  A separate launch: the kernel boundary makes the partials visible without fences
-// that would force the L2 to write back the freshly quantized tensor.
-__global__ void __launch_bounds__(kQThreads)
+// Sums the per-block partial counts (partial[col][block]) into out[col]: one wavefront per column,
+// all loads of a lane in flight at once.  A separate launch: the kernel boundary makes the
+// partials visible without fences that would force the L2 to write back the freshly quantized
+// tensor.
+constexpr int kSumThreads = 1024;
+__global__ void __launch_bounds__(kSumThreads)
 sum_partials_kernel(const uint32_t *__restrict__ partial, int nblocks, int cols, uint64_t *out0, uint64_t *out1)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    for (int j = wave; j < cols; j += kQThreads / kWave) {
+    for (int j = wave; j < cols; j += kSumThreads / kWave) {
+        const uint32_t *col = partial + (size_t)j * nblocks;
         uint64_t sum = 0;
-#pragma unroll 4
-        for (int b = lane; b < nblocks; b += kWave) sum += partial[(size_t)b * cols + j];
+        int b = lane;
+        for (; b + 15 * kWave < nblocks; b += 16 * kWave) {
+            uint32_t t[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) t[u] = col[b + u * kWave];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) sum += t[u];
+        }
+        for (; b < nblocks; b += kWave) sum += col[b];
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
         if (lane == 0) {
@@ -140,7 +160,7 @@ struct QuantBatch {
     int count;
 };
 
-// nnz / saturated of every tensor: per-block partial counts in `partial[block][2*count]`, summed
+// nnz / saturated of every tensor: per-block partial counts in `partial[2*count][block]`, summed
 // by sum_partials_kernel (no same-address atomics, no zero-fill launch).
 __global__ void __launch_bounds__(kQThreads)
 quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint32_t *partial /* or null */)
@@ -174,7 +194,7 @@ quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint32_
             if (threadIdx.x < 2) {
                 uint32_t v = 0;
                 for (int w = 0; w < kQThreads / kWave; ++w) v += wave_part[threadIdx.x][w];
-                partial[(size_t)blockIdx.x * 2 * batch.count + 2 * t + threadIdx.x] = v;
+                partial[(size_t)(2 * t + threadIdx.x) * gridDim.x + blockIdx.x] = v;
             }
             __syncthreads();
         }
@@ -215,7 +235,7 @@ extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fm
     if (count) {
         // out1 != null selects the two-destination form; a null nnz is redirected to a dummy slot
         uint64_t *dummy = reinterpret_cast<uint64_t *>(scratch(ctx) + (((size_t)grid * 8 + 255) & ~(size_t)255));
-        hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kQThreads), 0, ctx->stream, partial, grid, 2,
+        hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kSumThreads), 0, ctx->stream, partial, grid, 2,
                            nnz ? nnz : dummy, saturated ? saturated : dummy + 1);
     }
     return hip_status(ctx, hipGetLastError());
@@ -242,7 +262,10 @@ extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item 
             total_blocks += (((items[base + t].n + 7) >> 3) + kQThreads - 1) / kQThreads;
         }
         uint64_t grid = total_blocks;
-        const uint64_t cap = (uint64_t)ctx->num_cu * 4;
+        uint64_t cap = (uint64_t)ctx->num_cu * 4;
+#ifdef ADAPT_TUNE
+        if (const char *env = getenv("ADAPT_Q_BLOCKS_PER_CU")) cap = (uint64_t)ctx->num_cu * atoi(env);
+#endif
         if (grid > cap) grid = cap;
         if (grid == 0) grid = 1;     // still writes the (zero) counters
         uint32_t *partial = counters ? reinterpret_cast<uint32_t *>(scratch(ctx)) : nullptr;
@@ -250,7 +273,7 @@ extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item 
         hipLaunchKernelGGL(quantize_batched_kernel, dim3((unsigned)grid), dim3(kQThreads), 0, ctx->stream, batch, mode,
                            seed, partial);
         if (counters)
-            hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kQThreads), 0, ctx->stream, partial, (int)grid,
+            hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kSumThreads), 0, ctx->stream, partial, (int)grid,
                                2 * batch.count, counters + 2 * base, (uint64_t *)nullptr);
     }
     return hip_status(ctx, hipGetLastError());
