@@ -183,6 +183,52 @@ int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kld_item *ite
                                        int wl_lo, int wl_hi, double eps, double alpha, int mode,
                                        uint64_t seed, double *kld, int32_t *sel);
 
+/* ---- PushUp (Sec. 3.3 "The PushUp Operation") ---------------------------------------------- */
+
+/* Gradient diversity of one layer over a lookback window of `count` gradient tensors of n
+ * elements each, tensor k held as fixed-point codes g_k = c_k * 2^-fl_k (int8_t for wl <= 8,
+ * else int16_t, as written by the contractions' requantizing epilogue):
+ *   ds = sum_k ||g_k||_2 / || sum_k g_k ||_2
+ * All sums of codes and of squares are exact integers (the codes are aligned to the finest grid
+ * of the window before they are added); the norms and the ratio are fp64.
+ *   items  HOST array of `count` descriptors, oldest first (read before the call returns; `g`
+ *          inside is a device pointer, 16-byte aligned)
+ *   sums   device uint64_t[count + 2] or NULL: sum_i c_k[i]^2 for k < count, then the sums of
+ *          the low and of the high 32-bit halves of (sum_k c_k[i] * 2^(fl_max - fl_k))^2, so
+ *          that the squared norm of the sum is (sums[count+1] * 2^32 + sums[count]) * 4^-fl_max
+ *   out    device double[2]: ds (+inf if only the denominator is 0, NaN if both are), and
+ *          log ds (natural) when 0 < ds < inf, else 1 (the paper's "otherwise" case)
+ * Limits: 1 <= count <= 64, n <= 2^30, and sum_k 2^(wl_k - 1 + fl_max - fl_k) < 2^31 (the element
+ * sum is kept in 32 bits); ADAPT_EUNSUPPORTED beyond them.  n = 0 gives NaN and 1. */
+typedef struct { const void *g; int32_t wl, fl; } adapt_grad_item;
+int adapt_gradient_diversity(adapt_ctx *ctx, const adapt_grad_item *items, int count, size_t n,
+                             uint64_t *sums, double *out);
+
+/* The scalar rules of the switch controller.  Host functions: no device, no context.
+ * Strategy st of the suggestion rule. */
+enum { ADAPT_ST_MIN = 0, ADAPT_ST_MEAN = 1, ADAPT_ST_MAX = 2 };
+typedef struct { int wl, fl, s1, s2, s; } adapt_pushup_result;
+/* New <WL,FL> of a layer from its diversity `ds` and the PushDown result <wl_min, fl_min>.
+ * With L = log ds (natural) if 0 < ds < inf, else 1:
+ *   L > 0:  s1 = max(ceil(1/(L - 1)), 1)  (L = 1: wl_cap),  s2 = max(min(32 L^2 - 1, 32) - fl_min, 1)
+ *           rounded up, both at most wl_cap;  s = min | ceil(mean) | max of (s1, s2) by `strategy`
+ *   else    s = 1
+ *   FL = min(fl_min + s, wl_cap), WL = min(max(wl_min, fl_min) + 1, wl_cap), then the buffer bits of
+ *   "Dealing with Fixed-Points Limited Range": FL = min(FL, wl_cap - buff),
+ *   WL = max(min(FL + buff, wl_cap), WL).  wl_cap is the paper's 32 or the widest length the
+ *   caller's kernels take.  ADAPT_EINVAL for arguments out of range. */
+int adapt_pushup_suggest(double ds, int wl_min, int fl_min, int strategy, int buff, int wl_cap,
+                         adapt_pushup_result *res);
+/* "Strategy, Resolution and Lookback": |loss_avg| > |loss_now| gives min; otherwise min -> mean,
+ * mean -> max, max stays.  Returns the new strategy. */
+int adapt_strategy_next(int strategy, double loss_avg, double loss_now);
+/* lb_new = min(max(ceil(lb_upr / ds), lb_lwr), lb_upr) if 0 < ds < inf, else lb_upr; returns
+ * ceil(lb_new * gamma + (1 - gamma) * lb). */
+int adapt_lookback_next(int lb, double ds, int lb_lwr, int lb_upr, double gamma);
+/* r + 1 if lb == lb_upr, r - 1 if lb == lb_lwr (first case wins when both hold), clamped to
+ * [r_lwr, r_upr]; r unchanged otherwise. */
+int adapt_resolution_next(int r, int lb, int lb_lwr, int lb_upr, int r_lwr, int r_upr);
+
 #ifdef __cplusplus
 }
 #endif

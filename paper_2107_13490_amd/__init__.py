@@ -5,6 +5,6 @@ runs in the HIP library (paper_2107_13490_amd/libadapt_fxp.so); PyTorch only pro
 memory and streams.  There is no CPU fallback: if the library is missing, loading raises.
 """
 from .binding import (  # noqa: F401
-    RN_HALF_UP, SR, AdaptError, Context, ConvDesc, Epilogue, Fmt, Rng, acc_bits, library_path,
-    load_library,
+    RN_HALF_UP, SR, ST_MAX, ST_MEAN, ST_MIN, AdaptError, Context, ConvDesc, Epilogue, Fmt, Rng, acc_bits,
+    library_path, load_library, lookback_next, pushup_suggest, resolution_next, strategy_next,
 )

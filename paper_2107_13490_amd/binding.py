@@ -66,6 +66,17 @@ class KldItem(C.Structure):
                 ("stream", C.c_uint64)]
 
 
+class GradItem(C.Structure):
+    _fields_ = [("g", C.c_void_p), ("wl", C.c_int32), ("fl", C.c_int32)]
+
+
+class PushupResult(C.Structure):
+    _fields_ = [("wl", C.c_int), ("fl", C.c_int), ("s1", C.c_int), ("s2", C.c_int), ("s", C.c_int)]
+
+
+ST_MIN, ST_MEAN, ST_MAX = 0, 1, 2
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -93,12 +104,38 @@ def load_library():
         f.argtypes = [vp, ConvDesc, vp, Fmt, vp, Fmt, vp, Epilogue]
     lib.adapt_kld_precision_search.argtypes = [vp, vp, sz, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
     lib.adapt_kld_precision_search_batched.argtypes = [vp, C.POINTER(KldItem), i, i, i, dbl, dbl, i, u64, vp, vp]
+    lib.adapt_gradient_diversity.argtypes = [vp, C.POINTER(GradItem), i, sz, vp, vp]
+    lib.adapt_pushup_suggest.argtypes = [dbl, i, i, i, i, i, C.POINTER(PushupResult)]
+    lib.adapt_strategy_next.argtypes = [i, dbl, dbl]
+    lib.adapt_lookback_next.argtypes = [i, dbl, i, i, dbl]
+    lib.adapt_resolution_next.argtypes = [i, i, i, i, i, i]
     _lib = lib
     return lib
 
 
 def acc_bits(k: int, fa: Fmt, fb: Fmt) -> int:
     return load_library().adapt_acc_bits(k, fa, fb)
+
+
+# -- the scalar rules of the switch controller (host functions of the library) -----------------
+def pushup_suggest(ds: float, wl_min: int, fl_min: int, strategy: int, buff: int, wl_cap: int = 32):
+    """Returns (WL, FL, s1, s2, s)."""
+    res = PushupResult()
+    _check(load_library().adapt_pushup_suggest(ds, wl_min, fl_min, strategy, buff, wl_cap, C.byref(res)),
+           "adapt_pushup_suggest")
+    return res.wl, res.fl, res.s1, res.s2, res.s
+
+
+def strategy_next(strategy: int, loss_avg: float, loss_now: float) -> int:
+    return load_library().adapt_strategy_next(strategy, loss_avg, loss_now)
+
+
+def lookback_next(lb: int, ds: float, lb_lwr: int, lb_upr: int, gamma: float) -> int:
+    return load_library().adapt_lookback_next(lb, ds, lb_lwr, lb_upr, gamma)
+
+
+def resolution_next(r: int, lb: int, lb_lwr: int, lb_upr: int, r_lwr: int, r_upr: int) -> int:
+    return load_library().adapt_resolution_next(r, lb, lb_lwr, lb_upr, r_lwr, r_upr)
 
 
 def _ptr(t):
@@ -257,3 +294,25 @@ class Context:
         _check(self._lib.adapt_kld_precision_search_batched(self._h, items, n, wl_lo, wl_hi, eps, alpha, mode, seed,
                                                             _ptr(kld), _ptr(sel)), "adapt_kld_precision_search_batched")
         return kld, sel
+
+    # -- PushUp ---------------------------------------------------------------------------------
+    def gradient_diversity(self, gs, fmts, out=None, sums=None, want_sums=True):
+        """gs: device code tensors of one size (int8 for wl <= 8, else int16), oldest first; fmts: their
+        (wl, fl).  Returns (out, sums): out = float64[2] (ds, log ds or 1), sums = int64 view of the
+        uint64[count + 2] integer sums (None unless asked for)."""
+        torch = self._torch
+        count = len(gs)
+        n = gs[0].numel() if count else 0
+        dev = gs[0].device if count else "cuda"
+        if out is None:
+            out = torch.empty(2, dtype=torch.float64, device=dev)
+        if sums is None and want_sums:
+            sums = torch.empty(count + 2, dtype=torch.int64, device=dev)
+        items = (GradItem * max(count, 1))()
+        for k in range(count):
+            if gs[k].numel() != n:
+                raise ValueError("all gradients of a window have the same number of elements")
+            items[k] = GradItem(gs[k].data_ptr(), fmts[k][0], fmts[k][1])
+        _check(self._lib.adapt_gradient_diversity(self._h, items, count, n, _ptr(sums), _ptr(out)),
+               "adapt_gradient_diversity")
+        return out, sums

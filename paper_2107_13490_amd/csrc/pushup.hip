@@ -1,0 +1,244 @@
+// PushUp (Sec. 3.3 "The PushUp Operation", "Dealing with Fixed-Points Limited Range",
+// "Strategy, Resolution and Lookback") for gfx950.
+//
+// Device part: the gradient-diversity equation over a lookback window of gradient tensors held
+// as fixed-point codes.  One pass over the window: every thread owns 16 consecutive elements,
+// reads them from each tensor in turn (four tensors' loads in flight), keeps the running
+// element-wise sum of the aligned codes in registers and the per-tensor sums of squares in
+// per-wavefront counters.  All sums are integers (exact, order-independent); a one-block
+// follow-up kernel adds the block partials and forms the norms and the ratio in fp64.
+//
+// Host part: the scalar rules that turn the diversity into a new <WL,FL>, lookback,
+// resolution and strategy.  They are plain functions and need no device.
+#include <algorithm>
+#include <cmath>
+
+#include "common.hpp"
+#include "context.hpp"
+
+namespace adapt {
+
+constexpr int kGdThreads = 256;
+constexpr int kGdPerThread = 16;          // elements per thread
+constexpr int kGdMaxTensors = 64;
+constexpr int kGdFinalThreads = 1024;
+
+struct GradWindow {
+    const void *g[kGdMaxTensors];
+    uint8_t es[kGdMaxTensors];            // element bytes: 1 or 2
+    uint8_t shift[kGdMaxTensors];         // fl_max - fl_k
+    int8_t fl[kGdMaxTensors];
+    int count;
+    int fl_max;
+};
+
+typedef unsigned gd_v4u __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor((unsigned long long)v, off, 64);
+    return v;
+}
+
+// 16 codes of tensor k starting at element e0.  The buffer descriptor covers the tensor rounded up
+// to whole 16-byte units (the tensor is 16-byte aligned, so the last unit lies in a mapped page):
+// units past it read as 0; the codes past n inside the last unit are cleared by the caller.
+__device__ __forceinline__ void load16(const GradWindow &w, int k, uint32_t n, uint32_t e0, gd_v4u (&raw)[2])
+{
+    const uint32_t es = w.es[k];
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(w.g[k]), 0, (int)((n * es + 15u) & ~15u), 0x00020000);
+    raw[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, e0 * es, 0, 0);
+    raw[1] = es == 2 ? __builtin_amdgcn_raw_buffer_load_b128(rsrc, e0 * es + 16, 0, 0) : gd_v4u{0, 0, 0, 0};
+}
+
+__device__ __forceinline__ void unpack16(const gd_v4u (&raw)[2], int es, int (&c)[16])
+{
+    if (es == 1) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) c[j] = (int)(int8_t)(raw[0][j >> 2] >> (8 * (j & 3)));
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) c[j] = (int)(int16_t)(raw[j >> 3][(j >> 1) & 3] >> (16 * (j & 1)));
+    }
+}
+
+// partial[col][block]: col k < count: sum of squares of tensor k; col count / count+1: sums of the
+// low / high 32-bit halves of (aligned element sum)^2
+__global__ void __launch_bounds__(kGdThreads)
+gd_partial_kernel(const GradWindow w, uint32_t n, uint64_t *partial)
+{
+    __shared__ uint64_t wave_part[kGdThreads / kWave][kGdMaxTensors + 2];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const uint32_t e0 = (blockIdx.x * kGdThreads + threadIdx.x) * kGdPerThread;
+    int S[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) S[j] = 0;
+    for (int k0 = 0; k0 < w.count; k0 += 4) {
+        gd_v4u raw[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k0 + u < w.count) load16(w, k0 + u, n, e0, raw[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (k0 + u >= w.count) break;
+            int c[16];
+            unpack16(raw[u], w.es[k0 + u], c);
+            if (e0 + 16 > n) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (e0 + j >= n) c[j] = 0;
+            }
+            const int sh = w.shift[k0 + u];
+            uint64_t sq = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                sq += (uint32_t)(c[j] * c[j]);
+                S[j] += c[j] * (1 << sh);
+            }
+            sq = wave_sum_u64(sq);
+            if (lane == 0) wave_part[wave][k0 + u] = sq;
+        }
+    }
+    uint64_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const uint64_t q = (uint64_t)((long long)S[j] * (long long)S[j]);
+        lo += q & 0xffffffffull;
+        hi += q >> 32;
+    }
+    lo = wave_sum_u64(lo);
+    hi = wave_sum_u64(hi);
+    if (lane == 0) { wave_part[wave][w.count] = lo; wave_part[wave][w.count + 1] = hi; }
+    __syncthreads();
+    for (int col = threadIdx.x; col < w.count + 2; col += kGdThreads) {
+        uint64_t v = 0;
+#pragma unroll
+        for (int i = 0; i < kGdThreads / kWave; ++i) v += wave_part[i][col];
+        partial[(size_t)col * gridDim.x + blockIdx.x] = v;
+    }
+}
+
+// One block: column sums (one wavefront per column at a time), then the norms and the ratio.
+__global__ void __launch_bounds__(kGdFinalThreads)
+gd_final_kernel(const GradWindow w, const uint64_t *__restrict__ partial, int nblocks, uint64_t *sums_out, double *out)
+{
+    __shared__ uint64_t col_sum[kGdMaxTensors + 2];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (int col = wave; col < w.count + 2; col += kGdFinalThreads / kWave) {
+        const uint64_t *p = partial + (size_t)col * nblocks;
+        uint64_t v = 0;
+        int b = lane;
+        for (; b + 7 * kWave < nblocks; b += 8 * kWave) {
+            uint64_t t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = p[b + u * kWave];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v += t[u];
+        }
+        for (; b < nblocks; b += kWave) v += p[b];
+        v = wave_sum_u64(v);
+        if (lane == 0) {
+            col_sum[col] = v;
+            if (sums_out) sums_out[col] = v;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    double num = 0.0;
+    for (int k = 0; k < w.count; ++k) num += ldexp(sqrt((double)col_sum[k]), -(int)w.fl[k]);
+    const double sq = (double)col_sum[w.count + 1] * 4294967296.0 + (double)col_sum[w.count];
+    const double den = ldexp(sqrt(sq), -w.fl_max);
+    const double ds = den > 0.0 ? num / den : (num > 0.0 ? (double)INFINITY : (double)NAN);
+    out[0] = ds;
+    out[1] = (ds > 0.0 && ds < (double)INFINITY) ? log(ds) : 1.0;
+}
+
+}  // namespace adapt
+
+using namespace adapt;
+
+extern "C" int adapt_gradient_diversity(adapt_ctx *ctx, const adapt_grad_item *items, int count, size_t n,
+                                        uint64_t *sums, double *out)
+{
+    if (!ctx || !items || !out || count < 1) return ADAPT_EINVAL;
+    if (count > kGdMaxTensors) return ADAPT_EUNSUPPORTED;
+    if (((uintptr_t)out & 7) || (sums && ((uintptr_t)sums & 7))) return ADAPT_EINVAL;
+    if (n > ((size_t)1 << 30)) return ADAPT_EUNSUPPORTED;      // 32-bit byte offsets, with room for the last block's overhang
+    GradWindow w;
+    w.count = count;
+    w.fl_max = 0;
+    int wl_max = 0;
+    for (int k = 0; k < count; ++k) {
+        const adapt_fmt f = adapt_fmt{items[k].wl, items[k].fl};
+        if (!fmt_ok(f)) return ADAPT_EINVAL;
+        if (n > 0 && (!items[k].g || !aligned16(items[k].g))) return ADAPT_EINVAL;
+        w.fl_max = std::max(w.fl_max, f.fl);
+        wl_max = std::max(wl_max, f.wl);
+    }
+    // the aligned element sum is kept in int32: count * 2^(wl-1) * 2^(fl_max - fl) must stay below 2^31
+    double bound = 0.0;
+    for (int k = 0; k < count; ++k) {
+        w.g[k] = items[k].g;
+        w.es[k] = (uint8_t)(items[k].wl <= 8 ? 1 : 2);
+        w.shift[k] = (uint8_t)(w.fl_max - items[k].fl);
+        w.fl[k] = (int8_t)items[k].fl;
+        bound += std::ldexp(1.0, items[k].wl - 1 + w.fl_max - items[k].fl);
+    }
+    if (bound >= 2147483648.0) return ADAPT_EUNSUPPORTED;
+    const size_t per_block = (size_t)kGdThreads * kGdPerThread;
+    const int grid = (int)std::max<size_t>(1, (n + per_block - 1) / per_block);
+    if ((size_t)grid * (count + 2) * sizeof(uint64_t) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
+    hipLaunchKernelGGL(gd_partial_kernel, dim3(grid), dim3(kGdThreads), 0, ctx->stream, w, (uint32_t)n, partial);
+    hipLaunchKernelGGL(gd_final_kernel, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, w, partial, grid, sums, out);
+    return hip_status(ctx, hipGetLastError());
+}
+
+// ---- host-side scalar rules ------------------------------------------------------------------
+
+static bool usable(double ds) { return ds > 0.0 && ds < (double)INFINITY; }
+
+extern "C" int adapt_pushup_suggest(double ds, int wl_min, int fl_min, int strategy, int buff, int wl_cap,
+                                    adapt_pushup_result *res)
+{
+    if (!res || wl_cap < 2 || wl_cap > 32 || buff < 0 || buff > wl_cap || wl_min < 1 || fl_min < 0) return ADAPT_EINVAL;
+    if (strategy != ADAPT_ST_MIN && strategy != ADAPT_ST_MEAN && strategy != ADAPT_ST_MAX) return ADAPT_EINVAL;
+    const double L = usable(ds) ? std::log(ds) : 1.0;
+    int s1 = 1, s2 = 1, s = 1;
+    if (L > 0.0) {
+        s1 = L == 1.0 ? wl_cap : (int)std::min<double>(std::max(std::ceil(1.0 / (L - 1.0)), 1.0), (double)wl_cap);
+        const double s2f = std::max(std::min(32.0 * L * L - 1.0, 32.0) - (double)fl_min, 1.0);
+        s2 = (int)std::min<double>(std::ceil(s2f), (double)wl_cap);
+        if (strategy == ADAPT_ST_MIN) s = std::min(s1, s2);
+        else if (strategy == ADAPT_ST_MEAN) s = (int)std::ceil(0.5 * (s1 + s2));
+        else s = std::max(s1, s2);
+    }
+    int fl = std::min(fl_min + s, wl_cap);
+    int wl = std::min(std::max(wl_min, fl_min) + 1, wl_cap);
+    fl = std::min(fl, wl_cap - buff);
+    wl = std::max(std::min(fl + buff, wl_cap), wl);
+    res->wl = wl; res->fl = fl; res->s1 = s1; res->s2 = s2; res->s = s;
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_strategy_next(int strategy, double loss_avg, double loss_now)
+{
+    if (std::fabs(loss_avg) > std::fabs(loss_now)) return ADAPT_ST_MIN;
+    return strategy == ADAPT_ST_MIN ? ADAPT_ST_MEAN : ADAPT_ST_MAX;
+}
+
+extern "C" int adapt_lookback_next(int lb, double ds, int lb_lwr, int lb_upr, double gamma)
+{
+    double lb_new = (double)lb_upr;
+    if (usable(ds)) lb_new = std::min(std::max(std::ceil((double)lb_upr / ds), (double)lb_lwr), (double)lb_upr);
+    return (int)std::ceil(lb_new * gamma + (1.0 - gamma) * (double)lb);
+}
+
+extern "C" int adapt_resolution_next(int r, int lb, int lb_lwr, int lb_upr, int r_lwr, int r_upr)
+{
+    if (lb == lb_upr) return std::min(std::max(r + 1, r_lwr), r_upr);
+    if (lb == lb_lwr) return std::min(std::max(r - 1, r_lwr), r_upr);
+    return r;
+}
