@@ -60,6 +60,41 @@ def cpu_baseline(batch: int):
                       f"{dt:.2f} s"}
 
 
+def next_rows(ctx, pkg, torch, w):
+    """Per-call device time of the steps beyond the timed path (PushUp's gradient diversity, the fused
+    master-weight update + re-quantization), on the config-2 weight tensor and on a 16 M element one.
+    Algorithmic bytes: diversity = window x n x 1 B of int8 codes; update = 4 + 1 B read, 4 + 1 B written."""
+    def timed(fn, reps):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    res = {}
+    for tag, n, window, reps in (("config2_W", w.numel(), 25, 50), ("16M", 1 << 24, 25, 5)):
+        gs = [torch.randint(-128, 128, (n,), dtype=torch.int8, device="cuda") for _ in range(window)]
+        master = torch.randn(n, device="cuda") * 0.06
+        q = torch.empty(n, dtype=torch.int8, device="cuda")
+        out = torch.empty(2, dtype=torch.float64, device="cuda")
+        sums = torch.empty(window + 2, dtype=torch.int64, device="cuda")
+        cnt = torch.empty(2, dtype=torch.int64, device="cuda")
+        rr = torch.empty(2, dtype=torch.float32, device="cuda")
+        fm = [(8, 7)] * window
+        ms_gd = timed(lambda: ctx.gradient_diversity(gs, fm, out=out, sums=sums), reps)
+        ms_up = timed(lambda: ctx.sgd_update_quantize(master, gs[0], (8, 7), 0.01, 1e-5, 1e-4, 8, 5, g_sumsq=sums[0:1],
+                                                      out=q, counters=cnt, rng_range=rr), reps)
+        res[tag] = {"n": n, "window": window,
+                    "gradient_diversity_ms": ms_gd, "gradient_diversity_GBps": window * n / (ms_gd * 1e-3) / 1e9,
+                    "sgd_update_quantize_ms": ms_up, "sgd_update_quantize_GBps": 10.0 * n / (ms_up * 1e-3) / 1e9}
+        del gs, master, q
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -190,6 +225,7 @@ def main():
         "kld_GBps": kld_bytes / (call_ms["kld_search"] * 1e-3) / 1e9,
         "kld_frac_hbm": kld_bytes / (call_ms["kld_search"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
     }
+    out["next_rows"] = next_rows(ctx, pkg, torch, w)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_batch)
     print(json.dumps(out))

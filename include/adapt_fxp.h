@@ -171,6 +171,15 @@ int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t n, int wl_
                                int il, int bins, double eps, double alpha, adapt_rng rng,
                                double *kld, int32_t *sel, uint32_t *hist, int64_t *grid);
 
+/* The same search with the range already known: `range` = device float[2], (min, max) of the
+ * finite elements of w, e.g. as written by adapt_sgd_update_quantize; the range pass over w is
+ * skipped.  Elements outside a range that does not bound the tensor are counted in the end
+ * bins. */
+int adapt_kld_precision_search_ranged(adapt_ctx *ctx, const float *w, size_t n, const float *range,
+                                      int wl_lo, int wl_hi, int il, int bins, double eps,
+                                      double alpha, adapt_rng rng, double *kld, int32_t *sel,
+                                      uint32_t *hist, int64_t *grid);
+
 /* One call for all layers of a network (the loop of Alg. 2 over l in L): the same search on
  * `count` tensors described by a HOST array (read before the call returns; `w` inside is a
  * device pointer); tensor t writes kld[t*ncand ...] and
@@ -182,6 +191,31 @@ typedef struct {
 int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kld_item *items, int count,
                                        int wl_lo, int wl_hi, double eps, double alpha, int mode,
                                        uint64_t seed, double *kld, int32_t *sel);
+
+/* ---- master-weight update fused with re-quantization (Alg. 1: the backward-pass line and the
+ *      Quantize loop after it) ------------------------------------------------------------- */
+
+/* Plain SGD on the fp32 master copy with the quantized gradient of the layer, then Quantize:
+ *   step = fp32(lr / sqrt(*g_sumsq))  (the gradient divided by its 2-norm, Sec. 3.3 "Dealing with
+ *          Fixed-Points Limited Range"; 0 if the sum is 0), or fp32(lr * 2^-fg.fl) if g_sumsq is
+ *          NULL (no normalisation)
+ *   d  = fma(l2, w, l1 * sign(w))     (derivatives of the L1 / L2 terms of Sec. 3.4; sign(0) = 0)
+ *   w1 = fma(-step, c, w)             (c = the gradient code)
+ *   w' = fma(-lr, d, w1)              (lr, l1, l2 rounded to fp32 once; three fp32 fused
+ *                                      multiply-adds in exactly this order)
+ *   q  = quantize(w', fq) as adapt_quantize does, with `rng`
+ *   w         device fp32[n], updated in place
+ *   g         device codes of the gradient, int8_t[n] (fg.wl <= 8) or int16_t[n]
+ *   g_sumsq   device uint64_t or NULL: sum of the squared codes of g (adapt_gradient_diversity
+ *             writes it as sums[k])
+ *   q         device int8_t[n] (fq.wl <= 8) or int16_t[n]
+ *   counters  device uint64_t[2] or NULL: non-zero codes, saturated elements
+ *   range     device float[2] or NULL: min and max of the finite w' (+inf, -inf if there is none)
+ * Pointers 16-byte aligned; n <= 2^40. */
+typedef struct { double lr, l1, l2; } adapt_sgd_params;
+int adapt_sgd_update_quantize(adapt_ctx *ctx, float *w, size_t n, const void *g, adapt_fmt fg,
+                              const uint64_t *g_sumsq, adapt_sgd_params opt, adapt_fmt fq,
+                              adapt_rng rng, void *q, uint64_t *counters, float *range);
 
 /* ---- PushUp (Sec. 3.3 "The PushUp Operation") ---------------------------------------------- */
 

@@ -70,6 +70,10 @@ class GradItem(C.Structure):
     _fields_ = [("g", C.c_void_p), ("wl", C.c_int32), ("fl", C.c_int32)]
 
 
+class SgdParams(C.Structure):
+    _fields_ = [("lr", C.c_double), ("l1", C.c_double), ("l2", C.c_double)]
+
+
 class PushupResult(C.Structure):
     _fields_ = [("wl", C.c_int), ("fl", C.c_int), ("s1", C.c_int), ("s2", C.c_int), ("s", C.c_int)]
 
@@ -104,6 +108,8 @@ def load_library():
         f.argtypes = [vp, ConvDesc, vp, Fmt, vp, Fmt, vp, Epilogue]
     lib.adapt_kld_precision_search.argtypes = [vp, vp, sz, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
     lib.adapt_kld_precision_search_batched.argtypes = [vp, C.POINTER(KldItem), i, i, i, dbl, dbl, i, u64, vp, vp]
+    lib.adapt_kld_precision_search_ranged.argtypes = [vp, vp, sz, vp, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
+    lib.adapt_sgd_update_quantize.argtypes = [vp, vp, sz, vp, Fmt, vp, SgdParams, Fmt, Rng, vp, vp, vp]
     lib.adapt_gradient_diversity.argtypes = [vp, C.POINTER(GradItem), i, sz, vp, vp]
     lib.adapt_pushup_suggest.argtypes = [dbl, i, i, i, i, i, C.POINTER(PushupResult)]
     lib.adapt_strategy_next.argtypes = [i, dbl, dbl]
@@ -278,6 +284,21 @@ class Context:
                                                     _ptr(grid)), "adapt_kld_precision_search")
         return dict(kld=kld, sel=sel, hist=hist, grid=grid)
 
+    def kld_precision_search_ranged(self, w, rng_range, wl_lo, wl_hi, il, bins, eps, alpha=-1.0, mode=SR, seed=0,
+                                    stream=0, want_hist=False):
+        """As kld_precision_search, with the tensor's (min, max) given as a device float32[2]."""
+        torch = self._torch
+        dev = w.device
+        ncand = wl_hi - wl_lo + 1
+        kld = torch.empty(max(ncand, 1), dtype=torch.float64, device=dev)
+        sel = torch.empty(2, dtype=torch.int32, device=dev)
+        grid = torch.empty(3, dtype=torch.int64, device=dev)
+        hist = torch.empty((max(ncand, 0) + 1, bins), dtype=torch.int32, device=dev) if want_hist else None
+        _check(self._lib.adapt_kld_precision_search_ranged(self._h, _ptr(w), w.numel(), _ptr(rng_range), wl_lo, wl_hi, il,
+                                                           bins, eps, alpha, Rng(mode, seed, stream), _ptr(kld), _ptr(sel),
+                                                           _ptr(hist), _ptr(grid)), "adapt_kld_precision_search_ranged")
+        return dict(kld=kld, sel=sel, hist=hist, grid=grid)
+
     def kld_precision_search_batched(self, ws, ils, bins, streams, wl_lo, wl_hi, eps, alpha=-1.0, mode=SR, seed=0,
                                      kld=None, sel=None):
         torch = self._torch
@@ -316,3 +337,21 @@ class Context:
         _check(self._lib.adapt_gradient_diversity(self._h, items, count, n, _ptr(sums), _ptr(out)),
                "adapt_gradient_diversity")
         return out, sums
+
+    # -- master-weight update + re-quantization ---------------------------------------------------
+    def sgd_update_quantize(self, w, g, fg, lr, l1, l2, wl, fl, g_sumsq=None, mode=SR, seed=0, stream=0, out=None,
+                            counters=None, rng_range=None):
+        """w: fp32 master weights (updated in place); g: gradient codes with format fg = (wl, fl);
+        g_sumsq: device int64/uint64 scalar tensor (sum of squared codes) or None for an unnormalised
+        step.  Returns (q, counters, range)."""
+        torch = self._torch
+        if out is None:
+            out = torch.empty(w.shape, dtype=self.storage_dtype(wl), device=w.device)
+        if counters is None:
+            counters = torch.empty(2, dtype=torch.int64, device=w.device)
+        if rng_range is None:
+            rng_range = torch.empty(2, dtype=torch.float32, device=w.device)
+        _check(self._lib.adapt_sgd_update_quantize(self._h, _ptr(w), w.numel(), _ptr(g), Fmt(*fg), _ptr(g_sumsq),
+                                                   SgdParams(lr, l1, l2), Fmt(wl, fl), Rng(mode, seed, stream), _ptr(out),
+                                                   _ptr(counters), _ptr(rng_range)), "adapt_sgd_update_quantize")
+        return out, counters, rng_range

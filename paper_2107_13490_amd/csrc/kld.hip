@@ -270,7 +270,8 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
             const bool fin = j < cnt && fabsf(v[j]) < INFINITY;
             inc[j] = fin ? 1u : 0u;
             T[j] = (int)floorf(fminf(fmaxf(v[j] * tscale, tmin), tmax));      // NaN -> tmin
-            if (do_ref) atomicAdd(&hist[fin ? value_bin(v[j], e, base_f) : 0], inc[j]);
+            // (the clamp only acts when a caller-supplied range does not bound the tensor)
+            if (do_ref) atomicAdd(&hist[fin ? min(max(value_bin(v[j], e, base_f), 0), nb - 1) : 0], inc[j]);
         }
         for (int c = c_begin; c < c_end; ++c) count_candidate(plan.cand[c], hist + row_off[c], T, r, inc);
     };
@@ -451,7 +452,7 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
 
 static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int wl_hi, int il, int bins, double eps,
                       double alpha, int mode, uint64_t seed, uint64_t stream, double *kld, int32_t *sel,
-                      uint32_t *hist, int64_t *grid)
+                      uint32_t *hist, int64_t *grid, const float *range = nullptr /* device (min, max) or null */)
 {
     const int ncand = wl_hi - wl_lo + 1;
     const int rows = ncand + 1;
@@ -475,7 +476,11 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
     double *klpart = reinterpret_cast<double *>(ws + plan_bytes + partial_bytes);
     uint32_t *slabs = reinterpret_cast<uint32_t *>(ws + plan_bytes + partial_bytes + klpart_bytes);
 
-    hipLaunchKernelGGL(kld_range_kernel, dim3(range_grid), dim3(kRangeThreads), 0, ctx->stream, w, n, partial);
+    // a range the caller already holds (from the pass that produced the tensor) stands in for the
+    // range partials: one pair
+    const float *range_src = range ? range : partial;
+    const int range_count = range ? 1 : range_grid;
+    if (!range) hipLaunchKernelGGL(kld_range_kernel, dim3(range_grid), dim3(kRangeThreads), 0, ctx->stream, w, n, partial);
 
     const size_t row_bytes = (size_t)bins * 4;
     if (row_bytes <= kLdsBudget) {
@@ -486,13 +491,13 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
         const int groups = (rows + rows_per_group - 1) / rows_per_group;
         // one set of LDS histograms per block: per-wavefront replicas were measured no faster
         const size_t lds = (size_t)rows_per_group * row_bytes;
-        hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, partial,
-                           range_grid, wl_lo, wl_hi, il, bins, plan, slabs, rows, rows_per_group, mode, seed, stream);
+        hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, range_src,
+                           range_count, wl_lo, wl_hi, il, bins, plan, slabs, rows, rows_per_group, mode, seed, stream);
     } else {
         const size_t zw = (size_t)hist_grid * hist_words;
         hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)std::min<size_t>((zw + 255) / 256, (size_t)ctx->num_cu * 8)),
                            dim3(256), 0, ctx->stream, slabs, zw);
-        hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, partial, range_grid,
+        hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, range_src, range_count,
                            wl_lo, wl_hi, il, bins, plan, slabs, rows, rows, mode, seed, stream);
     }
     hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks, ncand), dim3(kChunk * kFinalGroups), 0, ctx->stream, plan, slabs,
@@ -535,6 +540,19 @@ extern "C" int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t
     if (((uintptr_t)kld & 7) || ((uintptr_t)sel & 3) || ((uintptr_t)hist & 3) || ((uintptr_t)grid & 7)) return ADAPT_EINVAL;
     if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
     return search_one(ctx, w, n, wl_lo, wl_hi, il, bins, eps, alpha, rng.mode, rng.seed, rng.stream, kld, sel, hist, grid);
+}
+
+extern "C" int adapt_kld_precision_search_ranged(adapt_ctx *ctx, const float *w, size_t n, const float *range, int wl_lo,
+                                                 int wl_hi, int il, int bins, double eps, double alpha, adapt_rng rng,
+                                                 double *kld, int32_t *sel, uint32_t *hist, int64_t *grid)
+{
+    if (!ctx || !kld || !sel || !range || ((uintptr_t)range & 3)) return ADAPT_EINVAL;
+    if (int s = check_search_args(wl_lo, wl_hi, il, bins, eps, alpha, rng.mode)) return s;
+    if (n > 0 && (!w || !aligned16(w))) return ADAPT_EINVAL;
+    if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
+    if (((uintptr_t)kld & 7) || ((uintptr_t)sel & 3) || ((uintptr_t)hist & 3) || ((uintptr_t)grid & 7)) return ADAPT_EINVAL;
+    if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
+    return search_one(ctx, w, n, wl_lo, wl_hi, il, bins, eps, alpha, rng.mode, rng.seed, rng.stream, kld, sel, hist, grid, range);
 }
 
 extern "C" int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kld_item *items, int count, int wl_lo,
