@@ -891,8 +891,16 @@ static hipError_t launch_tile(adapt_ctx *ctx, const ContractArgs &a, int splits,
         if constexpr (LIMBS == 1)
             if (t.bkt == 192) {
                 if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 192>(ctx, a, splits, t);
+#ifdef ADAPT_TUNE
+                if constexpr (OP == OP_FWD)
+                    if (t.bm == 256) return launch_bn<OP, LIMBS, AMODE, WMODE, 256, 192>(ctx, a, splits, t);
+#endif
                 return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 192>(ctx, a, splits, t);
             }
+#ifdef ADAPT_TUNE
+        if constexpr (LIMBS == 1 && OP == OP_FWD)
+            if (t.bm == 256) return launch_bn<OP, LIMBS, AMODE, WMODE, 256, 64>(ctx, a, splits, t);
+#endif
         if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 64>(ctx, a, splits, t);
         return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 64>(ctx, a, splits, t);
     }

@@ -3,7 +3,7 @@
 //
 // Device part: the gradient-diversity equation over a lookback window of gradient tensors held
 // as fixed-point codes.  One pass over the window: every thread owns 16 consecutive elements,
-// reads them from each tensor in turn (four tensors' loads in flight), keeps the running
+// reads them from each tensor in turn (eight tensors' loads in flight), keeps the running
 // element-wise sum of the aligned codes in registers and the per-tensor sums of squares in
 // per-wavefront counters.  All sums are integers (exact, order-independent); a one-block
 // follow-up kernel adds the block partials and forms the norms and the ratio in fp64.
@@ -75,13 +75,14 @@ gd_partial_kernel(const GradWindow w, uint32_t n, uint64_t *partial)
     int S[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) S[j] = 0;
-    for (int k0 = 0; k0 < w.count; k0 += 4) {
-        gd_v4u raw[4][2];
+    constexpr int U = 8;                  // tensors whose loads are in flight together
+    for (int k0 = 0; k0 < w.count; k0 += U) {
+        gd_v4u raw[U][2];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
             if (k0 + u < w.count) load16(w, k0 + u, n, e0, raw[u]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < U; ++u) {
             if (k0 + u >= w.count) break;
             int c[16];
             unpack16(raw[u], w.es[k0 + u], c);
