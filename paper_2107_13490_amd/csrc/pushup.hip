@@ -84,21 +84,37 @@ gd_partial_kernel(const GradWindow w, uint32_t n, uint64_t *partial)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (k0 + u >= w.count) break;
-            int c[16];
-            unpack16(raw[u], w.es[k0 + u], c);
-            if (e0 + 16 > n) {
+            const int es = w.es[k0 + u], sh = w.shift[k0 + u];
+            if (e0 + 16 > n) {                 // last unit of the tensor: clear the codes past n
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
-                    if (e0 + j >= n) c[j] = 0;
+                    if (e0 + j >= n) {
+                        if (es == 1) raw[u][0][j >> 2] &= ~(0xffu << (8 * (j & 3)));
+                        else raw[u][j >> 3][(j >> 1) & 3] &= ~(0xffffu << (16 * (j & 1)));
+                    }
             }
-            const int sh = w.shift[k0 + u];
-            uint64_t sq = 0;
+            int c[16];
+            unpack16(raw[u], es, c);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                sq += (uint32_t)(c[j] * c[j]);
-                S[j] += c[j] * (1 << sh);
+            for (int j = 0; j < 16; ++j) S[j] += (int)((unsigned)c[j] << sh);
+            // sums of squares with the packed dot-product instructions: 4 (int8) or 2 (int16) codes each
+            uint64_t sq;
+            if (es == 1) {
+                int d = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) d = __builtin_amdgcn_sdot4((int)raw[u][0][i], (int)raw[u][0][i], d, false);
+                sq = wave_sum_u32((uint32_t)d);                    // <= 64 * 16 * 2^14
+            } else {
+                uint64_t t = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    typedef short gd_v2s __attribute__((ext_vector_type(2)));
+                    const uint32_t x = raw[u][i >> 2][i & 3];
+                    const gd_v2s v = {(short)(x & 0xffff), (short)(x >> 16)};
+                    t += (uint32_t)__builtin_amdgcn_sdot2(v, v, 0, false);      // <= 2^31
+                }
+                sq = wave_sum_u64(t);
             }
-            sq = wave_sum_u64(sq);
             if (lane == 0) wave_part[wave][k0 + u] = sq;
         }
     }
