@@ -95,6 +95,145 @@ def next_rows(ctx, pkg, torch, w):
     return res
 
 
+def other_config(args, cfg):
+    """Configs 1, 3, 4 and 5 (supplementary lines; the default run is config 2).  A step is, for every
+    layer of the config, quantize(X, W, dY) + fwd + dgrad + wgrad (requantized with SR), then ONE
+    batched KLD call over all weight tensors of the config.  Config 1 is a GEMM instead of a layer."""
+    import numpy as np
+    import torch
+    import paper_2107_13490_amd as pkg
+    import workloads as wk
+    from paper_2107_13490_amd import ConvDesc, Epilogue
+
+    torch.cuda.set_device(0)
+    ctx = pkg.Context(workspace_bytes=1 << 30)
+    calls = []            # (kind, fn)
+    useful = issued = 0.0
+    q_bytes = 0.0
+    kld_ws, kld_bytes = [], 0.0
+    if cfg == 1:
+        a_h, b_h = wk.config1_gemm()
+        a, b = torch.from_numpy(a_h).cuda(), torch.from_numpy(b_h).cuda()
+        qa, qb = torch.empty(a.shape, dtype=torch.int8, device="cuda"), torch.empty(b.shape, dtype=torch.int8, device="cuda")
+        c = torch.empty((256, 256), dtype=torch.int32, device="cuda")
+        cnt = torch.empty(4, dtype=torch.int64, device="cuda")
+        calls.append(("quantize", lambda: ctx.quantize_batched([a, b], [(8, 6)] * 2, [1, 2], pkg.SR, 0, outs=[qa, qb], counters=cnt)))
+        calls.append(("fwd", lambda: ctx.fxp_gemm(qa, (8, 6), qb, (8, 6), Epilogue.exact(), out=c)))
+        useful = issued = 2.0 * 256 ** 3
+        q_bytes = 5.0 * 2 * 65536
+        kld_ws = [torch.from_numpy(wk.config1_kld_tensor()).cuda()]
+        kld_args = dict(ils=[2], wl_lo=2, wl_hi=16)
+        workload = "configs[0]: GEMM 256^3 <8,6> (exact int32 output) + KLD on 65,536 values (WL 2..16, 2048 bins)"
+        sample_layer = None
+    else:
+        if cfg == 3:
+            layers = [wk.config3()]
+            workload = "configs[2]: conv 128->128 3x3 @16x16, batch 256, <12,9> (two limbs), 50% zero weights"
+        elif cfg == 4:
+            layers = [wk.layer_inputs(sp, 40 + i) for i, sp in enumerate(wk.alexnet_cifar_layers())]
+            workload = "configs[3]: AlexNet-CIFAR layer sweep (5 conv + 3 FC), batch 128, WL per layer from {4,6,8,12,16}"
+        else:
+            layers = [wk.layer_inputs(sp, 50 + i) for i, sp in enumerate(wk.resnet18_cifar_layers())]
+            workload = "configs[4]: ResNet-18-CIFAR layer sweep (21 layers, 11.2 M weights), batch 256, WL per layer 4..16"
+        sample_layer = max(layers, key=lambda L: L.shape.macs)
+        for L in layers:
+            s = L.shape
+            d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+            f = (L.wl, L.fl)
+            dt = torch.int8 if L.wl <= 8 else torch.int16
+            x, w, dy = (torch.from_numpy(t).cuda() for t in (L.x, L.w, L.dy))
+            qx, qw, qdy = (torch.empty(t.shape, dtype=dt, device="cuda") for t in (x, w, dy))
+            y, dx, dw = torch.empty(dy.shape, dtype=dt, device="cuda"), torch.empty_like(qx), torch.empty_like(qw)
+            cnt = torch.empty(6, dtype=torch.int64, device="cuda")
+            eps = [Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10 + i, relu=(i == 0)) for i in range(3)]
+
+            def mk(d=d, f=f, x=x, w=w, dy=dy, qx=qx, qw=qw, qdy=qdy, y=y, dx=dx, dw=dw, cnt=cnt, eps=eps):
+                return [("quantize", lambda: ctx.quantize_batched([x, w, dy], [f] * 3, [1, 2, 3], pkg.SR, 0, outs=[qx, qw, qdy], counters=cnt)),
+                        ("fwd", lambda: ctx.conv_fwd(d, qx, f, qw, f, eps[0], out=y)),
+                        ("dgrad", lambda: ctx.conv_dgrad(d, qdy, f, qw, f, eps[1], out=dx)),
+                        ("wgrad", lambda: ctx.conv_wgrad(d, qdy, f, qx, f, eps[2], out=dw))]
+            calls += mk()
+            ops = 3 * 2.0 * s.macs
+            useful += ops
+            issued += ops * (4 if L.wl > 8 else 1)
+            q_bytes += (4.0 + (1 if L.wl <= 8 else 2)) * (x.numel() + w.numel() + dy.numel())
+            kld_ws.append(w.view(-1))
+        kld_args = dict(ils=[3] * len(kld_ws), wl_lo=4, wl_hi=16)
+    ncand = kld_args["wl_hi"] - kld_args["wl_lo"] + 1
+    kld = torch.empty((len(kld_ws), ncand), dtype=torch.float64, device="cuda")
+    sel = torch.empty((len(kld_ws), 2), dtype=torch.int32, device="cuda")
+    calls.append(("kld", lambda: ctx.kld_precision_search_batched(kld_ws, kld_args["ils"], [2048] * len(kld_ws),
+                                                                   list(range(2, 2 + len(kld_ws))), kld_args["wl_lo"],
+                                                                   kld_args["wl_hi"], 1e-2, kld=kld, sel=sel)))
+    kld_bytes = 8.0 * sum(t.numel() for t in kld_ws)
+
+    def step():
+        for _, fn in calls:
+            fn()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
+    kind_ms = {}
+    for kind, fn in calls:           # per-call device time, each call back to back
+        reps = 20
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        kind_ms[kind] = kind_ms.get(kind, 0.0) + e0.elapsed_time(e1) / reps
+    conv_ms = sum(kind_ms.get(k, 0.0) for k in ("fwd", "dgrad", "wgrad"))
+    out = {
+        "metric": "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s",
+        "value": useful / (ms_step * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": workload, "useful_ops_per_step": useful, "issued_int8_ops_per_step": issued},
+        "roofline": {"bound": "mfma", "kernel": "contract_kernel, all contraction calls of the step",
+                     "achieved": issued / (conv_ms * 1e-3) / 1e12, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
+                     "frac": issued / (conv_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, "traffic": None,
+                     "note": "issued int8 MFMA ops (useful x 4 for two-limb layers) over the summed back-to-back device "
+                             "time of the contraction calls"},
+        "calls_ms_back_to_back": kind_ms,
+        "useful_conv_TOPS": useful / (conv_ms * 1e-3) / 1e12,
+        "quantize_GBps": q_bytes / (kind_ms["quantize"] * 1e-3) / 1e9,
+        "quantize_frac_hbm": q_bytes / (kind_ms["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "kld_GBps": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9,
+        "kld_frac_hbm": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+    }
+    if not args.no_cpu_baseline and sample_layer is not None:
+        out["cpu_baseline"] = cpu_baseline_layer(sample_layer, args.cpu_batch)
+    print(json.dumps(out))
+
+
+def cpu_baseline_layer(L, batch):
+    """The oracle on the config's largest layer at a reduced batch (contractions only)."""
+    import workloads as wk
+    from oracle import conv_oracle as co
+    from oracle import fxp_oracle as orc
+    s = L.shape
+    small = wk.conv_layer(wk.ConvShape(min(batch, s.n), s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad), L.wl, L.fl, 99, 0.0, L.name)
+    co.load()
+    t0 = time.perf_counter()
+    qx, _, _ = orc.quantize(small.x, L.wl, L.fl, orc.SR, 0, 1)
+    qw, _, _ = orc.quantize(small.w, L.wl, L.fl, orc.SR, 0, 2)
+    qdy, _, _ = orc.quantize(small.dy, L.wl, L.fl, orc.SR, 0, 3)
+    co.conv_fwd(qx, qw, s.stride, s.pad)
+    co.conv_dgrad(qdy, qw, s.h, s.w, s.stride, s.pad)
+    co.conv_wgrad(qdy, qx, s.r, s.s, s.stride, s.pad)
+    dt = time.perf_counter() - t0
+    return {"value": 3 * 2.0 * small.shape.macs / dt / 1e12, "unit": "TOPS", "cores": co.num_threads(), "kind": "oracle",
+            "sample": f"layer {L.name} at batch {small.shape.n} (of {s.n}): quantize + fwd + dgrad + wgrad, {dt:.2f} s"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,10 +244,15 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (20 times): the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="which of the five workload configurations to run (default 2, the one the metric is quoted on)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (use --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    if args.config != 2 and not args.copy_calibration:
+        other_config(args, args.config)
+        return
 
     import torch
     import paper_2107_13490_amd as pkg
@@ -225,6 +369,23 @@ def main():
         "kld_GBps": kld_bytes / (call_ms["kld_search"] * 1e-3) / 1e9,
         "kld_frac_hbm": kld_bytes / (call_ms["kld_search"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
     }
+    # cold-cache rate of the HBM-bound quantize call: 8 distinct sets of the three tensors (340 MB of
+    # inputs and outputs, more than the 256 MB of last-level cache) used in turn
+    sets = [([t.clone() for t in (x, w, dy)], [torch.empty_like(t) for t in (qx, qw, qdy)]) for _ in range(8)]
+    for ins, outs in sets:
+        ctx.quantize_batched(ins, [f, f, f], [1, 2, 3], pkg.SR, 0, outs=outs, counters=counters)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for rep in range(5):
+        for ins, outs in sets:
+            ctx.quantize_batched(ins, [f, f, f], [1, 2, 3], pkg.SR, 0, outs=outs, counters=counters)
+    e1.record()
+    torch.cuda.synchronize()
+    cold_ms = e0.elapsed_time(e1) / 40
+    out["quantize_cold_GBps"] = q_bytes / (cold_ms * 1e-3) / 1e9
+    out["quantize_cold_frac_hbm"] = out["quantize_cold_GBps"] / PEAK_HBM_GBPS
+    del sets
     out["next_rows"] = next_rows(ctx, pkg, torch, w)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_batch)

@@ -912,6 +912,9 @@ template <int OP, int LIMBS>
 static hipError_t launch_modes(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
 {
     const bool scalar = a.act_load == LOAD_SCALAR || a.wgt_load == LOAD_SCALAR;
+    if constexpr (OP == OP_DGRAD)      // few input channels (first layer): the gradient tile still takes the vector path
+        if (a.act_load == LOAD_VEC && a.wgt_load == LOAD_SCALAR)
+            return launch_variant<OP, LIMBS, LOAD_VEC, LOAD_SCALAR, 128, 64, 2, 2, 64>(ctx, a, splits);
     if (scalar) return launch_tile<OP, LIMBS, LOAD_SCALAR, LOAD_SCALAR>(ctx, a, splits, t);
     if constexpr (OP == OP_WGRAD) {
         return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_ROWS>(ctx, a, splits, t);
@@ -945,6 +948,14 @@ static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
     // contractions get their parallelism from the splits instead.)
     const long long tiles128 = (long long)((a.M + 127) / 128) * ((a.N + t.bn - 1) / t.bn);
     t.bm = (!scalar && OP != OP_WGRAD && tiles128 < 2 * num_cu && a.M > 64) ? 64 : 128;
+    if (limbs == 2 && !scalar && OP != OP_WGRAD) {
+        // Two limbs: three accumulator sets leave a 128-wide tile one resident block per CU, a 64x64
+        // tile two.  The large tile pays only when it fills every CU without much padding.
+        const long long tm = (a.M + 127) / 128, tn = (a.N + 127) / 128;
+        const bool fits = a.M >= 128 && a.N >= 128 && tm * tn >= num_cu &&
+                          (double)(tm * 128) * (double)(tn * 128) < 1.15 * (double)a.M * (double)a.N;
+        t.bm = t.bn = fits ? 128 : 64;
+    }
     return t;
 }
 
@@ -959,14 +970,21 @@ static int pick_split_tile(const ContractArgs &a, int limbs, int acc_bits, int n
     const int bkt = t.bkt;
     double best = 1e30;
     int best_splits = 1;
-    for (int i = 0; i < (limbs == 1 ? 5 : 4); ++i) {
+    for (int i = 0; i < 5; ++i) {
         const int bm = cand[i][0], bn = cand[i][1];
+        // two limbs: only the 64x64 tile (two resident blocks per CU) and the 128x128 tile (one block
+        // per CU, whose exposed latencies cost about 1.6x) are worth considering
+        if (limbs == 2 && bm != bn) continue;
+        const bool single = limbs == 2 && bm == 128;
+        const long long per_cu = single ? 1 : 2;
         const long long tm = (a.M + bm - 1) / bm, tn = (a.N + bn - 1) / bn, tiles = tm * tn;
-        long long sp = tiles >= num_cu ? 1 : std::max(1ll, 2ll * num_cu / tiles);
+        long long sp = tiles >= num_cu ? 1 : std::max(1ll, per_cu * num_cu / tiles);
         sp = std::max(1ll, std::min(sp, (long long)a.K / (2 * bkt)));
-        const double slots = 2.0 * num_cu, wgs = (double)tiles * sp;
+        const double slots = (double)(per_cu * num_cu), wgs = (double)tiles * sp;
+        if (single && wgs < 0.9 * num_cu) continue;       // measured far slower than the model when CUs stay idle
         const double rounds = std::ceil(wgs / slots) / (wgs / slots);
-        const double operand = (double)a.K * (double)(tm * bm) * (double)(tn * bn) * (1.0 / bm + 1.0 / bn) * limbs;
+        const double operand = (double)a.K * (double)(tm * bm) * (double)(tn * bn) * (1.0 / bm + 1.0 / bn) * limbs *
+                               (single ? 1.6 : 1.0);
         const double slab = sp > 1 ? 2.0 * (double)a.M * a.N * (acc_bits / 8) * sp : 0.0;
         const double cost = operand * rounds / 10.7e12 + slab / 3.1e12 + (sp > 1 ? 5e-6 : 0.0);
         if (cost < best) { best = cost; best_splits = (int)sp; t.bm = bm; t.bn = bn; }
