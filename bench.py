@@ -4,7 +4,7 @@
 A step is one pass of the whole path over one synthetic batch of the AlexNet-CIFAR-style
 conv layer (batch 128, 64ch 16x16 -> 192ch 3x3, all tensors <8,5>):
 
-    quantize(X, W, dY)  ->  conv fwd (+ReLU)  ->  dgrad  ->  wgrad   (outputs requantized, SR)
+    quantize(X, W, dY)  ->  conv fwd (+ReLU)  ->  backward: dgrad + wgrad   (outputs requantized, SR)
     ->  KL-divergence precision search on W (WL 4..16, 2048 bins)
 
 All inputs are resident in HBM before the timed region.  `value` is useful conv/GEMM
@@ -97,7 +97,7 @@ def next_rows(ctx, pkg, torch, w):
 
 def other_config(args, cfg):
     """Configs 1, 3, 4 and 5 (supplementary lines; the default run is config 2).  A step is, for every
-    layer of the config, quantize(X, W, dY) + fwd + dgrad + wgrad (requantized with SR), then ONE
+    layer of the config, quantize(X, W, dY) + fwd + backward (dgrad + wgrad; requantized with SR), then ONE
     batched KLD call over all weight tensors of the config.  Config 1 is a GEMM instead of a layer."""
     import numpy as np
     import torch
@@ -150,8 +150,7 @@ def other_config(args, cfg):
             def mk(d=d, f=f, x=x, w=w, dy=dy, qx=qx, qw=qw, qdy=qdy, y=y, dx=dx, dw=dw, cnt=cnt, eps=eps):
                 return [("quantize", lambda: ctx.quantize_batched([x, w, dy], [f] * 3, [1, 2, 3], pkg.SR, 0, outs=[qx, qw, qdy], counters=cnt)),
                         ("fwd", lambda: ctx.conv_fwd(d, qx, f, qw, f, eps[0], out=y)),
-                        ("dgrad", lambda: ctx.conv_dgrad(d, qdy, f, qw, f, eps[1], out=dx)),
-                        ("wgrad", lambda: ctx.conv_wgrad(d, qdy, f, qx, f, eps[2], out=dw))]
+                        ("backward", lambda: ctx.conv_backward(d, qdy, f, qw, f, qx, f, eps[1], eps[2], out_dx=dx, out_dw=dw))]
             calls += mk()
             ops = 3 * 2.0 * s.macs
             useful += ops
@@ -190,7 +189,7 @@ def other_config(args, cfg):
         e1.record()
         torch.cuda.synchronize()
         kind_ms[kind] = kind_ms.get(kind, 0.0) + e0.elapsed_time(e1) / reps
-    conv_ms = sum(kind_ms.get(k, 0.0) for k in ("fwd", "dgrad", "wgrad"))
+    conv_ms = sum(kind_ms.get(k, 0.0) for k in ("fwd", "backward"))
     out = {
         "metric": "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s",
         "value": useful / (ms_step * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -291,8 +290,7 @@ def main():
         "quantize": lambda: ctx.quantize_batched([x, w, dy], [f, f, f], [1, 2, 3], pkg.SR, 0, outs=[qx, qw, qdy],
                                                  counters=counters),
         "conv_fwd": lambda: ctx.conv_fwd(d, qx, f, qw, f, ep_y, out=y),
-        "conv_dgrad": lambda: ctx.conv_dgrad(d, qdy, f, qw, f, ep_dx, out=dx),
-        "conv_wgrad": lambda: ctx.conv_wgrad(d, qdy, f, qx, f, ep_dw, out=dw),
+        "conv_backward": lambda: ctx.conv_backward(d, qdy, f, qw, f, qx, f, ep_dx, ep_dw, out_dx=dx, out_dw=dw),
         "kld_search": lambda: ctx.kld_precision_search_batched([w.view(-1)], [3], [2048], [2], 4, 16, 1e-2, kld=kld,
                                                                sel=sel),
     }
@@ -305,8 +303,7 @@ def main():
         calls["conv_fwd"]()
         if ev is not None:
             ev[1].record()
-        calls["conv_dgrad"]()
-        calls["conv_wgrad"]()
+        calls["conv_backward"]()      # dgrad + wgrad of the layer, one call
         calls["kld_search"]()
 
     for _ in range(args.warmup):
@@ -363,7 +360,8 @@ def main():
                                            "that rocprofv3's kernel duration excludes (about 2-4 us)"},
         "host_enqueue_ms_per_step": t_enq / args.steps * 1e3,
         "calls_ms_back_to_back": call_ms,
-        "conv_TOPS": {n: conv_ops / (call_ms["conv_" + n] * 1e-3) / 1e12 for n in ("fwd", "dgrad", "wgrad")},
+        "conv_TOPS": {"fwd": conv_ops / (call_ms["conv_fwd"] * 1e-3) / 1e12,
+                      "backward (dgrad + wgrad)": 2 * conv_ops / (call_ms["conv_backward"] * 1e-3) / 1e12},
         "quantize_GBps": q_bytes / (call_ms["quantize"] * 1e-3) / 1e9,
         "quantize_frac_hbm": q_bytes / (call_ms["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
         "kld_GBps": kld_bytes / (call_ms["kld_search"] * 1e-3) / 1e9,

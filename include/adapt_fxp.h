@@ -145,6 +145,15 @@ int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fm
 int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy,
                      const void *x, adapt_fmt fx, void *dw, adapt_epilogue ep);
 
+/* Both gradients of one convolution layer (the backward pass of Alg. 1 for that layer): dx exactly
+ * as adapt_conv_dgrad(d, dy, w) with ep_dx and dw exactly as adapt_conv_wgrad(d, dy, x) with ep_dw.
+ * When both contractions take the one-limb vector path (all word lengths <= 8, channel counts
+ * multiples of 16, 192-deep stages) they share one kernel launch; otherwise the two run one
+ * after the other.  Arguments and limits as for the two separate calls. */
+int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy,
+                        const void *w, adapt_fmt fw, const void *x, adapt_fmt fx,
+                        void *dx, adapt_epilogue ep_dx, void *dw, adapt_epilogue ep_dw);
+
 /* ---- PushDown: KL-divergence precision search (Sec. 3.3, Alg. 3) --------------------------- */
 
 /* For every candidate word length WL_c = wl_lo..wl_hi with FL_c = WL_c - il (il = integer bits

@@ -106,6 +106,7 @@ def load_library():
     lib.adapt_fxp_gemm.argtypes = [vp, i, i, i, i, i, vp, Fmt, i, vp, Fmt, i, vp, i, Epilogue]
     for f in (lib.adapt_conv_fwd, lib.adapt_conv_dgrad, lib.adapt_conv_wgrad):
         f.argtypes = [vp, ConvDesc, vp, Fmt, vp, Fmt, vp, Epilogue]
+    lib.adapt_conv_backward.argtypes = [vp, ConvDesc, vp, Fmt, vp, Fmt, vp, Fmt, vp, Epilogue, vp, Epilogue]
     lib.adapt_kld_precision_search.argtypes = [vp, vp, sz, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
     lib.adapt_kld_precision_search_batched.argtypes = [vp, C.POINTER(KldItem), i, i, i, dbl, dbl, i, u64, vp, vp]
     lib.adapt_kld_precision_search_ranged.argtypes = [vp, vp, sz, vp, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
@@ -266,6 +267,18 @@ class Context:
             out = torch.empty((d.k, d.r, d.s, d.c), dtype=self._out_dtype(d.n * d.p * d.q, fdy, fx, ep), device=dy.device)
         _check(self._lib.adapt_conv_wgrad(self._h, d, _ptr(dy), fdy, _ptr(x), fx, _ptr(out), ep), "adapt_conv_wgrad")
         return out
+
+    def conv_backward(self, d: ConvDesc, dy, fdy, w, fw, x, fx, ep_dx, ep_dw, out_dx=None, out_dw=None):
+        """Both gradients of a layer in one call; returns (dx, dw)."""
+        torch = self._torch
+        fdy, fw, fx = Fmt(*fdy), Fmt(*fw), Fmt(*fx)
+        if out_dx is None:
+            out_dx = torch.empty((d.n, d.h, d.w, d.c), dtype=self._out_dtype(d.r * d.s * d.k, fdy, fw, ep_dx), device=dy.device)
+        if out_dw is None:
+            out_dw = torch.empty((d.k, d.r, d.s, d.c), dtype=self._out_dtype(d.n * d.p * d.q, fdy, fx, ep_dw), device=dy.device)
+        _check(self._lib.adapt_conv_backward(self._h, d, _ptr(dy), fdy, _ptr(w), fw, _ptr(x), fx, _ptr(out_dx), ep_dx,
+                                             _ptr(out_dw), ep_dw), "adapt_conv_backward")
+        return out_dx, out_dw
 
     # -- KLD precision search -----------------------------------------------------------------
     def kld_precision_search(self, w, wl_lo, wl_hi, il, bins, eps, alpha=-1.0, mode=SR, seed=0, stream=0,

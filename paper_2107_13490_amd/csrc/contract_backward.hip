@@ -1,0 +1,52 @@
+// C entry point of a layer's backward pass: data gradient and weight gradient of one convolution
+// (Alg. 1, the backward-pass line, per layer).  Results are exactly those of adapt_conv_dgrad and
+// adapt_conv_wgrad; when both contractions take the one-limb vector path with 192-deep stages
+// they run as one launch.
+#include "contract_pair.hpp"
+
+using namespace adapt;
+
+static bool pairable(const ContractPlan &p, bool is_dgrad)
+{
+    if (p.empty || p.limbs != 1 || p.tile.bkt != 192) return false;
+    if (is_dgrad) {
+        if (p.splits != 1 || p.kern.act_load != LOAD_VEC || p.kern.wgt_load != LOAD_ROWS) return false;
+    } else {
+        if (p.kern.act_load != LOAD_ROWS || p.kern.wgt_load != LOAD_ROWS) return false;
+    }
+    return (p.tile.bm == 64 || p.tile.bm == 128) && (p.tile.bn == 64 || p.tile.bn == 128);
+}
+
+extern "C" int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *w,
+                                   adapt_fmt fw, const void *x, adapt_fmt fx, void *dx, adapt_epilogue ep_dx, void *dw,
+                                   adapt_epilogue ep_dw)
+{
+    if (!ctx || !fmt_ok(fdy) || !fmt_ok(fw) || !fmt_ok(fx) || !conv_ok(d)) return ADAPT_EINVAL;
+    if (!dw || !aligned16(dw)) return ADAPT_EINVAL;
+    if (d.n > 0 && (!check_ptrs(dy, w, dx) || !check_ptrs(dy, x, dw))) return ADAPT_EINVAL;
+    ContractArgs aw = {};
+    if (int s = fill_wgrad(aw, d, dy, fdy, x, fx, dw)) return s;
+    if (d.n == 0) return run_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0);      // dw = 0, no dx
+    ContractArgs ad = {};
+    if (int s = fill_dgrad(ad, d, dy, fdy, w, fw, dx)) return s;
+    ContractPlan pd, pw;
+    if (int s = plan_contraction<OP_DGRAD>(ctx, ad, fdy, fw, ep_dx, 0, pd)) return s;
+    if (int s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0, pw)) return s;
+    hipError_t e = hipSuccess;
+    bool paired = false;
+    if (pairable(pd, true) && pairable(pw, false)) {
+        if (pd.tile.bm == 64 && pd.tile.bn == 64) e = launch_pair_d64x64(ctx, pd, pw, &paired);
+        else if (pd.tile.bm == 128 && pd.tile.bn == 64) e = launch_pair_d128x64(ctx, pd, pw, &paired);
+        else if (pd.tile.bm == 64 && pd.tile.bn == 128) e = launch_pair_d64x128(ctx, pd, pw, &paired);
+        else e = launch_pair_d128x128(ctx, pd, pw, &paired);
+        if (e == hipSuccess && paired) e = finish_planned(ctx, pw);
+    }
+    if (!paired) {
+        // one after the other; both may use the scratch from its start because the stream orders them
+        e = launch_planned<OP_DGRAD>(ctx, pd);
+        if (e == hipSuccess) e = finish_planned(ctx, pd);
+        if (e == hipSuccess) e = launch_planned<OP_WGRAD>(ctx, pw);
+        if (e == hipSuccess) e = finish_planned(ctx, pw);
+    }
+    return hip_status(ctx, e);
+}

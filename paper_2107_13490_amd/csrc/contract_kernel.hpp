@@ -582,9 +582,11 @@ __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
 
+// `lin` of `nwg` blocks, `ntiles` output tiles (the rest of the factor nwg / ntiles are K splits);
+// `smem` is the block's dynamic LDS.
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PF>
-__global__ void __launch_bounds__(kThreads)
-contract_kernel(const ContractArgs a)
+__device__ __forceinline__ void contract_body(const ContractArgs &a, const unsigned lin, const unsigned nwg,
+                                              const unsigned ntiles, char *const smem)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per block");
     typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT, AES>::type LA;
@@ -592,7 +594,6 @@ contract_kernel(const ContractArgs a)
     constexpr bool A_R = AMODE == LOAD_ROWS, W_R = WMODE == LOAD_ROWS;
     constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
     constexpr int MB = WM / 32, NB = WN / 32;       // 32x32 blocks per wave
-    extern __shared__ __attribute__((aligned(16))) char smem[];
     char *const a_hi = smem, *const a_lo = smem + LA::TILE_BYTES;
     char *const b_hi = smem + LA::TILE_BYTES * LIMBS, *const b_lo = b_hi + LB::TILE_BYTES;
 
@@ -608,10 +609,9 @@ contract_kernel(const ContractArgs a)
     // Workgroups go to the 8 XCDs round-robin in launch order and each XCD has its own L2: give
     // every XCD one contiguous range of the (split, tile_m, tile_n) order, so that blocks which
     // share operand rows (neighbouring tiles, all tiles of one split) fetch them from HBM once.
-    const unsigned nwg = gridDim.x * gridDim.y, lin = blockIdx.y * gridDim.x + blockIdx.x;
     const unsigned per_xcd = nwg / kXcds, extra = nwg % kXcds, xcd = lin % kXcds;
     const unsigned vid = a.xcd_remap ? xcd * per_xcd + min(xcd, extra) + lin / kXcds : lin;
-    const int split = vid / gridDim.x, tile = vid % gridDim.x;
+    const int split = vid / ntiles, tile = vid % ntiles;
     const int tiles_n = (a.N + BN - 1) / BN;
     const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -785,6 +785,30 @@ contract_kernel(const ContractArgs a)
         }
     ADAPT_STAMP(4);
     ADAPT_STAMP_WG(1);
+}
+
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PF>
+__global__ void __launch_bounds__(kThreads)
+contract_kernel(const ContractArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    contract_body<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PF>(a, blockIdx.y * gridDim.x + blockIdx.x,
+                                                                               gridDim.x * gridDim.y, gridDim.x, smem);
+}
+
+// Two independent contractions in one launch (the two gradients of a layer): blocks [0, n_first)
+// run the first, the rest the second, so that each fills the CUs the other leaves idle and one
+// launch floor is paid instead of two.  One-limb, 192-deep stages, int8 operands.
+template <int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB>
+__global__ void __launch_bounds__(kThreads)
+contract_pair_kernel(const ContractArgs a, const ContractArgs b, const unsigned n_first, const unsigned tiles_a,
+                     const unsigned tiles_b)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    if (blockIdx.x < n_first)
+        contract_body<OPA, 1, AMA, WMA, 1, 1, BMA, BNA, 2, 2, 192, 1>(a, blockIdx.x, n_first, tiles_a, smem);
+    else
+        contract_body<OPB, 1, AMB, WMB, 1, 1, BMB, BNB, 2, 2, 192, 1>(b, blockIdx.x - n_first, gridDim.x - n_first, tiles_b, smem);
 }
 
 // ---- helper: split-K finish ---------------------------------------------------------------------------
@@ -992,12 +1016,21 @@ static int pick_split_tile(const ContractArgs &a, int limbs, int acc_bits, int n
     return best_splits;
 }
 
-// Fills the parts of ContractArgs common to all ops and runs the kernel.  K is split across
-// blocks (exact partial sums in workspace slabs, summed by finish_kernel) when a single block
-// could overflow its int32 accumulators or when the output has too few tiles to fill the GPU.
+// A contraction planned on the host: what the kernel gets, and what finish_kernel gets when K is
+// split across blocks (exact partial sums in workspace slabs) because a single block could overflow
+// its int32 accumulators or because the output has too few tiles to fill the GPU.
+struct ContractPlan {
+    ContractArgs kern;      // arguments of the contraction kernel (final output, or slabs)
+    ContractArgs fin;       // arguments of finish_kernel (splits > 1)
+    TileShape tile;
+    int limbs, bits, splits;
+    const char *acc;        // slabs
+    bool empty;             // nothing to do (M or N is 0)
+};
+
 template <int OP>
-static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_fmt fb, adapt_epilogue ep,
-                           size_t ws_offset /* bytes of scratch already in use */)
+static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_fmt fb, adapt_epilogue ep,
+                            size_t ws_offset /* bytes of scratch already in use */, ContractPlan &p)
 {
     const int limbs = (fa.wl > 8 || fb.wl > 8) ? 2 : 1;
     const int bits = adapt_acc_bits(a.K, fa, fb);
@@ -1014,7 +1047,12 @@ static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_f
         a.seed = ep.rng.seed;
         a.stream = ep.rng.stream;
     }
-    if (a.M == 0 || a.N == 0) return ADAPT_OK;
+    p.limbs = limbs;
+    p.bits = bits;
+    p.empty = a.M == 0 || a.N == 0;
+    p.splits = 1;
+    p.acc = nullptr;
+    if (p.empty) return ADAPT_OK;
 
     TileShape t = pick_tile<OP>(a, limbs, ctx->num_cu);
     int model_splits = 0;
@@ -1045,12 +1083,12 @@ static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_f
     splits = a.K == 0 ? 1 : (a.K + k_per - 1) / k_per;
     a.k_per_split = k_per;
     a.slab_bytes = 0;
-
-    hipError_t e;
+    p.tile = t;
+    p.splits = splits;
     if (splits == 1) {
         a.out_mode = final_mode;
-        e = limbs == 1 ? launch_modes<OP, 1>(ctx, a, 1, t) : launch_modes<OP, 2>(ctx, a, 1, t);
-        return hip_status(ctx, e);
+        p.kern = a;
+        return ADAPT_OK;
     }
     // a partial sum is bounded like the total, so the slabs use the total's accumulator type
     const size_t acc_bytes = bits == 32 ? 4 : 8;
@@ -1058,21 +1096,44 @@ static int run_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_f
     const size_t off = (ws_offset + 255) & ~(size_t)255;
     if (off + slab * splits > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     char *acc = scratch(ctx) + off;
-    ContractArgs part = a;
-    part.out = acc;
-    part.ldc = a.N;
-    part.slab_bytes = (long long)slab;
-    part.out_mode = bits == 32 ? OUT_RAW32 : OUT_RAW64;
-    e = limbs == 1 ? launch_modes<OP, 1>(ctx, part, splits, t) : launch_modes<OP, 2>(ctx, part, splits, t);
-    if (e != hipSuccess) return hip_status(ctx, e);
-    ContractArgs fin = a;
-    fin.out_mode = final_mode;
-    const unsigned fgrid = (unsigned)std::min<size_t>(((size_t)a.M * a.N + 255) / 256, (size_t)ctx->num_cu * 8);
-    if (bits == 32)
-        hipLaunchKernelGGL(finish_kernel<int32_t>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const int32_t *>(acc), splits, fin);
+    p.acc = acc;
+    p.kern = a;
+    p.kern.out = acc;
+    p.kern.ldc = a.N;
+    p.kern.slab_bytes = (long long)slab;
+    p.kern.out_mode = bits == 32 ? OUT_RAW32 : OUT_RAW64;
+    p.fin = a;
+    p.fin.out_mode = final_mode;
+    return ADAPT_OK;
+}
+
+template <int OP>
+static hipError_t launch_planned(adapt_ctx *ctx, const ContractPlan &p)
+{
+    if (p.empty) return hipSuccess;
+    return p.limbs == 1 ? launch_modes<OP, 1>(ctx, p.kern, p.splits, p.tile) : launch_modes<OP, 2>(ctx, p.kern, p.splits, p.tile);
+}
+
+// the slab sum + epilogue of a split contraction
+static hipError_t finish_planned(adapt_ctx *ctx, const ContractPlan &p)
+{
+    if (p.empty || p.splits == 1) return hipSuccess;
+    const unsigned fgrid = (unsigned)std::min<size_t>(((size_t)p.fin.M * p.fin.N + 255) / 256, (size_t)ctx->num_cu * 8);
+    if (p.bits == 32)
+        hipLaunchKernelGGL(finish_kernel<int32_t>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const int32_t *>(p.acc), p.splits, p.fin);
     else
-        hipLaunchKernelGGL(finish_kernel<long long>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const long long *>(acc), splits, fin);
-    return hip_status(ctx, hipGetLastError());
+        hipLaunchKernelGGL(finish_kernel<long long>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const long long *>(p.acc), p.splits, p.fin);
+    return hipGetLastError();
+}
+
+template <int OP>
+static int run_contraction(adapt_ctx *ctx, const ContractArgs &a, adapt_fmt fa, adapt_fmt fb, adapt_epilogue ep, size_t ws_offset)
+{
+    ContractPlan p;
+    if (int s = plan_contraction<OP>(ctx, a, fa, fb, ep, ws_offset, p)) return s;
+    hipError_t e = launch_planned<OP>(ctx, p);
+    if (e == hipSuccess) e = finish_planned(ctx, p);
+    return hip_status(ctx, e);
 }
 
 static bool conv_ok(const adapt_conv_desc &d)
@@ -1099,6 +1160,36 @@ static int fill_conv(ContractArgs &a, const adapt_conv_desc &d)
     a.div_c = make_fastdiv(d.c); a.div_s = make_fastdiv(d.s); a.div_q = make_fastdiv(a.q); a.div_p = make_fastdiv(a.p);
     a.div_k = make_fastdiv(d.k); a.div_w = make_fastdiv(d.w); a.div_h = make_fastdiv(d.h);
     a.div_stride = make_fastdiv(d.stride);
+    return ADAPT_OK;
+}
+
+static int fill_dgrad(ContractArgs &a, const adapt_conv_desc &d, const void *dy, adapt_fmt fdy, const void *w, adapt_fmt fw, void *dx)
+{
+    if (int s = fill_conv(a, d)) return s;
+    a.act = dy; a.wgt = w; a.out = dx;
+    a.M = d.n * d.h * d.w; a.N = d.c; a.K = d.r * d.s * d.k;
+    a.act_es = storage_bytes(fdy); a.wgt_es = storage_bytes(fw);
+    a.act_bytes = (uint32_t)((long long)d.n * a.p * a.q * d.k * a.act_es);
+    a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);
+    a.act_load = d.k % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
+    a.wgt_load = d.c % 16 == 0 ? LOAD_ROWS : LOAD_SCALAR;     // rows (c) are contiguous in w[kout][r][s][c]
+    a.ldc = d.c;
+    a.uniform_tap = d.k % 64 == 0;
+    return ADAPT_OK;
+}
+
+static int fill_wgrad(ContractArgs &a, const adapt_conv_desc &d, const void *dy, adapt_fmt fdy, const void *x, adapt_fmt fx, void *dw)
+{
+    if (int s = fill_conv(a, d)) return s;
+    a.act = dy; a.wgt = x; a.out = dw;
+    a.M = d.k; a.N = d.r * d.s * d.c; a.K = d.n * a.p * a.q;
+    a.act_es = storage_bytes(fdy); a.wgt_es = storage_bytes(fx);
+    a.act_bytes = (uint32_t)((long long)d.n * a.p * a.q * d.k * a.act_es);
+    a.wgt_bytes = (uint32_t)((long long)d.n * d.h * d.w * d.c * a.wgt_es);
+    // rows (kout / c) are the contiguous direction of both operands
+    a.act_load = (d.k % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR;
+    a.wgt_load = (d.c % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR;
+    a.ldc = a.N;
     return ADAPT_OK;
 }
 

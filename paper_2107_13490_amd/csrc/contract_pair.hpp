@@ -1,0 +1,48 @@
+// Paired launch of a layer's two gradient contractions (see contract_pair_kernel).  The kernels are
+// instantiated in one translation unit per data-gradient tile to keep build times parallel.
+#pragma once
+#include "contract_kernel.hpp"
+
+namespace adapt {
+
+template <int DBM, int DBN, int WBM, int WBN>
+static hipError_t launch_pair(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w)
+{
+    typedef typename LoaderSelect<OP_DGRAD, true, LOAD_VEC, DBM, 1, 192, 1>::type DA;
+    typedef typename LoaderSelect<OP_DGRAD, false, LOAD_ROWS, DBN, 1, 192, 1>::type DB;
+    typedef typename LoaderSelect<OP_WGRAD, true, LOAD_ROWS, WBM, 1, 192, 1>::type WA;
+    typedef typename LoaderSelect<OP_WGRAD, false, LOAD_ROWS, WBN, 1, 192, 1>::type WB;
+    const size_t lds = std::max<size_t>(DA::TILE_BYTES + DB::TILE_BYTES, WA::TILE_BYTES + WB::TILE_BYTES);
+    auto kern = contract_pair_kernel<OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
+    static bool attr_done = false;
+    if (!attr_done && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const unsigned tiles_d = (unsigned)(((d.kern.M + DBM - 1) / DBM) * ((d.kern.N + DBN - 1) / DBN));
+    const unsigned tiles_w = (unsigned)(((w.kern.M + WBM - 1) / WBM) * ((w.kern.N + WBN - 1) / WBN));
+    const unsigned n_d = tiles_d * (unsigned)d.splits, n_w = tiles_w * (unsigned)w.splits;
+    hipLaunchKernelGGL(kern, dim3(n_d + n_w), dim3(kThreads), lds, ctx->stream, d.kern, w.kern, n_d, tiles_d, tiles_w);
+    return hipGetLastError();
+}
+
+// dispatch on the weight-gradient tile; *done stays false when the tile has no paired kernel
+template <int DBM, int DBN>
+static hipError_t launch_pair_for(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w, bool *done)
+{
+    *done = true;
+    if (w.tile.bm == 64 && w.tile.bn == 64) return launch_pair<DBM, DBN, 64, 64>(ctx, d, w);
+    if (w.tile.bm == 128 && w.tile.bn == 64) return launch_pair<DBM, DBN, 128, 64>(ctx, d, w);
+    if (w.tile.bm == 64 && w.tile.bn == 128) return launch_pair<DBM, DBN, 64, 128>(ctx, d, w);
+    if (w.tile.bm == 128 && w.tile.bn == 128) return launch_pair<DBM, DBN, 128, 128>(ctx, d, w);
+    *done = false;
+    return hipSuccess;
+}
+
+hipError_t launch_pair_d64x64(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w, bool *done);
+hipError_t launch_pair_d128x64(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w, bool *done);
+hipError_t launch_pair_d64x128(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w, bool *done);
+hipError_t launch_pair_d128x128(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w, bool *done);
+
+}  // namespace adapt

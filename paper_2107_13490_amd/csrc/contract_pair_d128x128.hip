@@ -1,0 +1,9 @@
+// Paired gradient kernels whose data-gradient tile is 128 x 128
+#include "contract_pair.hpp"
+
+namespace adapt {
+hipError_t launch_pair_d128x128(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w, bool *done)
+{
+    return launch_pair_for<128, 128>(ctx, d, w, done);
+}
+}  // namespace adapt

@@ -296,3 +296,52 @@ def test_config4_alexnet_layer_sweep_reduced_batch():
 
 def test_config5_resnet18_layer_sweep_reduced_batch():
     _sweep(wk.resnet18_cifar_layers(), batch=2, seed=50)
+
+
+# ---- both gradients in one call --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape,wl", [
+    ((8, 16, 16, 64, 192, 3, 3, 1, 1), 8),      # config-2 layer, reduced batch: paired launch
+    ((16, 16, 16, 128, 128, 3, 3, 1, 1), 8),    # 128-wide tiles
+    ((4, 32, 32, 64, 64, 3, 3, 1, 1), 6),
+    ((6, 16, 16, 64, 128, 3, 3, 2, 1), 8),      # stride 2
+    ((5, 9, 7, 32, 48, 3, 3, 1, 1), 8),         # ragged tiles
+    ((4, 8, 8, 256, 512, 1, 1, 2, 0), 4),       # 1x1 projection (64-deep stages: not paired)
+    ((3, 12, 12, 3, 64, 3, 3, 1, 1), 8),        # 3 input channels: element-wise path, not paired
+    ((4, 16, 16, 64, 64, 3, 3, 1, 1), 12),      # two limbs: not paired
+    ((2, 8, 8, 192, 384, 3, 3, 1, 1), 8),       # 192-wide data-gradient tile: not paired
+])
+def test_backward_equals_the_two_separate_calls(shape, wl):
+    n, h, w_, c, k, r, s, stride, pad = shape
+    rng = np.random.default_rng(sum(shape) + wl)
+    lim = 1 << (wl - 1)
+    dt = np.int8 if wl <= 8 else np.int16
+    d = ConvDesc(n, h, w_, c, k, r, s, stride, pad)
+    x = rng.integers(-lim, lim, (n, h, w_, c)).astype(dt)
+    wt = rng.integers(-lim, lim, (k, r, s, c)).astype(dt)
+    dy = rng.integers(-lim, lim, (n, d.p, d.q, k)).astype(dt)
+    f = (wl, wl - 3)
+    for ep_dx, ep_dw in ((Epilogue.requant(wl, wl - 3, pkg.SR, 0, 11), Epilogue.requant(wl, wl - 2, pkg.SR, 0, 12)),
+                         (Epilogue.exact(), Epilogue.exact())):
+        dx1 = ctx().conv_dgrad(d, dev(dy), f, dev(wt), f, ep_dx)
+        dw1 = ctx().conv_wgrad(d, dev(dy), f, dev(x), f, ep_dw)
+        dx2, dw2 = ctx().conv_backward(d, dev(dy), f, dev(wt), f, dev(x), f, ep_dx, ep_dw)
+        assert torch.equal(dx1, dx2) and torch.equal(dw1, dw2)
+    # and against the oracle directly (exact outputs)
+    want_dx = co.conv_dgrad(dy.astype(np.int64), wt.astype(np.int64), h, w_, stride, pad)
+    want_dw = co.conv_wgrad(dy.astype(np.int64), x.astype(np.int64), r, s, stride, pad)
+    assert np.array_equal(host(dx2).astype(np.int64), want_dx) and np.array_equal(host(dw2).astype(np.int64), want_dw)
+
+
+def test_backward_config2_full_size():
+    L = wk.config2()
+    s = L.shape
+    d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+    f = (8, 5)
+    qx, qw, qdy = (ctx().quantize(dev(t), 8, 5, pkg.SR, 0, i + 1)[0] for i, t in enumerate((L.x, L.w, L.dy)))
+    ep_dx, ep_dw = Epilogue.requant(8, 5, pkg.SR, 0, 11), Epilogue.requant(8, 5, pkg.SR, 0, 12)
+    dx1 = ctx().conv_dgrad(d, qdy, f, qw, f, ep_dx)
+    dw1 = ctx().conv_wgrad(d, qdy, f, qx, f, ep_dw)
+    for _ in range(3):
+        dx2, dw2 = ctx().conv_backward(d, qdy, f, qw, f, qx, f, ep_dx, ep_dw)
+        assert torch.equal(dx1, dx2) and torch.equal(dw1, dw2)
