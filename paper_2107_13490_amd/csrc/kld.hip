@@ -24,7 +24,8 @@ namespace adapt {
 constexpr int kMaxCand = 15;
 constexpr int kHistMaxThreads = 1024;
 constexpr int kRangeThreads = 256;
-constexpr size_t kLdsBudget = 144 * 1024;
+constexpr size_t kLdsBudget = 156 * 1024;      // dynamic LDS of a block; 160 KB per CU less the static part
+constexpr int kPrivWords = 1024;                  // counters of one coarse candidate's private table
 
 struct KldCand {
     int d;        // T >> d gives floor(x * 2^(FL_c + 16))
@@ -34,6 +35,11 @@ struct KldCand {
     int hi;       // lo + bin of the largest code of the candidate (already clamped to [0, nb-1])
     int bmax;
     long long base64;
+    // Candidates whose codes are coarser than the bins populate few bins, and the LDS atomics of a
+    // wavefront would serialise on them: they are counted by code, in lane-private LDS counters
+    // (index (q - qmin) * 2^rsh + lane mod 2^rsh, q clamped to [qmin, qmax]), and mapped to bins once
+    // per block.
+    int coarse, qmin, qmax, rsh;
 };
 
 struct KldPlan {
@@ -107,6 +113,18 @@ __device__ void make_candidate(KldPlan *plan, int c, int wl_lo, int wl_hi, int i
     }
     k.bmax = (int)(braw < 0 ? 0 : braw > nb - 1 ? nb - 1 : braw);
     k.hi = k.lo + k.bmax;
+    // Codes coarser than the bins (kind 1) populate few bins: count them by code.  Only the codes
+    // whose bins fall inside the row matter (the others clamp to its ends, as their neighbours do).
+    k.coarse = 0; k.qmin = 0; k.qmax = 0; k.rsh = 0;
+    if (k.kind == 1) {
+        const int qa = k.lo >> k.s, qb = -((-k.hi) >> k.s);          // floor(lo / 2^s), ceil(hi / 2^s)
+        const int qlo = qa > -(int)(qmax + 1) ? qa : -(int)(qmax + 1), qhi = qb < (int)qmax ? qb : (int)qmax;
+        const int ncodes = qhi - qlo + 1;
+        if (ncodes >= 1 && ncodes <= kPrivWords) {
+            k.coarse = 1; k.qmin = qlo; k.qmax = qhi;
+            while (k.rsh < 6 && (ncodes << (k.rsh + 1)) <= kPrivWords) ++k.rsh;
+        }
+    }
     plan->cand[c] = k;
 }
 
@@ -156,6 +174,26 @@ __device__ __forceinline__ int value_bin(float v, int e, float base_f)
 // an element with scaled value T and rounding bits r; `inc` is 0 for non-finite elements (their
 // clamped bin is a valid address).  The branch on the candidate's kind is uniform and outside
 // the element loop, so the loop bodies are straight-line code.
+// bin + k.lo of code q (the value that count_candidate computes from T and r), clamped into the row
+__device__ __forceinline__ int bin_of_code(const KldCand &k, int q)
+{
+    if (k.kind == 0) return min(max(q >> (k.s - 16), k.lo), k.hi);
+    if (k.kind == 1) return min(max((int)((unsigned)q << k.s), k.lo), k.hi);
+    const long long b64 = (long long)((unsigned long long)(long long)q << k.s) - k.base64;
+    return (int)(b64 < 0 ? 0 : b64 > (long long)k.bmax ? (long long)k.bmax : b64) + k.lo;
+}
+
+__device__ __forceinline__ void count_candidate_by_code(const KldCand &k, uint32_t *priv, int lane, const int (&T)[8],
+                                                        const int (&r)[8], const uint32_t (&inc)[8])
+{
+    const int sub = lane & ((1 << k.rsh) - 1);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int q = min(max(((T[j] >> k.d) + r[j]) >> 16, k.qmin), k.qmax);
+        atomicAdd(&priv[((q - k.qmin) << k.rsh) + sub], inc[j]);
+    }
+}
+
 __device__ __forceinline__ void count_candidate(const KldCand &k, uint32_t *row, const int (&T)[8], const int (&r)[8],
                                                 const uint32_t (&inc)[8])
 {
@@ -205,6 +243,7 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     __shared__ KldPlan plan;
     __shared__ float slo[kHistMaxThreads / kWave], shi[kHistMaxThreads / kWave];
     __shared__ int row_off[kMaxCand];          // word offset of the candidate's row minus its bin origin
+    __shared__ int priv_off[kMaxCand];         // word offset of a coarse candidate's private table, else -1
     const int nthreads = blockDim.x, nwaves = nthreads / kWave;
     const int ncand = wl_hi - wl_lo + 1;
 
@@ -247,12 +286,23 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     uint32_t *hist;
     int row_stride;
     if (USE_LDS) {
-        const int total = rows * nb;
+        // rows, padded to a multiple of 4 words, then one private table per coarse candidate of this block
+        const int rows_words = (rows * nb + 3) & ~3;
+        int ncoarse = 0;
+        for (int c = c_begin; c < c_end; ++c) ncoarse += plan.cand[c].coarse;
+        const int total = rows_words + ncoarse * kPrivWords;
         for (int i = threadIdx.x; i < total / 4; i += nthreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
-        if ((int)threadIdx.x < (total & 3)) lds[(total & ~3) + threadIdx.x] = 0;
+        if (threadIdx.x == 0) {
+            int next = rows_words;
+            for (int c = c_begin; c < c_end; ++c) {
+                priv_off[c] = plan.cand[c].coarse ? next : -1;
+                next += plan.cand[c].coarse ? kPrivWords : 0;
+            }
+        }
         hist = lds;
         row_stride = nb;
     } else {
+        if ((int)threadIdx.x >= c_begin && (int)threadIdx.x < c_end) priv_off[threadIdx.x] = -1;
         hist = slabs + ((size_t)blockIdx.x * total_rows + row0) * bins;
         row_stride = bins;
     }
@@ -273,7 +323,10 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
             // (the clamp only acts when a caller-supplied range does not bound the tensor)
             if (do_ref) atomicAdd(&hist[fin ? min(max(value_bin(v[j], e, base_f), 0), nb - 1) : 0], inc[j]);
         }
-        for (int c = c_begin; c < c_end; ++c) count_candidate(plan.cand[c], hist + row_off[c], T, r, inc);
+        for (int c = c_begin; c < c_end; ++c) {
+            if (USE_LDS && priv_off[c] >= 0) count_candidate_by_code(plan.cand[c], lds + priv_off[c], threadIdx.x & (kWave - 1), T, r, inc);
+            else count_candidate(plan.cand[c], hist + row_off[c], T, r, inc);
+        }
     };
 
     const uint64_t full_groups = n >> 3;
@@ -309,6 +362,19 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     ADAPT_STAMP(3);
     if (USE_LDS) {
         __syncthreads();
+        // coarse candidates: per-code counts (summed over the lane-private copies) into the bins of the row
+        bool any = false;
+        for (int c = c_begin; c < c_end; ++c) {
+            if (priv_off[c] < 0) continue;
+            any = true;
+            const KldCand &k = plan.cand[c];
+            const uint32_t *priv = lds + priv_off[c];
+            for (int i = threadIdx.x; i < kPrivWords; i += nthreads) {
+                const uint32_t v = priv[i];
+                if (v) atomicAdd(&hist[row_off[c] + bin_of_code(k, (i >> k.rsh) + k.qmin)], v);
+            }
+        }
+        if (any) __syncthreads();
         ADAPT_STAMP(4);
         // slab rows are 16-byte aligned when bins % 4 == 0; otherwise every counter is written singly
         const int nb4 = (bins % 4 == 0) ? nb / 4 : 0;
@@ -483,14 +549,16 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
     if (!range) hipLaunchKernelGGL(kld_range_kernel, dim3(range_grid), dim3(kRangeThreads), 0, ctx->stream, w, n, partial);
 
     const size_t row_bytes = (size_t)bins * 4;
-    if (row_bytes <= kLdsBudget) {
+    // a row plus, for a candidate counted by code, its private table
+    const size_t per_row = row_bytes + kPrivWords * 4;
+    if (per_row + 16 <= kLdsBudget) {
         // rows per block: as many as LDS holds, fewer when the tensor alone cannot fill the GPU
-        int rows_per_group = (int)std::min<size_t>(rows, kLdsBudget / row_bytes);
+        int rows_per_group = (int)std::min<size_t>(rows, kLdsBudget / per_row);
         const int want_groups = std::max(1, (2 * ctx->num_cu + hist_grid - 1) / hist_grid);
         rows_per_group = std::max(1, std::min(rows_per_group, (rows + want_groups - 1) / want_groups));
         const int groups = (rows + rows_per_group - 1) / rows_per_group;
         // one set of LDS histograms per block: per-wavefront replicas were measured no faster
-        const size_t lds = (size_t)rows_per_group * row_bytes;
+        const size_t lds = (size_t)rows_per_group * per_row + 16;
         hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, range_src,
                            range_count, wl_lo, wl_hi, il, bins, plan, slabs, rows, rows_per_group, mode, seed, stream);
     } else {
