@@ -25,12 +25,12 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, 256 CU x 8192 op/clk x 2.4 GHz
 PEAK_HBM_GBPS = 8000.0
-# HBM bytes per launch of the forward-convolution kernel on this workload, from rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE (KiB per dispatch, scaled by what a plain 256 MiB device copy reads on
-# the same counters: x2.0 and x1.0); the summary with the commands is
-# profiles/bench_config2_hbm_traffic.md.  Counters cannot be read from inside this process.
-FWD_TRAFFIC_BYTES = {"read": 4036 * 1024, "written": 6144 * 1024}
-
+# HBM bytes per launch on this workload, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per
+# dispatch, scaled by what a plain 256 MiB device copy reads on the same counters: x2.0 and x1.0);
+# the summary with the commands is profiles/bench_config2_hbm_traffic.md.  Counters cannot be read
+# from inside this process.  Backward = the paired dgrad + wgrad kernel plus the slab-sum kernel.
+FWD_TRAFFIC_BYTES = {"read": 3283 * 1024, "written": 6144 * 1024}
+BWD_TRAFFIC_BYTES = {"read": (12697 + 7837) * 1024, "written": (9824 + 108) * 1024}
 
 def cpu_baseline(batch: int):
     """The oracle, as it stands, on a bounded sample (reduced batch) of the same layer."""
@@ -294,33 +294,41 @@ def main():
         "kld_search": lambda: ctx.kld_precision_search_batched([w.view(-1)], [3], [2048], [2], 4, 16, 1e-2, kld=kld,
                                                                sel=sel),
     }
-    EV_EVERY = 10    # the dominant kernel is bracketed by events on every 10th step of the timed region
+    EV_EVERY = 10    # on every 10th step of the timed region events bracket the backward call (the dominant
+                     # kernel), on every 10th + 5 the forward call
 
-    def step(ev=None):
+    def step(ev=None, which=None):
         calls["quantize"]()
-        if ev is not None:
+        if which == "fwd":
             ev[0].record()
         calls["conv_fwd"]()
-        if ev is not None:
+        if which == "fwd":
             ev[1].record()
+        if which == "bwd":
+            ev[0].record()
         calls["conv_backward"]()      # dgrad + wgrad of the layer, one call
+        if which == "bwd":
+            ev[1].record()
         calls["kld_search"]()
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] if i % EV_EVERY == 0 else None
-              for i in range(args.steps)]
+    kinds = ["bwd" if i % EV_EVERY == 0 else "fwd" if i % EV_EVERY == EV_EVERY // 2 else None for i in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] if k else None for k in kinds]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(events[i])
+        step(events[i], kinds[i])
     t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_step = dt / args.steps * 1e3
-    timed = [ev for ev in events if ev is not None]
-    fwd_ms = sum(ev[0].elapsed_time(ev[1]) for ev in timed) / len(timed)
+
+    def mean_ms(kind):
+        ts = [ev[0].elapsed_time(ev[1]) for ev, k in zip(events, kinds) if k == kind]
+        return sum(ts) / len(ts) if ts else float("nan")
+    fwd_ms, bwd_ms = mean_ms("fwd"), mean_ms("bwd")
 
     # per-call device time outside the timed region: each call repeated back to back between two events
     reps = 50
@@ -338,26 +346,33 @@ def main():
 
     conv_ops = 2.0 * s.macs
     value = 3 * conv_ops / (ms_step * 1e-3) / 1e12
-    # dominant kernel: the forward convolution is one launch of the MFMA contraction kernel
+    # dominant kernel: the paired dgrad + wgrad launch of the backward call (its slab-sum kernel is inside the
+    # bracket too); the forward convolution, one launch of the same contraction code, is reported beside it
     fwd_tops = conv_ops / (fwd_ms * 1e-3) / 1e12
+    bwd_tops = 2 * conv_ops / (bwd_ms * 1e-3) / 1e12
     q_bytes = 5.0 * (x.numel() + w.numel() + dy.numel())
     kld_bytes = 8.0 * w.numel()
+    note = ("HIP events around the call inside the timed region; includes the dispatch gaps that rocprofv3's kernel "
+            "durations exclude (about 2-4 us per launch)")
     out = {
         "metric": "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s",
         "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "configs[1]: AlexNet-CIFAR conv 64->192 3x3 @16x16, batch 128, <8,5>; quantize(X,W,dY) "
-                               "+ fwd + dgrad + wgrad (requantized, SR) + KLD search on W (WL 4..16, 2048 bins)",
+                               "+ fwd + backward (dgrad + wgrad) (requantized, SR) + KLD search on W (WL 4..16, 2048 bins)",
                    "useful_ops_per_step": 3 * conv_ops},
-        "roofline": {"bound": "mfma", "kernel": "contract_kernel<fwd> (the conv_fwd call is this one launch)",
-                     "achieved": fwd_tops, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": fwd_tops / PEAK_INT8_TOPS,
-                     "traffic": FWD_TRAFFIC_BYTES["read"] + FWD_TRAFFIC_BYTES["written"],
-                     "traffic_unit": "bytes of HBM per launch (rocprofv3 --pmc, see profiles/)",
-                     "algorithmic_bytes": x.numel() + w.numel() + y.numel(),
-                     "avg_launch_ms": fwd_ms,
-                     "avg_launch_ms_note": "HIP events around the call inside the timed region; includes the dispatch gap "
-                                           "that rocprofv3's kernel duration excludes (about 2-4 us)"},
+        "roofline": {"bound": "mfma",
+                     "kernel": "contract_pair_kernel<dgrad 64x64 | wgrad 64x64> + finish_kernel (the conv_backward call)",
+                     "achieved": bwd_tops, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": bwd_tops / PEAK_INT8_TOPS,
+                     "traffic": BWD_TRAFFIC_BYTES["read"] + BWD_TRAFFIC_BYTES["written"],
+                     "traffic_unit": "bytes of HBM per call (rocprofv3 --pmc, see profiles/)",
+                     "algorithmic_bytes": dy.numel() + w.numel() + x.numel() + dx.numel() + dw.numel(),
+                     "avg_launch_ms": bwd_ms, "avg_launch_ms_note": note},
+        "roofline_fwd": {"bound": "mfma", "kernel": "contract_kernel<fwd 64x192> (the conv_fwd call is this one launch)",
+                         "achieved": fwd_tops, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": fwd_tops / PEAK_INT8_TOPS,
+                         "traffic": FWD_TRAFFIC_BYTES["read"] + FWD_TRAFFIC_BYTES["written"],
+                         "algorithmic_bytes": x.numel() + w.numel() + y.numel(), "avg_launch_ms": fwd_ms},
         "host_enqueue_ms_per_step": t_enq / args.steps * 1e3,
         "calls_ms_back_to_back": call_ms,
         "conv_TOPS": {"fwd": conv_ops / (call_ms["conv_fwd"] * 1e-3) / 1e12,
