@@ -280,19 +280,23 @@ def main():
     dx = torch.empty(x.shape, dtype=torch.int8, device="cuda")
     dw = torch.empty(w.shape, dtype=torch.int8, device="cuda")
     counters = torch.empty(6, dtype=torch.int64, device="cuda")
-    kld = torch.empty((1, 13), dtype=torch.float64, device="cuda")
-    sel = torch.empty((1, 2), dtype=torch.int32, device="cuda")
+    kld = torch.empty(13, dtype=torch.float64, device="cuda")
+    sel = torch.empty(2, dtype=torch.int32, device="cuda")
+    grid = torch.empty(3, dtype=torch.int64, device="cuda")
+    ranges = torch.empty(6, dtype=torch.float32, device="cuda")
     ep_y = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10, relu=True)
     ep_dx = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 11)
     ep_dw = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 12)
 
     calls = {
+        # one launch quantizes the three tensors and, as a by-product of reading it, finds the range of W
         "quantize": lambda: ctx.quantize_batched([x, w, dy], [f, f, f], [1, 2, 3], pkg.SR, 0, outs=[qx, qw, qdy],
-                                                 counters=counters),
+                                                 counters=counters, ranges=ranges, range_of=[1]),
         "conv_fwd": lambda: ctx.conv_fwd(d, qx, f, qw, f, ep_y, out=y),
         "conv_backward": lambda: ctx.conv_backward(d, qdy, f, qw, f, qx, f, ep_dx, ep_dw, out_dx=dx, out_dw=dw),
-        "kld_search": lambda: ctx.kld_precision_search_batched([w.view(-1)], [3], [2048], [2], 4, 16, 1e-2, kld=kld,
-                                                               sel=sel),
+        # the search takes W's range from the quantize pass (no range pass of its own)
+        "kld_search": lambda: ctx.kld_precision_search_ranged(w.view(-1), ranges[2:4], 4, 16, 3, 2048, 1e-2, stream=2,
+                                                              kld=kld, sel=sel, grid=grid),
     }
     EV_EVERY = 10    # on every 10th step of the timed region events bracket the backward call (the dominant
                      # kernel), on every 10th + 5 the forward call
@@ -351,7 +355,7 @@ def main():
     fwd_tops = conv_ops / (fwd_ms * 1e-3) / 1e12
     bwd_tops = 2 * conv_ops / (bwd_ms * 1e-3) / 1e12
     q_bytes = 5.0 * (x.numel() + w.numel() + dy.numel())
-    kld_bytes = 8.0 * w.numel()
+    kld_bytes = 4.0 * w.numel()      # one read of W: the range comes from the quantize pass
     note = ("HIP events around the call inside the timed region; includes the dispatch gaps that rocprofv3's kernel "
             "durations exclude (about 2-4 us per launch)")
     out = {

@@ -112,6 +112,16 @@ typedef struct {
 } adapt_quantize_item;
 int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item *items, int count,
                            int mode, uint64_t seed, uint64_t *counters);
+/* The same, and the finite range of selected input tensors as a by-product of the pass that
+ * reads them: for every t with bit t of range_mask set, ranges[2t], ranges[2t+1] = min and max of
+ * the finite elements of item t's x (+inf, -inf if it has none); the other pairs are written as
+ * (+inf, -inf).  ranges: device float[2*count] or NULL; count <= 64 when it is given.  The pair of
+ * a weight tensor is what adapt_kld_precision_search_ranged takes, so that the precision search
+ * needs no range pass.  (Tracking costs a few instructions per element, so it is asked for per
+ * tensor: weights, not activations.) */
+int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantize_item *items, int count,
+                                  int mode, uint64_t seed, uint64_t *counters, float *ranges,
+                                  uint64_t range_mask);
 
 /* ---- integer contractions (ForwardPass / backward pass of Alg. 1 on quantized tensors) ---- */
 

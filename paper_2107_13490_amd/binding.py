@@ -103,6 +103,7 @@ def load_library():
     lib.adapt_acc_bits.argtypes = [i64, Fmt, Fmt]
     lib.adapt_quantize.argtypes = [vp, vp, sz, Fmt, Rng, vp, vp, vp]
     lib.adapt_quantize_batched.argtypes = [vp, C.POINTER(QuantizeItem), i, i, u64, vp]
+    lib.adapt_quantize_batched_ranges.argtypes = [vp, C.POINTER(QuantizeItem), i, i, u64, vp, vp, u64]
     lib.adapt_fxp_gemm.argtypes = [vp, i, i, i, i, i, vp, Fmt, i, vp, Fmt, i, vp, i, Epilogue]
     for f in (lib.adapt_conv_fwd, lib.adapt_conv_dgrad, lib.adapt_conv_wgrad):
         f.argtypes = [vp, ConvDesc, vp, Fmt, vp, Fmt, vp, Epilogue]
@@ -208,7 +209,11 @@ class Context:
                "adapt_quantize")
         return out, counters
 
-    def quantize_batched(self, xs, fmts, streams, mode=SR, seed=0, outs=None, counters=None):
+    def quantize_batched(self, xs, fmts, streams, mode=SR, seed=0, outs=None, counters=None, ranges=None,
+                         range_of=None):
+        """One launch for all tensors.  `ranges`: optional float32[2 * len(xs)] device tensor that receives
+        (min, max) of the finite elements of the inputs whose indices are listed in `range_of` (default:
+        all); returns (outs, counters)."""
         torch = self._torch
         n = len(xs)
         if outs is None:
@@ -219,8 +224,13 @@ class Context:
         for t in range(n):
             items[t] = QuantizeItem(xs[t].data_ptr(), outs[t].data_ptr(), xs[t].numel(), fmts[t][0], fmts[t][1],
                                     streams[t])
-        _check(self._lib.adapt_quantize_batched(self._h, items, n, mode, seed, _ptr(counters)),
-               "adapt_quantize_batched")
+        if ranges is None:
+            _check(self._lib.adapt_quantize_batched(self._h, items, n, mode, seed, _ptr(counters)),
+                   "adapt_quantize_batched")
+        else:
+            mask = sum(1 << t for t in (range(n) if range_of is None else range_of))
+            _check(self._lib.adapt_quantize_batched_ranges(self._h, items, n, mode, seed, _ptr(counters), _ptr(ranges), mask),
+                   "adapt_quantize_batched_ranges")
         return outs, counters
 
     # -- contractions -------------------------------------------------------------------------
@@ -298,14 +308,17 @@ class Context:
         return dict(kld=kld, sel=sel, hist=hist, grid=grid)
 
     def kld_precision_search_ranged(self, w, rng_range, wl_lo, wl_hi, il, bins, eps, alpha=-1.0, mode=SR, seed=0,
-                                    stream=0, want_hist=False):
+                                    stream=0, want_hist=False, kld=None, sel=None, grid=None):
         """As kld_precision_search, with the tensor's (min, max) given as a device float32[2]."""
         torch = self._torch
         dev = w.device
         ncand = wl_hi - wl_lo + 1
-        kld = torch.empty(max(ncand, 1), dtype=torch.float64, device=dev)
-        sel = torch.empty(2, dtype=torch.int32, device=dev)
-        grid = torch.empty(3, dtype=torch.int64, device=dev)
+        if kld is None:
+            kld = torch.empty(max(ncand, 1), dtype=torch.float64, device=dev)
+        if sel is None:
+            sel = torch.empty(2, dtype=torch.int32, device=dev)
+        if grid is None:
+            grid = torch.empty(3, dtype=torch.int64, device=dev)
         hist = torch.empty((max(ncand, 0) + 1, bins), dtype=torch.int32, device=dev) if want_hist else None
         _check(self._lib.adapt_kld_precision_search_ranged(self._h, _ptr(w), w.numel(), _ptr(rng_range), wl_lo, wl_hi, il,
                                                            bins, eps, alpha, Rng(mode, seed, stream), _ptr(kld), _ptr(sel),

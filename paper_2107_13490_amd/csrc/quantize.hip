@@ -39,11 +39,12 @@ __device__ __forceinline__ void store8<int16_t>(int16_t *q, const int (&v)[8])
 
 // Converts the elements [0, n) of one tensor; this block handles the groups
 // first_group, first_group + group_stride, ...  Returns the thread's (nnz, sat) counts.
-template <typename OutT>
+// With RANGE, lo / hi also track the smallest and largest finite input value.
+template <typename OutT, bool RANGE = false>
 __device__ __forceinline__ void quantize_span(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n,
                                               const QuantParams p, int mode, uint64_t seed, uint64_t stream,
                                               uint64_t first_group, uint64_t group_stride, uint32_t &nnz,
-                                              uint32_t &nsat)
+                                              uint32_t &nsat, float &lo, float &hi)
 {
     const uint64_t full_groups = n >> 3;
     auto convert = [&](uint64_t g, const float4 &a, const float4 &b) {
@@ -64,6 +65,7 @@ __device__ __forceinline__ void quantize_span(const float *__restrict__ x, OutT 
             c[e] = quantize_one(v[e], r[e], p, s);
             nnz += (c[e] != 0);
             nsat += s;
+            if (RANGE && fabsf(v[e]) < INFINITY) { lo = fminf(lo, v[e]); hi = fmaxf(hi, v[e]); }
         }
         store8<OutT>(q + 8 * g, c);
     };
@@ -85,6 +87,7 @@ __device__ __forceinline__ void quantize_span(const float *__restrict__ x, OutT 
             q[i] = (OutT)c;
             nnz += (c != 0);
             nsat += s;
+            if (RANGE && fabsf(x[i]) < INFINITY) { lo = fminf(lo, x[i]); hi = fmaxf(hi, x[i]); }
         }
     }
 }
@@ -111,8 +114,9 @@ quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, i
     const QuantParams p = make_quant_params(wl, fl);
     uint32_t nnz = 0, nsat = 0;
     // n <= 2^40 (checked by the host): per-thread and per-block counts stay below 2^32
+    float lo = 0.0f, hi = 0.0f;
     quantize_span<OutT>(x, q, n, p, mode, seed, stream, (uint64_t)blockIdx.x * kQThreads + threadIdx.x,
-                        (uint64_t)gridDim.x * kQThreads, nnz, nsat);
+                        (uint64_t)gridDim.x * kQThreads, nnz, nsat, lo, hi);
     if (partial == nullptr) return;
     uint64_t bn, bs;
     block_sum2(nnz, nsat, bn, bs);
@@ -128,9 +132,29 @@ quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, i
 // tensor.
 constexpr int kSumThreads = 1024;
 __global__ void __launch_bounds__(kSumThreads)
-sum_partials_kernel(const uint32_t *__restrict__ partial, int nblocks, int cols, uint64_t *out0, uint64_t *out1)
+sum_partials_kernel(const uint32_t *__restrict__ partial, int nblocks, int cols, uint64_t *out0, uint64_t *out1,
+                    const float *__restrict__ range_partial = nullptr /* [rcols][nblocks]: even columns min, odd max */,
+                    int rcols = 0, float *range_out = nullptr)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    // range columns are taken by the last wavefronts so that they run beside the counter columns
+    for (int j = kSumThreads / kWave - 1 - wave; j < rcols; j += kSumThreads / kWave) {
+        const float *col = range_partial + (size_t)j * nblocks;
+        const bool is_min = (j & 1) == 0;
+        float v = is_min ? INFINITY : -INFINITY;
+        int b = lane;
+        for (; b + 15 * kWave < nblocks; b += 16 * kWave) {        // all loads of a round in flight
+            float t[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) t[u] = col[b + u * kWave];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v = is_min ? fminf(v, t[u]) : fmaxf(v, t[u]);
+        }
+        for (; b < nblocks; b += kWave) v = is_min ? fminf(v, col[b]) : fmaxf(v, col[b]);
+        v = is_min ? wave_min_f32(v) : wave_max_f32(v);
+        if (lane == 0) range_out[j] = v;
+    }
+    if (out0 == nullptr) return;
     for (int j = wave; j < cols; j += kSumThreads / kWave) {
         const uint32_t *col = partial + (size_t)j * nblocks;
         uint64_t sum = 0;
@@ -163,9 +187,11 @@ struct QuantBatch {
 // nnz / saturated of every tensor: per-block partial counts in `partial[2*count][block]`, summed
 // by sum_partials_kernel (no same-address atomics, no zero-fill launch).
 __global__ void __launch_bounds__(kQThreads)
-quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint32_t *partial /* or null */)
+quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint32_t *partial /* or null */,
+                        float *range_partial /* [2*count][gridDim.x] or null */, uint64_t range_mask /* bit t: tensor t */)
 {
     __shared__ uint32_t wave_part[2][kQThreads / kWave];
+    __shared__ float wave_range[2][kQThreads / kWave];
     const int wave = threadIdx.x / kWave;
     // Blocks are dealt to tensors round-robin: tensor t starts at block `rot` so that small
     // tensors do not all land on block 0.
@@ -177,27 +203,53 @@ quantize_batched_kernel(const QuantBatch batch, int mode, uint64_t seed, uint32_
         const uint32_t slot = (blockIdx.x + gridDim.x - rot % gridDim.x) % gridDim.x;
         rot += blocks_needed;
         uint32_t nnz = 0, nsat = 0;
+        float lo = INFINITY, hi = -INFINITY;
         if (slot < blocks_needed) {
             const QuantParams p = make_quant_params(it.wl, it.fl);
             const uint64_t first = (uint64_t)slot * kQThreads + threadIdx.x;
             const uint64_t stride = (uint64_t)blocks_needed * kQThreads;
-            if (it.wl <= 8)
-                quantize_span<int8_t>(it.x, (int8_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat);
-            else
-                quantize_span<int16_t>(it.x, (int16_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat);
+            if (range_partial != nullptr && ((range_mask >> t) & 1)) {
+                if (it.wl <= 8)
+                    quantize_span<int8_t, true>(it.x, (int8_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat, lo, hi);
+                else
+                    quantize_span<int16_t, true>(it.x, (int16_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat, lo, hi);
+            } else {
+                if (it.wl <= 8)
+                    quantize_span<int8_t>(it.x, (int8_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat, lo, hi);
+                else
+                    quantize_span<int16_t>(it.x, (int16_t *)it.q, it.n, p, mode, seed, it.stream, first, stride, nnz, nsat, lo, hi);
+            }
         }
-        if (partial != nullptr) {
-            nnz = wave_sum_u32(nnz);
-            nsat = wave_sum_u32(nsat);
-            if ((threadIdx.x & (kWave - 1)) == 0) { wave_part[0][wave] = nnz; wave_part[1][wave] = nsat; }
+        // one barrier pair per tensor: counters and (for the tensors that asked for it) the range
+        const bool want_range = range_partial != nullptr && ((range_mask >> t) & 1);
+        if (partial != nullptr || want_range) {
+            const bool lead = (threadIdx.x & (kWave - 1)) == 0;
+            if (partial != nullptr) {
+                nnz = wave_sum_u32(nnz);
+                nsat = wave_sum_u32(nsat);
+                if (lead) { wave_part[0][wave] = nnz; wave_part[1][wave] = nsat; }
+            }
+            if (want_range) {
+                lo = wave_min_f32(lo);
+                hi = wave_max_f32(hi);
+                if (lead) { wave_range[0][wave] = lo; wave_range[1][wave] = hi; }
+            }
             __syncthreads();
-            if (threadIdx.x < 2) {
+            if (threadIdx.x < 2 && partial != nullptr) {
                 uint32_t v = 0;
                 for (int w = 0; w < kQThreads / kWave; ++w) v += wave_part[threadIdx.x][w];
                 partial[(size_t)(2 * t + threadIdx.x) * gridDim.x + blockIdx.x] = v;
             }
+            if (threadIdx.x >= kWave && threadIdx.x < kWave + 2 && want_range) {      // a second wavefront: runs beside the first
+                const int m = threadIdx.x - kWave;
+                float v = wave_range[m][0];
+                for (int w = 1; w < kQThreads / kWave; ++w) v = m == 0 ? fminf(v, wave_range[0][w]) : fmaxf(v, wave_range[1][w]);
+                range_partial[(size_t)(2 * t + m) * gridDim.x + blockIdx.x] = v;
+            }
             __syncthreads();
         }
+        if (range_partial != nullptr && !want_range && threadIdx.x < 2)      // not asked for: the neutral pair
+            range_partial[(size_t)(2 * t + threadIdx.x) * gridDim.x + blockIdx.x] = threadIdx.x == 0 ? INFINITY : -INFINITY;
     }
 }
 
@@ -244,9 +296,16 @@ extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fm
 extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item *items, int count, int mode,
                                       uint64_t seed, uint64_t *counters)
 {
+    return adapt_quantize_batched_ranges(ctx, items, count, mode, seed, counters, nullptr, 0);
+}
+
+extern "C" int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantize_item *items, int count, int mode,
+                                             uint64_t seed, uint64_t *counters, float *ranges, uint64_t range_mask)
+{
+    if (ranges && count > 64) return ADAPT_EUNSUPPORTED;      // one mask bit per tensor
     if (!ctx || count < 0 || (count > 0 && !items)) return ADAPT_EINVAL;
     if (mode != ADAPT_SR && mode != ADAPT_RN_HALF_UP) return ADAPT_EINVAL;
-    if (counters && ((uintptr_t)counters & 7)) return ADAPT_EINVAL;
+    if ((counters && ((uintptr_t)counters & 7)) || (ranges && ((uintptr_t)ranges & 3))) return ADAPT_EINVAL;
     for (int t = 0; t < count; ++t) {
         const adapt_quantize_item &it = items[t];
         if (!fmt_ok(adapt_fmt{it.wl, it.fl}) || it.n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
@@ -268,13 +327,16 @@ extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item 
 #endif
         if (grid > cap) grid = cap;
         if (grid == 0) grid = 1;     // still writes the (zero) counters
+        const size_t part_bytes = (grid * 2 * batch.count * sizeof(uint32_t) + 255) & ~(size_t)255;
+        if (2 * part_bytes > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
         uint32_t *partial = counters ? reinterpret_cast<uint32_t *>(scratch(ctx)) : nullptr;
-        if (grid * 2 * batch.count * sizeof(uint32_t) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+        float *range_partial = ranges ? reinterpret_cast<float *>(scratch(ctx) + part_bytes) : nullptr;
         hipLaunchKernelGGL(quantize_batched_kernel, dim3((unsigned)grid), dim3(kQThreads), 0, ctx->stream, batch, mode,
-                           seed, partial);
-        if (counters)
+                           seed, partial, range_partial, range_mask >> base);
+        if (counters || ranges)
             hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kSumThreads), 0, ctx->stream, partial, (int)grid,
-                               2 * batch.count, counters + 2 * base, (uint64_t *)nullptr);
+                               2 * batch.count, counters ? counters + 2 * base : (uint64_t *)nullptr, (uint64_t *)nullptr,
+                               range_partial, ranges ? 2 * batch.count : 0, ranges ? ranges + 2 * base : (float *)nullptr);
     }
     return hip_status(ctx, hipGetLastError());
 }

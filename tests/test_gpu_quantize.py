@@ -114,3 +114,38 @@ def test_invalid_arguments_are_rejected():
         ctx().quantize(x[1:], 8, 4)          # misaligned
     with pytest.raises(pkg.AdaptError):
         ctx().quantize(x, 8, 4, mode=5)
+
+
+def test_batched_ranges_feed_the_precision_search():
+    rng = np.random.default_rng(21)
+    xs = [(rng.standard_normal(n) * sc).astype(np.float32) for n, sc in ((110592, 0.06), (7, 3.0), (40000, 1e-3), (1, 1.0))]
+    xs[0][[5, 77, 1000]] = [np.inf, -np.inf, np.nan]          # non-finite values are left out of the range
+    xs.append(np.full(16, np.nan, dtype=np.float32))           # no finite element: (+inf, -inf)
+    fmts = [(8, 5), (12, 9), (8, 7), (4, 1), (8, 5)]
+    ranges = torch.empty(2 * len(xs), dtype=torch.float32, device="cuda")
+    outs, cnt = ctx().quantize_batched([dev(x) for x in xs], fmts, list(range(1, 6)), pkg.SR, 3, ranges=ranges)
+    got = host(ranges).reshape(-1, 2)
+    for t, x in enumerate(xs):
+        want, nnz, sat = orc.quantize(x, fmts[t][0], fmts[t][1], orc.SR, 3, t + 1)
+        assert np.array_equal(host(outs[t]).astype(np.int64), want)
+        assert u64(cnt)[2 * t:2 * t + 2].tolist() == [nnz, sat]
+        fin = x[np.isfinite(x)]
+        if fin.size:
+            assert (got[t, 0], got[t, 1]) == (fin.min(), fin.max())
+        else:
+            assert got[t, 0] == np.inf and got[t, 1] == -np.inf
+    # the pair of the first tensor drives the search without a range pass
+    res = ctx().kld_precision_search_ranged(dev(xs[0]), ranges[0:2], 4, 16, 3, 2048, 1e-2, stream=2)
+    ref = orc.kld_precision_search(xs[0], 4, 16, 3, 2048, 1e-2, None, orc.SR, 0, 2)
+    assert host(res["sel"]).tolist() == [ref["wl_sel"], ref["fl_sel"]]
+    assert np.allclose(host(res["kld"]), ref["kld"], rtol=1e-5, atol=1e-12)
+    # a mask: only tensor 2 is tracked, the others report (+inf, -inf)
+    ctx().quantize_batched([dev(x) for x in xs], fmts, list(range(1, 6)), pkg.SR, 3, ranges=ranges, range_of=[2])
+    got = host(ranges).reshape(-1, 2)
+    assert (got[2, 0], got[2, 1]) == (xs[2].min(), xs[2].max())
+    assert all(got[t, 0] == np.inf and got[t, 1] == -np.inf for t in (0, 1, 3, 4))
+    # ranges without counters
+    r2 = torch.empty(2, dtype=torch.float32, device="cuda")
+    it = (pkg.binding.QuantizeItem * 1)(pkg.binding.QuantizeItem(dev(xs[2]).data_ptr(), outs[2].data_ptr(), xs[2].size, 8, 7, 3))
+    assert pkg.load_library().adapt_quantize_batched_ranges(ctx().handle, it, 1, pkg.SR, 3, None, r2.data_ptr(), 1) == 0
+    assert host(r2).tolist() == [float(xs[2].min()), float(xs[2].max())]
