@@ -2,7 +2,7 @@
 // distribution of a tensor and of its <WL_c, FL_c> quantizations, for all candidate word
 // lengths in one pass over the tensor.
 //
-// Three launches per search, all on the context's stream, no host round trip (kernel boundaries
+// Three launches per search (per batch of searches in the batched form), all on the context's stream, no host round trip (kernel boundaries
 // order the phases; only the tiny final kernel uses a device-wide fence):
 //   range    per-block min / max of the finite elements.
 //   hist     every block first reduces the range partials and derives the bin grid (power-of-two
@@ -128,12 +128,16 @@ __device__ void make_candidate(KldPlan *plan, int c, int wl_lo, int wl_hi, int i
     plan->cand[c] = k;
 }
 
+// Position of a block inside the (sub-)grid of one tensor's search: the single-tensor kernels take
+// it from blockIdx / gridDim, the batched kernels from the batch table.
+struct BlockGeo { unsigned bx, by, gx, gy; };
+
 // ---- kernel 1: per-block range of the finite elements -----------------------------------------------
-__global__ void __launch_bounds__(kRangeThreads)
-kld_range_kernel(const float *__restrict__ w, uint64_t n, float *partial /* [2*gridDim.x] */)
+__device__ __forceinline__ void kld_range_body(const float *__restrict__ w, uint64_t n, float *partial /* [2*gx] */,
+                                               const BlockGeo geo)
 {
-    const uint64_t tid = (uint64_t)blockIdx.x * kRangeThreads + threadIdx.x;
-    const uint64_t nthreads = (uint64_t)gridDim.x * kRangeThreads;
+    const uint64_t tid = (uint64_t)geo.bx * kRangeThreads + threadIdx.x;
+    const uint64_t nthreads = (uint64_t)geo.gx * kRangeThreads;
     float lo = INFINITY, hi = -INFINITY;
     const uint64_t n4 = n >> 2;
     for (uint64_t i = tid; i < n4; i += nthreads) {
@@ -153,9 +157,15 @@ kld_range_kernel(const float *__restrict__ w, uint64_t n, float *partial /* [2*g
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 1; i < kRangeThreads / kWave; ++i) { lo = fminf(lo, slo[i]); hi = fmaxf(hi, shi[i]); }
-        partial[2 * blockIdx.x] = lo;
-        partial[2 * blockIdx.x + 1] = hi;
+        partial[2 * geo.bx] = lo;
+        partial[2 * geo.bx + 1] = hi;
     }
+}
+
+__global__ void __launch_bounds__(kRangeThreads)
+kld_range_kernel(const float *__restrict__ w, uint64_t n, float *partial /* [2*gridDim.x] */)
+{
+    kld_range_body(w, n, partial, BlockGeo{blockIdx.x, 0, gridDim.x, 1});
 }
 
 // ---- kernel 2: plan + histograms ------------------------------------------------------------------------
@@ -230,14 +240,14 @@ __global__ void zero_words_kernel(uint32_t *p, size_t n)
 // slower than that on this GPU.  USE_LDS = false (bins too large for LDS) counts with atomics
 // straight into the block's slab, which the host has cleared.
 template <bool USE_LDS>
-__global__ void __launch_bounds__(kHistMaxThreads)
-kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial, int range_blocks,
-                int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *slabs, int total_rows,
-                int rows_per_group, int mode, uint64_t seed, uint64_t stream)
+__device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial,
+                                              int range_blocks, int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out,
+                                              uint32_t *slabs, int total_rows, int rows_per_group, int mode, uint64_t seed,
+                                              uint64_t stream, const BlockGeo geo)
 {
-    // blockIdx.y selects a group of histogram rows: small tensors are spread over more CUs by
+    // geo.by selects a group of histogram rows: small tensors are spread over more CUs by
     // letting several blocks count different candidates of the same elements
-    const int row0 = blockIdx.y * rows_per_group;
+    const int row0 = geo.by * rows_per_group;
     const int rows = min(rows_per_group, total_rows - row0);
     extern __shared__ uint32_t lds[];
     __shared__ KldPlan plan;
@@ -272,7 +282,7 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
         __syncthreads();
         if (!plan.degenerate && (int)threadIdx.x < ncand) make_candidate(&plan, threadIdx.x, wl_lo, wl_hi, il);
         __syncthreads();
-        if (blockIdx.x == 0 && blockIdx.y == 0)
+        if (geo.bx == 0 && geo.by == 0)
             for (int i = threadIdx.x; i < (int)(sizeof(KldPlan) / 4); i += nthreads)
                 reinterpret_cast<uint32_t *>(plan_out)[i] = reinterpret_cast<const uint32_t *>(&plan)[i];
     }
@@ -303,7 +313,7 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
         row_stride = nb;
     } else {
         if ((int)threadIdx.x >= c_begin && (int)threadIdx.x < c_end) priv_off[threadIdx.x] = -1;
-        hist = slabs + ((size_t)blockIdx.x * total_rows + row0) * bins;
+        hist = slabs + ((size_t)geo.bx * total_rows + row0) * bins;
         row_stride = bins;
     }
     if ((int)threadIdx.x >= c_begin && (int)threadIdx.x < c_end)
@@ -330,8 +340,8 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
     };
 
     const uint64_t full_groups = n >> 3;
-    const uint64_t first = (uint64_t)blockIdx.x * nthreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * nthreads;
+    const uint64_t first = (uint64_t)geo.bx * nthreads + threadIdx.x;
+    const uint64_t stride = (uint64_t)geo.gx * nthreads;
     for (uint64_t g = first; g < full_groups; g += stride) {
         const float4 a = reinterpret_cast<const float4 *>(w)[2 * g];
         const float4 b = reinterpret_cast<const float4 *>(w)[2 * g + 1];
@@ -379,7 +389,7 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
         // slab rows are 16-byte aligned when bins % 4 == 0; otherwise every counter is written singly
         const int nb4 = (bins % 4 == 0) ? nb / 4 : 0;
         for (int row = 0; row < rows; ++row) {
-            uint32_t *dst = slabs + ((size_t)blockIdx.x * total_rows + row0 + row) * bins;
+            uint32_t *dst = slabs + ((size_t)geo.bx * total_rows + row0 + row) * bins;
             const uint32_t *src = lds + row * nb;
             for (int q = threadIdx.x; q < nb4; q += nthreads)
                 reinterpret_cast<uint4 *>(dst)[q] = make_uint4(src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]);
@@ -387,6 +397,16 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
         }
     }
     ADAPT_STAMP(5);
+}
+
+template <bool USE_LDS>
+__global__ void __launch_bounds__(kHistMaxThreads)
+kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial, int range_blocks,
+                int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *slabs, int total_rows,
+                int rows_per_group, int mode, uint64_t seed, uint64_t stream)
+{
+    kld_hist_body<USE_LDS>(w, n, range_partial, range_blocks, wl_lo, wl_hi, il, bins, plan_out, slabs, total_rows,
+                           rows_per_group, mode, seed, stream, BlockGeo{blockIdx.x, blockIdx.y, gridDim.x, gridDim.y});
 }
 
 // ---- kernel 3: slab sums and partial KL sums ------------------------------------------------------------------
@@ -400,17 +420,17 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
 constexpr int kChunk = 256;
 constexpr int kFinalGroups = 4;
 
-__global__ void __launch_bounds__(kChunk * kFinalGroups)
-kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs, int rows, int bins,
-                 double alpha_in, double *part, uint32_t *hist_out, int wl_lo, int il, double eps, double *kld, int32_t *sel,
-                 long long *grid_out, uint32_t *ticket)
+__device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs,
+                                               int rows, int bins, double alpha_in, double *part, uint32_t *hist_out, int wl_lo,
+                                               int il, double eps, double *kld, int32_t *sel, long long *grid_out,
+                                               uint32_t *ticket, const BlockGeo geo)
 {
     __shared__ uint32_t cq_s[kFinalGroups][kChunk], cp_s[kFinalGroups][kChunk];
     __shared__ double red[2][kChunk];
     ADAPT_STAMP_WG4(0);
-    const int c = blockIdx.y, nchunks = gridDim.x;
+    const int c = geo.by, nchunks = geo.gx;
     const int lane = threadIdx.x % kChunk, grp = threadIdx.x / kChunk;
-    const int b = blockIdx.x * kChunk + lane;
+    const int b = geo.bx * kChunk + lane;
     const int nb = plan->degenerate ? 0 : plan->nb;
     const size_t slab_words = (size_t)rows * bins;
     uint32_t uq = 0, up = 0;
@@ -460,19 +480,19 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
         if (lead && lane < off) { red[0][lane] += red[0][lane + off]; red[1][lane] += red[1][lane + off]; }
     }
     if (lead && lane == 0) {
-        part[2 * ((size_t)c * nchunks + blockIdx.x)] = red[0][0];
-        part[2 * ((size_t)c * nchunks + blockIdx.x) + 1] = red[1][0];
+        part[2 * ((size_t)c * nchunks + geo.bx)] = red[0][0];
+        part[2 * ((size_t)c * nchunks + geo.bx) + 1] = red[1][0];
     }
     // the last block to finish adds the partial sums in a fixed order and selects
     __shared__ bool last;
     ADAPT_STAMP_WG4(1);
     if (threadIdx.x == 0)      // release this block's partial sums, acquire everyone else's
-        last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x * gridDim.y - 1;
+        last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == geo.gx * geo.gy - 1;
     __syncthreads();
     ADAPT_STAMP_WG4(2);
     if (!last) return;
     __shared__ double kl_s[kMaxCand];
-    const int ncand = gridDim.y;
+    const int ncand = geo.gy;
     // all partial sums are loaded at once (one pair per thread), then added in a fixed order
     double *tail = &red[0][0];
     const int npart = 2 * ncand * nchunks;
@@ -514,6 +534,73 @@ kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ 
     }
     *ticket = 0;      // ready for the next search on this context
     ADAPT_STAMP_WG4(3);
+}
+
+__global__ void __launch_bounds__(kChunk * kFinalGroups)
+kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs, int rows, int bins,
+                 double alpha_in, double *part, uint32_t *hist_out, int wl_lo, int il, double eps, double *kld, int32_t *sel,
+                 long long *grid_out, uint32_t *ticket)
+{
+    kld_final_body(plan, slabs, nslabs, rows, bins, alpha_in, part, hist_out, wl_lo, il, eps, kld, sel, grid_out, ticket,
+                   BlockGeo{blockIdx.x, blockIdx.y, gridDim.x, gridDim.y});
+}
+
+// ---- batched form: the three phases of up to kKldBatchMax searches, one launch per phase --------------------
+constexpr int kKldBatchMax = 24;
+struct KldBatchItem {
+    const float *w;
+    uint64_t n, stream;
+    double *kld;
+    int32_t *sel;
+    unsigned long long off_plan, off_range, off_klpart, off_slabs;      // byte offsets into the scratch
+    int il, bins, range_blocks, hist_x, groups, rows_per_group, nchunks;
+};
+struct KldBatch {
+    KldBatchItem item[kKldBatchMax];
+    // first block of each tensor in the three launches (ascending)
+    unsigned first_range[kKldBatchMax], first_hist[kKldBatchMax], first_final[kKldBatchMax];
+    int count, wl_lo, wl_hi, mode;
+    unsigned long long seed;
+    double eps, alpha;
+    char *ws;
+    uint32_t *tickets;
+};
+
+// the tensor a block belongs to: every lane compares one table entry, the wavefront votes
+#define ADAPT_KLD_FIND(field)                                                                             \
+    const int lane_ = threadIdx.x & (kWave - 1);                                                          \
+    const unsigned first_ = lane_ < b.count ? b.field[lane_ < kKldBatchMax ? lane_ : 0] : 0xffffffffu;    \
+    const int t = __popcll(__ballot(blockIdx.x >= first_)) - 1;                                           \
+    const KldBatchItem &it = b.item[t];                                                                   \
+    const unsigned l = blockIdx.x - b.field[t]
+
+__global__ void __launch_bounds__(kRangeThreads)
+kld_range_batched_kernel(const KldBatch b)
+{
+    ADAPT_KLD_FIND(first_range);
+    kld_range_body(it.w, it.n, reinterpret_cast<float *>(b.ws + it.off_range), BlockGeo{l, 0, (unsigned)it.range_blocks, 1});
+}
+
+__global__ void __launch_bounds__(kHistMaxThreads)
+kld_hist_batched_kernel(const KldBatch b)
+{
+    ADAPT_KLD_FIND(first_hist);
+    const int rows = b.wl_hi - b.wl_lo + 2;
+    kld_hist_body<true>(it.w, it.n, reinterpret_cast<const float *>(b.ws + it.off_range), it.range_blocks, b.wl_lo, b.wl_hi,
+                        it.il, it.bins, reinterpret_cast<KldPlan *>(b.ws + it.off_plan),
+                        reinterpret_cast<uint32_t *>(b.ws + it.off_slabs), rows, it.rows_per_group, b.mode, b.seed, it.stream,
+                        BlockGeo{l % (unsigned)it.hist_x, l / (unsigned)it.hist_x, (unsigned)it.hist_x, (unsigned)it.groups});
+}
+
+__global__ void __launch_bounds__(kChunk * kFinalGroups)
+kld_final_batched_kernel(const KldBatch b)
+{
+    ADAPT_KLD_FIND(first_final);
+    const int ncand = b.wl_hi - b.wl_lo + 1;
+    kld_final_body(reinterpret_cast<const KldPlan *>(b.ws + it.off_plan), reinterpret_cast<const uint32_t *>(b.ws + it.off_slabs),
+                   it.hist_x, ncand + 1, it.bins, b.alpha, reinterpret_cast<double *>(b.ws + it.off_klpart), nullptr, b.wl_lo,
+                   it.il, b.eps, it.kld, it.sel, nullptr, b.tickets + t,
+                   BlockGeo{l % (unsigned)it.nchunks, l / (unsigned)it.nchunks, (unsigned)it.nchunks, (unsigned)ncand});
 }
 
 static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int wl_hi, int il, int bins, double eps,
@@ -586,9 +673,88 @@ static int check_search_args(int wl_lo, int wl_hi, int il, int bins, double eps,
 
 static hipError_t allow_big_lds()
 {
-    static hipError_t done = hipFuncSetAttribute(reinterpret_cast<const void *>(&kld_hist_kernel<true>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+    static hipError_t done = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&kld_hist_kernel<true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&kld_hist_batched_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+        return e;
+    }();
     return done;
+}
+
+// Searches on items[0 .. count): consecutive tensors are packed into batches (at most kKldBatchMax
+// tensors, as many as the workspace holds) that run their three phases in one launch each; a tensor
+// whose histogram rows do not fit LDS takes the single-tensor path.
+static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, int wl_lo, int wl_hi, double eps,
+                        double alpha, int mode, uint64_t seed, double *kld, int32_t *sel)
+{
+    const int ncand = wl_hi - wl_lo + 1, rows = ncand + 1;
+    auto a256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    int t0 = 0;
+    while (t0 < count) {
+        const size_t per_row0 = (size_t)items[t0].bins * 4 + kPrivWords * 4;
+        if (per_row0 + 16 > kLdsBudget) {
+            const int st = search_one(ctx, items[t0].w, items[t0].n, wl_lo, wl_hi, items[t0].il, items[t0].bins, eps, alpha, mode,
+                                      seed, items[t0].stream, kld + (size_t)t0 * ncand, sel + 2 * t0, nullptr, nullptr);
+            if (st != ADAPT_OK) return st;
+            ++t0;
+            continue;
+        }
+        // block size of the histogram launch: large blocks when the batch holds a large tensor
+        int threads = 512;
+        for (int m = 0; m < kKldBatchMax && t0 + m < count; ++m)
+            if (items[t0 + m].n >= ((uint64_t)1 << 20)) threads = 1024;
+        KldBatch b;
+        b.count = 0; b.wl_lo = wl_lo; b.wl_hi = wl_hi; b.mode = mode; b.seed = seed; b.eps = eps; b.alpha = alpha;
+        b.ws = scratch(ctx);
+        b.tickets = ticket(ctx, 16);
+        size_t off = 0, lds_max = 0;
+        unsigned nr = 0, nh = 0, nf = 0;
+        while (b.count < kKldBatchMax && t0 + b.count < count) {
+            const adapt_kld_item &src = items[t0 + b.count];
+            const size_t row_bytes = (size_t)src.bins * 4, per_row = row_bytes + kPrivWords * 4;
+            if (per_row + 16 > kLdsBudget) break;
+            KldBatchItem it;
+            it.w = src.w; it.n = src.n; it.stream = src.stream; it.il = src.il; it.bins = src.bins;
+            it.kld = kld + (size_t)(t0 + b.count) * ncand;
+            it.sel = sel + 2 * (t0 + b.count);
+            const uint64_t per_block = (uint64_t)threads * 8;
+            it.hist_x = (int)std::min<uint64_t>((uint64_t)ctx->num_cu, std::max<uint64_t>(1, (src.n + per_block - 1) / per_block));
+            it.range_blocks = (int)std::min<uint64_t>((uint64_t)ctx->num_cu * 4, std::max<uint64_t>(1, (src.n / 4 + kRangeThreads - 1) / kRangeThreads));
+            it.nchunks = (src.bins + kChunk - 1) / kChunk;
+            int rpg = (int)std::min<size_t>(rows, kLdsBudget / per_row);
+            const int want_groups = std::max(1, (2 * ctx->num_cu + it.hist_x - 1) / it.hist_x);
+            rpg = std::max(1, std::min(rpg, (rows + want_groups - 1) / want_groups));
+            it.rows_per_group = rpg;
+            it.groups = (rows + rpg - 1) / rpg;
+            const size_t need = a256(sizeof(KldPlan)) + a256((size_t)it.range_blocks * 8) + a256((size_t)ncand * it.nchunks * 16) +
+                                a256((size_t)it.hist_x * rows * src.bins * 4);
+            if (off + need > scratch_bytes(ctx)) {
+                if (b.count == 0) return ADAPT_EWORKSPACE;
+                break;
+            }
+            it.off_plan = off;
+            it.off_range = it.off_plan + a256(sizeof(KldPlan));
+            it.off_klpart = it.off_range + a256((size_t)it.range_blocks * 8);
+            it.off_slabs = it.off_klpart + a256((size_t)ncand * it.nchunks * 16);
+            off += need;
+            b.first_range[b.count] = nr; b.first_hist[b.count] = nh; b.first_final[b.count] = nf;
+            nr += (unsigned)it.range_blocks;
+            nh += (unsigned)(it.hist_x * it.groups);
+            nf += (unsigned)(it.nchunks * ncand);
+            lds_max = std::max(lds_max, (size_t)rpg * per_row + 16);
+            b.item[b.count++] = it;
+        }
+        for (int i = b.count; i < kKldBatchMax; ++i) { b.first_range[i] = b.first_hist[i] = b.first_final[i] = 0xffffffffu; }
+        hipLaunchKernelGGL(kld_range_batched_kernel, dim3(nr), dim3(kRangeThreads), 0, ctx->stream, b);
+        hipLaunchKernelGGL(kld_hist_batched_kernel, dim3(nh), dim3(threads), lds_max, ctx->stream, b);
+        hipLaunchKernelGGL(kld_final_batched_kernel, dim3(nf), dim3(kChunk * kFinalGroups), 0, ctx->stream, b);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return hip_status(ctx, e);
+        t0 += b.count;
+    }
+    return ADAPT_OK;
 }
 
 }  // namespace adapt
@@ -635,11 +801,5 @@ extern "C" int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kl
         if (items[t].n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     }
     if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
-    const int ncand = wl_hi - wl_lo + 1;
-    for (int t = 0; t < count; ++t) {
-        const int s = search_one(ctx, items[t].w, items[t].n, wl_lo, wl_hi, items[t].il, items[t].bins, eps, alpha, mode,
-                                 seed, items[t].stream, kld + (size_t)t * ncand, sel + 2 * t, nullptr, nullptr);
-        if (s != ADAPT_OK) return s;
-    }
-    return ADAPT_OK;
+    return search_batch(ctx, items, count, wl_lo, wl_hi, eps, alpha, mode, seed, kld, sel);
 }

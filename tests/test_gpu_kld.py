@@ -127,6 +127,32 @@ def test_batched():
         assert sel[t].tolist() == [ref["wl_sel"], ref["fl_sel"]]
 
 
+def test_batched_many_tensors_mixed_sizes():
+    # more tensors than one batch holds, a large tensor (1024-thread blocks), one whose rows do not fit LDS
+    # (single-tensor path in the middle of the list), constant and empty tensors; run twice (tickets reset)
+    g = np.random.default_rng(10)
+    sizes = [300, 4097, 36864, 147456, 1, 8, 0, 2 ** 20 + 3, 9000, 110592] + [1000 + 37 * i for i in range(22)]
+    ws = [(g.standard_normal(n) * (0.02 + 0.01 * (i % 5))).astype(np.float32) for i, n in enumerate(sizes)]
+    ws[4][:] = 0.25                                   # a single value: degenerate
+    ws[8][::7] = np.nan
+    bins = [2048] * len(ws)
+    bins[2] = 50000                                   # too wide for LDS
+    bins[5] = 16
+    ils = [3] * len(ws)
+    streams = list(range(2, 2 + len(ws)))
+    devs = [dev(w) if w.size else torch.empty(0, device="cuda") for w in ws]
+    refs = [orc.kld_precision_search(w, 4, 16, ils[t], bins[t], 1e-2, None, pkg.SR, 0, streams[t]) for t, w in enumerate(ws)]
+    for rep in range(2):
+        kld, sel = ctx().kld_precision_search_batched(devs, ils, bins, streams, 4, 16, 1e-2)
+        kld, sel = host(kld), host(sel)
+        for t, ref in enumerate(refs):
+            assert (np.abs(kld[t] - ref["kld"]) <= 1e-5 * np.abs(ref["kld"]) + 1e-12).all(), t
+            assert sel[t].tolist() == [ref["wl_sel"], ref["fl_sel"]], t
+    # and the batched results equal the single-tensor entry point's bit for bit
+    one = ctx().kld_precision_search(devs[9], 4, 16, 3, 2048, 1e-2, stream=streams[9])
+    assert np.array_equal(host(one["kld"]), kld[9])
+
+
 def test_invalid_arguments():
     w = torch.zeros(64, dtype=torch.float32, device="cuda")
     for args in ((1, 8, 2, 100), (4, 17, 2, 100), (8, 4, 2, 100), (4, 8, 5, 100), (4, 8, 2, 1), (4, 8, 2, 70000),
