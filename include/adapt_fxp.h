@@ -282,6 +282,29 @@ int adapt_lookback_next(int lb, double ds, int lb_lwr, int lb_upr, double gamma)
  * [r_lwr, r_upr]; r unchanged otherwise. */
 int adapt_resolution_next(int r, int lb, int lb_lwr, int lb_upr, int r_lwr, int r_upr);
 
+/* ---- the paper's performance model (Sec. 4.1 "Performance Model") --------------------------- */
+
+/* One layer at one training step: ops = multiply-adds of a forward pass, sp = fraction of
+ * non-zero weights (nnz / numel as adapt_quantize reports it), wl = its word length, numel = its
+ * number of weights, lookback and resolution as the switch controller holds them.  Host functions;
+ * NaN for arguments out of range. */
+typedef struct { double ops, sp, numel; int wl, lookback, resolution; } adapt_perf_layer;
+/* Bound on the operations of one PushDown: 2 log2(32 - 8) r 3 numel. */
+double adapt_perf_pushdown_ops(int resolution, double numel);
+/* Bound on the operations of one PushUp: (lb + 1) numel + 1. */
+double adapt_perf_pushup_ops(int lookback, double numel);
+/* One step's term of the training-cost bound: sum_l ops_l (sp_l WL_l + 32 / accs) (quantized
+ * sparse forward pass, 32-bit dense backward pass, accs gradient-accumulation steps). */
+double adapt_perf_step_cost(const adapt_perf_layer *layers, int count, int accs);
+/* One step's term of the overhead bound: sum_l 32 (sp_l pd_l + pu_l) / (accs lb_l). */
+double adapt_perf_step_overhead(const adapt_perf_layer *layers, int count, int accs);
+/* sz = sum_l sp_l WL_l (taken at the last step), and one step's term of mem = mean over steps of
+ * sum_l (sp_l WL_l + 32). */
+double adapt_perf_model_size(const adapt_perf_layer *layers, int count);
+double adapt_perf_step_memory(const adapt_perf_layer *layers, int count);
+/* SU = bs_other costs_other / (bs_ours costs_ours). */
+double adapt_perf_speedup(double bs_other, double costs_other, double bs_ours, double costs_ours);
+
 #ifdef __cplusplus
 }
 #endif

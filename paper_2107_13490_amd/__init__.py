@@ -6,5 +6,6 @@ memory and streams.  There is no CPU fallback: if the library is missing, loadin
 """
 from .binding import (  # noqa: F401
     RN_HALF_UP, SR, ST_MAX, ST_MEAN, ST_MIN, AdaptError, Context, ConvDesc, Epilogue, Fmt, Rng, acc_bits,
-    library_path, load_library, lookback_next, pushup_suggest, resolution_next, strategy_next,
+    library_path, load_library, lookback_next, perf_model_size, perf_step_cost, perf_step_memory, perf_step_overhead,
+    pushup_suggest, resolution_next, strategy_next,
 )

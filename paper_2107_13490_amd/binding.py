@@ -74,6 +74,11 @@ class SgdParams(C.Structure):
     _fields_ = [("lr", C.c_double), ("l1", C.c_double), ("l2", C.c_double)]
 
 
+class PerfLayer(C.Structure):
+    _fields_ = [("ops", C.c_double), ("sp", C.c_double), ("numel", C.c_double), ("wl", C.c_int), ("lookback", C.c_int),
+                ("resolution", C.c_int)]
+
+
 class PushupResult(C.Structure):
     _fields_ = [("wl", C.c_int), ("fl", C.c_int), ("s1", C.c_int), ("s2", C.c_int), ("s", C.c_int)]
 
@@ -112,6 +117,16 @@ def load_library():
     lib.adapt_kld_precision_search_batched.argtypes = [vp, C.POINTER(KldItem), i, i, i, dbl, dbl, i, u64, vp, vp]
     lib.adapt_kld_precision_search_ranged.argtypes = [vp, vp, sz, vp, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
     lib.adapt_sgd_update_quantize.argtypes = [vp, vp, sz, vp, Fmt, vp, SgdParams, Fmt, Rng, vp, vp, vp]
+    lib.adapt_perf_pushdown_ops.argtypes = [i, dbl]
+    lib.adapt_perf_pushup_ops.argtypes = [i, dbl]
+    lib.adapt_perf_speedup.argtypes = [dbl, dbl, dbl, dbl]
+    for f in (lib.adapt_perf_step_cost, lib.adapt_perf_step_overhead):
+        f.argtypes = [C.POINTER(PerfLayer), i, i]
+    for f in (lib.adapt_perf_model_size, lib.adapt_perf_step_memory):
+        f.argtypes = [C.POINTER(PerfLayer), i]
+    for f in (lib.adapt_perf_pushdown_ops, lib.adapt_perf_pushup_ops, lib.adapt_perf_speedup, lib.adapt_perf_step_cost,
+              lib.adapt_perf_step_overhead, lib.adapt_perf_model_size, lib.adapt_perf_step_memory):
+        f.restype = dbl
     lib.adapt_gradient_diversity.argtypes = [vp, C.POINTER(GradItem), i, sz, vp, vp]
     lib.adapt_pushup_suggest.argtypes = [dbl, i, i, i, i, i, C.POINTER(PushupResult)]
     lib.adapt_strategy_next.argtypes = [i, dbl, dbl]
@@ -144,6 +159,36 @@ def lookback_next(lb: int, ds: float, lb_lwr: int, lb_upr: int, gamma: float) ->
 
 def resolution_next(r: int, lb: int, lb_lwr: int, lb_upr: int, r_lwr: int, r_upr: int) -> int:
     return load_library().adapt_resolution_next(r, lb, lb_lwr, lb_upr, r_lwr, r_upr)
+
+
+# -- the paper's performance model (host functions of the library) ------------------------------
+def perf_layers(rows):
+    """rows: iterable of (ops, sp, numel, wl, lookback, resolution) -> ctypes array for the perf_* calls."""
+    rows = list(rows)
+    arr = (PerfLayer * max(len(rows), 1))()
+    for k, r in enumerate(rows):
+        arr[k] = PerfLayer(*r)
+    return arr, len(rows)
+
+
+def perf_step_cost(rows, accs=1):
+    arr, n = perf_layers(rows)
+    return load_library().adapt_perf_step_cost(arr, n, accs)
+
+
+def perf_step_overhead(rows, accs=1):
+    arr, n = perf_layers(rows)
+    return load_library().adapt_perf_step_overhead(arr, n, accs)
+
+
+def perf_model_size(rows):
+    arr, n = perf_layers(rows)
+    return load_library().adapt_perf_model_size(arr, n)
+
+
+def perf_step_memory(rows):
+    arr, n = perf_layers(rows)
+    return load_library().adapt_perf_step_memory(arr, n)
 
 
 def _ptr(t):
