@@ -1,14 +1,15 @@
 // C entry point of a layer's backward pass: data gradient and weight gradient of one convolution
 // (Alg. 1, the backward-pass line, per layer).  Results are exactly those of adapt_conv_dgrad and
-// adapt_conv_wgrad; when both contractions take the one-limb vector path with 192-deep stages
-// they run as one launch.
+// adapt_conv_wgrad; when both contractions take a vector path with matching tiles (one limb:
+// 192-deep stages; two limbs: int16 operands, equal square tiles) they run as one launch.
 #include "contract_pair.hpp"
 
 using namespace adapt;
 
 static bool pairable(const ContractPlan &p, bool is_dgrad)
 {
-    if (p.empty || p.limbs != 1 || p.tile.bkt != 192) return false;
+    if (p.empty || p.tile.bkt != (p.limbs == 1 ? 192 : 64)) return false;
+    if (p.limbs == 2 && (p.kern.act_es != 2 || p.kern.wgt_es != 2)) return false;      // mixed storage: not paired
     if (is_dgrad) {
         if (p.splits != 1 || p.kern.act_load != LOAD_VEC || p.kern.wgt_load != LOAD_ROWS) return false;
     } else {
@@ -34,7 +35,7 @@ extern "C" int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void
     if (int s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0, pw)) return s;
     hipError_t e = hipSuccess;
     bool paired = false;
-    if (pairable(pd, true) && pairable(pw, false)) {
+    if (pairable(pd, true) && pairable(pw, false) && pd.limbs == pw.limbs) {
         if (pd.tile.bm == 64 && pd.tile.bn == 64) e = launch_pair_d64x64(ctx, pd, pw, &paired);
         else if (pd.tile.bm == 128 && pd.tile.bn == 64) e = launch_pair_d128x64(ctx, pd, pw, &paired);
         else if (pd.tile.bm == 64 && pd.tile.bn == 128) e = launch_pair_d64x128(ctx, pd, pw, &paired);

@@ -798,17 +798,19 @@ contract_kernel(const ContractArgs a)
 
 // Two independent contractions in one launch (the two gradients of a layer): blocks [0, n_first)
 // run the first, the rest the second, so that each fills the CUs the other leaves idle and one
-// launch floor is paid instead of two.  One-limb, 192-deep stages, int8 operands.
-template <int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB>
+// launch floor is paid instead of two.  Both have the same number of limbs, element size (LIMBS
+// bytes) and stage depth.
+template <int LIMBS, int BKT, int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB>
 __global__ void __launch_bounds__(kThreads)
 contract_pair_kernel(const ContractArgs a, const ContractArgs b, const unsigned n_first, const unsigned tiles_a,
                      const unsigned tiles_b)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     if (blockIdx.x < n_first)
-        contract_body<OPA, 1, AMA, WMA, 1, 1, BMA, BNA, 2, 2, 192, 1>(a, blockIdx.x, n_first, tiles_a, smem);
+        contract_body<OPA, LIMBS, AMA, WMA, LIMBS, LIMBS, BMA, BNA, 2, 2, BKT, 1>(a, blockIdx.x, n_first, tiles_a, smem);
     else
-        contract_body<OPB, 1, AMB, WMB, 1, 1, BMB, BNB, 2, 2, 192, 1>(b, blockIdx.x - n_first, gridDim.x - n_first, tiles_b, smem);
+        contract_body<OPB, LIMBS, AMB, WMB, LIMBS, LIMBS, BMB, BNB, 2, 2, BKT, 1>(b, blockIdx.x - n_first, gridDim.x - n_first,
+                                                                                 tiles_b, smem);
 }
 
 // ---- helper: split-K finish ---------------------------------------------------------------------------

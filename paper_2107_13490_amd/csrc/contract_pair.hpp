@@ -5,15 +5,15 @@
 
 namespace adapt {
 
-template <int DBM, int DBN, int WBM, int WBN>
+template <int LIMBS, int BKT, int DBM, int DBN, int WBM, int WBN>
 static hipError_t launch_pair(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w)
 {
-    typedef typename LoaderSelect<OP_DGRAD, true, LOAD_VEC, DBM, 1, 192, 1>::type DA;
-    typedef typename LoaderSelect<OP_DGRAD, false, LOAD_ROWS, DBN, 1, 192, 1>::type DB;
-    typedef typename LoaderSelect<OP_WGRAD, true, LOAD_ROWS, WBM, 1, 192, 1>::type WA;
-    typedef typename LoaderSelect<OP_WGRAD, false, LOAD_ROWS, WBN, 1, 192, 1>::type WB;
-    const size_t lds = std::max<size_t>(DA::TILE_BYTES + DB::TILE_BYTES, WA::TILE_BYTES + WB::TILE_BYTES);
-    auto kern = contract_pair_kernel<OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
+    typedef typename LoaderSelect<OP_DGRAD, true, LOAD_VEC, DBM, LIMBS, BKT, LIMBS>::type DA;
+    typedef typename LoaderSelect<OP_DGRAD, false, LOAD_ROWS, DBN, LIMBS, BKT, LIMBS>::type DB;
+    typedef typename LoaderSelect<OP_WGRAD, true, LOAD_ROWS, WBM, LIMBS, BKT, LIMBS>::type WA;
+    typedef typename LoaderSelect<OP_WGRAD, false, LOAD_ROWS, WBN, LIMBS, BKT, LIMBS>::type WB;
+    const size_t lds = std::max<size_t>(DA::TILE_BYTES + DB::TILE_BYTES, WA::TILE_BYTES + WB::TILE_BYTES) * LIMBS;
+    auto kern = contract_pair_kernel<LIMBS, BKT, OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
     static bool attr_done = false;
     if (!attr_done && lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -27,15 +27,23 @@ static hipError_t launch_pair(adapt_ctx *ctx, const ContractPlan &d, const Contr
     return hipGetLastError();
 }
 
-// dispatch on the weight-gradient tile; *done stays false when the tile has no paired kernel
+// dispatch on the weight-gradient tile; *done stays false when the tile has no paired kernel.  Two-limb
+// pairs exist for equal square tiles only (a 128-wide two-limb tile allows one block per CU, which
+// would also hold back a 64-wide partner).
 template <int DBM, int DBN>
 static hipError_t launch_pair_for(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w, bool *done)
 {
     *done = true;
-    if (w.tile.bm == 64 && w.tile.bn == 64) return launch_pair<DBM, DBN, 64, 64>(ctx, d, w);
-    if (w.tile.bm == 128 && w.tile.bn == 64) return launch_pair<DBM, DBN, 128, 64>(ctx, d, w);
-    if (w.tile.bm == 64 && w.tile.bn == 128) return launch_pair<DBM, DBN, 64, 128>(ctx, d, w);
-    if (w.tile.bm == 128 && w.tile.bn == 128) return launch_pair<DBM, DBN, 128, 128>(ctx, d, w);
+    if (d.limbs == 2) {
+        if constexpr (DBM == DBN)
+            if (w.tile.bm == DBM && w.tile.bn == DBN) return launch_pair<2, 64, DBM, DBN, DBM, DBN>(ctx, d, w);
+        *done = false;
+        return hipSuccess;
+    }
+    if (w.tile.bm == 64 && w.tile.bn == 64) return launch_pair<1, 192, DBM, DBN, 64, 64>(ctx, d, w);
+    if (w.tile.bm == 128 && w.tile.bn == 64) return launch_pair<1, 192, DBM, DBN, 128, 64>(ctx, d, w);
+    if (w.tile.bm == 64 && w.tile.bn == 128) return launch_pair<1, 192, DBM, DBN, 64, 128>(ctx, d, w);
+    if (w.tile.bm == 128 && w.tile.bn == 128) return launch_pair<1, 192, DBM, DBN, 128, 128>(ctx, d, w);
     *done = false;
     return hipSuccess;
 }

@@ -308,7 +308,9 @@ def test_config5_resnet18_layer_sweep_reduced_batch():
     ((5, 9, 7, 32, 48, 3, 3, 1, 1), 8),         # ragged tiles
     ((4, 8, 8, 256, 512, 1, 1, 2, 0), 4),       # 1x1 projection (64-deep stages: not paired)
     ((3, 12, 12, 3, 64, 3, 3, 1, 1), 8),        # 3 input channels: element-wise path, not paired
-    ((4, 16, 16, 64, 64, 3, 3, 1, 1), 12),      # two limbs: not paired
+    ((4, 16, 16, 64, 64, 3, 3, 1, 1), 12),      # two limbs, 64-wide tiles: paired
+    ((32, 32, 32, 128, 128, 1, 1, 1, 0), 12),   # two limbs, 128-wide data-gradient tile
+    ((4, 16, 16, 64, 64, 3, 3, 1, 1), 16),
     ((2, 8, 8, 192, 384, 3, 3, 1, 1), 8),       # 192-wide data-gradient tile: not paired
 ])
 def test_backward_equals_the_two_separate_calls(shape, wl):
