@@ -1,0 +1,203 @@
+"""CPU oracle for one chained fixed-point training step of a feed-forward network (AdaPT,
+arXiv 2107.13490).
+
+TEST INFRASTRUCTURE ONLY.  Slow, plain reference; nothing in the product package may import it;
+only tests/, the smoke check and the benchmark's cpu_baseline leg do.  It shares no code with
+the HIP path.
+
+What it follows: Alg. 1 (AdaPT-SGD) for one batch -- ForwardPass on the quantized layers, the
+backward pass, the update of the master weights and the Quantize loop -- with every tensor that
+crosses a layer held as fixed-point codes (Sec. 2.1 "Fixed-Point Quantization", Sec. 3.2).  The
+paper states the training loop but not how a fixed-point backward pass keeps its gradients in
+range, nor the integer form of ReLU and max-pooling; the rules taken here:
+
+  layer l        z_l = conv(a_{l-1}, W^_l)   exact integer accumulator (FC = 1x1 conv on 1x1 maps)
+                 y_l = requantize(ReLU(z_l)) to the layer's own <WL_l,FL_l>, SR (ReLU optional)
+                 a_l = 2x2/2 max-pool of y_l (optional); max of codes = max of values
+  input          a_{-1} = quantize(x, <WL_0,FL_0>)
+  backward       dy_l = da_l routed through the pool to the FIRST maximum of each window in
+                 scan order (dh,dw) = (0,0),(0,1),(1,0),(1,1), and zeroed where y_l <= 0 (ReLU; the
+                 requantized output is what is stored, so it decides the mask)
+                 dW_l = wgrad(dy_l, a_{l-1}), da_{l-1} = dgrad(dy_l, W^_l), exact accumulators
+  gradient range back-propagation is linear in the incoming gradient and the weight update divides
+                 each layer's gradient by its 2-norm (Sec. 3.3 "Dealing with Fixed-Points Limited
+                 Range"), so a common power-of-two factor of a gradient tensor changes nothing but
+                 the rounding.  An exact accumulator tensor is therefore stored in WL bits with the
+                 smallest right shift that makes its largest magnitude fit:
+                 shift = max(0, bit_length(max|acc|) - (WL-1)), rounded by the requantize rule
+                 (SR), saturated.  da_{l-1} is stored in WL_{l-1} bits, dW_l in WL_l bits.
+  update         per layer the fused SGD update + Quantize of the sgd oracle, with the gradient
+                 codes and their sum of squares.
+
+Random streams: the step is given (seed, stream0); layer l uses stream0 + 8 l + slot with slot
+0 = forward output, 1 = data gradient it hands down, 2 = weight gradient, 3 = re-quantized weights,
+4 = network input (l = 0 only), 5 = first quantization of the weights.
+
+Also here: the residual addition of two fixed-point tensors (exact sum on the finer grid, then the
+requantize rule).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import conv_oracle as co
+from . import fxp_oracle as orc
+from . import sgd_oracle as so
+
+SLOT_FWD, SLOT_DA, SLOT_DW, SLOT_UPD, SLOT_IN, SLOT_WQ = 0, 1, 2, 3, 4, 5
+
+
+def stream_of(stream0: int, layer: int, slot: int) -> int:
+    return stream0 + 8 * layer + slot
+
+
+# ---- element-wise pieces ---------------------------------------------------------------------------------
+
+def maxpool2(y) -> np.ndarray:
+    """(n,h,w,c) codes -> (n,h/2,w/2,c): maximum of every 2x2 window (h, w even)."""
+    y = np.asarray(y)
+    n, h, w, c = y.shape
+    assert h % 2 == 0 and w % 2 == 0
+    out = np.empty((n, h // 2, w // 2, c), dtype=np.int64)
+    for i in range(h // 2):
+        for j in range(w // 2):
+            win = y[:, 2 * i:2 * i + 2, 2 * j:2 * j + 2, :].reshape(n, 4, c)
+            out[:, i, j, :] = win.max(axis=1)
+    return out
+
+
+def relu_pool_bwd(da, y, relu: bool, pool: bool) -> np.ndarray:
+    """Gradient w.r.t. the contraction output from the gradient w.r.t. the layer output.
+
+    y = the stored (requantized, post-ReLU) output before pooling, da = gradient of the pooled
+    tensor (or of y itself without pooling)."""
+    y = np.asarray(y).astype(np.int64)
+    da = np.asarray(da).astype(np.int64)
+    dy = np.zeros_like(y)
+    n, h, w, c = y.shape
+    if pool:
+        assert da.shape == (n, h // 2, w // 2, c)
+        for i in range(h // 2):
+            for j in range(w // 2):
+                win = y[:, 2 * i:2 * i + 2, 2 * j:2 * j + 2, :].reshape(n, 4, c)
+                first = win.argmax(axis=1)                      # numpy: index of the first maximum
+                for t in range(4):
+                    dy[:, 2 * i + t // 2, 2 * j + t % 2, :] = np.where(first == t, da[:, i, j, :], 0)
+    else:
+        assert da.shape == y.shape
+        dy[...] = da
+    if relu:
+        dy[y <= 0] = 0
+    return dy
+
+
+def fit_shift(acc, wl: int) -> int:
+    """Smallest right shift after which the largest magnitude of acc has at most wl-1 bits."""
+    a = np.asarray(acc, dtype=np.int64)
+    m = int(np.abs(a).max()) if a.size else 0
+    return max(0, m.bit_length() - (wl - 1))
+
+
+def requantize_fit(acc, wl: int, mode: int = orc.SR, seed: int = 0, stream: int = 0):
+    """Exact accumulators -> wl-bit codes with the fitting shift.  Returns (codes, shift, sum of squared codes)."""
+    sh = fit_shift(acc, wl)
+    q = orc.requantize(acc, sh, wl, mode, seed, stream, False)
+    return q, sh, int(np.sum(q.astype(object) ** 2)) if q.size else 0
+
+
+def residual_add(a, fl_a: int, b, fl_b: int, wl_o: int, fl_o: int, mode: int = orc.SR, seed: int = 0,
+                 stream: int = 0, relu: bool = False) -> np.ndarray:
+    """codes of a*2^-fl_a + b*2^-fl_b in <wl_o,fl_o>: exact sum with max(fl_a,fl_b) fractional bits, requantized."""
+    f = max(fl_a, fl_b)
+    s = np.asarray(a, dtype=np.int64) * (1 << (f - fl_a)) + np.asarray(b, dtype=np.int64) * (1 << (f - fl_b))
+    return orc.requantize(s, f - fl_o, wl_o, mode, seed, stream, relu)
+
+
+# ---- the chained step ------------------------------------------------------------------------------------
+
+@dataclass
+class Layer:
+    """Convolution (n,h,w,c) -> k filters r x s, or a fully connected layer (h = w = r = s = 1, pad 0)."""
+    h: int
+    w: int
+    c: int
+    k: int
+    r: int = 3
+    s: int = 3
+    stride: int = 1
+    pad: int = 1
+    relu: bool = True
+    pool: bool = False
+
+    @property
+    def p(self) -> int:
+        return (self.h + 2 * self.pad - self.r) // self.stride + 1
+
+    @property
+    def q(self) -> int:
+        return (self.w + 2 * self.pad - self.s) // self.stride + 1
+
+    def out_shape(self, n: int):
+        p, q = (self.p // 2, self.q // 2) if self.pool else (self.p, self.q)
+        return (n, p, q, self.k)
+
+
+def quantize_weights(layers, fmts, weights, seed: int, stream0: int):
+    """First Quantize of every layer's master weights (KRSC fp32) -> list of code arrays."""
+    return [orc.quantize(np.asarray(w, np.float32), wl, fl, orc.SR, seed, stream_of(stream0, l, SLOT_WQ))[0]
+            .reshape(L.k, L.r, L.s, L.c)
+            for l, (L, (wl, fl), w) in enumerate(zip(layers, fmts, weights))]
+
+
+def forward(layers, fmts, wq, x, seed: int, stream0: int):
+    """x: fp32 (n,h,w,c).  Returns dict(a_in, y[], a[]) of code arrays; a[-1] are the logits' codes."""
+    n = x.shape[0]
+    wl0, fl0 = fmts[0]
+    a_in = orc.quantize(np.asarray(x, np.float32), wl0, fl0, orc.SR, seed, stream_of(stream0, 0, SLOT_IN))[0].reshape(x.shape)
+    ys, acts = [], []
+    cur, fl_cur = a_in, fl0
+    for l, (L, (wl, fl)) in enumerate(zip(layers, fmts)):
+        cur = cur.reshape(n, L.h, L.w, L.c)                       # flatten / unflatten between conv and FC
+        z = co.conv_fwd(cur, wq[l], L.stride, L.pad)
+        shift = fl_cur + fl - fl                                   # FL of the activations + FL of the weights - FL of the output
+        y = orc.requantize(z, shift, wl, orc.SR, seed, stream_of(stream0, l, SLOT_FWD), L.relu)
+        ys.append(y)
+        cur = maxpool2(y) if L.pool else y
+        acts.append(cur)
+        fl_cur = fl
+    return {"a_in": a_in, "y": ys, "a": acts}
+
+
+def backward(layers, fmts, wq, fwd, dlogits, seed: int, stream0: int):
+    """dlogits: codes of the gradient w.r.t. the last layer's output (same shape).
+
+    Returns dict(g[] = weight-gradient codes, sumsq[], shift_w[], da[] = gradient codes handed to
+    layer l (da[L-1] = dlogits), dy[], shift_a[])."""
+    nl = len(layers)
+    n = fwd["a_in"].shape[0]
+    g, sumsq, shift_w = [None] * nl, [0] * nl, [0] * nl
+    da, dy, shift_a = [None] * nl, [None] * nl, [0] * nl
+    da[nl - 1] = np.asarray(dlogits).astype(np.int64).reshape(fwd["a"][nl - 1].shape)
+    for l in range(nl - 1, -1, -1):
+        L = layers[l]
+        wl, _ = fmts[l]
+        dy[l] = relu_pool_bwd(da[l], fwd["y"][l], L.relu, L.pool)
+        a_prev = (fwd["a"][l - 1] if l > 0 else fwd["a_in"]).reshape(n, L.h, L.w, L.c)
+        acc_w = co.conv_wgrad(dy[l], a_prev, L.r, L.s, L.stride, L.pad)
+        g[l], shift_w[l], sumsq[l] = requantize_fit(acc_w, wl, orc.SR, seed, stream_of(stream0, l, SLOT_DW))
+        if l > 0:
+            acc_a = co.conv_dgrad(dy[l], wq[l], L.h, L.w, L.stride, L.pad)
+            q, shift_a[l], _ = requantize_fit(acc_a, fmts[l - 1][0], orc.SR, seed, stream_of(stream0, l, SLOT_DA))
+            da[l - 1] = q.reshape(fwd["a"][l - 1].shape)
+    return {"g": g, "sumsq": sumsq, "shift_w": shift_w, "da": da, "dy": dy, "shift_a": shift_a}
+
+
+def update(layers, fmts, weights, bwd, lr: float, l1: float, l2: float, seed: int, stream0: int):
+    """Fused SGD update + Quantize per layer.  Returns list of sgd-oracle result dicts (w, q, nnz, sat, lo, hi)."""
+    out = []
+    for l, ((wl, fl), w) in enumerate(zip(fmts, weights)):
+        out.append(so.sgd_update_quantize(np.asarray(w, np.float32).ravel(), bwd["g"][l].ravel(), 0, lr, l1, l2, wl, fl,
+                                          orc.SR, seed, stream_of(stream0, l, SLOT_UPD), normalize=True))
+    return out
