@@ -157,8 +157,8 @@ int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fm
 
 /* Both gradients of one convolution layer (the backward pass of Alg. 1 for that layer): dx exactly
  * as adapt_conv_dgrad(d, dy, w) with ep_dx and dw exactly as adapt_conv_wgrad(d, dy, x) with ep_dw.
- * When both contractions take the one-limb vector path (all word lengths <= 8, channel counts
- * multiples of 16, 192-deep stages) they share one kernel launch; otherwise the two run one
+ * When both contractions take a vector path with matching tiles (all word lengths <= 8, or all
+ * above 8; channel counts multiples of 16) they share one kernel launch; otherwise the two run one
  * after the other.  Arguments and limits as for the two separate calls. */
 int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy,
                         const void *w, adapt_fmt fw, const void *x, adapt_fmt fx,
@@ -281,6 +281,111 @@ int adapt_lookback_next(int lb, double ds, int lb_lwr, int lb_upr, double gamma)
 /* r + 1 if lb == lb_upr, r - 1 if lb == lb_lwr (first case wins when both hold), clamped to
  * [r_lwr, r_upr]; r unchanged otherwise. */
 int adapt_resolution_next(int r, int lb, int lb_lwr, int lb_upr, int r_lwr, int r_upr);
+
+/* ---- a chained training step (Alg. 1 for one batch) and its element-wise integer operations ---- */
+
+/* The paper states the loop (ForwardPass, backward pass, update, Quantize per layer) and leaves
+ * the integer form of ReLU / pooling and the range of fixed-point gradients open; the rules of
+ * this library are stated with each call. */
+
+/* 2x2 max-pooling, stride 2, of codes: a[n,i,j,c] = max of y[n,2i..2i+1,2j..2j+1,c] (the code order
+ * is the value order).  y: device codes of an n x h x w x c tensor stored as format f (only the
+ * storage width of f matters), h and w even; a: device, n x h/2 x w/2 x c, same storage. */
+int adapt_maxpool2_fwd(adapt_ctx *ctx, const void *y, adapt_fmt f, int n, int h, int w, int c, void *a);
+
+/* Gradient with respect to a contraction's output from the gradient with respect to the layer's
+ * output.  y = the stored layer output before pooling (requantized, after ReLU), n x h x w x c.
+ *   pool != 0: da is n x h/2 x w/2 x c; each element goes to the FIRST maximum of its window of y
+ *              in the order (0,0),(0,1),(1,0),(1,1); the other three positions get 0
+ *   pool == 0: da is n x h x w x c and dy = da
+ *   relu != 0: additionally dy = 0 where y <= 0 (the stored output decides the mask)
+ * da, y and dy share the storage width of f.  dy must not overlap da or y. */
+int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y, adapt_fmt f, int n, int h,
+                        int w, int c, int relu, int pool, void *dy);
+
+/* Exact accumulators -> wl-bit codes that keep the leading bits.  Back-propagation is linear in
+ * the incoming gradient and the weight update divides a layer's gradient by its 2-norm (Sec. 3.3
+ * "Dealing with Fixed-Points Limited Range"), so a gradient tensor may be stored with any
+ * power-of-two factor:
+ *   shift = max(0, bit_length(max_i |acc[i]|) - (wl - 1))
+ *   q[i]  = the contraction epilogue's rule with this shift (SR on the dropped bits, saturation)
+ *   acc       device int32_t[n] (acc_bits = 32) or int64_t[n] (acc_bits = 64)
+ *   q         device int8_t[n] (wl <= 8) or int16_t[n]
+ *   shift     device int32_t or NULL
+ *   sumsq     device uint64_t or NULL: sum of q[i]^2 (what adapt_sgd_update_quantize takes)
+ * Two passes over acc.  n <= 2^40; n = 0 writes shift = 0, sumsq = 0. */
+int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl,
+                         adapt_rng rng, void *q, int32_t *shift, uint64_t *sumsq);
+
+/* Residual addition of two fixed-point tensors: out = a + b in format fo, i.e. the exact sum with
+ * max(fa.fl, fb.fl) fractional bits, then the contraction epilogue's rule with
+ * s = max(fa.fl, fb.fl) - fo.fl (SR or round-to-nearest, optional ReLU, saturation).  n <= 2^40. */
+int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *b, adapt_fmt fb,
+                       size_t n, adapt_fmt fo, adapt_rng rng, int relu, void *out);
+
+/* A feed-forward chain of convolution / fully connected layers (FC: h = w = r = s = 1, pad 0, c =
+ * the flattened NHWC input), each optionally followed by ReLU (fused into the contraction's
+ * epilogue) and then by 2x2/2 max-pooling.  All layers share the batch size conv.n, and the
+ * output of layer l has as many elements per sample as layer l+1 reads. */
+typedef struct { adapt_conv_desc conv; int relu, pool; } adapt_layer_desc;
+typedef struct adapt_net adapt_net; /* opaque, host */
+
+/* Per-layer record the step keeps in the workspace (device memory). */
+typedef struct {
+    uint64_t g_sumsq;            /* sum of the squared weight-gradient codes */
+    uint64_t nnz, saturated;     /* of the re-quantized weights (adapt_net_update) */
+    float range_lo, range_hi;    /* finite range of the updated master weights */
+    int32_t shift_w, shift_a;    /* shifts chosen for the weight gradient / the data gradient handed down */
+    int32_t reserved[6];
+} adapt_net_stats;
+
+enum { ADAPT_NT_INPUT = 0,   /* quantized network input (layer ignored) */
+       ADAPT_NT_Y = 1,       /* layer output before pooling */
+       ADAPT_NT_A = 2,       /* layer output (after pooling); the last layer's are the logits */
+       ADAPT_NT_DY = 3,      /* gradient w.r.t. the contraction output */
+       ADAPT_NT_DA = 4,      /* gradient w.r.t. the layer output (not written for the last layer) */
+       ADAPT_NT_QW = 5,      /* weight codes */
+       ADAPT_NT_G = 6,       /* weight-gradient codes */
+       ADAPT_NT_STATS = 7 }; /* adapt_net_stats */
+
+/* Bytes of device workspace the chain needs (activations, gradients, codes of weights and
+ * gradients at int16 storage so that word lengths may change, two accumulator buffers); 0 if the
+ * description is invalid (count outside 1..64, unequal batch sizes, shapes that do not chain,
+ * pooling of an odd-sized map). */
+size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count);
+
+/* layers, weights: HOST arrays of `count` entries; weights[l] = device fp32 master weights of layer
+ * l (KRSC), owned by the caller and updated in place by adapt_net_update.  workspace: device,
+ * 256-byte aligned, owned by the caller, must outlive the net.  Formats start as <8,4>. */
+int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
+                     float *const *weights, void *workspace, size_t workspace_bytes, adapt_net **net);
+int adapt_net_destroy(adapt_net *net);
+/* <WL,FL> of layer l: its weights, its output activations, and (WL only) its gradients. */
+int adapt_net_set_format(adapt_net *net, int layer, adapt_fmt f);
+/* Where a tensor of the chain lives: byte offset into the workspace, element count, bytes per
+ * element (for reading results; host pointers out). */
+int adapt_net_tensor(const adapt_net *net, int layer, int which, size_t *offset, size_t *count,
+                     int *elem_bytes);
+
+/* Random streams: every call takes (mode, seed, stream0); layer l uses stream0 + 8 l + slot with
+ * slot 0 = forward output, 1 = data gradient handed down, 2 = weight gradient, 3 = re-quantized
+ * weights, 4 = network input (l = 0), 5 = first quantization of the weights.
+ * A call that fails returns the failing step's status; steps enqueued before it have run. */
+
+/* Quantize of every layer's master weights into its format (one launch). */
+int adapt_net_quantize_weights(adapt_net *net, adapt_rng rng);
+/* x: device fp32, the batch in NHWC.  a_{-1} = quantize(x, format of layer 0); per layer
+ * y = requantize(ReLU(conv(a, W^))) into the layer's format, a = maxpool(y). */
+int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng);
+/* dlogits: device codes (storage of the last layer's format, its word length) of the loss gradient
+ * with respect to the last layer's output, any power-of-two scale.  Per layer, last to first:
+ * dy = adapt_relu_pool_bwd(da, y); exact dW = wgrad(dy, a_prev) and, above the first layer, exact
+ * da_prev = dgrad(dy, W^); both through adapt_requantize_fit (dW to the layer's word length, da_prev
+ * to the previous layer's).  Needs a forward pass since the last format change or update. */
+int adapt_net_backward(adapt_net *net, const void *dlogits, adapt_rng rng);
+/* Per layer adapt_sgd_update_quantize with the gradient codes and their sum of squares (the step
+ * has length lr per layer); writes the new weight codes and the stats record. */
+int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng rng);
 
 /* ---- the paper's performance model (Sec. 4.1 "Performance Model") --------------------------- */
 

@@ -79,6 +79,19 @@ class PerfLayer(C.Structure):
                 ("resolution", C.c_int)]
 
 
+class LayerDesc(C.Structure):
+    """One layer of a chain: a ConvDesc (FC: h = w = r = s = 1, pad 0), ReLU and 2x2/2 max-pool flags."""
+    _fields_ = [("conv", ConvDesc), ("relu", C.c_int), ("pool", C.c_int)]
+
+
+class NetStats(C.Structure):
+    _fields_ = [("g_sumsq", C.c_uint64), ("nnz", C.c_uint64), ("saturated", C.c_uint64), ("range_lo", C.c_float),
+                ("range_hi", C.c_float), ("shift_w", C.c_int32), ("shift_a", C.c_int32), ("reserved", C.c_int32 * 6)]
+
+
+NT_INPUT, NT_Y, NT_A, NT_DY, NT_DA, NT_QW, NT_G, NT_STATS = range(8)
+
+
 class PushupResult(C.Structure):
     _fields_ = [("wl", C.c_int), ("fl", C.c_int), ("s1", C.c_int), ("s2", C.c_int), ("s", C.c_int)]
 
@@ -127,6 +140,20 @@ def load_library():
     for f in (lib.adapt_perf_pushdown_ops, lib.adapt_perf_pushup_ops, lib.adapt_perf_speedup, lib.adapt_perf_step_cost,
               lib.adapt_perf_step_overhead, lib.adapt_perf_model_size, lib.adapt_perf_step_memory):
         f.restype = dbl
+    lib.adapt_maxpool2_fwd.argtypes = [vp, vp, Fmt, i, i, i, i, vp]
+    lib.adapt_relu_pool_bwd.argtypes = [vp, vp, vp, Fmt, i, i, i, i, i, i, vp]
+    lib.adapt_requantize_fit.argtypes = [vp, vp, i, sz, i, Rng, vp, vp, vp]
+    lib.adapt_residual_add.argtypes = [vp, vp, Fmt, vp, Fmt, sz, Fmt, Rng, i, vp]
+    lib.adapt_net_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i]
+    lib.adapt_net_workspace_bytes.restype = sz
+    lib.adapt_net_create.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), vp, sz, C.POINTER(vp)]
+    lib.adapt_net_destroy.argtypes = [vp]
+    lib.adapt_net_set_format.argtypes = [vp, i, Fmt]
+    lib.adapt_net_tensor.argtypes = [vp, i, i, C.POINTER(sz), C.POINTER(sz), C.POINTER(i)]
+    lib.adapt_net_quantize_weights.argtypes = [vp, Rng]
+    lib.adapt_net_forward.argtypes = [vp, vp, Rng]
+    lib.adapt_net_backward.argtypes = [vp, vp, Rng]
+    lib.adapt_net_update.argtypes = [vp, SgdParams, Rng]
     lib.adapt_gradient_diversity.argtypes = [vp, C.POINTER(GradItem), i, sz, vp, vp]
     lib.adapt_pushup_suggest.argtypes = [dbl, i, i, i, i, i, C.POINTER(PushupResult)]
     lib.adapt_strategy_next.argtypes = [i, dbl, dbl]
@@ -426,3 +453,98 @@ class Context:
                                                    SgdParams(lr, l1, l2), Fmt(wl, fl), Rng(mode, seed, stream), _ptr(out),
                                                    _ptr(counters), _ptr(rng_range)), "adapt_sgd_update_quantize")
         return out, counters, rng_range
+
+    # -- element-wise integer operations of a chained step ------------------------------------------
+    def maxpool2_fwd(self, y, wl, out=None):
+        """y: codes (n,h,w,c), h and w even.  Returns the 2x2/2 max-pooled codes."""
+        n, h, w, c = y.shape
+        if out is None:
+            out = self._torch.empty((n, h // 2, w // 2, c), dtype=y.dtype, device=y.device)
+        _check(self._lib.adapt_maxpool2_fwd(self._h, _ptr(y), Fmt(wl, 0), n, h, w, c, _ptr(out)), "adapt_maxpool2_fwd")
+        return out
+
+    def relu_pool_bwd(self, da, y, wl, relu, pool, out=None):
+        """Gradient w.r.t. the contraction output; y = stored output before pooling (n,h,w,c)."""
+        n, h, w, c = y.shape
+        if out is None:
+            out = self._torch.empty_like(y)
+        _check(self._lib.adapt_relu_pool_bwd(self._h, _ptr(da), _ptr(y), Fmt(wl, 0), n, h, w, c, int(relu), int(pool),
+                                             _ptr(out)), "adapt_relu_pool_bwd")
+        return out
+
+    def requantize_fit(self, acc, wl, mode=SR, seed=0, stream=0, out=None, want_sumsq=True):
+        """acc: int32 / int64 exact accumulators.  Returns (codes, shift int32[1], sumsq int64[1] or None)."""
+        torch = self._torch
+        if out is None:
+            out = torch.empty(acc.shape, dtype=self.storage_dtype(wl), device=acc.device)
+        shift = torch.empty(1, dtype=torch.int32, device=acc.device)
+        sumsq = torch.empty(1, dtype=torch.int64, device=acc.device) if want_sumsq else None
+        bits = 32 if acc.dtype == torch.int32 else 64
+        _check(self._lib.adapt_requantize_fit(self._h, _ptr(acc), bits, acc.numel(), wl, Rng(mode, seed, stream), _ptr(out),
+                                              _ptr(shift), _ptr(sumsq)), "adapt_requantize_fit")
+        return out, shift, sumsq
+
+    def residual_add(self, a, fa, b, fb, fo, mode=SR, seed=0, stream=0, relu=False, out=None):
+        """Codes of a + b in format fo = (wl, fl)."""
+        if out is None:
+            out = self._torch.empty(a.shape, dtype=self.storage_dtype(fo[0]), device=a.device)
+        _check(self._lib.adapt_residual_add(self._h, _ptr(a), Fmt(*fa), _ptr(b), Fmt(*fb), a.numel(), Fmt(*fo),
+                                            Rng(mode, seed, stream), int(relu), _ptr(out)), "adapt_residual_add")
+        return out
+
+
+class Net:
+    """A chained fixed-point training step (adapt_net_*).  Holds the workspace tensor and the master
+    weights (fp32 device tensors, KRSC, updated in place by update())."""
+
+    def __init__(self, ctx: Context, layers, weights):
+        import torch
+        self._ctx, self._lib, self._torch = ctx, ctx._lib, torch
+        self.layers = list(layers)
+        self.weights = list(weights)
+        n = len(self.layers)
+        descs = (LayerDesc * n)(*self.layers)
+        need = self._lib.adapt_net_workspace_bytes(descs, n)
+        if need == 0:
+            raise AdaptError(-1, "adapt_net_workspace_bytes")
+        self.workspace = torch.zeros(need, dtype=torch.uint8, device=self.weights[0].device)
+        wptrs = (C.c_void_p * n)(*[w.data_ptr() for w in self.weights])
+        h = C.c_void_p()
+        _check(self._lib.adapt_net_create(ctx.handle, descs, n, wptrs, _ptr(self.workspace), need, C.byref(h)), "adapt_net_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.adapt_net_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_format(self, layer, wl, fl):
+        _check(self._lib.adapt_net_set_format(self._h, layer, Fmt(wl, fl)), "adapt_net_set_format")
+
+    def tensor(self, layer, which):
+        """View of one of the chain's tensors inside the workspace (flat int8 / int16; NT_STATS: a NetStats copy)."""
+        torch = self._torch
+        off, cnt, es = C.c_size_t(), C.c_size_t(), C.c_int()
+        _check(self._lib.adapt_net_tensor(self._h, layer, which, C.byref(off), C.byref(cnt), C.byref(es)), "adapt_net_tensor")
+        raw = self.workspace[off.value:off.value + cnt.value * es.value]
+        if which == NT_STATS:
+            return NetStats.from_buffer_copy(bytes(raw.cpu().numpy()))
+        return raw.view(torch.int8 if es.value == 1 else torch.int16)
+
+    def quantize_weights(self, mode=SR, seed=0, stream=0):
+        _check(self._lib.adapt_net_quantize_weights(self._h, Rng(mode, seed, stream)), "adapt_net_quantize_weights")
+
+    def forward(self, x, mode=SR, seed=0, stream=0):
+        _check(self._lib.adapt_net_forward(self._h, _ptr(x), Rng(mode, seed, stream)), "adapt_net_forward")
+
+    def backward(self, dlogits, mode=SR, seed=0, stream=0):
+        _check(self._lib.adapt_net_backward(self._h, _ptr(dlogits), Rng(mode, seed, stream)), "adapt_net_backward")
+
+    def update(self, lr, l1=0.0, l2=0.0, mode=SR, seed=0, stream=0):
+        _check(self._lib.adapt_net_update(self._h, SgdParams(lr, l1, l2), Rng(mode, seed, stream)), "adapt_net_update")

@@ -109,6 +109,69 @@ __device__ __forceinline__ int quantize_one(float x, uint32_t r16, const QuantPa
 }
 
 // ---------------------------------------------------------------------------------------------
+// exact accumulator -> code of the output format: right shift with the SR rule on the dropped bits
+// (shift <= 0: left shift), optional ReLU, saturation to wl bits
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int requantize_one(long long acc, int shift, int wl, int relu, uint32_t r16)
+{
+    long long q;
+    if (shift <= 0) {
+        const long long lim = 1ll << 20;               // beyond any 16-bit range: saturates below
+        const long long c = acc > lim ? lim : acc < -lim ? -lim : acc;
+        q = (-shift >= 40) ? (c > 0 ? (1ll << 60) : c < 0 ? -(1ll << 60) : 0) : (long long)((unsigned long long)c << -shift);
+    } else if (shift <= 16) {
+        q = (acc + (long long)(r16 >> (16 - shift))) >> shift;
+    } else {
+        q = ((acc >> (shift - 16)) + (long long)r16) >> 16;
+    }
+    if (relu && q < 0) q = 0;
+    const long long qmax = (1ll << (wl - 1)) - 1, qmin = -(1ll << (wl - 1));
+    return (int)(q > qmax ? qmax : q < qmin ? qmin : q);
+}
+
+// ---------------------------------------------------------------------------------------------
+// eight consecutive codes (group index grp) of an int8 / int16 tensor, 16-byte aligned base
+// ---------------------------------------------------------------------------------------------
+template <typename GT>
+__device__ __forceinline__ void load_codes8(const GT *g, uint64_t grp, int (&c)[8]);
+template <>
+__device__ __forceinline__ void load_codes8<int8_t>(const int8_t *g, uint64_t grp, int (&c)[8])
+{
+    const uint2 v = reinterpret_cast<const uint2 *>(g)[grp];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = (int)(int8_t)((j < 4 ? v.x : v.y) >> (8 * (j & 3)));
+}
+template <>
+__device__ __forceinline__ void load_codes8<int16_t>(const int16_t *g, uint64_t grp, int (&c)[8])
+{
+    const uint4 v = reinterpret_cast<const uint4 *>(g)[grp];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
+}
+
+template <typename OutT>
+__device__ __forceinline__ void store_codes8(OutT *q, uint64_t grp, const int (&v)[8]);
+template <>
+__device__ __forceinline__ void store_codes8<int8_t>(int8_t *q, uint64_t grp, const int (&v)[8])
+{
+    uint2 o;
+    o.x = (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)(v[3] & 0xff) << 24);
+    o.y = (uint32_t)(v[4] & 0xff) | ((uint32_t)(v[5] & 0xff) << 8) | ((uint32_t)(v[6] & 0xff) << 16) | ((uint32_t)(v[7] & 0xff) << 24);
+    reinterpret_cast<uint2 *>(q)[grp] = o;
+}
+template <>
+__device__ __forceinline__ void store_codes8<int16_t>(int16_t *q, uint64_t grp, const int (&v)[8])
+{
+    uint4 o;
+    o.x = (uint32_t)(v[0] & 0xffff) | ((uint32_t)v[1] << 16);
+    o.y = (uint32_t)(v[2] & 0xffff) | ((uint32_t)v[3] << 16);
+    o.z = (uint32_t)(v[4] & 0xffff) | ((uint32_t)v[5] << 16);
+    o.w = (uint32_t)(v[6] & 0xffff) | ((uint32_t)v[7] << 16);
+    reinterpret_cast<uint4 *>(q)[grp] = o;
+}
+
+// ---------------------------------------------------------------------------------------------
 // wavefront reductions (64 lanes)
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)

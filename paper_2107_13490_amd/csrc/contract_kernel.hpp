@@ -452,23 +452,6 @@ struct LoaderSelect<OP, ACT, LOAD_ROWS, ROWS, LIMBS, BKT, ES> { typedef LoaderR<
 // ---------------------------------------------------------------------------------------------
 // accumulator -> output format (the SR rule applied to the accumulator's low bits)
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int requantize_one(long long acc, int shift, int wl, int relu, uint32_t r16)
-{
-    long long q;
-    if (shift <= 0) {
-        const long long lim = 1ll << 20;               // beyond any 16-bit range: saturates below
-        const long long c = acc > lim ? lim : acc < -lim ? -lim : acc;
-        q = (-shift >= 40) ? (c > 0 ? (1ll << 60) : c < 0 ? -(1ll << 60) : 0) : (long long)((unsigned long long)c << -shift);
-    } else if (shift <= 16) {
-        q = (acc + (long long)(r16 >> (16 - shift))) >> shift;
-    } else {
-        q = ((acc >> (shift - 16)) + (long long)r16) >> 16;
-    }
-    if (relu && q < 0) q = 0;
-    const long long qmax = (1ll << (wl - 1)) - 1, qmin = -(1ll << (wl - 1));
-    return (int)(q > qmax ? qmax : q < qmin ? qmin : q);
-}
-
 // one-limb accumulators fit 32 bits with room for the rounding bits (|acc| <= 2^30).  `w` holds the
 // rounding bits of two neighbouring outputs (low / high half); shift >= 1.
 __device__ __forceinline__ int requantize_i32(int acc, int shift, int qlo, int qhi, uint32_t w, int half)

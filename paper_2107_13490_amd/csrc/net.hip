@@ -1,0 +1,674 @@
+// One chained fixed-point training step of a feed-forward network (Alg. 1 for one batch:
+// ForwardPass on the quantized layers, the backward pass, the update of the master weights and the
+// per-layer Quantize), and the element-wise integer operations it needs between the contractions:
+// 2x2 max-pooling of codes, the routing of a gradient back through pooling and ReLU, the conversion
+// of exact gradient accumulators to WL-bit codes with the smallest shift that fits, and the
+// residual addition of two fixed-point tensors.
+//
+// The paper gives the training loop; how a fixed-point backward pass keeps gradients in range is
+// left open.  Back-propagation is linear in the incoming gradient and the update divides each
+// layer's gradient by its 2-norm (Sec. 3.3 "Dealing with Fixed-Points Limited Range"), so a gradient
+// tensor may carry any power-of-two factor: each exact accumulator tensor is shifted right just far
+// enough for its largest magnitude to fit WL-1 bits, with the SR rule of Sec. 3.2 on the dropped
+// bits.
+//
+// All four element-wise kernels are bound by HBM traffic (one read of every input, one write of
+// every output, 16-byte accesses); the chain itself is host code that enqueues this library's own
+// entry points on the context's stream.
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "common.hpp"
+#include "context.hpp"
+
+namespace adapt {
+
+constexpr int kEwThreads = 256;
+
+template <typename T, int V>
+struct alignas(sizeof(T) * V) CodeVec {
+    T v[V];
+};
+
+// pooled geometry: rows = n * (h/2), wo = w/2, cv = vectors per pixel; items = rows * wo * cv
+struct PoolGeo {
+    uint32_t wo, cv, items;
+};
+
+// a[n,i,j,c] = max over the 2x2 window of y[n,2i..2i+1,2j..2j+1,c]; codes compare like values
+template <typename T, int V>
+__global__ void __launch_bounds__(kEwThreads) maxpool2_kernel(const T *__restrict__ y, T *__restrict__ a, const PoolGeo g)
+{
+    typedef CodeVec<T, V> Vec;
+    const Vec *yv = reinterpret_cast<const Vec *>(y);
+    Vec *av = reinterpret_cast<Vec *>(a);
+    const uint32_t stride = gridDim.x * kEwThreads;
+    for (uint32_t i = blockIdx.x * kEwThreads + threadIdx.x; i < g.items; i += stride) {
+        const uint32_t pix = i / g.cv, cv = i - pix * g.cv;
+        const uint32_t row = pix / g.wo, wo = pix - row * g.wo;      // row = n*(h/2) + i: input row 2*row
+        const uint64_t down = 2ull * g.wo * g.cv;
+        const uint64_t p00 = (2ull * row * (2ull * g.wo) + 2ull * wo) * g.cv + cv;
+        const Vec v0 = yv[p00], v1 = yv[p00 + g.cv], v2 = yv[p00 + down], v3 = yv[p00 + down + g.cv];
+        Vec o;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const T m0 = v0.v[e] > v1.v[e] ? v0.v[e] : v1.v[e], m1 = v2.v[e] > v3.v[e] ? v2.v[e] : v3.v[e];
+            o.v[e] = m0 > m1 ? m0 : m1;
+        }
+        av[i] = o;
+    }
+}
+
+// POOL: dy = da at the first maximum (scan order) of each window of the stored output y, zero
+// elsewhere; with relu also zero where that maximum is not positive.  !POOL: dy = da where y > 0.
+template <typename T, int V, bool POOL>
+__global__ void __launch_bounds__(kEwThreads)
+relu_pool_bwd_kernel(const T *__restrict__ da, const T *__restrict__ y, T *__restrict__ dy, const PoolGeo g, const int relu)
+{
+    typedef CodeVec<T, V> Vec;
+    const Vec *yv = reinterpret_cast<const Vec *>(y);
+    const Vec *dv = reinterpret_cast<const Vec *>(da);
+    Vec *ov = reinterpret_cast<Vec *>(dy);
+    const uint32_t stride = gridDim.x * kEwThreads;
+    for (uint32_t i = blockIdx.x * kEwThreads + threadIdx.x; i < g.items; i += stride) {
+        if (POOL) {
+            const uint32_t pix = i / g.cv, cv = i - pix * g.cv;
+            const uint32_t row = pix / g.wo, wo = pix - row * g.wo;
+            const uint64_t down = 2ull * g.wo * g.cv;
+            const uint64_t p00 = (2ull * row * (2ull * g.wo) + 2ull * wo) * g.cv + cv;
+            const Vec v0 = yv[p00], v1 = yv[p00 + g.cv], v2 = yv[p00 + down], v3 = yv[p00 + down + g.cv], d = dv[i];
+            Vec o0, o1, o2, o3;
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const T m0 = v0.v[e] > v1.v[e] ? v0.v[e] : v1.v[e], m1 = v2.v[e] > v3.v[e] ? v2.v[e] : v3.v[e];
+                const T m = m0 > m1 ? m0 : m1;
+                const int first = v0.v[e] == m ? 0 : v1.v[e] == m ? 1 : v2.v[e] == m ? 2 : 3;
+                const T val = (!relu || m > 0) ? d.v[e] : (T)0;
+                o0.v[e] = first == 0 ? val : (T)0;
+                o1.v[e] = first == 1 ? val : (T)0;
+                o2.v[e] = first == 2 ? val : (T)0;
+                o3.v[e] = first == 3 ? val : (T)0;
+            }
+            ov[p00] = o0; ov[p00 + g.cv] = o1; ov[p00 + down] = o2; ov[p00 + down + g.cv] = o3;
+        } else {
+            const Vec v = yv[i], d = dv[i];
+            Vec o;
+#pragma unroll
+            for (int e = 0; e < V; ++e) o.v[e] = (!relu || v.v[e] > 0) ? d.v[e] : (T)0;
+            ov[i] = o;
+        }
+    }
+}
+
+__device__ __forceinline__ uint64_t magnitude(long long v) { return v < 0 ? 0ull - (uint64_t)v : (uint64_t)v; }
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint64_t o = __shfl_xor((unsigned long long)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+template <typename AccT>
+__device__ __forceinline__ void load_acc8(const AccT *acc, uint64_t grp, long long (&v)[8]);
+template <>
+__device__ __forceinline__ void load_acc8<int32_t>(const int32_t *acc, uint64_t grp, long long (&v)[8])
+{
+    const int4 a = reinterpret_cast<const int4 *>(acc)[2 * grp], b = reinterpret_cast<const int4 *>(acc)[2 * grp + 1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void load_acc8<int64_t>(const int64_t *acc, uint64_t grp, long long (&v)[8])
+{
+    const longlong2 *p = reinterpret_cast<const longlong2 *>(acc) + 4 * grp;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const longlong2 t = p[i];
+        v[2 * i] = t.x; v[2 * i + 1] = t.y;
+    }
+}
+
+// largest magnitude of acc[0..n): one partial per block; block 0 also clears the sum of squares that
+// the pass after this one accumulates
+template <typename AccT>
+__global__ void __launch_bounds__(kEwThreads)
+absmax_kernel(const AccT *__restrict__ acc, const uint64_t n, uint64_t *__restrict__ part, unsigned long long *sumsq)
+{
+    uint64_t m = 0;
+    const uint64_t groups = n >> 3;
+    const uint64_t first = (uint64_t)blockIdx.x * kEwThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kEwThreads;
+    for (uint64_t grp = first; grp < groups; grp += stride) {
+        long long v[8];
+        load_acc8<AccT>(acc, grp, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint64_t a = magnitude(v[e]);
+            m = a > m ? a : m;
+        }
+    }
+    if ((n & 7) && first == 0)
+        for (uint64_t i = groups << 3; i < n; ++i) {
+            const uint64_t a = magnitude((long long)acc[i]);
+            m = a > m ? a : m;
+        }
+    __shared__ uint64_t sm[kEwThreads / kWave];
+    m = wave_max_u64(m);
+    if ((threadIdx.x & (kWave - 1)) == 0) sm[threadIdx.x / kWave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 1; i < kEwThreads / kWave; ++i) m = sm[i] > m ? sm[i] : m;
+        part[blockIdx.x] = m;
+        if (blockIdx.x == 0 && sumsq) *sumsq = 0;
+    }
+}
+
+struct FitArgs {
+    const void *acc;
+    void *q;
+    const uint64_t *part;
+    int nparts;
+    uint64_t n;
+    int wl, mode;
+    uint64_t seed, stream;
+    int32_t *shift_out;
+    unsigned long long *sumsq;
+};
+
+// codes = requantize(acc, shift) with shift = max(0, bit_length(max |acc|) - (wl-1)); every block
+// derives the shift from the partial maxima itself
+template <typename AccT, typename OutT>
+__global__ void __launch_bounds__(kEwThreads) requant_fit_kernel(const FitArgs a)
+{
+    __shared__ uint64_t sm[kEwThreads / kWave];
+    uint64_t m = 0;
+    for (int i = threadIdx.x; i < a.nparts; i += kEwThreads) m = a.part[i] > m ? a.part[i] : m;
+    m = wave_max_u64(m);
+    if ((threadIdx.x & (kWave - 1)) == 0) sm[threadIdx.x / kWave] = m;
+    __syncthreads();
+    m = sm[0];
+#pragma unroll
+    for (int i = 1; i < kEwThreads / kWave; ++i) m = sm[i] > m ? sm[i] : m;
+    const int bits = m ? 64 - __clzll((long long)m) : 0;
+    const int shift = max(0, bits - (a.wl - 1));
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.shift_out) *a.shift_out = shift;
+    __syncthreads();                                    // sm is reused below
+
+    const AccT *acc = static_cast<const AccT *>(a.acc);
+    OutT *q = static_cast<OutT *>(a.q);
+    uint64_t ss = 0;
+    const uint64_t groups = a.n >> 3;
+    const uint64_t first = (uint64_t)blockIdx.x * kEwThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kEwThreads;
+    for (uint64_t grp = first; grp < groups; grp += stride) {
+        long long v[8];
+        load_acc8<AccT>(acc, grp, v);
+        uint32_t r[8];
+        if (a.mode == ADAPT_SR) {
+            const u32x4 blk = rounding_block(a.seed, a.stream, grp);
+            r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
+            r[4] = blk.z & 0xffffu; r[5] = blk.z >> 16; r[6] = blk.w & 0xffffu; r[7] = blk.w >> 16;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = 0x8000u;
+        }
+        int code[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            code[e] = requantize_one(v[e], shift, a.wl, 0, r[e]);
+            ss += (uint64_t)((long long)code[e] * code[e]);
+        }
+        store_codes8<OutT>(q, grp, code);
+    }
+    if ((a.n & 7) && first == 0)
+        for (uint64_t i = groups << 3; i < a.n; ++i) {
+            const int c = requantize_one((long long)acc[i], shift, a.wl, 0, rounding_bits_of(a.seed, a.stream, i, a.mode));
+            q[i] = (OutT)c;
+            ss += (uint64_t)((long long)c * c);
+        }
+    if (a.sumsq) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor((unsigned long long)ss, off, 64);
+        if ((threadIdx.x & (kWave - 1)) == 0) sm[threadIdx.x / kWave] = ss;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int i = 1; i < kEwThreads / kWave; ++i) ss += sm[i];
+            if (ss) atomicAdd(a.sumsq, (unsigned long long)ss);
+        }
+    }
+}
+
+struct AddArgs {
+    const void *a, *b;
+    void *out;
+    uint64_t n;
+    int sa, sb, shift, wl, relu, mode;
+    uint64_t seed, stream;
+};
+
+// out = requantize(a * 2^sa + b * 2^sb, shift): the exact sum on the finer of the two grids
+template <typename TA, typename TB, typename TO>
+__global__ void __launch_bounds__(kEwThreads) residual_add_kernel(const AddArgs p)
+{
+    const TA *a = static_cast<const TA *>(p.a);
+    const TB *b = static_cast<const TB *>(p.b);
+    TO *out = static_cast<TO *>(p.out);
+    const uint64_t groups = p.n >> 3;
+    const uint64_t first = (uint64_t)blockIdx.x * kEwThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kEwThreads;
+    for (uint64_t grp = first; grp < groups; grp += stride) {
+        int ca[8], cb[8], code[8];
+        load_codes8<TA>(a, grp, ca);
+        load_codes8<TB>(b, grp, cb);
+        uint32_t r[8];
+        if (p.mode == ADAPT_SR) {
+            const u32x4 blk = rounding_block(p.seed, p.stream, grp);
+            r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
+            r[4] = blk.z & 0xffffu; r[5] = blk.z >> 16; r[6] = blk.w & 0xffffu; r[7] = blk.w >> 16;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = 0x8000u;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const long long s = (long long)ca[e] * (1ll << p.sa) + (long long)cb[e] * (1ll << p.sb);
+            code[e] = requantize_one(s, p.shift, p.wl, p.relu, r[e]);
+        }
+        store_codes8<TO>(out, grp, code);
+    }
+    if ((p.n & 7) && first == 0)
+        for (uint64_t i = groups << 3; i < p.n; ++i) {
+            const long long s = (long long)a[i] * (1ll << p.sa) + (long long)b[i] * (1ll << p.sb);
+            out[i] = (TO)requantize_one(s, p.shift, p.wl, p.relu, rounding_bits_of(p.seed, p.stream, i, p.mode));
+        }
+}
+
+static int ew_grid(const adapt_ctx *ctx, uint64_t items)
+{
+    const uint64_t blocks = (items + kEwThreads - 1) / kEwThreads;
+    return (int)std::min<uint64_t>(std::max<uint64_t>(blocks, 1), (uint64_t)ctx->num_cu * 8);
+}
+
+static bool rng_ok(adapt_rng r) { return r.mode == ADAPT_SR || r.mode == ADAPT_RN_HALF_UP; }
+
+// geometry of a pooled / unpooled element-wise pass over an n x h x w x c tensor of es-byte codes
+static int pool_geo(int es, int n, int h, int w, int c, bool pool, PoolGeo &g, int &vec)
+{
+    if (n < 0 || h < 1 || w < 1 || c < 1) return ADAPT_EINVAL;
+    if (pool && ((h | w) & 1)) return ADAPT_EINVAL;
+    const int full = 16 / es;
+    vec = (c % full == 0) ? full : 1;
+    // without pooling the tensor is a flat array: vectors may straddle pixels
+    if (!pool && ((uint64_t)n * h * w * c) % full == 0) vec = full;
+    const uint64_t elems = (uint64_t)n * (pool ? h / 2 : h) * (pool ? w / 2 : w) * c;
+    const uint64_t items = elems / vec;
+    if ((uint64_t)n * h * w * c * es >= ((uint64_t)1 << 32) || items >= ((uint64_t)1 << 31)) return ADAPT_EUNSUPPORTED;
+    g.wo = (uint32_t)(pool ? w / 2 : w);
+    g.cv = (uint32_t)(pool ? c / vec : 1);
+    g.items = (uint32_t)items;
+    return ADAPT_OK;
+}
+
+}  // namespace adapt
+
+using namespace adapt;
+
+extern "C" int adapt_maxpool2_fwd(adapt_ctx *ctx, const void *y, adapt_fmt f, int n, int h, int w, int c, void *a)
+{
+    if (!ctx || !fmt_ok(f)) return ADAPT_EINVAL;
+    const int es = storage_bytes(f);
+    PoolGeo g;
+    int vec;
+    if (int s = pool_geo(es, n, h, w, c, true, g, vec)) return s;
+    if (g.items == 0) return ADAPT_OK;
+    if (!y || !a || !aligned16(y) || !aligned16(a)) return ADAPT_EINVAL;
+    const dim3 grid(ew_grid(ctx, g.items)), block(kEwThreads);
+    if (es == 1 && vec == 16) hipLaunchKernelGGL((maxpool2_kernel<int8_t, 16>), grid, block, 0, ctx->stream, (const int8_t *)y, (int8_t *)a, g);
+    else if (es == 1) hipLaunchKernelGGL((maxpool2_kernel<int8_t, 1>), grid, block, 0, ctx->stream, (const int8_t *)y, (int8_t *)a, g);
+    else if (vec == 8) hipLaunchKernelGGL((maxpool2_kernel<int16_t, 8>), grid, block, 0, ctx->stream, (const int16_t *)y, (int16_t *)a, g);
+    else hipLaunchKernelGGL((maxpool2_kernel<int16_t, 1>), grid, block, 0, ctx->stream, (const int16_t *)y, (int16_t *)a, g);
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y, adapt_fmt f, int n, int h, int w, int c,
+                                   int relu, int pool, void *dy)
+{
+    if (!ctx || !fmt_ok(f)) return ADAPT_EINVAL;
+    const int es = storage_bytes(f);
+    PoolGeo g;
+    int vec;
+    if (int s = pool_geo(es, n, h, w, c, pool != 0, g, vec)) return s;
+    if (g.items == 0) return ADAPT_OK;
+    if (!da || !y || !dy || !aligned16(da) || !aligned16(y) || !aligned16(dy)) return ADAPT_EINVAL;
+    const dim3 grid(ew_grid(ctx, g.items)), block(kEwThreads);
+#define ADAPT_BWD(T, V, P) hipLaunchKernelGGL((relu_pool_bwd_kernel<T, V, P>), grid, block, 0, ctx->stream, (const T *)da, (const T *)y, (T *)dy, g, relu)
+    if (pool) {
+        if (es == 1 && vec == 16) ADAPT_BWD(int8_t, 16, true);
+        else if (es == 1) ADAPT_BWD(int8_t, 1, true);
+        else if (vec == 8) ADAPT_BWD(int16_t, 8, true);
+        else ADAPT_BWD(int16_t, 1, true);
+    } else {
+        if (es == 1 && vec == 16) ADAPT_BWD(int8_t, 16, false);
+        else if (es == 1) ADAPT_BWD(int8_t, 1, false);
+        else if (vec == 8) ADAPT_BWD(int16_t, 8, false);
+        else ADAPT_BWD(int16_t, 1, false);
+    }
+#undef ADAPT_BWD
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q,
+                                    int32_t *shift, uint64_t *sumsq)
+{
+    if (!ctx || (acc_bits != 32 && acc_bits != 64) || wl < 2 || wl > 16 || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
+    if ((shift && ((uintptr_t)shift & 3)) || (sumsq && ((uintptr_t)sumsq & 7))) return ADAPT_EINVAL;
+    if (n > 0 && (!acc || !q || !aligned16(acc) || !aligned16(q))) return ADAPT_EINVAL;
+    const uint64_t groups = ((uint64_t)n + 7) >> 3;
+    const int grid1 = (int)std::min<uint64_t>(std::max<uint64_t>((groups + kEwThreads - 1) / kEwThreads, 1), (uint64_t)ctx->num_cu * 4);
+    const int grid2 = ew_grid(ctx, groups);
+    if ((size_t)grid1 * 8 > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    uint64_t *part = reinterpret_cast<uint64_t *>(scratch(ctx));
+    unsigned long long *ss = reinterpret_cast<unsigned long long *>(sumsq);
+    FitArgs a;
+    a.acc = acc; a.q = q; a.part = part; a.nparts = grid1; a.n = n; a.wl = wl; a.mode = rng.mode; a.seed = rng.seed;
+    a.stream = rng.stream; a.shift_out = shift; a.sumsq = ss;
+    const dim3 block(kEwThreads);
+    if (acc_bits == 32) hipLaunchKernelGGL(absmax_kernel<int32_t>, dim3(grid1), block, 0, ctx->stream, (const int32_t *)acc, (uint64_t)n, part, ss);
+    else hipLaunchKernelGGL(absmax_kernel<int64_t>, dim3(grid1), block, 0, ctx->stream, (const int64_t *)acc, (uint64_t)n, part, ss);
+    const bool o8 = wl <= 8;
+    if (acc_bits == 32 && o8) hipLaunchKernelGGL((requant_fit_kernel<int32_t, int8_t>), dim3(grid2), block, 0, ctx->stream, a);
+    else if (acc_bits == 32) hipLaunchKernelGGL((requant_fit_kernel<int32_t, int16_t>), dim3(grid2), block, 0, ctx->stream, a);
+    else if (o8) hipLaunchKernelGGL((requant_fit_kernel<int64_t, int8_t>), dim3(grid2), block, 0, ctx->stream, a);
+    else hipLaunchKernelGGL((requant_fit_kernel<int64_t, int16_t>), dim3(grid2), block, 0, ctx->stream, a);
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *b, adapt_fmt fb, size_t n,
+                                  adapt_fmt fo, adapt_rng rng, int relu, void *out)
+{
+    if (!ctx || !fmt_ok(fa) || !fmt_ok(fb) || !fmt_ok(fo) || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
+    if (n == 0) return ADAPT_OK;
+    if (!a || !b || !out || !aligned16(a) || !aligned16(b) || !aligned16(out)) return ADAPT_EINVAL;
+    const int f = std::max(fa.fl, fb.fl);
+    AddArgs p;
+    p.a = a; p.b = b; p.out = out; p.n = n; p.sa = f - fa.fl; p.sb = f - fb.fl; p.shift = f - fo.fl; p.wl = fo.wl;
+    p.relu = relu != 0; p.mode = rng.mode; p.seed = rng.seed; p.stream = rng.stream;
+    const dim3 grid(ew_grid(ctx, ((uint64_t)n + 7) >> 3)), block(kEwThreads);
+    const int sel = (storage_bytes(fa) == 2) * 4 + (storage_bytes(fb) == 2) * 2 + (storage_bytes(fo) == 2);
+#define ADAPT_ADD(TA, TB, TO) hipLaunchKernelGGL((residual_add_kernel<TA, TB, TO>), grid, block, 0, ctx->stream, p)
+    switch (sel) {
+    case 0: ADAPT_ADD(int8_t, int8_t, int8_t); break;
+    case 1: ADAPT_ADD(int8_t, int8_t, int16_t); break;
+    case 2: ADAPT_ADD(int8_t, int16_t, int8_t); break;
+    case 3: ADAPT_ADD(int8_t, int16_t, int16_t); break;
+    case 4: ADAPT_ADD(int16_t, int8_t, int8_t); break;
+    case 5: ADAPT_ADD(int16_t, int8_t, int16_t); break;
+    case 6: ADAPT_ADD(int16_t, int16_t, int8_t); break;
+    default: ADAPT_ADD(int16_t, int16_t, int16_t); break;
+    }
+#undef ADAPT_ADD
+    return hip_status(ctx, hipGetLastError());
+}
+
+// ---------------------------------------------------------------------------------------------
+// the chained step
+// ---------------------------------------------------------------------------------------------
+
+namespace {
+
+constexpr int kMaxLayers = 64;
+constexpr size_t kStatBytes = 64;      // per layer: the adapt_net_stats record
+
+struct NetLayer {
+    adapt_layer_desc d;
+    adapt_fmt fmt;
+    float *w;                 // master weights (caller's)
+    int p, q;                 // contraction output size
+    size_t n_y, n_a, n_in, n_w;
+    size_t off_y, off_a, off_dy, off_da, off_qw, off_g, off_stat;
+};
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Lays the workspace out; returns 0 for an invalid network.
+size_t plan_net(const adapt_layer_desc *descs, int count, std::vector<NetLayer> &L, size_t &off_in, size_t &off_accx,
+                size_t &off_accw)
+{
+    if (!descs || count < 1 || count > kMaxLayers) return 0;
+    L.assign(count, NetLayer());
+    size_t off = 0, max_in = 0, max_w = 0;
+    auto take = [&off](size_t bytes) { const size_t o = off; off += align_up(std::max<size_t>(bytes, 16)); return o; };
+    const int n = descs[0].conv.n;
+    if (n < 1) return 0;
+    for (int l = 0; l < count; ++l) {
+        const adapt_conv_desc &c = descs[l].conv;
+        if (c.n != n || c.h < 1 || c.w < 1 || c.c < 1 || c.k < 1 || c.r < 1 || c.s < 1 || c.stride < 1 || c.pad < 0) return 0;
+        if (c.h + 2 * c.pad < c.r || c.w + 2 * c.pad < c.s) return 0;
+        NetLayer &y = L[l];
+        y.d = descs[l];
+        y.fmt = adapt_fmt{8, 4};
+        y.w = nullptr;
+        y.p = (c.h + 2 * c.pad - c.r) / c.stride + 1;
+        y.q = (c.w + 2 * c.pad - c.s) / c.stride + 1;
+        if (y.d.pool && ((y.p | y.q) & 1)) return 0;
+        y.n_in = (size_t)n * c.h * c.w * c.c;
+        y.n_y = (size_t)n * y.p * y.q * c.k;
+        y.n_a = y.d.pool ? y.n_y / 4 : y.n_y;
+        y.n_w = (size_t)c.k * c.r * c.s * c.c;
+        if (l > 0 && L[l - 1].n_a != y.n_in) return 0;            // the output of a layer is the next one's input
+        // every code buffer holds int16 storage, so a layer may change its word length later
+        y.off_y = take(2 * y.n_y);
+        y.off_a = y.d.pool ? take(2 * y.n_a) : y.off_y;
+        y.off_dy = (y.d.pool || y.d.relu) ? take(2 * y.n_y) : 0;
+        y.off_da = take(2 * y.n_a);
+        if (!(y.d.pool || y.d.relu)) y.off_dy = y.off_da;
+        y.off_qw = take(2 * y.n_w);
+        y.off_g = take(2 * y.n_w);
+        y.off_stat = take(kStatBytes);
+        if (l > 0) max_in = std::max(max_in, y.n_in);
+        max_w = std::max(max_w, y.n_w);
+    }
+    off_in = take(2 * L[0].n_in);
+    off_accx = take(8 * max_in);
+    off_accw = take(8 * max_w);
+    return off;
+}
+
+}  // namespace
+
+struct adapt_net {
+    adapt_ctx *ctx;
+    std::vector<NetLayer> L;
+    char *ws;
+    size_t off_in, off_accx, off_accw, bytes;
+    bool forward_done;
+};
+
+namespace {
+
+adapt_rng slot_rng(adapt_rng r, int layer, int slot)
+{
+    r.stream += (uint64_t)(8 * layer + slot);
+    return r;
+}
+
+adapt_epilogue exact_ep()
+{
+    adapt_epilogue e = {};
+    e.raw = 1;
+    e.fmt = adapt_fmt{8, 0};
+    e.rng.mode = ADAPT_RN_HALF_UP;
+    return e;
+}
+
+}  // namespace
+
+extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count)
+{
+    std::vector<NetLayer> L;
+    size_t a, b, c;
+    return plan_net(layers, count, L, a, b, c);
+}
+
+extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
+                                void *workspace, size_t workspace_bytes, adapt_net **out)
+{
+    if (!ctx || !out || !weights || !workspace || ((uintptr_t)workspace & 255)) return ADAPT_EINVAL;
+    adapt_net *net = new (std::nothrow) adapt_net();
+    if (!net) return ADAPT_EINVAL;
+    net->ctx = ctx;
+    net->ws = static_cast<char *>(workspace);
+    net->forward_done = false;
+    net->bytes = plan_net(layers, count, net->L, net->off_in, net->off_accx, net->off_accw);
+    bool ok = net->bytes != 0 && net->bytes <= workspace_bytes;
+    for (int l = 0; ok && l < count; ++l) {
+        net->L[l].w = weights[l];
+        ok = weights[l] != nullptr && aligned16(weights[l]);
+    }
+    if (!ok) {
+        const int s = (net->bytes != 0 && net->bytes > workspace_bytes) ? ADAPT_EWORKSPACE : ADAPT_EINVAL;
+        delete net;
+        return s;
+    }
+    *out = net;
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_net_destroy(adapt_net *net)
+{
+    delete net;
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_net_set_format(adapt_net *net, int layer, adapt_fmt f)
+{
+    if (!net || layer < 0 || layer >= (int)net->L.size() || !fmt_ok(f)) return ADAPT_EINVAL;
+    net->L[layer].fmt = f;
+    net->forward_done = false;
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_net_tensor(const adapt_net *net, int layer, int which, size_t *offset, size_t *count, int *elem_bytes)
+{
+    if (!net || !offset || !count || !elem_bytes || layer < 0 || layer >= (int)net->L.size()) return ADAPT_EINVAL;
+    const NetLayer &y = net->L[layer];
+    const int es = storage_bytes(y.fmt);
+    switch (which) {
+    case ADAPT_NT_INPUT: *offset = net->off_in; *count = net->L[0].n_in; *elem_bytes = storage_bytes(net->L[0].fmt); break;
+    case ADAPT_NT_Y: *offset = y.off_y; *count = y.n_y; *elem_bytes = es; break;
+    case ADAPT_NT_A: *offset = y.off_a; *count = y.n_a; *elem_bytes = es; break;
+    case ADAPT_NT_DY: *offset = y.off_dy; *count = y.n_y; *elem_bytes = es; break;
+    case ADAPT_NT_DA: *offset = y.off_da; *count = y.n_a; *elem_bytes = es; break;
+    case ADAPT_NT_QW: *offset = y.off_qw; *count = y.n_w; *elem_bytes = es; break;
+    case ADAPT_NT_G: *offset = y.off_g; *count = y.n_w; *elem_bytes = es; break;
+    case ADAPT_NT_STATS: *offset = y.off_stat; *count = 1; *elem_bytes = (int)sizeof(adapt_net_stats); break;
+    default: return ADAPT_EINVAL;
+    }
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_net_quantize_weights(adapt_net *net, adapt_rng rng)
+{
+    if (!net || !rng_ok(rng)) return ADAPT_EINVAL;
+    const int count = (int)net->L.size();
+    adapt_quantize_item items[kMaxLayers];
+    for (int l = 0; l < count; ++l) {
+        const NetLayer &y = net->L[l];
+        items[l].x = y.w;
+        items[l].q = net->ws + y.off_qw;
+        items[l].n = y.n_w;
+        items[l].wl = y.fmt.wl;
+        items[l].fl = y.fmt.fl;
+        items[l].stream = rng.stream + (uint64_t)(8 * l + 5);
+    }
+    return adapt_quantize_batched(net->ctx, items, count, rng.mode, rng.seed, nullptr);
+}
+
+extern "C" int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng)
+{
+    if (!net || !x || !aligned16(x) || !rng_ok(rng)) return ADAPT_EINVAL;
+    adapt_ctx *ctx = net->ctx;
+    const int count = (int)net->L.size();
+    net->forward_done = false;
+    if (int s = adapt_quantize(ctx, x, net->L[0].n_in, net->L[0].fmt, slot_rng(rng, 0, 4), net->ws + net->off_in, nullptr, nullptr))
+        return s;
+    const void *cur = net->ws + net->off_in;
+    adapt_fmt fcur = net->L[0].fmt;
+    for (int l = 0; l < count; ++l) {
+        const NetLayer &y = net->L[l];
+        adapt_epilogue ep = {};
+        ep.raw = 0;
+        ep.fmt = y.fmt;
+        ep.rng = slot_rng(rng, l, 0);
+        ep.relu = y.d.relu != 0;
+        if (int s = adapt_conv_fwd(ctx, y.d.conv, cur, fcur, net->ws + y.off_qw, y.fmt, net->ws + y.off_y, ep)) return s;
+        if (y.d.pool)
+            if (int s = adapt_maxpool2_fwd(ctx, net->ws + y.off_y, y.fmt, y.d.conv.n, y.p, y.q, y.d.conv.k, net->ws + y.off_a)) return s;
+        cur = net->ws + y.off_a;
+        fcur = y.fmt;
+    }
+    net->forward_done = true;
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, adapt_rng rng)
+{
+    if (!net || !dlogits || !aligned16(dlogits) || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (!net->forward_done) return ADAPT_EINVAL;
+    adapt_ctx *ctx = net->ctx;
+    const int count = (int)net->L.size();
+    const adapt_epilogue ex = exact_ep();
+    for (int l = count - 1; l >= 0; --l) {
+        const NetLayer &y = net->L[l];
+        const adapt_conv_desc &c = y.d.conv;
+        const void *da = (l == count - 1) ? dlogits : net->ws + y.off_da;
+        const void *dy = da;
+        if (y.d.relu || y.d.pool) {
+            if (int s = adapt_relu_pool_bwd(ctx, da, net->ws + y.off_y, y.fmt, c.n, y.p, y.q, c.k, y.d.relu, y.d.pool, net->ws + y.off_dy))
+                return s;
+            dy = net->ws + y.off_dy;
+        }
+        const adapt_fmt fdy = {y.fmt.wl, 0};                       // gradient codes of the layer's word length
+        const adapt_fmt fin = l > 0 ? net->L[l - 1].fmt : net->L[0].fmt;
+        const void *a_prev = l > 0 ? net->ws + net->L[l - 1].off_a : net->ws + net->off_in;
+        char *accw = net->ws + net->off_accw, *accx = net->ws + net->off_accx;
+        adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
+        if (l > 0) {
+            if (int s = adapt_conv_backward(ctx, c, dy, fdy, net->ws + y.off_qw, y.fmt, a_prev, fin, accx, ex, accw, ex)) return s;
+        } else {
+            if (int s = adapt_conv_wgrad(ctx, c, dy, fdy, a_prev, fin, accw, ex)) return s;
+        }
+        const int bits_w = adapt_acc_bits((int64_t)c.n * y.p * y.q, fdy, fin);
+        if (int s = adapt_requantize_fit(ctx, accw, bits_w, y.n_w, y.fmt.wl, slot_rng(rng, l, 2), net->ws + y.off_g, &st->shift_w,
+                                         &st->g_sumsq))
+            return s;
+        if (l > 0) {
+            const int bits_x = adapt_acc_bits((int64_t)c.r * c.s * c.k, fdy, y.fmt);
+            if (int s = adapt_requantize_fit(ctx, accx, bits_x, y.n_in, net->L[l - 1].fmt.wl, slot_rng(rng, l, 1),
+                                             net->ws + net->L[l - 1].off_da, &st->shift_a, nullptr))
+                return s;
+        }
+    }
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng rng)
+{
+    if (!net || !rng_ok(rng)) return ADAPT_EINVAL;
+    const int count = (int)net->L.size();
+    for (int l = 0; l < count; ++l) {
+        const NetLayer &y = net->L[l];
+        adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
+        const adapt_fmt fg = {y.fmt.wl, 0};
+        if (int s = adapt_sgd_update_quantize(net->ctx, y.w, y.n_w, net->ws + y.off_g, fg, &st->g_sumsq, opt, y.fmt,
+                                              slot_rng(rng, l, 3), net->ws + y.off_qw, &st->nnz, &st->range_lo))
+            return s;
+    }
+    net->forward_done = false;
+    return ADAPT_OK;
+}

@@ -29,51 +29,12 @@ struct SgdArgs {
     uint64_t seed, stream;
 };
 
-template <typename GT>
-__device__ __forceinline__ void load_codes8(const GT *g, uint64_t grp, int (&c)[8]);
-template <>
-__device__ __forceinline__ void load_codes8<int8_t>(const int8_t *g, uint64_t grp, int (&c)[8])
-{
-    const uint2 v = reinterpret_cast<const uint2 *>(g)[grp];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) c[j] = (int)(int8_t)((j < 4 ? v.x : v.y) >> (8 * (j & 3)));
-}
-template <>
-__device__ __forceinline__ void load_codes8<int16_t>(const int16_t *g, uint64_t grp, int (&c)[8])
-{
-    const uint4 v = reinterpret_cast<const uint4 *>(g)[grp];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) c[j] = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
-}
-
 __device__ __forceinline__ float sgd_one(float w, int c, float step, float lr, float l1, float l2)
 {
     const float s = w > 0.0f ? l1 : (w < 0.0f ? -l1 : 0.0f);
     const float d = __builtin_fmaf(l2, w, s);
     const float w1 = __builtin_fmaf(-step, (float)c, w);
     return __builtin_fmaf(-lr, d, w1);
-}
-
-template <typename OutT>
-__device__ __forceinline__ void store_codes8(OutT *q, uint64_t grp, const int (&v)[8]);
-template <>
-__device__ __forceinline__ void store_codes8<int8_t>(int8_t *q, uint64_t grp, const int (&v)[8])
-{
-    uint2 o;
-    o.x = (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)(v[3] & 0xff) << 24);
-    o.y = (uint32_t)(v[4] & 0xff) | ((uint32_t)(v[5] & 0xff) << 8) | ((uint32_t)(v[6] & 0xff) << 16) | ((uint32_t)(v[7] & 0xff) << 24);
-    reinterpret_cast<uint2 *>(q)[grp] = o;
-}
-template <>
-__device__ __forceinline__ void store_codes8<int16_t>(int16_t *q, uint64_t grp, const int (&v)[8])
-{
-    uint4 o;
-    o.x = (uint32_t)(v[0] & 0xffff) | ((uint32_t)v[1] << 16);
-    o.y = (uint32_t)(v[2] & 0xffff) | ((uint32_t)v[3] << 16);
-    o.z = (uint32_t)(v[4] & 0xffff) | ((uint32_t)v[5] << 16);
-    o.w = (uint32_t)(v[6] & 0xffff) | ((uint32_t)v[7] << 16);
-    reinterpret_cast<uint4 *>(q)[grp] = o;
 }
 
 // counts[2][grid] (nnz, saturated) and range[grid][2] (min, max of the finite new weights)

@@ -1,0 +1,216 @@
+"""GPU parity: the element-wise integer operations of a chained step and the chained step itself
+(Alg. 1 for one batch: forward pass on quantized layers, backward pass, update, Quantize) against
+the CPU oracle, bit for bit: codes, shifts, sums of squares, master weights, counters, ranges."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2107_13490_amd as pkg
+import workloads as wk
+from oracle import fxp_oracle as orc
+from oracle import net_oracle as no
+from paper_2107_13490_amd import ConvDesc, LayerDesc
+
+from gpu_util import ctx, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _dt(wl):
+    return np.int8 if wl <= 8 else np.int16
+
+
+def _codes(rng, shape, wl, zero_frac=0.0):
+    lim = 1 << (wl - 1)
+    a = rng.integers(-lim, lim, shape)
+    if zero_frac:
+        a[rng.random(shape) < zero_frac] = 0
+    return a.astype(_dt(wl))
+
+
+# ---- pooling --------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape", [(2, 4, 6, 16), (3, 8, 8, 64), (1, 2, 2, 3), (5, 6, 4, 24), (2, 32, 32, 64), (4, 2, 10, 7)])
+@pytest.mark.parametrize("wl", [3, 8, 12])
+def test_maxpool_forward(shape, wl):
+    rng = np.random.default_rng(sum(shape) + wl)
+    y = _codes(rng, shape, wl)
+    got = host(ctx().maxpool2_fwd(dev(y), wl))
+    assert np.array_equal(got.astype(np.int64), no.maxpool2(y))
+
+
+@pytest.mark.parametrize("shape", [(2, 4, 6, 16), (3, 8, 8, 64), (1, 2, 2, 3), (5, 6, 4, 24), (2, 16, 16, 192), (4, 2, 10, 7)])
+@pytest.mark.parametrize("wl", [2, 4, 8, 16])
+@pytest.mark.parametrize("relu,pool", [(True, True), (False, True), (True, False)])
+def test_relu_pool_backward(shape, wl, relu, pool):
+    rng = np.random.default_rng(sum(shape) + 7 * wl + relu + 2 * pool)
+    y = _codes(rng, shape, wl, zero_frac=0.3)            # low word lengths and zeros: many ties
+    if relu:
+        y = np.maximum(y, 0)
+    n, h, w, c = shape
+    da = _codes(rng, (n, h // 2, w // 2, c) if pool else shape, wl)
+    got = host(ctx().relu_pool_bwd(dev(da), dev(y), wl, relu, pool))
+    assert np.array_equal(got.astype(np.int64), no.relu_pool_bwd(da, y, relu, pool))
+
+
+def test_pooling_rejects_odd_maps_and_empty_batch_is_a_no_op():
+    y = dev(np.zeros((1, 3, 4, 16), np.int8))
+    with pytest.raises(pkg.AdaptError):
+        ctx().maxpool2_fwd(y, 8, out=dev(np.zeros((1, 1, 2, 16), np.int8)))
+    e = torch.empty((0, 4, 4, 16), dtype=torch.int8, device="cuda")
+    assert ctx().maxpool2_fwd(e, 8).shape == (0, 2, 2, 16)
+
+
+# ---- fitting requantization -----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n", [1, 5, 8, 9, 2048, 100003, (1 << 20) + 1])
+@pytest.mark.parametrize("bits,wl,mag", [(32, 8, 20), (32, 4, 30), (32, 12, 9), (64, 16, 45), (64, 8, 33), (32, 16, 14), (64, 2, 50)])
+def test_requantize_fit(n, bits, wl, mag):
+    rng = np.random.default_rng(n + wl + mag)
+    acc = np.rint(rng.standard_normal(n) * 2.0 ** (mag - 2)).astype(np.int64)
+    acc = np.clip(acc, -(1 << (bits - 2)), 1 << (bits - 2))
+    d = dev(acc.astype(np.int32 if bits == 32 else np.int64))
+    for mode in (pkg.SR, pkg.RN_HALF_UP):
+        q, sh, ss = ctx().requantize_fit(d, wl, mode=mode, seed=3, stream=n)
+        want, wsh, wss = no.requantize_fit(acc, wl, mode, 3, n)
+        assert int(sh.item()) == wsh
+        assert np.array_equal(host(q).astype(np.int64), want)
+        assert int(ss.item()) == wss
+
+
+def test_requantize_fit_degenerate_inputs():
+    z = dev(np.zeros(100, np.int32))
+    q, sh, ss = ctx().requantize_fit(z, 8)
+    assert int(sh.item()) == 0 and int(ss.item()) == 0 and not host(q).any()
+    small = dev(np.array([-128, 127, 5], np.int32))            # 128 needs 8 magnitude bits: shift 1
+    q, sh, ss = ctx().requantize_fit(small, 8, mode=pkg.RN_HALF_UP)
+    want, wsh, wss = no.requantize_fit(np.array([-128, 127, 5]), 8, orc.RN_HALF_UP)
+    assert int(sh.item()) == wsh == 1 and host(q).tolist() == want.tolist() and int(ss.item()) == wss
+    e = torch.empty(0, dtype=torch.int32, device="cuda")
+    q, sh, ss = ctx().requantize_fit(e, 8)
+    assert int(sh.item()) == 0 and int(ss.item()) == 0
+    # the second call in a row starts its sum from zero again
+    big = dev(np.full(4096, 1000, np.int32))
+    _, _, s1 = ctx().requantize_fit(big, 8)
+    _, _, s2 = ctx().requantize_fit(big, 8)
+    assert int(s1.item()) == int(s2.item())
+
+
+# ---- residual addition ----------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n", [3, 8, 1000, 65537])
+@pytest.mark.parametrize("fa,fb,fo", [((8, 5), (8, 5), (8, 5)), ((8, 3), (12, 9), (8, 4)), ((12, 9), (8, 3), (16, 12)),
+                                      ((16, 12), (16, 6), (8, 2)), ((8, 5), (8, 7), (12, 9)), ((16, 14), (8, 0), (16, 10)),
+                                      ((12, 4), (16, 12), (12, 6)), ((8, 6), (16, 8), (8, 6))])
+def test_residual_add(n, fa, fb, fo):
+    rng = np.random.default_rng(n + fa[1] + 3 * fb[1] + fo[0])
+    a, b = _codes(rng, n, fa[0]), _codes(rng, n, fb[0])
+    for relu in (False, True):
+        got = host(ctx().residual_add(dev(a), fa, dev(b), fb, fo, seed=5, stream=n, relu=relu))
+        want = no.residual_add(a, fa[1], b, fb[1], fo[0], fo[1], orc.SR, 5, n, relu)
+        assert np.array_equal(got.astype(np.int64), want)
+
+
+# ---- the chained step -----------------------------------------------------------------------------------
+
+def _run_chain(layers, fmts, n, seed, lr=0.05, l1=1e-4, l2=1e-3):
+    rng = np.random.default_rng(seed)
+    first = layers[0]
+    x = rng.standard_normal((n, first.h, first.w, first.c)).astype(np.float32)
+    ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * (1.5 / np.sqrt(L.r * L.s * L.c))).astype(np.float32) for L in layers]
+    descs = [LayerDesc(ConvDesc(n, L.h, L.w, L.c, L.k, L.r, L.s, L.stride, L.pad), int(L.relu), int(L.pool)) for L in layers]
+    wdev = [dev(w.copy()) for w in ws]
+    net = pkg.Net(ctx(), descs, wdev)
+    for l, (wl, fl) in enumerate(fmts):
+        net.set_format(l, wl, fl)
+    s0 = 1000 + seed
+    net.quantize_weights(seed=seed, stream=s0)
+    net.forward(dev(x), seed=seed, stream=s0)
+    wq = no.quantize_weights(layers, fmts, ws, seed, s0)
+    fwd = no.forward(layers, fmts, wq, x, seed, s0)
+    last = len(layers) - 1
+    assert np.array_equal(host(net.tensor(0, pkg.NT_INPUT)).astype(np.int64), fwd["a_in"].ravel())
+    for l in range(len(layers)):
+        assert np.array_equal(host(net.tensor(l, pkg.NT_QW)).astype(np.int64), wq[l].ravel()), l
+        assert np.array_equal(host(net.tensor(l, pkg.NT_Y)).astype(np.int64), fwd["y"][l].ravel()), l
+        assert np.array_equal(host(net.tensor(l, pkg.NT_A)).astype(np.int64), fwd["a"][l].ravel()), l
+    # loss gradient: computed once on the host from the (identical) logits, handed to both sides
+    wl_last, fl_last = fmts[last]
+    logits = fwd["a"][last].reshape(n, -1) / 2.0 ** fl_last
+    e = np.exp(logits - logits.max(axis=1, keepdims=True))
+    soft = e / e.sum(axis=1, keepdims=True)
+    soft[np.arange(n), rng.integers(0, soft.shape[1], n)] -= 1.0
+    lim = 1 << (wl_last - 1)
+    dl = np.clip(np.rint(soft * (lim - 1)), -lim, lim - 1).astype(_dt(wl_last))
+    net.backward(dev(dl), seed=seed, stream=s0)
+    bwd = no.backward(layers, fmts, wq, fwd, dl, seed, s0)
+    for l in range(len(layers)):
+        st = net.tensor(l, pkg.NT_STATS)
+        assert np.array_equal(host(net.tensor(l, pkg.NT_G)).astype(np.int64), bwd["g"][l].ravel()), l
+        assert st.shift_w == bwd["shift_w"][l] and st.g_sumsq == bwd["sumsq"][l], l
+        if layers[l].relu or layers[l].pool:
+            assert np.array_equal(host(net.tensor(l, pkg.NT_DY)).astype(np.int64), bwd["dy"][l].ravel()), l
+        if l > 0:
+            assert st.shift_a == bwd["shift_a"][l], l
+            assert np.array_equal(host(net.tensor(l - 1, pkg.NT_DA)).astype(np.int64), bwd["da"][l - 1].ravel()), l
+    net.update(lr, l1, l2, seed=seed, stream=s0)
+    upd = no.update(layers, fmts, ws, bwd, lr, l1, l2, seed, s0)
+    for l in range(len(layers)):
+        st = net.tensor(l, pkg.NT_STATS)
+        assert np.array_equal(host(wdev[l]).ravel().view(np.uint32), upd[l]["w"].view(np.uint32)), l
+        assert np.array_equal(host(net.tensor(l, pkg.NT_QW)).astype(np.int64), upd[l]["q"]), l
+        assert (st.nnz, st.saturated) == (upd[l]["nnz"], upd[l]["sat"]), l
+        assert (st.range_lo, st.range_hi) == (np.float32(upd[l]["lo"]), np.float32(upd[l]["hi"])), l
+    # a second forward pass runs on the updated codes
+    net.forward(dev(x), seed=seed, stream=s0 + 500)
+    wq2 = [u["q"].reshape(w.shape) for u, w in zip(upd, wq)]
+    fwd2 = no.forward(layers, fmts, wq2, x, seed, s0 + 500)
+    assert np.array_equal(host(net.tensor(last, pkg.NT_A)).astype(np.int64), fwd2["a"][last].ravel())
+    net.close()
+
+
+def _small_net():
+    return [no.Layer(8, 8, 4, 8, relu=True, pool=True),
+            no.Layer(4, 4, 8, 8, relu=True, pool=False),
+            no.Layer(1, 1, 128, 10, 1, 1, 1, 0, relu=False, pool=False)]
+
+
+@pytest.mark.parametrize("fmts", [[(8, 5), (8, 5), (8, 4)], [(8, 5), (12, 8), (6, 3)], [(16, 11), (4, 2), (12, 8)],
+                                  [(12, 9), (16, 12), (16, 10)]])
+def test_small_chain_all_tensors(fmts):
+    _run_chain(_small_net(), fmts, n=5, seed=sum(w for w, _ in fmts))
+
+
+def test_vgg_like_chain_with_wide_channels():
+    layers = [no.Layer(16, 16, 16, 64, relu=True, pool=False),
+              no.Layer(16, 16, 64, 64, relu=True, pool=True),
+              no.Layer(8, 8, 64, 128, relu=True, pool=True),
+              no.Layer(1, 1, 4 * 4 * 128, 256, 1, 1, 1, 0, relu=True, pool=False),
+              no.Layer(1, 1, 256, 10, 1, 1, 1, 0, relu=False, pool=False)]
+    _run_chain(layers, [(8, 5), (8, 5), (6, 4), (12, 8), (8, 4)], n=8, seed=21)
+
+
+def test_alexnet_cifar_chain_reduced_batch():
+    specs = wk.alexnet_cifar_layers(batch=2)
+    pools = {"conv1": True, "conv2": True, "conv5": True}
+    layers, fmts = [], []
+    for sp in specs:
+        s = sp.shape
+        layers.append(no.Layer(s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad, relu=sp.name != "fc8", pool=pools.get(sp.name, False)))
+        fmts.append((sp.wl, sp.fl))
+    _run_chain(layers, fmts, n=2, seed=4)
+
+
+def test_invalid_chains_are_rejected():
+    bad = [LayerDesc(ConvDesc(2, 8, 8, 4, 8, 3, 3, 1, 1), 1, 1), LayerDesc(ConvDesc(2, 8, 8, 8, 8, 3, 3, 1, 1), 1, 0)]   # 4x4 != 8x8
+    w = [dev(np.zeros((8, 3, 3, 4), np.float32)), dev(np.zeros((8, 3, 3, 8), np.float32))]
+    with pytest.raises(pkg.AdaptError):
+        pkg.Net(ctx(), bad, w)
+    odd = [LayerDesc(ConvDesc(2, 7, 7, 4, 8, 3, 3, 1, 1), 1, 1)]
+    with pytest.raises(pkg.AdaptError):
+        pkg.Net(ctx(), odd, w[:1])
+    ok = [LayerDesc(ConvDesc(2, 8, 8, 4, 8, 3, 3, 1, 1), 1, 1)]
+    net = pkg.Net(ctx(), ok, w[:1])
+    with pytest.raises(pkg.AdaptError):                    # backward before any forward pass
+        net.backward(dev(np.zeros((2, 4, 4, 8), np.int8)))
+    net.close()
