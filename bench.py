@@ -95,6 +95,62 @@ def next_rows(ctx, pkg, torch, w):
     return res
 
 
+def chained_step(ctx, pkg, torch, batch=128):
+    """The AlexNet-CIFAR layers of config 4 as one chained fixed-point training step (forward pass, backward
+    pass with fitted gradient codes, update + re-quantization), formats of config 4; device time per phase."""
+    import numpy as np
+    import workloads as wk
+    from paper_2107_13490_amd import ConvDesc, LayerDesc
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4)
+    descs, ws, fmts, macs = [], [], [], 0
+    for sp, relu, pool in wk.alexnet_cifar_chain(batch):
+        s = sp.shape
+        descs.append(LayerDesc(ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad), int(relu), int(pool)))
+        ws.append(torch.randn((s.k, s.r, s.s, s.c), device="cuda", generator=gen) * (1.5 / np.sqrt(s.r * s.s * s.c)))
+        fmts.append((sp.wl, sp.fl))
+        macs += s.macs
+    ctx = pkg.Context(workspace_bytes=1 << 30)          # split-K partial sums of the larger layers
+    net = pkg.Net(ctx, descs, ws)
+    for l, (wl, fl) in enumerate(fmts):
+        net.set_format(l, wl, fl)
+    x = torch.randn((batch, 32, 32, 3), device="cuda", generator=gen)
+    dl = torch.randint(-4, 4, (batch, 10), device="cuda", dtype=torch.int32, generator=gen).to(
+        torch.int8 if fmts[-1][0] <= 8 else torch.int16)
+    net.quantize_weights()
+
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def fwd():
+        net.forward(x)
+
+    def fwd_bwd():
+        net.forward(x)
+        net.backward(dl)
+
+    def full():
+        net.forward(x)
+        net.backward(dl)
+        net.update(0.01, 1e-5, 1e-4)
+    t_f, t_fb, t_all = timed(fwd), timed(fwd_bwd), timed(full)
+    ops = 2.0 * macs * 3 - 2.0 * wk.alexnet_cifar_layers(batch)[0].shape.macs       # no data gradient below the first layer
+    res = {"workload": f"AlexNet-CIFAR chain, batch {batch}, formats of configs[3]", "formats": fmts,
+           "forward_ms": t_f, "forward_backward_ms": t_fb, "step_ms": t_all, "useful_TOPS": ops / (t_all * 1e-3) / 1e12}
+    net.close()
+    ctx.close()
+    return res
+
+
 def other_config(args, cfg):
     """Configs 1, 3, 4 and 5 (supplementary lines; the default run is config 2).  A step is, for every
     layer of the config, quantize(X, W, dY) + fwd + backward (dgrad + wgrad; requantized with SR), then ONE
@@ -208,6 +264,8 @@ def other_config(args, cfg):
         "kld_GBps": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9,
         "kld_frac_hbm": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
     }
+    if cfg == 4:
+        out["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
     if not args.no_cpu_baseline and sample_layer is not None:
         out["cpu_baseline"] = cpu_baseline_layer(sample_layer, args.cpu_batch)
     print(json.dumps(out))
@@ -404,6 +462,7 @@ def main():
     out["quantize_cold_frac_hbm"] = out["quantize_cold_GBps"] / PEAK_HBM_GBPS
     del sets
     out["next_rows"] = next_rows(ctx, pkg, torch, w)
+    out["next_rows"]["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_batch)
     print(json.dumps(out))

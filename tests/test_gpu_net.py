@@ -191,12 +191,10 @@ def test_vgg_like_chain_with_wide_channels():
 
 
 def test_alexnet_cifar_chain_reduced_batch():
-    specs = wk.alexnet_cifar_layers(batch=2)
-    pools = {"conv1": True, "conv2": True, "conv5": True}
     layers, fmts = [], []
-    for sp in specs:
+    for sp, relu, pool in wk.alexnet_cifar_chain(batch=2):
         s = sp.shape
-        layers.append(no.Layer(s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad, relu=sp.name != "fc8", pool=pools.get(sp.name, False)))
+        layers.append(no.Layer(s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad, relu=relu, pool=pool))
         fmts.append((sp.wl, sp.fl))
     _run_chain(layers, fmts, n=2, seed=4)
 

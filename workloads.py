@@ -138,6 +138,13 @@ def alexnet_cifar_layers(batch: int = 128, seed: int = 4) -> list[LayerSpec]:
     return out
 
 
+def alexnet_cifar_chain(batch: int = 128, seed: int = 4):
+    """The same eight layers as a feed-forward chain: (spec, relu, pool) per layer; 2x2/2 max-pooling after
+    conv1, conv2 and conv5 takes 32x32 down to the 4x4x256 = 4096 inputs of fc6; no ReLU on the logits."""
+    pooled = {"conv1", "conv2", "conv5"}
+    return [(sp, sp.name != "fc8", sp.name in pooled) for sp in alexnet_cifar_layers(batch, seed)]
+
+
 def resnet18_cifar_layers(batch: int = 256, seed: int = 5) -> list[LayerSpec]:
     """ResNet-18 at CIFAR resolution (about 11.2 M weights), 30% zero weights, WL uniform in 4..16."""
     g = _rng(seed, 0)
