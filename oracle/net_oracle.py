@@ -201,3 +201,91 @@ def update(layers, fmts, weights, bwd, lr: float, l1: float, l2: float, seed: in
         out.append(so.sgd_update_quantize(np.asarray(w, np.float32).ravel(), bwd["g"][l].ravel(), 0, lr, l1, l2, wl, fl,
                                           orc.SR, seed, stream_of(stream0, l, SLOT_UPD), normalize=True))
     return out
+
+
+# ---- the precision switch inside the chain (Alg. 2) ------------------------------------------------------
+#
+# Alg. 2 runs between the pass that produces the quantized gradients and the update.  The text leaves the
+# bookkeeping open; taken here:
+#   * the loss history excludes the current batch; L_avg is the mean of its last ceil(mean_l lb^l) entries
+#     (all of them if fewer; with an empty history the strategy is left alone)
+#   * a layer's window keeps at most lb_upr gradients (oldest dropped); the diversity of the batch uses its
+#     most recent min(len, lb^l) entries, lb^l before this batch's adaptation
+#   * a gradient tensor of the chain is codes * 2^-e with an exponent e that follows from the fitting shifts:
+#         e(dy_last) = FL of the loss gradient handed in
+#         e(g_l)     = e(dy_l) + FL(a_{l-1}) - shift_w(l)
+#         e(dy_{l-1}) = e(dy_l) + FL(W^_l) - shift_a(l)
+#     only differences inside a window matter (the diversity is a ratio): FL_k = e_k - min_k e_k
+#   * when len(window) >= lb^l (after adaptation): PushDown = the KL search on the master weights over
+#     WL_c = max(wl_lo, il) .. wl_hi with il = WL - FL integer bits kept and `resolution` bins, never above
+#     the current WL; PushUp = the closed-form suggestion; the window is emptied
+# --------------------------------------------------------------------------------------------------------
+from . import pushup_oracle as po  # noqa: E402
+
+SLOT_KLD = 6
+
+
+class SwitchState:
+    def __init__(self, nl: int, lb_lwr: int, lb_upr: int, lb_init: int, r_lwr: int, r_upr: int, r_init: int, gamma: float,
+                 eps: float, buff: int, wl_lo: int, wl_hi: int, strategy: int = po.ST_MIN):
+        self.p = dict(lb_lwr=lb_lwr, lb_upr=lb_upr, r_lwr=r_lwr, r_upr=r_upr, gamma=gamma, eps=eps, buff=buff, wl_lo=wl_lo,
+                      wl_hi=wl_hi)
+        self.lb = [lb_init] * nl
+        self.res = [r_init] * nl
+        self.windows = [[] for _ in range(nl)]            # entries (codes, wl, exponent)
+        self.strategy = strategy
+        self.losses = []
+
+
+def gradient_exponents(fmts, bwd, dlogits_fl: int):
+    """Fractional-bit count e(g_l) of every layer's weight-gradient codes for one backward pass."""
+    nl = len(fmts)
+    e_dy = dlogits_fl
+    out = [0] * nl
+    for l in range(nl - 1, -1, -1):
+        fl_in = fmts[l - 1][1] if l > 0 else fmts[0][1]
+        out[l] = e_dy + fl_in - bwd["shift_w"][l]
+        if l > 0:
+            e_dy = e_dy + fmts[l][1] - bwd["shift_a"][l]
+    return out
+
+
+def precision_switch(st: SwitchState, fmts, weights, bwd, dlogits_fl: int, loss: float, seed: int, stream0: int):
+    """One call of Alg. 2.  fmts is updated in place (list of (WL, FL)); returns a report per layer."""
+    import math
+    p = st.p
+    if st.losses:
+        k = min(len(st.losses), int(math.ceil(sum(st.lb) / len(st.lb))))
+        l_avg = sum(st.losses[-k:]) / k
+        st.strategy = po.adapt_strategy(st.strategy, l_avg, loss)
+    st.losses.append(loss)
+    exps = gradient_exponents(fmts, bwd, dlogits_fl)
+    report = []
+    for l, (wl, fl) in enumerate(fmts):
+        win = st.windows[l]
+        win.append((np.asarray(bwd["g"][l]).ravel().copy(), wl, exps[l]))
+        if len(win) > p["lb_upr"]:
+            win.pop(0)
+        use = win[-min(len(win), st.lb[l]):]
+        e_min = min(e for _, _, e in use)
+        gd = po.gradient_diversity_np([c for c, _, _ in use], [e - e_min for _, _, e in use])
+        ds = gd["ds"]
+        st.lb[l] = po.adapt_lookback(st.lb[l], ds, p["lb_lwr"], p["lb_upr"], p["gamma"])
+        st.res[l] = po.adapt_resolution(st.res[l], st.lb[l], p["lb_lwr"], p["lb_upr"], p["r_lwr"], p["r_upr"])
+        row = {"ds": ds, "lb": st.lb[l], "res": st.res[l], "switched": False, "wl_min": 0, "fl_min": 0}
+        if len(win) >= st.lb[l]:
+            il = wl - fl
+            lo = max(p["wl_lo"], il)
+            wl_min = wl
+            if lo <= p["wl_hi"]:
+                r = orc.kld_precision_search(np.asarray(weights[l], np.float32).ravel(), lo, p["wl_hi"], il, st.res[l], p["eps"],
+                                             seed=seed, stream=stream_of(stream0, l, SLOT_KLD))
+                wl_min = min(int(r["wl_sel"]), wl)
+            fl_min = wl_min - il
+            nw, nf, _, _, _ = po.pushup_suggest(ds, wl_min, fl_min, st.strategy, p["buff"], 16)
+            fmts[l] = (nw, nf)
+            win.clear()
+            row.update(switched=True, wl_min=wl_min, fl_min=fl_min)
+        row.update(wl=fmts[l][0], fl=fmts[l][1])
+        report.append(row)
+    return report

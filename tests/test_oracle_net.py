@@ -193,3 +193,69 @@ def test_update_moves_against_the_gradient_and_requantizes():
         assert float(step @ g) < 0 and abs(float(step @ g) / (np.linalg.norm(step) * np.linalg.norm(g)) + 1) < 1e-3
         q2, _, _ = orc.quantize(upd[l]["w"], fmts[l][0], fmts[l][1], orc.SR, 2, no.stream_of(0, l, no.SLOT_UPD))
         assert np.array_equal(upd[l]["q"], q2)
+
+
+def test_gradient_exponents_give_the_true_scale_of_the_gradient_codes():
+    """codes * 2^-e must be the floating-point network's gradient, not just parallel to it."""
+    rng = np.random.default_rng(7)
+    layers = _small_net()
+    n = 6
+    fmts = [(16, 10), (16, 11), (16, 9)]
+    x = rng.standard_normal((n, 8, 8, 4)).astype(np.float32)
+    ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * 0.2).astype(np.float32) for L in layers]
+    t = rng.standard_normal((n, 10))
+    wq = no.quantize_weights(layers, fmts, ws, 1, 100)
+    fwd = no.forward(layers, fmts, wq, x, 1, 100)
+    dl = np.round(t * 2 ** 11).astype(np.int64).reshape(n, 1, 1, 10)
+    bwd = no.backward(layers, fmts, wq, fwd, dl, 1, 100)
+    exps = no.gradient_exponents(fmts, bwd, 11)
+    tw = [torch.tensor(np.transpose(w.astype(np.float64), (0, 3, 1, 2)), requires_grad=True) for w in ws]
+    h = F.max_pool2d(F.relu(F.conv2d(_nchw(x.astype(np.float64)), tw[0], padding=1)), 2)
+    h = F.relu(F.conv2d(h, tw[1], padding=1))
+    logits = F.conv2d(h.permute(0, 2, 3, 1).reshape(n, 128, 1, 1), tw[2])
+    (logits.reshape(n, 10) * torch.tensor(t)).sum().backward()
+    for l in range(3):
+        want = np.transpose(tw[l].grad.numpy(), (0, 2, 3, 1)).ravel()
+        got = bwd["g"][l].astype(np.float64).ravel() * 2.0 ** -exps[l]
+        assert abs(np.linalg.norm(got) / np.linalg.norm(want) - 1) < 0.05, (l, exps[l])     # a slip in an exponent is a factor 2
+        assert np.linalg.norm(got - want) < 0.1 * np.linalg.norm(want)      # rounding noise of the 16-bit chain
+
+
+def test_precision_switch_bookkeeping_over_several_batches():
+    from oracle import pushup_oracle as po
+    rng = np.random.default_rng(8)
+    layers = _small_net()
+    n = 4
+    fmts = [(8, 5), (8, 5), (8, 4)]
+    ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * 0.3).astype(np.float32) for L in layers]
+    st = no.SwitchState(3, lb_lwr=2, lb_upr=4, lb_init=2, r_lwr=50, r_upr=60, r_init=55, gamma=0.5, eps=1e-2, buff=2, wl_lo=2,
+                        wl_hi=16)
+    wq = no.quantize_weights(layers, fmts, ws, 3, 0)
+    switched_any = False
+    for step in range(6):
+        x = rng.standard_normal((n, 8, 8, 4)).astype(np.float32)
+        fwd = no.forward(layers, fmts, wq, x, 3, 100 * step)
+        dl = rng.integers(-60, 60, (n, 1, 1, 10))
+        bwd = no.backward(layers, fmts, wq, fwd, dl, 3, 100 * step)
+        before = [len(w) for w in st.windows]
+        old = list(fmts)
+        rep = no.precision_switch(st, fmts, ws, bwd, 7, 2.0 - 0.1 * step, 3, 100 * step)
+        assert len(st.losses) == step + 1
+        for l, row in enumerate(rep):
+            assert 2 <= row["lb"] <= 4 and 50 <= row["res"] <= 60
+            assert row["ds"] >= 1.0 - 1e-12 or not np.isfinite(row["ds"])        # triangle inequality
+            if row["switched"]:
+                switched_any = True
+                assert st.windows[l] == [] and before[l] + 1 >= row["lb"]
+                assert row["wl_min"] <= old[l][0] and row["wl_min"] - row["fl_min"] == old[l][0] - old[l][1]
+                want = po.pushup_suggest(row["ds"], row["wl_min"], row["fl_min"], st.strategy, 2, 16)
+                assert fmts[l] == (want[0], want[1]) and fmts[l][0] >= fmts[l][1] + 2
+            else:
+                assert fmts[l] == old[l] and len(st.windows[l]) == min(before[l] + 1, 4)
+        # the loss falls every batch: after the first comparison the strategy is "min"
+        if step >= 1:
+            assert st.strategy == po.ST_MIN
+        upd = no.update(layers, fmts, ws, bwd, 0.05, 0.0, 0.0, 3, 100 * step)
+        ws = [u["w"].reshape(w.shape) for u, w in zip(upd, ws)]
+        wq = [u["q"].reshape(w.shape) for u, w in zip(upd, ws)]
+    assert switched_any
