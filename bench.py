@@ -136,11 +136,11 @@ def chained_step(ctx, pkg, torch, batch=128):
 
     def fwd_bwd():
         net.forward(x)
-        net.backward(dl)
+        net.backward(dl, 0)
 
     def full():
         net.forward(x)
-        net.backward(dl)
+        net.backward(dl, 0)
         net.update(0.01, 1e-5, 1e-4)
     t_f, t_fb, t_all = timed(fwd), timed(fwd_bwd), timed(full)
     ops = 2.0 * macs * 3 - 2.0 * wk.alexnet_cifar_layers(batch)[0].shape.macs       # no data gradient below the first layer

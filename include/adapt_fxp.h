@@ -348,17 +348,33 @@ enum { ADAPT_NT_INPUT = 0,   /* quantized network input (layer ignored) */
        ADAPT_NT_G = 6,       /* weight-gradient codes */
        ADAPT_NT_STATS = 7 }; /* adapt_net_stats */
 
+/* Hyper-parameters of the precision switch (Sec. 3.3 "Strategy, Resolution and Lookback"): bounds and
+ * start values of the lookback lb^l and the resolution r^l (the number of bins of the KL search),
+ * the lookback momentum gamma, the KL threshold eps, the buffer bits, the candidate word lengths
+ * of PushDown and the start strategy (ADAPT_ST_*).  1 <= lb_lwr <= lb_init <= lb_upr <= 64,
+ * 2 <= r_lwr <= r_init <= r_upr <= 65536, 0 <= gamma <= 1, eps >= 0, 1 <= buff <= 15,
+ * 2 <= wl_lo <= wl_hi <= 16. */
+typedef struct {
+    int lb_lwr, lb_upr, lb_init;
+    int r_lwr, r_upr, r_init;
+    double gamma, eps;
+    int buff, wl_lo, wl_hi, strategy_init;
+} adapt_switch_params;
+
 /* Bytes of device workspace the chain needs (activations, gradients, codes of weights and
- * gradients at int16 storage so that word lengths may change, two accumulator buffers); 0 if the
- * description is invalid (count outside 1..64, unequal batch sizes, shapes that do not chain,
- * pooling of an odd-sized map). */
-size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count);
+ * gradients at int16 storage so that word lengths may change, two accumulator buffers, and lb_upr
+ * gradient tensors per layer for the lookback windows; lb_upr = 0 without precision switching);
+ * 0 if the description is invalid (count outside 1..64, unequal batch sizes, shapes that do not
+ * chain, pooling of an odd-sized map, lb_upr outside 0..64). */
+size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr);
 
 /* layers, weights: HOST arrays of `count` entries; weights[l] = device fp32 master weights of layer
- * l (KRSC), owned by the caller and updated in place by adapt_net_update.  workspace: device,
- * 256-byte aligned, owned by the caller, must outlive the net.  Formats start as <8,4>. */
+ * l (KRSC), owned by the caller and updated in place by adapt_net_update.  sp: HOST, or NULL for a
+ * chain without adapt_net_precision_switch.  workspace: device, 256-byte aligned, owned by the
+ * caller, must outlive the net.  Formats start as <8,4>. */
 int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
-                     float *const *weights, void *workspace, size_t workspace_bytes, adapt_net **net);
+                     float *const *weights, const adapt_switch_params *sp, void *workspace,
+                     size_t workspace_bytes, adapt_net **net);
 int adapt_net_destroy(adapt_net *net);
 /* <WL,FL> of layer l: its weights, its output activations, and (WL only) its gradients. */
 int adapt_net_set_format(adapt_net *net, int layer, adapt_fmt f);
@@ -369,7 +385,7 @@ int adapt_net_tensor(const adapt_net *net, int layer, int which, size_t *offset,
 
 /* Random streams: every call takes (mode, seed, stream0); layer l uses stream0 + 8 l + slot with
  * slot 0 = forward output, 1 = data gradient handed down, 2 = weight gradient, 3 = re-quantized
- * weights, 4 = network input (l = 0), 5 = first quantization of the weights.
+ * weights, 4 = network input (l = 0), 5 = first quantization of the weights, 6 = PushDown.
  * A call that fails returns the failing step's status; steps enqueued before it have run. */
 
 /* Quantize of every layer's master weights into its format (one launch). */
@@ -378,11 +394,37 @@ int adapt_net_quantize_weights(adapt_net *net, adapt_rng rng);
  * y = requantize(ReLU(conv(a, W^))) into the layer's format, a = maxpool(y). */
 int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng);
 /* dlogits: device codes (storage of the last layer's format, its word length) of the loss gradient
- * with respect to the last layer's output, any power-of-two scale.  Per layer, last to first:
- * dy = adapt_relu_pool_bwd(da, y); exact dW = wgrad(dy, a_prev) and, above the first layer, exact
- * da_prev = dgrad(dy, W^); both through adapt_requantize_fit (dW to the layer's word length, da_prev
- * to the previous layer's).  Needs a forward pass since the last format change or update. */
-int adapt_net_backward(adapt_net *net, const void *dlogits, adapt_rng rng);
+ * with respect to the last layer's output, dlogits_fl = their fractional bits (any scale works
+ * for the update; the precision switch compares gradients of several batches, so keep it
+ * consistent).  Per layer, last to first: dy = adapt_relu_pool_bwd(da, y); exact
+ * dW = wgrad(dy, a_prev) and, above the first layer, exact da_prev = dgrad(dy, W^); both through
+ * adapt_requantize_fit (dW to the layer's word length, da_prev to the previous layer's).  Needs a
+ * forward pass since the last format change or update. */
+int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogits_fl, adapt_rng rng);
+
+/* PrecisionSwitch (Alg. 2), between the backward pass and the update.  `loss` is this batch's loss.
+ *   strategy   adapt_strategy_next(strategy, mean of the last ceil(mean_l lb^l) earlier losses, loss);
+ *              unchanged on the first call
+ *   per layer  the weight-gradient codes join the layer's window (at most lb_upr entries, oldest
+ *              dropped) with the exponent that follows from the fitting shifts:
+ *                e(dy_last) = dlogits_fl, e(g_l) = e(dy_l) + FL(a_{l-1}) - shift_w(l),
+ *                e(dy_{l-1}) = e(dy_l) + FL(W^_l) - shift_a(l);
+ *              ds = adapt_gradient_diversity of the most recent min(len, lb^l) entries with
+ *              fl_k = e_k - min e (ADAPT_EUNSUPPORTED if they differ by more than 31);
+ *              lb^l = adapt_lookback_next, r^l = adapt_resolution_next;
+ *              if len >= lb^l: PushDown = adapt_kld_precision_search on the master weights with
+ *              il = WL - FL, candidates max(wl_lo, il)..wl_hi, r^l bins, stream slot 6, its
+ *              selection limited to the current WL; PushUp = adapt_pushup_suggest with wl_cap 16;
+ *              the layer takes the new format and its window is emptied.
+ * The call synchronises the stream (it reads shifts, diversities and selections back).  The update
+ * that follows quantizes the weights in the new formats; a forward pass is needed before the next
+ * backward pass.  report: HOST array of `count` entries or NULL; strategy: HOST or NULL. */
+typedef struct {
+    double ds;
+    int32_t wl, fl, lb, res, switched, wl_min, fl_min, reserved;
+} adapt_switch_report;
+int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng rng,
+                               adapt_switch_report *report, int *strategy);
 /* Per layer adapt_sgd_update_quantize with the gradient codes and their sum of squares (the step
  * has length lr per layer); writes the new weight codes and the stats record. */
 int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng rng);

@@ -6,7 +6,7 @@ memory and streams.  There is no CPU fallback: if the library is missing, loadin
 """
 from .binding import (  # noqa: F401
     NT_A, NT_DA, NT_DY, NT_G, NT_INPUT, NT_QW, NT_STATS, NT_Y, RN_HALF_UP, SR, ST_MAX, ST_MEAN, ST_MIN, AdaptError, Context,
-    ConvDesc, Epilogue, Fmt, LayerDesc, Net, NetStats, Rng, acc_bits,
+    ConvDesc, Epilogue, Fmt, LayerDesc, Net, NetStats, Rng, SwitchParams, SwitchReport, acc_bits,
     library_path, load_library, lookback_next, perf_model_size, perf_step_cost, perf_step_memory, perf_step_overhead,
     pushup_suggest, resolution_next, strategy_next,
 )

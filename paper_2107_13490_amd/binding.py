@@ -92,6 +92,19 @@ class NetStats(C.Structure):
 NT_INPUT, NT_Y, NT_A, NT_DY, NT_DA, NT_QW, NT_G, NT_STATS = range(8)
 
 
+class SwitchParams(C.Structure):
+    """Hyper-parameters of the precision switch (bounds and start values of lookback and resolution, lookback
+    momentum, KL threshold, buffer bits, PushDown candidates, start strategy)."""
+    _fields_ = [("lb_lwr", C.c_int), ("lb_upr", C.c_int), ("lb_init", C.c_int), ("r_lwr", C.c_int), ("r_upr", C.c_int),
+                ("r_init", C.c_int), ("gamma", C.c_double), ("eps", C.c_double), ("buff", C.c_int), ("wl_lo", C.c_int),
+                ("wl_hi", C.c_int), ("strategy_init", C.c_int)]
+
+
+class SwitchReport(C.Structure):
+    _fields_ = [("ds", C.c_double), ("wl", C.c_int32), ("fl", C.c_int32), ("lb", C.c_int32), ("res", C.c_int32),
+                ("switched", C.c_int32), ("wl_min", C.c_int32), ("fl_min", C.c_int32), ("reserved", C.c_int32)]
+
+
 class PushupResult(C.Structure):
     _fields_ = [("wl", C.c_int), ("fl", C.c_int), ("s1", C.c_int), ("s2", C.c_int), ("s", C.c_int)]
 
@@ -144,15 +157,16 @@ def load_library():
     lib.adapt_relu_pool_bwd.argtypes = [vp, vp, vp, Fmt, i, i, i, i, i, i, vp]
     lib.adapt_requantize_fit.argtypes = [vp, vp, i, sz, i, Rng, vp, vp, vp]
     lib.adapt_residual_add.argtypes = [vp, vp, Fmt, vp, Fmt, sz, Fmt, Rng, i, vp]
-    lib.adapt_net_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i]
+    lib.adapt_net_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i, i]
     lib.adapt_net_workspace_bytes.restype = sz
-    lib.adapt_net_create.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), vp, sz, C.POINTER(vp)]
+    lib.adapt_net_create.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), C.POINTER(SwitchParams), vp, sz, C.POINTER(vp)]
+    lib.adapt_net_precision_switch.argtypes = [vp, dbl, Rng, C.POINTER(SwitchReport), C.POINTER(i)]
     lib.adapt_net_destroy.argtypes = [vp]
     lib.adapt_net_set_format.argtypes = [vp, i, Fmt]
     lib.adapt_net_tensor.argtypes = [vp, i, i, C.POINTER(sz), C.POINTER(sz), C.POINTER(i)]
     lib.adapt_net_quantize_weights.argtypes = [vp, Rng]
     lib.adapt_net_forward.argtypes = [vp, vp, Rng]
-    lib.adapt_net_backward.argtypes = [vp, vp, Rng]
+    lib.adapt_net_backward.argtypes = [vp, vp, i, Rng]
     lib.adapt_net_update.argtypes = [vp, SgdParams, Rng]
     lib.adapt_gradient_diversity.argtypes = [vp, C.POINTER(GradItem), i, sz, vp, vp]
     lib.adapt_pushup_suggest.argtypes = [dbl, i, i, i, i, i, C.POINTER(PushupResult)]
@@ -497,20 +511,21 @@ class Net:
     """A chained fixed-point training step (adapt_net_*).  Holds the workspace tensor and the master
     weights (fp32 device tensors, KRSC, updated in place by update())."""
 
-    def __init__(self, ctx: Context, layers, weights):
+    def __init__(self, ctx: Context, layers, weights, switch: "SwitchParams | None" = None):
         import torch
         self._ctx, self._lib, self._torch = ctx, ctx._lib, torch
         self.layers = list(layers)
         self.weights = list(weights)
         n = len(self.layers)
         descs = (LayerDesc * n)(*self.layers)
-        need = self._lib.adapt_net_workspace_bytes(descs, n)
+        need = self._lib.adapt_net_workspace_bytes(descs, n, switch.lb_upr if switch is not None else 0)
         if need == 0:
             raise AdaptError(-1, "adapt_net_workspace_bytes")
         self.workspace = torch.zeros(need, dtype=torch.uint8, device=self.weights[0].device)
         wptrs = (C.c_void_p * n)(*[w.data_ptr() for w in self.weights])
         h = C.c_void_p()
-        _check(self._lib.adapt_net_create(ctx.handle, descs, n, wptrs, _ptr(self.workspace), need, C.byref(h)), "adapt_net_create")
+        _check(self._lib.adapt_net_create(ctx.handle, descs, n, wptrs, C.byref(switch) if switch is not None else None,
+                                          _ptr(self.workspace), need, C.byref(h)), "adapt_net_create")
         self._h = h
 
     def close(self):
@@ -543,8 +558,17 @@ class Net:
     def forward(self, x, mode=SR, seed=0, stream=0):
         _check(self._lib.adapt_net_forward(self._h, _ptr(x), Rng(mode, seed, stream)), "adapt_net_forward")
 
-    def backward(self, dlogits, mode=SR, seed=0, stream=0):
-        _check(self._lib.adapt_net_backward(self._h, _ptr(dlogits), Rng(mode, seed, stream)), "adapt_net_backward")
+    def backward(self, dlogits, dlogits_fl=0, mode=SR, seed=0, stream=0):
+        _check(self._lib.adapt_net_backward(self._h, _ptr(dlogits), dlogits_fl, Rng(mode, seed, stream)), "adapt_net_backward")
+
+    def precision_switch(self, loss, mode=SR, seed=0, stream=0):
+        """Alg. 2 between backward() and update().  Returns (list of SwitchReport per layer, strategy)."""
+        n = len(self.layers)
+        rep = (SwitchReport * n)()
+        st = C.c_int()
+        _check(self._lib.adapt_net_precision_switch(self._h, float(loss), Rng(mode, seed, stream), rep, C.byref(st)),
+               "adapt_net_precision_switch")
+        return list(rep), st.value
 
     def update(self, lr, l1=0.0, l2=0.0, mode=SR, seed=0, stream=0):
         _check(self._lib.adapt_net_update(self._h, SgdParams(lr, l1, l2), Rng(mode, seed, stream)), "adapt_net_update")

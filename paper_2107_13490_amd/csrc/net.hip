@@ -16,6 +16,7 @@
 // every output, 16-byte accesses); the chain itself is host code that enqueues this library's own
 // entry points on the context's stream.
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -430,21 +431,34 @@ struct NetLayer {
     float *w;                 // master weights (caller's)
     int p, q;                 // contraction output size
     size_t n_y, n_a, n_in, n_w;
-    size_t off_y, off_a, off_dy, off_da, off_qw, off_g, off_stat;
+    size_t off_y, off_a, off_dy, off_da, off_qw, off_g, off_stat, off_ring, off_ds, off_kld, off_sel;
+    // state of the last backward pass
+    int g_wl;                 // word length of the gradient codes in off_g
+    int fl_in, fl_w;          // FL of the layer's input activations and of its weight codes
+    // precision switch (Alg. 2)
+    int lb, res;
+    std::vector<int> win;     // ring slots of the window, oldest first
+    int slot_wl[64];
+    long long slot_exp[64];
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+constexpr size_t kKldStride = 128;      // bytes per layer for the KL values of up to 15 candidates
+
 // Lays the workspace out; returns 0 for an invalid network.
-size_t plan_net(const adapt_layer_desc *descs, int count, std::vector<NetLayer> &L, size_t &off_in, size_t &off_accx,
-                size_t &off_accw)
+size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vector<NetLayer> &L, size_t &off_in,
+                size_t &off_accx, size_t &off_accw, size_t &off_stats)
 {
-    if (!descs || count < 1 || count > kMaxLayers) return 0;
+    if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64) return 0;
     L.assign(count, NetLayer());
     size_t off = 0, max_in = 0, max_w = 0;
     auto take = [&off](size_t bytes) { const size_t o = off; off += align_up(std::max<size_t>(bytes, 16)); return o; };
     const int n = descs[0].conv.n;
     if (n < 1) return 0;
+    // records that the host reads back in one copy each: stats, diversities, selections, KL values
+    off_stats = take((size_t)count * kStatBytes);
+    const size_t off_ds = take((size_t)count * 16), off_sel = take((size_t)count * 8), off_kld = take((size_t)count * kKldStride);
     for (int l = 0; l < count; ++l) {
         const adapt_conv_desc &c = descs[l].conv;
         if (c.n != n || c.h < 1 || c.w < 1 || c.c < 1 || c.k < 1 || c.r < 1 || c.s < 1 || c.stride < 1 || c.pad < 0) return 0;
@@ -469,7 +483,12 @@ size_t plan_net(const adapt_layer_desc *descs, int count, std::vector<NetLayer> 
         if (!(y.d.pool || y.d.relu)) y.off_dy = y.off_da;
         y.off_qw = take(2 * y.n_w);
         y.off_g = take(2 * y.n_w);
-        y.off_stat = take(kStatBytes);
+        y.off_stat = off_stats + (size_t)l * kStatBytes;
+        y.off_ds = off_ds + (size_t)l * 16;
+        y.off_sel = off_sel + (size_t)l * 8;
+        y.off_kld = off_kld + (size_t)l * kKldStride;
+        y.off_ring = lb_upr ? take((size_t)lb_upr * align_up(2 * y.n_w)) : 0;
+        y.g_wl = 0;
         if (l > 0) max_in = std::max(max_in, y.n_in);
         max_w = std::max(max_w, y.n_w);
     }
@@ -485,8 +504,14 @@ struct adapt_net {
     adapt_ctx *ctx;
     std::vector<NetLayer> L;
     char *ws;
-    size_t off_in, off_accx, off_accw, bytes;
-    bool forward_done;
+    size_t off_in, off_accx, off_accw, off_stats, bytes;
+    bool forward_done, backward_done;
+    int dlogits_fl;
+    // precision switch
+    bool has_switch;
+    adapt_switch_params sp;
+    int strategy;
+    std::vector<double> losses;
 };
 
 namespace {
@@ -508,26 +533,42 @@ adapt_epilogue exact_ep()
 
 }  // namespace
 
-extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count)
+static bool switch_params_ok(const adapt_switch_params &p)
+{
+    if (p.lb_lwr < 1 || p.lb_upr < p.lb_lwr || p.lb_upr > 64 || p.lb_init < p.lb_lwr || p.lb_init > p.lb_upr) return false;
+    if (p.r_lwr < 2 || p.r_upr < p.r_lwr || p.r_upr > 65536 || p.r_init < p.r_lwr || p.r_init > p.r_upr) return false;
+    if (!(p.gamma >= 0.0 && p.gamma <= 1.0) || !(p.eps >= 0.0)) return false;
+    if (p.buff < 1 || p.buff > 15 || p.wl_lo < 2 || p.wl_hi < p.wl_lo || p.wl_hi > 16) return false;
+    return p.strategy_init >= ADAPT_ST_MIN && p.strategy_init <= ADAPT_ST_MAX;
+}
+
+extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr)
 {
     std::vector<NetLayer> L;
-    size_t a, b, c;
-    return plan_net(layers, count, L, a, b, c);
+    size_t a, b, c, d;
+    return plan_net(layers, count, lb_upr, L, a, b, c, d);
 }
 
 extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
-                                void *workspace, size_t workspace_bytes, adapt_net **out)
+                                const adapt_switch_params *sp, void *workspace, size_t workspace_bytes, adapt_net **out)
 {
     if (!ctx || !out || !weights || !workspace || ((uintptr_t)workspace & 255)) return ADAPT_EINVAL;
+    if (sp && !switch_params_ok(*sp)) return ADAPT_EINVAL;
     adapt_net *net = new (std::nothrow) adapt_net();
     if (!net) return ADAPT_EINVAL;
     net->ctx = ctx;
     net->ws = static_cast<char *>(workspace);
-    net->forward_done = false;
-    net->bytes = plan_net(layers, count, net->L, net->off_in, net->off_accx, net->off_accw);
+    net->forward_done = net->backward_done = false;
+    net->dlogits_fl = 0;
+    net->has_switch = sp != nullptr;
+    if (sp) net->sp = *sp;
+    net->strategy = sp ? sp->strategy_init : ADAPT_ST_MIN;
+    net->bytes = plan_net(layers, count, sp ? sp->lb_upr : 0, net->L, net->off_in, net->off_accx, net->off_accw, net->off_stats);
     bool ok = net->bytes != 0 && net->bytes <= workspace_bytes;
     for (int l = 0; ok && l < count; ++l) {
         net->L[l].w = weights[l];
+        net->L[l].lb = sp ? sp->lb_init : 0;
+        net->L[l].res = sp ? sp->r_init : 0;
         ok = weights[l] != nullptr && aligned16(weights[l]);
     }
     if (!ok) {
@@ -549,7 +590,7 @@ extern "C" int adapt_net_set_format(adapt_net *net, int layer, adapt_fmt f)
 {
     if (!net || layer < 0 || layer >= (int)net->L.size() || !fmt_ok(f)) return ADAPT_EINVAL;
     net->L[layer].fmt = f;
-    net->forward_done = false;
+    net->forward_done = net->backward_done = false;
     return ADAPT_OK;
 }
 
@@ -565,7 +606,7 @@ extern "C" int adapt_net_tensor(const adapt_net *net, int layer, int which, size
     case ADAPT_NT_DY: *offset = y.off_dy; *count = y.n_y; *elem_bytes = es; break;
     case ADAPT_NT_DA: *offset = y.off_da; *count = y.n_a; *elem_bytes = es; break;
     case ADAPT_NT_QW: *offset = y.off_qw; *count = y.n_w; *elem_bytes = es; break;
-    case ADAPT_NT_G: *offset = y.off_g; *count = y.n_w; *elem_bytes = es; break;
+    case ADAPT_NT_G: *offset = y.off_g; *count = y.n_w; *elem_bytes = y.g_wl ? (y.g_wl <= 8 ? 1 : 2) : es; break;
     case ADAPT_NT_STATS: *offset = y.off_stat; *count = 1; *elem_bytes = (int)sizeof(adapt_net_stats); break;
     default: return ADAPT_EINVAL;
     }
@@ -594,7 +635,7 @@ extern "C" int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng)
     if (!net || !x || !aligned16(x) || !rng_ok(rng)) return ADAPT_EINVAL;
     adapt_ctx *ctx = net->ctx;
     const int count = (int)net->L.size();
-    net->forward_done = false;
+    net->forward_done = net->backward_done = false;
     if (int s = adapt_quantize(ctx, x, net->L[0].n_in, net->L[0].fmt, slot_rng(rng, 0, 4), net->ws + net->off_in, nullptr, nullptr))
         return s;
     const void *cur = net->ws + net->off_in;
@@ -616,15 +657,17 @@ extern "C" int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng)
     return ADAPT_OK;
 }
 
-extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, adapt_rng rng)
+extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogits_fl, adapt_rng rng)
 {
     if (!net || !dlogits || !aligned16(dlogits) || !rng_ok(rng)) return ADAPT_EINVAL;
     if (!net->forward_done) return ADAPT_EINVAL;
     adapt_ctx *ctx = net->ctx;
     const int count = (int)net->L.size();
     const adapt_epilogue ex = exact_ep();
+    net->backward_done = false;
+    net->dlogits_fl = dlogits_fl;
     for (int l = count - 1; l >= 0; --l) {
-        const NetLayer &y = net->L[l];
+        NetLayer &y = net->L[l];
         const adapt_conv_desc &c = y.d.conv;
         const void *da = (l == count - 1) ? dlogits : net->ws + y.off_da;
         const void *dy = da;
@@ -636,6 +679,9 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, adapt_rng
         const adapt_fmt fdy = {y.fmt.wl, 0};                       // gradient codes of the layer's word length
         const adapt_fmt fin = l > 0 ? net->L[l - 1].fmt : net->L[0].fmt;
         const void *a_prev = l > 0 ? net->ws + net->L[l - 1].off_a : net->ws + net->off_in;
+        y.g_wl = y.fmt.wl;
+        y.fl_in = fin.fl;
+        y.fl_w = y.fmt.fl;
         char *accw = net->ws + net->off_accw, *accx = net->ws + net->off_accx;
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
         if (l > 0) {
@@ -654,6 +700,131 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, adapt_rng
                 return s;
         }
     }
+    net->backward_done = true;
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng rng, adapt_switch_report *report, int *strategy)
+{
+    if (!net || !net->has_switch || !net->backward_done || !rng_ok(rng) || !(loss == loss)) return ADAPT_EINVAL;
+    adapt_ctx *ctx = net->ctx;
+    const adapt_switch_params &sp = net->sp;
+    const int count = (int)net->L.size();
+    // strategy from the loss history (the current batch excluded)
+    if (!net->losses.empty()) {
+        long long lb_sum = 0;
+        for (const NetLayer &y : net->L) lb_sum += y.lb;
+        const size_t k = std::min<size_t>(net->losses.size(), (size_t)std::ceil((double)lb_sum / (double)count));
+        double acc = 0.0;
+        for (size_t i = net->losses.size() - k; i < net->losses.size(); ++i) acc += net->losses[i];
+        net->strategy = adapt_strategy_next(net->strategy, acc / (double)k, loss);
+    }
+    net->losses.push_back(loss);
+    if (strategy) *strategy = net->strategy;
+
+    // the fitting shifts of this backward pass give every gradient tensor its exponent
+    std::vector<adapt_net_stats> st(count);
+    hipError_t e = hipMemcpyAsync(st.data(), net->ws + net->off_stats, (size_t)count * kStatBytes, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_status(ctx, e);
+    long long e_dy = net->dlogits_fl;
+    std::vector<long long> g_exp(count);
+    for (int l = count - 1; l >= 0; --l) {
+        const NetLayer &y = net->L[l];
+        g_exp[l] = e_dy + y.fl_in - st[l].shift_w;
+        if (l > 0) e_dy = e_dy + y.fl_w - st[l].shift_a;
+    }
+
+    // windows and diversities
+    for (int l = 0; l < count; ++l) {
+        NetLayer &y = net->L[l];
+        int slot;
+        if ((int)y.win.size() == sp.lb_upr) {                 // full: the oldest entry makes room
+            slot = y.win.front();
+            y.win.erase(y.win.begin());
+        } else {
+            bool used[64] = {};
+            for (int s2 : y.win) used[s2] = true;
+            slot = 0;
+            while (used[slot]) ++slot;
+        }
+        const size_t slot_bytes = align_up(2 * y.n_w);
+        e = hipMemcpyAsync(net->ws + y.off_ring + (size_t)slot * slot_bytes, net->ws + y.off_g,
+                           y.n_w * (size_t)(y.g_wl <= 8 ? 1 : 2), hipMemcpyDeviceToDevice, ctx->stream);
+        if (e != hipSuccess) return hip_status(ctx, e);
+        y.win.push_back(slot);
+        y.slot_wl[slot] = y.g_wl;
+        y.slot_exp[slot] = g_exp[l];
+        const int use = std::min<int>((int)y.win.size(), y.lb);
+        adapt_grad_item items[64];
+        long long e_min = 0;
+        for (int i = 0; i < use; ++i) {
+            const long long ex = y.slot_exp[y.win[y.win.size() - use + i]];
+            e_min = i == 0 ? ex : std::min(e_min, ex);
+        }
+        for (int i = 0; i < use; ++i) {
+            const int s2 = y.win[y.win.size() - use + i];
+            if (y.slot_exp[s2] - e_min > 31) return ADAPT_EUNSUPPORTED;      // scales too far apart for one exact sum
+            items[i].g = net->ws + y.off_ring + (size_t)s2 * slot_bytes;
+            items[i].wl = y.slot_wl[s2];
+            items[i].fl = (int32_t)(y.slot_exp[s2] - e_min);
+        }
+        if (int s = adapt_gradient_diversity(ctx, items, use, y.n_w, nullptr, reinterpret_cast<double *>(net->ws + y.off_ds)))
+            return s;
+    }
+    std::vector<double> ds(2 * (size_t)count);
+    e = hipMemcpyAsync(ds.data(), net->ws + net->L[0].off_ds, (size_t)count * 16, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_status(ctx, e);
+
+    // lookback, resolution; PushDown for the layers whose window is long enough
+    std::vector<int> lo_of(count, 0);
+    bool any = false;
+    for (int l = 0; l < count; ++l) {
+        NetLayer &y = net->L[l];
+        y.lb = adapt_lookback_next(y.lb, ds[2 * l], sp.lb_lwr, sp.lb_upr, sp.gamma);
+        y.res = adapt_resolution_next(y.res, y.lb, sp.lb_lwr, sp.lb_upr, sp.r_lwr, sp.r_upr);
+        if (report) {
+            report[l] = adapt_switch_report{};
+            report[l].ds = ds[2 * l];
+            report[l].lb = y.lb;
+            report[l].res = y.res;
+        }
+        if ((int)y.win.size() < y.lb) continue;
+        const int il = y.fmt.wl - y.fmt.fl;
+        if (il < 1) return ADAPT_EINVAL;
+        lo_of[l] = std::max(sp.wl_lo, il);
+        if (lo_of[l] <= sp.wl_hi) {
+            adapt_rng r = slot_rng(rng, l, 6);
+            if (int s = adapt_kld_precision_search(ctx, y.w, y.n_w, lo_of[l], sp.wl_hi, il, y.res, sp.eps, -1.0, r,
+                                                   reinterpret_cast<double *>(net->ws + y.off_kld),
+                                                   reinterpret_cast<int32_t *>(net->ws + y.off_sel), nullptr, nullptr))
+                return s;
+            any = true;
+        }
+    }
+    std::vector<int32_t> sel(2 * (size_t)count, 0);
+    if (any) {
+        e = hipMemcpyAsync(sel.data(), net->ws + net->L[0].off_sel, (size_t)count * 8, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) return hip_status(ctx, e);
+    }
+    for (int l = 0; l < count; ++l) {
+        NetLayer &y = net->L[l];
+        if ((int)y.win.size() >= y.lb) {
+            const int il = y.fmt.wl - y.fmt.fl;
+            int wl_min = y.fmt.wl;
+            if (lo_of[l] <= sp.wl_hi) wl_min = std::min<int>(sel[2 * l], y.fmt.wl);
+            const int fl_min = wl_min - il;
+            adapt_pushup_result r;
+            if (int s = adapt_pushup_suggest(ds[2 * l], wl_min, fl_min, net->strategy, sp.buff, 16, &r)) return s;
+            y.fmt = adapt_fmt{r.wl, r.fl};
+            y.win.clear();
+            net->forward_done = false;                   // activations of the old format no longer match
+            if (report) { report[l].switched = 1; report[l].wl_min = wl_min; report[l].fl_min = fl_min; }
+        }
+        if (report) { report[l].wl = y.fmt.wl; report[l].fl = y.fmt.fl; }
+    }
     return ADAPT_OK;
 }
 
@@ -664,11 +835,12 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
     for (int l = 0; l < count; ++l) {
         const NetLayer &y = net->L[l];
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
-        const adapt_fmt fg = {y.fmt.wl, 0};
+        if (y.g_wl == 0) return ADAPT_EINVAL;                        // no backward pass yet
+        const adapt_fmt fg = {y.g_wl, 0};                            // the gradient keeps the word length it was made with
         if (int s = adapt_sgd_update_quantize(net->ctx, y.w, y.n_w, net->ws + y.off_g, fg, &st->g_sumsq, opt, y.fmt,
                                               slot_rng(rng, l, 3), net->ws + y.off_qw, &st->nnz, &st->range_lo))
             return s;
     }
-    net->forward_done = false;
+    net->forward_done = net->backward_done = false;
     return ADAPT_OK;
 }

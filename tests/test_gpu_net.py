@@ -142,7 +142,7 @@ def _run_chain(layers, fmts, n, seed, lr=0.05, l1=1e-4, l2=1e-3):
     soft[np.arange(n), rng.integers(0, soft.shape[1], n)] -= 1.0
     lim = 1 << (wl_last - 1)
     dl = np.clip(np.rint(soft * (lim - 1)), -lim, lim - 1).astype(_dt(wl_last))
-    net.backward(dev(dl), seed=seed, stream=s0)
+    net.backward(dev(dl), 0, seed=seed, stream=s0)
     bwd = no.backward(layers, fmts, wq, fwd, dl, seed, s0)
     for l in range(len(layers)):
         st = net.tensor(l, pkg.NT_STATS)
@@ -210,5 +210,100 @@ def test_invalid_chains_are_rejected():
     ok = [LayerDesc(ConvDesc(2, 8, 8, 4, 8, 3, 3, 1, 1), 1, 1)]
     net = pkg.Net(ctx(), ok, w[:1])
     with pytest.raises(pkg.AdaptError):                    # backward before any forward pass
-        net.backward(dev(np.zeros((2, 4, 4, 8), np.int8)))
+        net.backward(dev(np.zeros((2, 4, 4, 8), np.int8)), 0)
+    net.close()
+
+
+# ---- the whole of Alg. 1 with the precision switch of Alg. 2 -----------------------------------------------
+
+def _train_with_switch(layers, fmts, n, steps, seed, sp_kw):
+    from oracle import pushup_oracle as po
+    rng = np.random.default_rng(seed)
+    first = layers[0]
+    ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * (1.5 / np.sqrt(L.r * L.s * L.c))).astype(np.float32) for L in layers]
+    descs = [LayerDesc(ConvDesc(n, L.h, L.w, L.c, L.k, L.r, L.s, L.stride, L.pad), int(L.relu), int(L.pool)) for L in layers]
+    wdev = [dev(w.copy()) for w in ws]
+    sp = pkg.SwitchParams(sp_kw["lb_lwr"], sp_kw["lb_upr"], sp_kw["lb_init"], sp_kw["r_lwr"], sp_kw["r_upr"], sp_kw["r_init"],
+                          sp_kw["gamma"], sp_kw["eps"], sp_kw["buff"], sp_kw["wl_lo"], sp_kw["wl_hi"], po.ST_MIN)
+    net = pkg.Net(ctx(), descs, wdev, switch=sp)
+    fmts = list(fmts)
+    for l, (wl, fl) in enumerate(fmts):
+        net.set_format(l, wl, fl)
+    st = no.SwitchState(len(layers), sp_kw["lb_lwr"], sp_kw["lb_upr"], sp_kw["lb_init"], sp_kw["r_lwr"], sp_kw["r_upr"],
+                        sp_kw["r_init"], sp_kw["gamma"], sp_kw["eps"], sp_kw["buff"], sp_kw["wl_lo"], sp_kw["wl_hi"])
+    net.quantize_weights(seed=seed, stream=5)
+    wq = no.quantize_weights(layers, fmts, ws, seed, 5)
+    last = len(layers) - 1
+    switches = 0
+    for step in range(steps):
+        s0 = 1000 * (step + 1)
+        x = rng.standard_normal((n, first.h, first.w, first.c)).astype(np.float32)
+        net.forward(dev(x), seed=seed, stream=s0)
+        fwd = no.forward(layers, fmts, wq, x, seed, s0)
+        got_logits = host(net.tensor(last, pkg.NT_A)).astype(np.int64)
+        assert np.array_equal(got_logits, fwd["a"][last].ravel()), step
+        wl_last, fl_last = fmts[last]
+        logits = fwd["a"][last].reshape(n, -1) / 2.0 ** fl_last
+        e = np.exp(logits - logits.max(axis=1, keepdims=True))
+        soft = e / e.sum(axis=1, keepdims=True)
+        labels = rng.integers(0, soft.shape[1], n)
+        loss = float(-np.mean(np.log(soft[np.arange(n), labels] + 1e-30)))
+        soft[np.arange(n), labels] -= 1.0
+        dl_fl = wl_last - 1                                           # gradient of the logits in [-1, 1): WL-1 fractional bits
+        lim = 1 << (wl_last - 1)
+        dl = np.clip(np.rint(soft * lim), -lim, lim - 1).astype(_dt(wl_last))
+        net.backward(dev(dl), dl_fl, seed=seed, stream=s0)
+        bwd = no.backward(layers, fmts, wq, fwd, dl, seed, s0)
+        rep, strat = net.precision_switch(loss, seed=seed, stream=s0)
+        want = no.precision_switch(st, fmts, ws, bwd, dl_fl, loss, seed, s0)
+        assert strat == st.strategy, step
+        for l, (r, w) in enumerate(zip(rep, want)):
+            if np.isfinite(w["ds"]):
+                assert abs(r.ds - w["ds"]) <= 1e-12 * abs(w["ds"]), (step, l)
+            else:
+                assert not np.isfinite(r.ds)
+            assert (r.lb, r.res, bool(r.switched), r.wl, r.fl) == (w["lb"], w["res"], w["switched"], w["wl"], w["fl"]), (step, l)
+            if w["switched"]:
+                switches += 1
+                assert (r.wl_min, r.fl_min) == (w["wl_min"], w["fl_min"]), (step, l)
+        net.update(0.05, 1e-5, 1e-4, seed=seed, stream=s0)
+        upd = no.update(layers, fmts, ws, bwd, 0.05, 1e-5, 1e-4, seed, s0)
+        for l in range(len(layers)):
+            assert np.array_equal(host(wdev[l]).ravel().view(np.uint32), upd[l]["w"].view(np.uint32)), (step, l)
+            assert np.array_equal(host(net.tensor(l, pkg.NT_QW)).astype(np.int64), upd[l]["q"]), (step, l)
+        ws = [u["w"].reshape(w.shape) for u, w in zip(upd, ws)]
+        wq = [u["q"].reshape(w.shape) for u, w in zip(upd, ws)]
+    net.close()
+    return switches, fmts
+
+
+def test_training_steps_with_precision_switching_follow_the_oracle():
+    kw = dict(lb_lwr=2, lb_upr=4, lb_init=2, r_lwr=50, r_upr=60, r_init=55, gamma=0.5, eps=1e-2, buff=2, wl_lo=2, wl_hi=16)
+    switches, fmts = _train_with_switch(_small_net(), [(8, 5), (8, 5), (8, 4)], n=6, steps=8, seed=31, sp_kw=kw)
+    assert switches >= 3
+
+
+def test_precision_switching_across_the_one_and_two_limb_boundary():
+    layers = [no.Layer(8, 8, 16, 32, relu=True, pool=True),
+              no.Layer(4, 4, 32, 32, relu=True, pool=False),
+              no.Layer(1, 1, 512, 16, 1, 1, 1, 0, relu=False, pool=False)]
+    kw = dict(lb_lwr=1, lb_upr=3, lb_init=1, r_lwr=100, r_upr=128, r_init=100, gamma=0.3, eps=1e-3, buff=3, wl_lo=4, wl_hi=16)
+    switches, fmts = _train_with_switch(layers, [(12, 9), (6, 3), (16, 12)], n=4, steps=6, seed=32, sp_kw=kw)
+    assert switches >= 3
+
+
+def test_precision_switch_needs_a_backward_pass_and_parameters():
+    ok = [LayerDesc(ConvDesc(2, 8, 8, 4, 8, 3, 3, 1, 1), 1, 1)]
+    w = [dev(np.zeros((8, 3, 3, 4), np.float32))]
+    net = pkg.Net(ctx(), ok, w)
+    with pytest.raises(pkg.AdaptError):
+        net.precision_switch(1.0)                         # created without switch parameters
+    net.close()
+    bad = pkg.SwitchParams(3, 2, 2, 50, 60, 55, 0.5, 1e-2, 2, 2, 16, 0)       # lb_lwr > lb_upr
+    with pytest.raises(pkg.AdaptError):
+        pkg.Net(ctx(), ok, w, switch=bad)
+    good = pkg.SwitchParams(2, 4, 2, 50, 60, 55, 0.5, 1e-2, 2, 2, 16, 0)
+    net = pkg.Net(ctx(), ok, w, switch=good)
+    with pytest.raises(pkg.AdaptError):
+        net.precision_switch(1.0)                         # no backward pass yet
     net.close()
