@@ -30,7 +30,7 @@ PEAK_HBM_GBPS = 8000.0
 # the summary with the commands is profiles/bench_config2_hbm_traffic.md.  Counters cannot be read
 # from inside this process.  Backward = the paired dgrad + wgrad kernel plus the slab-sum kernel.
 FWD_TRAFFIC_BYTES = {"read": 3283 * 1024, "written": 6144 * 1024}
-BWD_TRAFFIC_BYTES = {"read": (12697 + 7837) * 1024, "written": (9824 + 108) * 1024}
+BWD_TRAFFIC_BYTES = {"read": (12693 + 7837) * 1024, "written": (9824 + 108) * 1024}
 
 def cpu_baseline(batch: int):
     """The oracle, as it stands, on a bounded sample (reduced batch) of the same layer."""
@@ -297,6 +297,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="skip the measurements beyond the timed step (PushUp, fused update, chained step): for profiler runs")
     ap.add_argument("--cpu-batch", type=int, default=16)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (20 times): the known-size kernel that scales the "
@@ -461,8 +463,9 @@ def main():
     out["quantize_cold_GBps"] = q_bytes / (cold_ms * 1e-3) / 1e9
     out["quantize_cold_frac_hbm"] = out["quantize_cold_GBps"] / PEAK_HBM_GBPS
     del sets
-    out["next_rows"] = next_rows(ctx, pkg, torch, w)
-    out["next_rows"]["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
+    if not args.no_next_rows:
+        out["next_rows"] = next_rows(ctx, pkg, torch, w)
+        out["next_rows"]["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_batch)
     print(json.dumps(out))
