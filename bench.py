@@ -95,6 +95,43 @@ def next_rows(ctx, pkg, torch, w):
     return res
 
 
+def elementwise_rows(ctx, pkg, torch):
+    """Device time and algorithmic HBM rate of the chained step's element-wise kernels on tensors of the size
+    AlexNet-CIFAR's first layer produces at batch 128 (128 x 32 x 32 x 64 = 8.4 M elements).  Algorithmic bytes per
+    element: max-pool 1 read + 1/4 written (int8); pool/ReLU gradient 1 + 1/4 read, 1 written; fitting
+    requantization int32 -> int8: 4 read twice + 1 written; residual addition 1 + 1 read, 1 written."""
+    def timed(fn, reps=30):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    n, h, w, c = 128, 32, 32, 64
+    ne = n * h * w * c
+    y = torch.randint(0, 128, (n, h, w, c), dtype=torch.int8, device="cuda")
+    a = torch.empty((n, h // 2, w // 2, c), dtype=torch.int8, device="cuda")
+    da = torch.randint(-128, 128, a.shape, dtype=torch.int8, device="cuda")
+    dy = torch.empty_like(y)
+    acc = torch.randint(-(1 << 20), 1 << 20, (ne,), dtype=torch.int32, device="cuda")
+    q = torch.empty(ne, dtype=torch.int8, device="cuda")
+    b2 = torch.randint(-128, 128, (ne,), dtype=torch.int8, device="cuda")
+    rows = {}
+    for name, fn, bytes_per_call in (
+            ("maxpool2_fwd", lambda: ctx.maxpool2_fwd(y, 8, out=a), 1.25 * ne),
+            ("relu_pool_bwd", lambda: ctx.relu_pool_bwd(da, y, 8, True, True, out=dy), 2.25 * ne),
+            ("requantize_fit", lambda: ctx.requantize_fit(acc, 8, out=q), 9.0 * ne),
+            ("residual_add", lambda: ctx.residual_add(y.view(-1), (8, 5), b2, (8, 4), (8, 4), out=q), 3.0 * ne)):
+        ms = timed(fn)
+        rows[name] = {"ms": ms, "GBps": bytes_per_call / (ms * 1e-3) / 1e9, "frac_hbm": bytes_per_call / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    rows["elements"] = ne
+    return rows
+
+
 def chained_step(ctx, pkg, torch, batch=128):
     """The AlexNet-CIFAR layers of config 4 as one chained fixed-point training step (forward pass, backward
     pass with fitted gradient codes, update + re-quantization), formats of config 4; device time per phase."""
@@ -466,6 +503,7 @@ def main():
     if not args.no_next_rows:
         out["next_rows"] = next_rows(ctx, pkg, torch, w)
         out["next_rows"]["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
+        out["next_rows"]["chained_step_elementwise"] = elementwise_rows(ctx, pkg, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_batch)
     print(json.dumps(out))

@@ -180,6 +180,24 @@ struct FitArgs {
     unsigned long long *sumsq;
 };
 
+// The requantize rule for a shift that was fitted to the tensor: |acc| >> shift is below 2^(wl-1)
+// <= 2^15, so after one 64-bit shift everything is 32-bit arithmetic.  floor((acc + r') / 2^s) is
+// taken as (acc >> s) + carry of the dropped bits plus r', which cannot overflow.
+__device__ __forceinline__ int fit_one(long long acc, int shift, uint32_t r16, int qlo, int qhi)
+{
+    int q;
+    if (shift == 0) {
+        q = (int)acc;
+    } else if (shift <= 16) {
+        const uint32_t low = (uint32_t)acc & ((1u << shift) - 1u);
+        q = (int)(acc >> shift) + (int)((low + (r16 >> (16 - shift))) >> shift);
+    } else {
+        const int t = (int)(acc >> (shift - 16));            // |t| < 2^(wl-1+16) <= 2^31
+        q = (t >> 16) + (int)((((uint32_t)t & 0xffffu) + r16) >> 16);
+    }
+    return min(max(q, qlo), qhi);
+}
+
 // codes = requantize(acc, shift) with shift = max(0, bit_length(max |acc|) - (wl-1)); every block
 // derives the shift from the partial maxima itself
 template <typename AccT, typename OutT>
@@ -198,6 +216,7 @@ __global__ void __launch_bounds__(kEwThreads) requant_fit_kernel(const FitArgs a
     const int shift = max(0, bits - (a.wl - 1));
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.shift_out) *a.shift_out = shift;
     __syncthreads();                                    // sm is reused below
+    const int qhi = (1 << (a.wl - 1)) - 1, qlo = -(1 << (a.wl - 1));
 
     const AccT *acc = static_cast<const AccT *>(a.acc);
     OutT *q = static_cast<OutT *>(a.q);
@@ -219,16 +238,16 @@ __global__ void __launch_bounds__(kEwThreads) requant_fit_kernel(const FitArgs a
         int code[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            code[e] = requantize_one(v[e], shift, a.wl, 0, r[e]);
-            ss += (uint64_t)((long long)code[e] * code[e]);
+            code[e] = fit_one(v[e], shift, r[e], qlo, qhi);
+            ss += (uint32_t)(code[e] * code[e]);
         }
         store_codes8<OutT>(q, grp, code);
     }
     if ((a.n & 7) && first == 0)
         for (uint64_t i = groups << 3; i < a.n; ++i) {
-            const int c = requantize_one((long long)acc[i], shift, a.wl, 0, rounding_bits_of(a.seed, a.stream, i, a.mode));
+            const int c = fit_one((long long)acc[i], shift, rounding_bits_of(a.seed, a.stream, i, a.mode), qlo, qhi);
             q[i] = (OutT)c;
-            ss += (uint64_t)((long long)c * c);
+            ss += (uint32_t)(c * c);
         }
     if (a.sumsq) {
 #pragma unroll
@@ -370,7 +389,9 @@ extern "C" int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bit
     if (n > 0 && (!acc || !q || !aligned16(acc) || !aligned16(q))) return ADAPT_EINVAL;
     const uint64_t groups = ((uint64_t)n + 7) >> 3;
     const int grid1 = (int)std::min<uint64_t>(std::max<uint64_t>((groups + kEwThreads - 1) / kEwThreads, 1), (uint64_t)ctx->num_cu * 4);
-    const int grid2 = ew_grid(ctx, groups);
+    // Atomic additions to one address retire at about one per 10 ns on this chip, whoever issues them:
+    // with the sum of squares asked for, fewer and longer-running blocks keep that tail short.
+    const int grid2 = sumsq ? std::min(ew_grid(ctx, groups), ctx->num_cu * 2) : ew_grid(ctx, groups);
     if ((size_t)grid1 * 8 > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     uint64_t *part = reinterpret_cast<uint64_t *>(scratch(ctx));
     unsigned long long *ss = reinterpret_cast<unsigned long long *>(sumsq);
