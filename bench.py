@@ -148,7 +148,11 @@ def chained_step(ctx, pkg, torch, batch=128):
         fmts.append((sp.wl, sp.fl))
         macs += s.macs
     ctx = pkg.Context(workspace_bytes=1 << 30)          # split-K partial sums of the larger layers
-    net = pkg.Net(ctx, descs, ws)
+    # Alg. 2 with wide bounds on the formats so that the timing loop below keeps its layer formats close to
+    # config 4's (a switch changes a layer's word length by a bit or two)
+    sp = pkg.SwitchParams(lb_lwr=2, lb_upr=4, lb_init=2, r_lwr=100, r_upr=150, r_init=128, gamma=0.5, eps=1e-3, buff=3,
+                          wl_lo=4, wl_hi=16, strategy_init=pkg.ST_MIN)
+    net = pkg.Net(ctx, descs, ws, switch=sp)
     for l, (wl, fl) in enumerate(fmts):
         net.set_format(l, wl, fl)
     x = torch.randn((batch, 32, 32, 3), device="cuda", generator=gen)
@@ -180,9 +184,27 @@ def chained_step(ctx, pkg, torch, batch=128):
         net.backward(dl, 0)
         net.update(0.01, 1e-5, 1e-4)
     t_f, t_fb, t_all = timed(fwd), timed(fwd_bwd), timed(full)
+
+    # the precision switch between backward pass and update: wall time of the call (it synchronises three
+    # times and runs the diversity and KL kernels), over a few real steps so that windows fill and switches occur
+    import time
+    sw_ms, switched = [], 0
+    for step in range(8):
+        net.forward(x)
+        net.backward(dl, 0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rep, _ = net.precision_switch(2.0 - 0.1 * step, stream=100 * step)
+        sw_ms.append((time.perf_counter() - t0) * 1e3)
+        switched += sum(r.switched for r in rep)
+        net.update(0.01, 1e-5, 1e-4, stream=100 * step)
+    torch.cuda.synchronize()
     ops = 2.0 * macs * 3 - 2.0 * wk.alexnet_cifar_layers(batch)[0].shape.macs       # no data gradient below the first layer
     res = {"workload": f"AlexNet-CIFAR chain, batch {batch}, formats of configs[3]", "formats": fmts,
-           "forward_ms": t_f, "forward_backward_ms": t_fb, "step_ms": t_all, "useful_TOPS": ops / (t_all * 1e-3) / 1e12}
+           "forward_ms": t_f, "forward_backward_ms": t_fb, "step_ms": t_all, "useful_TOPS": ops / (t_all * 1e-3) / 1e12,
+           "precision_switch_ms_median": sorted(sw_ms)[len(sw_ms) // 2], "precision_switch_ms_max": max(sw_ms),
+           "layers_switched_in_8_steps": int(switched),
+           "formats_after": [(r.wl, r.fl) for r in rep]}
     net.close()
     ctx.close()
     return res
