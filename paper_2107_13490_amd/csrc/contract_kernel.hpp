@@ -995,7 +995,10 @@ static int pick_split_tile(const ContractArgs &a, int limbs, int acc_bits, int n
         const double operand = (double)a.K * (double)(tm * bm) * (double)(tn * bn) * (1.0 / bm + 1.0 / bn) * limbs *
                                (single ? 1.6 : 1.0);
         const double slab = sp > 1 ? 2.0 * (double)a.M * a.N * (acc_bits / 8) * sp : 0.0;
-        const double cost = operand * rounds / 10.7e12 + slab / 3.1e12 + (sp > 1 ? 5e-6 : 0.0);
+        // unsplit two-limb kernels with a large output and a short reduction (fully connected layers) are bound
+        // by their epilogue: about 0.5 T outputs/s with two resident blocks per CU, 0.28 T/s with one
+        const double epilogue = (limbs == 2 && sp == 1) ? (double)a.M * a.N / (single ? 0.28e12 : 0.5e12) : 0.0;
+        const double cost = operand * rounds / 10.7e12 + slab / 3.1e12 + (sp > 1 ? 5e-6 : 0.0) + epilogue;
         if (cost < best) { best = cost; best_splits = (int)sp; t.bm = bm; t.bn = bn; }
     }
     return best_splits;
@@ -1055,7 +1058,9 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     if (model_splits > 0) {
         splits = std::max(splits, model_splits);
     } else if (tiles < ctx->num_cu && a.K >= 8 * t.bkt) {
-        const long long want = (ctx->num_cu + tiles - 1) / tiles;
+        // few tiles and a long reduction (fully connected layers at training batch sizes): two blocks per
+        // CU hide each other's stage latencies (fc 128 x 4096 x 4096: 44 -> 34 us two-limb, 21 -> 19 one-limb)
+        const long long want = (2 * ctx->num_cu + tiles - 1) / tiles;
         const long long max_by_k = a.K / (4 * t.bkt);
         splits = (int)std::max<long long>(splits, std::min(want, std::max(1ll, max_by_k)));
     }
