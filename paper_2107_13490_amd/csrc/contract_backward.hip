@@ -25,14 +25,35 @@ extern "C" int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void
     if (!ctx || !fmt_ok(fdy) || !fmt_ok(fw) || !fmt_ok(fx) || !conv_ok(d)) return ADAPT_EINVAL;
     if (!dw || !aligned16(dw)) return ADAPT_EINVAL;
     if (d.n > 0 && (!check_ptrs(dy, w, dx) || !check_ptrs(dy, x, dw))) return ADAPT_EINVAL;
-    ContractArgs aw = {};
-    if (int s = fill_wgrad(aw, d, dy, fdy, x, fx, dw)) return s;
-    if (d.n == 0) return run_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0);      // dw = 0, no dx
-    ContractArgs ad = {};
-    if (int s = fill_dgrad(ad, d, dy, fdy, w, fw, dx)) return s;
+    if (!epilogue_ok(ep_dx) || !epilogue_ok(ep_dw)) return ADAPT_EINVAL;
+    ContractArgs aw = {}, ad = {};
     ContractPlan pd, pw;
-    if (int s = plan_contraction<OP_DGRAD>(ctx, ad, fdy, fw, ep_dx, 0, pd)) return s;
-    if (int s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0, pw)) return s;
+    bool planned = false;
+    if (d.c < kPadC && d.n > 0) {      // few input channels: zero-padded copies of x and w (see pad_channels)
+        size_t off = 0;
+        const void *xp, *wp;
+        if (pad_channels(ctx, x, storage_bytes(fx), (size_t)d.n * d.h * d.w, d.c, off, &xp) == ADAPT_OK &&
+            pad_channels(ctx, w, storage_bytes(fw), (size_t)d.k * d.r * d.s, d.c, off, &wp) == ADAPT_OK &&
+            fill_wgrad_padded(aw, d, dy, fdy, xp, fx, dw) == ADAPT_OK && fill_dgrad_padded(ad, d, dy, fdy, wp, fw, dx) == ADAPT_OK) {
+            int s = plan_contraction<OP_DGRAD>(ctx, ad, fdy, fw, ep_dx, off, pd);
+            if (s == ADAPT_OK) s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, off, pw);
+            if (s == ADAPT_OK) {
+                unpad_wgrad_finish(pw, d);
+                planned = true;
+            } else if (s != ADAPT_EWORKSPACE) {
+                return s;
+            }
+        }
+    }
+    if (!planned) {
+        aw = ContractArgs{};
+        ad = ContractArgs{};
+        if (int s = fill_wgrad(aw, d, dy, fdy, x, fx, dw)) return s;
+        if (d.n == 0) return run_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0);      // dw = 0, no dx
+        if (int s = fill_dgrad(ad, d, dy, fdy, w, fw, dx)) return s;
+        if (int s = plan_contraction<OP_DGRAD>(ctx, ad, fdy, fw, ep_dx, 0, pd)) return s;
+        if (int s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0, pw)) return s;
+    }
     hipError_t e = hipSuccess;
     bool paired = false;
     if (pairable(pd, true) && pairable(pw, false) && pd.limbs == pw.limbs) {

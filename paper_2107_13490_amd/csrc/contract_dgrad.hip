@@ -11,7 +11,18 @@ extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *d
     if (!ctx || !fmt_ok(fdy) || !fmt_ok(fw) || !conv_ok(d)) return ADAPT_EINVAL;
     if (d.n == 0) return ADAPT_OK;
     if (!check_ptrs(dy, w, dx)) return ADAPT_EINVAL;
+    if (!epilogue_ok(ep)) return ADAPT_EINVAL;
     ContractArgs a = {};
+    if (d.c < kPadC) {           // few input channels: the filters get zero channels appended (vector loads of their rows)
+        size_t off = 0;
+        const void *wp;
+        if (pad_channels(ctx, w, storage_bytes(fw), (size_t)d.k * d.r * d.s, d.c, off, &wp) == ADAPT_OK &&
+            fill_dgrad_padded(a, d, dy, fdy, wp, fw, dx) == ADAPT_OK) {
+            const int s = run_contraction<OP_DGRAD>(ctx, a, fdy, fw, ep, off);
+            if (s != ADAPT_EWORKSPACE) return s;
+        }
+        a = ContractArgs{};
+    }
     if (int s = fill_dgrad(a, d, dy, fdy, w, fw, dx)) return s;
     return run_contraction<OP_DGRAD>(ctx, a, fdy, fw, ep, 0);
 }

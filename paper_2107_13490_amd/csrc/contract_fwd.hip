@@ -11,17 +11,19 @@ extern "C" int adapt_conv_fwd(adapt_ctx *ctx, adapt_conv_desc d, const void *x, 
     if (!ctx || !fmt_ok(fx) || !fmt_ok(fw) || !conv_ok(d)) return ADAPT_EINVAL;
     if (d.n == 0) return ADAPT_OK;
     if (!check_ptrs(x, w, y)) return ADAPT_EINVAL;
+    if (!epilogue_ok(ep)) return ADAPT_EINVAL;
     ContractArgs a = {};
-    if (int s = fill_conv(a, d)) return s;
-    a.act = x; a.wgt = w; a.out = y;
-    a.M = d.n * a.p * a.q; a.N = d.k; a.K = d.r * d.s * d.c;
-    a.act_es = storage_bytes(fx); a.wgt_es = storage_bytes(fw);
-    a.act_bytes = (uint32_t)((long long)d.n * d.h * d.w * d.c * a.act_es);
-    a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);
-    a.act_load = d.c % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
-    a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
-    a.ldc = d.k;
-    a.uniform_tap = d.c % 64 == 0;
+    if (d.c < kPadC) {           // few input channels: run on zero-padded copies when the workspace holds them
+        size_t off = 0;
+        const void *xp, *wp;
+        if (pad_channels(ctx, x, storage_bytes(fx), (size_t)d.n * d.h * d.w, d.c, off, &xp) == ADAPT_OK &&
+            pad_channels(ctx, w, storage_bytes(fw), (size_t)d.k * d.r * d.s, d.c, off, &wp) == ADAPT_OK &&
+            fill_fwd_padded(a, d, xp, fx, wp, fw, y) == ADAPT_OK) {
+            const int s = run_contraction<OP_FWD>(ctx, a, fx, fw, ep, off);
+            if (s != ADAPT_EWORKSPACE) return s;
+        }
+        a = ContractArgs{};
+    }
+    if (int s = fill_fwd(a, d, x, fx, w, fw, y)) return s;
     return run_contraction<OP_FWD>(ctx, a, fx, fw, ep, 0);
 }
-

@@ -78,6 +78,10 @@ struct ContractArgs {
     int uniform_tap;             // 64 consecutive, 64-aligned k always lie in one filter tap
     int xcd_remap;               // contiguous ranges of blocks per XCD (see the kernel)
     int k_per_split;             // multiple of the kernel's stage depth
+    int k_bound;                 // reduction length that decides the accumulator type (0: K); smaller than K when
+                                 // zero channels were appended
+    int force_finish;            // always go through slabs and finish_kernel
+    int pad_c, pad_to;           // finish_kernel: the slabs hold pad_to channels per filter tap, the output pad_c (0: same)
     long long slab_bytes;        // split-K: split y writes its exact partial sums to out + y*slab_bytes
     long long ldc;               // output row stride in elements
     int out_mode;
@@ -803,18 +807,24 @@ __global__ void __launch_bounds__(256)
 finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 {
     const size_t total = (size_t)a.M * a.N;
+    const size_t slab = (size_t)a.slab_bytes / sizeof(AccT);        // elements per slab (more than total with appended channels)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t m = i / a.N, n = i % a.N;
+        size_t j = i;                                               // position inside a slab
+        if (a.pad_c) {
+            const size_t tap = n / a.pad_c, c = n - tap * a.pad_c;
+            j = m * ((size_t)a.N / a.pad_c * a.pad_to) + tap * a.pad_to + c;
+        }
         long long v = 0;
         int y = 0;
         for (; y + 8 <= splits; y += 8) {      // eight independent loads in flight
             AccT t[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = ws[(size_t)(y + u) * total + i];
+            for (int u = 0; u < 8; ++u) t[u] = ws[(size_t)(y + u) * slab + j];
 #pragma unroll
             for (int u = 0; u < 8; ++u) v += (long long)t[u];
         }
-        for (; y < splits; ++y) v += (long long)ws[(size_t)y * total + i];
-        const size_t m = i / a.N, n = i % a.N;
+        for (; y < splits; ++y) v += (long long)ws[(size_t)y * slab + j];
         const size_t o = m * (size_t)a.ldc + n;
         switch (a.out_mode) {
             case OUT_RAW32: static_cast<int32_t *>(a.out)[o] = (int32_t)v; break;
@@ -1021,7 +1031,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
                             size_t ws_offset /* bytes of scratch already in use */, ContractPlan &p)
 {
     const int limbs = (fa.wl > 8 || fb.wl > 8) ? 2 : 1;
-    const int bits = adapt_acc_bits(a.K, fa, fb);
+    const int bits = adapt_acc_bits(a.k_bound ? a.k_bound : a.K, fa, fb);
     int final_mode;
     if (ep.raw) {
         final_mode = bits == 32 ? OUT_RAW32 : OUT_RAW64;
@@ -1075,7 +1085,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     a.slab_bytes = 0;
     p.tile = t;
     p.splits = splits;
-    if (splits == 1) {
+    if (splits == 1 && !a.force_finish) {
         a.out_mode = final_mode;
         p.kern = a;
         return ADAPT_OK;
@@ -1094,6 +1104,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     p.kern.out_mode = bits == 32 ? OUT_RAW32 : OUT_RAW64;
     p.fin = a;
     p.fin.out_mode = final_mode;
+    p.fin.slab_bytes = (long long)slab;
     return ADAPT_OK;
 }
 
@@ -1107,7 +1118,7 @@ static hipError_t launch_planned(adapt_ctx *ctx, const ContractPlan &p)
 // the slab sum + epilogue of a split contraction
 static hipError_t finish_planned(adapt_ctx *ctx, const ContractPlan &p)
 {
-    if (p.empty || p.splits == 1) return hipSuccess;
+    if (p.empty || p.acc == nullptr) return hipSuccess;
     const unsigned fgrid = (unsigned)std::min<size_t>(((size_t)p.fin.M * p.fin.N + 255) / 256, (size_t)ctx->num_cu * 8);
     if (p.bits == 32)
         hipLaunchKernelGGL(finish_kernel<int32_t>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const int32_t *>(p.acc), p.splits, p.fin);
@@ -1124,6 +1135,58 @@ static int run_contraction(adapt_ctx *ctx, const ContractArgs &a, adapt_fmt fa, 
     hipError_t e = launch_planned<OP>(ctx, p);
     if (e == hipSuccess) e = finish_planned(ctx, p);
     return hip_status(ctx, e);
+}
+
+// ---- layers with few input channels ------------------------------------------------------------
+// The first layer of an image network has 3 input channels: too few for 16-byte operand loads, so
+// the contraction would gather element by element.  Such layers run on copies of x and w with
+// zero channels appended up to 16 (in the context's workspace): the zeros add nothing to any sum, the
+// outputs keep their logical shape and index (and with it their rounding bits), and the vector
+// paths apply.  Measured on 256 x 32 x 32 x 3 -> 64, <12,9>: fwd 90 -> 60 us, dgrad 277 -> 95, wgrad 104 -> 51.
+constexpr int kPadC = 16;
+
+template <typename T>
+__global__ void __launch_bounds__(256) pad_channels_kernel(const T *__restrict__ src, T *__restrict__ dst, const uint32_t rows, const int c)
+{
+    for (uint32_t r = blockIdx.x * 256 + threadIdx.x; r < rows; r += gridDim.x * 256) {
+        constexpr int PER = 4 / (int)sizeof(T);                      // codes per 32-bit word
+        uint32_t wds[kPadC / PER];
+#pragma unroll
+        for (int q = 0; q < kPadC / PER; ++q) wds[q] = 0;
+#pragma unroll
+        for (int e = 0; e < kPadC; ++e) {
+            const uint32_t v = e < c ? (uint32_t)src[(size_t)r * c + e] & (sizeof(T) == 1 ? 0xffu : 0xffffu) : 0u;
+            wds[e / PER] |= v << (8 * (int)sizeof(T) * (e % PER));
+        }
+        uint4 *o = reinterpret_cast<uint4 *>(dst + (size_t)r * kPadC);
+#pragma unroll
+        for (int q = 0; q < kPadC / PER / 4; ++q) o[q] = make_uint4(wds[4 * q], wds[4 * q + 1], wds[4 * q + 2], wds[4 * q + 3]);
+    }
+}
+
+// Appends zero channels to a [rows][c] tensor of es-byte codes; the copy lives at scratch + off, which is advanced.
+static int pad_channels(adapt_ctx *ctx, const void *src, int es, size_t rows, int c, size_t &off, const void **out)
+{
+    const size_t bytes = rows * kPadC * (size_t)es;
+    off = (off + 255) & ~(size_t)255;
+    if (rows >= ((size_t)1 << 31) || off + bytes > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    char *dst = scratch(ctx) + off;
+    const unsigned grid = (unsigned)std::min<size_t>(std::max<size_t>((rows + 255) / 256, 1), (size_t)ctx->num_cu * 8);
+    if (es == 1)
+        hipLaunchKernelGGL(pad_channels_kernel<int8_t>, dim3(grid), dim3(256), 0, ctx->stream, static_cast<const int8_t *>(src),
+                           reinterpret_cast<int8_t *>(dst), (uint32_t)rows, c);
+    else
+        hipLaunchKernelGGL(pad_channels_kernel<int16_t>, dim3(grid), dim3(256), 0, ctx->stream, static_cast<const int16_t *>(src),
+                           reinterpret_cast<int16_t *>(dst), (uint32_t)rows, c);
+    if (hipGetLastError() != hipSuccess) return ADAPT_EHIP;
+    *out = dst;
+    off += bytes;
+    return ADAPT_OK;
+}
+
+static bool epilogue_ok(const adapt_epilogue &ep)
+{
+    return ep.raw || (fmt_ok(ep.fmt) && (ep.rng.mode == ADAPT_SR || ep.rng.mode == ADAPT_RN_HALF_UP));
 }
 
 static bool conv_ok(const adapt_conv_desc &d)
@@ -1181,6 +1244,59 @@ static int fill_wgrad(ContractArgs &a, const adapt_conv_desc &d, const void *dy,
     a.wgt_load = (d.c % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR;
     a.ldc = a.N;
     return ADAPT_OK;
+}
+
+static int fill_fwd(ContractArgs &a, const adapt_conv_desc &d, const void *x, adapt_fmt fx, const void *w, adapt_fmt fw, void *y)
+{
+    if (int s = fill_conv(a, d)) return s;
+    a.act = x; a.wgt = w; a.out = y;
+    a.M = d.n * a.p * a.q; a.N = d.k; a.K = d.r * d.s * d.c;
+    a.act_es = storage_bytes(fx); a.wgt_es = storage_bytes(fw);
+    a.act_bytes = (uint32_t)((long long)d.n * d.h * d.w * d.c * a.act_es);
+    a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);
+    a.act_load = d.c % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
+    a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
+    a.ldc = d.k;
+    a.uniform_tap = d.c % 64 == 0;
+    return ADAPT_OK;
+}
+
+// The same contractions on operands with zero channels appended (see pad_channels): `wp` / `xp` hold kPadC channels.
+static int fill_fwd_padded(ContractArgs &a, const adapt_conv_desc &d, const void *xp, adapt_fmt fx, const void *wp, adapt_fmt fw, void *y)
+{
+    adapt_conv_desc d2 = d;
+    d2.c = kPadC;
+    if (int s = fill_fwd(a, d2, xp, fx, wp, fw, y)) return s;
+    a.k_bound = d.r * d.s * d.c;       // the caller's accumulator type follows the logical reduction length
+    return ADAPT_OK;
+}
+
+static int fill_dgrad_padded(ContractArgs &a, const adapt_conv_desc &d, const void *dy, adapt_fmt fdy, const void *wp, adapt_fmt fw, void *dx)
+{
+    if (int s = fill_dgrad(a, d, dy, fdy, wp, fw, dx)) return s;
+    a.c = kPadC;                       // stride of the filter rows; the output keeps d.c columns
+    a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * kPadC * a.wgt_es);
+    a.wgt_load = LOAD_ROWS;
+    return ADAPT_OK;
+}
+
+// Weight gradient on a padded x: the kernel fills slabs of r*s*kPadC columns, finish_kernel picks the d.c real ones.
+static int fill_wgrad_padded(ContractArgs &a, const adapt_conv_desc &d, const void *dy, adapt_fmt fdy, const void *xp, adapt_fmt fx, void *dw)
+{
+    adapt_conv_desc d2 = d;
+    d2.c = kPadC;
+    if (int s = fill_wgrad(a, d2, dy, fdy, xp, fx, dw)) return s;
+    a.force_finish = 1;
+    return ADAPT_OK;
+}
+
+static void unpad_wgrad_finish(ContractPlan &p, const adapt_conv_desc &d)
+{
+    if (p.empty) return;
+    p.fin.N = d.r * d.s * d.c;
+    p.fin.ldc = p.fin.N;
+    p.fin.pad_c = d.c;
+    p.fin.pad_to = kPadC;
 }
 
 static bool check_ptrs(const void *x, const void *y, const void *z) { return x && y && z && aligned16(x) && aligned16(y) && aligned16(z); }

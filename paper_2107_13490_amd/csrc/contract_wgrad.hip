@@ -11,7 +11,25 @@ extern "C" int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *d
     if (!ctx || !fmt_ok(fdy) || !fmt_ok(fx) || !conv_ok(d)) return ADAPT_EINVAL;
     if (!dw || !aligned16(dw)) return ADAPT_EINVAL;
     if (d.n > 0 && !check_ptrs(dy, x, dw)) return ADAPT_EINVAL;
+    if (!epilogue_ok(ep)) return ADAPT_EINVAL;
     ContractArgs a = {};
+    if (d.c < kPadC && d.n > 0) {      // few input channels: x gets zero channels appended, the finish kernel drops them again
+        size_t off = 0;
+        const void *xp;
+        ContractPlan p;
+        if (pad_channels(ctx, x, storage_bytes(fx), (size_t)d.n * d.h * d.w, d.c, off, &xp) == ADAPT_OK &&
+            fill_wgrad_padded(a, d, dy, fdy, xp, fx, dw) == ADAPT_OK) {
+            const int s = plan_contraction<OP_WGRAD>(ctx, a, fdy, fx, ep, off, p);
+            if (s == ADAPT_OK) {
+                unpad_wgrad_finish(p, d);
+                hipError_t e = launch_planned<OP_WGRAD>(ctx, p);
+                if (e == hipSuccess) e = finish_planned(ctx, p);
+                return hip_status(ctx, e);
+            }
+            if (s != ADAPT_EWORKSPACE) return s;
+        }
+        a = ContractArgs{};
+    }
     if (int s = fill_wgrad(a, d, dy, fdy, x, fx, dw)) return s;
     return run_contraction<OP_WGRAD>(ctx, a, fdy, fx, ep, 0);
 }

@@ -347,3 +347,61 @@ def test_backward_config2_full_size():
     for _ in range(3):
         dx2, dw2 = ctx().conv_backward(d, qdy, f, qw, f, qx, f, ep_dx, ep_dw)
         assert torch.equal(dx1, dx2) and torch.equal(dw1, dw2)
+
+
+# ---- layers with fewer than 16 input channels run on zero-padded copies --------------------------------------
+
+NARROW_CASES = [
+    (3, 12, 10, 3, 64, 3, 3, 1, 1),     # the first layer of an image network
+    (2, 9, 9, 1, 16, 3, 3, 1, 1),       # one channel
+    (2, 8, 8, 15, 24, 3, 3, 2, 1),      # just below the vector width, stride 2
+    (4, 6, 6, 5, 10, 1, 1, 1, 0),       # 1x1, nothing aligned
+    (1, 16, 16, 8, 32, 5, 5, 1, 2),
+]
+
+
+@pytest.mark.parametrize("case", NARROW_CASES)
+@pytest.mark.parametrize("wl", [8, 12])
+def test_narrow_layers_exact_and_requantized(case, wl):
+    n, h, w, c, k, r, s, st, pad = case
+    d = ConvDesc(n, h, w, c, k, r, s, st, pad)
+    x = codes((n, h, w, c), wl, 1)
+    wt = codes((k, r, s, c), wl, 2)
+    dy = codes((n, d.p, d.q, k), wl, 3)
+    f = (wl, wl - 3)
+    _conv_all(case, wl, wl, wl, extreme=True)
+    # requantized outputs: the rounding bits follow the logical output index, not the padded one
+    eps = [Epilogue.requant(wl, wl - 4, pkg.SR, 3, 30 + i, relu=(i == 0)) for i in range(3)]
+    sh = 2 * (wl - 3) - (wl - 4)
+    y = ctx().conv_fwd(d, to_dev(x), f, to_dev(wt), f, eps[0])
+    assert np.array_equal(host(y).astype(np.int64), orc.requantize(co.conv_fwd(x, wt, st, pad), sh, wl, orc.SR, 3, 30, True))
+    dx = ctx().conv_dgrad(d, to_dev(dy), f, to_dev(wt), f, eps[1])
+    assert np.array_equal(host(dx).astype(np.int64), orc.requantize(co.conv_dgrad(dy, wt, h, w, st, pad), sh, wl, orc.SR, 3, 31))
+    dw = ctx().conv_wgrad(d, to_dev(dy), f, to_dev(x), f, eps[2])
+    want_dw = orc.requantize(co.conv_wgrad(dy, x, r, s, st, pad), sh, wl, orc.SR, 3, 32)
+    assert np.array_equal(host(dw).astype(np.int64), want_dw)
+    dx2, dw2 = ctx().conv_backward(d, to_dev(dy), f, to_dev(wt), f, to_dev(x), f, eps[1], eps[2])
+    assert torch.equal(dx, dx2) and torch.equal(dw, dw2)
+
+
+def test_narrow_layer_accumulator_type_follows_the_logical_reduction():
+    # K = 3*3*3 = 27 fits int32 accumulators at <16,.> x <10,.>; the padded reduction (144) would not, and must not widen the output
+    d = ConvDesc(2, 8, 8, 3, 16, 3, 3, 1, 1)
+    fa, fb = (16, 8), (10, 5)
+    assert pkg.acc_bits(27, pkg.Fmt(*fa), pkg.Fmt(*fb)) == 32 and pkg.acc_bits(144, pkg.Fmt(*fa), pkg.Fmt(*fb)) == 64
+    x, wt = codes((2, 8, 8, 3), 16, 1, True), codes((16, 3, 3, 3), 10, 2, True)
+    y = ctx().conv_fwd(d, to_dev(x), fa, to_dev(wt), fb, Epilogue.exact())
+    assert y.dtype == torch.int32
+    assert np.array_equal(host(y).astype(np.int64), co.conv_fwd(x, wt, 1, 1))
+
+
+def test_narrow_layer_falls_back_when_the_workspace_is_small():
+    small = pkg.Context(workspace_bytes=1 << 16)            # 60 KiB of scratch: the padded input does not fit
+    n, h, w, c, k = 4, 32, 32, 3, 16
+    d = ConvDesc(n, h, w, c, k, 3, 3, 1, 1)
+    x, wt, dy = codes((n, h, w, c), 8, 1), codes((k, 3, 3, c), 8, 2), codes((n, h, w, k), 8, 3)
+    y = small.conv_fwd(d, to_dev(x), (8, 4), to_dev(wt), (8, 5), Epilogue.exact())
+    assert np.array_equal(host(y).astype(np.int64), co.conv_fwd(x, wt, 1, 1))
+    dx = small.conv_dgrad(d, to_dev(dy), (8, 4), to_dev(wt), (8, 5), Epilogue.exact())
+    assert np.array_equal(host(dx).astype(np.int64), co.conv_dgrad(dy, wt, h, w, 1, 1))
+    small.close()
