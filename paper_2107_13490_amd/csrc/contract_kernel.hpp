@@ -520,10 +520,15 @@ __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m
             rw[4 * h] = b.x; rw[4 * h + 1] = b.y; rw[4 * h + 2] = b.z; rw[4 * h + 3] = b.w;
         }
     } else {
+        // rows that do not start on a multiple of 8 (N not a multiple of 8): one Philox block per output,
+        // drawn only for the outputs that exist (a 3-channel data gradient has 3 of the 16)
 #pragma unroll
-        for (int i = 0; i < RUN / 2; ++i)
-            rw[i] = rounding_bits_of(a.seed, a.stream, idx0 + 2 * i, ADAPT_SR) |
-                    (rounding_bits_of(a.seed, a.stream, idx0 + 2 * i + 1, ADAPT_SR) << 16);
+        for (int i = 0; i < RUN / 2; ++i) {
+            rw[i] = 0;
+            if (2 * i < cnt)
+                rw[i] = rounding_bits_of(a.seed, a.stream, idx0 + 2 * i, ADAPT_SR) |
+                        (rounding_bits_of(a.seed, a.stream, idx0 + 2 * i + 1, ADAPT_SR) << 16);
+        }
     }
     int q[RUN];
     if (FITS32 && a.shift >= 1) {
