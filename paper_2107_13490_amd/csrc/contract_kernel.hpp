@@ -36,7 +36,10 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-enum { OP_GEMM = 0, OP_FWD = 1, OP_DGRAD = 2, OP_WGRAD = 3 };
+// OP_DGRAD_S2: the data gradient of a stride-2 convolution with its rows visited in parity-class order (see
+// ContractArgs::dg_classes); a separate instantiation so that the plain data-gradient kernels keep their registers
+enum { OP_GEMM = 0, OP_FWD = 1, OP_DGRAD = 2, OP_WGRAD = 3, OP_DGRAD_S2 = 4 };
+constexpr bool is_dgrad(int op) { return op == OP_DGRAD || op == OP_DGRAD_S2; }
 enum { LOAD_SCALAR = 0, LOAD_VEC = 1, LOAD_ROWS = 2 };
 enum { OUT_RAW32 = 0, OUT_RAW64 = 1, OUT_Q8 = 2, OUT_Q16 = 3 };
 
@@ -75,6 +78,13 @@ struct ContractArgs {
     // conv geometry
     int n, h, w, c, k, r, s, stride, pad, p, q;
     FastDiv div_c, div_s, div_q, div_p, div_k, div_w, div_h, div_stride;
+    // stride-2 data gradient: an input pixel sees only the filter taps of its row / column parity.
+    // Rows are visited in parity-class order (class = 2*(h%2) + w%2, each n*(h/2)*(w/2) rows), so a tile
+    // lies in one class and skips the stages of the other taps, which hold nothing but zeros.
+    int dg_classes;              // 0: off, 4: on
+    int dg_rows;                 // rows per class
+    FastDiv dg_div_w2, dg_div_h2;
+    uint32_t dg_mask[5];         // active taps (bit r*s_dim + s) of class 0..3; [4]: all taps, for tiles across classes
     int uniform_tap;             // 64 consecutive, 64-aligned k always lie in one filter tap
     int xcd_remap;               // contiguous ranges of blocks per XCD (see the kernel)
     int k_per_split;             // multiple of the kernel's stage depth
@@ -88,6 +98,25 @@ struct ContractArgs {
     int shift, wl_o, relu, rmode;
     uint64_t seed, stream;
 };
+
+// stride-2 data gradient in class order: visited row v -> row of dx (v < M)
+__device__ __forceinline__ uint32_t dgrad_class_of(const ContractArgs &a, uint32_t v)
+{
+    return (uint32_t)(v >= (uint32_t)a.dg_rows) + (uint32_t)(v >= 2u * (uint32_t)a.dg_rows) + (uint32_t)(v >= 3u * (uint32_t)a.dg_rows);
+}
+__device__ __forceinline__ uint32_t dgrad_real_row(const ContractArgs &a, uint32_t v)
+{
+    const uint32_t cls = dgrad_class_of(a, v), local = v - cls * (uint32_t)a.dg_rows;
+    const uint32_t nh = fdiv(local, a.dg_div_w2), w2 = local - nh * (uint32_t)(a.w >> 1);
+    const uint32_t n = fdiv(nh, a.dg_div_h2), h2 = nh - n * (uint32_t)(a.h >> 1);
+    return (n * (uint32_t)a.h + 2u * h2 + (cls >> 1)) * (uint32_t)a.w + 2u * w2 + (cls & 1u);
+}
+// position of the i-th set bit of mask (i < popcount)
+__device__ __forceinline__ int nth_set_bit(uint32_t mask, int i)
+{
+    for (; i > 0; --i) mask &= mask - 1u;
+    return __builtin_ctz(mask);
+}
 
 // ---------------------------------------------------------------------------------------------
 // address functions: element offset of ACT[row][k] / WGT[row][k], or -1 for a zero
@@ -106,7 +135,7 @@ __device__ __forceinline__ long long act_offset(const ContractArgs &a, int row, 
         if ((unsigned)hh >= (unsigned)a.h || (unsigned)ww >= (unsigned)a.w) return -1;
         return (((long long)n * a.h + hh) * a.w + ww) * a.c + c;
     }
-    if (OP == OP_DGRAD) {
+    if (is_dgrad(OP)) {
         const uint32_t nh = fdiv(row, a.div_w), w = row - nh * a.w;
         const uint32_t n = fdiv(nh, a.div_h), h = nh - n * a.h;
         const uint32_t tap = fdiv(k, a.div_k), ko = k - tap * a.k;
@@ -127,7 +156,7 @@ __device__ __forceinline__ long long wgt_offset(const ContractArgs &a, int row, 
     if (row >= a.N || k >= a.K) return -1;
     if (OP == OP_GEMM) return (long long)row * a.wgt_rs + (long long)k * a.wgt_ks;
     if (OP == OP_FWD) return (long long)row * a.K + k;
-    if (OP == OP_DGRAD) {                                       // row = c, k = (r,s,kout): w[kout][r][s][c]
+    if (is_dgrad(OP)) {                                         // row = c, k = (r,s,kout): w[kout][r][s][c]
         const uint32_t tap = fdiv(k, a.div_k), ko = k - tap * a.k;
         return ((long long)ko * (a.r * a.s) + tap) * a.c + row;
     }
@@ -248,8 +277,9 @@ struct LoaderK {
                 ra[i] = (int)p * a.stride - a.pad;
                 rb[i] = (int)q * a.stride - a.pad;
                 base[i] = ((n * (uint32_t)a.h + (uint32_t)ra[i]) * (uint32_t)a.w + (uint32_t)rb[i]) * (uint32_t)a.c;
-            } else if (ACT && OP == OP_DGRAD) {
-                const uint32_t nh = fdiv(row, a.div_w), w = row - nh * a.w;
+            } else if (ACT && is_dgrad(OP)) {
+                const uint32_t rr = (OP == OP_DGRAD_S2 && valid[i]) ? dgrad_real_row(a, row) : (uint32_t)row;
+                const uint32_t nh = fdiv(rr, a.div_w), w = rr - nh * a.w;
                 const uint32_t n = fdiv(nh, a.div_h), h = nh - n * a.h;
                 ra[i] = (int)h + a.pad;
                 rb[i] = (int)w + a.pad;
@@ -279,7 +309,7 @@ struct LoaderK {
                                 (unsigned)(rb[i] + (int)s) < (unsigned)a.w;
                 load_unit<LIMBS, ES>(ptr, base[i] + koff, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
             }
-        } else if (ACT && OP == OP_DGRAD) {
+        } else if (ACT && is_dgrad(OP)) {
             const uint32_t tap = fdiv(kq, a.div_k), ko = (uint32_t)k64 - tap * a.k;
             const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
 #pragma unroll
@@ -405,7 +435,7 @@ struct LoaderR {
                 off = coff[u] + (uint32_t)kk * (uint32_t)(ACT ? a.act_ks : a.wgt_ks);
             } else if (ACT) {                      // wgrad: dy[(n,p,q)][kout]
                 off = coff[u] + (uint32_t)kk * (uint32_t)a.k;
-            } else if (OP == OP_DGRAD) {           // filters w[kout][r][s][c], k line = (r,s,kout)
+            } else if (is_dgrad(OP)) {             // filters w[kout][r][s][c], k line = (r,s,kout)
                 const uint32_t tap = fdiv(ok ? kk : 0, a.div_k), ko = kk - tap * a.k;
                 off = (ko * (uint32_t)(a.r * a.s) + tap) * (uint32_t)a.c + coff[u];
             } else {                               // wgrad: x[n, p*st+r-pad, q*st+s-pad, c]
@@ -609,7 +639,32 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int kbeg = split * a.k_per_split;
     const int kend = min(a.K, kbeg + a.k_per_split);
-    const int ksteps = (kend - kbeg + BKT - 1) / BKT;
+    int ksteps = (kend - kbeg + BKT - 1) / BKT;
+    // stride-2 data gradient: only the stages of the taps this tile's parity class can see
+    uint32_t dg_mask = 0;
+    int dg_spt = 1;                 // stages per tap
+    constexpr bool dg = OP == OP_DGRAD_S2;
+    if (dg) {
+        const uint32_t c0 = dgrad_class_of(a, (uint32_t)m0), c1 = dgrad_class_of(a, (uint32_t)min(m0 + BM, a.M) - 1u);
+        dg_mask = a.dg_mask[c0 == c1 ? c0 : 4u];
+        dg_spt = a.k / BKT;
+        ksteps = __builtin_popcount(dg_mask) * dg_spt;
+    }
+    // the rows of dx this lane writes, mapped before the main loop (one register each; in the epilogue the
+    // temporaries of the mapping would come on top of the peak register use)
+    int dg_row[dg ? MB : 1];
+    if (dg) {
+#pragma unroll
+        for (int j = 0; j < MB; ++j) {
+            const int m = m0 + wm * WM + j * 32 + l32;
+            dg_row[j] = m < a.M ? (int)dgrad_real_row(a, (uint32_t)m) : m;
+        }
+    }
+    auto stage_k = [&](int j) -> int {
+        if (!dg) return kbeg + j * BKT;
+        const int t = j / dg_spt;
+        return nth_set_bit(dg_mask, t) * a.k + (j - t * dg_spt) * BKT;
+    };
 
     v16i acc_hh[NB][MB], acc_x[NB][MB], acc_ll[NB][MB];
 #pragma unroll
@@ -638,8 +693,9 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
 #pragma unroll
     for (int u = 0; u < PF; ++u)
         if (u < ksteps) {
-            la.load(a, m0, kbeg + u * BKT, ra[u]);
-            lb.load(a, n0, kbeg + u * BKT, rb[u]);
+            const int k0 = stage_k(u);
+            la.load(a, m0, k0, ra[u]);
+            lb.load(a, n0, k0, rb[u]);
         }
     ADAPT_STAMP(2);
 
@@ -706,8 +762,9 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                 __syncthreads();
                 ADAPT_STAMP(10 + 5 * min(kt, 10));
                 if (kt + PF < ksteps) {
-                    la.load(a, m0, kbeg + (kt + PF) * BKT, ra[u]);
-                    lb.load(a, n0, kbeg + (kt + PF) * BKT, rb[u]);
+                    const int k0 = stage_k(kt + PF);
+                    la.load(a, m0, k0, ra[u]);
+                    lb.load(a, n0, k0, rb[u]);
                 }
                 ADAPT_STAMP(11 + 5 * min(kt, 10));
                 multiply_stage();
@@ -750,7 +807,9 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                            128 * (corr_m[j] + s_n) + 16384 * kpad;
                 }
             }
-            const int m = m0 + wm * WM + j * 32 + l32, nb0 = n0 + wn * WN + i * 32;
+            int m = m0 + wm * WM + j * 32 + l32;
+            const int nb0 = n0 + wn * WN + i * 32;
+            if (dg) m = dg_row[dg ? j : 0];                                  // class order -> row of dx
             if constexpr (W_R) {
                 // lanes l and l^32 hold interleaved runs of 4 of the same output row: swap halves
                 // so that each ends up with 16 consecutive n (lane/32 = 0: n 0..15, 1: n 16..31)
@@ -936,10 +995,14 @@ template <int OP, int LIMBS>
 static hipError_t launch_modes(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
 {
     const bool scalar = a.act_load == LOAD_SCALAR || a.wgt_load == LOAD_SCALAR;
-    if constexpr (OP == OP_DGRAD)      // few input channels (first layer): the gradient tile still takes the vector path
+    if constexpr (is_dgrad(OP))        // few input channels (first layer): the gradient tile still takes the vector path
         if (a.act_load == LOAD_VEC && a.wgt_load == LOAD_SCALAR)
             return launch_variant<OP, LIMBS, LOAD_VEC, LOAD_SCALAR, 128, 64, 2, 2, 64>(ctx, a, splits);
-    if (scalar) return launch_tile<OP, LIMBS, LOAD_SCALAR, LOAD_SCALAR>(ctx, a, splits, t);
+    if constexpr (OP == OP_DGRAD_S2) {
+        if (scalar) return hipErrorInvalidValue;      // the class order is only planned for the vector path of dy
+    } else {
+        if (scalar) return launch_tile<OP, LIMBS, LOAD_SCALAR, LOAD_SCALAR>(ctx, a, splits, t);
+    }
     if constexpr (OP == OP_WGRAD) {
         return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_ROWS>(ctx, a, splits, t);
     } else if constexpr (OP == OP_GEMM) {
@@ -947,7 +1010,7 @@ static hipError_t launch_modes(adapt_ctx *ctx, const ContractArgs &a, int splits
         if (a.act_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_ROWS>(ctx, a, splits, t);
         if (a.wgt_load == LOAD_VEC) return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_VEC>(ctx, a, splits, t);
         return launch_tile<OP, LIMBS, LOAD_ROWS, LOAD_ROWS>(ctx, a, splits, t);
-    } else if constexpr (OP == OP_DGRAD) {
+    } else if constexpr (is_dgrad(OP)) {
         return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_ROWS>(ctx, a, splits, t);
     } else {
         return launch_tile<OP, LIMBS, LOAD_VEC, LOAD_VEC>(ctx, a, splits, t);
@@ -1061,6 +1124,11 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     int model_splits = 0;
     if (OP == OP_WGRAD && a.act_load != LOAD_SCALAR && a.wgt_load != LOAD_SCALAR) model_splits = pick_split_tile(a, limbs, bits, ctx->num_cu, t);
     a.xcd_remap = 1;
+    // stride-2 data gradient: three of four stages hold only zeros for any one parity class (see ContractArgs);
+    // skipping them needs stages that do not straddle taps
+    const bool want_dg = OP == OP_DGRAD && a.stride == 2 && a.h % 2 == 0 && a.w % 2 == 0 && a.act_load == LOAD_VEC &&
+                         a.k % 64 == 0 && a.r * a.s <= 32;
+    if (want_dg && a.k % t.bkt != 0) t.bkt = 64;
 #ifdef ADAPT_TUNE
     int tune_splits = 0;
     if (getenv("ADAPT_NOREMAP")) a.xcd_remap = 0;
@@ -1088,6 +1156,21 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     splits = a.K == 0 ? 1 : (a.K + k_per - 1) / k_per;
     a.k_per_split = k_per;
     a.slab_bytes = 0;
+    a.dg_classes = 0;
+    if (want_dg && splits == 1 && a.k % t.bkt == 0) {
+        a.dg_classes = 4;
+        a.dg_rows = a.n * (a.h / 2) * (a.w / 2);
+        a.dg_div_w2 = make_fastdiv(a.w / 2);
+        a.dg_div_h2 = make_fastdiv(a.h / 2);
+        for (int cls = 0; cls < 4; ++cls) {
+            uint32_t mask = 0;
+            for (int r = 0; r < a.r; ++r)
+                for (int sx = 0; sx < a.s; ++sx)
+                    if ((((cls >> 1) + a.pad - r) & 1) == 0 && (((cls & 1) + a.pad - sx) & 1) == 0) mask |= 1u << (r * a.s + sx);
+            a.dg_mask[cls] = mask;
+        }
+        a.dg_mask[4] = a.r * a.s == 32 ? 0xffffffffu : (1u << (a.r * a.s)) - 1u;
+    }
     p.tile = t;
     p.splits = splits;
     if (splits == 1 && !a.force_finish) {
@@ -1117,6 +1200,10 @@ template <int OP>
 static hipError_t launch_planned(adapt_ctx *ctx, const ContractPlan &p)
 {
     if (p.empty) return hipSuccess;
+    if constexpr (OP == OP_DGRAD)
+        if (p.kern.dg_classes)
+            return p.limbs == 1 ? launch_modes<OP_DGRAD_S2, 1>(ctx, p.kern, p.splits, p.tile)
+                                : launch_modes<OP_DGRAD_S2, 2>(ctx, p.kern, p.splits, p.tile);
     return p.limbs == 1 ? launch_modes<OP, 1>(ctx, p.kern, p.splits, p.tile) : launch_modes<OP, 2>(ctx, p.kern, p.splits, p.tile);
 }
 

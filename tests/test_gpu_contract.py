@@ -405,3 +405,42 @@ def test_narrow_layer_falls_back_when_the_workspace_is_small():
     dx = small.conv_dgrad(d, to_dev(dy), (8, 4), to_dev(wt), (8, 5), Epilogue.exact())
     assert np.array_equal(host(dx).astype(np.int64), co.conv_dgrad(dy, wt, h, w, 1, 1))
     small.close()
+
+
+# ---- stride-2 data gradient: rows in parity-class order, stages of invisible taps skipped --------------------
+
+STRIDE2_CASES = [
+    # n, h, w, c, k, r, s, pad
+    (2, 8, 8, 32, 64, 3, 3, 1),         # four classes of 32 rows: every 64-row tile straddles two classes
+    (8, 8, 8, 32, 64, 3, 3, 1),         # classes of 128 rows: tiles inside one class
+    (5, 12, 8, 16, 128, 3, 3, 1),       # ragged class size (120 rows): some tiles straddle
+    (4, 16, 16, 64, 128, 1, 1, 0),      # 1x1 projection: three classes see no tap at all
+    (3, 8, 8, 32, 64, 5, 5, 2),
+    (3, 8, 8, 32, 64, 2, 2, 0),         # even filter: every class sees exactly one tap
+    (4, 8, 8, 16, 64, 3, 3, 0),         # no padding
+    (4, 8, 8, 48, 192, 3, 3, 1),        # one limb: 192-deep stages stay (Kout % 192 == 0)
+    (4, 8, 8, 48, 256, 3, 3, 1),        # one limb: stages shortened to 64 for the skip
+    (2, 6, 10, 3, 64, 3, 3, 1),         # narrow layer (padded filters) and stride 2
+]
+
+
+@pytest.mark.parametrize("case", STRIDE2_CASES)
+@pytest.mark.parametrize("wl", [8, 13])
+def test_stride2_data_gradient(case, wl):
+    n, h, w, c, k, r, s, pad = case
+    d = ConvDesc(n, h, w, c, k, r, s, 2, pad)
+    wt = codes((k, r, s, c), wl, 2, True)
+    dy = codes((n, d.p, d.q, k), wl, 3, True)
+    x = codes((n, h, w, c), wl, 1)
+    f = (wl, wl - 3)
+    want = co.conv_dgrad(dy, wt, h, w, 2, pad)
+    dx = ctx().conv_dgrad(d, to_dev(dy), f, to_dev(wt), f, Epilogue.exact())
+    assert np.array_equal(host(dx).astype(np.int64), want)
+    ep = Epilogue.requant(wl, wl - 5, pkg.SR, 9, 77)
+    sh = 2 * (wl - 3) - (wl - 5)
+    dxq = ctx().conv_dgrad(d, to_dev(dy), f, to_dev(wt), f, ep)
+    assert np.array_equal(host(dxq).astype(np.int64), orc.requantize(want, sh, wl, orc.SR, 9, 77))
+    # the paired backward call takes the same path
+    dx2, dw2 = ctx().conv_backward(d, to_dev(dy), f, to_dev(wt), f, to_dev(x), f, ep, Epilogue.exact())
+    assert torch.equal(dxq, dx2)
+    assert np.array_equal(host(dw2).astype(np.int64), co.conv_wgrad(dy, x, r, s, 2, pad))
