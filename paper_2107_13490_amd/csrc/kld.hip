@@ -712,6 +712,19 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, 
         b.tickets = ticket(ctx, 16);
         size_t off = 0, lds_max = 0;
         unsigned nr = 0, nh = 0, nf = 0;
+        // The batch as a whole fills the GPU once (a full set of rows leaves room for one block per CU): every block
+        // clears and flushes its histogram rows, and the final phase reads the slabs back, so a tensor gets blocks
+        // in proportion to its share of the elements rather than as many as it could use alone.
+        uint64_t batch_elems = 0, batch_blocks = 0;
+        const uint64_t per_block = (uint64_t)threads * 8;
+        for (int m = 0; m < kKldBatchMax && t0 + m < count; ++m) batch_elems += items[t0 + m].n;
+        auto blocks_of = [&](uint64_t n) {
+            const uint64_t by_size = std::max<uint64_t>(1, (n + per_block - 1) / per_block);
+            const uint64_t by_share = batch_elems ? std::max<uint64_t>(1, ((uint64_t)ctx->num_cu * n + batch_elems / 2) / batch_elems) : 1;
+            return (int)std::min<uint64_t>((uint64_t)ctx->num_cu, std::min(by_size, by_share));
+        };
+        for (int m = 0; m < kKldBatchMax && t0 + m < count; ++m) batch_blocks += (uint64_t)blocks_of(items[t0 + m].n);
+        const int want_groups = (int)std::max<uint64_t>(1, (2 * (uint64_t)ctx->num_cu + batch_blocks - 1) / std::max<uint64_t>(batch_blocks, 1));
         while (b.count < kKldBatchMax && t0 + b.count < count) {
             const adapt_kld_item &src = items[t0 + b.count];
             const size_t row_bytes = (size_t)src.bins * 4, per_row = row_bytes + kPrivWords * 4;
@@ -720,13 +733,11 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, 
             it.w = src.w; it.n = src.n; it.stream = src.stream; it.il = src.il; it.bins = src.bins;
             it.kld = kld + (size_t)(t0 + b.count) * ncand;
             it.sel = sel + 2 * (t0 + b.count);
-            const uint64_t per_block = (uint64_t)threads * 8;
-            it.hist_x = (int)std::min<uint64_t>((uint64_t)ctx->num_cu, std::max<uint64_t>(1, (src.n + per_block - 1) / per_block));
+            it.hist_x = blocks_of(src.n);
             it.range_blocks = (int)std::min<uint64_t>((uint64_t)ctx->num_cu * 4, std::max<uint64_t>(1, (src.n / 4 + kRangeThreads - 1) / kRangeThreads));
             it.nchunks = (src.bins + kChunk - 1) / kChunk;
             int rpg = (int)std::min<size_t>(rows, kLdsBudget / per_row);
-            const int want_groups = std::max(1, (2 * ctx->num_cu + it.hist_x - 1) / it.hist_x);
-            rpg = std::max(1, std::min(rpg, (rows + want_groups - 1) / want_groups));
+            rpg = std::max(1, std::min(rpg, (rows + want_groups - 1) / want_groups));      // a small batch splits the candidates
             it.rows_per_group = rpg;
             it.groups = (rows + rpg - 1) / rpg;
             const size_t need = a256(sizeof(KldPlan)) + a256((size_t)it.range_blocks * 8) + a256((size_t)ncand * it.nchunks * 16) +
