@@ -362,12 +362,20 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (20 times): the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
+    ap.add_argument("--chained-step", action="store_true",
+                    help="run only the chained AlexNet-CIFAR training step measurement (supplementary; for profiler runs)")
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="which of the five workload configurations to run (default 2, the one the metric is quoted on)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (use --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    if args.chained_step:
+        import torch
+        import paper_2107_13490_amd as pkg
+        torch.cuda.set_device(0)
+        print(json.dumps({"chained_step": chained_step(None, pkg, torch, batch=128)}))
+        return
     if args.config != 2 and not args.copy_calibration:
         other_config(args, args.config)
         return
