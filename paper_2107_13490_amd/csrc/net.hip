@@ -617,7 +617,9 @@ extern "C" int adapt_net_set_format(adapt_net *net, int layer, adapt_fmt f)
 
 extern "C" int adapt_net_tensor(const adapt_net *net, int layer, int which, size_t *offset, size_t *count, int *elem_bytes)
 {
-    if (!net || !offset || !count || !elem_bytes || layer < 0 || layer >= (int)net->L.size()) return ADAPT_EINVAL;
+    if (!net || !offset || !count || !elem_bytes) return ADAPT_EINVAL;
+    if (which == ADAPT_NT_INPUT) layer = 0;                 // the network input belongs to no layer
+    if (layer < 0 || layer >= (int)net->L.size()) return ADAPT_EINVAL;
     const NetLayer &y = net->L[layer];
     const int es = storage_bytes(y.fmt);
     switch (which) {
