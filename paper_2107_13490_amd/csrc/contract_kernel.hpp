@@ -611,13 +611,19 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                                               const unsigned ntiles, char *const smem)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per block");
-    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT, AES>::type LA;
-    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT, WES>::type LB;
+    // Limbs per operand: in a two-limb kernel an operand stored as int8 (WL <= 8) stays one limb, so a mixed
+    // layer issues two MFMA products per step instead of four:
+    //   a one limb, b = 256 b_hi + b_lo' + 128:   a b = 256 (a b_hi) + (a b_lo') + 128 a
+    //   a = 256 a_hi + a_lo' + 128, b one limb:   a b = 256 (a_hi b) + (a_lo' b) + 128 b
+    constexpr int LAL = LIMBS == 2 ? AES : 1, LBL = LIMBS == 2 ? WES : 1;
+    constexpr bool BOTH2 = LAL == 2 && LBL == 2;
+    typedef typename LoaderSelect<OP, true, AMODE, BM, LAL, BKT, AES>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, LBL, BKT, WES>::type LB;
     constexpr bool A_R = AMODE == LOAD_ROWS, W_R = WMODE == LOAD_ROWS;
     constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
     constexpr int MB = WM / 32, NB = WN / 32;       // 32x32 blocks per wave
     char *const a_hi = smem, *const a_lo = smem + LA::TILE_BYTES;
-    char *const b_hi = smem + LA::TILE_BYTES * LIMBS, *const b_lo = b_hi + LB::TILE_BYTES;
+    char *const b_hi = smem + LA::TILE_BYTES * LAL, *const b_lo = b_hi + LB::TILE_BYTES;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -707,20 +713,20 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
             for (int j = 0; j < MB; ++j) {
                 if constexpr (A_R) {
                     fa_h[j] = LA::frag(a_hi, wm * WM + j * 32, ks, lane);
-                    if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32, ks, lane);
+                    if (LAL == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32, ks, lane);
                 } else {
                     fa_h[j] = LA::frag(a_hi, wm * WM + j * 32 + l32, ks, g);
-                    if (LIMBS == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32 + l32, ks, g);
+                    if (LAL == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32 + l32, ks, g);
                 }
             }
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
                 if constexpr (W_R) {
                     fb_h[i] = LB::frag(b_hi, wn * WN + i * 32, ks, lane);
-                    if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32, ks, lane);
+                    if (LBL == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32, ks, lane);
                 } else {
                     fb_h[i] = LB::frag(b_hi, wn * WN + i * 32 + nperm, ks, g);
-                    if (LIMBS == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32 + nperm, ks, g);
+                    if (LBL == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32 + nperm, ks, g);
                 }
             }
 #pragma unroll
@@ -728,23 +734,27 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
 #pragma unroll
                 for (int j = 0; j < MB; ++j) {
                     acc_hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_h[j], acc_hh[i][j], 0, 0, 0);
-                    if (LIMBS == 2) {
-                        acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_l[j], acc_x[i][j], 0, 0, 0);
-                        acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_h[j], acc_x[i][j], 0, 0, 0);
-                        acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_l[j], acc_ll[i][j], 0, 0, 0);
-                    }
+                    if (LAL == 2) acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_l[j], acc_x[i][j], 0, 0, 0);
+                    if (LBL == 2) acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_h[j], acc_x[i][j], 0, 0, 0);
+                    if (BOTH2) acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_l[j], acc_ll[i][j], 0, 0, 0);
                 }
-            if (LIMBS == 2) {
+            // sums of the other side's k-values for the "+128" terms: of a' = 256 a_hi + a_lo' when a has two
+            // limbs, of the plain codes when it has one (needed only when b has two limbs); likewise for b
+            if (LBL == 2) {
 #pragma unroll
                 for (int j = 0; j < MB; ++j)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        sum_m[j] += 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e]);
+                        sum_m[j] += LAL == 2 ? 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e])
+                                             : dot4_ones((uint32_t)fa_h[j][e]);
+            }
+            if (LAL == 2) {
 #pragma unroll
                 for (int i = 0; i < NB; ++i)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        sum_n[i] += 256 * dot4_ones((uint32_t)fb_h[i][e]) + dot4_ones((uint32_t)fb_l[i][e]);
+                        sum_n[i] += LBL == 2 ? 256 * dot4_ones((uint32_t)fb_h[i][e]) + dot4_ones((uint32_t)fb_l[i][e])
+                                             : dot4_ones((uint32_t)fb_h[i][e]);
             }
         }
     };
@@ -803,8 +813,11 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                 } else {
                     const int nl = W_R ? 8 * (r >> 2) + 4 * g + (r & 3) : 16 * g + r;
                     const long long s_n = sn[(wave * NB + i) * 32 + nl];
-                    v[r] = ((long long)acc_hh[i][j][r] << 16) + ((long long)acc_x[i][j][r] << 8) + (long long)acc_ll[i][j][r] +
-                           128 * (corr_m[j] + s_n) + 16384 * kpad;
+                    if (BOTH2)
+                        v[r] = ((long long)acc_hh[i][j][r] << 16) + ((long long)acc_x[i][j][r] << 8) + (long long)acc_ll[i][j][r] +
+                               128 * (corr_m[j] + s_n) + 16384 * kpad;
+                    else      // one side has one limb: the other side's sums are zero and never enter
+                        v[r] = ((long long)acc_hh[i][j][r] << 8) + (long long)acc_x[i][j][r] + 128 * (LBL == 2 ? corr_m[j] : s_n);
                 }
             }
             int m = m0 + wm * WM + j * 32 + l32;
@@ -838,8 +851,16 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
     ADAPT_STAMP_WG(1);
 }
 
+// Two-limb 64x64 tiles: three accumulator sets and the staging registers land a few registers above what three
+// resident wavefronts per SIMD allow; asking for three makes the register allocator fit them without spills
+// (forward 64->64 3x3 at 32x32, batch 256, <14,11>: 118 -> 86 us).  The weight gradient on its own gains nothing from it.
+constexpr int min_waves_per_simd(int op, int limbs, int aes, int wes, int bm, int bn)
+{
+    return (op != OP_WGRAD && limbs == 2 && aes == 2 && wes == 2 && bm == 64 && bn == 64) ? 3 : 1;
+}
+
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PF>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, min_waves_per_simd(OP, LIMBS, AES, WES, BM, BN))
 contract_kernel(const ContractArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -852,7 +873,7 @@ contract_kernel(const ContractArgs a)
 // launch floor is paid instead of two.  Both have the same number of limbs, element size (LIMBS
 // bytes) and stage depth.
 template <int LIMBS, int BKT, int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, (LIMBS == 2 && BMA == 64 && BNA == 64 && BMB == 64 && BNB == 64) ? 3 : 1)      // as above; measured faster for the pair
 contract_pair_kernel(const ContractArgs a, const ContractArgs b, const unsigned n_first, const unsigned tiles_a,
                      const unsigned tiles_b)
 {
@@ -922,10 +943,11 @@ constexpr int prefetch_depth(int /*limbs*/, int /*amode*/, int /*bm*/, int /*bn*
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
 static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
-    typedef typename LoaderSelect<OP, true, AMODE, BM, LIMBS, BKT, AES>::type LA;
-    typedef typename LoaderSelect<OP, false, WMODE, BN, LIMBS, BKT, WES>::type LB;
+    constexpr int LAL = LIMBS == 2 ? AES : 1, LBL = LIMBS == 2 ? WES : 1;      // limbs per operand, as in the kernel
+    typedef typename LoaderSelect<OP, true, AMODE, BM, LAL, BKT, AES>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, LBL, BKT, WES>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    const size_t lds = (size_t)(LA::TILE_BYTES + LB::TILE_BYTES) * LIMBS;
+    const size_t lds = std::max<size_t>((size_t)LA::TILE_BYTES * LAL + (size_t)LB::TILE_BYTES * LBL, 4 * 4 * 32 * sizeof(int) * 4);
     constexpr int PF = prefetch_depth(LIMBS, AMODE, BM, BN, BKT);
     auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PF>;
     static bool attr_done = false;
