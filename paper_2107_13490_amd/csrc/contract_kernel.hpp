@@ -1058,12 +1058,10 @@ static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
     const long long tiles128 = (long long)((a.M + 127) / 128) * ((a.N + t.bn - 1) / t.bn);
     t.bm = (!scalar && OP != OP_WGRAD && tiles128 < 2 * num_cu && a.M > 64) ? 64 : 128;
     if (limbs == 2 && !scalar && OP != OP_WGRAD) {
-        // Two limbs: three accumulator sets leave a 128-wide tile one resident block per CU, a 64x64
-        // tile two.  The large tile pays only when it fills every CU without much padding.
-        const long long tm = (a.M + 127) / 128, tn = (a.N + 127) / 128;
-        const bool fits = a.M >= 128 && a.N >= 128 && tm * tn >= num_cu &&
-                          (double)(tm * 128) * (double)(tn * 128) < 1.15 * (double)a.M * (double)a.N;
-        t.bm = t.bn = fits ? 128 : 64;
+        // Two limbs: the 64x64 tile runs four resident wavefronts per SIMD (three accumulator sets fit one unified
+        // register file, see min_waves_per_simd), the 128x128 tile one; 64x64 was measured faster at every size
+        // (conv 128->128 at 16x16, batch 256: 67 against 82 us; at 32x32: 250 against 325 us).
+        t.bm = t.bn = 64;
     }
     return t;
 }
