@@ -854,13 +854,20 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
 // Two-limb 64x64 tiles: three accumulator sets and the staging registers land a few registers above what three
 // resident wavefronts per SIMD allow; asking for three makes the register allocator fit them without spills
 // (forward 64->64 3x3 at 32x32, batch 256, <14,11>: 118 -> 86 us).  The weight gradient on its own gains nothing from it.
-constexpr int min_waves_per_simd(int op, int limbs, int aes, int wes, int bm, int bn)
+constexpr int min_waves_per_simd(int op, int limbs, int amode, int wmode, int aes, int wes, int bm, int bn)
 {
+    if (amode == LOAD_SCALAR || wmode == LOAD_SCALAR) return 1;      // the element-wise gather needs its registers
+    // one limb: the same request moves the 128x128 tile from two to three resident wavefronts per SIMD
+    // and the 128x64 tile from three to four
+    // (only where the allocator manages without spills and it was measured to help: 256 x 32 x 32 x 256 -> 256 forward
+    // 209 -> 200 us; the 64x128 tile spills, the 64x192 tile gains nothing)
+    if (limbs == 1 && bm == 128 && bn == 128) return 3;
+    if (limbs == 1 && bm == 128 && bn == 64) return 4;
     return (op != OP_WGRAD && limbs == 2 && aes == 2 && wes == 2 && bm == 64 && bn == 64) ? 3 : 1;
 }
 
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PF>
-__global__ void __launch_bounds__(kThreads, min_waves_per_simd(OP, LIMBS, AES, WES, BM, BN))
+__global__ void __launch_bounds__(kThreads, min_waves_per_simd(OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN))
 contract_kernel(const ContractArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
