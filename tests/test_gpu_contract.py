@@ -444,3 +444,31 @@ def test_stride2_data_gradient(case, wl):
     dx2, dw2 = ctx().conv_backward(d, to_dev(dy), f, to_dev(wt), f, to_dev(x), f, ep, Epilogue.exact())
     assert torch.equal(dxq, dx2)
     assert np.array_equal(host(dw2).astype(np.int64), co.conv_wgrad(dy, x, r, s, 2, pad))
+
+
+# ---- mixed word lengths: the int8 operand stays one limb inside the two-limb kernels -----------------------------
+
+@pytest.mark.parametrize("case", CONV_CASES + NARROW_CASES[:2])
+@pytest.mark.parametrize("wls", [(8, 16, 8), (16, 8, 16), (16, 8, 8), (5, 9, 13)])
+def test_conv_mixed_one_and_two_limb_operands(case, wls):
+    _conv_all(case, *wls, extreme=True)
+    _conv_all(case, *wls)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("wla,wlb", [(8, 16), (16, 8)])
+def test_gemm_mixed_worst_case_and_transposes(ta, tb, wla, wlb):
+    m, n, k = 96, 160, 4096 + 64
+    for va, vb in ((-1, -1), (-1, 1), (1, -1)):           # every product at its bound, all sign combinations
+        a = np.full((m, k), -(1 << (wla - 1)) if va < 0 else (1 << (wla - 1)) - 1, dtype=np.int8 if wla <= 8 else np.int16)
+        b = np.full((k, n), -(1 << (wlb - 1)) if vb < 0 else (1 << (wlb - 1)) - 1, dtype=np.int8 if wlb <= 8 else np.int16)
+        da = to_dev(a.T.copy() if ta else a)
+        db = to_dev(b.T.copy() if tb else b)
+        c = ctx().fxp_gemm(da, (wla, 0), db, (wlb, 0), Epilogue.exact(), trans_a=bool(ta), trans_b=bool(tb))
+        assert (host(c).astype(np.int64) == k * int(a[0, 0]) * int(b[0, 0])).all()
+    a, b = codes((m, k), wla, 3, True), codes((k, n), wlb, 4, True)
+    da = to_dev(a.T.copy() if ta else a)
+    db = to_dev(b.T.copy() if tb else b)
+    ep = Epilogue.requant(12, 0, pkg.SR, seed=2, stream=9)
+    c = ctx().fxp_gemm(da, (wla, 7), db, (wlb, 7), ep, trans_a=bool(ta), trans_b=bool(tb))
+    assert np.array_equal(host(c).astype(np.int64), orc.requantize(orc.gemm(a, b), 14, 12, orc.SR, 2, 9))
