@@ -29,8 +29,8 @@ PEAK_HBM_GBPS = 8000.0
 # dispatch, scaled by what a plain 256 MiB device copy reads on the same counters: x2.0 and x1.0);
 # the summary with the commands is profiles/bench_config2_hbm_traffic.md.  Counters cannot be read
 # from inside this process.  Backward = the paired dgrad + wgrad kernel plus the slab-sum kernel.
-FWD_TRAFFIC_BYTES = {"read": 3283 * 1024, "written": 6144 * 1024}
-BWD_TRAFFIC_BYTES = {"read": (12693 + 7837) * 1024, "written": (9824 + 108) * 1024}
+FWD_TRAFFIC_BYTES = {"read": 3258 * 1024, "written": 6144 * 1024}
+BWD_TRAFFIC_BYTES = {"read": (12695 + 7856) * 1024, "written": (9824 + 108) * 1024}
 
 def cpu_baseline(batch: int):
     """The oracle, as it stands, on a bounded sample (reduced batch) of the same layer."""
