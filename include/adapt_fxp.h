@@ -412,7 +412,7 @@ int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogits_fl, adap
  *              ds = adapt_gradient_diversity of the most recent min(len, lb^l) entries with
  *              fl_k = e_k - min e (ADAPT_EUNSUPPORTED if they differ by more than 31);
  *              lb^l = adapt_lookback_next, r^l = adapt_resolution_next;
- *              if len >= lb^l: PushDown = adapt_kld_precision_search on the master weights with
+ *              if len >= lb^l: PushDown = the KL search (batched over the layers that switch) on the master weights with
  *              il = WL - FL, candidates max(wl_lo, il)..wl_hi, r^l bins, stream slot 6, its
  *              selection limited to the current WL; PushUp = adapt_pushup_suggest with wl_cap 16;
  *              the layer takes the new format and its window is emptied.

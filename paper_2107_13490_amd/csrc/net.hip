@@ -469,7 +469,7 @@ constexpr size_t kKldStride = 128;      // bytes per layer for the KL values of 
 
 // Lays the workspace out; returns 0 for an invalid network.
 size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vector<NetLayer> &L, size_t &off_in,
-                size_t &off_accx, size_t &off_accw, size_t &off_stats)
+                size_t &off_accx, size_t &off_accw, size_t &off_stats, size_t &off_sel_group, size_t &off_kld_group)
 {
     if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64) return 0;
     L.assign(count, NetLayer());
@@ -480,6 +480,8 @@ size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vecto
     // records that the host reads back in one copy each: stats, diversities, selections, KL values
     off_stats = take((size_t)count * kStatBytes);
     const size_t off_ds = take((size_t)count * 16), off_sel = take((size_t)count * 8), off_kld = take((size_t)count * kKldStride);
+    off_sel_group = off_sel;       // the batched searches of a precision switch write their results densely, in group order
+    off_kld_group = off_kld;
     for (int l = 0; l < count; ++l) {
         const adapt_conv_desc &c = descs[l].conv;
         if (c.n != n || c.h < 1 || c.w < 1 || c.c < 1 || c.k < 1 || c.r < 1 || c.s < 1 || c.stride < 1 || c.pad < 0) return 0;
@@ -525,7 +527,7 @@ struct adapt_net {
     adapt_ctx *ctx;
     std::vector<NetLayer> L;
     char *ws;
-    size_t off_in, off_accx, off_accw, off_stats, bytes;
+    size_t off_in, off_accx, off_accw, off_stats, off_sel_group, off_kld_group, bytes;
     bool forward_done, backward_done;
     int dlogits_fl;
     // precision switch
@@ -566,8 +568,8 @@ static bool switch_params_ok(const adapt_switch_params &p)
 extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr)
 {
     std::vector<NetLayer> L;
-    size_t a, b, c, d;
-    return plan_net(layers, count, lb_upr, L, a, b, c, d);
+    size_t a, b, c, d, e, f;
+    return plan_net(layers, count, lb_upr, L, a, b, c, d, e, f);
 }
 
 extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
@@ -584,7 +586,8 @@ extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, 
     net->has_switch = sp != nullptr;
     if (sp) net->sp = *sp;
     net->strategy = sp ? sp->strategy_init : ADAPT_ST_MIN;
-    net->bytes = plan_net(layers, count, sp ? sp->lb_upr : 0, net->L, net->off_in, net->off_accx, net->off_accw, net->off_stats);
+    net->bytes = plan_net(layers, count, sp ? sp->lb_upr : 0, net->L, net->off_in, net->off_accx, net->off_accw, net->off_stats,
+                          net->off_sel_group, net->off_kld_group);
     bool ok = net->bytes != 0 && net->bytes <= workspace_bytes;
     for (int l = 0; ok && l < count; ++l) {
         net->L[l].w = weights[l];
@@ -800,7 +803,10 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return hip_status(ctx, e);
 
-    // lookback, resolution; PushDown for the layers whose window is long enough
+    int group_base = 0;
+    std::vector<int> group_slot(count, 0);
+    // lookback, resolution; PushDown for the layers whose window is long enough: one batched search per group of
+    // layers that share the lowest candidate word length (the batched call takes one candidate range)
     std::vector<int> lo_of(count, 0);
     bool any = false;
     for (int l = 0; l < count; ++l) {
@@ -817,18 +823,37 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
         const int il = y.fmt.wl - y.fmt.fl;
         if (il < 1) return ADAPT_EINVAL;
         lo_of[l] = std::max(sp.wl_lo, il);
-        if (lo_of[l] <= sp.wl_hi) {
-            adapt_rng r = slot_rng(rng, l, 6);
-            if (int s = adapt_kld_precision_search(ctx, y.w, y.n_w, lo_of[l], sp.wl_hi, il, y.res, sp.eps, -1.0, r,
-                                                   reinterpret_cast<double *>(net->ws + y.off_kld),
-                                                   reinterpret_cast<int32_t *>(net->ws + y.off_sel), nullptr, nullptr))
-                return s;
-            any = true;
+    }
+    for (int lo = 2; lo <= sp.wl_hi; ++lo) {
+        adapt_kld_item items[kMaxLayers];
+        int members[kMaxLayers], m = 0;
+        for (int l = 0; l < count; ++l) {
+            const NetLayer &y = net->L[l];
+            if (lo_of[l] != lo || (int)y.win.size() < y.lb) continue;
+            items[m].w = y.w;
+            items[m].n = y.n_w;
+            items[m].il = y.fmt.wl - y.fmt.fl;
+            items[m].bins = y.res;
+            items[m].stream = rng.stream + (uint64_t)(8 * l + 6);
+            members[m++] = l;
         }
+        if (m == 0) continue;
+        // results of the group land in a contiguous scratch of the workspace and are copied to the layers' slots
+        // by the host after the read-back below: the group writes kld[t*ncand] and sel[2t] for its t-th member
+        const int ncand = sp.wl_hi - lo + 1;
+        double *gk = reinterpret_cast<double *>(net->ws + net->off_kld_group);
+        int32_t *gs = reinterpret_cast<int32_t *>(net->ws + net->off_sel_group);
+        if (int s = adapt_kld_precision_search_batched(ctx, items, m, lo, sp.wl_hi, sp.eps, -1.0, rng.mode, rng.seed,
+                                                       gk + (size_t)group_base * 16, gs + 2 * (size_t)group_base))
+            return s;
+        for (int t = 0; t < m; ++t) group_slot[members[t]] = group_base + t;
+        group_base += m;
+        (void)ncand;
+        any = true;
     }
     std::vector<int32_t> sel(2 * (size_t)count, 0);
     if (any) {
-        e = hipMemcpyAsync(sel.data(), net->ws + net->L[0].off_sel, (size_t)count * 8, hipMemcpyDeviceToHost, ctx->stream);
+        e = hipMemcpyAsync(sel.data(), net->ws + net->off_sel_group, (size_t)count * 8, hipMemcpyDeviceToHost, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e != hipSuccess) return hip_status(ctx, e);
     }
@@ -837,7 +862,7 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
         if ((int)y.win.size() >= y.lb) {
             const int il = y.fmt.wl - y.fmt.fl;
             int wl_min = y.fmt.wl;
-            if (lo_of[l] <= sp.wl_hi) wl_min = std::min<int>(sel[2 * l], y.fmt.wl);
+            if (lo_of[l] <= sp.wl_hi) wl_min = std::min<int>(sel[2 * (size_t)group_slot[l]], y.fmt.wl);
             const int fl_min = wl_min - il;
             adapt_pushup_result r;
             if (int s = adapt_pushup_suggest(ds[2 * l], wl_min, fl_min, net->strategy, sp.buff, 16, &r)) return s;
