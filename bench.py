@@ -211,9 +211,9 @@ def chained_step(ctx, pkg, torch, batch=128):
 
 
 def other_config(args, cfg):
-    """Configs 1, 3, 4 and 5 (supplementary lines; the default run is config 2).  A step is, for every
-    layer of the config, quantize(X, W, dY) + fwd + backward (dgrad + wgrad; requantized with SR), then ONE
-    batched KLD call over all weight tensors of the config.  Config 1 is a GEMM instead of a layer."""
+    """Configs 1, 3, 4 and 5 (supplementary lines; the default run is config 2).  A step is ONE batched quantize
+    call over the X, W and dY of every layer of the config, then for every layer fwd + backward (dgrad + wgrad;
+    requantized with SR), then ONE batched KLD call over all weight tensors.  Config 1 is a GEMM instead of a layer."""
     import numpy as np
     import torch
     import paper_2107_13490_amd as pkg
@@ -251,6 +251,7 @@ def other_config(args, cfg):
             layers = [wk.layer_inputs(sp, 50 + i) for i, sp in enumerate(wk.resnet18_cifar_layers())]
             workload = "configs[4]: ResNet-18-CIFAR layer sweep (21 layers, 11.2 M weights), batch 256, WL per layer 4..16"
         sample_layer = max(layers, key=lambda L: L.shape.macs)
+        q_in, q_out, q_fmt = [], [], []
         for L in layers:
             s = L.shape
             d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
@@ -259,20 +260,25 @@ def other_config(args, cfg):
             x, w, dy = (torch.from_numpy(t).cuda() for t in (L.x, L.w, L.dy))
             qx, qw, qdy = (torch.empty(t.shape, dtype=dt, device="cuda") for t in (x, w, dy))
             y, dx, dw = torch.empty(dy.shape, dtype=dt, device="cuda"), torch.empty_like(qx), torch.empty_like(qw)
-            cnt = torch.empty(6, dtype=torch.int64, device="cuda")
             eps = [Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10 + i, relu=(i == 0)) for i in range(3)]
 
-            def mk(d=d, f=f, x=x, w=w, dy=dy, qx=qx, qw=qw, qdy=qdy, y=y, dx=dx, dw=dw, cnt=cnt, eps=eps):
-                return [("quantize", lambda: ctx.quantize_batched([x, w, dy], [f] * 3, [1, 2, 3], pkg.SR, 0, outs=[qx, qw, qdy], counters=cnt)),
-                        ("fwd", lambda: ctx.conv_fwd(d, qx, f, qw, f, eps[0], out=y)),
+            def mk(d=d, f=f, qx=qx, qw=qw, qdy=qdy, y=y, dx=dx, dw=dw, eps=eps):
+                return [("fwd", lambda: ctx.conv_fwd(d, qx, f, qw, f, eps[0], out=y)),
                         ("backward", lambda: ctx.conv_backward(d, qdy, f, qw, f, qx, f, eps[1], eps[2], out_dx=dx, out_dw=dw))]
             calls += mk()
+            q_in += [x, w, dy]
+            q_out += [qx, qw, qdy]
+            q_fmt += [f] * 3
             ops = 3 * 2.0 * s.macs
             useful += ops
             issued += ops * (4 if L.wl > 8 else 1)
             q_bytes += (4.0 + (1 if L.wl <= 8 else 2)) * (x.numel() + w.numel() + dy.numel())
             kld_ws.append(w.view(-1))
         kld_args = dict(ils=[3] * len(kld_ws), wl_lo=4, wl_hi=16)
+        # Quantize of the whole network: one call, one launch per 64 tensors (the per-layer loop of Alg. 1)
+        q_cnt = torch.empty(2 * len(q_in), dtype=torch.int64, device="cuda")
+        q_streams = list(range(1, len(q_in) + 1))
+        calls.insert(0, ("quantize", lambda: ctx.quantize_batched(q_in, q_fmt, q_streams, pkg.SR, 0, outs=q_out, counters=q_cnt)))
     ncand = kld_args["wl_hi"] - kld_args["wl_lo"] + 1
     kld = torch.empty((len(kld_ws), ncand), dtype=torch.float64, device="cuda")
     sel = torch.empty((len(kld_ws), 2), dtype=torch.int32, device="cuda")
