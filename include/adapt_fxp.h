@@ -131,7 +131,11 @@ int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantize_item *ite
  * tensor must be smaller than 4 GiB (the kernels use 32-bit byte offsets): larger ones return
  * ADAPT_EUNSUPPORTED.  Reductions too long for an int32 accumulator, and weight gradients, are
  * split over K through the context's workspace (ADAPT_EWORKSPACE if it is too small); the
- * result is bit-identical to the unsplit sum.  Empty outputs (M or N = 0) return ADAPT_OK. */
+ * result is bit-identical to the unsplit sum.  Empty outputs (M or N = 0) return ADAPT_OK.
+ * Convolutions with fewer than 16 input channels work on zero-padded copies of x and w that
+ * they place in the workspace (when it has room; otherwise they gather element by element);
+ * results, output shapes and rounding bits are those of the unpadded operands.  When one operand
+ * has wl <= 8 and the other 9..16, the int8 operand is multiplied as a single limb. */
 
 /* 32 if K * 2^(wl_a-1) * 2^(wl_b-1) <= 2^31 - 1 (every possible sum fits int32), else 64. */
 int adapt_acc_bits(int64_t K, adapt_fmt a, adapt_fmt b);
