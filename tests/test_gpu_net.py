@@ -307,3 +307,36 @@ def test_precision_switch_needs_a_backward_pass_and_parameters():
     with pytest.raises(pkg.AdaptError):
         net.precision_switch(1.0)                         # no backward pass yet
     net.close()
+
+
+# ---- random small chains: narrow first layers, stride 2, mixed word lengths, pooling in any combination ---------
+
+def _random_net(rng):
+    h = w = int(rng.choice([8, 12, 16]))
+    c = int(rng.choice([1, 3, 5, 16, 24]))
+    layers, fmts = [], []
+    nconv = int(rng.integers(2, 5))
+    for i in range(nconv):
+        k = int(rng.choice([8, 16, 32, 64]))
+        r = int(rng.choice([1, 3]))
+        stride = int(rng.choice([1, 1, 2])) if h % 2 == 0 and h >= 8 else 1
+        pad = r // 2
+        L = no.Layer(h, w, c, k, r, r, stride, pad, relu=bool(rng.integers(0, 4) > 0), pool=False)
+        p, q = L.p, L.q
+        if p % 2 == 0 and q % 2 == 0 and p >= 4 and rng.integers(0, 3) == 0:
+            L.pool = True
+            p, q = p // 2, q // 2
+        layers.append(L)
+        fmts.append((int(rng.choice([4, 6, 8, 8, 11, 14, 16])), 0))
+        h, w, c = p, q, k
+    layers.append(no.Layer(1, 1, h * w * c, int(rng.choice([10, 16, 100])), 1, 1, 1, 0, relu=False, pool=False))
+    fmts.append((int(rng.choice([6, 8, 12, 16])), 0))
+    fmts = [(wl, wl - 3) for wl, _ in fmts]
+    return layers, fmts
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_chains(seed):
+    rng = np.random.default_rng(1000 + seed)
+    layers, fmts = _random_net(rng)
+    _run_chain(layers, fmts, n=int(rng.choice([2, 3, 5])), seed=100 + seed)
