@@ -29,7 +29,7 @@ PEAK_HBM_GBPS = 8000.0
 # dispatch, scaled by what a plain 256 MiB device copy reads on the same counters: x2.0 and x1.0);
 # the summary with the commands is profiles/bench_config2_hbm_traffic.md.  Counters cannot be read
 # from inside this process.  Backward = the paired dgrad + wgrad kernel plus the slab-sum kernel.
-FWD_TRAFFIC_BYTES = {"read": 3258 * 1024, "written": 6144 * 1024}
+FWD_TRAFFIC_BYTES = {"read": 3171 * 1024, "written": 6144 * 1024}
 BWD_TRAFFIC_BYTES = {"read": (12695 + 7856) * 1024, "written": (9824 + 108) * 1024}
 
 def cpu_baseline(batch: int):
@@ -506,7 +506,7 @@ def main():
                      "traffic_unit": "bytes of HBM per call (rocprofv3 --pmc, see profiles/)",
                      "algorithmic_bytes": dy.numel() + w.numel() + x.numel() + dx.numel() + dw.numel(),
                      "avg_launch_ms": bwd_ms, "avg_launch_ms_note": note},
-        "roofline_fwd": {"bound": "mfma", "kernel": "contract_kernel<fwd 64x192> (the conv_fwd call is this one launch)",
+        "roofline_fwd": {"bound": "mfma", "kernel": "contract_kernel<fwd 128x64> (the conv_fwd call is this one launch)",
                          "achieved": fwd_tops, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": fwd_tops / PEAK_INT8_TOPS,
                          "traffic": FWD_TRAFFIC_BYTES["read"] + FWD_TRAFFIC_BYTES["written"],
                          "algorithmic_bytes": x.numel() + w.numel() + y.numel(), "avg_launch_ms": fwd_ms},

@@ -1064,6 +1064,28 @@ static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
     // contractions get their parallelism from the splits instead.)
     const long long tiles128 = (long long)((a.M + 127) / 128) * ((a.N + t.bn - 1) / t.bn);
     t.bm = (!scalar && OP != OP_WGRAD && tiles128 < 2 * num_cu && a.M > 64) ? 64 : 128;
+    if (limbs == 1 && !scalar && OP != OP_WGRAD) {
+        // One limb, forward / data gradient / GEMM: the largest of the 128x128, 128x64, 64x128 and 64x64 tiles that
+        // still gives every CU two blocks (three when the reduction is short and a block's fixed costs weigh more)
+        // without much padding; 64x64 when none does.  Measured (batch 128..256, 3x3): 64->192 at 16x16 forward
+        // 12.0 us with 64x192 tiles, 10.6 with 128x64; 192->384 at 8x8 17.8 -> 14.0 (forward) and 35.9 -> 21.6
+        // (data gradient, which had been split over K); 512->512 at 4x4 28.0 -> 23.3.
+        const long long want = (long long)(a.K >= 1024 ? 2 : 3) * num_cu;
+        auto fits = [&](int bm, int bn, double &waste) {
+            const long long tm = (a.M + bm - 1) / bm, tn = (a.N + bn - 1) / bn;
+            waste = (double)(tm * bm) * (double)(tn * bn) / ((double)a.M * (double)a.N);
+            return tm * tn >= want && waste <= 1.25;
+        };
+        double w0, w1, w2;
+        t.bm = t.bn = 64;
+        if (fits(128, 128, w0)) {
+            t.bm = t.bn = 128;
+        } else {
+            const bool tall = fits(128, 64, w1), wide = fits(64, 128, w2);
+            if (tall && (!wide || w1 <= w2)) { t.bm = 128; t.bn = 64; }
+            else if (wide) { t.bm = 64; t.bn = 128; }
+        }
+    }
     if (limbs == 2 && !scalar && OP != OP_WGRAD) {
         // Two limbs: the 64x64 tile runs four resident wavefronts per SIMD (three accumulator sets fit one unified
         // register file, see min_waves_per_simd), the 128x128 tile one; 64x64 was measured faster at every size
