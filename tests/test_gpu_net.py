@@ -340,3 +340,32 @@ def test_random_chains(seed):
     rng = np.random.default_rng(1000 + seed)
     layers, fmts = _random_net(rng)
     _run_chain(layers, fmts, n=int(rng.choice([2, 3, 5])), seed=100 + seed)
+
+
+def test_alexnet_chain_full_batch_forward_matches_the_oracle_on_its_first_samples():
+    """Batch 128 is the size the benchmark times (other tiles, K splits and launch shapes than the small cases).  The
+    forward pass treats samples independently and a sample's rounding bits depend only on its element indices, so the
+    first samples of the full batch must equal the oracle's forward pass on those samples alone."""
+    batch, sub = 128, 2
+    rng = np.random.default_rng(77)
+    layers, fmts, descs = [], [], []
+    for sp, relu, pool in wk.alexnet_cifar_chain(batch=batch):
+        s = sp.shape
+        layers.append(no.Layer(s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad, relu=relu, pool=pool))
+        descs.append(LayerDesc(ConvDesc(batch, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad), int(relu), int(pool)))
+        fmts.append((sp.wl, sp.fl))
+    x = rng.standard_normal((batch, 32, 32, 3)).astype(np.float32)
+    ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * (1.5 / np.sqrt(L.r * L.s * L.c))).astype(np.float32) for L in layers]
+    big = pkg.Context(workspace_bytes=1 << 30)
+    net = pkg.Net(big, descs, [dev(w) for w in ws])
+    for l, (wl, fl) in enumerate(fmts):
+        net.set_format(l, wl, fl)
+    net.quantize_weights(seed=5, stream=9)
+    net.forward(dev(x), seed=5, stream=9)
+    wq = no.quantize_weights(layers, fmts, ws, 5, 9)
+    fwd = no.forward(layers, fmts, wq, x[:sub], 5, 9)
+    for l, L in enumerate(layers):
+        got = host(net.tensor(l, pkg.NT_A)).astype(np.int64).reshape(L.out_shape(batch))[:sub]
+        assert np.array_equal(got, fwd["a"][l]), l
+    net.close()
+    big.close()
