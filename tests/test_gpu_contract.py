@@ -472,3 +472,48 @@ def test_gemm_mixed_worst_case_and_transposes(ta, tb, wla, wlb):
     ep = Epilogue.requant(12, 0, pkg.SR, seed=2, stream=9)
     c = ctx().fxp_gemm(da, (wla, 7), db, (wlb, 7), ep, trans_a=bool(ta), trans_b=bool(tb))
     assert np.array_equal(host(c).astype(np.int64), orc.requantize(orc.gemm(a, b), 14, 12, orc.SR, 2, 9))
+
+
+# ---- the launch configurations of the full bench sizes, checked against runs that the oracle tests cover --------
+
+def _full_batch_consistency(specs):
+    """Forward and data gradient treat samples independently and the weight gradient is a sum over samples: the full
+    batch (tiles, K splits and pairings of the size the benchmark times) must reproduce, exactly, what small-batch
+    runs of the same layer give (those configurations are compared with the oracle in the sweeps above)."""
+    c = pkg.Context(workspace_bytes=1 << 30)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    for sp in specs:
+        s = sp.shape
+        wl = sp.wl
+        dt = torch.int8 if wl <= 8 else torch.int16
+        lo, hi = -(1 << (wl - 1)), 1 << (wl - 1)
+        d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+        x = torch.randint(lo, hi, (s.n, s.h, s.w, s.c), device="cuda", generator=g, dtype=torch.int32).to(dt)
+        wt = torch.randint(lo, hi, (s.k, s.r, s.s, s.c), device="cuda", generator=g, dtype=torch.int32).to(dt)
+        dy = torch.randint(lo, hi, (s.n, d.p, d.q, s.k), device="cuda", generator=g, dtype=torch.int32).to(dt)
+        f = (wl, wl - 3)
+        ex = Epilogue.exact()
+        ep = Epilogue.requant(wl, wl - 3, pkg.SR, 1, 40, relu=True)
+        sub = 2
+        ds = ConvDesc(sub, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+        y = c.conv_fwd(d, x, f, wt, f, ep)
+        assert torch.equal(y[:sub], c.conv_fwd(ds, x[:sub].contiguous(), f, wt, f, ep)), sp.name
+        dx, dw = c.conv_backward(d, dy, f, wt, f, x, f, ex, ex)
+        assert torch.equal(dx[:sub], c.conv_dgrad(ds, dy[:sub].contiguous(), f, wt, f, ex)), sp.name
+        chunk = s.n // 8
+        dc = ConvDesc(chunk, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+        total = torch.zeros(dw.shape, dtype=torch.int64, device="cuda")
+        for i in range(8):
+            part = c.conv_wgrad(dc, dy[i * chunk:(i + 1) * chunk].contiguous(), f, x[i * chunk:(i + 1) * chunk].contiguous(), f, ex)
+            total += part.to(torch.int64)
+        assert torch.equal(dw.to(torch.int64), total), sp.name
+    c.close()
+
+
+def test_config4_full_batch_launch_configurations():
+    _full_batch_consistency(wk.alexnet_cifar_layers())
+
+
+def test_config5_full_batch_launch_configurations():
+    _full_batch_consistency(wk.resnet18_cifar_layers())
