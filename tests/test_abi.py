@@ -63,3 +63,17 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "one GPU" in r.stderr
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, and every declared function must be usable
+    from C (its address is taken below)."""
+    import subprocess
+    names = _declared()
+    src = tmp_path / "use_header.c"
+    body = ",\n".join(f"    (fn){n}" for n in names)
+    src.write_text('#include "adapt_fxp.h"\n\ntypedef void (*fn)(void);\nfn table[] = {\n' + body + "\n};\n")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
