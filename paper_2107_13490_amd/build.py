@@ -33,13 +33,21 @@ def _run(cmd, verbose):
 
 def build(verbose: bool = False, only=None, extra_flags=(), lib=LIB, objdir=OBJDIR) -> str:
     """Compiles every source to an object (in parallel) and links the shared library.
-    `only` restricts recompilation to the named sources (the other objects must exist)."""
+    `only` restricts recompilation to the named sources plus whatever is out of date."""
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(objdir, exist_ok=True)
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
-    jobs = [(s, o) for s, o in zip(SOURCES, objs) if only is None or s in only or not os.path.exists(o)]
+    # an object older than its source or than any header is rebuilt even when `only` does not name it: the
+    # structs that cross translation units (kernel arguments, plans) must have one layout in the whole library
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    headers += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h")]
+    newest_header = max(os.path.getmtime(h) for h in headers)
+
+    def stale(src, obj):
+        return not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(os.path.join(CSRC, src)), newest_header)
+    jobs = [(s, o) for s, o in zip(SOURCES, objs) if only is None or s in only or stale(s, o)]
     with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as ex:
         list(ex.map(lambda so: _run([hipcc, *FLAGS, *extra_flags, *inc, "-c", os.path.join(CSRC, so[0]), "-o", so[1]], verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], verbose)
