@@ -37,9 +37,10 @@ typedef enum {
     ADAPT_OK = 0,
     ADAPT_EINVAL = -1,       /* null / misaligned pointer, size, WL, FL, bins or range out of bounds */
     ADAPT_EUNSUPPORTED = -2, /* valid request this build does not implement (WL > 16, dilation, groups) */
-    ADAPT_EBOUND = -3,       /* exact result does not fit the requested accumulator / output type */
+    ADAPT_EBOUND = -3,       /* the reduction is too long for one block's int32 accumulators and the workspace
+                                cannot hold the partial sums of the splits that would keep them in bounds */
     ADAPT_EHIP = -4,         /* HIP runtime failure (see adapt_error_string / hipGetLastError) */
-    ADAPT_EWORKSPACE = -5    /* context workspace too small for this call */
+    ADAPT_EWORKSPACE = -5    /* context workspace too small for this call (see adapt_workspace_bytes) */
 } adapt_status;
 
 typedef struct adapt_ctx adapt_ctx; /* opaque: stream, device, workspace */
@@ -82,6 +83,47 @@ typedef struct { int raw; adapt_fmt fmt; adapt_rng rng; int relu; } adapt_epilog
 int adapt_create(adapt_ctx **ctx, void *hip_stream, size_t workspace_bytes);
 int adapt_destroy(adapt_ctx *ctx);
 int adapt_set_stream(adapt_ctx *ctx, void *hip_stream);
+
+/* How much workspace a call takes, from the planning code the call itself runs (the boundary the
+ * paper's operations need once they are library calls: Quantize, the layer contractions, PushDown,
+ * PushUp and the update all stage partial results on the device).  Fill `call` and the fields that
+ * call reads; the others are ignored:
+ *   QUANTIZE, SGD_UPDATE, REQUANTIZE_FIT   n
+ *   QUANTIZE_BATCHED                       count
+ *   GEMM                                   transA, transB, M, N, K, fa, fb, lda, ldb (0 = dense)
+ *   CONV_FWD                               conv, fa = format of x, fb = of w
+ *   CONV_DGRAD                             conv, fa = dy, fb = w
+ *   CONV_WGRAD                             conv, fa = dy, fb = x
+ *   CONV_BACKWARD                          conv, fa = dy, fb = w, fc = x
+ *   KLD_SEARCH                             n, wl_lo, wl_hi, bins
+ *   KLD_SEARCH_BATCHED                     kld_items (HOST array; only n and bins are read), count, wl_lo, wl_hi
+ *   GRADIENT_DIVERSITY                     n, count
+ * Returns the workspace_bytes with which the call takes its preferred plan (all K splits, padded
+ * copies of narrow layers, one batch for up to 24 searches) and returns neither ADAPT_EWORKSPACE nor
+ * ADAPT_EBOUND; 0 for a query that is invalid.  With less, contractions use fewer K splits and
+ * batched searches smaller batches where they can.  ctx may be NULL: the current device is asked
+ * for its number of compute units.  Host pointers; no device work. */
+typedef enum {
+    ADAPT_CALL_QUANTIZE = 0, ADAPT_CALL_QUANTIZE_BATCHED = 1, ADAPT_CALL_GEMM = 2, ADAPT_CALL_CONV_FWD = 3,
+    ADAPT_CALL_CONV_DGRAD = 4, ADAPT_CALL_CONV_WGRAD = 5, ADAPT_CALL_CONV_BACKWARD = 6, ADAPT_CALL_KLD_SEARCH = 7,
+    ADAPT_CALL_KLD_SEARCH_BATCHED = 8, ADAPT_CALL_SGD_UPDATE = 9, ADAPT_CALL_GRADIENT_DIVERSITY = 10,
+    ADAPT_CALL_REQUANTIZE_FIT = 11
+} adapt_call;
+struct adapt_kld_item_s;
+typedef struct {
+    int call;
+    uint64_t n;
+    int count;
+    int transA, transB, M, N, K, lda, ldb;
+    adapt_conv_desc conv;
+    adapt_fmt fa, fb, fc;
+    int wl_lo, wl_hi, bins;
+    const struct adapt_kld_item_s *kld_items;
+} adapt_workspace_query;
+size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_workspace_query *query);
+/* Grows the context's workspace to at least `bytes` (never shrinks it).  Synchronises the stream
+ * and allocates when it has to grow; call it while setting up, not inside a step. */
+int adapt_reserve_workspace(adapt_ctx *ctx, size_t bytes);
 const char *adapt_error_string(int status);
 /* Library / ABI version (incremented on incompatible changes). */
 int adapt_version(void);
@@ -130,8 +172,10 @@ int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantize_item *ite
  * accumulators: int32_t if adapt_acc_bits() is 32, else int64_t; or requantized codes).  Every
  * tensor must be smaller than 4 GiB (the kernels use 32-bit byte offsets): larger ones return
  * ADAPT_EUNSUPPORTED.  Reductions too long for an int32 accumulator, and weight gradients, are
- * split over K through the context's workspace (ADAPT_EWORKSPACE if it is too small); the
- * result is bit-identical to the unsplit sum.  Empty outputs (M or N = 0) return ADAPT_OK.
+ * split over K through the context's workspace; the result is bit-identical to the unsplit sum.
+ * With too little workspace for the preferred number of splits fewer are taken; ADAPT_EBOUND if
+ * even the splits that the int32 accumulators of a block require (K above 65,536 with both
+ * operands at most 8 bits, above 32,768 otherwise) do not fit.  Empty outputs (M or N = 0) return ADAPT_OK.
  * Convolutions with fewer than 16 input channels work on zero-padded copies of x and w that
  * they place in the workspace (when it has room; otherwise they gather element by element);
  * results, output shapes and rounding bits are those of the unpadded operands.  When one operand
@@ -208,7 +252,7 @@ int adapt_kld_precision_search_ranged(adapt_ctx *ctx, const float *w, size_t n, 
  * device pointer); tensor t writes kld[t*ncand ...] and
  * sel[2t], sel[2t+1], with ncand = wl_hi - wl_lo + 1.  il, bins and the rng stream are per
  * tensor; candidate range, eps, alpha, mode and seed are shared. */
-typedef struct {
+typedef struct adapt_kld_item_s {
     const float *w; uint64_t n; int32_t il, bins; uint64_t stream;
 } adapt_kld_item;
 int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kld_item *items, int count,

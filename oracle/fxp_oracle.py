@@ -26,6 +26,7 @@ Integers are int64 / Python ints, floating point is fp64.
 from __future__ import annotations
 
 import math
+import os
 
 import numpy as np
 
@@ -118,7 +119,23 @@ def quantize_with_bits(x, wl: int, fl: int, rbits):
 
 def rounding_bits(n: int, mode: int, seed: int, stream: int, start: int = 0) -> np.ndarray:
     if mode == SR:
-        return r16(seed, stream, np.arange(start, start + n, dtype=np.uint64))
+        # drawn in blocks of 2^20 elements, the blocks spread over the host's cores: the same values as one call of
+        # r16 over the whole index range, with temporaries that stay in the caches
+        out = np.empty(n, dtype=np.int64)
+
+        def block(a):
+            b = min(n, a + (1 << 20))
+            out[a:b] = r16(seed, stream, np.arange(start + a, start + b, dtype=np.uint64))
+
+        starts = range(0, n, 1 << 20)
+        if len(starts) > 1:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(max_workers=min(len(starts), os.cpu_count() or 1)) as pool:
+                list(pool.map(block, starts))
+        else:
+            for a in starts:
+                block(a)
+        return out
     if mode == RN_HALF_UP:
         return np.full(n, 1 << 15, dtype=np.int64)
     raise ValueError("unknown rounding mode")
@@ -151,7 +168,7 @@ def gemm(a, b, trans_a: bool = False, trans_b: bool = False) -> np.ndarray:
 
 
 def requantize(acc, shift: int, wl_o: int, mode: int = SR, seed: int = 0, stream: int = 0,
-               relu: bool = False) -> np.ndarray:
+               relu: bool = False, start: int = 0) -> np.ndarray:
     """Exact accumulator (FL_a+FL_b fractional bits) -> <wl_o, FL_o>, shift = FL_a+FL_b-FL_o.
 
     shift <= 0 : multiply by 2^-shift.
@@ -159,14 +176,14 @@ def requantize(acc, shift: int, wl_o: int, mode: int = SR, seed: int = 0, stream
                  arithmetic shift right.
     > 16       : drop shift-16 bits first (floor), then 16 guard bits as in `quantize`.
     ReLU (optional) and saturation come last.  Element i of the flattened output uses
-    r16(seed, stream, i).
+    r16(seed, stream, start + i): `start` > 0 converts a slice of a larger tensor.
     """
     a = np.asarray(acc, dtype=np.int64)
     flat = a.ravel()
     if shift <= 0:
         q = flat * (1 << (-shift))
     else:
-        bits = rounding_bits(flat.size, mode, seed, stream)
+        bits = rounding_bits(flat.size, mode, seed, stream, start)
         if shift <= 16:
             r = bits >> (16 - shift)
             q = (flat + r) >> shift

@@ -66,6 +66,17 @@ class KldItem(C.Structure):
                 ("stream", C.c_uint64)]
 
 
+class WorkspaceQuery(C.Structure):
+    _fields_ = [("call", C.c_int), ("n", C.c_uint64), ("count", C.c_int), ("transA", C.c_int), ("transB", C.c_int),
+                ("M", C.c_int), ("N", C.c_int), ("K", C.c_int), ("lda", C.c_int), ("ldb", C.c_int), ("conv", ConvDesc),
+                ("fa", Fmt), ("fb", Fmt), ("fc", Fmt), ("wl_lo", C.c_int), ("wl_hi", C.c_int), ("bins", C.c_int),
+                ("kld_items", C.POINTER(KldItem))]
+
+
+(CALL_QUANTIZE, CALL_QUANTIZE_BATCHED, CALL_GEMM, CALL_CONV_FWD, CALL_CONV_DGRAD, CALL_CONV_WGRAD, CALL_CONV_BACKWARD,
+ CALL_KLD_SEARCH, CALL_KLD_SEARCH_BATCHED, CALL_SGD_UPDATE, CALL_GRADIENT_DIVERSITY, CALL_REQUANTIZE_FIT) = range(12)
+
+
 class GradItem(C.Structure):
     _fields_ = [("g", C.c_void_p), ("wl", C.c_int32), ("fl", C.c_int32)]
 
@@ -132,6 +143,9 @@ def load_library():
     lib.adapt_destroy.argtypes = [vp]
     lib.adapt_set_stream.argtypes = [vp, vp]
     lib.adapt_acc_bits.argtypes = [i64, Fmt, Fmt]
+    lib.adapt_workspace_bytes.argtypes = [vp, C.POINTER(WorkspaceQuery)]
+    lib.adapt_workspace_bytes.restype = sz
+    lib.adapt_reserve_workspace.argtypes = [vp, sz]
     lib.adapt_quantize.argtypes = [vp, vp, sz, Fmt, Rng, vp, vp, vp]
     lib.adapt_quantize_batched.argtypes = [vp, C.POINTER(QuantizeItem), i, i, u64, vp]
     lib.adapt_quantize_batched_ranges.argtypes = [vp, C.POINTER(QuantizeItem), i, i, u64, vp, vp, u64]
@@ -275,6 +289,45 @@ class Context:
     @property
     def handle(self):
         return self._h
+
+    def workspace_bytes(self, call, **fields) -> int:
+        """adapt_workspace_bytes for one call: `call` is a CALL_* constant, `fields` the query fields that call reads
+        (formats as (wl, fl) pairs, `conv` a ConvDesc, `kld_items` a list of (n, bins))."""
+        q = WorkspaceQuery()
+        q.call = call
+        keep = None
+        for k, v in fields.items():
+            if k in ("fa", "fb", "fc"):
+                v = Fmt(*v) if not isinstance(v, Fmt) else v
+            if k == "kld_items":
+                keep = (KldItem * max(len(v), 1))()
+                for t, (n, bins) in enumerate(v):
+                    keep[t] = KldItem(None, n, 1, bins, 0)
+                q.count = len(v)
+                v = keep
+            setattr(q, k, v)
+        need = self._lib.adapt_workspace_bytes(self._h, C.byref(q))
+        if need == 0:
+            raise AdaptError(-1, "adapt_workspace_bytes")
+        return need
+
+    def reserve_workspace(self, nbytes: int):
+        _check(self._lib.adapt_reserve_workspace(self._h, nbytes), "adapt_reserve_workspace")
+
+    def reserve_for_layers(self, layers, kld_bins=None, wl_lo=2, wl_hi=16):
+        """Grows the workspace to what the forward and backward calls of the given layers need, and, with `kld_bins`, one
+        batched precision search over their weight tensors.  layers: iterable of (ConvDesc, fx, fw, fdy) with (wl, fl) pairs."""
+        need = 0
+        items = []
+        for d, fx, fw, fdy in layers:
+            need = max(need, self.workspace_bytes(CALL_CONV_FWD, conv=d, fa=fx, fb=fw),
+                       self.workspace_bytes(CALL_CONV_BACKWARD, conv=d, fa=fdy, fb=fw, fc=fx))
+            items.append((d.k * d.r * d.s * d.c, kld_bins))
+        if kld_bins:
+            need = max(need, self.workspace_bytes(CALL_KLD_SEARCH_BATCHED, kld_items=items, wl_lo=wl_lo, wl_hi=wl_hi))
+        need = max(need, self.workspace_bytes(CALL_QUANTIZE_BATCHED, count=64))
+        self.reserve_workspace(need)
+        return need
 
     @staticmethod
     def storage_dtype(wl: int):

@@ -6,24 +6,6 @@
 
 #include "adapt_fxp.h"
 
-#ifdef ADAPT_PROF
-// development builds only: phase timestamps of block 0 (s_memtime ticks) and begin/end of every
-// block, one array per source file
-static __device__ unsigned long long g_adapt_prof[64 + 2 * 4096];
-#define ADAPT_STAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_adapt_prof[i] = clock64(); } while (0)
-#define ADAPT_STAMP_WG(which) do { const unsigned l_ = blockIdx.y * gridDim.x + blockIdx.x; \
-    if (threadIdx.x == 0 && l_ < 4096) g_adapt_prof[64 + 2 * l_ + (which)] = wall_clock64(); } while (0)
-#define ADAPT_STAMP_WG4(which) do { const unsigned l_ = blockIdx.y * gridDim.x + blockIdx.x; \
-    if (threadIdx.x == 0 && l_ < 2048) g_adapt_prof[64 + 4 * l_ + (which)] = clock64(); } while (0)
-#define ADAPT_PROF_GETTER(name) extern "C" int name(unsigned long long *host_out) { \
-    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_adapt_prof), sizeof(unsigned long long) * (64 + 2 * 4096)) == hipSuccess ? 0 : -4; }
-#else
-#define ADAPT_STAMP(i) do { } while (0)
-#define ADAPT_STAMP_WG(which) do { } while (0)
-#define ADAPT_STAMP_WG4(which) do { } while (0)
-#define ADAPT_PROF_GETTER(name)
-#endif
-
 namespace adapt {
 
 constexpr int kWave = 64;

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "adapt_fxp.h"
 
 struct adapt_ctx {
@@ -17,6 +19,8 @@ struct adapt_ctx {
     char *ws;
     size_t ws_bytes;
     hipError_t last_hip_error;
+    // kernels whose dynamic LDS limit this context has already raised above the 64 KiB default
+    std::vector<const void *> big_lds_kernels;
 };
 
 namespace adapt {
@@ -36,6 +40,27 @@ inline int hip_status(adapt_ctx *c, hipError_t e)
     c->last_hip_error = e;
     return ADAPT_EHIP;
 }
+
+// A kernel that wants more than 64 KiB of dynamic LDS needs the limit raised once before its first launch;
+// the context remembers which kernels it has done that for (no process-wide state).
+inline hipError_t allow_big_lds(adapt_ctx *c, const void *kernel, size_t lds_bytes)
+{
+    if (lds_bytes <= 64 * 1024) return hipSuccess;
+    for (const void *k : c->big_lds_kernels)
+        if (k == kernel) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e == hipSuccess) c->big_lds_kernels.push_back(kernel);
+    return e;
+}
+
+// Bytes of scratch the calls of each source file take at most for the given sizes (adapt_workspace_bytes)
+size_t ws_need_quantize(int num_cu, uint64_t n);
+size_t ws_need_quantize_batched(int num_cu, int count);
+size_t ws_need_kld_search(int num_cu, uint64_t n, int wl_lo, int wl_hi, int bins);
+size_t ws_need_kld_search_batched(int num_cu, const adapt_kld_item *items, int count, int wl_lo, int wl_hi);
+size_t ws_need_sgd_update(int num_cu, uint64_t n);
+size_t ws_need_gradient_diversity(uint64_t n, int count);
+size_t ws_need_requantize_fit(int num_cu, uint64_t n);
 
 inline bool fmt_ok(adapt_fmt f) { return f.wl >= 2 && f.wl <= 16 && f.fl >= 0 && f.fl <= 31; }
 inline int storage_bytes(adapt_fmt f) { return f.wl <= 8 ? 1 : 2; }

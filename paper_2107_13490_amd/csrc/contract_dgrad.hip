@@ -3,7 +3,6 @@
 
 using namespace adapt;
 
-ADAPT_PROF_GETTER(adapt_debug_prof_dgrad)
 
 extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *w,
                                 adapt_fmt fw, void *dx, adapt_epilogue ep)

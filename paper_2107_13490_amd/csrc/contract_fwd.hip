@@ -3,7 +3,6 @@
 
 using namespace adapt;
 
-ADAPT_PROF_GETTER(adapt_debug_prof_fwd)
 
 extern "C" int adapt_conv_fwd(adapt_ctx *ctx, adapt_conv_desc d, const void *x, adapt_fmt fx, const void *w, adapt_fmt fw,
                               void *y, adapt_epilogue ep)

@@ -599,14 +599,14 @@ __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m
 // ---------------------------------------------------------------------------------------------
 // the kernel: block tile BM x BN, 4 wavefronts in a WGM x WGN grid, wave tile (BM/WGM) x (BN/WGN)
 // built from 32x32 MFMA blocks; BKT reduction indices per stage.  One LDS stage: the global
-// loads of the next PF stages are in flight (in registers) while the MFMAs of the current one
+// loads of the next stage are in flight (in registers) while the MFMAs of the current one
 // run; several blocks per CU cover the rest of the load latency and each other's epilogues.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
 
 // `lin` of `nwg` blocks, `ntiles` output tiles (the rest of the factor nwg / ntiles are K splits);
 // `smem` is the block's dynamic LDS.
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PF>
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
 __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsigned lin, const unsigned nwg,
                                               const unsigned ntiles, char *const smem)
 {
@@ -685,25 +685,21 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
 #pragma unroll
     for (int i = 0; i < NB; ++i) sum_n[i] = 0;
 
-    ADAPT_STAMP(0);
-    ADAPT_STAMP_WG(0);
     LA la;
     LB lb;
     la.init(a, m0);
     lb.init(a, n0);
-    ADAPT_STAMP(1);
-    // Register staging, PF stages deep: the global loads of stages kt+1 .. kt+PF are in flight while
-    // stage kt is multiplied out of LDS.
-    typename LA::Regs ra[PF];
-    typename LB::Regs rb[PF];
-#pragma unroll
-    for (int u = 0; u < PF; ++u)
-        if (u < ksteps) {
-            const int k0 = stage_k(u);
-            la.load(a, m0, k0, ra[u]);
-            lb.load(a, n0, k0, rb[u]);
-        }
-    ADAPT_STAMP(2);
+    // Register staging: the global loads of stage kt+1 are in flight while stage kt is multiplied out
+    // of LDS.  (Two and three stages in flight were measured no faster at any tile shape: a stage is
+    // bound by the rate at which the CU's vector-memory and LDS pipes move the operand bytes, not by
+    // the latency of the loads, and the extra staging registers cost the large tiles a resident block.)
+    typename LA::Regs ra;
+    typename LB::Regs rb;
+    if (ksteps > 0) {
+        const int k0 = stage_k(0);
+        la.load(a, m0, k0, ra);
+        lb.load(a, n0, k0, rb);
+    }
 
     auto multiply_stage = [&]() {
 #pragma unroll
@@ -759,31 +755,19 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
         }
     };
 
-    for (int kt0 = 0; kt0 < ksteps; kt0 += PF) {
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int kt = kt0 + u;
-            if (kt < ksteps) {
-                ADAPT_STAMP(8 + 5 * min(kt, 10));
-                __syncthreads();                 // every wavefront is done with the previous stage
-                ADAPT_STAMP(9 + 5 * min(kt, 10));
-                LA::store(ra[u], a_hi, a_lo);
-                LB::store(rb[u], b_hi, b_lo);
-                __syncthreads();
-                ADAPT_STAMP(10 + 5 * min(kt, 10));
-                if (kt + PF < ksteps) {
-                    const int k0 = stage_k(kt + PF);
-                    la.load(a, m0, k0, ra[u]);
-                    lb.load(a, n0, k0, rb[u]);
-                }
-                ADAPT_STAMP(11 + 5 * min(kt, 10));
-                multiply_stage();
-                ADAPT_STAMP(12 + 5 * min(kt, 10));
-            }
+    for (int kt = 0; kt < ksteps; ++kt) {
+        __syncthreads();                 // every wavefront is done with the previous stage
+        LA::store(ra, a_hi, a_lo);
+        LB::store(rb, b_hi, b_lo);
+        __syncthreads();
+        if (kt + 1 < ksteps) {
+            const int k0 = stage_k(kt + 1);
+            la.load(a, m0, k0, ra);
+            lb.load(a, n0, k0, rb);
         }
+        multiply_stage();
     }
 
-    ADAPT_STAMP(3);
     // ---- epilogue -----------------------------------------------------------------------------
     // lane holds, for block (i,j): m = m0 + wm*WM + j*32 + l32 and 16 values of n (see above)
     long long corr_m[MB];
@@ -847,8 +831,6 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                 emit_run<16, LIMBS == 1>(a, out, m, nb0 + 16 * g, v);
             }
         }
-    ADAPT_STAMP(4);
-    ADAPT_STAMP_WG(1);
 }
 
 // Two-limb 64x64 tiles: three accumulator sets and the staging registers land a few registers above what three
@@ -866,12 +848,12 @@ constexpr int min_waves_per_simd(int op, int limbs, int amode, int wmode, int ae
     return (op != OP_WGRAD && limbs == 2 && aes == 2 && wes == 2 && bm == 64 && bn == 64) ? 3 : 1;
 }
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PF>
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
 __global__ void __launch_bounds__(kThreads, min_waves_per_simd(OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN))
 contract_kernel(const ContractArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    contract_body<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PF>(a, blockIdx.y * gridDim.x + blockIdx.x,
+    contract_body<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT>(a, blockIdx.y * gridDim.x + blockIdx.x,
                                                                                gridDim.x * gridDim.y, gridDim.x, smem);
 }
 
@@ -886,9 +868,9 @@ contract_pair_kernel(const ContractArgs a, const ContractArgs b, const unsigned 
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     if (blockIdx.x < n_first)
-        contract_body<OPA, LIMBS, AMA, WMA, LIMBS, LIMBS, BMA, BNA, 2, 2, BKT, 1>(a, blockIdx.x, n_first, tiles_a, smem);
+        contract_body<OPA, LIMBS, AMA, WMA, LIMBS, LIMBS, BMA, BNA, 2, 2, BKT>(a, blockIdx.x, n_first, tiles_a, smem);
     else
-        contract_body<OPB, LIMBS, AMB, WMB, LIMBS, LIMBS, BMB, BNB, 2, 2, BKT, 1>(b, blockIdx.x - n_first, gridDim.x - n_first,
+        contract_body<OPB, LIMBS, AMB, WMB, LIMBS, LIMBS, BMB, BNB, 2, 2, BKT>(b, blockIdx.x - n_first, gridDim.x - n_first,
                                                                                  tiles_b, smem);
 }
 
@@ -933,20 +915,6 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 // ---- host side ---------------------------------------------------------------------------------
 struct TileShape { int bm, bn, bkt; };
 
-// Stages of global loads kept in flight in registers.  Depths 2 and 3 were measured no faster at
-// any tile shape: a stage is bound by the rate at which the CU's vector-memory and LDS pipes move
-// the operand bytes (issuing the loads of a stage takes as long as multiplying it), not by the
-// latency of the loads, and the extra staging registers cost the large tiles their second
-// resident block.  The kernel keeps the parameter; every instantiation uses depth 1.
-constexpr int prefetch_depth(int /*limbs*/, int /*amode*/, int /*bm*/, int /*bn*/, int /*bkt*/)
-{
-#ifdef ADAPT_PF_OVERRIDE
-    return ADAPT_PF_OVERRIDE;
-#else
-    return 1;
-#endif
-}
-
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
 static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
@@ -955,14 +923,8 @@ static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
     typedef typename LoaderSelect<OP, false, WMODE, BN, LBL, BKT, WES>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const size_t lds = std::max<size_t>((size_t)LA::TILE_BYTES * LAL + (size_t)LB::TILE_BYTES * LBL, 4 * 4 * 32 * sizeof(int) * 4);
-    constexpr int PF = prefetch_depth(LIMBS, AMODE, BM, BN, BKT);
-    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PF>;
-    static bool attr_done = false;
-    if (!attr_done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT>;
+    if (hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(kern), lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(tiles, splits), dim3(kThreads), lds, ctx->stream, a);
     return hipGetLastError();
 }
@@ -1003,16 +965,8 @@ static hipError_t launch_tile(adapt_ctx *ctx, const ContractArgs &a, int splits,
         if constexpr (LIMBS == 1)
             if (t.bkt == 192) {
                 if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 192>(ctx, a, splits, t);
-#ifdef ADAPT_TUNE
-                if constexpr (OP == OP_FWD)
-                    if (t.bm == 256) return launch_bn<OP, LIMBS, AMODE, WMODE, 256, 192>(ctx, a, splits, t);
-#endif
                 return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 192>(ctx, a, splits, t);
             }
-#ifdef ADAPT_TUNE
-        if constexpr (LIMBS == 1 && OP == OP_FWD)
-            if (t.bm == 256) return launch_bn<OP, LIMBS, AMODE, WMODE, 256, 64>(ctx, a, splits, t);
-#endif
         if (t.bm == 64) return launch_bn<OP, LIMBS, AMODE, WMODE, 64, 64>(ctx, a, splits, t);
         return launch_bn<OP, LIMBS, AMODE, WMODE, 128, 64>(ctx, a, splits, t);
     }
@@ -1141,12 +1095,15 @@ struct ContractPlan {
     int limbs, bits, splits;
     const char *acc;        // slabs
     bool empty;             // nothing to do (M or N is 0)
+    size_t ws_end;          // bytes of scratch in use after this contraction's slabs
 };
 
 template <int OP>
 static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_fmt fb, adapt_epilogue ep,
-                            size_t ws_offset /* bytes of scratch already in use */, ContractPlan &p)
+                            size_t ws_offset /* bytes of scratch already in use */, ContractPlan &p,
+                            size_t ws_limit = (size_t)-1 /* bytes of scratch there are; default: the context's */)
 {
+    if (ws_limit == (size_t)-1) ws_limit = scratch_bytes(ctx);
     const int limbs = (fa.wl > 8 || fb.wl > 8) ? 2 : 1;
     const int bits = adapt_acc_bits(a.k_bound ? a.k_bound : a.K, fa, fb);
     int final_mode;
@@ -1167,6 +1124,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     p.empty = a.M == 0 || a.N == 0;
     p.splits = 1;
     p.acc = nullptr;
+    p.ws_end = ws_offset;
     if (p.empty) return ADAPT_OK;
 
     TileShape t = pick_tile<OP>(a, limbs, ctx->num_cu);
@@ -1178,11 +1136,6 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     const bool want_dg = OP == OP_DGRAD && a.stride == 2 && a.h % 2 == 0 && a.w % 2 == 0 && a.act_load == LOAD_VEC &&
                          a.k % 64 == 0 && a.r * a.s <= 32;
     if (want_dg && a.k % t.bkt != 0) t.bkt = 64;
-#ifdef ADAPT_TUNE
-    int tune_splits = 0;
-    if (getenv("ADAPT_NOREMAP")) a.xcd_remap = 0;
-    if (const char *env = getenv("ADAPT_TILE")) sscanf(env, "%d,%d,%d,%d", &t.bm, &t.bn, &t.bkt, &tune_splits);
-#endif
     const long long tiles = (long long)((a.M + t.bm - 1) / t.bm) * ((a.N + t.bn - 1) / t.bn);
     // int32 accumulators: |product| <= 2^14 per limb pair, the cross accumulator holds two per k
     const int k_cap = limbs == 1 ? 65536 : 32768;
@@ -1196,9 +1149,6 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
         const long long max_by_k = a.K / (4 * t.bkt);
         splits = (int)std::max<long long>(splits, std::min(want, std::max(1ll, max_by_k)));
     }
-#ifdef ADAPT_TUNE
-    if (tune_splits > 0) splits = tune_splits;
-#endif
     if (splits < 1) splits = 1;
     int k_per = ((a.K + splits - 1) / splits + t.bkt - 1) / t.bkt * t.bkt;
     if (k_per == 0) k_per = t.bkt;
@@ -1222,6 +1172,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     }
     p.tile = t;
     p.splits = splits;
+    p.ws_end = ws_offset;
     if (splits == 1 && !a.force_finish) {
         a.out_mode = final_mode;
         p.kern = a;
@@ -1231,8 +1182,31 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     const size_t acc_bytes = bits == 32 ? 4 : 8;
     const size_t slab = (size_t)a.M * a.N * acc_bytes;
     const size_t off = (ws_offset + 255) & ~(size_t)255;
-    if (off + slab * splits > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
-    char *acc = scratch(ctx) + off;
+    const size_t room = ws_limit > off ? ws_limit - off : 0;
+    if (slab * (size_t)splits > room) {
+        // Not enough workspace for the preferred number of splits: take as many as fit.  Splits that only
+        // serve parallelism may go down to none (the result is the same, only slower); the splits that
+        // keep a block's int32 accumulators inside their bound may not.
+        const int must = std::max(1, (a.K + k_cap - 1) / k_cap);
+        int take = (int)std::min<size_t>(room / slab, (size_t)splits);
+        if (take < must) {
+            if (must > 1) return ADAPT_EBOUND;
+            if (a.force_finish) return ADAPT_EWORKSPACE;
+            take = 1;                                  // unsplit, straight to the output: no workspace needed
+        }
+        k_per = ((a.K + take - 1) / take + t.bkt - 1) / t.bkt * t.bkt;
+        if (k_per == 0) k_per = t.bkt;
+        splits = a.K == 0 ? 1 : (a.K + k_per - 1) / k_per;
+        a.k_per_split = k_per;
+        p.splits = splits;
+        if (splits == 1 && !a.force_finish) {
+            a.out_mode = final_mode;
+            p.kern = a;
+            return ADAPT_OK;
+        }
+    }
+    p.ws_end = off + slab * (size_t)splits;
+    char *acc = ctx->ws ? scratch(ctx) + off : nullptr;      // no workspace: a sizing query, nothing is launched
     p.acc = acc;
     p.kern = a;
     p.kern.out = acc;
@@ -1438,6 +1412,25 @@ static void unpad_wgrad_finish(ContractPlan &p, const adapt_conv_desc &d)
     p.fin.ldc = p.fin.N;
     p.fin.pad_c = d.c;
     p.fin.pad_to = kPadC;
+}
+
+static void fill_gemm(ContractArgs &a, int transA, int transB, int M, int N, int K, const void *A, adapt_fmt fa, int lda,
+                      const void *B, adapt_fmt fb, int ldb, void *C, int ldc)
+{
+    a.act = A; a.wgt = B; a.out = C;
+    a.M = M; a.N = N; a.K = K;
+    a.act_es = storage_bytes(fa); a.wgt_es = storage_bytes(fb);
+    // extents: the last row may be shorter than the leading dimension
+    a.act_bytes = (uint32_t)((((long long)(transA ? K : M) - 1) * lda + (transA ? M : K)) * a.act_es);
+    a.wgt_bytes = (uint32_t)((((long long)(transB ? N : K) - 1) * ldb + (transB ? K : N)) * a.wgt_es);
+    a.act_rs = transA ? 1 : lda; a.act_ks = transA ? lda : 1;
+    a.wgt_rs = transB ? ldb : 1; a.wgt_ks = transB ? 1 : ldb;
+    // vector paths need whole 16-element groups (along k, or along rows) inside the matrix and aligned starts
+    a.act_load = !transA ? ((K % 16 == 0 && lda % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
+                         : ((M % 16 == 0 && lda % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR);
+    a.wgt_load = transB ? ((K % 16 == 0 && ldb % 16 == 0) ? LOAD_VEC : LOAD_SCALAR)
+                        : ((N % 16 == 0 && ldb % 16 == 0) ? LOAD_ROWS : LOAD_SCALAR);
+    a.ldc = ldc;
 }
 
 static bool check_ptrs(const void *x, const void *y, const void *z) { return x && y && z && aligned16(x) && aligned16(y) && aligned16(z); }

@@ -14,12 +14,7 @@ static hipError_t launch_pair(adapt_ctx *ctx, const ContractPlan &d, const Contr
     typedef typename LoaderSelect<OP_WGRAD, false, LOAD_ROWS, WBN, LIMBS, BKT, LIMBS>::type WB;
     const size_t lds = std::max<size_t>(DA::TILE_BYTES + DB::TILE_BYTES, WA::TILE_BYTES + WB::TILE_BYTES) * LIMBS;
     auto kern = contract_pair_kernel<LIMBS, BKT, OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
-    static bool attr_done = false;
-    if (!attr_done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(kern), lds); e != hipSuccess) return e;
     const unsigned tiles_d = (unsigned)(((d.kern.M + DBM - 1) / DBM) * ((d.kern.N + DBN - 1) / DBN));
     const unsigned tiles_w = (unsigned)(((w.kern.M + WBM - 1) / WBM) * ((w.kern.N + WBN - 1) / WBN));
     const unsigned n_d = tiles_d * (unsigned)d.splits, n_w = tiles_w * (unsigned)w.splits;

@@ -3,7 +3,6 @@
 
 using namespace adapt;
 
-ADAPT_PROF_GETTER(adapt_debug_prof_wgrad)
 
 extern "C" int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *x,
                                 adapt_fmt fx, void *dw, adapt_epilogue ep)

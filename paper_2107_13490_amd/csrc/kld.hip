@@ -257,7 +257,6 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
     const int nthreads = blockDim.x, nwaves = nthreads / kWave;
     const int ncand = wl_hi - wl_lo + 1;
 
-    ADAPT_STAMP(0);
     // ---- plan (identical in every block) ----
     {
         float lo = INFINITY, hi = -INFINITY;
@@ -287,7 +286,6 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
                 reinterpret_cast<uint32_t *>(plan_out)[i] = reinterpret_cast<const uint32_t *>(&plan)[i];
     }
     if (plan.degenerate) return;
-    ADAPT_STAMP(1);
 
     const int nb = plan.nb, e = plan.e;
     const float base_f = plan.base_f, tscale = plan.tscale, tmin = plan.tmin, tmax = plan.tmax;
@@ -319,7 +317,6 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
     if ((int)threadIdx.x >= c_begin && (int)threadIdx.x < c_end)
         row_off[threadIdx.x] = (threadIdx.x + 1 - row0) * row_stride - plan.cand[threadIdx.x].lo;
     __syncthreads();
-    ADAPT_STAMP(2);
 
     // one group = 8 consecutive elements of one thread (one Philox block)
     auto count_group = [&](const float (&v)[8], const int (&r)[8], int cnt) {
@@ -369,7 +366,6 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
         count_group(v, r, cnt);
     }
 
-    ADAPT_STAMP(3);
     if (USE_LDS) {
         __syncthreads();
         // coarse candidates: per-code counts (summed over the lane-private copies) into the bins of the row
@@ -385,7 +381,6 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
             }
         }
         if (any) __syncthreads();
-        ADAPT_STAMP(4);
         // slab rows are 16-byte aligned when bins % 4 == 0; otherwise every counter is written singly
         const int nb4 = (bins % 4 == 0) ? nb / 4 : 0;
         for (int row = 0; row < rows; ++row) {
@@ -396,7 +391,6 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
             for (int b = 4 * nb4 + threadIdx.x; b < nb; b += nthreads) dst[b] = src[b];
         }
     }
-    ADAPT_STAMP(5);
 }
 
 template <bool USE_LDS>
@@ -427,7 +421,6 @@ __device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan,
 {
     __shared__ uint32_t cq_s[kFinalGroups][kChunk], cp_s[kFinalGroups][kChunk];
     __shared__ double red[2][kChunk];
-    ADAPT_STAMP_WG4(0);
     const int c = geo.by, nchunks = geo.gx;
     const int lane = threadIdx.x % kChunk, grp = threadIdx.x / kChunk;
     const int b = geo.bx * kChunk + lane;
@@ -485,11 +478,9 @@ __device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan,
     }
     // the last block to finish adds the partial sums in a fixed order and selects
     __shared__ bool last;
-    ADAPT_STAMP_WG4(1);
     if (threadIdx.x == 0)      // release this block's partial sums, acquire everyone else's
         last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == geo.gx * geo.gy - 1;
     __syncthreads();
-    ADAPT_STAMP_WG4(2);
     if (!last) return;
     __shared__ double kl_s[kMaxCand];
     const int ncand = geo.gy;
@@ -533,7 +524,6 @@ __device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan,
         grid_out[2] = plan->degenerate ? 0 : plan->nb;
     }
     *ticket = 0;      // ready for the next search on this context
-    ADAPT_STAMP_WG4(3);
 }
 
 __global__ void __launch_bounds__(kChunk * kFinalGroups)
@@ -671,17 +661,11 @@ static int check_search_args(int wl_lo, int wl_hi, int il, int bins, double eps,
     return ADAPT_OK;
 }
 
-static hipError_t allow_big_lds()
+static hipError_t allow_hist_lds(adapt_ctx *ctx)
 {
-    static hipError_t done = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&kld_hist_kernel<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&kld_hist_batched_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
-        return e;
-    }();
-    return done;
+    hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_kernel<true>), kLdsBudget);
+    if (e == hipSuccess) e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_batched_kernel), kLdsBudget);
+    return e;
 }
 
 // Searches on items[0 .. count): consecutive tensors are packed into batches (at most kKldBatchMax
@@ -768,11 +752,39 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, 
     return ADAPT_OK;
 }
 
+// upper bounds of what search_one / one batch of search_batch lay out in the scratch
+static size_t need_of_tensor(int num_cu, uint64_t n, int ncand, int bins)
+{
+    auto a256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    const int threads = n >= ((uint64_t)1 << 20) ? 1024 : n >= ((uint64_t)1 << 16) ? 512 : 256;
+    const uint64_t per_block = (uint64_t)threads * 8;
+    const uint64_t hist_grid = std::min<uint64_t>((uint64_t)num_cu, std::max<uint64_t>(1, (n + per_block - 1) / per_block));
+    const uint64_t range_grid = std::min<uint64_t>((uint64_t)num_cu * 4, std::max<uint64_t>(1, (n / 4 + kRangeThreads - 1) / kRangeThreads));
+    const size_t nchunks = (size_t)(bins + kChunk - 1) / kChunk;
+    return a256(sizeof(KldPlan)) + a256((size_t)range_grid * 8) + a256((size_t)ncand * nchunks * 16) +
+           a256((size_t)hist_grid * (size_t)(ncand + 1) * (size_t)bins * 4);
+}
+
+size_t ws_need_kld_search(int num_cu, uint64_t n, int wl_lo, int wl_hi, int bins)
+{
+    return need_of_tensor(num_cu, n, wl_hi - wl_lo + 1, bins);
+}
+
+size_t ws_need_kld_search_batched(int num_cu, const adapt_kld_item *items, int count, int wl_lo, int wl_hi)
+{
+    size_t worst = 0;
+    for (int t0 = 0; t0 < count; t0 += kKldBatchMax) {
+        size_t sum = 0;
+        for (int t = t0; t < count && t < t0 + kKldBatchMax; ++t) sum += need_of_tensor(num_cu, items[t].n, wl_hi - wl_lo + 1, items[t].bins);
+        worst = std::max(worst, sum);
+    }
+    return worst;
+}
+
 }  // namespace adapt
 
 using namespace adapt;
 
-ADAPT_PROF_GETTER(adapt_debug_prof_kld)
 
 extern "C" int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t n, int wl_lo, int wl_hi, int il,
                                           int bins, double eps, double alpha, adapt_rng rng, double *kld, int32_t *sel,
@@ -783,7 +795,7 @@ extern "C" int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t
     if (n > 0 && (!w || !aligned16(w))) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if (((uintptr_t)kld & 7) || ((uintptr_t)sel & 3) || ((uintptr_t)hist & 3) || ((uintptr_t)grid & 7)) return ADAPT_EINVAL;
-    if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
+    if (hipError_t e = allow_hist_lds(ctx); e != hipSuccess) return hip_status(ctx, e);
     return search_one(ctx, w, n, wl_lo, wl_hi, il, bins, eps, alpha, rng.mode, rng.seed, rng.stream, kld, sel, hist, grid);
 }
 
@@ -796,7 +808,7 @@ extern "C" int adapt_kld_precision_search_ranged(adapt_ctx *ctx, const float *w,
     if (n > 0 && (!w || !aligned16(w))) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if (((uintptr_t)kld & 7) || ((uintptr_t)sel & 3) || ((uintptr_t)hist & 3) || ((uintptr_t)grid & 7)) return ADAPT_EINVAL;
-    if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
+    if (hipError_t e = allow_hist_lds(ctx); e != hipSuccess) return hip_status(ctx, e);
     return search_one(ctx, w, n, wl_lo, wl_hi, il, bins, eps, alpha, rng.mode, rng.seed, rng.stream, kld, sel, hist, grid, range);
 }
 
@@ -811,6 +823,6 @@ extern "C" int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kl
         if (items[t].n > 0 && (!items[t].w || !aligned16(items[t].w))) return ADAPT_EINVAL;
         if (items[t].n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     }
-    if (allow_big_lds() != hipSuccess) return hip_status(ctx, allow_big_lds());
+    if (hipError_t e = allow_hist_lds(ctx); e != hipSuccess) return hip_status(ctx, e);
     return search_batch(ctx, items, count, wl_lo, wl_hi, eps, alpha, mode, seed, kld, sel);
 }

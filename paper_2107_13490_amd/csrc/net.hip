@@ -332,6 +332,12 @@ static int pool_geo(int es, int n, int h, int w, int c, bool pool, PoolGeo &g, i
     return ADAPT_OK;
 }
 
+size_t ws_need_requantize_fit(int num_cu, uint64_t n)
+{
+    const uint64_t groups = (n + 7) >> 3;
+    return (size_t)std::min<uint64_t>(std::max<uint64_t>((groups + kEwThreads - 1) / kEwThreads, 1), (uint64_t)num_cu * 4) * 8;
+}
+
 }  // namespace adapt
 
 using namespace adapt;

@@ -172,6 +172,12 @@ gd_final_kernel(const GradWindow w, const uint64_t *__restrict__ partial, int nb
     out[1] = (ds > 0.0 && ds < (double)INFINITY) ? log(ds) : 1.0;
 }
 
+size_t ws_need_gradient_diversity(uint64_t n, int count)
+{
+    const size_t per_block = (size_t)kGdThreads * kGdPerThread;
+    return std::max<size_t>(1, (n + per_block - 1) / per_block) * (size_t)(count + 2) * sizeof(uint64_t);
+}
+
 }  // namespace adapt
 
 using namespace adapt;

@@ -6,6 +6,8 @@
 // the block partials (integer, order-independent).
 #include <cstdlib>
 
+#include <algorithm>
+
 #include "common.hpp"
 #include "context.hpp"
 
@@ -263,6 +265,20 @@ static int grid_for(const adapt_ctx *ctx, uint64_t n)
     return (int)blocks;
 }
 
+size_t ws_need_quantize(int num_cu, uint64_t n)
+{
+    adapt_ctx c = {};
+    c.num_cu = num_cu;
+    return (((size_t)grid_for(&c, n) * 8 + 255) & ~(size_t)255) + 16;      // per-block counters, and the dummy slot
+}
+
+// the batched call takes at most 4 blocks per CU; counter and range partials per block and tensor
+size_t ws_need_quantize_batched(int num_cu, int count)
+{
+    const size_t per = std::min(std::max(count, 1), kMaxItems);
+    return 2 * (((size_t)num_cu * 4 * 2 * per * sizeof(uint32_t) + 255) & ~(size_t)255);
+}
+
 }  // namespace adapt
 
 using namespace adapt;
@@ -322,9 +338,6 @@ extern "C" int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantiz
         }
         uint64_t grid = total_blocks;
         uint64_t cap = (uint64_t)ctx->num_cu * 4;
-#ifdef ADAPT_TUNE
-        if (const char *env = getenv("ADAPT_Q_BLOCKS_PER_CU")) cap = (uint64_t)ctx->num_cu * atoi(env);
-#endif
         if (grid > cap) grid = cap;
         if (grid == 0) grid = 1;     // still writes the (zero) counters
         const size_t part_bytes = (grid * 2 * batch.count * sizeof(uint32_t) + 255) & ~(size_t)255;

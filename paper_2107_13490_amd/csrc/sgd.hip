@@ -157,6 +157,13 @@ sgd_final_kernel(const uint32_t *__restrict__ counts, const float *__restrict__ 
     }
 }
 
+size_t ws_need_sgd_update(int num_cu, uint64_t n)
+{
+    const uint64_t groups = (n + 7) >> 3;
+    const uint64_t blocks = std::min<uint64_t>(std::max<uint64_t>((groups + kSgdThreads - 1) / kSgdThreads, 1), (uint64_t)num_cu * 8);
+    return (((size_t)blocks * 8 + 255) & ~(size_t)255) + (size_t)blocks * 8;
+}
+
 }  // namespace adapt
 
 using namespace adapt;

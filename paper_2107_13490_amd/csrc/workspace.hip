@@ -1,0 +1,137 @@
+// adapt_workspace_bytes / adapt_reserve_workspace: what a call will take of the context's workspace, from the same
+// planning code the call itself runs.
+#include "contract_kernel.hpp"
+
+using namespace adapt;
+
+namespace {
+
+constexpr size_t kInvalid = 0;
+
+size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// zero-padded copies of a narrow layer's operands (see pad_channels)
+size_t pad_bytes(size_t off, size_t rows, int es) { return a256(off) + rows * kPadC * (size_t)es; }
+
+size_t conv_need(adapt_ctx *dry, int call, const adapt_conv_desc &d, adapt_fmt fa, adapt_fmt fb, adapt_fmt fc)
+{
+    const adapt_epilogue ep = {1, {8, 0}, {ADAPT_RN_HALF_UP, 0, 0}, 0};      // exact output: the widest slabs
+    const size_t big = (size_t)1 << 62;
+    const bool narrow = d.c < kPadC && d.n > 0;
+    const size_t x_rows = (size_t)d.n * d.h * d.w, w_rows = (size_t)d.k * d.r * d.s;
+    ContractArgs a = {};
+    ContractPlan p;
+    size_t need = 0;
+    if (call == ADAPT_CALL_CONV_FWD) {                       // operands x (fa), w (fb)
+        size_t off = 0;
+        if (narrow) {
+            off = pad_bytes(pad_bytes(0, x_rows, storage_bytes(fa)), w_rows, storage_bytes(fb));
+            if (fill_fwd_padded(a, d, nullptr, fa, nullptr, fb, nullptr) != ADAPT_OK) return kInvalid;
+        } else if (fill_fwd(a, d, nullptr, fa, nullptr, fb, nullptr) != ADAPT_OK) return kInvalid;
+        if (plan_contraction<OP_FWD>(dry, a, fa, fb, ep, off, p, big) != ADAPT_OK) return kInvalid;
+        need = p.ws_end;
+    }
+    if (call == ADAPT_CALL_CONV_DGRAD || call == ADAPT_CALL_CONV_BACKWARD) {      // operands dy (fa), w (fb)
+        size_t off = 0;
+        a = ContractArgs{};
+        if (narrow) {
+            if (call == ADAPT_CALL_CONV_BACKWARD) off = pad_bytes(0, x_rows, storage_bytes(fc));
+            off = pad_bytes(off, w_rows, storage_bytes(fb));
+            if (fill_dgrad_padded(a, d, nullptr, fa, nullptr, fb, nullptr) != ADAPT_OK) return kInvalid;
+        } else if (fill_dgrad(a, d, nullptr, fa, nullptr, fb, nullptr) != ADAPT_OK) return kInvalid;
+        if (plan_contraction<OP_DGRAD>(dry, a, fa, fb, ep, off, p, big) != ADAPT_OK) return kInvalid;
+        need = std::max(need, p.ws_end);
+    }
+    if (call == ADAPT_CALL_CONV_WGRAD || call == ADAPT_CALL_CONV_BACKWARD) {      // operands dy (fa), x (fb; fc in a backward call)
+        const adapt_fmt fx = call == ADAPT_CALL_CONV_BACKWARD ? fc : fb;
+        size_t off = 0;
+        a = ContractArgs{};
+        if (narrow) {
+            off = pad_bytes(0, x_rows, storage_bytes(fx));
+            if (call == ADAPT_CALL_CONV_BACKWARD) off = pad_bytes(off, w_rows, storage_bytes(fb));
+            if (fill_wgrad_padded(a, d, nullptr, fa, nullptr, fx, nullptr) != ADAPT_OK) return kInvalid;
+        } else if (fill_wgrad(a, d, nullptr, fa, nullptr, fx, nullptr) != ADAPT_OK) return kInvalid;
+        if (plan_contraction<OP_WGRAD>(dry, a, fa, fx, ep, off, p, big) != ADAPT_OK) return kInvalid;
+        need = std::max(need, p.ws_end);
+    }
+    return need;
+}
+
+}  // namespace
+
+extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_workspace_query *q)
+{
+    if (!q) return kInvalid;
+    int num_cu = 0;
+    if (ctx) {
+        num_cu = ctx->num_cu;
+    } else {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return kInvalid;
+        num_cu = prop.multiProcessorCount;
+    }
+    adapt_ctx dry = {};      // plans like a context with unlimited workspace; nothing is launched through it
+    dry.num_cu = num_cu;
+    const size_t slack = 256;      // alignment of the first block
+    switch (q->call) {
+        case ADAPT_CALL_QUANTIZE:
+            return q->n > ((uint64_t)1 << 40) ? kInvalid : ws_need_quantize(num_cu, q->n) + slack;
+        case ADAPT_CALL_QUANTIZE_BATCHED:
+            return q->count < 0 ? kInvalid : ws_need_quantize_batched(num_cu, q->count) + slack;
+        case ADAPT_CALL_GEMM: {
+            if (q->M < 0 || q->N < 0 || q->K < 0 || !fmt_ok(q->fa) || !fmt_ok(q->fb)) return kInvalid;
+            const int lda = q->lda ? q->lda : (q->transA ? q->M : q->K), ldb = q->ldb ? q->ldb : (q->transB ? q->K : q->N);
+            ContractArgs a = {};
+            fill_gemm(a, q->transA, q->transB, q->M, q->N, q->K, nullptr, q->fa, lda, nullptr, q->fb, ldb, nullptr, q->N);
+            ContractPlan p;
+            const adapt_epilogue ep = {1, {8, 0}, {ADAPT_RN_HALF_UP, 0, 0}, 0};
+            if (plan_contraction<OP_GEMM>(&dry, a, q->fa, q->fb, ep, 0, p, (size_t)1 << 62) != ADAPT_OK) return kInvalid;
+            return p.ws_end + slack;
+        }
+        case ADAPT_CALL_CONV_FWD:
+        case ADAPT_CALL_CONV_DGRAD:
+        case ADAPT_CALL_CONV_WGRAD:
+        case ADAPT_CALL_CONV_BACKWARD: {
+            if (!fmt_ok(q->fa) || !fmt_ok(q->fb) || !conv_ok(q->conv)) return kInvalid;
+            if (q->call == ADAPT_CALL_CONV_BACKWARD && !fmt_ok(q->fc)) return kInvalid;
+            const size_t need = conv_need(&dry, q->call, q->conv, q->fa, q->fb, q->fc);
+            return need + slack;
+        }
+        case ADAPT_CALL_KLD_SEARCH:
+            if (q->wl_lo < 2 || q->wl_hi > 16 || q->wl_lo > q->wl_hi || q->bins < 2 || q->bins > 65536) return kInvalid;
+            return ws_need_kld_search(num_cu, q->n, q->wl_lo, q->wl_hi, q->bins) + slack;
+        case ADAPT_CALL_KLD_SEARCH_BATCHED:
+            if (q->wl_lo < 2 || q->wl_hi > 16 || q->wl_lo > q->wl_hi || q->count < 0 || (q->count > 0 && !q->kld_items)) return kInvalid;
+            for (int t = 0; t < q->count; ++t)
+                if (q->kld_items[t].bins < 2 || q->kld_items[t].bins > 65536) return kInvalid;
+            return ws_need_kld_search_batched(num_cu, q->kld_items, q->count, q->wl_lo, q->wl_hi) + slack;
+        case ADAPT_CALL_SGD_UPDATE:
+            return ws_need_sgd_update(num_cu, q->n) + slack;
+        case ADAPT_CALL_GRADIENT_DIVERSITY:
+            return q->count < 1 ? kInvalid : ws_need_gradient_diversity(q->n, q->count) + slack;
+        case ADAPT_CALL_REQUANTIZE_FIT:
+            return ws_need_requantize_fit(num_cu, q->n) + slack;
+        default:
+            return kInvalid;
+    }
+}
+
+extern "C" int adapt_reserve_workspace(adapt_ctx *ctx, size_t bytes)
+{
+    if (!ctx) return ADAPT_EINVAL;
+    if (bytes + kCtlBytes <= ctx->ws_bytes) return ADAPT_OK;
+    hipError_t e = hipStreamSynchronize(ctx->stream);      // nothing in flight may still use the old block
+    char *grown = nullptr;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&grown), bytes + kCtlBytes);
+    if (e == hipSuccess) e = hipMemset(grown, 0, kCtlBytes);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        if (grown) (void)hipFree(grown);
+        return hip_status(ctx, e);
+    }
+    (void)hipFree(ctx->ws);
+    ctx->ws = grown;
+    ctx->ws_bytes = bytes + kCtlBytes;
+    return ADAPT_OK;
+}

@@ -474,13 +474,109 @@ def test_gemm_mixed_worst_case_and_transposes(ta, tb, wla, wlb):
     assert np.array_equal(host(c).astype(np.int64), orc.requantize(orc.gemm(a, b), 14, 12, orc.SR, 2, 9))
 
 
+# ---- the full bench sizes (configs 4 and 5 at their own batch) against the oracle ----------------------------------
+
+def _spread_samples(n, rows_per_sample):
+    """First and last sample, and two neighbours in the middle of the batch that lie on either side of a boundary of
+    the 64-, 128- and 256-row output tiles (samples smaller than a tile share tiles; larger ones span several)."""
+    per_tile = max(1, 256 // rows_per_sample)
+    k = max(1, (n // 2) // per_tile * per_tile)
+    return sorted({0, k - 1, min(k, n - 1), n - 1})
+
+
+def _full_batch_layer(spec, seed):
+    """One layer at the batch the benchmark times, in the calls the benchmark makes (forward with the requantizing ReLU
+    epilogue, both gradients through conv_backward), on the seeded workload tensors.  The oracle quantizes the same
+    fp32 tensors (codes compared in full), computes the weight gradient in full and the forward output and data
+    gradient, which treat samples independently, for samples spread over the batch."""
+    from gpu_util import oracle_quantize
+    L = wk.layer_inputs(spec, seed)
+    s = L.shape
+    d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+    f = (L.wl, L.fl)
+    c = ctx()
+    c.reserve_for_layers([(d, f, f, f)])
+    (qx, qw, qdy), _ = c.quantize_batched([dev(L.x), dev(L.w), dev(L.dy)], [f, f, f], [1, 2, 3], pkg.SR, seed=0)
+    hx, hw, hdy = (oracle_quantize(t, L.wl, L.fl, 0, i + 1) for i, t in enumerate((L.x, L.w, L.dy)))
+    for got, want in ((qx, hx), (qw, hw), (qdy, hdy)):
+        assert np.array_equal(host(got).astype(np.int64), want), spec.name
+    eps = [Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10 + i, relu=(i == 0)) for i in range(3)]
+    ex = Epilogue.exact()
+    y, yq = host(c.conv_fwd(d, qx, f, qw, f, ex)), host(c.conv_fwd(d, qx, f, qw, f, eps[0]))
+    dx, dw = (host(t) for t in c.conv_backward(d, qdy, f, qw, f, qx, f, ex, ex))
+    dxq, dwq = (host(t) for t in c.conv_backward(d, qdy, f, qw, f, qx, f, eps[1], eps[2]))
+    want_dw = co.conv_wgrad(hdy, hx, s.r, s.s, s.stride, s.pad)
+    assert np.array_equal(dw.astype(np.int64), want_dw), spec.name
+    assert np.array_equal(dwq.astype(np.int64), orc.requantize(want_dw, L.fl, L.wl, orc.SR, 0, 12)), spec.name
+    per_y, per_x = s.p * s.q * s.k, s.h * s.w * s.c
+    for i in _spread_samples(s.n, min(s.p * s.q, s.h * s.w)):
+        want_y = co.conv_fwd(hx[i:i + 1], hw, s.stride, s.pad)
+        assert np.array_equal(y[i:i + 1].astype(np.int64), want_y), (spec.name, i)
+        assert np.array_equal(yq[i:i + 1].astype(np.int64), orc.requantize(want_y, L.fl, L.wl, orc.SR, 0, 10, True, start=i * per_y)), (spec.name, i)
+        want_dx = co.conv_dgrad(hdy[i:i + 1], hw, s.h, s.w, s.stride, s.pad)
+        assert np.array_equal(dx[i:i + 1].astype(np.int64), want_dx), (spec.name, i)
+        assert np.array_equal(dxq[i:i + 1].astype(np.int64), orc.requantize(want_dx, L.fl, L.wl, orc.SR, 0, 11, False, start=i * per_x)), (spec.name, i)
+
+
+@pytest.mark.parametrize("li", range(8))
+def test_config4_full_batch_against_the_oracle(li):
+    _full_batch_layer(wk.alexnet_cifar_layers()[li], 40 + li)
+
+
+@pytest.mark.parametrize("li", range(21))
+def test_config5_full_batch_against_the_oracle(li):
+    _full_batch_layer(wk.resnet18_cifar_layers()[li], 50 + li)
+
+
+# ---- workspace: sizing query, fewer splits when it is short, the accumulator bound ------------------------------------
+
+def test_workspace_query_matches_what_the_calls_take():
+    """A context created with exactly the bytes the query returns runs the call with its preferred plan; the result is
+    the one a roomy context gives."""
+    d = ConvDesc(16, 16, 16, 64, 64, 3, 3, 1, 1)
+    f = (8, 5)
+    x, wt, dy = codes((16, 16, 16, 64), 8, 1), codes((64, 3, 3, 64), 8, 2), codes((16, 16, 16, 64), 8, 3)
+    need = ctx().workspace_bytes(pkg.CALL_CONV_BACKWARD, conv=d, fa=f, fb=f, fc=f)
+    assert need > 64 * 3 * 3 * 64 * 4              # at least one slab of the weight gradient
+    exact = pkg.Context(workspace_bytes=need)
+    dx, dw = exact.conv_backward(d, to_dev(dy), f, to_dev(wt), f, to_dev(x), f, Epilogue.exact(), Epilogue.exact())
+    assert np.array_equal(host(dw).astype(np.int64), co.conv_wgrad(dy, x, 3, 3, 1, 1))
+    assert np.array_equal(host(dx).astype(np.int64), co.conv_dgrad(dy, wt, 16, 16, 1, 1))
+    exact.close()
+    assert ctx().workspace_bytes(pkg.CALL_KLD_SEARCH, n=65536, wl_lo=2, wl_hi=16, bins=2048) > 16 * 2048 * 4
+    with pytest.raises(pkg.AdaptError):
+        ctx().workspace_bytes(pkg.CALL_CONV_FWD, conv=ConvDesc(1, 2, 2, 16, 16, 5, 5, 1, 0), fa=f, fb=f)
+    grown = pkg.Context(workspace_bytes=1 << 16)
+    grown.reserve_workspace(need)
+    _, dw2 = grown.conv_backward(d, to_dev(dy), f, to_dev(wt), f, to_dev(x), f, Epilogue.exact(), Epilogue.exact())
+    assert torch.equal(dw2, dw)
+    grown.close()
+
+
+def test_short_workspace_takes_fewer_splits_and_long_reductions_report_the_bound():
+    small = pkg.Context(workspace_bytes=1 << 16)            # 60 KiB of scratch
+    d = ConvDesc(16, 16, 16, 64, 64, 3, 3, 1, 1)            # a weight gradient that would like many splits of 147 KB slabs
+    x, dy = codes((16, 16, 16, 64), 8, 1), codes((16, 16, 16, 64), 8, 3)
+    dw = small.conv_wgrad(d, to_dev(dy), (8, 4), to_dev(x), (8, 4), Epilogue.exact())
+    assert np.array_equal(host(dw).astype(np.int64), co.conv_wgrad(dy, x, 3, 3, 1, 1))
+    # K = 200,000 needs four splits of int32 partial sums whatever the workspace: 4 x 64 x 64 x 8 bytes do not fit 60 KiB
+    k = 200000
+    a, b = codes((64, k), 8, 5), codes((k, 64), 8, 6)
+    with pytest.raises(pkg.AdaptError) as err:
+        small.fxp_gemm(to_dev(a), (8, 0), to_dev(b), (8, 0), Epilogue.exact())
+    assert err.value.status == -3                           # ADAPT_EBOUND
+    small.close()
+    c = ctx().fxp_gemm(to_dev(a), (8, 0), to_dev(b), (8, 0), Epilogue.exact())
+    assert np.array_equal(host(c), orc.gemm(a, b))
+
+
 # ---- the launch configurations of the full bench sizes, checked against runs that the oracle tests cover --------
 
 def _full_batch_consistency(specs):
     """Forward and data gradient treat samples independently and the weight gradient is a sum over samples: the full
     batch (tiles, K splits and pairings of the size the benchmark times) must reproduce, exactly, what small-batch
     runs of the same layer give (those configurations are compared with the oracle in the sweeps above)."""
-    c = pkg.Context(workspace_bytes=1 << 30)
+    c = ctx()
     g = torch.Generator(device="cuda")
     g.manual_seed(11)
     for sp in specs:
@@ -489,6 +585,7 @@ def _full_batch_consistency(specs):
         dt = torch.int8 if wl <= 8 else torch.int16
         lo, hi = -(1 << (wl - 1)), 1 << (wl - 1)
         d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+        c.reserve_for_layers([(d, (wl, wl - 3), (wl, wl - 3), (wl, wl - 3))])
         x = torch.randint(lo, hi, (s.n, s.h, s.w, s.c), device="cuda", generator=g, dtype=torch.int32).to(dt)
         wt = torch.randint(lo, hi, (s.k, s.r, s.s, s.c), device="cuda", generator=g, dtype=torch.int32).to(dt)
         dy = torch.randint(lo, hi, (s.n, d.p, d.q, s.k), device="cuda", generator=g, dtype=torch.int32).to(dt)
@@ -508,7 +605,6 @@ def _full_batch_consistency(specs):
             part = c.conv_wgrad(dc, dy[i * chunk:(i + 1) * chunk].contiguous(), f, x[i * chunk:(i + 1) * chunk].contiguous(), f, ex)
             total += part.to(torch.int64)
         assert torch.equal(dw.to(torch.int64), total), sp.name
-    c.close()
 
 
 def test_config4_full_batch_launch_configurations():

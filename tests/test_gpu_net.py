@@ -356,7 +356,8 @@ def test_alexnet_chain_full_batch_forward_matches_the_oracle_on_its_first_sample
         fmts.append((sp.wl, sp.fl))
     x = rng.standard_normal((batch, 32, 32, 3)).astype(np.float32)
     ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * (1.5 / np.sqrt(L.r * L.s * L.c))).astype(np.float32) for L in layers]
-    big = pkg.Context(workspace_bytes=1 << 30)
+    big = ctx()
+    big.reserve_for_layers([(d.conv, f, f, f) for d in descs for f in ((8, 5), (16, 13))])
     net = pkg.Net(big, descs, [dev(w) for w in ws])
     for l, (wl, fl) in enumerate(fmts):
         net.set_format(l, wl, fl)
@@ -368,4 +369,116 @@ def test_alexnet_chain_full_batch_forward_matches_the_oracle_on_its_first_sample
         got = host(net.tensor(l, pkg.NT_A)).astype(np.int64).reshape(L.out_shape(batch))[:sub]
         assert np.array_equal(got, fwd["a"][l]), l
     net.close()
-    big.close()
+
+
+# ---- the chain at the batch the benchmark times, every tensor against the oracle --------------------------------------
+#
+# Batch 128 takes other tiles, K splits and launch shapes than the small chains above.  One GPU step (forward,
+# backward, update) is run once and its tensors kept on the host; the oracle's step is computed stage by stage, each
+# test comparing one stage in full (every element of every tensor, all 128 samples).
+
+_A128 = {}
+
+
+def _alexnet128_gpu():
+    if "gpu" in _A128:
+        return _A128["gpu"]
+    batch, seed, s0 = 128, 6, 4000
+    rng = np.random.default_rng(78)
+    layers, fmts, descs = [], [], []
+    for sp, relu, pool in wk.alexnet_cifar_chain(batch=batch):
+        s = sp.shape
+        layers.append(no.Layer(s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad, relu=relu, pool=pool))
+        descs.append(LayerDesc(ConvDesc(batch, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad), int(relu), int(pool)))
+        fmts.append((sp.wl, sp.fl))
+    x = rng.standard_normal((batch, 32, 32, 3)).astype(np.float32)
+    ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * (1.5 / np.sqrt(L.r * L.s * L.c))).astype(np.float32) for L in layers]
+    c = ctx()
+    # operand formats differ between neighbouring layers of a chain: room for every layer at either storage width
+    c.reserve_for_layers([(d.conv, f, f, f) for d in descs for f in ((8, 5), (16, 13))])
+    wdev = [dev(w.copy()) for w in ws]
+    net = pkg.Net(c, descs, wdev)
+    for l, (wl, fl) in enumerate(fmts):
+        net.set_format(l, wl, fl)
+    net.quantize_weights(seed=seed, stream=s0)
+    net.forward(dev(x), seed=seed, stream=s0)
+    nl = len(layers)
+    g = {"layers": layers, "fmts": fmts, "x": x, "ws": ws, "seed": seed, "s0": s0, "batch": batch}
+    g["a_in"] = host(net.tensor(0, pkg.NT_INPUT)).astype(np.int64)
+    g["qw"] = [host(net.tensor(l, pkg.NT_QW)).astype(np.int64) for l in range(nl)]
+    g["y"] = [host(net.tensor(l, pkg.NT_Y)).astype(np.int64) for l in range(nl)]
+    g["a"] = [host(net.tensor(l, pkg.NT_A)).astype(np.int64) for l in range(nl)]
+    # the loss gradient is a function of the logits the GPU produced; the forward test shows them equal to the oracle's
+    wl_last, fl_last = fmts[-1]
+    logits = g["a"][-1].reshape(batch, -1) / 2.0 ** fl_last
+    e = np.exp(logits - logits.max(axis=1, keepdims=True))
+    soft = e / e.sum(axis=1, keepdims=True)
+    soft[np.arange(batch), rng.integers(0, soft.shape[1], batch)] -= 1.0
+    lim = 1 << (wl_last - 1)
+    g["dl"] = np.clip(np.rint(soft * (lim - 1)), -lim, lim - 1).astype(_dt(wl_last))
+    net.backward(dev(g["dl"]), 0, seed=seed, stream=s0)
+    g["g"] = [host(net.tensor(l, pkg.NT_G)).astype(np.int64) for l in range(nl)]
+    g["dy"] = [host(net.tensor(l, pkg.NT_DY)).astype(np.int64) for l in range(nl)]
+    g["da"] = [host(net.tensor(l, pkg.NT_DA)).astype(np.int64) if l < nl - 1 else None for l in range(nl)]
+    g["stats_bwd"] = [(st.shift_w, st.shift_a, st.g_sumsq) for st in (net.tensor(l, pkg.NT_STATS) for l in range(nl))]
+    net.update(0.05, 1e-4, 1e-3, seed=seed, stream=s0)
+    g["w_new"] = [host(w).ravel().view(np.uint32).copy() for w in wdev]
+    g["qw_new"] = [host(net.tensor(l, pkg.NT_QW)).astype(np.int64) for l in range(nl)]
+    g["stats_upd"] = [(st.nnz, st.saturated, st.range_lo, st.range_hi) for st in (net.tensor(l, pkg.NT_STATS) for l in range(nl))]
+    net.close()
+    _A128["gpu"] = g
+    return g
+
+
+def _alexnet128_oracle_fwd():
+    if "fwd" not in _A128:
+        g = _alexnet128_gpu()
+        _A128["wq"] = no.quantize_weights(g["layers"], g["fmts"], g["ws"], g["seed"], g["s0"])
+        _A128["fwd"] = no.forward(g["layers"], g["fmts"], _A128["wq"], g["x"], g["seed"], g["s0"])
+    return _A128["wq"], _A128["fwd"]
+
+
+def _alexnet128_oracle_bwd():
+    if "bwd" not in _A128:
+        g = _alexnet128_gpu()
+        wq, fwd = _alexnet128_oracle_fwd()
+        _A128["bwd"] = no.backward(g["layers"], g["fmts"], wq, fwd, g["dl"], g["seed"], g["s0"])
+    return _A128["bwd"]
+
+
+def test_alexnet_chain_full_batch_forward_in_full():
+    g = _alexnet128_gpu()
+    wq, fwd = _alexnet128_oracle_fwd()
+    assert np.array_equal(g["a_in"], fwd["a_in"].ravel())
+    for l in range(len(g["layers"])):
+        assert np.array_equal(g["qw"][l], wq[l].ravel()), l
+        assert np.array_equal(g["y"][l], fwd["y"][l].ravel()), l
+        assert np.array_equal(g["a"][l], fwd["a"][l].ravel()), l
+
+
+def test_alexnet_chain_full_batch_backward_in_full():
+    g = _alexnet128_gpu()
+    bwd = _alexnet128_oracle_bwd()
+    for l, L in enumerate(g["layers"]):
+        shift_w, shift_a, sumsq = g["stats_bwd"][l]
+        assert np.array_equal(g["g"][l], bwd["g"][l].ravel()), l
+        assert (shift_w, sumsq) == (bwd["shift_w"][l], bwd["sumsq"][l]), l
+        if L.relu or L.pool:
+            assert np.array_equal(g["dy"][l], bwd["dy"][l].ravel()), l
+        if l > 0:
+            assert shift_a == bwd["shift_a"][l], l
+            assert np.array_equal(g["da"][l - 1], bwd["da"][l - 1].ravel()), l
+
+
+@pytest.mark.parametrize("l", range(8))
+def test_alexnet_chain_full_batch_update_in_full(l):
+    from oracle import sgd_oracle as so
+    g = _alexnet128_gpu()
+    bwd = _alexnet128_oracle_bwd()
+    wl, fl = g["fmts"][l]
+    u = so.sgd_update_quantize(g["ws"][l].ravel(), bwd["g"][l].ravel(), 0, 0.05, 1e-4, 1e-3, wl, fl, orc.SR, g["seed"],
+                               no.stream_of(g["s0"], l, no.SLOT_UPD), normalize=True)
+    assert np.array_equal(g["w_new"][l], u["w"].view(np.uint32)), l
+    assert np.array_equal(g["qw_new"][l], u["q"]), l
+    nnz, sat, lo, hi = g["stats_upd"][l]
+    assert (nnz, sat) == (u["nnz"], u["sat"]) and (lo, hi) == (np.float32(u["lo"]), np.float32(u["hi"])), l
