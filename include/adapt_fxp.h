@@ -143,6 +143,19 @@ int adapt_version(void);
 int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng,
                    void *q, uint64_t *nnz, uint64_t *saturated);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it) and cannot spare the context's workspace either: adapt_quantize with its scratch (the
+ * per-block counter partials, at most 16 KiB) in a 32 KiB array that is part of the library's device
+ * image instead of the context's workspace.  Same arguments, results and limits as adapt_quantize
+ * (n <= 2^40; ADAPT_EWORKSPACE only on a device with more than 4,000 compute units, ADAPT_EHIP if the
+ * array's address could not be taken when the context was created).  It calls no allocating routine
+ * and does not touch the workspace.  Every call on one GPU, from any context, shares that GPU's copy of
+ * the array: calls that overlap on one GPU (two streams) race on the counters; the codes are unaffected.
+ * Nothing in the array needs clearing between calls: every block writes its own partials before they
+ * are summed. */
+int adapt_quantize_noalloc(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng,
+                           void *q, uint64_t *nnz, uint64_t *saturated);
+
 /* One launch for a whole network (the per-layer loop of Alg. 1).  `items` is a HOST array of
  * `count` descriptors (read before the call returns; the pointers inside are device
  * pointers); each tensor is quantized exactly as by adapt_quantize with the item's own format

@@ -147,6 +147,7 @@ def load_library():
     lib.adapt_workspace_bytes.restype = sz
     lib.adapt_reserve_workspace.argtypes = [vp, sz]
     lib.adapt_quantize.argtypes = [vp, vp, sz, Fmt, Rng, vp, vp, vp]
+    lib.adapt_quantize_noalloc.argtypes = [vp, vp, sz, Fmt, Rng, vp, vp, vp]
     lib.adapt_quantize_batched.argtypes = [vp, C.POINTER(QuantizeItem), i, i, u64, vp]
     lib.adapt_quantize_batched_ranges.argtypes = [vp, C.POINTER(QuantizeItem), i, i, u64, vp, vp, u64]
     lib.adapt_fxp_gemm.argtypes = [vp, i, i, i, i, i, vp, Fmt, i, vp, Fmt, i, vp, i, Epilogue]
@@ -346,6 +347,13 @@ class Context:
         _check(self._lib.adapt_quantize(self._h, _ptr(x), x.numel(), Fmt(wl, fl), Rng(mode, seed, stream), _ptr(out),
                                         C.c_void_p(counters.data_ptr()), C.c_void_p(counters.data_ptr() + 8)),
                "adapt_quantize")
+        return out, counters
+
+    def quantize_noalloc(self, x, wl, fl, mode, seed, stream, out, counters):
+        """adapt_quantize_noalloc: every buffer is the caller's (nothing is allocated here either)."""
+        _check(self._lib.adapt_quantize_noalloc(self._h, _ptr(x), x.numel(), Fmt(wl, fl), Rng(mode, seed, stream), _ptr(out),
+                                                C.c_void_p(counters.data_ptr()), C.c_void_p(counters.data_ptr() + 8)),
+               "adapt_quantize_noalloc")
         return out, counters
 
     def quantize_batched(self, xs, fmts, streams, mode=SR, seed=0, outs=None, counters=None, ranges=None,

@@ -39,6 +39,12 @@ extern "C" int adapt_create(adapt_ctx **out, void *hip_stream, size_t workspace_
     if (e == hipSuccess) e = hipMemset(c->ws, 0, kCtlBytes);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) { if (c->ws) (void)hipFree(c->ws); delete c; return ADAPT_EHIP; }
+    // the current device's copy of the static scratch array (see adapt_quantize_noalloc); a failure here only
+    // disables that entry point
+    if (static_scratch_address(&c->static_scratch) != hipSuccess) {
+        c->static_scratch = nullptr;
+        (void)hipGetLastError();
+    }
     *out = c;
     return ADAPT_OK;
 }

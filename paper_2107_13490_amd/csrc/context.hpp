@@ -21,11 +21,15 @@ struct adapt_ctx {
     hipError_t last_hip_error;
     // kernels whose dynamic LDS limit this context has already raised above the 64 KiB default
     std::vector<const void *> big_lds_kernels;
+    // this device's copy of the static scratch array of adapt_quantize_noalloc (null if its address could not be taken)
+    void *static_scratch;
 };
 
 namespace adapt {
 
 constexpr size_t kCtlBytes = 4096;
+constexpr size_t kStaticScratchBytes = 32 * 1024;      // static scratch of the entry point that allocates nothing
+hipError_t static_scratch_address(void **ptr);         // of the current device's copy
 constexpr size_t kDefaultWorkspace = (size_t)64 << 20;
 
 inline char *scratch(adapt_ctx *c) { return c->ws + kCtlBytes; }

@@ -283,8 +283,10 @@ size_t ws_need_quantize_batched(int num_cu, int count)
 
 using namespace adapt;
 
-extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng, void *q,
-                              uint64_t *nnz, uint64_t *saturated)
+// adapt_quantize with the per-block counter partials at `base` (room for `room` bytes): the context's workspace, or
+// the static array of the entry point that allocates nothing
+static int quantize_on(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng, void *q, uint64_t *nnz,
+                       uint64_t *saturated, char *base, size_t room)
 {
     if (!ctx || !fmt_ok(fmt) || (rng.mode != ADAPT_SR && rng.mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
     if (n > 0 && (!x || !q || !aligned16(x) || !aligned16(q))) return ADAPT_EINVAL;
@@ -292,8 +294,9 @@ extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fm
     if ((nnz && ((uintptr_t)nnz & 7)) || (saturated && ((uintptr_t)saturated & 7))) return ADAPT_EINVAL;
     const int grid = grid_for(ctx, n);
     const bool count = nnz || saturated;
-    uint32_t *partial = count ? reinterpret_cast<uint32_t *>(scratch(ctx)) : nullptr;
-    if ((size_t)grid * 8 > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    const size_t part_bytes = ((size_t)grid * 8 + 255) & ~(size_t)255;
+    if (part_bytes + 16 > room) return ADAPT_EWORKSPACE;
+    uint32_t *partial = count ? reinterpret_cast<uint32_t *>(base) : nullptr;
     if (fmt.wl <= 8)
         hipLaunchKernelGGL(quantize_kernel<int8_t>, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int8_t *)q,
                            (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, partial);
@@ -301,12 +304,44 @@ extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fm
         hipLaunchKernelGGL(quantize_kernel<int16_t>, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int16_t *)q,
                            (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, partial);
     if (count) {
-        // out1 != null selects the two-destination form; a null nnz is redirected to a dummy slot
-        uint64_t *dummy = reinterpret_cast<uint64_t *>(scratch(ctx) + (((size_t)grid * 8 + 255) & ~(size_t)255));
+        // out1 != null selects the two-destination form; a null destination is redirected to a dummy slot
+        uint64_t *dummy = reinterpret_cast<uint64_t *>(base + part_bytes);
         hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kSumThreads), 0, ctx->stream, partial, grid, 2,
                            nnz ? nnz : dummy, saturated ? saturated : dummy + 1);
     }
     return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_quantize(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng, void *q,
+                              uint64_t *nnz, uint64_t *saturated)
+{
+    if (!ctx) return ADAPT_EINVAL;
+    return quantize_on(ctx, x, n, fmt, rng, q, nnz, saturated, scratch(ctx), scratch_bytes(ctx));
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------------------
+// Its scratch (the per-block counter partials and the dummy slot) is a file-scope device array: every GPU the
+// library runs on holds its own copy at its own address for the life of the process.  The array's name is a
+// host-side stand-in, not a device address; host code uses the address hipGetSymbolAddress returns for the
+// device that is current, taken once per context at creation and kept in the context.
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+
+namespace adapt {
+hipError_t static_scratch_address(void **ptr)
+{
+    *ptr = nullptr;
+    return hipGetSymbolAddress(ptr, HIP_SYMBOL(g_static_scratch));
+}
+}  // namespace adapt
+
+extern "C" int adapt_quantize_noalloc(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng, void *q,
+                                      uint64_t *nnz, uint64_t *saturated)
+{
+    if (!ctx) return ADAPT_EINVAL;
+    if (!ctx->static_scratch) return ADAPT_EHIP;      // the address could not be taken when the context was created
+    // at most 8 blocks per compute unit, 8 bytes each: more than kStaticScratchBytes only on a device with more
+    // than 4,000 compute units, which quantize_on reports as ADAPT_EWORKSPACE
+    return quantize_on(ctx, x, n, fmt, rng, q, nnz, saturated, static_cast<char *>(ctx->static_scratch), kStaticScratchBytes);
 }
 
 extern "C" int adapt_quantize_batched(adapt_ctx *ctx, const adapt_quantize_item *items, int count, int mode,
