@@ -1,15 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the fixed-point hot path on one MI355X.
 
-A step is one pass of the whole path over one synthetic batch of the AlexNet-CIFAR-style
-conv layer (batch 128, 64ch 16x16 -> 192ch 3x3, all tensors <8,5>):
+The headline workload is the largest single-GPU configuration: the ResNet-18-CIFAR layer sweep at batch 256
+(configs[4]: 21 layers, 11.2 M weights, a word length of 4..16 bits per layer).  A step is one pass of the
+whole path over one synthetic batch:
 
-    quantize(X, W, dY)  ->  conv fwd (+ReLU)  ->  backward: dgrad + wgrad   (outputs requantized, SR)
-    ->  KL-divergence precision search on W (WL 4..16, 2048 bins)
+    ONE batched quantize call over the X, W and dY of every layer (it also returns the range of every W)
+    -> per layer: conv fwd (+ReLU) and conv backward (dgrad + wgrad), outputs requantized with SR
+    -> ONE batched KL-divergence precision search over all weight tensors (WL 4..16, 2048 bins)
 
-All inputs are resident in HBM before the timed region.  `value` is useful conv/GEMM
-tera-ops (2*M*N*K per contraction, three contractions) divided by the whole step time.
-Prints ONE JSON line.
+All inputs are resident in HBM before the timed region.  `value` is useful conv/GEMM tera-ops (2*M*N*K per
+contraction, three contractions per layer) divided by the whole step time.  The other configurations run as
+shorter sub-records of the same JSON line (`--config N` makes N the headline instead).  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -25,44 +27,308 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, 256 CU x 8192 op/clk x 2.4 GHz
 PEAK_HBM_GBPS = 8000.0
-# HBM bytes per launch on this workload, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per
-# dispatch, scaled by what a plain 256 MiB device copy reads on the same counters: x2.0 and x1.0);
-# the summary with the commands is profiles/bench_config2_hbm_traffic.md.  Counters cannot be read
-# from inside this process.  Backward = the paired dgrad + wgrad kernel plus the slab-sum kernel.
-FWD_TRAFFIC_BYTES = {"read": 3171 * 1024, "written": 6144 * 1024}
-BWD_TRAFFIC_BYTES = {"read": (12695 + 7856) * 1024, "written": (9824 + 108) * 1024}
+METRIC = "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s"
 
-def cpu_baseline(batch: int):
-    """The oracle, as it stands, on a bounded sample (reduced batch) of the same layer."""
-    import numpy as np
+# HBM bytes per step of the contraction kernels on the headline workload, from two rocprofv3 --pmc runs (FETCH_SIZE,
+# then WRITE_SIZE, KiB per dispatch summed over the contraction launches of one step) scaled by what a plain 256 MiB
+# device copy reads on the same counters.  Counters cannot be read from inside this process; the summary with the
+# commands is the file named here, and tests/test_bench_constants.py checks that the numbers agree with it.
+TRAFFIC = {
+    "profile": "profiles/bench_config5_hbm_traffic.md",
+    "contractions_read_bytes": None,
+    "contractions_written_bytes": None,
+}
+
+WORKLOADS = {
+    1: "configs[0]: GEMM 256^3 <8,6> (exact int32 output) + KLD on 65,536 values (WL 2..16, 2048 bins)",
+    2: "configs[1]: AlexNet-CIFAR conv 64->192 3x3 @16x16, batch 128, <8,5>",
+    3: "configs[2]: conv 128->128 3x3 @16x16, batch 256, <12,9> (two limbs), 50% zero weights",
+    4: "configs[3]: AlexNet-CIFAR layer sweep (5 conv + 3 FC), batch 128, WL per layer from {4,6,8,12,16}",
+    5: "configs[4]: ResNet-18-CIFAR layer sweep (21 layers, 11.2 M weights, 30% zeros), batch 256, WL per layer 4..16",
+}
+
+
+def _stats(ms):
+    s = sorted(ms)
+    return {"mean": sum(s) / len(s), "median": s[len(s) // 2], "min": s[0], "n": len(s)}
+
+
+def _layers_of(cfg):
+    import workloads as wk
+    if cfg == 2:
+        return [wk.config2()]
+    if cfg == 3:
+        return [wk.config3()]
+    if cfg == 4:
+        return [wk.layer_inputs(sp, 40 + i) for i, sp in enumerate(wk.alexnet_cifar_layers())]
+    return [wk.layer_inputs(sp, 50 + i) for i, sp in enumerate(wk.resnet18_cifar_layers())]
+
+
+def run_config(cfg, steps, warmup, ctx, pkg, torch, per_layer=False):
+    """Builds the device tensors of configuration `cfg`, runs `warmup` + `steps` steps and returns the measurements.
+    The timed region is bracketed by synchronisations; inside it HIP events on the library's stream mark every step
+    boundary (median / min) and, on every tenth step, bracket each contraction call (roofline of the contractions)."""
+    import workloads as wk
+    from paper_2107_13490_amd import ConvDesc, Epilogue
+
+    calls = []            # (kind, tag, fn)
+    useful = issued = q_bytes = 0.0
+    kld_ws = []
+    layer_rows = []
+    if cfg == 1:
+        a_h, b_h = wk.config1_gemm()
+        a, b = torch.from_numpy(a_h).cuda(), torch.from_numpy(b_h).cuda()
+        qa, qb = torch.empty(a.shape, dtype=torch.int8, device="cuda"), torch.empty(b.shape, dtype=torch.int8, device="cuda")
+        c = torch.empty((256, 256), dtype=torch.int32, device="cuda")
+        cnt = torch.empty(4, dtype=torch.int64, device="cuda")
+        calls.append(("quantize", "A,B", lambda: ctx.quantize_batched([a, b], [(8, 6)] * 2, [1, 2], pkg.SR, 0, outs=[qa, qb], counters=cnt)))
+        calls.append(("fwd", "gemm", lambda: ctx.fxp_gemm(qa, (8, 6), qb, (8, 6), Epilogue.exact(), out=c)))
+        useful = issued = 2.0 * 256 ** 3
+        q_bytes = 5.0 * 2 * 65536
+        kld_ws = [torch.from_numpy(wk.config1_kld_tensor()).cuda()]
+        kld_args = dict(ils=[2], wl_lo=2, wl_hi=16)
+        layer_rows.append({"name": "gemm256", "issued_ops": issued, "idx": [1]})
+        ranges = None
+    else:
+        layers = _layers_of(cfg)
+        q_in, q_out, q_fmt, w_slots, reserve = [], [], [], [], []
+        for L in layers:
+            s = L.shape
+            d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
+            f = (L.wl, L.fl)
+            dt = torch.int8 if L.wl <= 8 else torch.int16
+            x, w, dy = (torch.from_numpy(t).cuda() for t in (L.x, L.w, L.dy))
+            qx, qw, qdy = (torch.empty(t.shape, dtype=dt, device="cuda") for t in (x, w, dy))
+            y, dx, dw = torch.empty(dy.shape, dtype=dt, device="cuda"), torch.empty_like(qx), torch.empty_like(qw)
+            eps = [Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10 + i, relu=(i == 0)) for i in range(3)]
+            ops = 2.0 * s.macs
+            mult = 4 if L.wl > 8 else 1
+            row = {"name": L.name, "shape": [s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad], "wl": L.wl,
+                   "issued_ops": 3 * ops * mult, "idx": [len(calls), len(calls) + 1]}
+            layer_rows.append(row)
+
+            def mk(d=d, f=f, qx=qx, qw=qw, qdy=qdy, y=y, dx=dx, dw=dw, eps=eps, name=L.name):
+                return [("fwd", name, lambda: ctx.conv_fwd(d, qx, f, qw, f, eps[0], out=y)),
+                        ("backward", name, lambda: ctx.conv_backward(d, qdy, f, qw, f, qx, f, eps[1], eps[2], out_dx=dx, out_dw=dw))]
+            calls += mk()
+            w_slots.append(len(q_in) + 1)
+            q_in += [x, w, dy]
+            q_out += [qx, qw, qdy]
+            q_fmt += [f] * 3
+            reserve.append((d, f, f, f))
+            useful += 3 * ops
+            issued += 3 * ops * mult
+            q_bytes += (4.0 + (1 if L.wl <= 8 else 2)) * (x.numel() + w.numel() + dy.numel())
+            kld_ws.append(w.view(-1))
+        ctx.reserve_for_layers(reserve, kld_bins=2048, wl_lo=4, wl_hi=16)
+        kld_args = dict(ils=[3] * len(kld_ws), wl_lo=4, wl_hi=16)
+        # Quantize of the whole network: one call (the per-layer loop of Alg. 1); the ranges of the weight tensors
+        # are a by-product of the pass that reads them
+        q_cnt = torch.empty(2 * len(q_in), dtype=torch.int64, device="cuda")
+        ranges = torch.empty(2 * len(q_in), dtype=torch.float32, device="cuda")
+        q_streams = list(range(1, len(q_in) + 1))
+        for r in layer_rows:
+            r["idx"] = [i + 1 for i in r["idx"]]
+        calls.insert(0, ("quantize", "all", lambda: ctx.quantize_batched(q_in, q_fmt, q_streams, pkg.SR, 0, outs=q_out, counters=q_cnt,
+                                                                          ranges=ranges, range_of=w_slots)))
+    ncand = kld_args["wl_hi"] - kld_args["wl_lo"] + 1
+    kld = torch.empty((len(kld_ws), ncand), dtype=torch.float64, device="cuda")
+    sel = torch.empty((len(kld_ws), 2), dtype=torch.int32, device="cuda")
+    if ranges is not None and len(kld_ws) == 1:
+        # one tensor: the search takes W's range from the quantize pass (no range pass of its own)
+        calls.append(("kld", "W", lambda: ctx.kld_precision_search_ranged(kld_ws[0], ranges[2:4], kld_args["wl_lo"], kld_args["wl_hi"],
+                                                                           kld_args["ils"][0], 2048, 1e-2, stream=2, kld=kld[0], sel=sel[0])))
+        kld_bytes = 4.0 * kld_ws[0].numel()
+    else:
+        calls.append(("kld", "all W", lambda: ctx.kld_precision_search_batched(kld_ws, kld_args["ils"], [2048] * len(kld_ws),
+                                                                               list(range(2, 2 + len(kld_ws))), kld_args["wl_lo"],
+                                                                               kld_args["wl_hi"], 1e-2, kld=kld, sel=sel)))
+        kld_bytes = 8.0 * sum(t.numel() for t in kld_ws)      # range pass + histogram pass
+
+    EV_EVERY = 10
+    conv_idx = [i for i, (k, _, _) in enumerate(calls) if k in ("fwd", "backward")]
+
+    def step(ev=None):
+        for i, (_, _, fn) in enumerate(calls):
+            if ev is not None and i in ev:
+                ev[i][0].record()
+                fn()
+                ev[i][1].record()
+            else:
+                fn()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    brackets = [{i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in conv_idx}
+                if s % EV_EVERY == 0 else None for s in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record()
+    for s in range(steps):
+        step(brackets[s])
+        marks[s + 1].record()
+    t_enq = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / steps * 1e3
+    step_ms = [marks[s].elapsed_time(marks[s + 1]) for s in range(steps)]
+    # contraction calls: device time between the events around each call, per call averaged over the sampled steps
+    per_call = {i: [] for i in conv_idx}
+    for br in brackets:
+        if br:
+            for i, (e0, e1) in br.items():
+                per_call[i].append(e0.elapsed_time(e1))
+    call_ms = {i: sum(v) / len(v) for i, v in per_call.items() if v}
+    conv_ms = sum(call_ms.values())
+
+    # per-kind device time outside the timed region: each call repeated back to back between two events
+    kind_ms = {}
+    for kind, _, fn in calls:
+        reps = 20
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        kind_ms[kind] = kind_ms.get(kind, 0.0) + e0.elapsed_time(e1) / reps
+
+    out = {
+        "workload": WORKLOADS[cfg], "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_step, "step_ms_device": _stats(step_ms), "host_enqueue_ms_per_step": t_enq / steps * 1e3,
+        "useful_ops_per_step": useful, "issued_int8_ops_per_step": issued,
+        "useful_TOPS": useful / (ms_step * 1e-3) / 1e12,
+        "contractions": {"calls_per_step": len(conv_idx), "ms_per_step_in_timed_region": conv_ms,
+                         "useful_TOPS": useful / (conv_ms * 1e-3) / 1e12, "issued_TOPS": issued / (conv_ms * 1e-3) / 1e12,
+                         "frac_int8_peak": issued / (conv_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+                         "note": "HIP events around every conv_fwd / conv_backward / gemm call on every 10th step of the timed region, "
+                                 "on the stream the library launches on; includes the dispatch gaps inside a call"},
+        "calls_ms_back_to_back": kind_ms,
+        "quantize": {"bytes": q_bytes, "GBps": q_bytes / (kind_ms["quantize"] * 1e-3) / 1e9,
+                     "frac_hbm": q_bytes / (kind_ms["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBPS, "cache": "warm"},
+        "kld": {"bytes": kld_bytes, "GBps": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9,
+                "frac_hbm": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                "tensors": len(kld_ws), "elements": int(sum(t.numel() for t in kld_ws))},
+    }
+    if per_layer:
+        rows = []
+        for r in layer_rows:
+            ms = sum(call_ms.get(i, 0.0) for i in r["idx"])
+            rows.append({"name": r["name"], "shape_nhwc_krs_stride_pad": r.get("shape"), "wl": r.get("wl"), "ms": ms,
+                         "issued_TOPS": r["issued_ops"] / (ms * 1e-3) / 1e12 if ms else None})
+        out["layers"] = rows
+        heavy = max(rows, key=lambda r: r["ms"])
+        out["heaviest_layer"] = heavy
+    return out
+
+
+def cold_quantize(ctx, pkg, torch, cfg=2):
+    """Cold-cache rate of the HBM-bound quantize call: distinct sets of configs[1]'s three tensors (340 MB of inputs and
+    outputs in all, more than the 256 MB of last-level cache) used in turn."""
+    import workloads as wk
+    L = wk.config2()
+    f = (L.wl, L.fl)
+    x, w, dy = (torch.from_numpy(t).cuda() for t in (L.x, L.w, L.dy))
+    counters = torch.empty(6, dtype=torch.int64, device="cuda")
+    q_bytes = 5.0 * (x.numel() + w.numel() + dy.numel())
+    sets = [([t.clone() for t in (x, w, dy)], [torch.empty(t.shape, dtype=torch.int8, device="cuda") for t in (x, w, dy)]) for _ in range(8)]
+    for ins, outs in sets:
+        ctx.quantize_batched(ins, [f, f, f], [1, 2, 3], pkg.SR, 0, outs=outs, counters=counters)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        for ins, outs in sets:
+            ctx.quantize_batched(ins, [f, f, f], [1, 2, 3], pkg.SR, 0, outs=outs, counters=counters)
+    e1.record()
+    torch.cuda.synchronize()
+    cold_ms = e0.elapsed_time(e1) / 40
+    return {"workload": "configs[1] tensors, 8 sets in rotation", "ms": cold_ms, "GBps": q_bytes / (cold_ms * 1e-3) / 1e9,
+            "frac_hbm": q_bytes / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(cfg):
+    """The oracle, as it stands, on a bounded sample of the headline workload: its largest layer at reduced batch
+    (quantize + fwd + dgrad + wgrad + requantize), once on one thread and once on all host cores, plus the precision
+    search on that layer's weight tensor."""
+    import ctypes
     import workloads as wk
     from oracle import conv_oracle as co
     from oracle import fxp_oracle as orc
 
-    L = wk.config2(batch=batch)
-    s = L.shape
+    if cfg == 1:
+        cfg = 2
+    spec = max(_specs_of(cfg), key=lambda sp: sp.shape.macs)
+    s = spec.shape
     co.load()
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+    except OSError:
+        gomp = None
+    cores = co.num_threads()
+
+    def run(batch, threads):
+        if gomp is not None:
+            gomp.omp_set_num_threads(threads)
+        small = wk.conv_layer(wk.ConvShape(batch, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad), spec.wl, spec.fl, 99, spec.zero_frac, spec.name)
+        t0 = time.perf_counter()
+        qx, _, _ = orc.quantize(small.x, spec.wl, spec.fl, orc.SR, 0, 1)
+        qw, _, _ = orc.quantize(small.w, spec.wl, spec.fl, orc.SR, 0, 2)
+        qdy, _, _ = orc.quantize(small.dy, spec.wl, spec.fl, orc.SR, 0, 3)
+        y = co.conv_fwd(qx, qw, s.stride, s.pad)
+        dx = co.conv_dgrad(qdy, qw, s.h, s.w, s.stride, s.pad)
+        dw = co.conv_wgrad(qdy, qx, s.r, s.s, s.stride, s.pad)
+        orc.requantize(y, spec.fl, spec.wl, orc.SR, 0, 10, True)
+        orc.requantize(dx, spec.fl, spec.wl, orc.SR, 0, 11)
+        orc.requantize(dw, spec.fl, spec.wl, orc.SR, 0, 12)
+        dt = time.perf_counter() - t0
+        return 3 * 2.0 * small.shape.macs / dt / 1e12, dt, small
+
+    one_tops, one_s, one = run(max(2, s.n // 4), 1)
+    all_tops, all_s, small = run(s.n, cores)
+    if gomp is not None:
+        gomp.omp_set_num_threads(cores)
     t0 = time.perf_counter()
-    qx, _, _ = orc.quantize(L.x, L.wl, L.fl, orc.SR, 0, 1)
-    qw, _, _ = orc.quantize(L.w, L.wl, L.fl, orc.SR, 0, 2)
-    qdy, _, _ = orc.quantize(L.dy, L.wl, L.fl, orc.SR, 0, 3)
-    y = co.conv_fwd(qx, qw, s.stride, s.pad)
-    dx = co.conv_dgrad(qdy, qw, s.h, s.w, s.stride, s.pad)
-    dw = co.conv_wgrad(qdy, qx, s.r, s.s, s.stride, s.pad)
-    orc.requantize(y, L.fl, L.wl, orc.SR, 0, 10, True)
-    orc.requantize(dx, L.fl, L.wl, orc.SR, 0, 11)
-    orc.requantize(dw, L.fl, L.wl, orc.SR, 0, 12)
-    orc.kld_precision_search(L.w.ravel(), 4, 16, 3, 2048, 1e-2, None, orc.SR, 0, 2)
-    dt = time.perf_counter() - t0
-    ops = 3 * 2.0 * s.macs
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": co.num_threads(), "kind": "oracle",
-            "sample": f"same layer at batch {batch} (of 128): quantize + fwd + dgrad + wgrad + requantize + KLD, "
-                      f"{dt:.2f} s"}
+    orc.kld_precision_search(small.w.ravel(), 4, 16, 3, 2048, 1e-2, None, orc.SR, 0, 2)
+    kld_s = time.perf_counter() - t0
+    return {"value": all_tops, "unit": "TOPS", "cores": cores, "kind": "oracle", "cpu_model": cpu_model(),
+            "single_thread": {"value": one_tops, "unit": "TOPS", "cores": 1, "seconds": one_s,
+                              "sample": f"layer {spec.name} at batch {one.shape.n} (of {s.n}); the contractions run on one OpenMP thread, "
+                                        "the rounding bits of quantize / requantize are still drawn on all cores"},
+            "kld_search": {"GBps": 8.0 * small.w.size / kld_s / 1e9, "seconds": kld_s,
+                           "sample": f"weight tensor of {spec.name}, {small.w.size} elements, WL 4..16, 2048 bins"},
+            "sample": f"largest layer of the workload ({spec.name}, <{spec.wl},{spec.fl}>) at batch {small.shape.n} (of {s.n}): "
+                      f"quantize + fwd + dgrad + wgrad + requantize, {all_s:.2f} s on {cores} threads"}
 
 
-def next_rows(ctx, pkg, torch, w):
+def _specs_of(cfg):
+    import workloads as wk
+    if cfg == 2:
+        return [wk.LayerSpec("alexnet_conv2", wk.ConvShape(128, 16, 16, 64, 192), 8, 5)]
+    if cfg == 3:
+        return [wk.LayerSpec("resnet_block_conv", wk.ConvShape(256, 16, 16, 128, 128), 12, 9, 0.5)]
+    if cfg == 4:
+        return wk.alexnet_cifar_layers()
+    return wk.resnet18_cifar_layers()
+
+
+def next_rows(ctx, pkg, torch, n_small):
     """Per-call device time of the steps beyond the timed path (PushUp's gradient diversity, the fused
-    master-weight update + re-quantization), on the config-2 weight tensor and on a 16 M element one.
+    master-weight update + re-quantization), on a weight tensor of configs[1]'s size and on a 16 M element one.
     Algorithmic bytes: diversity = window x n x 1 B of int8 codes; update = 4 + 1 B read, 4 + 1 B written."""
     def timed(fn, reps):
         for _ in range(5):
@@ -76,7 +342,7 @@ def next_rows(ctx, pkg, torch, w):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
     res = {}
-    for tag, n, window, reps in (("config2_W", w.numel(), 25, 50), ("16M", 1 << 24, 25, 5)):
+    for tag, n, window, reps in (("config2_W", n_small, 25, 50), ("16M", 1 << 24, 25, 5)):
         gs = [torch.randint(-128, 128, (n,), dtype=torch.int8, device="cuda") for _ in range(window)]
         master = torch.randn(n, device="cuda") * 0.06
         q = torch.empty(n, dtype=torch.int8, device="cuda")
@@ -133,8 +399,8 @@ def elementwise_rows(ctx, pkg, torch):
 
 
 def chained_step(ctx, pkg, torch, batch=128):
-    """The AlexNet-CIFAR layers of config 4 as one chained fixed-point training step (forward pass, backward
-    pass with fitted gradient codes, update + re-quantization), formats of config 4; device time per phase."""
+    """The AlexNet-CIFAR layers of configs[3] as one chained fixed-point training step (forward pass, backward
+    pass with fitted gradient codes, update + re-quantization), formats of configs[3]; device time per phase."""
     import numpy as np
     import workloads as wk
     from paper_2107_13490_amd import ConvDesc, LayerDesc
@@ -147,9 +413,9 @@ def chained_step(ctx, pkg, torch, batch=128):
         ws.append(torch.randn((s.k, s.r, s.s, s.c), device="cuda", generator=gen) * (1.5 / np.sqrt(s.r * s.s * s.c)))
         fmts.append((sp.wl, sp.fl))
         macs += s.macs
-    ctx = pkg.Context(workspace_bytes=1 << 30)          # split-K partial sums of the larger layers
+    ctx.reserve_for_layers([(d.conv, f, f, f) for d in descs for f in ((8, 5), (16, 13))], kld_bins=150, wl_lo=4, wl_hi=16)
     # Alg. 2 with wide bounds on the formats so that the timing loop below keeps its layer formats close to
-    # config 4's (a switch changes a layer's word length by a bit or two)
+    # configs[3]'s (a switch changes a layer's word length by a bit or two)
     sp = pkg.SwitchParams(lb_lwr=2, lb_upr=4, lb_init=2, r_lwr=100, r_upr=150, r_init=128, gamma=0.5, eps=1e-3, buff=3,
                           wl_lo=4, wl_hi=16, strategy_init=pkg.ST_MIN)
     net = pkg.Net(ctx, descs, ws, switch=sp)
@@ -185,9 +451,8 @@ def chained_step(ctx, pkg, torch, batch=128):
         net.update(0.01, 1e-5, 1e-4)
     t_f, t_fb, t_all = timed(fwd), timed(fwd_bwd), timed(full)
 
-    # the precision switch between backward pass and update: wall time of the call (it synchronises three
-    # times and runs the diversity and KL kernels), over a few real steps so that windows fill and switches occur
-    import time
+    # the precision switch between backward pass and update: wall time of the call, over a few real steps so that
+    # windows fill and switches occur
     sw_ms, switched = [], 0
     for step in range(8):
         net.forward(x)
@@ -206,190 +471,32 @@ def chained_step(ctx, pkg, torch, batch=128):
            "layers_switched_in_8_steps": int(switched),
            "formats_after": [(r.wl, r.fl) for r in rep]}
     net.close()
-    ctx.close()
     return res
-
-
-def other_config(args, cfg):
-    """Configs 1, 3, 4 and 5 (supplementary lines; the default run is config 2).  A step is ONE batched quantize
-    call over the X, W and dY of every layer of the config, then for every layer fwd + backward (dgrad + wgrad;
-    requantized with SR), then ONE batched KLD call over all weight tensors.  Config 1 is a GEMM instead of a layer."""
-    import numpy as np
-    import torch
-    import paper_2107_13490_amd as pkg
-    import workloads as wk
-    from paper_2107_13490_amd import ConvDesc, Epilogue
-
-    torch.cuda.set_device(0)
-    ctx = pkg.Context(workspace_bytes=1 << 30)
-    calls = []            # (kind, fn)
-    useful = issued = 0.0
-    q_bytes = 0.0
-    kld_ws, kld_bytes = [], 0.0
-    if cfg == 1:
-        a_h, b_h = wk.config1_gemm()
-        a, b = torch.from_numpy(a_h).cuda(), torch.from_numpy(b_h).cuda()
-        qa, qb = torch.empty(a.shape, dtype=torch.int8, device="cuda"), torch.empty(b.shape, dtype=torch.int8, device="cuda")
-        c = torch.empty((256, 256), dtype=torch.int32, device="cuda")
-        cnt = torch.empty(4, dtype=torch.int64, device="cuda")
-        calls.append(("quantize", lambda: ctx.quantize_batched([a, b], [(8, 6)] * 2, [1, 2], pkg.SR, 0, outs=[qa, qb], counters=cnt)))
-        calls.append(("fwd", lambda: ctx.fxp_gemm(qa, (8, 6), qb, (8, 6), Epilogue.exact(), out=c)))
-        useful = issued = 2.0 * 256 ** 3
-        q_bytes = 5.0 * 2 * 65536
-        kld_ws = [torch.from_numpy(wk.config1_kld_tensor()).cuda()]
-        kld_args = dict(ils=[2], wl_lo=2, wl_hi=16)
-        workload = "configs[0]: GEMM 256^3 <8,6> (exact int32 output) + KLD on 65,536 values (WL 2..16, 2048 bins)"
-        sample_layer = None
-    else:
-        if cfg == 3:
-            layers = [wk.config3()]
-            workload = "configs[2]: conv 128->128 3x3 @16x16, batch 256, <12,9> (two limbs), 50% zero weights"
-        elif cfg == 4:
-            layers = [wk.layer_inputs(sp, 40 + i) for i, sp in enumerate(wk.alexnet_cifar_layers())]
-            workload = "configs[3]: AlexNet-CIFAR layer sweep (5 conv + 3 FC), batch 128, WL per layer from {4,6,8,12,16}"
-        else:
-            layers = [wk.layer_inputs(sp, 50 + i) for i, sp in enumerate(wk.resnet18_cifar_layers())]
-            workload = "configs[4]: ResNet-18-CIFAR layer sweep (21 layers, 11.2 M weights), batch 256, WL per layer 4..16"
-        sample_layer = max(layers, key=lambda L: L.shape.macs)
-        q_in, q_out, q_fmt = [], [], []
-        for L in layers:
-            s = L.shape
-            d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
-            f = (L.wl, L.fl)
-            dt = torch.int8 if L.wl <= 8 else torch.int16
-            x, w, dy = (torch.from_numpy(t).cuda() for t in (L.x, L.w, L.dy))
-            qx, qw, qdy = (torch.empty(t.shape, dtype=dt, device="cuda") for t in (x, w, dy))
-            y, dx, dw = torch.empty(dy.shape, dtype=dt, device="cuda"), torch.empty_like(qx), torch.empty_like(qw)
-            eps = [Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10 + i, relu=(i == 0)) for i in range(3)]
-
-            def mk(d=d, f=f, qx=qx, qw=qw, qdy=qdy, y=y, dx=dx, dw=dw, eps=eps):
-                return [("fwd", lambda: ctx.conv_fwd(d, qx, f, qw, f, eps[0], out=y)),
-                        ("backward", lambda: ctx.conv_backward(d, qdy, f, qw, f, qx, f, eps[1], eps[2], out_dx=dx, out_dw=dw))]
-            calls += mk()
-            q_in += [x, w, dy]
-            q_out += [qx, qw, qdy]
-            q_fmt += [f] * 3
-            ops = 3 * 2.0 * s.macs
-            useful += ops
-            issued += ops * (4 if L.wl > 8 else 1)
-            q_bytes += (4.0 + (1 if L.wl <= 8 else 2)) * (x.numel() + w.numel() + dy.numel())
-            kld_ws.append(w.view(-1))
-        kld_args = dict(ils=[3] * len(kld_ws), wl_lo=4, wl_hi=16)
-        # Quantize of the whole network: one call, one launch per 64 tensors (the per-layer loop of Alg. 1)
-        q_cnt = torch.empty(2 * len(q_in), dtype=torch.int64, device="cuda")
-        q_streams = list(range(1, len(q_in) + 1))
-        calls.insert(0, ("quantize", lambda: ctx.quantize_batched(q_in, q_fmt, q_streams, pkg.SR, 0, outs=q_out, counters=q_cnt)))
-    ncand = kld_args["wl_hi"] - kld_args["wl_lo"] + 1
-    kld = torch.empty((len(kld_ws), ncand), dtype=torch.float64, device="cuda")
-    sel = torch.empty((len(kld_ws), 2), dtype=torch.int32, device="cuda")
-    calls.append(("kld", lambda: ctx.kld_precision_search_batched(kld_ws, kld_args["ils"], [2048] * len(kld_ws),
-                                                                   list(range(2, 2 + len(kld_ws))), kld_args["wl_lo"],
-                                                                   kld_args["wl_hi"], 1e-2, kld=kld, sel=sel)))
-    kld_bytes = 8.0 * sum(t.numel() for t in kld_ws)
-
-    def step():
-        for _, fn in calls:
-            fn()
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
-    kind_ms = {}
-    for kind, fn in calls:           # per-call device time, each call back to back
-        reps = 20
-        fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        kind_ms[kind] = kind_ms.get(kind, 0.0) + e0.elapsed_time(e1) / reps
-    conv_ms = sum(kind_ms.get(k, 0.0) for k in ("fwd", "backward"))
-    out = {
-        "metric": "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s",
-        "value": useful / (ms_step * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8", "data": "synthetic",
-        "config": {"workload": workload, "useful_ops_per_step": useful, "issued_int8_ops_per_step": issued},
-        "roofline": {"bound": "mfma", "kernel": "contract_kernel, all contraction calls of the step",
-                     "achieved": issued / (conv_ms * 1e-3) / 1e12, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
-                     "frac": issued / (conv_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, "traffic": None,
-                     "note": "issued int8 MFMA ops (useful x 4 for two-limb layers) over the summed back-to-back device "
-                             "time of the contraction calls"},
-        "calls_ms_back_to_back": kind_ms,
-        "useful_conv_TOPS": useful / (conv_ms * 1e-3) / 1e12,
-        "quantize_GBps": q_bytes / (kind_ms["quantize"] * 1e-3) / 1e9,
-        "quantize_frac_hbm": q_bytes / (kind_ms["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
-        "kld_GBps": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9,
-        "kld_frac_hbm": kld_bytes / (kind_ms["kld"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
-    }
-    if cfg == 4:
-        out["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
-    if not args.no_cpu_baseline and sample_layer is not None:
-        out["cpu_baseline"] = cpu_baseline_layer(sample_layer, args.cpu_batch)
-    print(json.dumps(out))
-
-
-def cpu_baseline_layer(L, batch):
-    """The oracle on the config's largest layer at a reduced batch (contractions only)."""
-    import workloads as wk
-    from oracle import conv_oracle as co
-    from oracle import fxp_oracle as orc
-    s = L.shape
-    small = wk.conv_layer(wk.ConvShape(min(batch, s.n), s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad), L.wl, L.fl, 99, 0.0, L.name)
-    co.load()
-    t0 = time.perf_counter()
-    qx, _, _ = orc.quantize(small.x, L.wl, L.fl, orc.SR, 0, 1)
-    qw, _, _ = orc.quantize(small.w, L.wl, L.fl, orc.SR, 0, 2)
-    qdy, _, _ = orc.quantize(small.dy, L.wl, L.fl, orc.SR, 0, 3)
-    co.conv_fwd(qx, qw, s.stride, s.pad)
-    co.conv_dgrad(qdy, qw, s.h, s.w, s.stride, s.pad)
-    co.conv_wgrad(qdy, qx, s.r, s.s, s.stride, s.pad)
-    dt = time.perf_counter() - t0
-    return {"value": 3 * 2.0 * small.shape.macs / dt / 1e12, "unit": "TOPS", "cores": co.num_threads(), "kind": "oracle",
-            "sample": f"layer {L.name} at batch {small.shape.n} (of {s.n}): quantize + fwd + dgrad + wgrad, {dt:.2f} s"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true",
-                    help="skip the measurements beyond the timed step (PushUp, fused update, chained step): for profiler runs")
-    ap.add_argument("--cpu-batch", type=int, default=16)
+                    help="skip everything beyond the headline configuration's timed steps (sub-records of the other "
+                         "configurations, PushUp, fused update, chained step): for profiler runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (20 times): the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
     ap.add_argument("--chained-step", action="store_true",
                     help="run only the chained AlexNet-CIFAR training step measurement (supplementary; for profiler runs)")
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
-                    help="which of the five workload configurations to run (default 2, the one the metric is quoted on)")
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5],
+                    help="the headline configuration (default 5, the largest that fits one GPU)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (use --gpus 1)", file=sys.stderr)
         sys.exit(2)
-    if args.chained_step:
-        import torch
-        import paper_2107_13490_amd as pkg
-        torch.cuda.set_device(0)
-        print(json.dumps({"chained_step": chained_step(None, pkg, torch, batch=128)}))
-        return
-    if args.config != 2 and not args.copy_calibration:
-        other_config(args, args.config)
-        return
 
     import torch
     import paper_2107_13490_amd as pkg
-    import workloads as wk
-    from paper_2107_13490_amd import ConvDesc, Epilogue
 
     torch.cuda.set_device(0)
     if args.copy_calibration:
@@ -401,147 +508,50 @@ def main():
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "launches": 20}))
         return
     ctx = pkg.Context()
-    L = wk.config2()
-    s = L.shape
-    d = ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad)
-    f = (L.wl, L.fl)
-    x, w, dy = (torch.from_numpy(t).cuda() for t in (L.x, L.w, L.dy))
-    qx = torch.empty(x.shape, dtype=torch.int8, device="cuda")
-    qw = torch.empty(w.shape, dtype=torch.int8, device="cuda")
-    qdy = torch.empty(dy.shape, dtype=torch.int8, device="cuda")
-    y = torch.empty((s.n, s.p, s.q, s.k), dtype=torch.int8, device="cuda")
-    dx = torch.empty(x.shape, dtype=torch.int8, device="cuda")
-    dw = torch.empty(w.shape, dtype=torch.int8, device="cuda")
-    counters = torch.empty(6, dtype=torch.int64, device="cuda")
-    kld = torch.empty(13, dtype=torch.float64, device="cuda")
-    sel = torch.empty(2, dtype=torch.int32, device="cuda")
-    grid = torch.empty(3, dtype=torch.int64, device="cuda")
-    ranges = torch.empty(6, dtype=torch.float32, device="cuda")
-    ep_y = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 10, relu=True)
-    ep_dx = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 11)
-    ep_dw = Epilogue.requant(L.wl, L.fl, pkg.SR, 0, 12)
+    if args.chained_step:
+        print(json.dumps({"chained_step": chained_step(ctx, pkg, torch, batch=128)}))
+        return
 
-    calls = {
-        # one launch quantizes the three tensors and, as a by-product of reading it, finds the range of W
-        "quantize": lambda: ctx.quantize_batched([x, w, dy], [f, f, f], [1, 2, 3], pkg.SR, 0, outs=[qx, qw, qdy],
-                                                 counters=counters, ranges=ranges, range_of=[1]),
-        "conv_fwd": lambda: ctx.conv_fwd(d, qx, f, qw, f, ep_y, out=y),
-        "conv_backward": lambda: ctx.conv_backward(d, qdy, f, qw, f, qx, f, ep_dx, ep_dw, out_dx=dx, out_dw=dw),
-        # the search takes W's range from the quantize pass (no range pass of its own)
-        "kld_search": lambda: ctx.kld_precision_search_ranged(w.view(-1), ranges[2:4], 4, 16, 3, 2048, 1e-2, stream=2,
-                                                              kld=kld, sel=sel, grid=grid),
-    }
-    EV_EVERY = 10    # on every 10th step of the timed region events bracket the backward call (the dominant
-                     # kernel), on every 10th + 5 the forward call
-
-    def step(ev=None, which=None):
-        calls["quantize"]()
-        if which == "fwd":
-            ev[0].record()
-        calls["conv_fwd"]()
-        if which == "fwd":
-            ev[1].record()
-        if which == "bwd":
-            ev[0].record()
-        calls["conv_backward"]()      # dgrad + wgrad of the layer, one call
-        if which == "bwd":
-            ev[1].record()
-        calls["kld_search"]()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    kinds = ["bwd" if i % EV_EVERY == 0 else "fwd" if i % EV_EVERY == EV_EVERY // 2 else None for i in range(args.steps)]
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] if k else None for k in kinds]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events[i], kinds[i])
-    t_enq = time.perf_counter() - t0
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_step = dt / args.steps * 1e3
-
-    def mean_ms(kind):
-        ts = [ev[0].elapsed_time(ev[1]) for ev, k in zip(events, kinds) if k == kind]
-        return sum(ts) / len(ts) if ts else float("nan")
-    fwd_ms, bwd_ms = mean_ms("fwd"), mean_ms("bwd")
-
-    # per-call device time outside the timed region: each call repeated back to back between two events
-    reps = 50
-    call_ms = {}
-    for name, fn in calls.items():
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        call_ms[name] = e0.elapsed_time(e1) / reps
-
-    conv_ops = 2.0 * s.macs
-    value = 3 * conv_ops / (ms_step * 1e-3) / 1e12
-    # dominant kernel: the paired dgrad + wgrad launch of the backward call (its slab-sum kernel is inside the
-    # bracket too); the forward convolution, one launch of the same contraction code, is reported beside it
-    fwd_tops = conv_ops / (fwd_ms * 1e-3) / 1e12
-    bwd_tops = 2 * conv_ops / (bwd_ms * 1e-3) / 1e12
-    q_bytes = 5.0 * (x.numel() + w.numel() + dy.numel())
-    kld_bytes = 4.0 * w.numel()      # one read of W: the range comes from the quantize pass
-    note = ("HIP events around the call inside the timed region; includes the dispatch gaps that rocprofv3's kernel "
-            "durations exclude (about 2-4 us per launch)")
+    head = run_config(args.config, args.steps, args.warmup, ctx, pkg, torch, per_layer=True)
+    con = head["contractions"]
+    traffic = None
+    if args.config == 5 and TRAFFIC["contractions_read_bytes"] is not None:
+        traffic = TRAFFIC["contractions_read_bytes"] + TRAFFIC["contractions_written_bytes"]
     out = {
-        "metric": "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s",
-        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "configs[1]: AlexNet-CIFAR conv 64->192 3x3 @16x16, batch 128, <8,5>; quantize(X,W,dY) "
-                               "+ fwd + backward (dgrad + wgrad) (requantized, SR) + KLD search on W (WL 4..16, 2048 bins)",
-                   "useful_ops_per_step": 3 * conv_ops},
+        "metric": METRIC, "value": head["useful_TOPS"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "ms_per_step_device": head["step_ms_device"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": head["workload"], "useful_ops_per_step": head["useful_ops_per_step"],
+                   "issued_int8_ops_per_step": head["issued_int8_ops_per_step"]},
         "roofline": {"bound": "mfma",
-                     "kernel": "contract_pair_kernel<dgrad 64x64 | wgrad 64x64> + finish_kernel (the conv_backward call)",
-                     "achieved": bwd_tops, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": bwd_tops / PEAK_INT8_TOPS,
-                     "traffic": BWD_TRAFFIC_BYTES["read"] + BWD_TRAFFIC_BYTES["written"],
-                     "traffic_unit": "bytes of HBM per call (rocprofv3 --pmc, see profiles/)",
-                     "algorithmic_bytes": dy.numel() + w.numel() + x.numel() + dx.numel() + dw.numel(),
-                     "avg_launch_ms": bwd_ms, "avg_launch_ms_note": note},
-        "roofline_fwd": {"bound": "mfma", "kernel": "contract_kernel<fwd 128x64> (the conv_fwd call is this one launch)",
-                         "achieved": fwd_tops, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": fwd_tops / PEAK_INT8_TOPS,
-                         "traffic": FWD_TRAFFIC_BYTES["read"] + FWD_TRAFFIC_BYTES["written"],
-                         "algorithmic_bytes": x.numel() + w.numel() + y.numel(), "avg_launch_ms": fwd_ms},
-        "host_enqueue_ms_per_step": t_enq / args.steps * 1e3,
-        "calls_ms_back_to_back": call_ms,
-        "conv_TOPS": {"fwd": conv_ops / (call_ms["conv_fwd"] * 1e-3) / 1e12,
-                      "backward (dgrad + wgrad)": 2 * conv_ops / (call_ms["conv_backward"] * 1e-3) / 1e12},
-        "quantize_GBps": q_bytes / (call_ms["quantize"] * 1e-3) / 1e9,
-        "quantize_frac_hbm": q_bytes / (call_ms["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
-        "kld_GBps": kld_bytes / (call_ms["kld_search"] * 1e-3) / 1e9,
-        "kld_frac_hbm": kld_bytes / (call_ms["kld_search"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                     "kernel": "the contraction kernels of one step (contract_kernel<...> instances, contract_pair_kernel, finish_kernel): "
+                               f"{con['calls_per_step']} conv_fwd / conv_backward calls",
+                     "units_per_launch": "issued int8 MFMA ops of one step (useful 2*M*N*K x 4 for layers above 8 bits) over the "
+                                         "summed device time of these calls",
+                     "achieved": con["issued_TOPS"], "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": con["frac_int8_peak"],
+                     "avg_launch_ms": con["ms_per_step_in_timed_region"], "avg_launch_ms_note": con["note"],
+                     "traffic": traffic, "traffic_profile": TRAFFIC["profile"] if traffic else None,
+                     "useful_TOPS": con["useful_TOPS"], "heaviest_layer": head.get("heaviest_layer")},
+        "quantize": head["quantize"], "kld": head["kld"], "calls_ms_back_to_back": head["calls_ms_back_to_back"],
+        "host_enqueue_ms_per_step": head["host_enqueue_ms_per_step"],
+        "layers": head.get("layers"),
     }
-    # cold-cache rate of the HBM-bound quantize call: 8 distinct sets of the three tensors (340 MB of
-    # inputs and outputs, more than the 256 MB of last-level cache) used in turn
-    sets = [([t.clone() for t in (x, w, dy)], [torch.empty_like(t) for t in (qx, qw, qdy)]) for _ in range(8)]
-    for ins, outs in sets:
-        ctx.quantize_batched(ins, [f, f, f], [1, 2, 3], pkg.SR, 0, outs=outs, counters=counters)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for rep in range(5):
-        for ins, outs in sets:
-            ctx.quantize_batched(ins, [f, f, f], [1, 2, 3], pkg.SR, 0, outs=outs, counters=counters)
-    e1.record()
-    torch.cuda.synchronize()
-    cold_ms = e0.elapsed_time(e1) / 40
-    out["quantize_cold_GBps"] = q_bytes / (cold_ms * 1e-3) / 1e9
-    out["quantize_cold_frac_hbm"] = out["quantize_cold_GBps"] / PEAK_HBM_GBPS
-    del sets
+    out["quantize_cold"] = cold_quantize(ctx, pkg, torch)
     if not args.no_next_rows:
-        out["next_rows"] = next_rows(ctx, pkg, torch, w)
+        subs = {}
+        for cfg in (1, 2, 3, 4):
+            if cfg == args.config:
+                continue
+            torch.cuda.empty_cache()
+            r = run_config(cfg, 30, 5, ctx, pkg, torch)
+            subs[f"configs[{cfg - 1}]"] = r
+        out["other_configs"] = subs
+        torch.cuda.empty_cache()
+        out["next_rows"] = next_rows(ctx, pkg, torch, 110592)
         out["next_rows"]["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
         out["next_rows"]["chained_step_elementwise"] = elementwise_rows(ctx, pkg, torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_batch)
+        out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))
 
 
