@@ -16,11 +16,16 @@
 // operand, so that a lane ends up holding 16 consecutive n for one m: the requantizing
 // epilogue then needs one Philox block per 8 outputs and issues 16-byte stores.
 //
-// 9..16-bit operands are split on load into two int8 limbs, a = 256*hi + (lo - 128) + 128
-// with hi = a >> 8 and lo - 128 = (a & 255) ^ 0x80, both in [-128,127] for every int16 a.
-// The four limb products accumulate in three int32 accumulators (hi*hi, cross, lo*lo); the
-// "+128" offsets are undone in the epilogue from the row sums of both operands:
-//   sum a*b = sum a'b' + 128 (sum a' + sum b') + 16384 * K,   a' = a - 128.
+// 9..16-bit operands are split on load into two int8 limbs; the four limb products accumulate in
+// three int32 accumulators (hi*hi, cross, lo*lo) that the epilogue recombines in 64 bits.
+//   balanced split (word lengths up to 15): a = 256*hi + lo with lo = the low byte read as a signed
+//     int8 and hi = (a + 128) >> 8, which stays in [-64, 64] for |a| <= 2^14: nothing to correct.
+//   offset split (word length 16, where the balanced hi would reach +128): a = 256*hi + (lo - 128) + 128
+//     with hi = a >> 8 and lo - 128 = (a & 255) ^ 0x80, both in [-128,127] for every int16 a; the
+//     "+128" offsets are undone in the epilogue from the row sums of both operands:
+//       sum a*b = sum a'b' + 128 (sum a' + sum b') + 16384 * K,   a' = a - 128.
+// An operand's limb mode: 1 = int8 storage, one limb; 2 = int16 storage, offset split; 3 = int16
+// storage, balanced split.
 #pragma once
 #include <cmath>
 #include <cstdlib>
@@ -71,6 +76,7 @@ struct ContractArgs {
     void *out;
     int M, N, K;
     int act_es, wgt_es;          // element size in bytes (1: int8, 2: int16)
+    int balanced;                // every int16 operand has a word length of at most 15: balanced limb split
     uint32_t act_bytes, wgt_bytes;   // operand extents (the vector paths read through bounds-checked buffer loads)
     int act_load, wgt_load;      // LOAD_*
     // gemm: element (row,k) at row*rs + k*ks
@@ -179,17 +185,25 @@ __device__ __forceinline__ long long operand_offset(const ContractArgs &a, int r
 // ---------------------------------------------------------------------------------------------
 // limb splitting
 // ---------------------------------------------------------------------------------------------
-// four int16 in (d0 = e1:e0, d1 = e3:e2) -> high bytes / offset low bytes of e0..e3
+constexpr int es_of(int limb_mode) { return limb_mode == 1 ? 1 : 2; }          // bytes per stored code
+constexpr int limbs_of(int limb_mode) { return limb_mode == 1 ? 1 : 2; }
+constexpr bool bal_of(int limb_mode) { return limb_mode == 3; }
+
+typedef short v2s __attribute__((ext_vector_type(2)));
+// four int16 in (d0 = e1:e0, d1 = e3:e2) -> the limbs of e0..e3 (see the header of this file)
+template <bool BAL>
 __device__ __forceinline__ void split16(uint32_t d0, uint32_t d1, uint32_t &hi, uint32_t &lo)
 {
-    hi = __builtin_amdgcn_perm(d1, d0, 0x07050301u);
-    lo = __builtin_amdgcn_perm(d1, d0, 0x06040200u) ^ 0x80808080u;
-}
-// four int8 treated as 16-bit codes: high limb is the sign, low limb the offset byte
-__device__ __forceinline__ void split8(uint32_t d, uint32_t &hi, uint32_t &lo)
-{
-    hi = ((d >> 7) & 0x01010101u) * 0xffu;
-    lo = d ^ 0x80808080u;
+    if (BAL) {
+        const v2s half = {128, 128};
+        const uint32_t t0 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2s, d0) + half);      // one packed 16-bit add
+        const uint32_t t1 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(v2s, d1) + half);
+        hi = __builtin_amdgcn_perm(t1, t0, 0x07050301u);
+        lo = __builtin_amdgcn_perm(d1, d0, 0x06040200u);
+    } else {
+        hi = __builtin_amdgcn_perm(d1, d0, 0x07050301u);
+        lo = __builtin_amdgcn_perm(d1, d0, 0x06040200u) ^ 0x80808080u;
+    }
 }
 // ---------------------------------------------------------------------------------------------
 // tile staging: global -> registers (prefetch) -> LDS
@@ -203,16 +217,11 @@ __device__ __forceinline__ void split8(uint32_t d, uint32_t &hi, uint32_t &lo)
 //            operands).  Global 16-byte loads go to LDS untouched and fragments are read with
 //            ds_read_b64_tr_b8, which hands each lane the 8 k-values of its row out of an
 //            8 (k) x 16 (rows) byte block: no shuffling in registers.
-// Zero elements are stored as code 0, i.e. limbs (hi = 0, lo = 0x80) in two-limb mode.
+// Zero elements are stored as code 0, i.e. limbs (hi = 0, lo = 0x80) after the offset split, (0, 0) after the balanced one.
 // Everything that depends only on the thread's rows is computed once (init); per stage only
 // the k-dependent part of the address remains, and when 64 consecutive k share one filter tap
 // (a.uniform_tap) that part is the same for the whole block and lives in scalar registers.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void zero_unit(uint32_t (&hi)[4], uint32_t (&lo)[4])
-{
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { hi[i] = 0; lo[i] = 0x80808080u; }
-}
 
 // Loads 16 codes (ES = 1: one 16-byte load, ES = 2: two) at element offset `off` and converts them
 // into limb words.  Branch-free: the operand is read through a raw buffer descriptor whose range
@@ -226,7 +235,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
 
-template <int LIMBS, int ES>
+template <int LIMBS, int ES, bool BAL>
 __device__ __forceinline__ void load_unit(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, bool ok, uint32_t (&hi)[4], uint32_t (&lo)[4])
 {
     const uint32_t byte_off = ok ? off * ES : 0xfffffff0u;
@@ -234,22 +243,22 @@ __device__ __forceinline__ void load_unit(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
         const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (LIMBS == 1) hi[i] = v[i]; else split8(v[i], hi[i], lo[i]);
+            hi[i] = v[i];
         }
     } else {
         const v4u v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
         const v4u v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 16, 0);
-        split16(v0[0], v0[1], hi[0], lo[0]);
-        split16(v0[2], v0[3], hi[1], lo[1]);
-        split16(v1[0], v1[1], hi[2], lo[2]);
-        split16(v1[2], v1[3], hi[3], lo[3]);
+        split16<BAL>(v0[0], v0[1], hi[0], lo[0]);
+        split16<BAL>(v0[2], v0[3], hi[1], lo[1]);
+        split16<BAL>(v1[0], v1[1], hi[2], lo[2]);
+        split16<BAL>(v1[2], v1[3], hi[3], lo[3]);
     }
 }
 
 // ---- K-major operand: thread t owns rows (t/4) + 64*i and the 16-byte column (t%4) of every
 //      64-k sub-chunk of the stage.  Element offsets are 32-bit (operands below 2^32 elements,
 //      checked by the host); intermediate values may wrap, valid results do not.
-template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT, int ES>
+template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT, int ES, bool BAL>
 struct LoaderK {
     static constexpr int RPT = ROWS / 64, SUB = BKT / 64, UNITS = RPT * SUB;
     static constexpr int ROW_BYTES = BKT + 16;
@@ -307,7 +316,7 @@ struct LoaderK {
             for (int i = 0; i < RPT; ++i) {
                 const bool ok = valid[i] && kin && (unsigned)(ra[i] + (int)r) < (unsigned)a.h &&
                                 (unsigned)(rb[i] + (int)s) < (unsigned)a.w;
-                load_unit<LIMBS, ES>(ptr, base[i] + koff, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
+                load_unit<LIMBS, ES, BAL>(ptr, base[i] + koff, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
             }
         } else if (ACT && is_dgrad(OP)) {
             const uint32_t tap = fdiv(kq, a.div_k), ko = (uint32_t)k64 - tap * a.k;
@@ -322,12 +331,12 @@ struct LoaderK {
                     ok = ok && (int)(p * a.stride) == hp && (int)(q * a.stride) == wp;
                 }
                 ok = ok && (int)p < a.p && (int)q < a.q;
-                load_unit<LIMBS, ES>(ptr, base[i] + (p * a.q + q) * a.k + ko, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
+                load_unit<LIMBS, ES, BAL>(ptr, base[i] + (p * a.q + q) * a.k + ko, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < RPT; ++i)
-                load_unit<LIMBS, ES>(ptr, base[i] + (uint32_t)k64, valid[i] && kin, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
+                load_unit<LIMBS, ES, BAL>(ptr, base[i] + (uint32_t)k64, valid[i] && kin, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
         }
     }
 
@@ -358,6 +367,9 @@ struct LoaderK {
                             v = ES == 1 ? (int)static_cast<const int8_t *>(ptr)[off] : (int)static_cast<const int16_t *>(ptr)[off];
                         if (LIMBS == 1) {
                             h |= (uint32_t)(v & 0xff) << (8 * b);
+                        } else if (BAL) {
+                            h |= (uint32_t)(((v + 128) >> 8) & 0xff) << (8 * b);
+                            l |= (uint32_t)(v & 0xff) << (8 * b);
                         } else {
                             h |= (uint32_t)((v >> 8) & 0xff) << (8 * b);
                             l |= (uint32_t)((v & 0xff) ^ 0x80) << (8 * b);
@@ -391,7 +403,7 @@ struct LoaderK {
 };
 
 // ---- R-major operand: a unit is 16 consecutive rows of one k
-template <int OP, bool ACT, int ROWS, int LIMBS, int BKT, int ES>
+template <int OP, bool ACT, int ROWS, int LIMBS, int BKT, int ES, bool BAL>
 struct LoaderR {
     static constexpr int CPL = ROWS / 16;                 // 16-row chunks per k line
     static constexpr int UNITS = BKT * CPL / kThreads;
@@ -445,7 +457,7 @@ struct LoaderR {
                 ok = ok && (unsigned)hh < (unsigned)a.h && (unsigned)ww < (unsigned)a.w;
                 off = ((n * (uint32_t)a.h + (uint32_t)hh) * (uint32_t)a.w + (uint32_t)ww) * (uint32_t)a.c + coff[u];
             }
-            load_unit<LIMBS, ES>(ptr, off, ok, rg.hi[u], rg.lo[u]);
+            load_unit<LIMBS, ES, BAL>(ptr, off, ok, rg.hi[u], rg.lo[u]);
         }
     }
 
@@ -478,10 +490,11 @@ struct LoaderR {
     }
 };
 
-template <int OP, bool ACT, int MODE, int ROWS, int LIMBS, int BKT, int ES>
-struct LoaderSelect { typedef LoaderK<OP, ACT, MODE, ROWS, LIMBS, BKT, ES> type; };
-template <int OP, bool ACT, int ROWS, int LIMBS, int BKT, int ES>
-struct LoaderSelect<OP, ACT, LOAD_ROWS, ROWS, LIMBS, BKT, ES> { typedef LoaderR<OP, ACT, ROWS, LIMBS, BKT, ES> type; };
+// LM: the operand's limb mode; LIMBS: of the kernel (a one-limb kernel has both operands in mode 1)
+template <int OP, bool ACT, int MODE, int ROWS, int LM, int BKT>
+struct LoaderSelect { typedef LoaderK<OP, ACT, MODE, ROWS, limbs_of(LM), BKT, es_of(LM), bal_of(LM)> type; };
+template <int OP, bool ACT, int ROWS, int LM, int BKT>
+struct LoaderSelect<OP, ACT, LOAD_ROWS, ROWS, LM, BKT> { typedef LoaderR<OP, ACT, ROWS, limbs_of(LM), BKT, es_of(LM), bal_of(LM)> type; };
 
 // ---------------------------------------------------------------------------------------------
 // accumulator -> output format (the SR rule applied to the accumulator's low bits)
@@ -615,10 +628,14 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
     // layer issues two MFMA products per step instead of four:
     //   a one limb, b = 256 b_hi + b_lo' + 128:   a b = 256 (a b_hi) + (a b_lo') + 128 a
     //   a = 256 a_hi + a_lo' + 128, b one limb:   a b = 256 (a_hi b) + (a_lo' b) + 128 b
-    constexpr int LAL = LIMBS == 2 ? AES : 1, LBL = LIMBS == 2 ? WES : 1;
+    // AES / WES are the operands' limb modes
+    static_assert(LIMBS == 2 || (AES == 1 && WES == 1), "a one-limb kernel takes int8 operands");
+    static_assert(AES == 1 || WES == 1 || AES == WES, "two int16 operands share their split");
+    constexpr int LAL = limbs_of(AES), LBL = limbs_of(WES);
     constexpr bool BOTH2 = LAL == 2 && LBL == 2;
-    typedef typename LoaderSelect<OP, true, AMODE, BM, LAL, BKT, AES>::type LA;
-    typedef typename LoaderSelect<OP, false, WMODE, BN, LBL, BKT, WES>::type LB;
+    constexpr bool OFFS = AES == 2 || WES == 2;      // offset split: the "+128" terms need the operands' row sums
+    typedef typename LoaderSelect<OP, true, AMODE, BM, AES, BKT>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, WES, BKT>::type LB;
     constexpr bool A_R = AMODE == LOAD_ROWS, W_R = WMODE == LOAD_ROWS;
     constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
     constexpr int MB = WM / 32, NB = WN / 32;       // 32x32 blocks per wave
@@ -736,7 +753,7 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                 }
             // sums of the other side's k-values for the "+128" terms: of a' = 256 a_hi + a_lo' when a has two
             // limbs, of the plain codes when it has one (needed only when b has two limbs); likewise for b
-            if (LBL == 2) {
+            if (OFFS && LBL == 2) {
 #pragma unroll
                 for (int j = 0; j < MB; ++j)
 #pragma unroll
@@ -744,7 +761,7 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                         sum_m[j] += LAL == 2 ? 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e])
                                              : dot4_ones((uint32_t)fa_h[j][e]);
             }
-            if (LAL == 2) {
+            if (OFFS && LAL == 2) {
 #pragma unroll
                 for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -772,7 +789,7 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
     // lane holds, for block (i,j): m = m0 + wm*WM + j*32 + l32 and 16 values of n (see above)
     long long corr_m[MB];
     int *sn = reinterpret_cast<int *>(smem);          // [4 waves][NB][32] n-side sums
-    if (LIMBS == 2) {
+    if (OFFS) {
         __syncthreads();                              // the tiles are no longer read
 #pragma unroll
         for (int j = 0; j < MB; ++j) corr_m[j] = (long long)(sum_m[j] + __shfl_xor(sum_m[j], 32, 64));
@@ -795,13 +812,14 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                 if (LIMBS == 1) {
                     v[r] = acc_hh[i][j][r];
                 } else {
-                    const int nl = W_R ? 8 * (r >> 2) + 4 * g + (r & 3) : 16 * g + r;
-                    const long long s_n = sn[(wave * NB + i) * 32 + nl];
-                    if (BOTH2)
-                        v[r] = ((long long)acc_hh[i][j][r] << 16) + ((long long)acc_x[i][j][r] << 8) + (long long)acc_ll[i][j][r] +
-                               128 * (corr_m[j] + s_n) + 16384 * kpad;
-                    else      // one side has one limb: the other side's sums are zero and never enter
-                        v[r] = ((long long)acc_hh[i][j][r] << 8) + (long long)acc_x[i][j][r] + 128 * (LBL == 2 ? corr_m[j] : s_n);
+                    if (BOTH2) v[r] = ((long long)acc_hh[i][j][r] << 16) + ((long long)acc_x[i][j][r] << 8) + (long long)acc_ll[i][j][r];
+                    else v[r] = ((long long)acc_hh[i][j][r] << 8) + (long long)acc_x[i][j][r];
+                    if (OFFS) {
+                        const int nl = W_R ? 8 * (r >> 2) + 4 * g + (r & 3) : 16 * g + r;
+                        const long long s_n = sn[(wave * NB + i) * 32 + nl];
+                        // one side with one limb: the other side's sums are zero and never enter
+                        v[r] += BOTH2 ? 128 * (corr_m[j] + s_n) + 16384 * kpad : 128 * (LBL == 2 ? corr_m[j] : s_n);
+                    }
                 }
             }
             int m = m0 + wm * WM + j * 32 + l32;
@@ -845,7 +863,7 @@ constexpr int min_waves_per_simd(int op, int limbs, int amode, int wmode, int ae
     // 209 -> 200 us; the 64x128 tile spills, the 64x192 tile gains nothing)
     if (limbs == 1 && bm == 128 && bn == 128) return 3;
     if (limbs == 1 && bm == 128 && bn == 64) return 4;
-    return (op != OP_WGRAD && limbs == 2 && aes == 2 && wes == 2 && bm == 64 && bn == 64) ? 3 : 1;
+    return (op != OP_WGRAD && limbs == 2 && aes >= 2 && wes >= 2 && bm == 64 && bn == 64) ? 3 : 1;
 }
 
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
@@ -859,18 +877,18 @@ contract_kernel(const ContractArgs a)
 
 // Two independent contractions in one launch (the two gradients of a layer): blocks [0, n_first)
 // run the first, the rest the second, so that each fills the CUs the other leaves idle and one
-// launch floor is paid instead of two.  Both have the same number of limbs, element size (LIMBS
-// bytes) and stage depth.
-template <int LIMBS, int BKT, int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB>
-__global__ void __launch_bounds__(kThreads, (LIMBS == 2 && BMA == 64 && BNA == 64 && BMB == 64 && BNB == 64) ? 3 : 1)      // as above; measured faster for the pair
+// launch floor is paid instead of two.  Both have the same limb mode and stage depth.
+// LM: the limb mode of all four operands (1, or 2 / 3 for int16 operands).
+template <int LM, int BKT, int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB>
+__global__ void __launch_bounds__(kThreads, (LM >= 2 && BMA == 64 && BNA == 64 && BMB == 64 && BNB == 64) ? 3 : 1)      // as above; measured faster for the pair
 contract_pair_kernel(const ContractArgs a, const ContractArgs b, const unsigned n_first, const unsigned tiles_a,
                      const unsigned tiles_b)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     if (blockIdx.x < n_first)
-        contract_body<OPA, LIMBS, AMA, WMA, LIMBS, LIMBS, BMA, BNA, 2, 2, BKT>(a, blockIdx.x, n_first, tiles_a, smem);
+        contract_body<OPA, limbs_of(LM), AMA, WMA, LM, LM, BMA, BNA, 2, 2, BKT>(a, blockIdx.x, n_first, tiles_a, smem);
     else
-        contract_body<OPB, LIMBS, AMB, WMB, LIMBS, LIMBS, BMB, BNB, 2, 2, BKT>(b, blockIdx.x - n_first, gridDim.x - n_first,
+        contract_body<OPB, limbs_of(LM), AMB, WMB, LM, LM, BMB, BNB, 2, 2, BKT>(b, blockIdx.x - n_first, gridDim.x - n_first,
                                                                                  tiles_b, smem);
 }
 
@@ -918,9 +936,9 @@ struct TileShape { int bm, bn, bkt; };
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
 static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
-    constexpr int LAL = LIMBS == 2 ? AES : 1, LBL = LIMBS == 2 ? WES : 1;      // limbs per operand, as in the kernel
-    typedef typename LoaderSelect<OP, true, AMODE, BM, LAL, BKT, AES>::type LA;
-    typedef typename LoaderSelect<OP, false, WMODE, BN, LBL, BKT, WES>::type LB;
+    constexpr int LAL = limbs_of(AES), LBL = limbs_of(WES);      // limbs per operand, as in the kernel
+    typedef typename LoaderSelect<OP, true, AMODE, BM, AES, BKT>::type LA;
+    typedef typename LoaderSelect<OP, false, WMODE, BN, WES, BKT>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const size_t lds = std::max<size_t>((size_t)LA::TILE_BYTES * LAL + (size_t)LB::TILE_BYTES * LBL, 4 * 4 * 32 * sizeof(int) * 4);
     auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT>;
@@ -936,8 +954,16 @@ static hipError_t launch_variant(adapt_ctx *ctx, const ContractArgs &a, int spli
     if constexpr (LIMBS == 1) {
         return launch_es<OP, 1, AMODE, WMODE, 1, 1, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
     } else {
-        if (a.act_es == 2 && a.wgt_es == 2) return launch_es<OP, 2, AMODE, WMODE, 2, 2, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
-        if (a.act_es == 2) return launch_es<OP, 2, AMODE, WMODE, 2, 1, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+        // limb modes: balanced split when no int16 operand is wider than 15 bits, else the offset split
+        if (a.act_es == 2 && a.wgt_es == 2) {
+            if (a.balanced) return launch_es<OP, 2, AMODE, WMODE, 3, 3, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+            return launch_es<OP, 2, AMODE, WMODE, 2, 2, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+        }
+        if (a.act_es == 2) {
+            if (a.balanced) return launch_es<OP, 2, AMODE, WMODE, 3, 1, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+            return launch_es<OP, 2, AMODE, WMODE, 2, 1, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
+        }
+        if (a.balanced) return launch_es<OP, 2, AMODE, WMODE, 1, 3, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
         return launch_es<OP, 2, AMODE, WMODE, 1, 2, BM, BN, WGM, WGN, BKT>(ctx, a, splits);
     }
 }
@@ -1119,6 +1145,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
         a.seed = ep.rng.seed;
         a.stream = ep.rng.stream;
     }
+    a.balanced = fa.wl <= 15 && fb.wl <= 15;
     p.limbs = limbs;
     p.bits = bits;
     p.empty = a.M == 0 || a.N == 0;

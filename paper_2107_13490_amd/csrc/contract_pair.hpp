@@ -5,15 +5,15 @@
 
 namespace adapt {
 
-template <int LIMBS, int BKT, int DBM, int DBN, int WBM, int WBN>
+template <int LM, int BKT, int DBM, int DBN, int WBM, int WBN>
 static hipError_t launch_pair(adapt_ctx *ctx, const ContractPlan &d, const ContractPlan &w)
 {
-    typedef typename LoaderSelect<OP_DGRAD, true, LOAD_VEC, DBM, LIMBS, BKT, LIMBS>::type DA;
-    typedef typename LoaderSelect<OP_DGRAD, false, LOAD_ROWS, DBN, LIMBS, BKT, LIMBS>::type DB;
-    typedef typename LoaderSelect<OP_WGRAD, true, LOAD_ROWS, WBM, LIMBS, BKT, LIMBS>::type WA;
-    typedef typename LoaderSelect<OP_WGRAD, false, LOAD_ROWS, WBN, LIMBS, BKT, LIMBS>::type WB;
-    const size_t lds = std::max<size_t>(DA::TILE_BYTES + DB::TILE_BYTES, WA::TILE_BYTES + WB::TILE_BYTES) * LIMBS;
-    auto kern = contract_pair_kernel<LIMBS, BKT, OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
+    typedef typename LoaderSelect<OP_DGRAD, true, LOAD_VEC, DBM, LM, BKT>::type DA;
+    typedef typename LoaderSelect<OP_DGRAD, false, LOAD_ROWS, DBN, LM, BKT>::type DB;
+    typedef typename LoaderSelect<OP_WGRAD, true, LOAD_ROWS, WBM, LM, BKT>::type WA;
+    typedef typename LoaderSelect<OP_WGRAD, false, LOAD_ROWS, WBN, LM, BKT>::type WB;
+    const size_t lds = std::max<size_t>(DA::TILE_BYTES + DB::TILE_BYTES, WA::TILE_BYTES + WB::TILE_BYTES) * limbs_of(LM);
+    auto kern = contract_pair_kernel<LM, BKT, OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
     if (hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(kern), lds); e != hipSuccess) return e;
     const unsigned tiles_d = (unsigned)(((d.kern.M + DBM - 1) / DBM) * ((d.kern.N + DBN - 1) / DBN));
     const unsigned tiles_w = (unsigned)(((w.kern.M + WBM - 1) / WBM) * ((w.kern.N + WBN - 1) / WBN));
@@ -31,7 +31,11 @@ static hipError_t launch_pair_for(adapt_ctx *ctx, const ContractPlan &d, const C
     *done = true;
     if (d.limbs == 2) {
         if constexpr (DBM == DBN)
-            if (w.tile.bm == DBM && w.tile.bn == DBN) return launch_pair<2, 64, DBM, DBN, DBM, DBN>(ctx, d, w);
+            if (w.tile.bm == DBM && w.tile.bn == DBN) {
+                // one limb mode for the launch: balanced only when both contractions can take it
+                if (d.kern.balanced && w.kern.balanced) return launch_pair<3, 64, DBM, DBN, DBM, DBN>(ctx, d, w);
+                return launch_pair<2, 64, DBM, DBN, DBM, DBN>(ctx, d, w);
+            }
         *done = false;
         return hipSuccess;
     }
