@@ -8,7 +8,7 @@ using namespace adapt;
 
 static bool pairable(const ContractPlan &p, bool is_dgrad)
 {
-    if (p.empty || p.tile.bkt != (p.limbs == 1 ? 192 : 64)) return false;
+    if (p.empty || p.tile.pipe || p.tile.bkt != (p.limbs == 1 ? 192 : 64)) return false;
     if (p.limbs == 2 && (p.kern.act_es != 2 || p.kern.wgt_es != 2)) return false;      // mixed storage: not paired
     if (is_dgrad) {
         if (p.kern.dg_classes) return false;      // stride 2 in class order: its own kernel, worth more than the shared launch

@@ -31,6 +31,7 @@
 #include <cstdlib>
 #include <cstdio>
 #include <algorithm>
+#include <type_traits>
 
 #include "common.hpp"
 #include "context.hpp"
@@ -77,6 +78,7 @@ struct ContractArgs {
     int M, N, K;
     int act_es, wgt_es;          // element size in bytes (1: int8, 2: int16)
     int balanced;                // every int16 operand has a word length of at most 15: balanced limb split
+    int fast;                    // two limbs, requantized output: the sums are small enough for 32-bit forms (see emit_run)
     uint32_t act_bytes, wgt_bytes;   // operand extents (the vector paths read through bounds-checked buffer loads)
     int act_load, wgt_load;      // LOAD_*
     // gemm: element (row,k) at row*rs + k*ks
@@ -223,10 +225,11 @@ __device__ __forceinline__ void split16(uint32_t d0, uint32_t d1, uint32_t &hi, 
 // (a.uniform_tap) that part is the same for the whole block and lives in scalar registers.
 // ---------------------------------------------------------------------------------------------
 
-// Loads 16 codes (ES = 1: one 16-byte load, ES = 2: two) at element offset `off` and converts them
-// into limb words.  Branch-free: the operand is read through a raw buffer descriptor whose range
-// check returns zeros for out-of-range offsets, so an invalid unit just uses an offset beyond
-// the tensor; zeros split into the limbs of code 0.
+// A unit is 16 codes.  load_unit fetches one (ES = 1: one 16-byte load, ES = 2: two) at element offset `off` into
+// staging registers as it lies in memory; split_unit turns a staged unit into limb words, which happens only when the
+// unit is written to LDS, a stage later: a wavefront never waits on a load it has just issued.  Branch-free: the
+// operand is read through a raw buffer descriptor whose range check returns zeros for out-of-range offsets, so an
+// invalid unit just uses an offset beyond the tensor; zeros split into the limbs of code 0.
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
@@ -235,23 +238,31 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
 
-template <int LIMBS, int ES, bool BAL>
-__device__ __forceinline__ void load_unit(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, bool ok, uint32_t (&hi)[4], uint32_t (&lo)[4])
+template <int ES>
+__device__ __forceinline__ void load_unit(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, bool ok, uint32_t (&r0)[4], uint32_t (&r1)[4])
 {
     const uint32_t byte_off = ok ? off * ES : 0xfffffff0u;
-    if (ES == 1) {
-        const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
+    const v4u v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            hi[i] = v[i];
-        }
-    } else {
-        const v4u v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
+    for (int i = 0; i < 4; ++i) r0[i] = v0[i];
+    if (ES == 2) {
         const v4u v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 16, 0);
-        split16<BAL>(v0[0], v0[1], hi[0], lo[0]);
-        split16<BAL>(v0[2], v0[3], hi[1], lo[1]);
-        split16<BAL>(v1[0], v1[1], hi[2], lo[2]);
-        split16<BAL>(v1[2], v1[3], hi[3], lo[3]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r1[i] = v1[i];
+    }
+}
+
+template <int ES, bool BAL>
+__device__ __forceinline__ void split_unit(const uint32_t (&r0)[4], const uint32_t (&r1)[4], uint32_t (&hi)[4], uint32_t (&lo)[4])
+{
+    if (ES == 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hi[i] = r0[i];
+    } else {
+        split16<BAL>(r0[0], r0[1], hi[0], lo[0]);
+        split16<BAL>(r0[2], r0[3], hi[1], lo[1]);
+        split16<BAL>(r1[0], r1[1], hi[2], lo[2]);
+        split16<BAL>(r1[2], r1[3], hi[3], lo[3]);
     }
 }
 
@@ -263,9 +274,13 @@ struct LoaderK {
     static constexpr int RPT = ROWS / 64, SUB = BKT / 64, UNITS = RPT * SUB;
     static constexpr int ROW_BYTES = BKT + 16;
     static constexpr int TILE_BYTES = ROWS * ROW_BYTES;
-    struct Regs { uint32_t hi[UNITS][4], lo[UNITS][4]; };   // one stage in flight
+    // one stage in flight: the units as loaded (hi = first, lo = second 16 bytes of a unit of int16 codes); the
+    // element-wise gather stages limb words instead
+    struct Regs { uint32_t hi[UNITS][4], lo[UNITS][4]; };
     uint32_t base[RPT];       // row part of the element offset, plus the thread's 16-element column
-    int ra[RPT], rb[RPT];
+    // convolution activations (forward x, data-gradient dy): bit t = filter tap t reads inside the tensor for this row
+    // (0 for rows beyond M); at most 32 taps on this path.  Other operands: all ones / zero by row validity.
+    uint32_t tapmask[RPT];
     bool valid[RPT];
     __amdgpu_buffer_rsrc_t rsrc;
 
@@ -276,23 +291,44 @@ struct LoaderK {
         for (int i = 0; i < RPT; ++i) {
             const int row = row0 + (threadIdx.x >> 2) + 64 * i;
             valid[i] = row < (ACT ? a.M : a.N);
-            ra[i] = 0; rb[i] = 0; base[i] = 0;
+            base[i] = 0;
+            tapmask[i] = valid[i] ? 0xffffffffu : 0u;
             if (MODE == LOAD_SCALAR) continue;
             if (OP == OP_GEMM) {
                 base[i] = (uint32_t)row * (uint32_t)(ACT ? a.act_rs : a.wgt_rs);
             } else if (ACT && OP == OP_FWD) {
                 const uint32_t pq = fdiv(row, a.div_q), q = row - pq * a.q;
                 const uint32_t n = fdiv(pq, a.div_p), p = pq - n * a.p;
-                ra[i] = (int)p * a.stride - a.pad;
-                rb[i] = (int)q * a.stride - a.pad;
-                base[i] = ((n * (uint32_t)a.h + (uint32_t)ra[i]) * (uint32_t)a.w + (uint32_t)rb[i]) * (uint32_t)a.c;
+                const int ra = (int)p * a.stride - a.pad, rb = (int)q * a.stride - a.pad;
+                base[i] = ((n * (uint32_t)a.h + (uint32_t)ra) * (uint32_t)a.w + (uint32_t)rb) * (uint32_t)a.c;
+                // tap (r, s) reads x[ra + r][rb + s]
+                uint32_t vs = 0, m = 0;
+                for (int ss = 0; ss < a.s; ++ss) vs |= (uint32_t)((unsigned)(rb + ss) < (unsigned)a.w) << ss;
+                for (int rr = 0; rr < a.r; ++rr)
+                    if ((unsigned)(ra + rr) < (unsigned)a.h) m |= vs << (rr * a.s);
+                tapmask[i] = valid[i] ? m : 0u;
             } else if (ACT && is_dgrad(OP)) {
                 const uint32_t rr = (OP == OP_DGRAD_S2 && valid[i]) ? dgrad_real_row(a, row) : (uint32_t)row;
                 const uint32_t nh = fdiv(rr, a.div_w), w = rr - nh * a.w;
                 const uint32_t n = fdiv(nh, a.div_h), h = nh - n * a.h;
-                ra[i] = (int)h + a.pad;
-                rb[i] = (int)w + a.pad;
-                base[i] = n * (uint32_t)(a.p * a.q) * (uint32_t)a.k;
+                const int ra = (int)h + a.pad, rb = (int)w + a.pad;
+                // tap (r, s) reads dy[(ra - r) / stride][(rb - s) / stride] when both divide and lie inside; then
+                // (ra - r) / stride = floor(ra / stride) - floor(r / stride) (equal remainders cancel), so the offset
+                // splits into a row part (here) and a tap part (uniform, see load_sub)
+                const uint32_t pa = fdiv((uint32_t)ra, a.div_stride), qa = fdiv((uint32_t)rb, a.div_stride);
+                base[i] = (n * (uint32_t)(a.p * a.q) + pa * (uint32_t)a.q + qa) * (uint32_t)a.k;
+                uint32_t vs = 0, m = 0;
+                for (int ss = 0; ss < a.s; ++ss) {
+                    const int wp = rb - ss;
+                    const uint32_t qq = fdiv((uint32_t)max(wp, 0), a.div_stride);
+                    vs |= (uint32_t)(wp >= 0 && (int)(qq * a.stride) == wp && (int)qq < a.q) << ss;
+                }
+                for (int r2 = 0; r2 < a.r; ++r2) {
+                    const int hp = ra - r2;
+                    const uint32_t pp = fdiv((uint32_t)max(hp, 0), a.div_stride);
+                    if (hp >= 0 && (int)(pp * a.stride) == hp && (int)pp < a.p) m |= vs << (r2 * a.s);
+                }
+                tapmask[i] = valid[i] ? m : 0u;
             } else {
                 base[i] = (uint32_t)row * (uint32_t)a.K;      // filters: [row][k]
             }
@@ -303,8 +339,9 @@ struct LoaderK {
     // One 64-k sub-chunk of all the thread's rows.  kq decides the filter tap: the sub-chunk's first k
     // when 64 aligned k share a tap (a uniform value: the tap arithmetic runs on the scalar unit),
     // else the thread's own k.
+    // rows [i0, i1) of the thread's RPT rows
     template <typename KQ>
-    __device__ __forceinline__ void load_sub(const ContractArgs &a, int sc, int k, int k64, KQ kq, Regs &rg) const
+    __device__ __forceinline__ void load_sub(const ContractArgs &a, int sc, int k, int k64, KQ kq, Regs &rg, int i0 = 0, int i1 = RPT) const
     {
         const __amdgpu_buffer_rsrc_t ptr = rsrc;
         const bool kin = k < a.K;
@@ -314,29 +351,24 @@ struct LoaderK {
             const uint32_t koff = (r * a.w + s) * a.c + ((uint32_t)k64 - tap * a.c);
 #pragma unroll
             for (int i = 0; i < RPT; ++i) {
-                const bool ok = valid[i] && kin && (unsigned)(ra[i] + (int)r) < (unsigned)a.h &&
-                                (unsigned)(rb[i] + (int)s) < (unsigned)a.w;
-                load_unit<LIMBS, ES, BAL>(ptr, base[i] + koff, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
+                if (i < i0 || i >= i1) continue;
+                const bool ok = kin && ((tapmask[i] >> (tap & 31u)) & 1u);
+                load_unit<ES>(ptr, base[i] + koff, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
             }
         } else if (ACT && is_dgrad(OP)) {
             const uint32_t tap = fdiv(kq, a.div_k), ko = (uint32_t)k64 - tap * a.k;
             const uint32_t r = fdiv(tap, a.div_s), s = tap - r * a.s;
+            const uint32_t koff = ko - (fdiv(r, a.div_stride) * (uint32_t)a.q + fdiv(s, a.div_stride)) * (uint32_t)a.k;
 #pragma unroll
             for (int i = 0; i < RPT; ++i) {
-                const int hp = ra[i] - (int)r, wp = rb[i] - (int)s;
-                uint32_t p = hp, q = wp;
-                bool ok = valid[i] && kin && hp >= 0 && wp >= 0;
-                if (a.stride != 1) {
-                    p = fdiv(ok ? hp : 0, a.div_stride); q = fdiv(ok ? wp : 0, a.div_stride);
-                    ok = ok && (int)(p * a.stride) == hp && (int)(q * a.stride) == wp;
-                }
-                ok = ok && (int)p < a.p && (int)q < a.q;
-                load_unit<LIMBS, ES, BAL>(ptr, base[i] + (p * a.q + q) * a.k + ko, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
+                if (i < i0 || i >= i1) continue;
+                const bool ok = kin && ((tapmask[i] >> (tap & 31u)) & 1u);
+                load_unit<ES>(ptr, base[i] + koff, ok, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < RPT; ++i)
-                load_unit<LIMBS, ES, BAL>(ptr, base[i] + (uint32_t)k64, valid[i] && kin, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
+                if (i >= i0 && i < i1) load_unit<ES>(ptr, base[i] + (uint32_t)k64, valid[i] && kin, rg.hi[sc * RPT + i], rg.lo[sc * RPT + i]);
         }
     }
 
@@ -382,17 +414,35 @@ struct LoaderK {
         }
     }
 
+    // unit u = sc * RPT + i alone (vector path): the pipelined main loop spreads a stage's loads over its MFMAs
+    __device__ __forceinline__ void load_one(const ContractArgs &a, int k0, int u, Regs &rg) const
+    {
+        static_assert(MODE == LOAD_VEC, "per-unit loads exist for the vector path");
+        const int sc = u / RPT, i = u % RPT;
+        const int k64 = k0 + sc * 64, k = k64 + (threadIdx.x & 3) * 16;
+        if (a.uniform_tap) load_sub(a, sc, k, k64, (uint32_t)__builtin_amdgcn_readfirstlane(k64), rg, i, i + 1);
+        else load_sub(a, sc, k, k64, (uint32_t)k, rg, i, i + 1);
+    }
+
+    __device__ __forceinline__ static void store_one(const Regs &rg, int u, char *tile_hi, char *tile_lo)
+    {
+        const int sc = u / RPT, i = u % RPT;
+        const int o = ((threadIdx.x >> 2) + 64 * i) * ROW_BYTES + sc * 64 + (threadIdx.x & 3) * 16;
+        uint32_t hi[4], lo[4];
+        if (MODE == LOAD_SCALAR) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { hi[w] = rg.hi[u][w]; lo[w] = rg.lo[u][w]; }
+        } else {
+            split_unit<ES, BAL>(rg.hi[u], rg.lo[u], hi, lo);
+        }
+        *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    }
+
     __device__ __forceinline__ static void store(const Regs &rg, char *tile_hi, char *tile_lo)
     {
 #pragma unroll
-        for (int sc = 0; sc < SUB; ++sc)
-#pragma unroll
-            for (int i = 0; i < RPT; ++i) {
-                const int u = sc * RPT + i;
-                const int o = ((threadIdx.x >> 2) + 64 * i) * ROW_BYTES + sc * 64 + (threadIdx.x & 3) * 16;
-                *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(rg.hi[u][0], rg.hi[u][1], rg.hi[u][2], rg.hi[u][3]);
-                if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(rg.lo[u][0], rg.lo[u][1], rg.lo[u][2], rg.lo[u][3]);
-            }
+        for (int u = 0; u < UNITS; ++u) store_one(rg, u, tile_hi, tile_lo);
     }
 
     // MFMA fragment: the 16 k-values [32*ks + 16*g, +16) of tile row `row`
@@ -436,9 +486,16 @@ struct LoaderR {
 
     __device__ __forceinline__ void load(const ContractArgs &a, int row0, int k0, Regs &rg) const
     {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) load_one(a, k0, u, rg);
+    }
+
+    __device__ __forceinline__ void load_one(const ContractArgs &a, int k0, int u0, Regs &rg) const
+    {
         const __amdgpu_buffer_rsrc_t ptr = rsrc;
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
+            if (u != u0) continue;
             const int id = threadIdx.x + u * kThreads;
             const int kk = k0 + id / CPL;
             bool ok = valid[u] && kk < a.K;
@@ -457,19 +514,24 @@ struct LoaderR {
                 ok = ok && (unsigned)hh < (unsigned)a.h && (unsigned)ww < (unsigned)a.w;
                 off = ((n * (uint32_t)a.h + (uint32_t)hh) * (uint32_t)a.w + (uint32_t)ww) * (uint32_t)a.c + coff[u];
             }
-            load_unit<LIMBS, ES, BAL>(ptr, off, ok, rg.hi[u], rg.lo[u]);
+            load_unit<ES>(ptr, off, ok, rg.hi[u], rg.lo[u]);
         }
+    }
+
+    __device__ __forceinline__ static void store_one(const Regs &rg, int u, char *tile_hi, char *tile_lo)
+    {
+        const int id = threadIdx.x + u * kThreads;
+        const int o = (id / CPL) * ROW_BYTES + (id % CPL) * 16;
+        uint32_t hi[4], lo[4];
+        split_unit<ES, BAL>(rg.hi[u], rg.lo[u], hi, lo);
+        *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
     }
 
     __device__ __forceinline__ static void store(const Regs &rg, char *tile_hi, char *tile_lo)
     {
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const int id = threadIdx.x + u * kThreads;
-            const int o = (id / CPL) * ROW_BYTES + (id % CPL) * 16;
-            *reinterpret_cast<uint4 *>(tile_hi + o) = make_uint4(rg.hi[u][0], rg.hi[u][1], rg.hi[u][2], rg.hi[u][3]);
-            if (LIMBS == 2) *reinterpret_cast<uint4 *>(tile_lo + o) = make_uint4(rg.lo[u][0], rg.lo[u][1], rg.lo[u][2], rg.lo[u][3]);
-        }
+        for (int u = 0; u < UNITS; ++u) store_one(rg, u, tile_hi, tile_lo);
     }
 
     // MFMA fragment for the 32 rows starting at row32: lane l gets row row32 + l%32, k-values
@@ -515,11 +577,19 @@ __device__ __forceinline__ uint32_t pack4_i8(int q0, int q1, int q2, int q3)
     return __builtin_amdgcn_perm((uint32_t)q1, (uint32_t)q0, 0x0c0c0400u) | __builtin_amdgcn_perm((uint32_t)q3, (uint32_t)q2, 0x04000c0cu);
 }
 
-// Writes 16 consecutive outputs (m, n0 .. n0+15) held by one lane.  FITS32: the values are int32
-// accumulators of the one-limb path.
-template <int RUN, bool FITS32>
+// Writes 16 consecutive outputs (m, n0 .. n0+15) held by one lane.  FORM says what v holds:
+//   FORM_I64   the exact value
+//   FORM_I32   the exact value, known to fit 32 bits with room for the rounding bits (one-limb accumulators; mixed
+//              two-limb sums whose bound allows it)
+//   FORM_PAIR  (u, lo8) in the high and low halves of v, the exact value being 256 u + lo8 with 0 <= lo8 < 256 and u
+//              in 32 bits: the two-limb sum with its lowest byte split off, for 1 <= shift <= 16.  With r the top
+//              `shift` rounding bits, floor((256 u + lo8 + r) / 2^shift) = (u + ((lo8 + r) >> 8)) >> (shift - 8):
+//              everything stays in 32-bit arithmetic.  Only requantized outputs take this form.
+enum { FORM_I64 = 0, FORM_I32 = 1, FORM_PAIR = 2 };
+template <int RUN, int FORM>
 __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m, int n0, const long long (&v)[RUN])
 {
+    constexpr bool FITS32 = FORM == FORM_I32;
     static_assert(RUN == 16, "a lane holds runs of 16 outputs");
     if (m >= a.M || n0 >= a.N) return;
     const int cnt = min(RUN, a.N - n0);
@@ -574,7 +644,28 @@ __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m
         }
     }
     int q[RUN];
-    if (FITS32 && a.shift >= 1) {
+    if (FORM == FORM_PAIR) {
+        const int qhi = (1 << (a.wl_o - 1)) - 1, qlo = a.relu ? 0 : -(1 << (a.wl_o - 1));
+        if (a.shift >= 8) {
+            const int sh8 = a.shift - 8;
+#pragma unroll
+            for (int i = 0; i < RUN; ++i) {
+                const int u = (int)(v[i] >> 32), lo8 = (int)(uint32_t)v[i];
+                const int r = (int)__builtin_amdgcn_ubfe(rw[i >> 1], 16 * (i & 1) + 16 - a.shift, a.shift);
+                q[i] = min(max((u + ((lo8 + r) >> 8)) >> sh8, qlo), qhi);
+            }
+        } else {
+            // shift below 8: (256 u + lo8 + r) >> shift = (u << (8 - shift)) + ((lo8 + r) >> shift); |u| >= 2^16 saturates
+            // whatever the rest, so u is clamped to +-2^20 first and the left shift stays in 32 bits
+            const int up = 8 - a.shift;
+#pragma unroll
+            for (int i = 0; i < RUN; ++i) {
+                const int u = min(max((int)(v[i] >> 32), -(1 << 20)), 1 << 20), lo8 = (int)(uint32_t)v[i];
+                const int r = (int)__builtin_amdgcn_ubfe(rw[i >> 1], 16 * (i & 1) + 16 - a.shift, a.shift);
+                q[i] = min(max((u << up) + ((lo8 + r) >> a.shift), qlo), qhi);
+            }
+        }
+    } else if (FITS32 && a.shift >= 1) {
         const int qhi = (1 << (a.wl_o - 1)) - 1, qlo = a.relu ? 0 : -(1 << (a.wl_o - 1));
 #pragma unroll
         for (int i = 0; i < RUN; ++i) q[i] = requantize_i32((int)v[i], a.shift, qlo, qhi, rw[i >> 1], i & 1);
@@ -619,7 +710,15 @@ __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_s
 
 // `lin` of `nwg` blocks, `ntiles` output tiles (the rest of the factor nwg / ntiles are K splits);
 // `smem` is the block's dynamic LDS.
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
+//
+// PIPE = 1 is the pipeline of the large tiles (one wavefront per SIMD, so nothing else on the CU covers a
+// wavefront's waits; PIPE = 2: the same with one staging set, for tiles that run two blocks per CU so that one
+// block's epilogue overlaps the other's MFMAs): two LDS stages and one barrier per stage.  While stage kt is multiplied out of one
+// buffer, the tile of stage kt+1 (loaded from memory during stage kt-1) is written to the other and the
+// loads of stage kt+2 are issued; MFMA fragments are read one 32-deep sub-step ahead into a second set of
+// registers, and the barrier sits before the last sub-step, so that the fragment reads of the next stage's
+// first sub-step are in flight behind the MFMAs of this stage's last one.
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0>
 __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsigned lin, const unsigned nwg,
                                               const unsigned ntiles, char *const smem)
 {
@@ -639,8 +738,9 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
     constexpr bool A_R = AMODE == LOAD_ROWS, W_R = WMODE == LOAD_ROWS;
     constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
     constexpr int MB = WM / 32, NB = WN / 32;       // 32x32 blocks per wave
-    char *const a_hi = smem, *const a_lo = smem + LA::TILE_BYTES;
-    char *const b_hi = smem + LA::TILE_BYTES * LAL, *const b_lo = b_hi + LB::TILE_BYTES;
+    // one LDS stage: [ACT hi | ACT lo | WGT hi | WGT lo]
+    constexpr int A_LO = LA::TILE_BYTES, B_HI = LA::TILE_BYTES * LAL, B_LO = B_HI + LB::TILE_BYTES;
+    constexpr int STAGE_BYTES = B_HI + LB::TILE_BYTES * LBL;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -718,71 +818,193 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
         lb.load(a, n0, k0, rb);
     }
 
-    auto multiply_stage = [&]() {
+    struct Frags { v4i fa_h[MB], fa_l[MB], fb_h[NB], fb_l[NB]; };
+    // MFMA fragments of the 32-deep sub-step ks of the stage at `st`
+    auto read_frags = [&](const char *st, int ks, Frags &f) {
 #pragma unroll
-        for (int ks = 0; ks < BKT / 32; ++ks) {
-            v4i fa_h[MB], fa_l[MB], fb_h[NB], fb_l[NB];
-#pragma unroll
-            for (int j = 0; j < MB; ++j) {
-                if constexpr (A_R) {
-                    fa_h[j] = LA::frag(a_hi, wm * WM + j * 32, ks, lane);
-                    if (LAL == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32, ks, lane);
-                } else {
-                    fa_h[j] = LA::frag(a_hi, wm * WM + j * 32 + l32, ks, g);
-                    if (LAL == 2) fa_l[j] = LA::frag(a_lo, wm * WM + j * 32 + l32, ks, g);
-                }
+        for (int j = 0; j < MB; ++j) {
+            if constexpr (A_R) {
+                f.fa_h[j] = LA::frag(st, wm * WM + j * 32, ks, lane);
+                if (LAL == 2) f.fa_l[j] = LA::frag(st + A_LO, wm * WM + j * 32, ks, lane);
+            } else {
+                f.fa_h[j] = LA::frag(st, wm * WM + j * 32 + l32, ks, g);
+                if (LAL == 2) f.fa_l[j] = LA::frag(st + A_LO, wm * WM + j * 32 + l32, ks, g);
             }
+        }
 #pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                if constexpr (W_R) {
-                    fb_h[i] = LB::frag(b_hi, wn * WN + i * 32, ks, lane);
-                    if (LBL == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32, ks, lane);
-                } else {
-                    fb_h[i] = LB::frag(b_hi, wn * WN + i * 32 + nperm, ks, g);
-                    if (LBL == 2) fb_l[i] = LB::frag(b_lo, wn * WN + i * 32 + nperm, ks, g);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < NB; ++i)
-#pragma unroll
-                for (int j = 0; j < MB; ++j) {
-                    acc_hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_h[j], acc_hh[i][j], 0, 0, 0);
-                    if (LAL == 2) acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_h[i], fa_l[j], acc_x[i][j], 0, 0, 0);
-                    if (LBL == 2) acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_h[j], acc_x[i][j], 0, 0, 0);
-                    if (BOTH2) acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb_l[i], fa_l[j], acc_ll[i][j], 0, 0, 0);
-                }
-            // sums of the other side's k-values for the "+128" terms: of a' = 256 a_hi + a_lo' when a has two
-            // limbs, of the plain codes when it has one (needed only when b has two limbs); likewise for b
-            if (OFFS && LBL == 2) {
-#pragma unroll
-                for (int j = 0; j < MB; ++j)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        sum_m[j] += LAL == 2 ? 256 * dot4_ones((uint32_t)fa_h[j][e]) + dot4_ones((uint32_t)fa_l[j][e])
-                                             : dot4_ones((uint32_t)fa_h[j][e]);
-            }
-            if (OFFS && LAL == 2) {
-#pragma unroll
-                for (int i = 0; i < NB; ++i)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        sum_n[i] += LBL == 2 ? 256 * dot4_ones((uint32_t)fb_h[i][e]) + dot4_ones((uint32_t)fb_l[i][e])
-                                             : dot4_ones((uint32_t)fb_h[i][e]);
+        for (int i = 0; i < NB; ++i) {
+            if constexpr (W_R) {
+                f.fb_h[i] = LB::frag(st + B_HI, wn * WN + i * 32, ks, lane);
+                if (LBL == 2) f.fb_l[i] = LB::frag(st + B_LO, wn * WN + i * 32, ks, lane);
+            } else {
+                f.fb_h[i] = LB::frag(st + B_HI, wn * WN + i * 32 + nperm, ks, g);
+                if (LBL == 2) f.fb_l[i] = LB::frag(st + B_LO, wn * WN + i * 32 + nperm, ks, g);
             }
         }
     };
-
-    for (int kt = 0; kt < ksteps; ++kt) {
-        __syncthreads();                 // every wavefront is done with the previous stage
-        LA::store(ra, a_hi, a_lo);
-        LB::store(rb, b_hi, b_lo);
-        __syncthreads();
-        if (kt + 1 < ksteps) {
-            const int k0 = stage_k(kt + 1);
-            la.load(a, m0, k0, ra);
-            lb.load(a, n0, k0, rb);
+    // the MFMAs of one 32 x 32 output block (i, j) for one sub-step, with that block's share of the row sums
+    auto mfma_block = [&](const Frags &f, int i, int j) {
+        acc_hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb_h[i], f.fa_h[j], acc_hh[i][j], 0, 0, 0);
+        if (LAL == 2) acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb_h[i], f.fa_l[j], acc_x[i][j], 0, 0, 0);
+        if (LBL == 2) acc_x[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb_l[i], f.fa_h[j], acc_x[i][j], 0, 0, 0);
+        if (BOTH2) acc_ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb_l[i], f.fa_l[j], acc_ll[i][j], 0, 0, 0);
+        // sums of the other side's k-values for the "+128" terms: of a' = 256 a_hi + a_lo' when a has two
+        // limbs, of the plain codes when it has one (needed only when b has two limbs); likewise for b
+        if (OFFS && LBL == 2 && i == 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                sum_m[j] += LAL == 2 ? 256 * dot4_ones((uint32_t)f.fa_h[j][e]) + dot4_ones((uint32_t)f.fa_l[j][e])
+                                     : dot4_ones((uint32_t)f.fa_h[j][e]);
         }
-        multiply_stage();
+        if (OFFS && LAL == 2 && j == 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                sum_n[i] += LBL == 2 ? 256 * dot4_ones((uint32_t)f.fb_h[i][e]) + dot4_ones((uint32_t)f.fb_l[i][e])
+                                     : dot4_ones((uint32_t)f.fb_h[i][e]);
+        }
+    };
+    auto mfma_step = [&](const Frags &f) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j < MB; ++j) mfma_block(f, i, j);
+    };
+
+    if constexpr (PIPE == 0) {
+        for (int kt = 0; kt < ksteps; ++kt) {
+            __syncthreads();                 // every wavefront is done with the previous stage
+            LA::store(ra, smem, smem + A_LO);
+            LB::store(rb, smem + B_HI, smem + B_LO);
+            __syncthreads();
+            if (kt + 1 < ksteps) {
+                const int k0 = stage_k(kt + 1);
+                la.load(a, m0, k0, ra);
+                lb.load(a, n0, k0, rb);
+            }
+#pragma unroll
+            for (int ks = 0; ks < BKT / 32; ++ks) {
+                Frags f;
+                read_frags(smem, ks, f);
+                mfma_step(f);
+            }
+        }
+    } else {
+        // Everything a stage does besides its MFMAs is cut into NC pieces per sub-step, one after each output block's
+        // MFMAs, with a scheduling fence between the pieces: the wavefront is alone on its SIMD, so LDS stores, global
+        // loads and fragment reads overlap with the matrix unit only if they are issued between its instructions.
+        //   sub-steps 0 .. KS-2 (before the barrier): the tile of stage kt+1 goes from staging set (kt+1)&1 to the other
+        //     LDS buffer; fragments of the next sub-step
+        //   sub-step KS-1 (after the barrier): loads of stage kt+3 into the staging set just freed; fragments of the
+        //     next stage's first sub-step
+        // The loop has no branches: beyond the last stage the loads are out of range (they read zeros without
+        // memory traffic) and the stores and fragment reads touch LDS that nobody uses any more.
+        constexpr int KS = BKT / 32, NC = NB * MB;
+        static_assert(KS % 2 == 0, "the two fragment register sets alternate per sub-step");
+        constexpr int UA = LA::UNITS, UT = LA::UNITS + LB::UNITS;      // staged units of a stage
+        constexpr int FI = MB + NB;                                   // fragment items of a sub-step (one 32-row block each)
+        Frags f[2];
+        typename LA::Regs ra2;
+        typename LB::Regs rb2;
+        auto frag_item = [&](const char *st, int ks, int item, Frags &fr) {
+            if (item < MB) {
+                const int j = item;
+                if constexpr (A_R) {
+                    fr.fa_h[j] = LA::frag(st, wm * WM + j * 32, ks, lane);
+                    if (LAL == 2) fr.fa_l[j] = LA::frag(st + A_LO, wm * WM + j * 32, ks, lane);
+                } else {
+                    fr.fa_h[j] = LA::frag(st, wm * WM + j * 32 + l32, ks, g);
+                    if (LAL == 2) fr.fa_l[j] = LA::frag(st + A_LO, wm * WM + j * 32 + l32, ks, g);
+                }
+            } else {
+                const int i = item - MB;
+                if constexpr (W_R) {
+                    fr.fb_h[i] = LB::frag(st + B_HI, wn * WN + i * 32, ks, lane);
+                    if (LBL == 2) fr.fb_l[i] = LB::frag(st + B_LO, wn * WN + i * 32, ks, lane);
+                } else {
+                    fr.fb_h[i] = LB::frag(st + B_HI, wn * WN + i * 32 + nperm, ks, g);
+                    if (LBL == 2) fr.fb_l[i] = LB::frag(st + B_LO, wn * WN + i * 32 + nperm, ks, g);
+                }
+            }
+        };
+        // reduction offset of stage j; beyond the last stage an offset past the reduction, whose loads return zeros
+        auto stage_of = [&](int j) { return j < ksteps ? stage_k(j) : (a.K + 63) / 64 * 64; };
+        // one stage; SET: the parity of kt (LDS buffer of the stage; the other staging set holds stage kt+1)
+        auto run_stage = [&](auto setc, int kt) {
+            constexpr int SET = decltype(setc)::value;
+            char *const cur = smem + SET * STAGE_BYTES, *const nxt = smem + (SET ^ 1) * STAGE_BYTES;
+            // staging set of this stage: with two sets, set (kt+1)&1 (set 0 = (ra, rb), set 1 = (ra2, rb2)), which holds
+            // stage kt+1 and then takes stage kt+3; with one set (PIPE = 2) it holds stage kt+1 and takes stage kt+2
+            typename LA::Regs &sa = (PIPE == 2 || SET) ? ra : ra2;
+            typename LB::Regs &sb = (PIPE == 2 || SET) ? rb : rb2;
+            const int k3 = stage_of(kt + (PIPE == 2 ? 2 : 3));
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == KS - 1) __syncthreads();      // the next stage's tile is written, this stage's fragments are read
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    if (ks < KS - 1) {
+                        constexpr int R1 = (KS - 1) * NC;                 // pieces before the barrier
+                        const int piece = ks * NC + c;
+#pragma unroll
+                        for (int u = 0; u < UT; ++u)
+                            if (u * R1 / UT == piece) {
+                                if (u < UA) LA::store_one(sa, u, nxt, nxt + A_LO);
+                                else LB::store_one(sb, u - UA, nxt + B_HI, nxt + B_LO);
+                            }
+#pragma unroll
+                        for (int it = 0; it < FI; ++it)
+                            if (it * NC / FI == c) frag_item(cur, ks + 1, it, f[(ks + 1) & 1]);
+                    } else {
+#pragma unroll
+                        for (int it = 0; it < FI; ++it)
+                            if (it * NC / FI == c) frag_item(nxt, 0, it, f[0]);
+#pragma unroll
+                        for (int u = 0; u < UT; ++u)
+                            if (u * NC / UT == c) {
+                                if (u < UA) la.load_one(a, k3, u, sa);
+                                else lb.load_one(a, k3, u - UA, sb);
+                            }
+                    }
+                    mfma_block(f[ks & 1], c / MB, c % MB);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        // No path around the loop: with nothing to reduce (K = 0, or a parity class that sees no filter tap) one stage of
+        // zeros is multiplied.  (A second path from the zeroed accumulators to the epilogue made the register allocator
+        // hold a copy of every accumulator in VGPRs across the loop.)
+        const int nsteps = max(ksteps, 1);
+        {
+            // stage 0 is in set 0: write it, then stage 1 into set 1 and stage 2 into set 0
+            if (ksteps <= 0) {
+                la.load(a, m0, stage_of(0), ra);
+                lb.load(a, n0, stage_of(0), rb);
+            }
+            LA::store(ra, smem, smem + A_LO);
+            LB::store(rb, smem + B_HI, smem + B_LO);
+            if constexpr (PIPE == 2) {
+                la.load(a, m0, stage_of(1), ra);
+                lb.load(a, n0, stage_of(1), rb);
+            } else {
+                la.load(a, m0, stage_of(1), ra2);
+                lb.load(a, n0, stage_of(1), rb2);
+                la.load(a, m0, stage_of(2), ra);
+                lb.load(a, n0, stage_of(2), rb);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < FI; ++it) frag_item(smem, 0, it, f[0]);
+        }
+        // Stage 0 always runs; then pairs of stages, then a last odd one.  (Written this way every path into a stage
+        // has the same order of outstanding loads, older staging set first, so that the stores of a stage wait for their
+        // own set only; with a conditional second stage inside the loop body the compiler had to drain all loads.)
+        run_stage(std::integral_constant<int, 0>{}, 0);
+        int kt = 1;
+        for (; kt + 1 < nsteps; kt += 2) {
+            run_stage(std::integral_constant<int, 1>{}, kt);
+            run_stage(std::integral_constant<int, 0>{}, kt + 1);
+        }
+        if (kt < nsteps) run_stage(std::integral_constant<int, 1>{}, kt);
     }
 
     // ---- epilogue -----------------------------------------------------------------------------
@@ -806,11 +1028,19 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
     for (int i = 0; i < NB; ++i)
 #pragma unroll
         for (int j = 0; j < MB; ++j) {
+            int m_of = 0, nb_of = 0;
             long long v[16];
+            // a.fast: the host has checked the bound that lets a two-limb sum take one of the 32-bit forms
+            const bool pair_form = BOTH2 && !OFFS && a.fast, i32_form = LIMBS == 2 && !BOTH2 && !OFFS && a.fast;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 if (LIMBS == 1) {
                     v[r] = acc_hh[i][j][r];
+                } else if (pair_form) {
+                    const int u = (acc_hh[i][j][r] << 8) + acc_x[i][j][r] + (acc_ll[i][j][r] >> 8);
+                    v[r] = ((long long)u << 32) | (uint32_t)(acc_ll[i][j][r] & 255);
+                } else if (i32_form) {
+                    v[r] = (long long)((acc_hh[i][j][r] << 8) + acc_x[i][j][r]);
                 } else {
                     if (BOTH2) v[r] = ((long long)acc_hh[i][j][r] << 16) + ((long long)acc_x[i][j][r] << 8) + (long long)acc_ll[i][j][r];
                     else v[r] = ((long long)acc_hh[i][j][r] << 8) + (long long)acc_x[i][j][r];
@@ -822,9 +1052,16 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                     }
                 }
             }
+            auto emit = [&](const long long (&vals)[16]) {
+                if (LIMBS == 1) emit_run<16, FORM_I32>(a, out, m_of, nb_of + 16 * g, vals);
+                else if (pair_form) emit_run<16, FORM_PAIR>(a, out, m_of, nb_of + 16 * g, vals);
+                else if (i32_form) emit_run<16, FORM_I32>(a, out, m_of, nb_of + 16 * g, vals);
+                else emit_run<16, FORM_I64>(a, out, m_of, nb_of + 16 * g, vals);
+            };
             int m = m0 + wm * WM + j * 32 + l32;
             const int nb0 = n0 + wn * WN + i * 32;
             if (dg) m = dg_row[dg ? j : 0];                                  // class order -> row of dx
+            m_of = m; nb_of = nb0;
             if constexpr (W_R) {
                 // lanes l and l^32 hold interleaved runs of 4 of the same output row: swap halves
                 // so that each ends up with 16 consecutive n (lane/32 = 0: n 0..15, 1: n 16..31)
@@ -844,9 +1081,9 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                     w[8 + t] = g == 0 ? v[4 + t] : recv[4 + t];
                     w[12 + t] = g == 0 ? recv[4 + t] : v[12 + t];
                 }
-                emit_run<16, LIMBS == 1>(a, out, m, nb0 + 16 * g, w);
+                emit(w);
             } else {
-                emit_run<16, LIMBS == 1>(a, out, m, nb0 + 16 * g, v);
+                emit(v);
             }
         }
 }
@@ -854,8 +1091,10 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
 // Two-limb 64x64 tiles: three accumulator sets and the staging registers land a few registers above what three
 // resident wavefronts per SIMD allow; asking for three makes the register allocator fit them without spills
 // (forward 64->64 3x3 at 32x32, batch 256, <14,11>: 118 -> 86 us).  The weight gradient on its own gains nothing from it.
-constexpr int min_waves_per_simd(int op, int limbs, int amode, int wmode, int aes, int wes, int bm, int bn)
+constexpr int min_waves_per_simd(int op, int limbs, int amode, int wmode, int aes, int wes, int bm, int bn, int pipe)
 {
+    if (pipe == 1) return 1;                                         // the large tiles: one wavefront per SIMD
+    if (pipe == 2) return 2;                                         // two blocks per CU
     if (amode == LOAD_SCALAR || wmode == LOAD_SCALAR) return 1;      // the element-wise gather needs its registers
     // one limb: the same request moves the 128x128 tile from two to three resident wavefronts per SIMD
     // and the 128x64 tile from three to four
@@ -866,12 +1105,12 @@ constexpr int min_waves_per_simd(int op, int limbs, int amode, int wmode, int ae
     return (op != OP_WGRAD && limbs == 2 && aes >= 2 && wes >= 2 && bm == 64 && bn == 64) ? 3 : 1;
 }
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
-__global__ void __launch_bounds__(kThreads, min_waves_per_simd(OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN))
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0>
+__global__ void __launch_bounds__(kThreads, min_waves_per_simd(OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, PIPE))
 contract_kernel(const ContractArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    contract_body<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT>(a, blockIdx.y * gridDim.x + blockIdx.x,
+    contract_body<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PIPE>(a, blockIdx.y * gridDim.x + blockIdx.x,
                                                                                gridDim.x * gridDim.y, gridDim.x, smem);
 }
 
@@ -931,17 +1170,17 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 }
 
 // ---- host side ---------------------------------------------------------------------------------
-struct TileShape { int bm, bn, bkt; };
+struct TileShape { int bm, bn, bkt, pipe; };      // pipe: the double-buffered pipeline of the large tiles
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT>
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0>
 static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
 {
     constexpr int LAL = limbs_of(AES), LBL = limbs_of(WES);      // limbs per operand, as in the kernel
     typedef typename LoaderSelect<OP, true, AMODE, BM, AES, BKT>::type LA;
     typedef typename LoaderSelect<OP, false, WMODE, BN, WES, BKT>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    const size_t lds = std::max<size_t>((size_t)LA::TILE_BYTES * LAL + (size_t)LB::TILE_BYTES * LBL, 4 * 4 * 32 * sizeof(int) * 4);
-    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT>;
+    const size_t lds = std::max<size_t>(((size_t)LA::TILE_BYTES * LAL + (size_t)LB::TILE_BYTES * LBL) * (PIPE ? 2 : 1), 4 * 4 * 32 * sizeof(int) * 4);
+    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PIPE>;
     if (hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(kern), lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(tiles, splits), dim3(kThreads), lds, ctx->stream, a);
     return hipGetLastError();
@@ -979,9 +1218,22 @@ static hipError_t launch_bn(adapt_ctx *ctx, const ContractArgs &a, int splits, T
     return launch_variant<OP, LIMBS, AMODE, WMODE, BM, 128, 2, 2, BKT>(ctx, a, splits);
 }
 
+// The tiles of the double-buffered pipeline: two limbs (both operands int16, one split for both).
+template <int OP, int AMODE, int WMODE, int LM>
+static hipError_t launch_pipe2(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
+{
+    if (t.pipe == 2) {
+        if (t.bm == 128) return launch_es<OP, 2, AMODE, WMODE, LM, LM, 128, 64, 2, 2, 64, 2>(ctx, a, splits);
+        return launch_es<OP, 2, AMODE, WMODE, LM, LM, 64, 128, 2, 2, 64, 2>(ctx, a, splits);
+    }
+    return launch_es<OP, 2, AMODE, WMODE, LM, LM, 128, 128, 2, 2, 64, 1>(ctx, a, splits);
+}
+
 template <int OP, int LIMBS, int AMODE, int WMODE>
 static hipError_t launch_tile(adapt_ctx *ctx, const ContractArgs &a, int splits, TileShape t)
 {
+    if constexpr (LIMBS == 2 && AMODE != LOAD_SCALAR && WMODE != LOAD_SCALAR && OP != OP_GEMM && OP != OP_WGRAD)
+        if (t.pipe) return a.balanced ? launch_pipe2<OP, AMODE, WMODE, 3>(ctx, a, splits, t) : launch_pipe2<OP, AMODE, WMODE, 2>(ctx, a, splits, t);
     if constexpr (AMODE == LOAD_SCALAR) {
         return launch_variant<OP, LIMBS, AMODE, WMODE, 128, 64, 2, 2, 64>(ctx, a, splits);
     } else if constexpr (OP == OP_GEMM) {
@@ -1030,6 +1282,7 @@ template <int OP>
 static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
 {
     TileShape t;
+    t.pipe = 0;
     const bool scalar = a.act_load == LOAD_SCALAR || a.wgt_load == LOAD_SCALAR;
     if (a.N <= 64 || scalar) t.bn = 64;
     else if (OP != OP_GEMM && limbs == 1 && (a.N % 192 == 0 || (a.N > 128 && a.N <= 192))) t.bn = 192;   // 3 x 96 accumulators do not fit
@@ -1071,6 +1324,22 @@ static TileShape pick_tile(const ContractArgs &a, int limbs, int num_cu)
         // register file, see min_waves_per_simd), the 128x128 tile one; 64x64 was measured faster at every size
         // (conv 128->128 at 16x16, batch 256: 67 against 82 us; at 32x32: 250 against 325 us).
         t.bm = t.bn = 64;
+        // Both operands int16, long rows of tiles: the double-buffered pipeline.  A stage of a 64 x 64 tile stores as many
+        // bytes to LDS per MFMA clock as the LDS can take (about 64 B/clk per CU).  128 x 128 tiles store half of that and
+        // run one block per CU, which leaves the epilogue (Philox, 64-bit recombination) uncovered: they pay when the
+        // reduction is long.  128 x 64 / 64 x 128 tiles (three quarters) run two blocks per CU, one block's epilogue
+        // behind the other's MFMAs.
+        if (OP != OP_GEMM && a.act_es == 2 && a.wgt_es == 2 && a.K % 64 == 0) {
+            auto tiles_of = [&](int bm, int bn) { return (long long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+            auto waste_of = [&](int bm, int bn) { return (double)tiles_of(bm, bn) * bm * bn / ((double)a.M * (double)a.N); };
+            if (a.K >= 1536 && tiles_of(128, 128) >= num_cu && waste_of(128, 128) <= 1.15) {
+                t.bm = t.bn = 128; t.bkt = 64; t.pipe = 1;
+            } else if (tiles_of(128, 64) >= 2 * num_cu && waste_of(128, 64) <= 1.15) {
+                t.bm = 128; t.bn = 64; t.bkt = 64; t.pipe = 2;
+            } else if (tiles_of(64, 128) >= 2 * num_cu && waste_of(64, 128) <= 1.15) {
+                t.bm = 64; t.bn = 128; t.bkt = 64; t.pipe = 2;
+            }
+        }
     }
     return t;
 }
@@ -1146,6 +1415,16 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
         a.stream = ep.rng.stream;
     }
     a.balanced = fa.wl <= 15 && fb.wl <= 15;
+    a.fast = 0;
+    if (!ep.raw && limbs == 2 && a.balanced) {
+        // bound of |sum|: K 2^(wl_a-1) 2^(wl_b-1)
+        const long long kb = a.k_bound ? a.k_bound : a.K;
+        const int mag = fa.wl + fb.wl - 2;
+        int kbits = 0;
+        while ((1ll << kbits) < kb) ++kbits;
+        if (fa.wl > 8 && fb.wl > 8) a.fast = a.shift >= 1 && a.shift <= 16 && kbits + mag <= 38;      // (u, low byte) form
+        else a.fast = a.shift >= 1 && kbits + mag <= 30;                                                // fits 32 bits
+    }
     p.limbs = limbs;
     p.bits = bits;
     p.empty = a.M == 0 || a.N == 0;
@@ -1240,6 +1519,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     p.kern.ldc = a.N;
     p.kern.slab_bytes = (long long)slab;
     p.kern.out_mode = bits == 32 ? OUT_RAW32 : OUT_RAW64;
+    p.kern.fast = 0;                                  // exact partial sums go to the slabs
     p.fin = a;
     p.fin.out_mode = final_mode;
     p.fin.slab_bytes = (long long)slab;
@@ -1366,8 +1646,9 @@ static int fill_dgrad(ContractArgs &a, const adapt_conv_desc &d, const void *dy,
     a.act_es = storage_bytes(fdy); a.wgt_es = storage_bytes(fw);
     a.act_bytes = (uint32_t)((long long)d.n * a.p * a.q * d.k * a.act_es);
     a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);
-    a.act_load = d.k % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
-    a.wgt_load = d.c % 16 == 0 ? LOAD_ROWS : LOAD_SCALAR;     // rows (c) are contiguous in w[kout][r][s][c]
+    // the vector path of dy keeps one validity bit per filter tap and row: at most 32 taps
+    a.act_load = (d.k % 16 == 0 && d.r * d.s <= 32) ? LOAD_VEC : LOAD_SCALAR;
+    a.wgt_load = (d.c % 16 == 0 && d.r * d.s <= 32) ? LOAD_ROWS : LOAD_SCALAR;     // rows (c) are contiguous in w[kout][r][s][c]
     a.ldc = d.c;
     a.uniform_tap = d.k % 64 == 0;
     return ADAPT_OK;
@@ -1396,7 +1677,8 @@ static int fill_fwd(ContractArgs &a, const adapt_conv_desc &d, const void *x, ad
     a.act_es = storage_bytes(fx); a.wgt_es = storage_bytes(fw);
     a.act_bytes = (uint32_t)((long long)d.n * d.h * d.w * d.c * a.act_es);
     a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);
-    a.act_load = d.c % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
+    // the vector path of x keeps one validity bit per filter tap and row: at most 32 taps
+    a.act_load = (d.c % 16 == 0 && d.r * d.s <= 32) ? LOAD_VEC : LOAD_SCALAR;
     a.wgt_load = a.K % 16 == 0 ? LOAD_VEC : LOAD_SCALAR;
     a.ldc = d.k;
     a.uniform_tap = d.c % 64 == 0;

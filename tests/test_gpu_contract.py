@@ -152,6 +152,8 @@ CONV_CASES = [
     (2, 5, 6, 20, 12, 3, 3, 1, 0),        # C multiple of 4 only
     (1, 4, 4, 7, 5, 2, 2, 1, 1),          # nothing aligned
     (9, 1, 1, 256, 100, 1, 1, 1, 0),      # fully connected layer
+    (2, 12, 12, 16, 32, 7, 7, 2, 3),      # 49 filter taps: beyond the per-row tap masks of the vector path
+    (2, 9, 9, 32, 32, 5, 5, 2, 2),        # 25 taps, stride 2
 ]
 
 
