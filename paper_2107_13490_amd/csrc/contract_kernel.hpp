@@ -626,22 +626,29 @@ __device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m
     if (a.rmode != ADAPT_SR) {
 #pragma unroll
         for (int i = 0; i < RUN / 2; ++i) rw[i] = 0x80008000u;
-    } else if ((idx0 & 7) == 0) {
+    } else if ((a.N & 7) == 0) {
+        // rows are whole groups of 8 outputs (n0 is a multiple of 16): two Philox blocks cover the run
 #pragma unroll
         for (int h = 0; h < RUN / 8; ++h) {
             const u32x4 b = rounding_block(a.seed, a.stream, (idx0 >> 3) + h);
             rw[4 * h] = b.x; rw[4 * h + 1] = b.y; rw[4 * h + 2] = b.z; rw[4 * h + 3] = b.w;
         }
     } else {
-        // rows that do not start on a multiple of 8 (N not a multiple of 8): one Philox block per output,
-        // drawn only for the outputs that exist (a 3-channel data gradient has 3 of the 16)
+        // Any row length: the run starts at 16-bit lane idx0 % 8 of block idx0 / 8 and touches at most three blocks.
+        // Their 24 lanes are drawn and shifted down by the lane's own offset (a select by word, then by half word).
+        uint32_t w[13];
 #pragma unroll
-        for (int i = 0; i < RUN / 2; ++i) {
-            rw[i] = 0;
-            if (2 * i < cnt)
-                rw[i] = rounding_bits_of(a.seed, a.stream, idx0 + 2 * i, ADAPT_SR) |
-                        (rounding_bits_of(a.seed, a.stream, idx0 + 2 * i + 1, ADAPT_SR) << 16);
+        for (int h = 0; h < 3; ++h) {
+            const u32x4 b = rounding_block(a.seed, a.stream, (idx0 >> 3) + h);
+            w[4 * h] = b.x; w[4 * h + 1] = b.y; w[4 * h + 2] = b.z; w[4 * h + 3] = b.w;
         }
+        w[12] = 0;
+        const uint32_t first = (uint32_t)idx0 & 7u, wo = first >> 1;
+        uint32_t t[RUN / 2 + 1];
+#pragma unroll
+        for (int k = 0; k <= RUN / 2; ++k) t[k] = wo == 0 ? w[k] : wo == 1 ? w[k + 1] : wo == 2 ? w[k + 2] : w[k + 3];
+#pragma unroll
+        for (int k = 0; k < RUN / 2; ++k) rw[k] = (first & 1u) ? __builtin_amdgcn_alignbit(t[k + 1], t[k], 16) : t[k];
     }
     int q[RUN];
     if (FORM == FORM_PAIR) {
