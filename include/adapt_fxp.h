@@ -423,8 +423,9 @@ typedef struct {
 } adapt_switch_params;
 
 /* Bytes of device workspace the chain needs (activations, gradients, codes of weights and
- * gradients at int16 storage so that word lengths may change, two accumulator buffers, and lb_upr
- * gradient tensors per layer for the lookback windows; lb_upr = 0 without precision switching);
+ * gradients at int16 storage so that word lengths may change, two accumulator buffers, and
+ * lb_upr + 1 gradient tensors per layer for the lookback windows, into one of which the backward
+ * pass writes; lb_upr = 0 without precision switching);
  * 0 if the description is invalid (count outside 1..64, unequal batch sizes, shapes that do not
  * chain, pooling of an odd-sized map, lb_upr outside 0..64). */
 size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr);
@@ -471,18 +472,23 @@ int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogits_fl, adap
  *                e(dy_last) = dlogits_fl, e(g_l) = e(dy_l) + FL(a_{l-1}) - shift_w(l),
  *                e(dy_{l-1}) = e(dy_l) + FL(W^_l) - shift_a(l);
  *              ds = adapt_gradient_diversity of the most recent min(len, lb^l) entries with
- *              fl_k = e_k - min e (ADAPT_EUNSUPPORTED if they differ by more than 31);
+ *              fl_k = e_k - min e.  The aligned sum of the window is kept in 32-bit integers: while
+ *              sum_k 2^(wl_k - 1 + max e - e_k) reaches 2^31 the oldest of these entries is left out
+ *              (the newest always stays); `used` reports how many entered;
  *              lb^l = adapt_lookback_next, r^l = adapt_resolution_next;
  *              if len >= lb^l: PushDown = the KL search (batched over the layers that switch) on the master weights with
  *              il = WL - FL, candidates max(wl_lo, il)..wl_hi, r^l bins, stream slot 6, its
  *              selection limited to the current WL; PushUp = adapt_pushup_suggest with wl_cap 16;
  *              the layer takes the new format and its window is emptied.
- * The call synchronises the stream (it reads shifts, diversities and selections back).  The update
+ * The call synchronises the stream once for the diversities and, when a layer switches, once more
+ * for the selections.  A call that returns an error has changed nothing (strategy, loss history,
+ * windows, lookbacks, resolutions and formats are as before) and may be repeated; a second call
+ * after the same backward pass is ADAPT_EINVAL.  The update
  * that follows quantizes the weights in the new formats; a forward pass is needed before the next
  * backward pass.  report: HOST array of `count` entries or NULL; strategy: HOST or NULL. */
 typedef struct {
     double ds;
-    int32_t wl, fl, lb, res, switched, wl_min, fl_min, reserved;
+    int32_t wl, fl, lb, res, switched, wl_min, fl_min, used;
 } adapt_switch_report;
 int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng rng,
                                adapt_switch_report *report, int *strategy);

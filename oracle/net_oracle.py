@@ -267,12 +267,16 @@ def precision_switch(st: SwitchState, fmts, weights, bwd, dlogits_fl: int, loss:
         if len(win) > p["lb_upr"]:
             win.pop(0)
         use = win[-min(len(win), st.lb[l]):]
+        # The element-wise sum of the window, aligned to its finest grid, is held in 32-bit integers: while the bound
+        # sum_k 2^(wl_k - 1 + e_max - e_k) reaches 2^31 the oldest entry is left out (the newest always stays).
+        while len(use) > 1 and sum(2 ** (w - 1 + max(e for _, _, e in use) - e) for _, w, e in use) >= 2 ** 31:
+            use = use[1:]
         e_min = min(e for _, _, e in use)
         gd = po.gradient_diversity_np([c for c, _, _ in use], [e - e_min for _, _, e in use])
         ds = gd["ds"]
         st.lb[l] = po.adapt_lookback(st.lb[l], ds, p["lb_lwr"], p["lb_upr"], p["gamma"])
         st.res[l] = po.adapt_resolution(st.res[l], st.lb[l], p["lb_lwr"], p["lb_upr"], p["r_lwr"], p["r_upr"])
-        row = {"ds": ds, "lb": st.lb[l], "res": st.res[l], "switched": False, "wl_min": 0, "fl_min": 0}
+        row = {"ds": ds, "lb": st.lb[l], "res": st.res[l], "switched": False, "wl_min": 0, "fl_min": 0, "used": len(use)}
         if len(win) >= st.lb[l]:
             il = wl - fl
             lo = max(p["wl_lo"], il)

@@ -113,7 +113,7 @@ class SwitchParams(C.Structure):
 
 class SwitchReport(C.Structure):
     _fields_ = [("ds", C.c_double), ("wl", C.c_int32), ("fl", C.c_int32), ("lb", C.c_int32), ("res", C.c_int32),
-                ("switched", C.c_int32), ("wl_min", C.c_int32), ("fl_min", C.c_int32), ("reserved", C.c_int32)]
+                ("switched", C.c_int32), ("wl_min", C.c_int32), ("fl_min", C.c_int32), ("used", C.c_int32)]
 
 
 class PushupResult(C.Structure):

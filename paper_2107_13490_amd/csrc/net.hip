@@ -22,6 +22,7 @@
 
 #include "common.hpp"
 #include "context.hpp"
+#include "grad_window.hpp"
 
 namespace adapt {
 
@@ -450,6 +451,7 @@ extern "C" int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, c
 namespace {
 
 constexpr int kMaxLayers = 64;
+constexpr int kRingMax = 65;           // ring slots per layer: the longest window and the gradient being made
 constexpr size_t kStatBytes = 64;      // per layer: the adapt_net_stats record
 
 struct NetLayer {
@@ -460,13 +462,18 @@ struct NetLayer {
     size_t n_y, n_a, n_in, n_w;
     size_t off_y, off_a, off_dy, off_da, off_qw, off_g, off_stat, off_ring, off_ds, off_kld, off_sel;
     // state of the last backward pass
-    int g_wl;                 // word length of the gradient codes in off_g
+    int g_wl;                 // word length of the gradient codes
+    int g_slot;               // with precision switching: the ring slot that holds them (never one of the window's)
     int fl_in, fl_w;          // FL of the layer's input activations and of its weight codes
     // precision switch (Alg. 2)
     int lb, res;
     std::vector<int> win;     // ring slots of the window, oldest first
-    int slot_wl[64];
-    long long slot_exp[64];
+    int slot_wl[kRingMax];
+    long long slot_exp[kRingMax];
+    size_t slot_bytes;
+
+    // where the gradient codes of the last backward pass lie in the workspace
+    size_t g_off() const { return g_slot >= 0 ? off_ring + (size_t)g_slot * slot_bytes : off_g; }
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -475,7 +482,7 @@ constexpr size_t kKldStride = 128;      // bytes per layer for the KL values of 
 
 // Lays the workspace out; returns 0 for an invalid network.
 size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vector<NetLayer> &L, size_t &off_in,
-                size_t &off_accx, size_t &off_accw, size_t &off_stats, size_t &off_sel_group, size_t &off_kld_group)
+                size_t &off_accx, size_t &off_accw, size_t &off_stats, size_t &off_sel_group, size_t &off_kld_group, size_t &off_win)
 {
     if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64) return 0;
     L.assign(count, NetLayer());
@@ -488,6 +495,7 @@ size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vecto
     const size_t off_ds = take((size_t)count * 16), off_sel = take((size_t)count * 8), off_kld = take((size_t)count * kKldStride);
     off_sel_group = off_sel;       // the batched searches of a precision switch write their results densely, in group order
     off_kld_group = off_kld;
+    off_win = take((size_t)count * sizeof(GradWindow));
     for (int l = 0; l < count; ++l) {
         const adapt_conv_desc &c = descs[l].conv;
         if (c.n != n || c.h < 1 || c.w < 1 || c.c < 1 || c.k < 1 || c.r < 1 || c.s < 1 || c.stride < 1 || c.pad < 0) return 0;
@@ -511,12 +519,16 @@ size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vecto
         y.off_da = take(2 * y.n_a);
         if (!(y.d.pool || y.d.relu)) y.off_dy = y.off_da;
         y.off_qw = take(2 * y.n_w);
-        y.off_g = take(2 * y.n_w);
+        // The weight gradient is written straight into a slot of the lookback ring (one slot more than the longest
+        // window, so a free one always exists); without precision switching it has a buffer of its own.
+        y.off_g = lb_upr ? 0 : take(2 * y.n_w);
+        y.g_slot = -1;
+        y.slot_bytes = align_up(2 * y.n_w);
         y.off_stat = off_stats + (size_t)l * kStatBytes;
         y.off_ds = off_ds + (size_t)l * 16;
         y.off_sel = off_sel + (size_t)l * 8;
         y.off_kld = off_kld + (size_t)l * kKldStride;
-        y.off_ring = lb_upr ? take((size_t)lb_upr * align_up(2 * y.n_w)) : 0;
+        y.off_ring = lb_upr ? take((size_t)(lb_upr + 1) * y.slot_bytes) : 0;
         y.g_wl = 0;
         if (l > 0) max_in = std::max(max_in, y.n_in);
         max_w = std::max(max_w, y.n_w);
@@ -533,14 +545,18 @@ struct adapt_net {
     adapt_ctx *ctx;
     std::vector<NetLayer> L;
     char *ws;
-    size_t off_in, off_accx, off_accw, off_stats, off_sel_group, off_kld_group, bytes;
+    size_t off_in, off_accx, off_accw, off_stats, off_sel_group, off_kld_group, off_win, bytes;
     bool forward_done, backward_done;
     int dlogits_fl;
     // precision switch
     bool has_switch;
+    bool switch_due;          // a backward pass whose gradients have not joined the windows yet
     adapt_switch_params sp;
     int strategy;
     std::vector<double> losses;
+    void *pinned;             // host-pinned, device-visible: count ChainLayerIn records, then count ChainLayerOut
+    ChainLayerIn *chain_in;
+    ChainLayerOut *chain_out;
 };
 
 namespace {
@@ -574,8 +590,8 @@ static bool switch_params_ok(const adapt_switch_params &p)
 extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr)
 {
     std::vector<NetLayer> L;
-    size_t a, b, c, d, e, f;
-    return plan_net(layers, count, lb_upr, L, a, b, c, d, e, f);
+    size_t a, b, c, d, e, f, g;
+    return plan_net(layers, count, lb_upr, L, a, b, c, d, e, f, g);
 }
 
 extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
@@ -590,11 +606,25 @@ extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, 
     net->forward_done = net->backward_done = false;
     net->dlogits_fl = 0;
     net->has_switch = sp != nullptr;
+    net->switch_due = false;
     if (sp) net->sp = *sp;
     net->strategy = sp ? sp->strategy_init : ADAPT_ST_MIN;
+    net->pinned = nullptr;
+    net->chain_in = nullptr;
+    net->chain_out = nullptr;
     net->bytes = plan_net(layers, count, sp ? sp->lb_upr : 0, net->L, net->off_in, net->off_accx, net->off_accw, net->off_stats,
-                          net->off_sel_group, net->off_kld_group);
+                          net->off_sel_group, net->off_kld_group, net->off_win);
     bool ok = net->bytes != 0 && net->bytes <= workspace_bytes;
+    if (ok && sp) {
+        const size_t in_bytes = align_up((size_t)count * sizeof(ChainLayerIn));
+        const hipError_t e = hipHostMalloc(&net->pinned, in_bytes + (size_t)count * sizeof(ChainLayerOut), hipHostMallocDefault);
+        if (e != hipSuccess) {
+            delete net;
+            return hip_status(ctx, e);
+        }
+        net->chain_in = static_cast<ChainLayerIn *>(net->pinned);
+        net->chain_out = reinterpret_cast<ChainLayerOut *>(static_cast<char *>(net->pinned) + in_bytes);
+    }
     for (int l = 0; ok && l < count; ++l) {
         net->L[l].w = weights[l];
         net->L[l].lb = sp ? sp->lb_init : 0;
@@ -603,6 +633,7 @@ extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, 
     }
     if (!ok) {
         const int s = (net->bytes != 0 && net->bytes > workspace_bytes) ? ADAPT_EWORKSPACE : ADAPT_EINVAL;
+        if (net->pinned) (void)hipHostFree(net->pinned);
         delete net;
         return s;
     }
@@ -612,6 +643,11 @@ extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, 
 
 extern "C" int adapt_net_destroy(adapt_net *net)
 {
+    if (net && net->pinned) {
+        // the device may still be reading or writing the pinned records of the last precision switch
+        (void)hipStreamSynchronize(net->ctx->stream);
+        (void)hipHostFree(net->pinned);
+    }
     delete net;
     return ADAPT_OK;
 }
@@ -638,7 +674,7 @@ extern "C" int adapt_net_tensor(const adapt_net *net, int layer, int which, size
     case ADAPT_NT_DY: *offset = y.off_dy; *count = y.n_y; *elem_bytes = es; break;
     case ADAPT_NT_DA: *offset = y.off_da; *count = y.n_a; *elem_bytes = es; break;
     case ADAPT_NT_QW: *offset = y.off_qw; *count = y.n_w; *elem_bytes = es; break;
-    case ADAPT_NT_G: *offset = y.off_g; *count = y.n_w; *elem_bytes = y.g_wl ? (y.g_wl <= 8 ? 1 : 2) : es; break;
+    case ADAPT_NT_G: *offset = y.g_off(); *count = y.n_w; *elem_bytes = y.g_wl ? (y.g_wl <= 8 ? 1 : 2) : es; break;
     case ADAPT_NT_STATS: *offset = y.off_stat; *count = 1; *elem_bytes = (int)sizeof(adapt_net_stats); break;
     default: return ADAPT_EINVAL;
     }
@@ -714,6 +750,12 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
         y.g_wl = y.fmt.wl;
         y.fl_in = fin.fl;
         y.fl_w = y.fmt.fl;
+        if (net->has_switch) {                                    // a ring slot outside the window
+            bool used[kRingMax] = {};
+            for (int s2 : y.win) used[s2] = true;
+            y.g_slot = 0;
+            while (used[y.g_slot]) ++y.g_slot;
+        }
         char *accw = net->ws + net->off_accw, *accx = net->ws + net->off_accx;
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
         if (l > 0) {
@@ -722,7 +764,7 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
             if (int s = adapt_conv_wgrad(ctx, c, dy, fdy, a_prev, fin, accw, ex)) return s;
         }
         const int bits_w = adapt_acc_bits((int64_t)c.n * y.p * y.q, fdy, fin);
-        if (int s = adapt_requantize_fit(ctx, accw, bits_w, y.n_w, y.fmt.wl, slot_rng(rng, l, 2), net->ws + y.off_g, &st->shift_w,
+        if (int s = adapt_requantize_fit(ctx, accw, bits_w, y.n_w, y.fmt.wl, slot_rng(rng, l, 2), net->ws + y.g_off(), &st->shift_w,
                                          &st->g_sumsq))
             return s;
         if (l > 0) {
@@ -733,120 +775,90 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
         }
     }
     net->backward_done = true;
+    net->switch_due = net->has_switch;
     return ADAPT_OK;
 }
 
 extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng rng, adapt_switch_report *report, int *strategy)
 {
-    if (!net || !net->has_switch || !net->backward_done || !rng_ok(rng) || !(loss == loss)) return ADAPT_EINVAL;
+    if (!net || !net->has_switch || !net->backward_done || !net->switch_due || !rng_ok(rng) || !(loss == loss)) return ADAPT_EINVAL;
     adapt_ctx *ctx = net->ctx;
     const adapt_switch_params &sp = net->sp;
     const int count = (int)net->L.size();
+    // Nothing of the network's state changes before the last step that can fail has passed: a call that returns an
+    // error leaves strategy, loss history, windows, lookbacks, resolutions and formats as they were, and may be repeated.
+    for (const NetLayer &y : net->L)
+        if (y.fmt.wl - y.fmt.fl < 1 || y.g_slot < 0) return ADAPT_EINVAL;
+
     // strategy from the loss history (the current batch excluded)
+    int strategy_new = net->strategy;
     if (!net->losses.empty()) {
         long long lb_sum = 0;
         for (const NetLayer &y : net->L) lb_sum += y.lb;
         const size_t k = std::min<size_t>(net->losses.size(), (size_t)std::ceil((double)lb_sum / (double)count));
         double acc = 0.0;
         for (size_t i = net->losses.size() - k; i < net->losses.size(); ++i) acc += net->losses[i];
-        net->strategy = adapt_strategy_next(net->strategy, acc / (double)k, loss);
+        strategy_new = adapt_strategy_next(net->strategy, acc / (double)k, loss);
     }
-    net->losses.push_back(loss);
-    if (strategy) *strategy = net->strategy;
 
-    // the fitting shifts of this backward pass give every gradient tensor its exponent
-    std::vector<adapt_net_stats> st(count);
-    hipError_t e = hipMemcpyAsync(st.data(), net->ws + net->off_stats, (size_t)count * kStatBytes, hipMemcpyDeviceToHost, ctx->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    if (e != hipSuccess) return hip_status(ctx, e);
-    long long e_dy = net->dlogits_fl;
-    std::vector<long long> g_exp(count);
+    // Windows as they will be once this batch's gradients have joined them, and their diversities.  The fitting shifts
+    // of the backward pass give every gradient tensor its exponent,
+    //   e(g_l) = dlogits_fl + sum_{j>l} FL(W^_j) + FL(a_{l-1}) - shift_w(l) - sum_{j>l} shift_a(j);
+    // the shifts are on the device, so the host hands over the other terms and the device finishes the sum.
+    std::vector<std::vector<int>> win_new(count);
+    size_t n_w[kMaxLayers];
+    long long fl_above = net->dlogits_fl;
     for (int l = count - 1; l >= 0; --l) {
         const NetLayer &y = net->L[l];
-        g_exp[l] = e_dy + y.fl_in - st[l].shift_w;
-        if (l > 0) e_dy = e_dy + y.fl_w - st[l].shift_a;
-    }
-
-    // windows and diversities
-    for (int l = 0; l < count; ++l) {
-        NetLayer &y = net->L[l];
-        int slot;
-        if ((int)y.win.size() == sp.lb_upr) {                 // full: the oldest entry makes room
-            slot = y.win.front();
-            y.win.erase(y.win.begin());
-        } else {
-            bool used[64] = {};
-            for (int s2 : y.win) used[s2] = true;
-            slot = 0;
-            while (used[slot]) ++slot;
-        }
-        const size_t slot_bytes = align_up(2 * y.n_w);
-        e = hipMemcpyAsync(net->ws + y.off_ring + (size_t)slot * slot_bytes, net->ws + y.off_g,
-                           y.n_w * (size_t)(y.g_wl <= 8 ? 1 : 2), hipMemcpyDeviceToDevice, ctx->stream);
-        if (e != hipSuccess) return hip_status(ctx, e);
-        y.win.push_back(slot);
-        y.slot_wl[slot] = y.g_wl;
-        y.slot_exp[slot] = g_exp[l];
-        const int use = std::min<int>((int)y.win.size(), y.lb);
-        adapt_grad_item items[64];
-        long long e_min = 0;
+        std::vector<int> &w = win_new[l];
+        w.assign(y.win.begin() + ((int)y.win.size() == sp.lb_upr ? 1 : 0), y.win.end());      // full: the oldest entry makes room
+        w.push_back(y.g_slot);
+        const int use = std::min<int>((int)w.size(), y.lb);
+        ChainLayerIn &c = net->chain_in[l];
+        c.count = use;
         for (int i = 0; i < use; ++i) {
-            const long long ex = y.slot_exp[y.win[y.win.size() - use + i]];
-            e_min = i == 0 ? ex : std::min(e_min, ex);
+            const int s2 = w[w.size() - use + i];
+            c.g[i] = net->ws + y.off_ring + (size_t)s2 * y.slot_bytes;
+            c.wl[i] = (uint8_t)(i == use - 1 ? y.g_wl : y.slot_wl[s2]);
+            c.exp[i] = i == use - 1 ? fl_above + y.fl_in : y.slot_exp[s2];
         }
-        for (int i = 0; i < use; ++i) {
-            const int s2 = y.win[y.win.size() - use + i];
-            if (y.slot_exp[s2] - e_min > 31) return ADAPT_EUNSUPPORTED;      // scales too far apart for one exact sum
-            items[i].g = net->ws + y.off_ring + (size_t)s2 * slot_bytes;
-            items[i].wl = y.slot_wl[s2];
-            items[i].fl = (int32_t)(y.slot_exp[s2] - e_min);
-        }
-        if (int s = adapt_gradient_diversity(ctx, items, use, y.n_w, nullptr, reinterpret_cast<double *>(net->ws + y.off_ds)))
-            return s;
+        n_w[l] = y.n_w;
+        fl_above += y.fl_w;
     }
-    std::vector<double> ds(2 * (size_t)count);
-    e = hipMemcpyAsync(ds.data(), net->ws + net->L[0].off_ds, (size_t)count * 16, hipMemcpyDeviceToHost, ctx->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (int s = gradient_diversity_chain(ctx, net->chain_in, count, n_w, reinterpret_cast<const adapt_net_stats *>(net->ws + net->off_stats),
+                                         reinterpret_cast<GradWindow *>(net->ws + net->off_win), net->chain_out))
+        return s;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return hip_status(ctx, e);
+    const ChainLayerOut *out = net->chain_out;
 
-    int group_base = 0;
-    std::vector<int> group_slot(count, 0);
     // lookback, resolution; PushDown for the layers whose window is long enough: one batched search per group of
     // layers that share the lowest candidate word length (the batched call takes one candidate range)
-    std::vector<int> lo_of(count, 0);
-    bool any = false;
+    std::vector<int> lb_new(count), res_new(count), lo_of(count, 0), group_slot(count, 0);
+    std::vector<char> switches(count, 0);
     for (int l = 0; l < count; ++l) {
-        NetLayer &y = net->L[l];
-        y.lb = adapt_lookback_next(y.lb, ds[2 * l], sp.lb_lwr, sp.lb_upr, sp.gamma);
-        y.res = adapt_resolution_next(y.res, y.lb, sp.lb_lwr, sp.lb_upr, sp.r_lwr, sp.r_upr);
-        if (report) {
-            report[l] = adapt_switch_report{};
-            report[l].ds = ds[2 * l];
-            report[l].lb = y.lb;
-            report[l].res = y.res;
-        }
-        if ((int)y.win.size() < y.lb) continue;
-        const int il = y.fmt.wl - y.fmt.fl;
-        if (il < 1) return ADAPT_EINVAL;
-        lo_of[l] = std::max(sp.wl_lo, il);
+        const NetLayer &y = net->L[l];
+        lb_new[l] = adapt_lookback_next(y.lb, out[l].ds, sp.lb_lwr, sp.lb_upr, sp.gamma);
+        res_new[l] = adapt_resolution_next(y.res, lb_new[l], sp.lb_lwr, sp.lb_upr, sp.r_lwr, sp.r_upr);
+        switches[l] = (int)win_new[l].size() >= lb_new[l];
+        if (switches[l]) lo_of[l] = std::max(sp.wl_lo, y.fmt.wl - y.fmt.fl);
     }
+    int group_base = 0;
     for (int lo = 2; lo <= sp.wl_hi; ++lo) {
         adapt_kld_item items[kMaxLayers];
         int members[kMaxLayers], m = 0;
         for (int l = 0; l < count; ++l) {
             const NetLayer &y = net->L[l];
-            if (lo_of[l] != lo || (int)y.win.size() < y.lb) continue;
+            if (!switches[l] || lo_of[l] != lo) continue;
             items[m].w = y.w;
             items[m].n = y.n_w;
             items[m].il = y.fmt.wl - y.fmt.fl;
-            items[m].bins = y.res;
+            items[m].bins = res_new[l];
             items[m].stream = rng.stream + (uint64_t)(8 * l + 6);
             members[m++] = l;
         }
         if (m == 0) continue;
-        // results of the group land in a contiguous scratch of the workspace and are copied to the layers' slots
-        // by the host after the read-back below: the group writes kld[t*ncand] and sel[2t] for its t-th member
-        const int ncand = sp.wl_hi - lo + 1;
+        // the t-th member of a group writes kld[16 * (group_base + t)...] and sel[2 * (group_base + t)]
         double *gk = reinterpret_cast<double *>(net->ws + net->off_kld_group);
         int32_t *gs = reinterpret_cast<int32_t *>(net->ws + net->off_sel_group);
         if (int s = adapt_kld_precision_search_batched(ctx, items, m, lo, sp.wl_hi, sp.eps, -1.0, rng.mode, rng.seed,
@@ -854,30 +866,59 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
             return s;
         for (int t = 0; t < m; ++t) group_slot[members[t]] = group_base + t;
         group_base += m;
-        (void)ncand;
-        any = true;
     }
     std::vector<int32_t> sel(2 * (size_t)count, 0);
-    if (any) {
-        e = hipMemcpyAsync(sel.data(), net->ws + net->off_sel_group, (size_t)count * 8, hipMemcpyDeviceToHost, ctx->stream);
+    if (group_base > 0) {
+        e = hipMemcpyAsync(sel.data(), net->ws + net->off_sel_group, (size_t)group_base * 8, hipMemcpyDeviceToHost, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e != hipSuccess) return hip_status(ctx, e);
     }
+    std::vector<adapt_fmt> fmt_new(count);
+    std::vector<int> wl_min_of(count, 0), fl_min_of(count, 0);
+    for (int l = 0; l < count; ++l) {
+        const NetLayer &y = net->L[l];
+        fmt_new[l] = y.fmt;
+        if (!switches[l]) continue;
+        const int il = y.fmt.wl - y.fmt.fl;
+        int wl_min = y.fmt.wl;
+        if (lo_of[l] <= sp.wl_hi) wl_min = std::min<int>(sel[2 * (size_t)group_slot[l]], y.fmt.wl);
+        const int fl_min = wl_min - il;
+        adapt_pushup_result r;
+        if (int s = adapt_pushup_suggest(out[l].ds, wl_min, fl_min, strategy_new, sp.buff, 16, &r)) return s;
+        fmt_new[l] = adapt_fmt{r.wl, r.fl};
+        wl_min_of[l] = wl_min;
+        fl_min_of[l] = fl_min;
+    }
+
+    // commit
+    net->strategy = strategy_new;
+    net->losses.push_back(loss);
+    net->switch_due = false;
+    if (strategy) *strategy = strategy_new;
     for (int l = 0; l < count; ++l) {
         NetLayer &y = net->L[l];
-        if ((int)y.win.size() >= y.lb) {
-            const int il = y.fmt.wl - y.fmt.fl;
-            int wl_min = y.fmt.wl;
-            if (lo_of[l] <= sp.wl_hi) wl_min = std::min<int>(sel[2 * (size_t)group_slot[l]], y.fmt.wl);
-            const int fl_min = wl_min - il;
-            adapt_pushup_result r;
-            if (int s = adapt_pushup_suggest(ds[2 * l], wl_min, fl_min, net->strategy, sp.buff, 16, &r)) return s;
-            y.fmt = adapt_fmt{r.wl, r.fl};
+        y.slot_wl[y.g_slot] = y.g_wl;
+        y.slot_exp[y.g_slot] = out[l].exp_new;
+        y.win.swap(win_new[l]);
+        y.lb = lb_new[l];
+        y.res = res_new[l];
+        if (switches[l]) {
+            y.fmt = fmt_new[l];
             y.win.clear();
             net->forward_done = false;                   // activations of the old format no longer match
-            if (report) { report[l].switched = 1; report[l].wl_min = wl_min; report[l].fl_min = fl_min; }
         }
-        if (report) { report[l].wl = y.fmt.wl; report[l].fl = y.fmt.fl; }
+        if (report) {
+            report[l] = adapt_switch_report{};
+            report[l].ds = out[l].ds;
+            report[l].lb = y.lb;
+            report[l].res = y.res;
+            report[l].used = out[l].used;
+            report[l].switched = switches[l];
+            report[l].wl_min = wl_min_of[l];
+            report[l].fl_min = fl_min_of[l];
+            report[l].wl = y.fmt.wl;
+            report[l].fl = y.fmt.fl;
+        }
     }
     return ADAPT_OK;
 }
@@ -891,7 +932,7 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
         if (y.g_wl == 0) return ADAPT_EINVAL;                        // no backward pass yet
         const adapt_fmt fg = {y.g_wl, 0};                            // the gradient keeps the word length it was made with
-        if (int s = adapt_sgd_update_quantize(net->ctx, y.w, y.n_w, net->ws + y.off_g, fg, &st->g_sumsq, opt, y.fmt,
+        if (int s = adapt_sgd_update_quantize(net->ctx, y.w, y.n_w, net->ws + y.g_off(), fg, &st->g_sumsq, opt, y.fmt,
                                               slot_rng(rng, l, 3), net->ws + y.off_qw, &st->nnz, &st->range_lo))
             return s;
     }

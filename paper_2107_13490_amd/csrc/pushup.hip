@@ -15,22 +15,13 @@
 
 #include "common.hpp"
 #include "context.hpp"
+#include "grad_window.hpp"
 
 namespace adapt {
 
 constexpr int kGdThreads = 256;
 constexpr int kGdPerThread = 16;          // elements per thread
-constexpr int kGdMaxTensors = 64;
 constexpr int kGdFinalThreads = 1024;
-
-struct GradWindow {
-    const void *g[kGdMaxTensors];
-    uint8_t es[kGdMaxTensors];            // element bytes: 1 or 2
-    uint8_t shift[kGdMaxTensors];         // fl_max - fl_k
-    int8_t fl[kGdMaxTensors];
-    int count;
-    int fl_max;
-};
 
 typedef unsigned gd_v4u __attribute__((ext_vector_type(4)));
 
@@ -66,9 +57,13 @@ __device__ __forceinline__ void unpack16(const gd_v4u (&raw)[2], int es, int (&c
 
 // partial[col][block]: col k < count: sum of squares of tensor k; col count / count+1: sums of the
 // low / high 32-bit halves of (aligned element sum)^2
+// BYPTR: the window description lies in device memory (written by chain_prep_kernel) instead of the
+// kernel arguments
+template <bool BYPTR>
 __global__ void __launch_bounds__(kGdThreads)
-gd_partial_kernel(const GradWindow w, uint32_t n, uint64_t *partial)
+gd_partial_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, uint32_t n, uint64_t *partial)
 {
+    const GradWindow &w = BYPTR ? *wp : wv;
     __shared__ uint64_t wave_part[kGdThreads / kWave][kGdMaxTensors + 2];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const uint32_t e0 = (blockIdx.x * kGdThreads + threadIdx.x) * kGdPerThread;
@@ -138,9 +133,12 @@ gd_partial_kernel(const GradWindow w, uint32_t n, uint64_t *partial)
 }
 
 // One block: column sums (one wavefront per column at a time), then the norms and the ratio.
+template <bool BYPTR>
 __global__ void __launch_bounds__(kGdFinalThreads)
-gd_final_kernel(const GradWindow w, const uint64_t *__restrict__ partial, int nblocks, uint64_t *sums_out, double *out)
+gd_final_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const uint64_t *__restrict__ partial, int nblocks,
+                uint64_t *sums_out, double *out)
 {
+    const GradWindow &w = BYPTR ? *wp : wv;
     __shared__ uint64_t col_sum[kGdMaxTensors + 2];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     for (int col = wave; col < w.count + 2; col += kGdFinalThreads / kWave) {
@@ -170,6 +168,78 @@ gd_final_kernel(const GradWindow w, const uint64_t *__restrict__ partial, int nb
     const double ds = den > 0.0 ? num / den : (num > 0.0 ? (double)INFINITY : (double)NAN);
     out[0] = ds;
     out[1] = (ds > 0.0 && ds < (double)INFINITY) ? log(ds) : 1.0;
+}
+
+size_t ws_need_gradient_diversity(uint64_t n, int count);
+
+// One thread per layer of a chained step: the exponent of this batch's gradient follows from the
+// fitting shifts that the backward pass left in the statistics records, so the window can be laid
+// out without the host reading them first.  The aligned element sum of the diversity kernel is a
+// 32-bit integer: when the scales of the window lie too far apart for that, the oldest entries are
+// left out until the rest fits (at least the newest entry stays).
+__global__ void chain_prep_kernel(const ChainLayerIn *__restrict__ in, int nlayers, const adapt_net_stats *__restrict__ stats,
+                                  GradWindow *__restrict__ win, ChainLayerOut *__restrict__ out)
+{
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= nlayers) return;
+    const ChainLayerIn &c = in[l];
+    long long shifts = stats[l].shift_w;
+    for (int j = l + 1; j < nlayers; ++j) shifts += stats[j].shift_a;
+    const int count = c.count;
+    const long long e_new = c.exp[count - 1] - shifts;
+    auto exp_of = [&](int k) { return k == count - 1 ? e_new : c.exp[k]; };
+    int first = 0;
+    long long e_min = 0, e_max = 0;
+    for (;; ++first) {
+        e_min = e_max = exp_of(first);
+        for (int k = first + 1; k < count; ++k) {
+            const long long e = exp_of(k);
+            e_min = e < e_min ? e : e_min;
+            e_max = e > e_max ? e : e_max;
+        }
+        unsigned long long bound = 0;               // sum of 2^(wl - 1 + e_max - e_k), capped
+        for (int k = first; k < count; ++k) {
+            const long long b = (long long)c.wl[k] - 1 + e_max - exp_of(k);
+            bound += b >= 31 ? (1ull << 31) : (1ull << b);
+        }
+        if (bound < (1ull << 31) || first == count - 1) break;
+    }
+    GradWindow &w = win[l];
+    const int used = count - first;
+    for (int i = 0; i < used; ++i) {
+        const int k = first + i;
+        w.g[i] = c.g[k];
+        w.es[i] = (uint8_t)(c.wl[k] <= 8 ? 1 : 2);
+        w.shift[i] = (uint8_t)(e_max - exp_of(k));
+        w.fl[i] = (int8_t)(exp_of(k) - e_min);
+    }
+    w.count = used;
+    w.fl_max = (int)(e_max - e_min);
+    out[l].exp_new = e_new;
+    out[l].used = used;
+}
+
+int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers, const size_t *n, const adapt_net_stats *stats,
+                             GradWindow *win, ChainLayerOut *out)
+{
+    if (nlayers < 1) return ADAPT_EINVAL;
+    size_t need = 0;
+    for (int l = 0; l < nlayers; ++l) {
+        if (in[l].count < 1 || in[l].count > kGdMaxTensors || n[l] > ((size_t)1 << 30)) return ADAPT_EUNSUPPORTED;
+        need = std::max(need, ws_need_gradient_diversity(n[l], in[l].count));
+    }
+    if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
+    hipLaunchKernelGGL(chain_prep_kernel, dim3(1), dim3(64), 0, ctx->stream, in, nlayers, stats, win, out);
+    const size_t per_block = (size_t)kGdThreads * kGdPerThread;
+    const GradWindow none = {};
+    for (int l = 0; l < nlayers; ++l) {
+        const int grid = (int)std::max<size_t>(1, (n[l] + per_block - 1) / per_block);
+        hipLaunchKernelGGL(gd_partial_kernel<true>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, none, win + l, (uint32_t)n[l], partial);
+        hipLaunchKernelGGL(gd_final_kernel<true>, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, none, win + l, partial, grid,
+                           nullptr, &out[l].ds);
+    }
+    return hip_status(ctx, hipGetLastError());
 }
 
 size_t ws_need_gradient_diversity(uint64_t n, int count)
@@ -214,8 +284,8 @@ extern "C" int adapt_gradient_diversity(adapt_ctx *ctx, const adapt_grad_item *i
     const int grid = (int)std::max<size_t>(1, (n + per_block - 1) / per_block);
     if ((size_t)grid * (count + 2) * sizeof(uint64_t) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
-    hipLaunchKernelGGL(gd_partial_kernel, dim3(grid), dim3(kGdThreads), 0, ctx->stream, w, (uint32_t)n, partial);
-    hipLaunchKernelGGL(gd_final_kernel, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, w, partial, grid, sums, out);
+    hipLaunchKernelGGL(gd_partial_kernel<false>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, w, nullptr, (uint32_t)n, partial);
+    hipLaunchKernelGGL(gd_final_kernel<false>, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, w, nullptr, partial, grid, sums, out);
     return hip_status(ctx, hipGetLastError());
 }
 

@@ -216,7 +216,10 @@ def test_invalid_chains_are_rejected():
 
 # ---- the whole of Alg. 1 with the precision switch of Alg. 2 -----------------------------------------------
 
-def _train_with_switch(layers, fmts, n, steps, seed, sp_kw):
+def _train_with_switch(layers, fmts, n, steps, seed, sp_kw, fl_jumps=None, cx=None, starved=None, used_seen=None):
+    """fl_jumps: step -> added to the fractional bits the loss gradient is declared with (its codes stay the same);
+    cx: the context to run on; starved: an empty list: the first precision switch that fails for lack of scratch in cx
+    is repeated after the scratch has grown, and its step is appended; used_seen: list that collects r.used."""
     from oracle import pushup_oracle as po
     rng = np.random.default_rng(seed)
     first = layers[0]
@@ -225,7 +228,7 @@ def _train_with_switch(layers, fmts, n, steps, seed, sp_kw):
     wdev = [dev(w.copy()) for w in ws]
     sp = pkg.SwitchParams(sp_kw["lb_lwr"], sp_kw["lb_upr"], sp_kw["lb_init"], sp_kw["r_lwr"], sp_kw["r_upr"], sp_kw["r_init"],
                           sp_kw["gamma"], sp_kw["eps"], sp_kw["buff"], sp_kw["wl_lo"], sp_kw["wl_hi"], po.ST_MIN)
-    net = pkg.Net(ctx(), descs, wdev, switch=sp)
+    net = pkg.Net(cx if cx is not None else ctx(), descs, wdev, switch=sp)
     fmts = list(fmts)
     for l, (wl, fl) in enumerate(fmts):
         net.set_format(l, wl, fl)
@@ -249,20 +252,31 @@ def _train_with_switch(layers, fmts, n, steps, seed, sp_kw):
         labels = rng.integers(0, soft.shape[1], n)
         loss = float(-np.mean(np.log(soft[np.arange(n), labels] + 1e-30)))
         soft[np.arange(n), labels] -= 1.0
-        dl_fl = wl_last - 1                                           # gradient of the logits in [-1, 1): WL-1 fractional bits
+        dl_fl = wl_last - 1 + (fl_jumps or {}).get(step, 0)           # gradient of the logits in [-1, 1): WL-1 fractional bits
         lim = 1 << (wl_last - 1)
         dl = np.clip(np.rint(soft * lim), -lim, lim - 1).astype(_dt(wl_last))
         net.backward(dev(dl), dl_fl, seed=seed, stream=s0)
         bwd = no.backward(layers, fmts, wq, fwd, dl, seed, s0)
-        rep, strat = net.precision_switch(loss, seed=seed, stream=s0)
+        try:
+            rep, strat = net.precision_switch(loss, seed=seed, stream=s0)
+        except pkg.AdaptError as err:
+            if starved is None or starved or "workspace" not in str(err):
+                raise
+            starved.append(step)
+            cx.reserve_workspace(64 << 20)
+            rep, strat = net.precision_switch(loss, seed=seed, stream=s0)
+        with pytest.raises(pkg.AdaptError):                           # the gradients of one backward pass join the windows once
+            net.precision_switch(loss, seed=seed, stream=s0)
         want = no.precision_switch(st, fmts, ws, bwd, dl_fl, loss, seed, s0)
+        if used_seen is not None:
+            used_seen.extend(r.used for r in rep)
         assert strat == st.strategy, step
         for l, (r, w) in enumerate(zip(rep, want)):
             if np.isfinite(w["ds"]):
                 assert abs(r.ds - w["ds"]) <= 1e-12 * abs(w["ds"]), (step, l)
             else:
                 assert not np.isfinite(r.ds)
-            assert (r.lb, r.res, bool(r.switched), r.wl, r.fl) == (w["lb"], w["res"], w["switched"], w["wl"], w["fl"]), (step, l)
+            assert (r.lb, r.res, bool(r.switched), r.wl, r.fl, r.used) == (w["lb"], w["res"], w["switched"], w["wl"], w["fl"], w["used"]), (step, l)
             if w["switched"]:
                 switches += 1
                 assert (r.wl_min, r.fl_min) == (w["wl_min"], w["fl_min"]), (step, l)
@@ -290,6 +304,34 @@ def test_precision_switching_across_the_one_and_two_limb_boundary():
     kw = dict(lb_lwr=1, lb_upr=3, lb_init=1, r_lwr=100, r_upr=128, r_init=100, gamma=0.3, eps=1e-3, buff=3, wl_lo=4, wl_hi=16)
     switches, fmts = _train_with_switch(layers, [(12, 9), (6, 3), (16, 12)], n=4, steps=6, seed=32, sp_kw=kw)
     assert switches >= 3
+
+
+def test_gradient_scales_too_far_apart_drop_the_oldest_window_entries():
+    # the declared scale of the loss gradient jumps by 2^40 between batches: a window that spans the jump cannot be
+    # summed in 32 bits, so the entries before it are left out of the diversity (the oracle applies the same rule)
+    kw = dict(lb_lwr=3, lb_upr=5, lb_init=4, r_lwr=50, r_upr=60, r_init=55, gamma=0.2, eps=1e-2, buff=2, wl_lo=2, wl_hi=16)
+    used = []
+    _train_with_switch(_small_net(), [(8, 5), (12, 8), (8, 4)], n=6, steps=7, seed=33, sp_kw=kw,
+                       fl_jumps={2: 40, 3: 40, 4: 40, 5: -20, 6: -20}, used_seen=used)
+    per_step = [used[i:i + 3] for i in range(0, len(used), 3)]
+    assert any(u == 1 for u in per_step[2]) and any(u > 1 for row in per_step for u in row), per_step
+
+
+def test_a_precision_switch_that_fails_changes_nothing():
+    # scratch that is enough for the contractions and the diversities but not for the KL search of a 64K-weight layer
+    # at 4000 bins: the first call fails after the diversities were made, the repeated call must match the oracle,
+    # and so must the steps after it (strategy, loss history, windows, lookbacks and formats were left alone)
+    layers = [no.Layer(8, 8, 16, 32, relu=True, pool=True),
+              no.Layer(4, 4, 32, 32, relu=True, pool=False),
+              no.Layer(1, 1, 512, 128, 1, 1, 1, 0, relu=False, pool=False)]
+    kw = dict(lb_lwr=1, lb_upr=3, lb_init=2, r_lwr=3000, r_upr=4096, r_init=4000, gamma=0.3, eps=1e-3, buff=3, wl_lo=4, wl_hi=16)
+    cx = pkg.Context(workspace_bytes=1 << 20)
+    try:
+        starved = []
+        switches, _ = _train_with_switch(layers, [(12, 9), (6, 3), (16, 12)], n=4, steps=5, seed=34, sp_kw=kw, cx=cx, starved=starved)
+    finally:
+        cx.close()
+    assert switches >= 2 and len(starved) == 1 and starved[0] >= 1        # the loss history was in use when the call failed
 
 
 def test_precision_switch_needs_a_backward_pass_and_parameters():
