@@ -64,7 +64,7 @@ def _layers_of(cfg):
     return [wk.layer_inputs(sp, 50 + i) for i, sp in enumerate(wk.resnet18_cifar_layers())]
 
 
-def run_config(cfg, steps, warmup, ctx, pkg, torch, per_layer=False):
+def run_config(cfg, steps, warmup, ctx, pkg, torch, per_layer=False, plain=False):
     """Builds the device tensors of configuration `cfg`, runs `warmup` + `steps` steps and returns the measurements.
     The timed region is bracketed by synchronisations; inside it HIP events on the library's stream mark every step
     boundary (median / min) and, on every tenth step, bracket each contraction call (roofline of the contractions)."""
@@ -140,10 +140,13 @@ def run_config(cfg, steps, warmup, ctx, pkg, torch, per_layer=False):
                                                                            kld_args["ils"][0], 2048, 1e-2, stream=2, kld=kld[0], sel=sel[0])))
         kld_bytes = 4.0 * kld_ws[0].numel()
     else:
+        # the search takes every W's range from the quantize pass (no range pass of its own) where that pass ran
+        kld_ranges = [ranges[2 * i:2 * i + 2] for i in w_slots] if ranges is not None else None
         calls.append(("kld", "all W", lambda: ctx.kld_precision_search_batched(kld_ws, kld_args["ils"], [2048] * len(kld_ws),
                                                                                list(range(2, 2 + len(kld_ws))), kld_args["wl_lo"],
-                                                                               kld_args["wl_hi"], 1e-2, kld=kld, sel=sel)))
-        kld_bytes = 8.0 * sum(t.numel() for t in kld_ws)      # range pass + histogram pass
+                                                                               kld_args["wl_hi"], 1e-2, kld=kld, sel=sel,
+                                                                               ranges=kld_ranges)))
+        kld_bytes = (4.0 if kld_ranges else 8.0) * sum(t.numel() for t in kld_ws)      # histogram pass (+ range pass)
 
     EV_EVERY = 10
     conv_idx = [i for i, (k, _, _) in enumerate(calls) if k in ("fwd", "backward")]
@@ -160,6 +163,11 @@ def run_config(cfg, steps, warmup, ctx, pkg, torch, per_layer=False):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    if plain:                                   # profiler runs: whole steps only, so that launches divide by the step count
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return {"workload": WORKLOADS[cfg], "steps_run": steps + warmup, "calls_per_step": len(calls)}
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     brackets = [{i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in conv_idx}
                 if s % EV_EVERY == 0 else None for s in range(steps)]
@@ -483,6 +491,9 @@ def main():
     ap.add_argument("--no-next-rows", action="store_true",
                     help="skip everything beyond the headline configuration's timed steps (sub-records of the other "
                          "configurations, PushUp, fused update, chained step): for profiler runs")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="run warmup + steps whole steps of --config and nothing else (no per-call timing loops): every kernel's "
+                         "launch count is then a multiple of the step count, which the rocprofv3 summaries under profiles/ rely on")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 256 MiB (20 times): the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
@@ -510,6 +521,9 @@ def main():
     ctx = pkg.Context()
     if args.chained_step:
         print(json.dumps({"chained_step": chained_step(ctx, pkg, torch, batch=128)}))
+        return
+    if args.steps_only:
+        print(json.dumps(run_config(args.config, args.steps, args.warmup, ctx, pkg, torch, plain=True)))
         return
 
     head = run_config(args.config, args.steps, args.warmup, ctx, pkg, torch, per_layer=True)

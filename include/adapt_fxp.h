@@ -272,6 +272,16 @@ int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kld_item *ite
                                        int wl_lo, int wl_hi, double eps, double alpha, int mode,
                                        uint64_t seed, double *kld, int32_t *sel);
 
+/* The batched search with ranges already known (e.g. from adapt_quantize_batched_ranges or
+ * adapt_sgd_update_quantize): ranges = HOST array of `count` device pointers, ranges[t] = device
+ * float[2] (min, max) of the finite elements of tensor t, or NULL for a tensor whose range the call
+ * computes itself.  When every entry is set the range pass over the tensors is skipped.  Elements
+ * outside a range that does not bound its tensor are counted in the end bins. */
+int adapt_kld_precision_search_batched_ranged(adapt_ctx *ctx, const adapt_kld_item *items,
+                                              const float *const *ranges, int count, int wl_lo,
+                                              int wl_hi, double eps, double alpha, int mode,
+                                              uint64_t seed, double *kld, int32_t *sel);
+
 /* ---- master-weight update fused with re-quantization (Alg. 1: the backward-pass line and the
  *      Quantize loop after it) ------------------------------------------------------------- */
 
@@ -476,7 +486,9 @@ int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogits_fl, adap
  *              sum_k 2^(wl_k - 1 + max e - e_k) reaches 2^31 the oldest of these entries is left out
  *              (the newest always stays); `used` reports how many entered;
  *              lb^l = adapt_lookback_next, r^l = adapt_resolution_next;
- *              if len >= lb^l: PushDown = the KL search (batched over the layers that switch) on the master weights with
+ *              if len >= lb^l: PushDown = the KL search (batched over the layers that switch; it takes the
+ *              range of the weights from the last adapt_net_update, so master weights that the caller
+ *              rewrites must be followed by adapt_net_quantize_weights) on the master weights with
  *              il = WL - FL, candidates max(wl_lo, il)..wl_hi, r^l bins, stream slot 6, its
  *              selection limited to the current WL; PushUp = adapt_pushup_suggest with wl_cap 16;
  *              the layer takes the new format and its window is emptied.

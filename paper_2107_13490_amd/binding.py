@@ -156,6 +156,8 @@ def load_library():
     lib.adapt_conv_backward.argtypes = [vp, ConvDesc, vp, Fmt, vp, Fmt, vp, Fmt, vp, Epilogue, vp, Epilogue]
     lib.adapt_kld_precision_search.argtypes = [vp, vp, sz, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
     lib.adapt_kld_precision_search_batched.argtypes = [vp, C.POINTER(KldItem), i, i, i, dbl, dbl, i, u64, vp, vp]
+    lib.adapt_kld_precision_search_batched_ranged.argtypes = [vp, C.POINTER(KldItem), C.POINTER(C.c_void_p), i, i, i, dbl, dbl, i, u64,
+                                                              vp, vp]
     lib.adapt_kld_precision_search_ranged.argtypes = [vp, vp, sz, vp, i, i, i, i, dbl, dbl, Rng, vp, vp, vp, vp]
     lib.adapt_sgd_update_quantize.argtypes = [vp, vp, sz, vp, Fmt, vp, SgdParams, Fmt, Rng, vp, vp, vp]
     lib.adapt_perf_pushdown_ops.argtypes = [i, dbl]
@@ -473,7 +475,8 @@ class Context:
         return dict(kld=kld, sel=sel, hist=hist, grid=grid)
 
     def kld_precision_search_batched(self, ws, ils, bins, streams, wl_lo, wl_hi, eps, alpha=-1.0, mode=SR, seed=0,
-                                     kld=None, sel=None):
+                                     kld=None, sel=None, ranges=None):
+        """ranges: optional list with, per tensor, a device float32[2] tensor (min, max of its finite elements) or None."""
         torch = self._torch
         n = len(ws)
         ncand = wl_hi - wl_lo + 1
@@ -485,8 +488,16 @@ class Context:
         items = (KldItem * max(n, 1))()
         for t in range(n):
             items[t] = KldItem(ws[t].data_ptr(), ws[t].numel(), ils[t], bins[t], streams[t])
-        _check(self._lib.adapt_kld_precision_search_batched(self._h, items, n, wl_lo, wl_hi, eps, alpha, mode, seed,
-                                                            _ptr(kld), _ptr(sel)), "adapt_kld_precision_search_batched")
+        if ranges is None:
+            _check(self._lib.adapt_kld_precision_search_batched(self._h, items, n, wl_lo, wl_hi, eps, alpha, mode, seed,
+                                                                _ptr(kld), _ptr(sel)), "adapt_kld_precision_search_batched")
+        else:
+            rp = (C.c_void_p * max(n, 1))()
+            for t in range(n):
+                rp[t] = ranges[t].data_ptr() if ranges[t] is not None else None
+            _check(self._lib.adapt_kld_precision_search_batched_ranged(self._h, items, rp, n, wl_lo, wl_hi, eps, alpha, mode, seed,
+                                                                       _ptr(kld), _ptr(sel)),
+                   "adapt_kld_precision_search_batched_ranged")
         return kld, sel
 
     # -- PushUp ---------------------------------------------------------------------------------

@@ -2,19 +2,21 @@
 // distribution of a tensor and of its <WL_c, FL_c> quantizations, for all candidate word
 // lengths in one pass over the tensor.
 //
-// Three launches per search (per batch of searches in the batched form), all on the context's stream, no host round trip (kernel boundaries
-// order the phases; only the tiny final kernel uses a device-wide fence):
+// Four launches per search (per batch of searches in the batched form), all on the context's stream, no host round trip (kernel boundaries
+// order the phases; only the small final kernel uses a device-wide fence):
 //   range    per-block min / max of the finite elements.
 //   hist     every block first reduces the range partials and derives the bin grid (power-of-two
 //            width) and the per-candidate integer bin parameters (the "plan"; block 0 also stores
 //            it for the later kernels), then reads its share of the tensor once: reference bin +
 //            one bin per candidate for every element, counted in LDS histograms, and written to the block's own slab with plain stores.
-//   final    blocks of (256 bins, candidate): add the slabs of the reference row and of the
-//            candidate's row, partial KL sums in fp64; the last block to finish adds the partial
-//            sums in a fixed order and picks the lowest WL with KL < eps.
+//   sum      blocks of (256 bins, row): add the slabs of one row.
+//   final    blocks of 256 bins: partial KL sums of every candidate on those bins in fp64; the last
+//            block to finish adds the partial sums in a fixed order and picks the lowest WL with
+//            KL < eps.
 // All counts are integers, so the result does not depend on the order of accumulation.
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.hpp"
 #include "context.hpp"
@@ -26,6 +28,7 @@ constexpr int kHistMaxThreads = 1024;
 constexpr int kRangeThreads = 256;
 constexpr size_t kLdsBudget = 156 * 1024;      // dynamic LDS of a block; 160 KB per CU less the static part
 constexpr int kPrivWords = 1024;                  // counters of one coarse candidate's private table
+constexpr int kChunk = 256;                       // bins per block of the final kernel
 
 struct KldCand {
     int d;        // T >> d gives floor(x * 2^(FL_c + 16))
@@ -175,8 +178,7 @@ kld_range_kernel(const float *__restrict__ w, uint64_t n, float *partial /* [2*g
 __device__ __forceinline__ int value_bin(float v, int e, float base_f)
 {
     const float t = ldexpf(v, -e);
-    float f = floorf(t);
-    if (t == 0.0f && v < 0.0f) f = -1.0f;
+    const float f = (t == 0.0f && v < 0.0f) ? -1.0f : floorf(t);
     return (int)(f - base_f);
 }
 
@@ -193,31 +195,51 @@ __device__ __forceinline__ int bin_of_code(const KldCand &k, int q)
     return (int)(b64 < 0 ? 0 : b64 > (long long)k.bmax ? (long long)k.bmax : b64) + k.lo;
 }
 
-__device__ __forceinline__ void count_candidate_by_code(const KldCand &k, uint32_t *priv, int lane, const int (&T)[8],
+// min(max(x, lo), hi) for lo <= hi in one instruction (the median of the three)
+__device__ __forceinline__ int clamp_i32(int x, int lo, int hi)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
+    return r;
+}
+
+// `park` is a lane-private LDS word that takes the (zero) additions of the elements that are counted elsewhere: zeros
+// and non-finite elements.  An atomic addition of 0 still takes its turn at the counter's address, and the zeros of
+// a pruned tensor would queue up there.
+__device__ __forceinline__ void count_candidate_by_code(const KldCand &k, uint32_t *priv, uint32_t *park, int lane, const int (&T)[8],
                                                         const int (&r)[8], const uint32_t (&inc)[8])
 {
     const int sub = lane & ((1 << k.rsh) - 1);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const int q = min(max(((T[j] >> k.d) + r[j]) >> 16, k.qmin), k.qmax);
-        atomicAdd(&priv[((q - k.qmin) << k.rsh) + sub], inc[j]);
+        const int q = clamp_i32(((T[j] >> k.d) + r[j]) >> 16, k.qmin, k.qmax);
+        atomicAdd(inc[j] ? &priv[((q - k.qmin) << k.rsh) + sub] : park, inc[j]);
     }
 }
 
-__device__ __forceinline__ void count_candidate(const KldCand &k, uint32_t *row, const int (&T)[8], const int (&r)[8],
+// USE_LDS: row and park are LDS words; else row is global memory and the skipped elements are predicated off
+template <bool USE_LDS>
+__device__ __forceinline__ void count_one(uint32_t *row, uint32_t *park, int x, uint32_t inc)
+{
+    if (USE_LDS) atomicAdd(inc ? &row[x] : park, inc);
+    else if (inc) atomicAdd(&row[x], inc);
+}
+
+template <bool USE_LDS>
+__device__ __forceinline__ void count_candidate(const KldCand &k, uint32_t *row, uint32_t *park, const int (&T)[8], const int (&r)[8],
                                                 const uint32_t (&inc)[8])
 {
     if (k.kind == 0) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int x = ((T[j] >> k.d) + r[j]) >> k.s;
-            atomicAdd(&row[min(max(x, k.lo), k.hi)], inc[j]);
+            count_one<USE_LDS>(row, park, clamp_i32(x, k.lo, k.hi), inc[j]);
         }
     } else if (k.kind == 1) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int x = (int)((unsigned)(((T[j] >> k.d) + r[j]) >> 16) << k.s);
-            atomicAdd(&row[min(max(x, k.lo), k.hi)], inc[j]);
+            count_one<USE_LDS>(row, park, clamp_i32(x, k.lo, k.hi), inc[j]);
         }
     } else {
 #pragma unroll
@@ -225,7 +247,7 @@ __device__ __forceinline__ void count_candidate(const KldCand &k, uint32_t *row,
             const long long q = (long long)(((T[j] >> k.d) + r[j]) >> 16);
             const long long b64 = (long long)((unsigned long long)q << k.s) - k.base64;
             const int x = (int)(b64 < 0 ? 0 : b64 > (long long)k.bmax ? (long long)k.bmax : b64) + k.lo;
-            atomicAdd(&row[x], inc[j]);
+            count_one<USE_LDS>(row, park, x, inc[j]);
         }
     }
 }
@@ -242,8 +264,8 @@ __global__ void zero_words_kernel(uint32_t *p, size_t n)
 template <bool USE_LDS>
 __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial,
                                               int range_blocks, int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out,
-                                              uint32_t *slabs, int total_rows, int rows_per_group, int mode, uint64_t seed,
-                                              uint64_t stream, const BlockGeo geo)
+                                              uint32_t *tickets, uint32_t *slabs, int total_rows, int rows_per_group, int mode,
+                                              uint64_t seed, uint64_t stream, const BlockGeo geo)
 {
     // geo.by selects a group of histogram rows: small tensors are spread over more CUs by
     // letting several blocks count different candidates of the same elements
@@ -254,6 +276,8 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
     __shared__ float slo[kHistMaxThreads / kWave], shi[kHistMaxThreads / kWave];
     __shared__ int row_off[kMaxCand];          // word offset of the candidate's row minus its bin origin
     __shared__ int priv_off[kMaxCand];         // word offset of a coarse candidate's private table, else -1
+    __shared__ uint32_t park_words[kWave];     // where the additions of skipped elements go, one word per lane
+    uint32_t *park = &park_words[threadIdx.x & (kWave - 1)];
     const int nthreads = blockDim.x, nwaves = nthreads / kWave;
     const int ncand = wl_hi - wl_lo + 1;
 
@@ -281,9 +305,11 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
         __syncthreads();
         if (!plan.degenerate && (int)threadIdx.x < ncand) make_candidate(&plan, threadIdx.x, wl_lo, wl_hi, il);
         __syncthreads();
-        if (geo.bx == 0 && geo.by == 0)
+        if (geo.bx == 0 && geo.by == 0) {
             for (int i = threadIdx.x; i < (int)(sizeof(KldPlan) / 4); i += nthreads)
                 reinterpret_cast<uint32_t *>(plan_out)[i] = reinterpret_cast<const uint32_t *>(&plan)[i];
+            if (threadIdx.x == 0) tickets[0] = 0;      // the ticket of the final kernel
+        }
     }
     if (plan.degenerate) return;
 
@@ -318,32 +344,60 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
         row_off[threadIdx.x] = (threadIdx.x + 1 - row0) * row_stride - plan.cand[threadIdx.x].lo;
     __syncthreads();
 
-    // one group = 8 consecutive elements of one thread (one Philox block)
-    auto count_group = [&](const float (&v)[8], const int (&r)[8], int cnt) {
-        int T[8];
-        uint32_t inc[8];
+    // Zeros (pruned weights, Sec. 3.4) all land in one counter of every row, where the LDS atomics of a wavefront
+    // would serialise: each thread counts its zeros in a register and the block adds the total to the rows once.
+    // A zero has code 0 under every candidate, whatever its rounding bits.
+    uint32_t nzero = 0;
+    // One group = 8 consecutive elements of one thread (one Philox block).  A pass takes G groups into registers,
+    // counts the reference row, then visits the candidates one after the other: a candidate's parameters are read
+    // (and made wavefront-uniform) once per pass, and its kind is one uniform branch around 8 G straight-line elements.
+    auto count_groups = [&](auto gtag, const float (&v)[decltype(gtag)::value][8], const int (&r)[decltype(gtag)::value][8],
+                            const int (&cnt)[decltype(gtag)::value]) {
+        constexpr int G = decltype(gtag)::value;
+        int T[G][8];
+        uint32_t inc[G][8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bool fin = j < cnt && fabsf(v[j]) < INFINITY;
-            inc[j] = fin ? 1u : 0u;
-            T[j] = (int)floorf(fminf(fmaxf(v[j] * tscale, tmin), tmax));      // NaN -> tmin
-            // (the clamp only acts when a caller-supplied range does not bound the tensor)
-            if (do_ref) atomicAdd(&hist[fin ? min(max(value_bin(v[j], e, base_f), 0), nb - 1) : 0], inc[j]);
+        for (int u = 0; u < G; ++u)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool zero = v[u][j] == 0.0f;
+                const bool fin = j < cnt[u] && fabsf(v[u][j]) < INFINITY;
+                nzero += (fin && zero) ? 1u : 0u;
+                inc[u][j] = (fin && !zero) ? 1u : 0u;
+                T[u][j] = (int)floorf(fminf(fmaxf(v[u][j] * tscale, tmin), tmax));      // NaN -> tmin
+                // (the clamp only acts when a caller-supplied range does not bound the tensor)
+            }
+        if (do_ref) {
+#pragma unroll
+            for (int u = 0; u < G; ++u)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    count_one<USE_LDS>(hist, park, inc[u][j] ? min(max(value_bin(v[u][j], e, base_f), 0), nb - 1) : 0, inc[u][j]);
         }
         for (int c = c_begin; c < c_end; ++c) {
-            if (USE_LDS && priv_off[c] >= 0) count_candidate_by_code(plan.cand[c], lds + priv_off[c], threadIdx.x & (kWave - 1), T, r, inc);
-            else count_candidate(plan.cand[c], hist + row_off[c], T, r, inc);
+            KldCand k;
+            k.d = __builtin_amdgcn_readfirstlane(plan.cand[c].d);
+            k.kind = __builtin_amdgcn_readfirstlane(plan.cand[c].kind);
+            k.s = __builtin_amdgcn_readfirstlane(plan.cand[c].s);
+            k.lo = __builtin_amdgcn_readfirstlane(plan.cand[c].lo);
+            k.hi = __builtin_amdgcn_readfirstlane(plan.cand[c].hi);
+            k.bmax = __builtin_amdgcn_readfirstlane(plan.cand[c].bmax);
+            k.base64 = plan.cand[c].base64;
+            k.coarse = 0;
+            k.qmin = __builtin_amdgcn_readfirstlane(plan.cand[c].qmin);
+            k.qmax = __builtin_amdgcn_readfirstlane(plan.cand[c].qmax);
+            k.rsh = __builtin_amdgcn_readfirstlane(plan.cand[c].rsh);
+            const int poff = __builtin_amdgcn_readfirstlane(priv_off[c]), roff = __builtin_amdgcn_readfirstlane(row_off[c]);
+            if (USE_LDS && poff >= 0) {
+#pragma unroll
+                for (int u = 0; u < G; ++u) count_candidate_by_code(k, lds + poff, park, threadIdx.x & (kWave - 1), T[u], r[u], inc[u]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < G; ++u) count_candidate<USE_LDS>(k, hist + roff, park, T[u], r[u], inc[u]);
+            }
         }
     };
-
-    const uint64_t full_groups = n >> 3;
-    const uint64_t first = (uint64_t)geo.bx * nthreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)geo.gx * nthreads;
-    for (uint64_t g = first; g < full_groups; g += stride) {
-        const float4 a = reinterpret_cast<const float4 *>(w)[2 * g];
-        const float4 b = reinterpret_cast<const float4 *>(w)[2 * g + 1];
-        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        int r[8];
+    auto rounding_of = [&](uint64_t g, int (&r)[8]) {
         if (mode == ADAPT_SR) {
             const u32x4 blk = rounding_block(seed, stream, g);
             r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
@@ -352,18 +406,75 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
 #pragma unroll
             for (int j = 0; j < 8; ++j) r[j] = 0x8000;
         }
-        count_group(v, r, 8);
+    };
+
+    constexpr int kPass = 4;
+    const uint64_t full_groups = n >> 3;
+    const uint64_t first = (uint64_t)geo.bx * nthreads + threadIdx.x;
+    const uint64_t stride = (uint64_t)geo.gx * nthreads;
+    uint64_t g = first;
+    for (; g + (kPass - 1) * stride < full_groups; g += kPass * stride) {
+        float v[kPass][8];
+        int r[kPass][8], cnt[kPass];
+#pragma unroll
+        for (int u = 0; u < kPass; ++u) {
+            const float4 a = reinterpret_cast<const float4 *>(w)[2 * (g + u * stride)];
+            const float4 b = reinterpret_cast<const float4 *>(w)[2 * (g + u * stride) + 1];
+            v[u][0] = a.x; v[u][1] = a.y; v[u][2] = a.z; v[u][3] = a.w; v[u][4] = b.x; v[u][5] = b.y; v[u][6] = b.z; v[u][7] = b.w;
+            cnt[u] = 8;
+        }
+#pragma unroll
+        for (int u = 0; u < kPass; ++u) rounding_of(g + u * stride, r[u]);
+        count_groups(std::integral_constant<int, kPass>{}, v, r, cnt);
+    }
+    // the last groups of the thread (fewer than kPass): a pass of two, then single groups
+    if (g + stride < full_groups) {
+        float v[2][8];
+        int r[2][8];
+        const int cnt[2] = {8, 8};
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float4 a = reinterpret_cast<const float4 *>(w)[2 * (g + u * stride)];
+            const float4 b = reinterpret_cast<const float4 *>(w)[2 * (g + u * stride) + 1];
+            v[u][0] = a.x; v[u][1] = a.y; v[u][2] = a.z; v[u][3] = a.w; v[u][4] = b.x; v[u][5] = b.y; v[u][6] = b.z; v[u][7] = b.w;
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) rounding_of(g + u * stride, r[u]);
+        count_groups(std::integral_constant<int, 2>{}, v, r, cnt);
+        g += 2 * stride;
+    }
+    for (; g < full_groups; g += stride) {
+        const float4 a = reinterpret_cast<const float4 *>(w)[2 * g];
+        const float4 b = reinterpret_cast<const float4 *>(w)[2 * g + 1];
+        const float v[1][8] = {{a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w}};
+        int r[1][8];
+        const int cnt[1] = {8};
+        rounding_of(g, r[0]);
+        count_groups(std::integral_constant<int, 1>{}, v, r, cnt);
     }
     if ((n & 7) && first == 0) {
-        float v[8];
-        int r[8];
-        const int cnt = (int)(n & 7);
+        float v[1][8];
+        int r[1][8];
+        const int cnt[1] = {(int)(n & 7)};
         for (int j = 0; j < 8; ++j) {
             const uint64_t i = (full_groups << 3) + j;
-            v[j] = j < cnt ? w[i] : 0.0f;
-            r[j] = (int)rounding_bits_of(seed, stream, i, mode);
+            v[0][j] = j < cnt[0] ? w[i] : 0.0f;
+            r[0][j] = (int)rounding_bits_of(seed, stream, i, mode);
         }
-        count_group(v, r, cnt);
+        count_groups(std::integral_constant<int, 1>{}, v, r, cnt);
+    }
+
+    // the block's zeros: one addition per row
+    __shared__ uint32_t zero_total;
+    if (threadIdx.x == 0) zero_total = 0;
+    __syncthreads();
+    nzero = wave_sum_u32(nzero);
+    if ((threadIdx.x & (kWave - 1)) == 0 && nzero) atomicAdd(&zero_total, nzero);
+    __syncthreads();
+    if (zero_total) {
+        if (do_ref && threadIdx.x == 0) atomicAdd(&hist[min(max(value_bin(0.0f, e, base_f), 0), nb - 1)], zero_total);
+        if ((int)threadIdx.x >= c_begin && (int)threadIdx.x < c_end)
+            atomicAdd(&hist[row_off[threadIdx.x] + bin_of_code(plan.cand[threadIdx.x], 0)], zero_total);
     }
 
     if (USE_LDS) {
@@ -396,116 +507,131 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
 template <bool USE_LDS>
 __global__ void __launch_bounds__(kHistMaxThreads)
 kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial, int range_blocks,
-                int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *slabs, int total_rows,
+                int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *tickets, uint32_t *slabs, int total_rows,
                 int rows_per_group, int mode, uint64_t seed, uint64_t stream)
 {
-    kld_hist_body<USE_LDS>(w, n, range_partial, range_blocks, wl_lo, wl_hi, il, bins, plan_out, slabs, total_rows,
+    kld_hist_body<USE_LDS>(w, n, range_partial, range_blocks, wl_lo, wl_hi, il, bins, plan_out, tickets, slabs, total_rows,
                            rows_per_group, mode, seed, stream, BlockGeo{blockIdx.x, blockIdx.y, gridDim.x, gridDim.y});
 }
 
-// ---- kernel 3: slab sums and partial KL sums ------------------------------------------------------------------
+// ---- kernel 3: slab sums, partial KL sums, selection ---------------------------------------------------------
 // With the same smoothing and the same total on both sides,
 //   KL = sum_b P(b) log2(P(b)/Q(b)) = (1/D) sum_b (cp_b + alpha) log2((cp_b + alpha)/(cq_b + alpha)),
 // D = n_finite + alpha nb, so bins with cp_b == cq_b contribute nothing and need no logarithm.
-// Block (x, c) handles bins [x*kChunk, (x+1)*kChunk) of candidate c: its 1024 threads are 4 groups
-// of 256; group s adds every 4th slab (all loads independent), LDS combines the groups.  The
-// partial sums go to part[c][x] = (sum of terms, sum of reference counts); the last block to finish
-// adds them in a fixed order and selects.
-constexpr int kChunk = 256;
-constexpr int kFinalGroups = 4;
-
-__device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs,
-                                               int rows, int bins, double alpha_in, double *part, uint32_t *hist_out, int wl_lo,
-                                               int il, double eps, double *kld, int32_t *sel, long long *grid_out,
-                                               uint32_t *ticket, const BlockGeo geo)
+// Two launches (a device-wide fence per block, which a single launch would need, empties the caches the slab
+// loads live on).  Sum: block (x, row) adds bins [x*kChunk, (x+1)*kChunk) of one row over the slabs into
+// sums[row][bins].  Final: block x forms the terms of every candidate on its bins and their sums
+// part[c][x] = (sum of terms), part[ncand][x] = (sum of reference counts); the last block of the search to
+// finish (a ticket) adds them in a fixed order and selects.
+// The region of a search in the scratch: ticket | part | sums.
+struct KlRegion {
+    uint32_t *tickets;      // [0]: blocks of the final kernel that have finished
+    double *part;           // [(ncand + 1) * nchunks]
+    uint32_t *sums;         // [rows * bins]
+};
+__host__ __device__ inline size_t kl_region_bytes(int ncand, int nchunks, int bins)
 {
-    __shared__ uint32_t cq_s[kFinalGroups][kChunk], cp_s[kFinalGroups][kChunk];
-    __shared__ double red[2][kChunk];
-    const int c = geo.by, nchunks = geo.gx;
-    const int lane = threadIdx.x % kChunk, grp = threadIdx.x / kChunk;
-    const int b = geo.bx * kChunk + lane;
+    auto a256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    return a256((size_t)(nchunks + 1) * 4) + a256((size_t)(ncand + 1) * nchunks * 8) + a256((size_t)(ncand + 1) * bins * 4);
+}
+__host__ __device__ inline KlRegion kl_region(char *base, int ncand, int nchunks)
+{
+    auto a256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    KlRegion r;
+    r.tickets = reinterpret_cast<uint32_t *>(base);
+    r.part = reinterpret_cast<double *>(base + a256((size_t)(nchunks + 1) * 4));
+    r.sums = reinterpret_cast<uint32_t *>(base + a256((size_t)(nchunks + 1) * 4) + a256((size_t)(ncand + 1) * nchunks * 8));
+    return r;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);      // the same tree in every lane
+    return v;
+}
+
+// kernel 3a, block (x, row): sums[row][b] = sum over the slabs, one thread per bin, eight loads in flight
+__device__ __forceinline__ void kld_sum_body(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs,
+                                             int rows, int bins, uint32_t *__restrict__ sums, uint32_t *hist_out, const BlockGeo geo)
+{
+    const int row = geo.by;
+    const int b = geo.bx * kChunk + threadIdx.x;
     const int nb = plan->degenerate ? 0 : plan->nb;
     const size_t slab_words = (size_t)rows * bins;
-    uint32_t uq = 0, up = 0;
+    uint32_t u = 0;
     if (b < nb) {
-        // slabs grp, grp + 4, ...: eight pairs of loads in flight at a time (a slab index past the end
-        // is redirected to slab 0 and its value dropped, so the loads carry no branches)
-        const uint32_t *pq = slabs + b, *pp = slabs + (size_t)(c + 1) * bins + b;
-        for (int s0 = grp; s0 < nslabs; s0 += 8 * kFinalGroups) {
-            uint32_t tq[8], tp[8];
+        // a slab index past the end is redirected to slab 0 and its value dropped, so the loads carry no branches
+        const uint32_t *p = slabs + (size_t)row * bins + b;
+        for (int s0 = 0; s0 < nslabs; s0 += 8) {
+            uint32_t t[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int sidx = s0 + u * kFinalGroups;
-                const size_t off = sidx < nslabs ? (size_t)sidx * slab_words : 0;
-                tq[u] = pq[off];
-                tp[u] = pp[off];
-            }
+            for (int i = 0; i < 8; ++i) t[i] = p[s0 + i < nslabs ? (size_t)(s0 + i) * slab_words : 0];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const bool in = s0 + u * kFinalGroups < nslabs;
-                uq += in ? tq[u] : 0u;
-                up += in ? tp[u] : 0u;
-            }
+            for (int i = 0; i < 8; ++i) u += s0 + i < nslabs ? t[i] : 0u;
         }
     }
-    cq_s[grp][lane] = uq;
-    cp_s[grp][lane] = up;
+    if (b < bins) {
+        sums[(size_t)row * bins + b] = u;
+        if (hist_out) hist_out[(size_t)row * bins + b] = u;
+    }
+}
+
+// kernel 3b, block x: terms of every candidate on bins [x*kChunk, (x+1)*kChunk), summed over the chunk in a fixed
+// order (lanes, then wavefronts); the last block of the search to finish adds the chunks in a fixed order and selects
+__device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan, int rows, int bins, double alpha_in,
+                                               const KlRegion reg, int wl_lo, int il, double eps, double *kld, int32_t *sel,
+                                               long long *grid_out, const BlockGeo geo)
+{
+    const int x = geo.bx, nchunks = geo.gx, ncand = rows - 1;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int b = x * kChunk + threadIdx.x;
+    const int nb = plan->degenerate ? 0 : plan->nb;
+    __shared__ double red[kMaxCand + 1][kChunk / kWave];
+    const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
+    const uint32_t uq = b < nb ? reg.sums[b] : 0u;
+    uint32_t up[kMaxCand];
+#pragma unroll
+    for (int c = 0; c < kMaxCand; ++c) up[c] = (c < ncand && b < nb) ? reg.sums[(size_t)(c + 1) * bins + b] : uq;
+#pragma unroll
+    for (int c = 0; c < kMaxCand; ++c) {
+        if (c >= ncand) break;
+        double term = 0.0;
+        if (up[c] != uq) {
+            const double pp = (double)up[c] + alpha, qq = (double)uq + alpha;
+            if (pp > 0.0) term = (qq > 0.0) ? pp * log2(pp / qq) : (double)INFINITY;
+        }
+        term = wave_sum_f64(term);
+        if (lane == 0) red[c][wave] = term;
+    }
+    {
+        const double cnt = wave_sum_f64((double)uq);      // exact
+        if (lane == 0) red[ncand][wave] = cnt;
+    }
     __syncthreads();
-    const bool lead = grp == 0;          // group 0 finishes; the others only keep the barriers company
-    double term = 0.0;
-    if (lead) {
+    if ((int)threadIdx.x <= ncand) {
+        double t = red[threadIdx.x][0];
 #pragma unroll
-        for (int s = 1; s < kFinalGroups; ++s) { uq += cq_s[s][lane]; up += cp_s[s][lane]; }
-        if (hist_out && b < bins) {
-            hist_out[(size_t)(c + 1) * bins + b] = up;
-            if (c == 0) hist_out[b] = uq;
-        }
-        const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
-        if (b < nb && up != uq) {
-            const double p = (double)up + alpha, q = (double)uq + alpha;
-            if (p > 0.0) term = (q > 0.0) ? p * log2(p / q) : (double)INFINITY;
-        }
-        red[0][lane] = term;
-        red[1][lane] = (double)uq;
+        for (int i = 1; i < kChunk / kWave; ++i) t += red[threadIdx.x][i];
+        __hip_atomic_store(reg.part + (size_t)threadIdx.x * nchunks + x, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    for (int off = kChunk / 2; off > 0; off >>= 1) {
-        __syncthreads();
-        if (lead && lane < off) { red[0][lane] += red[0][lane + off]; red[1][lane] += red[1][lane + off]; }
-    }
-    if (lead && lane == 0) {
-        part[2 * ((size_t)c * nchunks + geo.bx)] = red[0][0];
-        part[2 * ((size_t)c * nchunks + geo.bx) + 1] = red[1][0];
-    }
-    // the last block to finish adds the partial sums in a fixed order and selects
-    __shared__ bool last;
-    if (threadIdx.x == 0)      // release this block's partial sums, acquire everyone else's
-        last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == geo.gx * geo.gy - 1;
+    // every wavefront waits for its stores, the barrier orders them before thread 0's ticket
+    __shared__ bool last_chunk;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    if (!last) return;
+    if (threadIdx.x == 0)
+        last_chunk = __hip_atomic_fetch_add(reg.tickets, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)nchunks - 1;
+    __syncthreads();
+    if (!last_chunk) return;
+
     __shared__ double kl_s[kMaxCand];
-    const int ncand = geo.gy;
-    // all partial sums are loaded at once (one pair per thread), then added in a fixed order
-    double *tail = &red[0][0];
-    const int npart = 2 * ncand * nchunks;
-    const bool fits = npart <= 2 * kChunk;      // else (very many bins) each candidate's thread loads its own
-    if (fits)
-        for (int i = threadIdx.x; i < npart; i += blockDim.x)
-            tail[i] = __hip_atomic_load(part + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
     if ((int)threadIdx.x < ncand) {
         const int cc = threadIdx.x;
         double total = 0.0, nfin = 0.0;
-        for (int x = 0; x < nchunks; ++x) {
-            const size_t i = 2 * ((size_t)cc * nchunks + x);
-            if (fits) {
-                total += tail[i];
-                nfin += tail[i + 1];      // exact
-            } else {
-                total += __hip_atomic_load(part + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                nfin += __hip_atomic_load(part + i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+        for (int i = 0; i < nchunks; ++i) {
+            total += __hip_atomic_load(reg.part + (size_t)cc * nchunks + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            nfin += __hip_atomic_load(reg.part + (size_t)ncand * nchunks + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // exact
         }
-        const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
         const double kl = nb > 0 ? total / (nfin + alpha * (double)nb) : 0.0;
         kld[cc] = kl;
         kl_s[cc] = kl;
@@ -523,22 +649,29 @@ __device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan,
         grid_out[1] = plan->degenerate ? 0 : plan->base;
         grid_out[2] = plan->degenerate ? 0 : plan->nb;
     }
-    *ticket = 0;      // ready for the next search on this context
 }
 
-__global__ void __launch_bounds__(kChunk * kFinalGroups)
-kld_final_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs, int rows, int bins,
-                 double alpha_in, double *part, uint32_t *hist_out, int wl_lo, int il, double eps, double *kld, int32_t *sel,
-                 long long *grid_out, uint32_t *ticket)
+__global__ void __launch_bounds__(kChunk)
+kld_sum_kernel(const KldPlan *__restrict__ plan, const uint32_t *__restrict__ slabs, int nslabs, int rows, int bins, char *region,
+               uint32_t *hist_out)
 {
-    kld_final_body(plan, slabs, nslabs, rows, bins, alpha_in, part, hist_out, wl_lo, il, eps, kld, sel, grid_out, ticket,
-                   BlockGeo{blockIdx.x, blockIdx.y, gridDim.x, gridDim.y});
+    kld_sum_body(plan, slabs, nslabs, rows, bins, kl_region(region, rows - 1, gridDim.x).sums, hist_out,
+                 BlockGeo{blockIdx.x, blockIdx.y, gridDim.x, gridDim.y});
+}
+
+__global__ void __launch_bounds__(kChunk)
+kld_final_kernel(const KldPlan *__restrict__ plan, int rows, int bins, double alpha_in, char *region, int wl_lo, int il, double eps,
+                 double *kld, int32_t *sel, long long *grid_out)
+{
+    kld_final_body(plan, rows, bins, alpha_in, kl_region(region, rows - 1, gridDim.x), wl_lo, il, eps, kld, sel, grid_out,
+                   BlockGeo{blockIdx.x, 0, gridDim.x, 1});
 }
 
 // ---- batched form: the three phases of up to kKldBatchMax searches, one launch per phase --------------------
 constexpr int kKldBatchMax = 24;
 struct KldBatchItem {
     const float *w;
+    const float *range;       // device (min, max) of the finite elements, or null: the range pass computes it
     uint64_t n, stream;
     double *kld;
     int32_t *sel;
@@ -547,13 +680,12 @@ struct KldBatchItem {
 };
 struct KldBatch {
     KldBatchItem item[kKldBatchMax];
-    // first block of each tensor in the three launches (ascending)
-    unsigned first_range[kKldBatchMax], first_hist[kKldBatchMax], first_final[kKldBatchMax];
+    // first block of each tensor in the four launches (ascending)
+    unsigned first_range[kKldBatchMax], first_hist[kKldBatchMax], first_sum[kKldBatchMax], first_final[kKldBatchMax];
     int count, wl_lo, wl_hi, mode;
     unsigned long long seed;
     double eps, alpha;
     char *ws;
-    uint32_t *tickets;
 };
 
 // the tensor a block belongs to: every lane compares one table entry, the wavefront votes
@@ -576,21 +708,32 @@ kld_hist_batched_kernel(const KldBatch b)
 {
     ADAPT_KLD_FIND(first_hist);
     const int rows = b.wl_hi - b.wl_lo + 2;
-    kld_hist_body<true>(it.w, it.n, reinterpret_cast<const float *>(b.ws + it.off_range), it.range_blocks, b.wl_lo, b.wl_hi,
+    kld_hist_body<true>(it.w, it.n, it.range ? it.range : reinterpret_cast<const float *>(b.ws + it.off_range),
+                        it.range ? 1 : it.range_blocks, b.wl_lo, b.wl_hi,
                         it.il, it.bins, reinterpret_cast<KldPlan *>(b.ws + it.off_plan),
-                        reinterpret_cast<uint32_t *>(b.ws + it.off_slabs), rows, it.rows_per_group, b.mode, b.seed, it.stream,
+                        reinterpret_cast<uint32_t *>(b.ws + it.off_klpart), reinterpret_cast<uint32_t *>(b.ws + it.off_slabs), rows,
+                        it.rows_per_group, b.mode, b.seed, it.stream,
                         BlockGeo{l % (unsigned)it.hist_x, l / (unsigned)it.hist_x, (unsigned)it.hist_x, (unsigned)it.groups});
 }
 
-__global__ void __launch_bounds__(kChunk * kFinalGroups)
+__global__ void __launch_bounds__(kChunk)
+kld_sum_batched_kernel(const KldBatch b)
+{
+    ADAPT_KLD_FIND(first_sum);
+    const int ncand = b.wl_hi - b.wl_lo + 1;
+    kld_sum_body(reinterpret_cast<const KldPlan *>(b.ws + it.off_plan), reinterpret_cast<const uint32_t *>(b.ws + it.off_slabs),
+                 it.hist_x, ncand + 1, it.bins, kl_region(b.ws + it.off_klpart, ncand, it.nchunks).sums, nullptr,
+                 BlockGeo{l % (unsigned)it.nchunks, l / (unsigned)it.nchunks, (unsigned)it.nchunks, (unsigned)(ncand + 1)});
+}
+
+__global__ void __launch_bounds__(kChunk)
 kld_final_batched_kernel(const KldBatch b)
 {
     ADAPT_KLD_FIND(first_final);
     const int ncand = b.wl_hi - b.wl_lo + 1;
-    kld_final_body(reinterpret_cast<const KldPlan *>(b.ws + it.off_plan), reinterpret_cast<const uint32_t *>(b.ws + it.off_slabs),
-                   it.hist_x, ncand + 1, it.bins, b.alpha, reinterpret_cast<double *>(b.ws + it.off_klpart), nullptr, b.wl_lo,
-                   it.il, b.eps, it.kld, it.sel, nullptr, b.tickets + t,
-                   BlockGeo{l % (unsigned)it.nchunks, l / (unsigned)it.nchunks, (unsigned)it.nchunks, (unsigned)ncand});
+    kld_final_body(reinterpret_cast<const KldPlan *>(b.ws + it.off_plan), ncand + 1, it.bins, b.alpha,
+                   kl_region(b.ws + it.off_klpart, ncand, it.nchunks), b.wl_lo, it.il, b.eps, it.kld, it.sel, nullptr,
+                   BlockGeo{l, 0, (unsigned)it.nchunks, 1});
 }
 
 static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int wl_hi, int il, int bins, double eps,
@@ -607,7 +750,7 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
     // workspace: plan | range partials | KL partials | slabs
     char *ws = scratch(ctx);
     const int nchunks = (bins + kChunk - 1) / kChunk;
-    const size_t klpart_bytes = ((size_t)ncand * nchunks * 16 + 255) & ~(size_t)255;
+    const size_t klpart_bytes = kl_region_bytes(ncand, nchunks, bins);
     const size_t plan_bytes = (sizeof(KldPlan) + 255) & ~(size_t)255;
     const int range_grid = (int)std::min<uint64_t>((uint64_t)ctx->num_cu * 4, std::max<uint64_t>(1, (n / 4 + kRangeThreads - 1) / kRangeThreads));
     const size_t partial_bytes = ((size_t)range_grid * 8 + 255) & ~(size_t)255;
@@ -616,7 +759,7 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
     if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     KldPlan *plan = reinterpret_cast<KldPlan *>(ws);
     float *partial = reinterpret_cast<float *>(ws + plan_bytes);
-    double *klpart = reinterpret_cast<double *>(ws + plan_bytes + partial_bytes);
+    char *klpart = ws + plan_bytes + partial_bytes;
     uint32_t *slabs = reinterpret_cast<uint32_t *>(ws + plan_bytes + partial_bytes + klpart_bytes);
 
     // a range the caller already holds (from the pass that produced the tensor) stands in for the
@@ -637,17 +780,19 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
         // one set of LDS histograms per block: per-wavefront replicas were measured no faster
         const size_t lds = (size_t)rows_per_group * per_row + 16;
         hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, range_src,
-                           range_count, wl_lo, wl_hi, il, bins, plan, slabs, rows, rows_per_group, mode, seed, stream);
+                           range_count, wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows_per_group, mode, seed,
+                           stream);
     } else {
         const size_t zw = (size_t)hist_grid * hist_words;
         hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)std::min<size_t>((zw + 255) / 256, (size_t)ctx->num_cu * 8)),
                            dim3(256), 0, ctx->stream, slabs, zw);
         hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, range_src, range_count,
-                           wl_lo, wl_hi, il, bins, plan, slabs, rows, rows, mode, seed, stream);
+                           wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows, mode, seed, stream);
     }
-    hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks, ncand), dim3(kChunk * kFinalGroups), 0, ctx->stream, plan, slabs,
-                       hist_grid, rows, bins, alpha, klpart, hist, wl_lo, il, eps, kld, sel, reinterpret_cast<long long *>(grid),
-                       ticket(ctx, 2));
+    hipLaunchKernelGGL(kld_sum_kernel, dim3(nchunks, rows), dim3(kChunk), 0, ctx->stream, plan, slabs, hist_grid, rows, bins, klpart,
+                       hist);
+    hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks), dim3(kChunk), 0, ctx->stream, plan, rows, bins, alpha, klpart, wl_lo, il, eps,
+                       kld, sel, reinterpret_cast<long long *>(grid));
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -671,8 +816,8 @@ static hipError_t allow_hist_lds(adapt_ctx *ctx)
 // Searches on items[0 .. count): consecutive tensors are packed into batches (at most kKldBatchMax
 // tensors, as many as the workspace holds) that run their three phases in one launch each; a tensor
 // whose histogram rows do not fit LDS takes the single-tensor path.
-static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, int wl_lo, int wl_hi, double eps,
-                        double alpha, int mode, uint64_t seed, double *kld, int32_t *sel)
+static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, const float *const *ranges, int count, int wl_lo, int wl_hi,
+                        double eps, double alpha, int mode, uint64_t seed, double *kld, int32_t *sel)
 {
     const int ncand = wl_hi - wl_lo + 1, rows = ncand + 1;
     auto a256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
@@ -681,7 +826,8 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, 
         const size_t per_row0 = (size_t)items[t0].bins * 4 + kPrivWords * 4;
         if (per_row0 + 16 > kLdsBudget) {
             const int st = search_one(ctx, items[t0].w, items[t0].n, wl_lo, wl_hi, items[t0].il, items[t0].bins, eps, alpha, mode,
-                                      seed, items[t0].stream, kld + (size_t)t0 * ncand, sel + 2 * t0, nullptr, nullptr);
+                                      seed, items[t0].stream, kld + (size_t)t0 * ncand, sel + 2 * t0, nullptr, nullptr,
+                                      ranges ? ranges[t0] : nullptr);
             if (st != ADAPT_OK) return st;
             ++t0;
             continue;
@@ -693,21 +839,28 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, 
         KldBatch b;
         b.count = 0; b.wl_lo = wl_lo; b.wl_hi = wl_hi; b.mode = mode; b.seed = seed; b.eps = eps; b.alpha = alpha;
         b.ws = scratch(ctx);
-        b.tickets = ticket(ctx, 16);
         size_t off = 0, lds_max = 0;
-        unsigned nr = 0, nh = 0, nf = 0;
+        unsigned nr = 0, nh = 0, nsum = 0, nf = 0;
         // The batch as a whole fills the GPU once (a full set of rows leaves room for one block per CU): every block
         // clears and flushes its histogram rows, and the final phase reads the slabs back, so a tensor gets blocks
         // in proportion to its share of the elements rather than as many as it could use alone.
         uint64_t batch_elems = 0, batch_blocks = 0;
         const uint64_t per_block = (uint64_t)threads * 8;
         for (int m = 0; m < kKldBatchMax && t0 + m < count; ++m) batch_elems += items[t0 + m].n;
+        // the launch ends with its most loaded block: no block takes more than `load` elements, and `load` is chosen so
+        // that the blocks of all tensors (each rounded up) still number at most one per CU
+        int batch_count = 0;
+        for (int m = 0; m < kKldBatchMax && t0 + m < count; ++m) ++batch_count;
+        const uint64_t spare = (uint64_t)std::max(1, ctx->num_cu - batch_count);
+        const uint64_t load = std::max<uint64_t>(1, (batch_elems + spare - 1) / spare);
         auto blocks_of = [&](uint64_t n) {
             const uint64_t by_size = std::max<uint64_t>(1, (n + per_block - 1) / per_block);
-            const uint64_t by_share = batch_elems ? std::max<uint64_t>(1, ((uint64_t)ctx->num_cu * n + batch_elems / 2) / batch_elems) : 1;
+            const uint64_t by_share = std::max<uint64_t>(1, (n + load - 1) / load);
             return (int)std::min<uint64_t>((uint64_t)ctx->num_cu, std::min(by_size, by_share));
         };
         for (int m = 0; m < kKldBatchMax && t0 + m < count; ++m) batch_blocks += (uint64_t)blocks_of(items[t0 + m].n);
+        // Every group of rows repeats the per-element work that the rows share (rounding bits, scaled values), so the rows
+        // are split over several blocks only when the batch leaves CUs idle.
         const int want_groups = (int)std::max<uint64_t>(1, (2 * (uint64_t)ctx->num_cu + batch_blocks - 1) / std::max<uint64_t>(batch_blocks, 1));
         while (b.count < kKldBatchMax && t0 + b.count < count) {
             const adapt_kld_item &src = items[t0 + b.count];
@@ -715,16 +868,17 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, 
             if (per_row + 16 > kLdsBudget) break;
             KldBatchItem it;
             it.w = src.w; it.n = src.n; it.stream = src.stream; it.il = src.il; it.bins = src.bins;
+            it.range = ranges ? ranges[t0 + b.count] : nullptr;
             it.kld = kld + (size_t)(t0 + b.count) * ncand;
             it.sel = sel + 2 * (t0 + b.count);
             it.hist_x = blocks_of(src.n);
-            it.range_blocks = (int)std::min<uint64_t>((uint64_t)ctx->num_cu * 4, std::max<uint64_t>(1, (src.n / 4 + kRangeThreads - 1) / kRangeThreads));
+            it.range_blocks = it.range ? 0 : (int)std::min<uint64_t>((uint64_t)ctx->num_cu * 4, std::max<uint64_t>(1, (src.n / 4 + kRangeThreads - 1) / kRangeThreads));
             it.nchunks = (src.bins + kChunk - 1) / kChunk;
             int rpg = (int)std::min<size_t>(rows, kLdsBudget / per_row);
             rpg = std::max(1, std::min(rpg, (rows + want_groups - 1) / want_groups));      // a small batch splits the candidates
             it.rows_per_group = rpg;
             it.groups = (rows + rpg - 1) / rpg;
-            const size_t need = a256(sizeof(KldPlan)) + a256((size_t)it.range_blocks * 8) + a256((size_t)ncand * it.nchunks * 16) +
+            const size_t need = a256(sizeof(KldPlan)) + a256((size_t)it.range_blocks * 8) + kl_region_bytes(ncand, it.nchunks, src.bins) +
                                 a256((size_t)it.hist_x * rows * src.bins * 4);
             if (off + need > scratch_bytes(ctx)) {
                 if (b.count == 0) return ADAPT_EWORKSPACE;
@@ -733,19 +887,21 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, int count, 
             it.off_plan = off;
             it.off_range = it.off_plan + a256(sizeof(KldPlan));
             it.off_klpart = it.off_range + a256((size_t)it.range_blocks * 8);
-            it.off_slabs = it.off_klpart + a256((size_t)ncand * it.nchunks * 16);
+            it.off_slabs = it.off_klpart + kl_region_bytes(ncand, it.nchunks, src.bins);
             off += need;
-            b.first_range[b.count] = nr; b.first_hist[b.count] = nh; b.first_final[b.count] = nf;
+            b.first_range[b.count] = nr; b.first_hist[b.count] = nh; b.first_sum[b.count] = nsum; b.first_final[b.count] = nf;
             nr += (unsigned)it.range_blocks;
             nh += (unsigned)(it.hist_x * it.groups);
-            nf += (unsigned)(it.nchunks * ncand);
+            nsum += (unsigned)(it.nchunks * rows);
+            nf += (unsigned)it.nchunks;
             lds_max = std::max(lds_max, (size_t)rpg * per_row + 16);
             b.item[b.count++] = it;
         }
-        for (int i = b.count; i < kKldBatchMax; ++i) { b.first_range[i] = b.first_hist[i] = b.first_final[i] = 0xffffffffu; }
-        hipLaunchKernelGGL(kld_range_batched_kernel, dim3(nr), dim3(kRangeThreads), 0, ctx->stream, b);
+        for (int i = b.count; i < kKldBatchMax; ++i) { b.first_range[i] = b.first_hist[i] = b.first_sum[i] = b.first_final[i] = 0xffffffffu; }
+        if (nr) hipLaunchKernelGGL(kld_range_batched_kernel, dim3(nr), dim3(kRangeThreads), 0, ctx->stream, b);
         hipLaunchKernelGGL(kld_hist_batched_kernel, dim3(nh), dim3(threads), lds_max, ctx->stream, b);
-        hipLaunchKernelGGL(kld_final_batched_kernel, dim3(nf), dim3(kChunk * kFinalGroups), 0, ctx->stream, b);
+        hipLaunchKernelGGL(kld_sum_batched_kernel, dim3(nsum), dim3(kChunk), 0, ctx->stream, b);
+        hipLaunchKernelGGL(kld_final_batched_kernel, dim3(nf), dim3(kChunk), 0, ctx->stream, b);
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return hip_status(ctx, e);
         t0 += b.count;
     }
@@ -761,7 +917,7 @@ static size_t need_of_tensor(int num_cu, uint64_t n, int ncand, int bins)
     const uint64_t hist_grid = std::min<uint64_t>((uint64_t)num_cu, std::max<uint64_t>(1, (n + per_block - 1) / per_block));
     const uint64_t range_grid = std::min<uint64_t>((uint64_t)num_cu * 4, std::max<uint64_t>(1, (n / 4 + kRangeThreads - 1) / kRangeThreads));
     const size_t nchunks = (size_t)(bins + kChunk - 1) / kChunk;
-    return a256(sizeof(KldPlan)) + a256((size_t)range_grid * 8) + a256((size_t)ncand * nchunks * 16) +
+    return a256(sizeof(KldPlan)) + a256((size_t)range_grid * 8) + kl_region_bytes(ncand, (int)nchunks, bins) +
            a256((size_t)hist_grid * (size_t)(ncand + 1) * (size_t)bins * 4);
 }
 
@@ -824,5 +980,20 @@ extern "C" int adapt_kld_precision_search_batched(adapt_ctx *ctx, const adapt_kl
         if (items[t].n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     }
     if (hipError_t e = allow_hist_lds(ctx); e != hipSuccess) return hip_status(ctx, e);
-    return search_batch(ctx, items, count, wl_lo, wl_hi, eps, alpha, mode, seed, kld, sel);
+    return search_batch(ctx, items, nullptr, count, wl_lo, wl_hi, eps, alpha, mode, seed, kld, sel);
+}
+
+extern "C" int adapt_kld_precision_search_batched_ranged(adapt_ctx *ctx, const adapt_kld_item *items, const float *const *ranges,
+                                                         int count, int wl_lo, int wl_hi, double eps, double alpha, int mode,
+                                                         uint64_t seed, double *kld, int32_t *sel)
+{
+    if (!ctx || count < 0 || (count > 0 && (!items || !ranges || !kld || !sel))) return ADAPT_EINVAL;
+    if (((uintptr_t)kld & 7) || ((uintptr_t)sel & 3)) return ADAPT_EINVAL;
+    for (int t = 0; t < count; ++t) {
+        if (int s = check_search_args(wl_lo, wl_hi, items[t].il, items[t].bins, eps, alpha, mode)) return s;
+        if (items[t].n > 0 && (!items[t].w || !aligned16(items[t].w))) return ADAPT_EINVAL;
+        if (items[t].n > ((uint64_t)1 << 40) || ((uintptr_t)ranges[t] & 3)) return ADAPT_EINVAL;
+    }
+    if (hipError_t e = allow_hist_lds(ctx); e != hipSuccess) return hip_status(ctx, e);
+    return search_batch(ctx, items, ranges, count, wl_lo, wl_hi, eps, alpha, mode, seed, kld, sel);
 }

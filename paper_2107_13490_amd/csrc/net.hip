@@ -465,6 +465,7 @@ struct NetLayer {
     int g_wl;                 // word length of the gradient codes
     int g_slot;               // with precision switching: the ring slot that holds them (never one of the window's)
     int fl_in, fl_w;          // FL of the layer's input activations and of its weight codes
+    bool range_valid;         // the statistics record holds the range of the master weights as they are now
     // precision switch (Alg. 2)
     int lb, res;
     std::vector<int> win;     // ring slots of the window, oldest first
@@ -530,6 +531,7 @@ size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vecto
         y.off_kld = off_kld + (size_t)l * kKldStride;
         y.off_ring = lb_upr ? take((size_t)(lb_upr + 1) * y.slot_bytes) : 0;
         y.g_wl = 0;
+        y.range_valid = false;
         if (l > 0) max_in = std::max(max_in, y.n_in);
         max_w = std::max(max_w, y.n_w);
     }
@@ -685,6 +687,7 @@ extern "C" int adapt_net_quantize_weights(adapt_net *net, adapt_rng rng)
 {
     if (!net || !rng_ok(rng)) return ADAPT_EINVAL;
     const int count = (int)net->L.size();
+    for (NetLayer &y : net->L) y.range_valid = false;          // the caller may have written the master weights
     adapt_quantize_item items[kMaxLayers];
     for (int l = 0; l < count; ++l) {
         const NetLayer &y = net->L[l];
@@ -846,6 +849,7 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
     int group_base = 0;
     for (int lo = 2; lo <= sp.wl_hi; ++lo) {
         adapt_kld_item items[kMaxLayers];
+        const float *ranges[kMaxLayers];       // the last update left the range of the weights it wrote
         int members[kMaxLayers], m = 0;
         for (int l = 0; l < count; ++l) {
             const NetLayer &y = net->L[l];
@@ -855,14 +859,15 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
             items[m].il = y.fmt.wl - y.fmt.fl;
             items[m].bins = res_new[l];
             items[m].stream = rng.stream + (uint64_t)(8 * l + 6);
+            ranges[m] = y.range_valid ? &reinterpret_cast<const adapt_net_stats *>(net->ws + y.off_stat)->range_lo : nullptr;
             members[m++] = l;
         }
         if (m == 0) continue;
         // the t-th member of a group writes kld[16 * (group_base + t)...] and sel[2 * (group_base + t)]
         double *gk = reinterpret_cast<double *>(net->ws + net->off_kld_group);
         int32_t *gs = reinterpret_cast<int32_t *>(net->ws + net->off_sel_group);
-        if (int s = adapt_kld_precision_search_batched(ctx, items, m, lo, sp.wl_hi, sp.eps, -1.0, rng.mode, rng.seed,
-                                                       gk + (size_t)group_base * 16, gs + 2 * (size_t)group_base))
+        if (int s = adapt_kld_precision_search_batched_ranged(ctx, items, ranges, m, lo, sp.wl_hi, sp.eps, -1.0, rng.mode, rng.seed,
+                                                              gk + (size_t)group_base * 16, gs + 2 * (size_t)group_base))
             return s;
         for (int t = 0; t < m; ++t) group_slot[members[t]] = group_base + t;
         group_base += m;
@@ -928,13 +933,15 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
     if (!net || !rng_ok(rng)) return ADAPT_EINVAL;
     const int count = (int)net->L.size();
     for (int l = 0; l < count; ++l) {
-        const NetLayer &y = net->L[l];
+        NetLayer &y = net->L[l];
+        y.range_valid = false;
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
         if (y.g_wl == 0) return ADAPT_EINVAL;                        // no backward pass yet
         const adapt_fmt fg = {y.g_wl, 0};                            // the gradient keeps the word length it was made with
         if (int s = adapt_sgd_update_quantize(net->ctx, y.w, y.n_w, net->ws + y.g_off(), fg, &st->g_sumsq, opt, y.fmt,
                                               slot_rng(rng, l, 3), net->ws + y.off_qw, &st->nnz, &st->range_lo))
             return s;
+        y.range_valid = true;
     }
     net->forward_done = net->backward_done = false;
     return ADAPT_OK;

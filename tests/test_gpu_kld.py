@@ -77,6 +77,45 @@ def test_non_finite_elements_are_ignored():
     _compare(w, 2, 16, 2, 100, 1e-3)
 
 
+@pytest.mark.parametrize("bins", [64, 2048, 50000])
+def test_pruned_tensors_with_many_zeros(bins):
+    # zeros of either sign are counted outside the histogram atomics: large and small tensors, a range that excludes
+    # zero on one side, a tensor that is all zeros but one element, and the path whose rows do not fit LDS
+    g = np.random.default_rng(21)
+    for n, frac in ((200003 if bins < 50000 else 20003, 0.5), (9001, 0.9), (17, 0.5)):      # (slabs of wide rows are large)
+        w = (g.standard_normal(n) * 0.05).astype(np.float32)
+        w[g.random(n) < frac] = 0.0
+        w[::5][w[::5] == 0] = -0.0
+        _compare(w, 4, 16, 3, bins, 1e-2, seed=3, stream=n)
+    w = np.abs(g.standard_normal(5000) * 0.1).astype(np.float32)         # zero is the minimum
+    w[::3] = 0.0
+    _compare(w, 4, 16, 3, bins, 1e-2)
+    w = np.zeros(4096, np.float32)
+    w[77] = -0.375
+    _compare(w, 2, 12, 2, bins, 1e-2)
+
+
+def test_batched_with_known_ranges():
+    g = np.random.default_rng(22)
+    ws = [(g.standard_normal(n) * s).astype(np.float32) for n, s in ((5000, 0.05), (300000, 0.1), (70001, 0.2), (64, 1.0))]
+    ws[1][g.random(ws[1].size) < 0.3] = 0.0
+    ils, bins, streams = [2, 3, 2, 2], [100, 2048, 2048, 64], [1, 2, 3, 4]
+    devs = [dev(w) for w in ws]
+    exact = [dev(np.array([w.min(), w.max()], np.float32)) for w in ws]
+    wide = dev(np.array([-1.0, 1.0], np.float32))                    # a range that is wider than the tensor's own
+    refs = [orc.kld_precision_search(w, 4, 14, ils[t], bins[t], 1e-3, None, pkg.SR, 5, streams[t]) for t, w in enumerate(ws)]
+    for ranges in (exact, [exact[0], None, exact[2], None], [None] * 4):
+        kld, sel = ctx().kld_precision_search_batched(devs, ils, bins, streams, 4, 14, 1e-3, seed=5, ranges=ranges)
+        kld, sel = host(kld), host(sel)
+        for t, ref in enumerate(refs):
+            assert (np.abs(kld[t] - ref["kld"]) <= 1e-5 * np.abs(ref["kld"]) + 1e-12).all(), t
+            assert sel[t].tolist() == [ref["wl_sel"], ref["fl_sel"]], t
+    # a given range is used as it is: the same as the single-tensor entry point with that range
+    kld, sel = ctx().kld_precision_search_batched(devs[:1], ils[:1], bins[:1], streams[:1], 4, 14, 1e-3, seed=5, ranges=[wide])
+    one = ctx().kld_precision_search_ranged(devs[0], wide, 4, 14, ils[0], bins[0], 1e-3, seed=5, stream=streams[0])
+    assert np.array_equal(host(kld)[0], host(one["kld"])) and host(sel)[0].tolist() == host(one["sel"]).tolist()
+
+
 def test_degenerate_inputs():
     _compare(np.full(1000, 0.25, dtype=np.float32), 3, 8, 2, 100, 1e-3)
     _compare(np.array([np.nan, np.inf, -np.inf, np.nan], dtype=np.float32), 3, 8, 2, 100, 1e-3)
