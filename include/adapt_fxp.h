@@ -394,6 +394,65 @@ int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n
 int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *b, adapt_fmt fb,
                        size_t n, adapt_fmt fo, adapt_rng rng, int relu, void *out);
 
+/* ---- batch normalisation, global average pooling and gradient merging on fixed-point codes ----
+ * The paper trains residual networks with batch normalisation (Sec. 4.1) and does not say how these
+ * steps are carried out on codes; the rules below are this library's.  Tensors are NHWC, so the
+ * `channels` codes of one position are contiguous ("a row"); channels % 8 == 0, channels <= 4096,
+ * rows <= 2^23.
+ *
+ * adapt_bn_forward (training mode: statistics of the batch).  Per channel k over the `rows` codes of
+ * y (format fy): S1 = sum y, S2 = sum y^2 (exact); in fp64, one rounded operation at a time:
+ *   mean = S1/rows, var = max(S2/rows - mean*mean, 0), sig = sqrt(var + eps 4^fy.fl),
+ *   alpha = gamma 2^fo.fl / sig, off = beta 2^fo.fl - mean alpha;
+ *   FA = clamp(30 - E, 0, 30) where max_k |alpha_k| = f 2^E, 1/2 <= f < 1 (30 if that maximum is 0);
+ *   A_k = rint(alpha_k 2^FA) clamped to +-2^30, B_k = rint(off_k 2^FA) clamped to +-2^61;
+ *   out = requantize(A_k y + B_k + res 2^(fo.fl + FA - fres.fl), FA) in format fo (the epilogue rule of
+ *   the contractions: SR or nearest, optional ReLU, saturation; a negative exponent of the shortcut is
+ *   an arithmetic right shift).  res = NULL: no shortcut.
+ * gamma, beta: device float[channels] (finite).  state: device, 64-byte aligned,
+ * adapt_bn_state_bytes(channels) bytes, written here and read by adapt_bn_backward; layout: a 64-byte
+ * header (int32 channels, fl_y, fl_o, FA, FB, 3 reserved; uint64 rows), then mean[K], sig[K], alpha[K]
+ * (double), B[K], R[K] (int64), A[K], P[K], Q[K] (int32).  Three launches. */
+size_t adapt_bn_state_bytes(int channels);
+int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, size_t rows, int channels,
+                     const float *gamma, const float *beta, double eps, const void *res,
+                     adapt_fmt fres, adapt_fmt fo, adapt_rng rng, int relu, void *out, void *state);
+
+/* Backward of the same normalisation from dz, the wl_dz-bit codes of the gradient at its output (any
+ * power-of-two scale 2^-e).  D1 = sum dz, D2 = sum dz y (exact);
+ *   dgamma = (D2 - mean D1)/sig, dbeta = D1 (device double[channels], in units of 2^-e);
+ *   c1 = D1/rows, c2 = dgamma/(rows sig); P = alpha, Q = -(alpha c2), R = alpha (mean c2 - c1);
+ *   FB from max(|P|,|Q|) as FA above; codes P^, Q^ (+-2^30), R^ (+-2^61) = rint(. 2^FB);
+ *   dy = requantize_fit(P^ dz + Q^ y + R^) in wl_out bits (the rule of adapt_requantize_fit).
+ * The gradient with respect to y's values is dy 2^-(e + FB - shift + fo.fl - fy.fl).  shift: device
+ * int32 or NULL; e_in / e_out: device int64 or NULL, *e_out = *e_in + FB - shift + fo.fl - fy.fl
+ * (e_in = NULL counts as 0).  y, fy, rows, channels as in the forward call.  Four launches. */
+int adapt_bn_backward(adapt_ctx *ctx, const void *dz, int wl_dz, const void *y, adapt_fmt fy,
+                      size_t rows, int channels, void *state, int wl_out, adapt_rng rng, void *dy,
+                      double *dgamma, double *dbeta, int32_t *shift, const int64_t *e_in,
+                      int64_t *e_out);
+
+/* gamma[k] = fma(-lr, (float)(dgamma[k] / |dgamma|_2), gamma[k]) and the same for beta, fp32; the
+ * norms are summed in channel order in fp64; a zero or non-finite norm leaves that vector alone. */
+int adapt_bn_update(adapt_ctx *ctx, float *gamma, float *beta, const double *dgamma,
+                    const double *dbeta, int channels, double lr);
+
+/* Global average pooling of an n x hw x c tensor of codes (hw a power of two, c % 8 == 0):
+ * out[n, c] = requantize(sum over the hw positions, log2 hw), same format.  Backward: da[n, p, c] =
+ * dout[n, c] for every position p; the caller adds log2 hw to the gradient's exponent. */
+int adapt_gap_fwd(adapt_ctx *ctx, const void *a, adapt_fmt f, int n, int hw, int c, adapt_rng rng,
+                  void *out);
+int adapt_gap_bwd(adapt_ctx *ctx, const void *dout, int wl, int n, int hw, int c, void *da);
+
+/* Sum of two gradient tensors a 2^-e_a + b 2^-e_b (codes of wl_a / wl_b bits, exponents in device
+ * memory; NULL counts as 0) as wl_out-bit codes: the exact sum on the grid of max(e_a, e_b), then the
+ * rule of adapt_requantize_fit; *e_out = max(e_a, e_b) - shift.  If the exponents differ by more than
+ * 40, the tensor with the larger exponent (far smaller values) is left out.  b = NULL: a alone is
+ * refitted to wl_out bits.  out may be a or b.  Two launches. */
+int adapt_grad_add(adapt_ctx *ctx, const void *a, int wl_a, const int64_t *e_a, const void *b,
+                   int wl_b, const int64_t *e_b, size_t n, int wl_out, adapt_rng rng, void *out,
+                   int32_t *shift, int64_t *e_out);
+
 /* A feed-forward chain of convolution / fully connected layers (FC: h = w = r = s = 1, pad 0, c =
  * the flattened NHWC input), each optionally followed by ReLU (fused into the contraction's
  * epilogue) and then by 2x2/2 max-pooling.  All layers share the batch size conv.n, and the

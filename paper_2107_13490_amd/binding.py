@@ -174,6 +174,14 @@ def load_library():
     lib.adapt_relu_pool_bwd.argtypes = [vp, vp, vp, Fmt, i, i, i, i, i, i, vp]
     lib.adapt_requantize_fit.argtypes = [vp, vp, i, sz, i, Rng, vp, vp, vp]
     lib.adapt_residual_add.argtypes = [vp, vp, Fmt, vp, Fmt, sz, Fmt, Rng, i, vp]
+    lib.adapt_bn_state_bytes.argtypes = [i]
+    lib.adapt_bn_state_bytes.restype = sz
+    lib.adapt_bn_forward.argtypes = [vp, vp, Fmt, sz, i, vp, vp, dbl, vp, Fmt, Fmt, Rng, i, vp, vp]
+    lib.adapt_bn_backward.argtypes = [vp, vp, i, vp, Fmt, sz, i, vp, i, Rng, vp, vp, vp, vp, vp, vp]
+    lib.adapt_bn_update.argtypes = [vp, vp, vp, vp, vp, i, dbl]
+    lib.adapt_gap_fwd.argtypes = [vp, vp, Fmt, i, i, i, Rng, vp]
+    lib.adapt_gap_bwd.argtypes = [vp, vp, i, i, i, i, vp]
+    lib.adapt_grad_add.argtypes = [vp, vp, i, vp, vp, i, vp, sz, i, Rng, vp, vp, vp]
     lib.adapt_net_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i, i]
     lib.adapt_net_workspace_bytes.restype = sz
     lib.adapt_net_create.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), C.POINTER(SwitchParams), vp, sz, C.POINTER(vp)]
@@ -577,6 +585,68 @@ class Context:
         _check(self._lib.adapt_residual_add(self._h, _ptr(a), Fmt(*fa), _ptr(b), Fmt(*fb), a.numel(), Fmt(*fo),
                                             Rng(mode, seed, stream), int(relu), _ptr(out)), "adapt_residual_add")
         return out
+
+
+    # -- batch normalisation, pooling, gradient merging -------------------------------------------
+    def bn_forward(self, y, fy, gamma, beta, eps, fo, relu=False, res=None, fres=None, mode=SR, seed=0, stream=0, out=None,
+                   state=None):
+        """y: codes (..., channels).  Returns (out codes in format fo, state: uint8 device tensor for bn_backward)."""
+        torch = self._torch
+        k = y.shape[-1]
+        rows = y.numel() // k
+        if out is None:
+            out = torch.empty(y.shape, dtype=self.storage_dtype(fo[0]), device=y.device)
+        if state is None:
+            state = torch.empty(max(self._lib.adapt_bn_state_bytes(k), 64), dtype=torch.uint8, device=y.device)
+        _check(self._lib.adapt_bn_forward(self._h, _ptr(y), Fmt(*fy), rows, k, _ptr(gamma), _ptr(beta), float(eps),
+                                          _ptr(res) if res is not None else None, Fmt(*(fres or (8, 0))), Fmt(*fo),
+                                          Rng(mode, seed, stream), int(relu), _ptr(out), _ptr(state)), "adapt_bn_forward")
+        return out, state
+
+    def bn_backward(self, dz, wl_dz, y, fy, state, wl_out, mode=SR, seed=0, stream=0, e_in=None):
+        """Returns dict(dy, dgamma, dbeta (float64), shift (int32[1]), e_out (int64[1]))."""
+        torch = self._torch
+        k = y.shape[-1]
+        rows = y.numel() // k
+        dy = torch.empty(y.shape, dtype=self.storage_dtype(wl_out), device=y.device)
+        dg = torch.empty(k, dtype=torch.float64, device=y.device)
+        db = torch.empty(k, dtype=torch.float64, device=y.device)
+        shift = torch.empty(1, dtype=torch.int32, device=y.device)
+        e_out = torch.empty(1, dtype=torch.int64, device=y.device)
+        _check(self._lib.adapt_bn_backward(self._h, _ptr(dz), wl_dz, _ptr(y), Fmt(*fy), rows, k, _ptr(state), wl_out,
+                                           Rng(mode, seed, stream), _ptr(dy), _ptr(dg), _ptr(db), _ptr(shift),
+                                           _ptr(e_in) if e_in is not None else None, _ptr(e_out)), "adapt_bn_backward")
+        return {"dy": dy, "dgamma": dg, "dbeta": db, "shift": shift, "e_out": e_out}
+
+    def bn_update(self, gamma, beta, dgamma, dbeta, lr):
+        _check(self._lib.adapt_bn_update(self._h, _ptr(gamma), _ptr(beta), _ptr(dgamma), _ptr(dbeta), gamma.numel(), float(lr)),
+               "adapt_bn_update")
+
+    def gap_fwd(self, a, fmt, mode=SR, seed=0, stream=0):
+        """a: (n, h, w, c) codes -> (n, c) codes of the mean over the positions."""
+        n, h, w, c = a.shape
+        out = self._torch.empty((n, c), dtype=a.dtype, device=a.device)
+        _check(self._lib.adapt_gap_fwd(self._h, _ptr(a), Fmt(*fmt), n, h * w, c, Rng(mode, seed, stream), _ptr(out)), "adapt_gap_fwd")
+        return out
+
+    def gap_bwd(self, dout, wl, h, w):
+        n, c = dout.shape
+        da = self._torch.empty((n, h, w, c), dtype=dout.dtype, device=dout.device)
+        _check(self._lib.adapt_gap_bwd(self._h, _ptr(dout), wl, n, h * w, c, _ptr(da)), "adapt_gap_bwd")
+        return da
+
+    def grad_add(self, a, wl_a, e_a, b, wl_b, e_b, wl_out, mode=SR, seed=0, stream=0, out=None):
+        """e_a, e_b: int64[1] device tensors (or None = 0); b may be None.  Returns (codes, shift int32[1], e_out int64[1])."""
+        torch = self._torch
+        if out is None:
+            out = torch.empty(a.shape, dtype=self.storage_dtype(wl_out), device=a.device)
+        shift = torch.empty(1, dtype=torch.int32, device=a.device)
+        e_out = torch.empty(1, dtype=torch.int64, device=a.device)
+        _check(self._lib.adapt_grad_add(self._h, _ptr(a), wl_a, _ptr(e_a) if e_a is not None else None,
+                                        _ptr(b) if b is not None else None, wl_b, _ptr(e_b) if e_b is not None else None,
+                                        a.numel(), wl_out, Rng(mode, seed, stream), _ptr(out), _ptr(shift), _ptr(e_out)),
+               "adapt_grad_add")
+        return out, shift, e_out
 
 
 class Net:

@@ -1,0 +1,727 @@
+// Fixed-point batch normalisation, global average pooling and the merge of two gradient tensors: the
+// element-wise steps that the chained training step (Alg. 1) needs on the residual networks of
+// Sec. 4.1.  The paper does not say how these are done on fixed-point codes; the rules implemented:
+//
+//   forward    per channel k over the m rows of the convolution output y (codes, NHWC so a row is one
+//              position): S1 = sum y, S2 = sum y^2 as exact integers; mean = S1/m,
+//              var = max(S2/m - mean*mean, 0), sig = sqrt(var + eps 4^FL_y), alpha = gamma 2^FL_o / sig,
+//              off = beta 2^FL_o - mean alpha in fp64 (one correctly rounded operation at a time, no
+//              contraction); FA = clamp(30 - E, 0, 30) with max |alpha| = f 2^E, 1/2 <= f < 1;
+//              A = rint(alpha 2^FA) (|A| <= 2^30), B = rint(off 2^FA) (|B| <= 2^61);
+//              out = requantize(A y + B [+ shortcut on that grid], FA) to <WL_o,FL_o>, SR, optional ReLU
+//   backward   D1 = sum dz, D2 = sum dz y (exact); dgamma = (D2 - mean D1)/sig, dbeta = D1;
+//              c1 = D1/m, c2 = dgamma/(m sig); P = alpha, Q = -(alpha c2), R = alpha (mean c2 - c1);
+//              FB from max(|P|,|Q|) like FA; exact acc = P^ dz + Q^ y + R^ stored in WL bits with the
+//              fitting shift: exponent e + FB - shift + FL_o - FL_y
+//   update     gamma and beta each step against their gradient divided by its 2-norm over the channels
+//              (the rule of Sec. 3.3 "Dealing with Fixed-Points Limited Range" for weights)
+//   pooling    mean over the h*w (a power of two) positions: integer sum, requantize by log2(h*w)
+//   merge      exact sum of two gradient tensors on the finer of their grids, fitting shift; exponents
+//              more than 40 apart: the far smaller tensor is left out
+//
+// All element-wise kernels read every input once and write every output once in 8- or 16-byte accesses
+// (HBM-bound); the statistics kernels keep a thread's eight channels in registers when the channel count
+// divides the thread stride, and fall back to LDS atomics otherwise.
+#include <algorithm>
+#include <cmath>
+
+#include "common.hpp"
+#include "context.hpp"
+#include "fit.hpp"
+
+// every fp64 operation of the coefficient kernels is rounded on its own: no fused multiply-adds
+#pragma clang fp contract(off)
+
+namespace adapt {
+
+constexpr int kBnThreads = 256;
+constexpr int kBnMaxChannels = 4096;
+
+struct BnHeader {
+    int32_t channels, fl_y, fl_o, fa, fb, pad[3];
+    unsigned long long rows;
+};
+constexpr size_t kBnHeaderBytes = 64;
+static_assert(sizeof(BnHeader) <= kBnHeaderBytes, "header");
+
+// state: header | mean[K] sig[K] alpha[K] (fp64) | B[K] R[K] (int64) | A[K] P[K] Q[K] (int32)
+struct BnState {
+    BnHeader *h;
+    double *mean, *sig, *alpha;
+    long long *B, *R;
+    int32_t *A, *P, *Q;
+};
+__host__ __device__ inline size_t bn_state_bytes(int k) { return kBnHeaderBytes + (size_t)k * (3 * 8 + 2 * 8 + 3 * 4); }
+__host__ __device__ inline BnState bn_state(void *p, int k)
+{
+    char *c = static_cast<char *>(p);
+    BnState s;
+    s.h = reinterpret_cast<BnHeader *>(c);
+    s.mean = reinterpret_cast<double *>(c + kBnHeaderBytes);
+    s.sig = s.mean + k;
+    s.alpha = s.sig + k;
+    s.B = reinterpret_cast<long long *>(s.alpha + k);
+    s.R = s.B + k;
+    s.A = reinterpret_cast<int32_t *>(s.R + k);
+    s.P = s.A + k;
+    s.Q = s.P + k;
+    return s;
+}
+
+// ---- per-channel sums -----------------------------------------------------------------------------------
+// MODE 0: (sum y, sum y^2); MODE 1: (sum dz, sum dz*y).  One group = 8 consecutive elements = 8 consecutive
+// channels of one row (channels % 8 == 0).  REG: the thread stride in groups is a multiple of channels/8, so a
+// thread meets the same eight channels every time and sums them in registers.
+template <typename TA, typename TB, int MODE, bool REG>
+__global__ void __launch_bounds__(kBnThreads)
+bn_sums_kernel(const TA *__restrict__ a, const TB *__restrict__ b, uint64_t groups, int channels, long long *__restrict__ partial)
+{
+    extern __shared__ long long lsum[];          // [2 * channels]
+    for (int i = threadIdx.x; i < 2 * channels; i += kBnThreads) lsum[i] = 0;
+    __syncthreads();
+    const uint32_t cg = (uint32_t)channels >> 3;
+    const uint64_t first = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kBnThreads;
+    if (REG) {
+        long long s1[8], s2[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s1[e] = s2[e] = 0;
+        for (uint64_t g = first; g < groups; g += stride) {
+            int x[8], y[8];
+            load_codes8<TA>(a, g, x);
+            if (MODE == 1) load_codes8<TB>(b, g, y);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                s1[e] += x[e];
+                s2[e] += (long long)(MODE == 1 ? x[e] * y[e] : x[e] * x[e]);
+            }
+        }
+        if (first < groups) {
+            const uint32_t c0 = (uint32_t)(first % cg) * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                atomicAdd(reinterpret_cast<unsigned long long *>(&lsum[c0 + e]), (unsigned long long)s1[e]);
+                atomicAdd(reinterpret_cast<unsigned long long *>(&lsum[channels + c0 + e]), (unsigned long long)s2[e]);
+            }
+        }
+    } else {
+        for (uint64_t g = first; g < groups; g += stride) {
+            int x[8], y[8];
+            load_codes8<TA>(a, g, x);
+            if (MODE == 1) load_codes8<TB>(b, g, y);
+            const uint32_t c0 = (uint32_t)(g % cg) * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                atomicAdd(reinterpret_cast<unsigned long long *>(&lsum[c0 + e]), (unsigned long long)(long long)x[e]);
+                atomicAdd(reinterpret_cast<unsigned long long *>(&lsum[channels + c0 + e]),
+                          (unsigned long long)(long long)(MODE == 1 ? x[e] * y[e] : x[e] * x[e]));
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * channels; i += kBnThreads) partial[(size_t)blockIdx.x * 2 * channels + i] = lsum[i];
+}
+
+// clamp(30 - E, 0, 30) for vmax = f 2^E, 1/2 <= f < 1; 30 for vmax = 0 or infinite
+__device__ inline int coef_exponent(double vmax)
+{
+    if (!(vmax > 0.0) || vmax == (double)INFINITY) return 30;
+    int e;
+    (void)frexp(vmax, &e);
+    return min(max(30 - e, 0), 30);
+}
+
+__device__ inline long long rint_clamped(double v, int sh, double lim)
+{
+    const double t = rint(ldexp(v, sh));
+    return (long long)fmin(fmax(t, -lim), lim);      // NaN -> -lim (the callers' inputs are finite)
+}
+
+// block-wide maximum of doubles >= 0 (all threads get it)
+__device__ inline double block_max_f64(double v, double *sm)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off, 64));
+    if ((threadIdx.x & (kWave - 1)) == 0) sm[threadIdx.x / kWave] = v;
+    __syncthreads();
+    v = sm[0];
+    for (int i = 1; i < (int)blockDim.x / kWave; ++i) v = fmax(v, sm[i]);
+    __syncthreads();
+    return v;
+}
+
+// One block: totals of the block partials, statistics and forward coefficients.
+__global__ void __launch_bounds__(1024)
+bn_coef_fwd_kernel(const long long *__restrict__ partial, int nparts, int channels, unsigned long long rows, int fl_y, int fl_o,
+                   const float *__restrict__ gamma, const float *__restrict__ beta, double eps, void *state)
+{
+    __shared__ double sm[16];
+    const BnState st = bn_state(state, channels);
+    const double m = (double)rows;
+    double amax = 0.0;
+    for (int k = threadIdx.x; k < channels; k += blockDim.x) {
+        long long s1 = 0, s2 = 0;
+        for (int p = 0; p < nparts; ++p) {
+            s1 += partial[(size_t)p * 2 * channels + k];
+            s2 += partial[(size_t)p * 2 * channels + channels + k];
+        }
+        const double mean = (double)s1 / m;
+        const double ex2 = (double)s2 / m;
+        const double var = fmax(ex2 - mean * mean, 0.0);
+        const double sig = sqrt(var + ldexp(eps, 2 * fl_y));
+        const double alpha = ((ldexp((double)gamma[k], fl_o)) / (sig));
+        st.mean[k] = mean;
+        st.sig[k] = sig;
+        st.alpha[k] = alpha;
+        amax = fmax(amax, fabs(alpha));
+    }
+    amax = block_max_f64(amax, sm);
+    const int fa = coef_exponent(amax);
+    for (int k = threadIdx.x; k < channels; k += blockDim.x) {
+        const double alpha = st.alpha[k];
+        const double off = ((ldexp((double)beta[k], fl_o)) - (((st.mean[k]) * (alpha))));
+        st.A[k] = (int32_t)rint_clamped(alpha, fa, 1073741824.0);
+        st.B[k] = rint_clamped(off, fa, 2305843009213693952.0);
+    }
+    if (threadIdx.x == 0) {
+        st.h->channels = channels; st.h->fl_y = fl_y; st.h->fl_o = fl_o; st.h->fa = fa; st.h->fb = 0; st.h->rows = rows;
+    }
+}
+
+// One block: totals of (sum dz, sum dz*y), the parameter gradients and the backward coefficients.
+__global__ void __launch_bounds__(1024)
+bn_coef_bwd_kernel(const long long *__restrict__ partial, int nparts, int channels, void *state, double *__restrict__ dgamma,
+                   double *__restrict__ dbeta)
+{
+    __shared__ double sm[16];
+    const BnState st = bn_state(state, channels);
+    const double m = (double)st.h->rows;
+    double pmax = 0.0;
+    for (int k = threadIdx.x; k < channels; k += blockDim.x) {
+        long long d1 = 0, d2 = 0;
+        for (int p = 0; p < nparts; ++p) {
+            d1 += partial[(size_t)p * 2 * channels + k];
+            d2 += partial[(size_t)p * 2 * channels + channels + k];
+        }
+        const double mean = st.mean[k], sig = st.sig[k], alpha = st.alpha[k];
+        const double dg = ((double)d2 - mean * (double)d1) / sig;
+        const double c1 = (((double)d1) / (m));
+        const double c2 = dg / (m * sig);
+        const double q = -((alpha) * (c2));
+        const double r = alpha * (mean * c2 - c1);
+        dgamma[k] = dg;
+        dbeta[k] = (double)d1;
+        // Q and R wait in the slots of their codes until the common exponent is known
+        reinterpret_cast<double *>(st.R)[k] = r;
+        reinterpret_cast<double *>(st.B)[k] = q;       // B is not needed after the forward pass
+        pmax = fmax(pmax, fmax(fabs(alpha), fabs(q)));
+    }
+    pmax = block_max_f64(pmax, sm);
+    const int fb = coef_exponent(pmax);
+    for (int k = threadIdx.x; k < channels; k += blockDim.x) {
+        const double q = reinterpret_cast<const double *>(st.B)[k], r = reinterpret_cast<const double *>(st.R)[k];
+        st.P[k] = (int32_t)rint_clamped(st.alpha[k], fb, 1073741824.0);
+        st.Q[k] = (int32_t)rint_clamped(q, fb, 1073741824.0);
+        st.R[k] = rint_clamped(r, fb, 2305843009213693952.0);
+    }
+    if (threadIdx.x == 0) st.h->fb = fb;
+}
+
+// ---- forward: out = requantize(A y + B [+ shortcut], FA) ---------------------------------------------------
+struct BnApplyArgs {
+    const void *y, *res;
+    void *out;
+    const void *state;
+    uint64_t groups;
+    int channels, wl, relu, mode, has_res, fl_res;
+    uint64_t seed, stream;
+};
+
+template <typename TY, typename TR, typename TO>
+__global__ void __launch_bounds__(kBnThreads) bn_apply_kernel(const BnApplyArgs a)
+{
+    extern __shared__ long long coef[];          // B[channels] then A[channels] (int32)
+    const BnState st = bn_state(const_cast<void *>(a.state), a.channels);
+    int32_t *la = reinterpret_cast<int32_t *>(coef + a.channels);
+    for (int i = threadIdx.x; i < a.channels; i += kBnThreads) { coef[i] = st.B[i]; la[i] = st.A[i]; }
+    __syncthreads();
+    const int fa = st.h->fa;
+    const int rsh = st.h->fl_o + fa - a.fl_res;                  // alignment of the shortcut: left shift, or floor
+    const uint32_t cg = (uint32_t)a.channels >> 3;
+    const TY *y = static_cast<const TY *>(a.y);
+    const TR *res = static_cast<const TR *>(a.res);
+    TO *out = static_cast<TO *>(a.out);
+    const uint64_t first = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kBnThreads;
+    for (uint64_t g = first; g < a.groups; g += stride) {
+        int x[8], s[8], code[8];
+        load_codes8<TY>(y, g, x);
+        if (a.has_res) load_codes8<TR>(res, g, s);
+        uint32_t r[8];
+        if (a.mode == ADAPT_SR) {
+            const u32x4 blk = rounding_block(a.seed, a.stream, g);
+            r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
+            r[4] = blk.z & 0xffffu; r[5] = blk.z >> 16; r[6] = blk.w & 0xffffu; r[7] = blk.w >> 16;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = 0x8000u;
+        }
+        const uint32_t c0 = (uint32_t)(g % cg) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            long long acc = (long long)la[c0 + e] * x[e] + coef[c0 + e];
+            if (a.has_res) acc += rsh >= 0 ? (long long)((unsigned long long)(long long)s[e] << rsh) : ((long long)s[e] >> -rsh);
+            code[e] = requantize_one(acc, fa, a.wl, a.relu, r[e]);
+        }
+        store_codes8<TO>(out, g, code);
+    }
+}
+
+// ---- backward: acc = P dz + Q y + R, fitted ----------------------------------------------------------------
+struct BnBwdArgs {
+    const void *dz, *y;
+    void *dy;
+    const void *state;
+    uint64_t groups;
+    int channels, wl, mode;
+    uint64_t seed, stream;
+    uint64_t *part;
+    int nparts;
+    int32_t *shift_out;
+    const long long *e_in;
+    long long *e_out;
+};
+
+template <typename TD, typename TY, typename TO, bool FIT>
+__global__ void __launch_bounds__(kBnThreads) bn_bwd_kernel(const BnBwdArgs a)
+{
+    extern __shared__ long long coef[];          // R[channels], then P[channels], Q[channels] (int32)
+    __shared__ uint64_t sm[kBnThreads / kWave];
+    const BnState st = bn_state(const_cast<void *>(a.state), a.channels);
+    int32_t *lp = reinterpret_cast<int32_t *>(coef + a.channels), *lq = lp + a.channels;
+    for (int i = threadIdx.x; i < a.channels; i += kBnThreads) { coef[i] = st.R[i]; lp[i] = st.P[i]; lq[i] = st.Q[i]; }
+    int shift = 0;
+    if (FIT) {
+        uint64_t m = 0;
+        for (int i = threadIdx.x; i < a.nparts; i += kBnThreads) m = a.part[i] > m ? a.part[i] : m;
+        m = block_max_u64(m, sm, kBnThreads / kWave);
+        shift = fit_shift_of(m, a.wl);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            if (a.shift_out) *a.shift_out = shift;
+            if (a.e_out) *a.e_out = (a.e_in ? *a.e_in : 0) + st.h->fb - shift + st.h->fl_o - st.h->fl_y;
+        }
+    } else {
+        __syncthreads();
+    }
+    const int qhi = (1 << (a.wl - 1)) - 1, qlo = -(1 << (a.wl - 1));
+    const uint32_t cg = (uint32_t)a.channels >> 3;
+    const TD *dz = static_cast<const TD *>(a.dz);
+    const TY *y = static_cast<const TY *>(a.y);
+    TO *dy = static_cast<TO *>(a.dy);
+    uint64_t mx = 0;
+    const uint64_t first = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kBnThreads;
+    for (uint64_t g = first; g < a.groups; g += stride) {
+        int d[8], x[8];
+        load_codes8<TD>(dz, g, d);
+        load_codes8<TY>(y, g, x);
+        const uint32_t c0 = (uint32_t)(g % cg) * 8;
+        long long acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = (long long)lp[c0 + e] * d[e] + (long long)lq[c0 + e] * x[e] + coef[c0 + e];
+        if (!FIT) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t v = magnitude(acc[e]);
+                mx = v > mx ? v : mx;
+            }
+        } else {
+            uint32_t r[8];
+            if (a.mode == ADAPT_SR) {
+                const u32x4 blk = rounding_block(a.seed, a.stream, g);
+                r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
+                r[4] = blk.z & 0xffffu; r[5] = blk.z >> 16; r[6] = blk.w & 0xffffu; r[7] = blk.w >> 16;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] = 0x8000u;
+            }
+            int code[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) code[e] = fit_one(acc[e], shift, r[e], qlo, qhi);
+            store_codes8<TO>(dy, g, code);
+        }
+    }
+    if (!FIT) {
+        mx = block_max_u64(mx, sm, kBnThreads / kWave);
+        if (threadIdx.x == 0) a.part[blockIdx.x] = mx;
+    }
+}
+
+// ---- update of gamma and beta -------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+bn_update_kernel(float *gamma, float *beta, const double *__restrict__ dgamma, const double *__restrict__ dbeta, int channels, float lr)
+{
+    __shared__ double nrm[2];
+    if (threadIdx.x < 2) {                           // the two sums of squares, each in channel order
+        const double *d = threadIdx.x == 0 ? dgamma : dbeta;
+        double t = 0.0;
+        for (int k = 0; k < channels; ++k) t = t + d[k] * d[k];
+        nrm[threadIdx.x] = sqrt(t);
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < channels; k += blockDim.x) {
+        if (nrm[0] > 0.0 && nrm[0] < (double)INFINITY) gamma[k] = __builtin_fmaf(-lr, (float)((dgamma[k]) / (nrm[0])), gamma[k]);
+        if (nrm[1] > 0.0 && nrm[1] < (double)INFINITY) beta[k] = __builtin_fmaf(-lr, (float)((dbeta[k]) / (nrm[1])), beta[k]);
+    }
+}
+
+// ---- global average pooling ----------------------------------------------------------------------------------
+// out[n, c] = requantize(sum over hw positions, log2 hw); one thread per 8 channels of one sample
+template <typename T>
+__global__ void __launch_bounds__(kBnThreads)
+gap_fwd_kernel(const T *__restrict__ a, T *__restrict__ out, uint32_t n, uint32_t hw, uint32_t cg, int sh, int wl, int mode,
+               uint64_t seed, uint64_t stream)
+{
+    const uint32_t total = n * cg;
+    for (uint32_t i = blockIdx.x * kBnThreads + threadIdx.x; i < total; i += gridDim.x * kBnThreads) {
+        const uint32_t s = i / cg, c = i - s * cg;
+        long long acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0;
+        for (uint32_t p = 0; p < hw; ++p) {
+            int x[8];
+            load_codes8<T>(a, ((uint64_t)s * hw + p) * cg + c, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += x[e];
+        }
+        int code[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) code[e] = requantize_one(acc[e], sh, wl, 0, rounding_bits_of(seed, stream, (uint64_t)i * 8 + e, mode));
+        store_codes8<T>(out, i, code);
+    }
+}
+
+// da[n, p, c] = dout[n, c]
+template <typename T>
+__global__ void __launch_bounds__(kBnThreads)
+gap_bwd_kernel(const T *__restrict__ dout, T *__restrict__ da, uint64_t groups, uint32_t hw, uint32_t cg)
+{
+    for (uint64_t g = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x; g < groups; g += (uint64_t)gridDim.x * kBnThreads) {
+        const uint64_t pos = g / cg;
+        const uint32_t c = (uint32_t)(g - pos * cg);
+        int x[8];
+        load_codes8<T>(dout, (pos / hw) * cg + c, x);
+        store_codes8<T>(da, g, x);
+    }
+}
+
+// ---- merge of two gradient tensors ---------------------------------------------------------------------------
+struct MergeArgs {
+    const void *a, *b;
+    void *out;
+    const long long *e_a, *e_b;
+    long long *e_out;
+    int32_t *shift_out;
+    uint64_t n;
+    int wl, mode;
+    uint64_t seed, stream;
+    uint64_t *part;
+    int nparts;
+};
+
+constexpr int kMergeMaxGap = 40;
+
+// alignment of the two tensors: left shifts (or -1: the tensor is left out) and the exponent of the sum
+__device__ __forceinline__ void merge_plan(const MergeArgs &a, int &sa, int &sb, long long &e)
+{
+    const long long ea = a.e_a ? *a.e_a : 0;
+    if (!a.b) { sa = 0; sb = -1; e = ea; return; }
+    const long long eb = a.e_b ? *a.e_b : 0;
+    if (ea - eb > kMergeMaxGap) { sa = -1; sb = 0; e = eb; }
+    else if (eb - ea > kMergeMaxGap) { sa = 0; sb = -1; e = ea; }
+    else { e = ea > eb ? ea : eb; sa = (int)(e - ea); sb = (int)(e - eb); }
+}
+
+template <typename TA, typename TB, typename TO, bool FIT>
+__global__ void __launch_bounds__(kBnThreads) merge_kernel(const MergeArgs a)
+{
+    __shared__ uint64_t sm[kBnThreads / kWave];
+    int sa, sb;
+    long long e;
+    merge_plan(a, sa, sb, e);
+    int shift = 0;
+    if (FIT) {
+        uint64_t m = 0;
+        for (int i = threadIdx.x; i < a.nparts; i += kBnThreads) m = a.part[i] > m ? a.part[i] : m;
+        m = block_max_u64(m, sm, kBnThreads / kWave);
+        shift = fit_shift_of(m, a.wl);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            if (a.shift_out) *a.shift_out = shift;
+            if (a.e_out) *a.e_out = e - shift;
+        }
+    }
+    const int qhi = (1 << (a.wl - 1)) - 1, qlo = -(1 << (a.wl - 1));
+    const TA *pa = static_cast<const TA *>(a.a);
+    const TB *pb = static_cast<const TB *>(a.b);
+    TO *out = static_cast<TO *>(a.out);
+    auto sum_of = [&](int x, int y) {
+        long long s = 0;
+        if (sa >= 0) s += (long long)((unsigned long long)(long long)x << sa);
+        if (sb >= 0) s += (long long)((unsigned long long)(long long)y << sb);
+        return s;
+    };
+    uint64_t mx = 0;
+    const uint64_t groups = a.n >> 3;
+    const uint64_t first = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kBnThreads;
+    for (uint64_t g = first; g < groups; g += stride) {
+        int x[8], y[8];
+        load_codes8<TA>(pa, g, x);
+        if (a.b) load_codes8<TB>(pb, g, y);
+        else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) y[i] = 0;
+        }
+        if (!FIT) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint64_t v = magnitude(sum_of(x[i], y[i]));
+                mx = v > mx ? v : mx;
+            }
+        } else {
+            uint32_t r[8];
+            if (a.mode == ADAPT_SR) {
+                const u32x4 blk = rounding_block(a.seed, a.stream, g);
+                r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
+                r[4] = blk.z & 0xffffu; r[5] = blk.z >> 16; r[6] = blk.w & 0xffffu; r[7] = blk.w >> 16;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = 0x8000u;
+            }
+            int code[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) code[i] = fit_one(sum_of(x[i], y[i]), shift, r[i], qlo, qhi);
+            store_codes8<TO>(out, g, code);
+        }
+    }
+    if ((a.n & 7) && first == 0)
+        for (uint64_t i = groups << 3; i < a.n; ++i) {
+            const long long s = sum_of((int)pa[i], a.b ? (int)pb[i] : 0);
+            if (!FIT) { const uint64_t v = magnitude(s); mx = v > mx ? v : mx; }
+            else out[i] = (TO)fit_one(s, shift, rounding_bits_of(a.seed, a.stream, i, a.mode), qlo, qhi);
+        }
+    if (!FIT) {
+        mx = block_max_u64(mx, sm, kBnThreads / kWave);
+        if (threadIdx.x == 0) a.part[blockIdx.x] = mx;
+    }
+}
+
+static int bn_grid(const adapt_ctx *ctx, uint64_t groups)
+{
+    const uint64_t blocks = (groups + kBnThreads - 1) / kBnThreads;
+    return (int)std::min<uint64_t>(std::max<uint64_t>(blocks, 1), (uint64_t)ctx->num_cu * 8);
+}
+// blocks of the statistics launch: each flushes 2 * channels sums, so fewer and longer-running ones
+static int sums_grid(const adapt_ctx *ctx, uint64_t groups, int channels, bool &reg)
+{
+    int grid = (int)std::min<uint64_t>(std::max<uint64_t>((groups + kBnThreads * 4 - 1) / (kBnThreads * 4), 1), (uint64_t)ctx->num_cu * 2);
+    const uint64_t cg = (uint64_t)channels / 8;
+    // register sums need a thread stride (grid * threads groups) that is a multiple of channels / 8
+    reg = false;
+    if (cg <= kBnThreads && kBnThreads % cg == 0) reg = true;
+    else if ((uint64_t)grid * kBnThreads % cg == 0) reg = true;
+    return grid;
+}
+static bool rng_ok(adapt_rng r) { return r.mode == ADAPT_SR || r.mode == ADAPT_RN_HALF_UP; }
+
+size_t ws_need_bn(int num_cu, int channels)
+{
+    return (size_t)num_cu * 2 * 2 * (size_t)channels * 8 + (size_t)num_cu * 8 * 8 + 256;
+}
+
+}  // namespace adapt
+
+using namespace adapt;
+
+extern "C" size_t adapt_bn_state_bytes(int channels)
+{
+    return channels > 0 && channels <= kBnMaxChannels ? ((bn_state_bytes(channels) + 255) & ~(size_t)255) : 0;
+}
+
+template <int MODE>
+static int launch_sums(adapt_ctx *ctx, const void *a, int es_a, const void *b, int es_b, uint64_t groups, int channels, long long *partial,
+                       int &grid)
+{
+    bool reg;
+    grid = sums_grid(ctx, groups, channels, reg);
+    const size_t lds = (size_t)2 * channels * 8;
+    const dim3 g(grid), t(kBnThreads);
+#define ADAPT_SUMS(TA, TB)                                                                                                          \
+    do {                                                                                                                            \
+        if (reg) hipLaunchKernelGGL((bn_sums_kernel<TA, TB, MODE, true>), g, t, lds, ctx->stream, (const TA *)a, (const TB *)b, groups, channels, partial); \
+        else hipLaunchKernelGGL((bn_sums_kernel<TA, TB, MODE, false>), g, t, lds, ctx->stream, (const TA *)a, (const TB *)b, groups, channels, partial);    \
+    } while (0)
+    if (es_a == 1 && es_b == 1) ADAPT_SUMS(int8_t, int8_t);
+    else if (es_a == 1) ADAPT_SUMS(int8_t, int16_t);
+    else if (es_b == 1) ADAPT_SUMS(int16_t, int8_t);
+    else ADAPT_SUMS(int16_t, int16_t);
+#undef ADAPT_SUMS
+    return ADAPT_OK;
+}
+
+extern "C" int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, size_t rows, int channels, const float *gamma,
+                                const float *beta, double eps, const void *res, adapt_fmt fres, adapt_fmt fo, adapt_rng rng, int relu,
+                                void *out, void *state)
+{
+    if (!ctx || !fmt_ok(fy) || !fmt_ok(fo) || !rng_ok(rng) || !(eps >= 0.0) || (res && !fmt_ok(fres))) return ADAPT_EINVAL;
+    if (channels < 8 || channels > kBnMaxChannels || (channels & 7)) return ADAPT_EUNSUPPORTED;
+    if (rows < 1 || rows > ((size_t)1 << 23)) return ADAPT_EUNSUPPORTED;         // sums of squares stay below 2^53
+    if (!y || !out || !state || !gamma || !beta || !aligned16(y) || !aligned16(out) || ((uintptr_t)state & 63) || (res && !aligned16(res)))
+        return ADAPT_EINVAL;
+    const uint64_t groups = (uint64_t)rows * channels / 8;
+    if (ws_need_bn(ctx->num_cu, channels) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    long long *partial = reinterpret_cast<long long *>(scratch(ctx));
+    int grid;
+    launch_sums<0>(ctx, y, storage_bytes(fy), y, storage_bytes(fy), groups, channels, partial, grid);
+    hipLaunchKernelGGL(bn_coef_fwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, partial, grid, channels, (unsigned long long)rows, fy.fl,
+                       fo.fl, gamma, beta, eps, state);
+    BnApplyArgs a;
+    a.y = y; a.res = res; a.out = out; a.state = state; a.groups = groups; a.channels = channels; a.wl = fo.wl; a.relu = relu != 0;
+    a.mode = rng.mode; a.has_res = res != nullptr; a.fl_res = res ? fres.fl : 0; a.seed = rng.seed; a.stream = rng.stream;
+    const size_t lds = (size_t)channels * 12;
+    const dim3 g(bn_grid(ctx, groups)), t(kBnThreads);
+    const int sel = (storage_bytes(fy) == 2) * 4 + ((res ? storage_bytes(fres) : 1) == 2) * 2 + (storage_bytes(fo) == 2);
+#define ADAPT_APPLY(TY, TR, TO) hipLaunchKernelGGL((bn_apply_kernel<TY, TR, TO>), g, t, lds, ctx->stream, a)
+    switch (sel) {
+    case 0: ADAPT_APPLY(int8_t, int8_t, int8_t); break;
+    case 1: ADAPT_APPLY(int8_t, int8_t, int16_t); break;
+    case 2: ADAPT_APPLY(int8_t, int16_t, int8_t); break;
+    case 3: ADAPT_APPLY(int8_t, int16_t, int16_t); break;
+    case 4: ADAPT_APPLY(int16_t, int8_t, int8_t); break;
+    case 5: ADAPT_APPLY(int16_t, int8_t, int16_t); break;
+    case 6: ADAPT_APPLY(int16_t, int16_t, int8_t); break;
+    default: ADAPT_APPLY(int16_t, int16_t, int16_t); break;
+    }
+#undef ADAPT_APPLY
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_bn_backward(adapt_ctx *ctx, const void *dz, int wl_dz, const void *y, adapt_fmt fy, size_t rows, int channels,
+                                 void *state, int wl_out, adapt_rng rng, void *dy, double *dgamma, double *dbeta, int32_t *shift,
+                                 const int64_t *e_in, int64_t *e_out)
+{
+    if (!ctx || !fmt_ok(fy) || wl_dz < 2 || wl_dz > 16 || wl_out < 2 || wl_out > 16 || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (channels < 8 || channels > kBnMaxChannels || (channels & 7)) return ADAPT_EUNSUPPORTED;
+    if (rows < 1 || rows > ((size_t)1 << 23)) return ADAPT_EUNSUPPORTED;
+    if (!dz || !y || !dy || !state || !dgamma || !dbeta || !aligned16(dz) || !aligned16(y) || !aligned16(dy) || ((uintptr_t)state & 63))
+        return ADAPT_EINVAL;
+    if (((uintptr_t)dgamma & 7) || ((uintptr_t)dbeta & 7) || ((uintptr_t)shift & 3) || ((uintptr_t)e_in & 7) || ((uintptr_t)e_out & 7))
+        return ADAPT_EINVAL;
+    const uint64_t groups = (uint64_t)rows * channels / 8;
+    if (ws_need_bn(ctx->num_cu, channels) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    long long *partial = reinterpret_cast<long long *>(scratch(ctx));
+    const int es_d = wl_dz <= 8 ? 1 : 2, es_y = storage_bytes(fy), es_o = wl_out <= 8 ? 1 : 2;
+    int grid;
+    launch_sums<1>(ctx, dz, es_d, y, es_y, groups, channels, partial, grid);
+    hipLaunchKernelGGL(bn_coef_bwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, partial, grid, channels, state, dgamma, dbeta);
+    BnBwdArgs a;
+    a.dz = dz; a.y = y; a.dy = dy; a.state = state; a.groups = groups; a.channels = channels; a.wl = wl_out; a.mode = rng.mode;
+    a.seed = rng.seed; a.stream = rng.stream; a.shift_out = shift;
+    a.e_in = reinterpret_cast<const long long *>(e_in); a.e_out = reinterpret_cast<long long *>(e_out);
+    const int grid1 = (int)std::min<uint64_t>(std::max<uint64_t>((groups + kBnThreads - 1) / kBnThreads, 1), (uint64_t)ctx->num_cu * 4);
+    a.part = reinterpret_cast<uint64_t *>(scratch(ctx) + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels * 8);
+    a.nparts = grid1;
+    const size_t lds = (size_t)channels * 16;
+    const dim3 t(kBnThreads), g2(bn_grid(ctx, groups));
+    const int sel = (es_d == 2) * 4 + (es_y == 2) * 2 + (es_o == 2);
+#define ADAPT_BWD(TD, TY, TO)                                                                                     \
+    do {                                                                                                          \
+        hipLaunchKernelGGL((bn_bwd_kernel<TD, TY, TO, false>), dim3(grid1), t, lds, ctx->stream, a);              \
+        hipLaunchKernelGGL((bn_bwd_kernel<TD, TY, TO, true>), g2, t, lds, ctx->stream, a);                        \
+    } while (0)
+    switch (sel) {
+    case 0: ADAPT_BWD(int8_t, int8_t, int8_t); break;
+    case 1: ADAPT_BWD(int8_t, int8_t, int16_t); break;
+    case 2: ADAPT_BWD(int8_t, int16_t, int8_t); break;
+    case 3: ADAPT_BWD(int8_t, int16_t, int16_t); break;
+    case 4: ADAPT_BWD(int16_t, int8_t, int8_t); break;
+    case 5: ADAPT_BWD(int16_t, int8_t, int16_t); break;
+    case 6: ADAPT_BWD(int16_t, int16_t, int8_t); break;
+    default: ADAPT_BWD(int16_t, int16_t, int16_t); break;
+    }
+#undef ADAPT_BWD
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_bn_update(adapt_ctx *ctx, float *gamma, float *beta, const double *dgamma, const double *dbeta, int channels,
+                               double lr)
+{
+    if (!ctx || !gamma || !beta || !dgamma || !dbeta || channels < 1 || channels > kBnMaxChannels || !(lr == lr)) return ADAPT_EINVAL;
+    if (((uintptr_t)dgamma & 7) || ((uintptr_t)dbeta & 7)) return ADAPT_EINVAL;
+    hipLaunchKernelGGL(bn_update_kernel, dim3(1), dim3(1024), 0, ctx->stream, gamma, beta, dgamma, dbeta, channels, (float)lr);
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_gap_fwd(adapt_ctx *ctx, const void *a, adapt_fmt f, int n, int hw, int c, adapt_rng rng, void *out)
+{
+    if (!ctx || !fmt_ok(f) || !rng_ok(rng) || n < 0 || hw < 1 || c < 1) return ADAPT_EINVAL;
+    if ((hw & (hw - 1)) || (c & 7) || hw > (1 << 20) || (uint64_t)n * c >= ((uint64_t)1 << 31)) return ADAPT_EUNSUPPORTED;
+    if (n == 0) return ADAPT_OK;
+    if (!a || !out || !aligned16(a) || !aligned16(out)) return ADAPT_EINVAL;
+    int sh = 0;
+    while ((1 << sh) < hw) ++sh;
+    const uint32_t cg = (uint32_t)c / 8;
+    const dim3 g(bn_grid(ctx, (uint64_t)n * cg)), t(kBnThreads);
+    if (storage_bytes(f) == 1)
+        hipLaunchKernelGGL(gap_fwd_kernel<int8_t>, g, t, 0, ctx->stream, (const int8_t *)a, (int8_t *)out, (uint32_t)n, (uint32_t)hw, cg, sh,
+                           f.wl, rng.mode, rng.seed, rng.stream);
+    else
+        hipLaunchKernelGGL(gap_fwd_kernel<int16_t>, g, t, 0, ctx->stream, (const int16_t *)a, (int16_t *)out, (uint32_t)n, (uint32_t)hw, cg,
+                           sh, f.wl, rng.mode, rng.seed, rng.stream);
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_gap_bwd(adapt_ctx *ctx, const void *dout, int wl, int n, int hw, int c, void *da)
+{
+    if (!ctx || wl < 2 || wl > 16 || n < 0 || hw < 1 || c < 1) return ADAPT_EINVAL;
+    if ((hw & (hw - 1)) || (c & 7)) return ADAPT_EUNSUPPORTED;
+    if (n == 0) return ADAPT_OK;
+    if (!dout || !da || !aligned16(dout) || !aligned16(da)) return ADAPT_EINVAL;
+    const uint32_t cg = (uint32_t)c / 8;
+    const uint64_t groups = (uint64_t)n * hw * cg;
+    const dim3 g(bn_grid(ctx, groups)), t(kBnThreads);
+    if (wl <= 8) hipLaunchKernelGGL(gap_bwd_kernel<int8_t>, g, t, 0, ctx->stream, (const int8_t *)dout, (int8_t *)da, groups, (uint32_t)hw, cg);
+    else hipLaunchKernelGGL(gap_bwd_kernel<int16_t>, g, t, 0, ctx->stream, (const int16_t *)dout, (int16_t *)da, groups, (uint32_t)hw, cg);
+    return hip_status(ctx, hipGetLastError());
+}
+
+extern "C" int adapt_grad_add(adapt_ctx *ctx, const void *a, int wl_a, const int64_t *e_a, const void *b, int wl_b, const int64_t *e_b,
+                              size_t n, int wl_out, adapt_rng rng, void *out, int32_t *shift, int64_t *e_out)
+{
+    if (!ctx || wl_a < 2 || wl_a > 16 || wl_out < 2 || wl_out > 16 || (b && (wl_b < 2 || wl_b > 16)) || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
+    if (((uintptr_t)e_a & 7) || ((uintptr_t)e_b & 7) || ((uintptr_t)e_out & 7) || ((uintptr_t)shift & 3)) return ADAPT_EINVAL;
+    if (n > 0 && (!a || !out || !aligned16(a) || !aligned16(out) || (b && !aligned16(b)))) return ADAPT_EINVAL;
+    const uint64_t groups = ((uint64_t)n + 7) >> 3;
+    const int grid1 = (int)std::min<uint64_t>(std::max<uint64_t>((groups + kBnThreads - 1) / kBnThreads, 1), (uint64_t)ctx->num_cu * 4);
+    if ((size_t)grid1 * 8 > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    MergeArgs m;
+    m.a = a; m.b = b; m.out = out; m.e_a = reinterpret_cast<const long long *>(e_a); m.e_b = reinterpret_cast<const long long *>(e_b);
+    m.e_out = reinterpret_cast<long long *>(e_out); m.shift_out = shift; m.n = n; m.wl = wl_out; m.mode = rng.mode; m.seed = rng.seed;
+    m.stream = rng.stream; m.part = reinterpret_cast<uint64_t *>(scratch(ctx)); m.nparts = grid1;
+    const dim3 t(kBnThreads), g2(bn_grid(ctx, groups));
+    const int sel = (wl_a > 8) * 4 + ((b ? wl_b : 8) > 8) * 2 + (wl_out > 8);
+#define ADAPT_MERGE(TA, TB, TO)                                                                               \
+    do {                                                                                                      \
+        hipLaunchKernelGGL((merge_kernel<TA, TB, TO, false>), dim3(grid1), t, 0, ctx->stream, m);             \
+        hipLaunchKernelGGL((merge_kernel<TA, TB, TO, true>), g2, t, 0, ctx->stream, m);                       \
+    } while (0)
+    switch (sel) {
+    case 0: ADAPT_MERGE(int8_t, int8_t, int8_t); break;
+    case 1: ADAPT_MERGE(int8_t, int8_t, int16_t); break;
+    case 2: ADAPT_MERGE(int8_t, int16_t, int8_t); break;
+    case 3: ADAPT_MERGE(int8_t, int16_t, int16_t); break;
+    case 4: ADAPT_MERGE(int16_t, int8_t, int8_t); break;
+    case 5: ADAPT_MERGE(int16_t, int8_t, int16_t); break;
+    case 6: ADAPT_MERGE(int16_t, int16_t, int8_t); break;
+    default: ADAPT_MERGE(int16_t, int16_t, int16_t); break;
+    }
+#undef ADAPT_MERGE
+    return hip_status(ctx, hipGetLastError());
+}

@@ -22,6 +22,7 @@
 
 #include "common.hpp"
 #include "context.hpp"
+#include "fit.hpp"
 #include "grad_window.hpp"
 
 namespace adapt {
@@ -103,18 +104,6 @@ relu_pool_bwd_kernel(const T *__restrict__ da, const T *__restrict__ y, T *__res
     }
 }
 
-__device__ __forceinline__ uint64_t magnitude(long long v) { return v < 0 ? 0ull - (uint64_t)v : (uint64_t)v; }
-
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint64_t o = __shfl_xor((unsigned long long)v, off, 64);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-
 template <typename AccT>
 __device__ __forceinline__ void load_acc8(const AccT *acc, uint64_t grp, long long (&v)[8]);
 template <>
@@ -180,24 +169,6 @@ struct FitArgs {
     int32_t *shift_out;
     unsigned long long *sumsq;
 };
-
-// The requantize rule for a shift that was fitted to the tensor: |acc| >> shift is below 2^(wl-1)
-// <= 2^15, so after one 64-bit shift everything is 32-bit arithmetic.  floor((acc + r') / 2^s) is
-// taken as (acc >> s) + carry of the dropped bits plus r', which cannot overflow.
-__device__ __forceinline__ int fit_one(long long acc, int shift, uint32_t r16, int qlo, int qhi)
-{
-    int q;
-    if (shift == 0) {
-        q = (int)acc;
-    } else if (shift <= 16) {
-        const uint32_t low = (uint32_t)acc & ((1u << shift) - 1u);
-        q = (int)(acc >> shift) + (int)((low + (r16 >> (16 - shift))) >> shift);
-    } else {
-        const int t = (int)(acc >> (shift - 16));            // |t| < 2^(wl-1+16) <= 2^31
-        q = (t >> 16) + (int)((((uint32_t)t & 0xffffu) + r16) >> 16);
-    }
-    return min(max(q, qlo), qhi);
-}
 
 // codes = requantize(acc, shift) with shift = max(0, bit_length(max |acc|) - (wl-1)); every block
 // derives the shift from the partial maxima itself
