@@ -476,7 +476,14 @@ enum { ADAPT_NT_INPUT = 0,   /* quantized network input (layer ignored) */
        ADAPT_NT_DA = 4,      /* gradient w.r.t. the layer output (not written for the last layer) */
        ADAPT_NT_QW = 5,      /* weight codes */
        ADAPT_NT_G = 6,       /* weight-gradient codes */
-       ADAPT_NT_STATS = 7 }; /* adapt_net_stats */
+       ADAPT_NT_STATS = 7,   /* adapt_net_stats */
+       ADAPT_NT_YC = 8,      /* batch-norm layers: the convolution output that is normalised */
+       ADAPT_NT_DYC = 9,     /* gradient w.r.t. the convolution output (= NT_DY without batch norm) */
+       ADAPT_NT_BN = 10,     /* batch-norm layers: the state of adapt_bn_forward (bytes) */
+       ADAPT_NT_EXP = 11,    /* int64[4]: exponents of the gradient codes of the last backward pass: of NT_DA
+                              * (for the last layer: dlogits_fl), of NT_DYC after batch norm, of NT_G, one spare */
+       ADAPT_NT_DGAMMA = 12, /* batch-norm layers: double[k], gradient of gamma in units of 2^-e(NT_DA) */
+       ADAPT_NT_DBETA = 13 };
 
 /* Hyper-parameters of the precision switch (Sec. 3.3 "Strategy, Resolution and Lookback"): bounds and
  * start values of the lookback lb^l and the resolution r^l (the number of bins of the KL search),
@@ -490,6 +497,27 @@ typedef struct {
     double gamma, eps;
     int buff, wl_lo, wl_hi, strategy_init;
 } adapt_switch_params;
+
+/* A network as a graph of layers (the residual networks of Sec. 4.1): layer l is a convolution of
+ * the output of layer `src` (-1: the layer before, or the network input for layer 0), optionally
+ * followed by batch normalisation (bn; with it the ReLU comes after the normalisation and `res` >= 0
+ * adds the output of layer `res` inside it: adapt_bn_forward), then ReLU, then 2x2 max-pooling (pool)
+ * or global average pooling (gap: adapt_gap_fwd).  src, res < l; every layer but the last needs a
+ * consumer, at most four.  Backward, a layer's output gradient is the sum of what its consumers hand
+ * back: the first contribution is stored (refitted with adapt_grad_add when it comes from a layer of
+ * another word length), later ones are added with adapt_grad_add; exponents stay in device memory
+ * (ADAPT_NT_EXP).  Random streams of the additional steps: rng.stream + 2^20 + 8 l + slot with slot
+ * 0 = batch-norm output, 1 = batch-norm data gradient, 2 = average pooling, 3 + k = the k-th contribution
+ * to the gradient of layer l's output. */
+typedef struct { adapt_conv_desc conv; int relu, pool, bn, src, res, gap; } adapt_node_desc;
+size_t adapt_graph_workspace_bytes(const adapt_node_desc *nodes, int count, int lb_upr);
+/* As adapt_net_create.  gammas, betas: HOST arrays of `count` device float[k] pointers (read for the
+ * layers with bn; the arrays may be NULL when no layer has it), owned by the caller and updated in
+ * place by adapt_net_update (adapt_bn_update with the step's learning rate).  bn_eps >= 0. */
+int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights,
+                       float *const *gammas, float *const *betas, double bn_eps,
+                       const adapt_switch_params *sp, void *workspace, size_t workspace_bytes,
+                       adapt_net **out);
 
 /* Bytes of device workspace the chain needs (activations, gradients, codes of weights and
  * gradients at int16 storage so that word lengths may change, two accumulator buffers, and
@@ -537,9 +565,10 @@ int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogits_fl, adap
  *   strategy   adapt_strategy_next(strategy, mean of the last ceil(mean_l lb^l) earlier losses, loss);
  *              unchanged on the first call
  *   per layer  the weight-gradient codes join the layer's window (at most lb_upr entries, oldest
- *              dropped) with the exponent that follows from the fitting shifts:
+ *              dropped) with the exponent that follows from the fitting shifts (kept in device memory,
+ *              ADAPT_NT_EXP; on a plain chain:
  *                e(dy_last) = dlogits_fl, e(g_l) = e(dy_l) + FL(a_{l-1}) - shift_w(l),
- *                e(dy_{l-1}) = e(dy_l) + FL(W^_l) - shift_a(l);
+ *                e(dy_{l-1}) = e(dy_l) + FL(W^_l) - shift_a(l));
  *              ds = adapt_gradient_diversity of the most recent min(len, lb^l) entries with
  *              fl_k = e_k - min e.  The aligned sum of the window is kept in 32-bit integers: while
  *              sum_k 2^(wl_k - 1 + max e - e_k) reaches 2^31 the oldest of these entries is left out

@@ -259,7 +259,7 @@ def precision_switch(st: SwitchState, fmts, weights, bwd, dlogits_fl: int, loss:
         l_avg = sum(st.losses[-k:]) / k
         st.strategy = po.adapt_strategy(st.strategy, l_avg, loss)
     st.losses.append(loss)
-    exps = gradient_exponents(fmts, bwd, dlogits_fl)
+    exps = bwd["e_g"] if "e_g" in bwd else gradient_exponents(fmts, bwd, dlogits_fl)    # a graph's backward pass gives them itself
     report = []
     for l, (wl, fl) in enumerate(fmts):
         win = st.windows[l]

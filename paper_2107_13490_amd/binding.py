@@ -95,12 +95,19 @@ class LayerDesc(C.Structure):
     _fields_ = [("conv", ConvDesc), ("relu", C.c_int), ("pool", C.c_int)]
 
 
+class NodeDesc(C.Structure):
+    """One layer of a network graph: a LayerDesc plus batch norm (bn), the layer that feeds the convolution (src, -1: the
+    one before), the layer whose output is added inside the batch norm (res, -1: none), global average pooling (gap)."""
+    _fields_ = [("conv", ConvDesc), ("relu", C.c_int), ("pool", C.c_int), ("bn", C.c_int), ("src", C.c_int), ("res", C.c_int),
+                ("gap", C.c_int)]
+
+
 class NetStats(C.Structure):
     _fields_ = [("g_sumsq", C.c_uint64), ("nnz", C.c_uint64), ("saturated", C.c_uint64), ("range_lo", C.c_float),
                 ("range_hi", C.c_float), ("shift_w", C.c_int32), ("shift_a", C.c_int32), ("reserved", C.c_int32 * 6)]
 
 
-NT_INPUT, NT_Y, NT_A, NT_DY, NT_DA, NT_QW, NT_G, NT_STATS = range(8)
+NT_INPUT, NT_Y, NT_A, NT_DY, NT_DA, NT_QW, NT_G, NT_STATS, NT_YC, NT_DYC, NT_BN, NT_EXP, NT_DGAMMA, NT_DBETA = range(14)
 
 
 class SwitchParams(C.Structure):
@@ -185,6 +192,10 @@ def load_library():
     lib.adapt_net_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i, i]
     lib.adapt_net_workspace_bytes.restype = sz
     lib.adapt_net_create.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), C.POINTER(SwitchParams), vp, sz, C.POINTER(vp)]
+    lib.adapt_graph_workspace_bytes.argtypes = [C.POINTER(NodeDesc), i, i]
+    lib.adapt_graph_workspace_bytes.restype = sz
+    lib.adapt_graph_create.argtypes = [vp, C.POINTER(NodeDesc), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), dbl,
+                                       C.POINTER(SwitchParams), vp, sz, C.POINTER(vp)]
     lib.adapt_net_precision_switch.argtypes = [vp, dbl, Rng, C.POINTER(SwitchReport), C.POINTER(i)]
     lib.adapt_net_destroy.argtypes = [vp]
     lib.adapt_net_set_format.argtypes = [vp, i, Fmt]
@@ -653,21 +664,37 @@ class Net:
     """A chained fixed-point training step (adapt_net_*).  Holds the workspace tensor and the master
     weights (fp32 device tensors, KRSC, updated in place by update())."""
 
-    def __init__(self, ctx: Context, layers, weights, switch: "SwitchParams | None" = None):
+    def __init__(self, ctx: Context, layers, weights, switch: "SwitchParams | None" = None, bn=None, bn_eps: float = 1e-5):
+        """layers: LayerDesc entries (a plain chain) or NodeDesc entries (a graph; bn = list with, per layer, a
+        (gamma, beta) pair of device fp32 tensors or None)."""
         import torch
         self._ctx, self._lib, self._torch = ctx, ctx._lib, torch
         self.layers = list(layers)
         self.weights = list(weights)
+        self.bn = list(bn) if bn is not None else None
         n = len(self.layers)
-        descs = (LayerDesc * n)(*self.layers)
-        need = self._lib.adapt_net_workspace_bytes(descs, n, switch.lb_upr if switch is not None else 0)
+        graph = any(isinstance(d, NodeDesc) for d in self.layers)
+        lb_upr = switch.lb_upr if switch is not None else 0
+        if graph:
+            descs = (NodeDesc * n)(*self.layers)
+            need = self._lib.adapt_graph_workspace_bytes(descs, n, lb_upr)
+        else:
+            descs = (LayerDesc * n)(*self.layers)
+            need = self._lib.adapt_net_workspace_bytes(descs, n, lb_upr)
         if need == 0:
             raise AdaptError(-1, "adapt_net_workspace_bytes")
         self.workspace = torch.zeros(need, dtype=torch.uint8, device=self.weights[0].device)
         wptrs = (C.c_void_p * n)(*[w.data_ptr() for w in self.weights])
         h = C.c_void_p()
-        _check(self._lib.adapt_net_create(ctx.handle, descs, n, wptrs, C.byref(switch) if switch is not None else None,
-                                          _ptr(self.workspace), need, C.byref(h)), "adapt_net_create")
+        sw = C.byref(switch) if switch is not None else None
+        if graph:
+            gp = (C.c_void_p * n)(*[(p[0].data_ptr() if p is not None else None) for p in (self.bn or [None] * n)])
+            bp = (C.c_void_p * n)(*[(p[1].data_ptr() if p is not None else None) for p in (self.bn or [None] * n)])
+            _check(self._lib.adapt_graph_create(ctx.handle, descs, n, wptrs, gp, bp, float(bn_eps), sw, _ptr(self.workspace), need,
+                                                C.byref(h)), "adapt_graph_create")
+        else:
+            _check(self._lib.adapt_net_create(ctx.handle, descs, n, wptrs, sw, _ptr(self.workspace), need, C.byref(h)),
+                   "adapt_net_create")
         self._h = h
 
     def close(self):
@@ -692,6 +719,12 @@ class Net:
         raw = self.workspace[off.value:off.value + cnt.value * es.value]
         if which == NT_STATS:
             return NetStats.from_buffer_copy(bytes(raw.cpu().numpy()))
+        if which == NT_BN:
+            return raw
+        if which == NT_EXP:
+            return raw.view(torch.int64)
+        if which in (NT_DGAMMA, NT_DBETA):
+            return raw.view(torch.float64)
         return raw.view(torch.int8 if es.value == 1 else torch.int16)
 
     def quantize_weights(self, mode=SR, seed=0, stream=0):

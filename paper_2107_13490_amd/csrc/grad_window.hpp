@@ -22,8 +22,7 @@ struct GradWindow {
 
 // Chained step, written by the host into pinned memory: the window of one layer, oldest first, whose
 // last entry is this batch's gradient.  exp[k] is the exponent e of entry k (value = code * 2^-e);
-// for the last entry it holds the part the host knows, from which the device subtracts the fitting
-// shifts of the backward pass.
+// the last entry's is not known to the host: the device takes it from the record the backward pass wrote.
 struct ChainLayerIn {
     const void *g[kGdMaxTensors];
     long long exp[kGdMaxTensors];
@@ -46,9 +45,9 @@ struct adapt_ctx;
 namespace adapt {
 
 // Enqueues the diversities of all layers of a chained step: in / out are host-pinned, device-visible
-// arrays of nlayers records, stats the layers' statistics records in device memory, win device
-// scratch for nlayers window descriptions, n[l] the element count of layer l's gradient.
-int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers, const size_t *n, const adapt_net_stats *stats,
+// arrays of nlayers records, e_g[l * e_stride] the exponent of layer l's newest gradient in device
+// memory, win device scratch for nlayers window descriptions, n[l] the element count of layer l's gradient.
+int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers, const size_t *n, const long long *e_g, size_t e_stride,
                              GradWindow *win, ChainLayerOut *out);
 
 }  // namespace adapt

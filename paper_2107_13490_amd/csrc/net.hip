@@ -168,6 +168,10 @@ struct FitArgs {
     uint64_t seed, stream;
     int32_t *shift_out;
     unsigned long long *sumsq;
+    // exponent of the codes: *e_out = (e_in ? *e_in : 0) + e_add - shift (device memory; e_out may be null)
+    const long long *e_in;
+    long long e_add;
+    long long *e_out;
 };
 
 // codes = requantize(acc, shift) with shift = max(0, bit_length(max |acc|) - (wl-1)); every block
@@ -186,7 +190,10 @@ __global__ void __launch_bounds__(kEwThreads) requant_fit_kernel(const FitArgs a
     for (int i = 1; i < kEwThreads / kWave; ++i) m = sm[i] > m ? sm[i] : m;
     const int bits = m ? 64 - __clzll((long long)m) : 0;
     const int shift = max(0, bits - (a.wl - 1));
-    if (blockIdx.x == 0 && threadIdx.x == 0 && a.shift_out) *a.shift_out = shift;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (a.shift_out) *a.shift_out = shift;
+        if (a.e_out) *a.e_out = (a.e_in ? *a.e_in : 0) + a.e_add - shift;
+    }
     __syncthreads();                                    // sm is reused below
     const int qhi = (1 << (a.wl - 1)) - 1, qlo = -(1 << (a.wl - 1));
 
@@ -358,8 +365,8 @@ extern "C" int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y
     return hip_status(ctx, hipGetLastError());
 }
 
-extern "C" int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q,
-                                    int32_t *shift, uint64_t *sumsq)
+static int requantize_fit_exp(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q, int32_t *shift,
+                              uint64_t *sumsq, const long long *e_in, long long e_add, long long *e_out)
 {
     if (!ctx || (acc_bits != 32 && acc_bits != 64) || wl < 2 || wl > 16 || !rng_ok(rng)) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
@@ -375,7 +382,7 @@ extern "C" int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bit
     unsigned long long *ss = reinterpret_cast<unsigned long long *>(sumsq);
     FitArgs a;
     a.acc = acc; a.q = q; a.part = part; a.nparts = grid1; a.n = n; a.wl = wl; a.mode = rng.mode; a.seed = rng.seed;
-    a.stream = rng.stream; a.shift_out = shift; a.sumsq = ss;
+    a.stream = rng.stream; a.shift_out = shift; a.sumsq = ss; a.e_in = e_in; a.e_add = e_add; a.e_out = e_out;
     const dim3 block(kEwThreads);
     if (acc_bits == 32) hipLaunchKernelGGL(absmax_kernel<int32_t>, dim3(grid1), block, 0, ctx->stream, (const int32_t *)acc, (uint64_t)n, part, ss);
     else hipLaunchKernelGGL(absmax_kernel<int64_t>, dim3(grid1), block, 0, ctx->stream, (const int64_t *)acc, (uint64_t)n, part, ss);
@@ -386,6 +393,15 @@ extern "C" int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bit
     else hipLaunchKernelGGL((requant_fit_kernel<int64_t, int16_t>), dim3(grid2), block, 0, ctx->stream, a);
     return hip_status(ctx, hipGetLastError());
 }
+
+extern "C" int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q,
+                                    int32_t *shift, uint64_t *sumsq)
+{
+    return requantize_fit_exp(ctx, acc, acc_bits, n, wl, rng, q, shift, sumsq, nullptr, 0, nullptr);
+}
+
+// *dst = (src ? *src : 0) + add: the exponent bookkeeping of the chained step stays on the device
+__global__ void exp_set_kernel(long long *dst, const long long *src, long long add) { *dst = (src ? *src : 0) + add; }
 
 extern "C" int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *b, adapt_fmt fb, size_t n,
                                   adapt_fmt fo, adapt_rng rng, int relu, void *out)
@@ -424,21 +440,29 @@ namespace {
 constexpr int kMaxLayers = 64;
 constexpr int kRingMax = 65;           // ring slots per layer: the longest window and the gradient being made
 constexpr size_t kStatBytes = 64;      // per layer: the adapt_net_stats record
+constexpr size_t kExpBytes = 32;       // per layer: exponents of da, of the gradient at the convolution output, of dW
+
+// random streams of the steps that only residual / batch-norm networks have
+constexpr uint64_t kStreamX = (uint64_t)1 << 20;
+enum { X_BN = 0, X_BNB = 1, X_GAP = 2, X_MERGE = 3 };
 
 struct NetLayer {
     adapt_layer_desc d;
+    int bn, src, res, gap;    // src: the layer that feeds the convolution (-1: the network input); res: shortcut layer or -1
     adapt_fmt fmt;
     float *w;                 // master weights (caller's)
+    float *gamma, *beta;      // batch-norm parameters (caller's) or null
     int p, q;                 // contraction output size
     size_t n_y, n_a, n_in, n_w;
     size_t off_y, off_a, off_dy, off_da, off_qw, off_g, off_stat, off_ring, off_ds, off_kld, off_sel;
+    size_t off_yc, off_dyc, off_bn, off_dgam, off_dbet, off_dgap, off_exp;
     // state of the last backward pass
     int g_wl;                 // word length of the gradient codes
     int g_slot;               // with precision switching: the ring slot that holds them (never one of the window's)
     int fl_in, fl_w;          // FL of the layer's input activations and of its weight codes
     bool range_valid;         // the statistics record holds the range of the master weights as they are now
     // precision switch (Alg. 2)
-    int lb, res;
+    int lb, res_bins;
     std::vector<int> win;     // ring slots of the window, oldest first
     int slot_wl[kRingMax];
     long long slot_exp[kRingMax];
@@ -452,65 +476,101 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 constexpr size_t kKldStride = 128;      // bytes per layer for the KL values of up to 15 candidates
 
-// Lays the workspace out; returns 0 for an invalid network.
-size_t plan_net(const adapt_layer_desc *descs, int count, int lb_upr, std::vector<NetLayer> &L, size_t &off_in,
-                size_t &off_accx, size_t &off_accw, size_t &off_stats, size_t &off_sel_group, size_t &off_kld_group, size_t &off_win)
+struct NetPlan {
+    size_t off_in, off_accx, off_accw, off_stats, off_sel_group, off_kld_group, off_win, off_tmp, bytes;
+};
+
+// Lays the workspace out; returns false for an invalid network.
+bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, std::vector<NetLayer> &L, NetPlan &P)
 {
-    if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64) return 0;
+    if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64) return false;
     L.assign(count, NetLayer());
-    size_t off = 0, max_in = 0, max_w = 0;
+    size_t off = 0, max_in = 0, max_w = 0, max_merge = 0;
     auto take = [&off](size_t bytes) { const size_t o = off; off += align_up(std::max<size_t>(bytes, 16)); return o; };
     const int n = descs[0].conv.n;
-    if (n < 1) return 0;
+    if (n < 1) return false;
     // records that the host reads back in one copy each: stats, diversities, selections, KL values
-    off_stats = take((size_t)count * kStatBytes);
+    P.off_stats = take((size_t)count * kStatBytes);
     const size_t off_ds = take((size_t)count * 16), off_sel = take((size_t)count * 8), off_kld = take((size_t)count * kKldStride);
-    off_sel_group = off_sel;       // the batched searches of a precision switch write their results densely, in group order
-    off_kld_group = off_kld;
-    off_win = take((size_t)count * sizeof(GradWindow));
+    P.off_sel_group = off_sel;     // the batched searches of a precision switch write their results densely, in group order
+    P.off_kld_group = off_kld;
+    P.off_win = take((size_t)count * sizeof(GradWindow));
+    const size_t off_exp = take((size_t)count * kExpBytes);
+    std::vector<int> consumers(count, 0);
     for (int l = 0; l < count; ++l) {
         const adapt_conv_desc &c = descs[l].conv;
-        if (c.n != n || c.h < 1 || c.w < 1 || c.c < 1 || c.k < 1 || c.r < 1 || c.s < 1 || c.stride < 1 || c.pad < 0) return 0;
-        if (c.h + 2 * c.pad < c.r || c.w + 2 * c.pad < c.s) return 0;
+        if (c.n != n || c.h < 1 || c.w < 1 || c.c < 1 || c.k < 1 || c.r < 1 || c.s < 1 || c.stride < 1 || c.pad < 0) return false;
+        if (c.h + 2 * c.pad < c.r || c.w + 2 * c.pad < c.s) return false;
         NetLayer &y = L[l];
-        y.d = descs[l];
+        y.d.conv = c;
+        y.d.relu = descs[l].relu;
+        y.d.pool = descs[l].pool;
+        y.bn = descs[l].bn != 0;
+        y.gap = descs[l].gap != 0;
+        y.src = descs[l].src >= 0 ? descs[l].src : l - 1;
+        y.res = descs[l].res;
+        if (y.src >= l || descs[l].src < -1 || y.res >= l || y.res < -1) return false;
+        if (y.res >= 0 && !y.bn) return false;                     // the shortcut is added inside the batch-norm output
+        if (y.gap && y.d.pool) return false;
         y.fmt = adapt_fmt{8, 4};
         y.w = nullptr;
+        y.gamma = y.beta = nullptr;
         y.p = (c.h + 2 * c.pad - c.r) / c.stride + 1;
         y.q = (c.w + 2 * c.pad - c.s) / c.stride + 1;
-        if (y.d.pool && ((y.p | y.q) & 1)) return 0;
+        if (y.d.pool && ((y.p | y.q) & 1)) return false;
+        if (y.gap && (((y.p * y.q) & (y.p * y.q - 1)) || (c.k & 7))) return false;
+        if (y.bn && ((c.k & 7) || c.k > 4096 || (size_t)n * y.p * y.q > ((size_t)1 << 23))) return false;
         y.n_in = (size_t)n * c.h * c.w * c.c;
         y.n_y = (size_t)n * y.p * y.q * c.k;
-        y.n_a = y.d.pool ? y.n_y / 4 : y.n_y;
+        y.n_a = y.d.pool ? y.n_y / 4 : y.gap ? (size_t)n * c.k : y.n_y;
         y.n_w = (size_t)c.k * c.r * c.s * c.c;
-        if (l > 0 && L[l - 1].n_a != y.n_in) return 0;            // the output of a layer is the next one's input
+        if (y.src >= 0 && L[y.src].n_a != y.n_in) return false;   // the output of the source layer is what this one reads
+        if (y.res >= 0 && L[y.res].n_a != y.n_y) return false;
+        if (y.src >= 0) ++consumers[y.src];
+        if (y.res >= 0) ++consumers[y.res];
         // every code buffer holds int16 storage, so a layer may change its word length later
+        const bool post = y.d.pool || y.gap;                        // something follows the activation
         y.off_y = take(2 * y.n_y);
-        y.off_a = y.d.pool ? take(2 * y.n_a) : y.off_y;
-        y.off_dy = (y.d.pool || y.d.relu) ? take(2 * y.n_y) : 0;
+        y.off_a = post ? take(2 * y.n_a) : y.off_y;
         y.off_da = take(2 * y.n_a);
-        if (!(y.d.pool || y.d.relu)) y.off_dy = y.off_da;
+        y.off_dgap = y.gap ? take(2 * y.n_y) : 0;
+        y.off_dy = (y.d.pool || y.d.relu) ? take(2 * y.n_y) : (y.gap ? y.off_dgap : y.off_da);
+        y.off_yc = y.bn ? take(2 * y.n_y) : 0;
+        y.off_dyc = y.bn ? take(2 * y.n_y) : y.off_dy;
+        y.off_bn = y.bn ? take(adapt_bn_state_bytes(c.k)) : 0;
+        y.off_dgam = y.bn ? take((size_t)c.k * 8) : 0;
+        y.off_dbet = y.bn ? take((size_t)c.k * 8) : 0;
         y.off_qw = take(2 * y.n_w);
         // The weight gradient is written straight into a slot of the lookback ring (one slot more than the longest
         // window, so a free one always exists); without precision switching it has a buffer of its own.
         y.off_g = lb_upr ? 0 : take(2 * y.n_w);
         y.g_slot = -1;
         y.slot_bytes = align_up(2 * y.n_w);
-        y.off_stat = off_stats + (size_t)l * kStatBytes;
+        y.off_stat = P.off_stats + (size_t)l * kStatBytes;
+        y.off_exp = off_exp + (size_t)l * kExpBytes;
         y.off_ds = off_ds + (size_t)l * 16;
         y.off_sel = off_sel + (size_t)l * 8;
         y.off_kld = off_kld + (size_t)l * kKldStride;
         y.off_ring = lb_upr ? take((size_t)(lb_upr + 1) * y.slot_bytes) : 0;
         y.g_wl = 0;
         y.range_valid = false;
-        if (l > 0) max_in = std::max(max_in, y.n_in);
+        if (y.src >= 0) max_in = std::max(max_in, y.n_in);
         max_w = std::max(max_w, y.n_w);
     }
-    off_in = take(2 * L[0].n_in);
-    off_accx = take(8 * max_in);
-    off_accw = take(8 * max_w);
-    return off;
+    for (int l = 0; l < count; ++l) {
+        if (l < count - 1 && consumers[l] == 0) return false;     // an output nobody reads has no gradient
+        if (consumers[l] > 4) return false;
+        if (consumers[l] > 1) max_merge = std::max(max_merge, L[l].n_a);
+    }
+    P.off_in = take(2 * L[0].n_in);
+    P.off_accx = take(8 * max_in);
+    P.off_accw = take(8 * max_w);
+    P.off_tmp = max_merge ? take(2 * max_merge) : 0;
+    P.bytes = off;
+    return true;
 }
+
+struct ExpRec { long long e_da, e_dyc, e_g, spare; };
 
 }  // namespace
 
@@ -518,7 +578,8 @@ struct adapt_net {
     adapt_ctx *ctx;
     std::vector<NetLayer> L;
     char *ws;
-    size_t off_in, off_accx, off_accw, off_stats, off_sel_group, off_kld_group, off_win, bytes;
+    NetPlan P;
+    double bn_eps;
     bool forward_done, backward_done;
     int dlogits_fl;
     // precision switch
@@ -530,6 +591,8 @@ struct adapt_net {
     void *pinned;             // host-pinned, device-visible: count ChainLayerIn records, then count ChainLayerOut
     ChainLayerIn *chain_in;
     ChainLayerOut *chain_out;
+
+    ExpRec *exps(int l) const { return reinterpret_cast<ExpRec *>(ws + L[l].off_exp); }
 };
 
 namespace {
@@ -537,6 +600,11 @@ namespace {
 adapt_rng slot_rng(adapt_rng r, int layer, int slot)
 {
     r.stream += (uint64_t)(8 * layer + slot);
+    return r;
+}
+adapt_rng slot_rng_x(adapt_rng r, int layer, int slot)
+{
+    r.stream += kStreamX + (uint64_t)(8 * layer + slot);
     return r;
 }
 
@@ -560,17 +628,39 @@ static bool switch_params_ok(const adapt_switch_params &p)
     return p.strategy_init >= ADAPT_ST_MIN && p.strategy_init <= ADAPT_ST_MAX;
 }
 
-extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr)
+static std::vector<adapt_node_desc> plain_nodes(const adapt_layer_desc *layers, int count)
 {
-    std::vector<NetLayer> L;
-    size_t a, b, c, d, e, f, g;
-    return plan_net(layers, count, lb_upr, L, a, b, c, d, e, f, g);
+    std::vector<adapt_node_desc> nodes;
+    if (!layers || count < 1 || count > kMaxLayers) return nodes;
+    nodes.resize(count);
+    for (int l = 0; l < count; ++l) {
+        nodes[l] = adapt_node_desc{};
+        nodes[l].conv = layers[l].conv;
+        nodes[l].relu = layers[l].relu;
+        nodes[l].pool = layers[l].pool;
+        nodes[l].src = nodes[l].res = -1;
+    }
+    return nodes;
 }
 
-extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
-                                const adapt_switch_params *sp, void *workspace, size_t workspace_bytes, adapt_net **out)
+extern "C" size_t adapt_graph_workspace_bytes(const adapt_node_desc *nodes, int count, int lb_upr)
 {
-    if (!ctx || !out || !weights || !workspace || ((uintptr_t)workspace & 255)) return ADAPT_EINVAL;
+    std::vector<NetLayer> L;
+    NetPlan P;
+    return plan_net(nodes, count, lb_upr, L, P) ? P.bytes : 0;
+}
+
+extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr)
+{
+    const std::vector<adapt_node_desc> nodes = plain_nodes(layers, count);
+    return nodes.empty() ? 0 : adapt_graph_workspace_bytes(nodes.data(), count, lb_upr);
+}
+
+extern "C" int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights, float *const *gammas,
+                                  float *const *betas, double bn_eps, const adapt_switch_params *sp, void *workspace,
+                                  size_t workspace_bytes, adapt_net **out)
+{
+    if (!ctx || !out || !weights || !workspace || ((uintptr_t)workspace & 255) || !(bn_eps >= 0.0)) return ADAPT_EINVAL;
     if (sp && !switch_params_ok(*sp)) return ADAPT_EINVAL;
     adapt_net *net = new (std::nothrow) adapt_net();
     if (!net) return ADAPT_EINVAL;
@@ -578,6 +668,7 @@ extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, 
     net->ws = static_cast<char *>(workspace);
     net->forward_done = net->backward_done = false;
     net->dlogits_fl = 0;
+    net->bn_eps = bn_eps;
     net->has_switch = sp != nullptr;
     net->switch_due = false;
     if (sp) net->sp = *sp;
@@ -585,9 +676,19 @@ extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, 
     net->pinned = nullptr;
     net->chain_in = nullptr;
     net->chain_out = nullptr;
-    net->bytes = plan_net(layers, count, sp ? sp->lb_upr : 0, net->L, net->off_in, net->off_accx, net->off_accw, net->off_stats,
-                          net->off_sel_group, net->off_kld_group, net->off_win);
-    bool ok = net->bytes != 0 && net->bytes <= workspace_bytes;
+    const bool planned = plan_net(nodes, count, sp ? sp->lb_upr : 0, net->L, net->P);
+    bool ok = planned && net->P.bytes <= workspace_bytes;
+    for (int l = 0; ok && l < count; ++l) {
+        NetLayer &y = net->L[l];
+        y.w = weights[l];
+        y.lb = sp ? sp->lb_init : 0;
+        y.res_bins = sp ? sp->r_init : 0;
+        ok = weights[l] != nullptr && aligned16(weights[l]);
+        if (ok && y.bn) {
+            ok = gammas && betas && gammas[l] && betas[l];
+            if (ok) { y.gamma = gammas[l]; y.beta = betas[l]; }
+        }
+    }
     if (ok && sp) {
         const size_t in_bytes = align_up((size_t)count * sizeof(ChainLayerIn));
         const hipError_t e = hipHostMalloc(&net->pinned, in_bytes + (size_t)count * sizeof(ChainLayerOut), hipHostMallocDefault);
@@ -598,20 +699,21 @@ extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, 
         net->chain_in = static_cast<ChainLayerIn *>(net->pinned);
         net->chain_out = reinterpret_cast<ChainLayerOut *>(static_cast<char *>(net->pinned) + in_bytes);
     }
-    for (int l = 0; ok && l < count; ++l) {
-        net->L[l].w = weights[l];
-        net->L[l].lb = sp ? sp->lb_init : 0;
-        net->L[l].res = sp ? sp->r_init : 0;
-        ok = weights[l] != nullptr && aligned16(weights[l]);
-    }
     if (!ok) {
-        const int s = (net->bytes != 0 && net->bytes > workspace_bytes) ? ADAPT_EWORKSPACE : ADAPT_EINVAL;
-        if (net->pinned) (void)hipHostFree(net->pinned);
+        const int s = (planned && net->P.bytes > workspace_bytes) ? ADAPT_EWORKSPACE : ADAPT_EINVAL;
         delete net;
         return s;
     }
     *out = net;
     return ADAPT_OK;
+}
+
+extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
+                                const adapt_switch_params *sp, void *workspace, size_t workspace_bytes, adapt_net **out)
+{
+    const std::vector<adapt_node_desc> nodes = plain_nodes(layers, count);
+    if (nodes.empty()) return ADAPT_EINVAL;
+    return adapt_graph_create(ctx, nodes.data(), count, weights, nullptr, nullptr, 0.0, sp, workspace, workspace_bytes, out);
 }
 
 extern "C" int adapt_net_destroy(adapt_net *net)
@@ -641,7 +743,7 @@ extern "C" int adapt_net_tensor(const adapt_net *net, int layer, int which, size
     const NetLayer &y = net->L[layer];
     const int es = storage_bytes(y.fmt);
     switch (which) {
-    case ADAPT_NT_INPUT: *offset = net->off_in; *count = net->L[0].n_in; *elem_bytes = storage_bytes(net->L[0].fmt); break;
+    case ADAPT_NT_INPUT: *offset = net->P.off_in; *count = net->L[0].n_in; *elem_bytes = storage_bytes(net->L[0].fmt); break;
     case ADAPT_NT_Y: *offset = y.off_y; *count = y.n_y; *elem_bytes = es; break;
     case ADAPT_NT_A: *offset = y.off_a; *count = y.n_a; *elem_bytes = es; break;
     case ADAPT_NT_DY: *offset = y.off_dy; *count = y.n_y; *elem_bytes = es; break;
@@ -649,6 +751,12 @@ extern "C" int adapt_net_tensor(const adapt_net *net, int layer, int which, size
     case ADAPT_NT_QW: *offset = y.off_qw; *count = y.n_w; *elem_bytes = es; break;
     case ADAPT_NT_G: *offset = y.g_off(); *count = y.n_w; *elem_bytes = y.g_wl ? (y.g_wl <= 8 ? 1 : 2) : es; break;
     case ADAPT_NT_STATS: *offset = y.off_stat; *count = 1; *elem_bytes = (int)sizeof(adapt_net_stats); break;
+    case ADAPT_NT_YC: if (!y.bn) return ADAPT_EINVAL; *offset = y.off_yc; *count = y.n_y; *elem_bytes = es; break;
+    case ADAPT_NT_DYC: *offset = y.off_dyc; *count = y.n_y; *elem_bytes = es; break;
+    case ADAPT_NT_BN: if (!y.bn) return ADAPT_EINVAL; *offset = y.off_bn; *count = adapt_bn_state_bytes(y.d.conv.k); *elem_bytes = 1; break;
+    case ADAPT_NT_EXP: *offset = y.off_exp; *count = 4; *elem_bytes = 8; break;
+    case ADAPT_NT_DGAMMA: if (!y.bn) return ADAPT_EINVAL; *offset = y.off_dgam; *count = (size_t)y.d.conv.k; *elem_bytes = 8; break;
+    case ADAPT_NT_DBETA: if (!y.bn) return ADAPT_EINVAL; *offset = y.off_dbet; *count = (size_t)y.d.conv.k; *elem_bytes = 8; break;
     default: return ADAPT_EINVAL;
     }
     return ADAPT_OK;
@@ -678,22 +786,31 @@ extern "C" int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng)
     adapt_ctx *ctx = net->ctx;
     const int count = (int)net->L.size();
     net->forward_done = net->backward_done = false;
-    if (int s = adapt_quantize(ctx, x, net->L[0].n_in, net->L[0].fmt, slot_rng(rng, 0, 4), net->ws + net->off_in, nullptr, nullptr))
+    if (int s = adapt_quantize(ctx, x, net->L[0].n_in, net->L[0].fmt, slot_rng(rng, 0, 4), net->ws + net->P.off_in, nullptr, nullptr))
         return s;
-    const void *cur = net->ws + net->off_in;
-    adapt_fmt fcur = net->L[0].fmt;
     for (int l = 0; l < count; ++l) {
         const NetLayer &y = net->L[l];
+        const adapt_conv_desc &c = y.d.conv;
+        const void *cur = y.src >= 0 ? net->ws + net->L[y.src].off_a : net->ws + net->P.off_in;
+        const adapt_fmt fcur = y.src >= 0 ? net->L[y.src].fmt : net->L[0].fmt;
         adapt_epilogue ep = {};
         ep.raw = 0;
         ep.fmt = y.fmt;
         ep.rng = slot_rng(rng, l, 0);
-        ep.relu = y.d.relu != 0;
-        if (int s = adapt_conv_fwd(ctx, y.d.conv, cur, fcur, net->ws + y.off_qw, y.fmt, net->ws + y.off_y, ep)) return s;
+        ep.relu = !y.bn && y.d.relu != 0;                           // with batch norm the ReLU follows the normalisation
+        char *conv_out = net->ws + (y.bn ? y.off_yc : y.off_y);
+        if (int s = adapt_conv_fwd(ctx, c, cur, fcur, net->ws + y.off_qw, y.fmt, conv_out, ep)) return s;
+        if (y.bn) {
+            const void *res = y.res >= 0 ? net->ws + net->L[y.res].off_a : nullptr;
+            const adapt_fmt fres = y.res >= 0 ? net->L[y.res].fmt : adapt_fmt{8, 0};
+            if (int s = adapt_bn_forward(ctx, conv_out, y.fmt, (size_t)c.n * y.p * y.q, c.k, y.gamma, y.beta, net->bn_eps, res, fres, y.fmt,
+                                         slot_rng_x(rng, l, X_BN), y.d.relu, net->ws + y.off_y, net->ws + y.off_bn))
+                return s;
+        }
         if (y.d.pool)
-            if (int s = adapt_maxpool2_fwd(ctx, net->ws + y.off_y, y.fmt, y.d.conv.n, y.p, y.q, y.d.conv.k, net->ws + y.off_a)) return s;
-        cur = net->ws + y.off_a;
-        fcur = y.fmt;
+            if (int s = adapt_maxpool2_fwd(ctx, net->ws + y.off_y, y.fmt, c.n, y.p, y.q, c.k, net->ws + y.off_a)) return s;
+        if (y.gap)
+            if (int s = adapt_gap_fwd(ctx, net->ws + y.off_y, y.fmt, c.n, y.p * y.q, c.k, slot_rng_x(rng, l, X_GAP), net->ws + y.off_a)) return s;
     }
     net->forward_done = true;
     return ADAPT_OK;
@@ -708,19 +825,59 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
     const adapt_epilogue ex = exact_ep();
     net->backward_done = false;
     net->dlogits_fl = dlogits_fl;
+    int ncontrib[kMaxLayers] = {};
+    // The gradient of layer j's output is the sum of what its consumers hand back.  The first contribution is stored
+    // (refitted to layer j's word length when it comes from a layer of another word length), every later one is added
+    // to it exactly and the sum refitted.  Exponents stay in device memory.
+    auto contribute = [&](int j, const void *codes, int wl, const long long *e, bool fitted) -> int {
+        NetLayer &t = net->L[j];
+        const int k = ncontrib[j]++;
+        char *dst = net->ws + t.off_da;
+        long long *e_dst = &net->exps(j)->e_da;
+        if (k == 0 && fitted) return ADAPT_OK;                       // written in place by the fitting pass
+        if (k == 0) return adapt_grad_add(ctx, codes, wl, (const int64_t *)e, nullptr, 8, nullptr, t.n_a, t.fmt.wl,
+                                          slot_rng_x(rng, j, X_MERGE), dst, nullptr, (int64_t *)e_dst);
+        return adapt_grad_add(ctx, dst, t.fmt.wl, (const int64_t *)e_dst, codes, wl, (const int64_t *)e, t.n_a, t.fmt.wl,
+                              slot_rng_x(rng, j, X_MERGE + k), dst, nullptr, (int64_t *)e_dst);
+    };
+    hipLaunchKernelGGL(exp_set_kernel, dim3(1), dim3(1), 0, ctx->stream, &net->exps(count - 1)->e_da, (const long long *)nullptr,
+                       (long long)dlogits_fl);
     for (int l = count - 1; l >= 0; --l) {
         NetLayer &y = net->L[l];
         const adapt_conv_desc &c = y.d.conv;
+        ExpRec *ex_l = net->exps(l);
         const void *da = (l == count - 1) ? dlogits : net->ws + y.off_da;
-        const void *dy = da;
+        const long long *e_cur = &ex_l->e_da;
+        if (y.gap) {
+            int up = 0;
+            while ((1 << up) < y.p * y.q) ++up;
+            if (int s = adapt_gap_bwd(ctx, da, y.fmt.wl, c.n, y.p * y.q, c.k, net->ws + y.off_dgap)) return s;
+            hipLaunchKernelGGL(exp_set_kernel, dim3(1), dim3(1), 0, ctx->stream, &ex_l->spare, e_cur, (long long)up);
+            da = net->ws + y.off_dgap;
+            e_cur = &ex_l->spare;
+        }
+        const void *dz = da;
         if (y.d.relu || y.d.pool) {
             if (int s = adapt_relu_pool_bwd(ctx, da, net->ws + y.off_y, y.fmt, c.n, y.p, y.q, c.k, y.d.relu, y.d.pool, net->ws + y.off_dy))
                 return s;
-            dy = net->ws + y.off_dy;
+            dz = net->ws + y.off_dy;
+        }
+        if (y.res >= 0)
+            if (int s = contribute(y.res, dz, y.fmt.wl, e_cur, false)) return s;
+        adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
+        const void *dyc = dz;
+        if (y.bn) {
+            if (int s = adapt_bn_backward(ctx, dz, y.fmt.wl, net->ws + y.off_yc, y.fmt, (size_t)c.n * y.p * y.q, c.k, net->ws + y.off_bn,
+                                          y.fmt.wl, slot_rng_x(rng, l, X_BNB), net->ws + y.off_dyc,
+                                          reinterpret_cast<double *>(net->ws + y.off_dgam), reinterpret_cast<double *>(net->ws + y.off_dbet),
+                                          &st->reserved[0], (const int64_t *)e_cur, (int64_t *)&ex_l->e_dyc))
+                return s;
+            dyc = net->ws + y.off_dyc;
+            e_cur = &ex_l->e_dyc;
         }
         const adapt_fmt fdy = {y.fmt.wl, 0};                       // gradient codes of the layer's word length
-        const adapt_fmt fin = l > 0 ? net->L[l - 1].fmt : net->L[0].fmt;
-        const void *a_prev = l > 0 ? net->ws + net->L[l - 1].off_a : net->ws + net->off_in;
+        const adapt_fmt fin = y.src >= 0 ? net->L[y.src].fmt : net->L[0].fmt;
+        const void *a_prev = y.src >= 0 ? net->ws + net->L[y.src].off_a : net->ws + net->P.off_in;
         y.g_wl = y.fmt.wl;
         y.fl_in = fin.fl;
         y.fl_w = y.fmt.fl;
@@ -730,27 +887,31 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
             y.g_slot = 0;
             while (used[y.g_slot]) ++y.g_slot;
         }
-        char *accw = net->ws + net->off_accw, *accx = net->ws + net->off_accx;
-        adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
-        if (l > 0) {
-            if (int s = adapt_conv_backward(ctx, c, dy, fdy, net->ws + y.off_qw, y.fmt, a_prev, fin, accx, ex, accw, ex)) return s;
+        char *accw = net->ws + net->P.off_accw, *accx = net->ws + net->P.off_accx;
+        if (y.src >= 0) {
+            if (int s = adapt_conv_backward(ctx, c, dyc, fdy, net->ws + y.off_qw, y.fmt, a_prev, fin, accx, ex, accw, ex)) return s;
         } else {
-            if (int s = adapt_conv_wgrad(ctx, c, dy, fdy, a_prev, fin, accw, ex)) return s;
+            if (int s = adapt_conv_wgrad(ctx, c, dyc, fdy, a_prev, fin, accw, ex)) return s;
         }
         const int bits_w = adapt_acc_bits((int64_t)c.n * y.p * y.q, fdy, fin);
-        if (int s = adapt_requantize_fit(ctx, accw, bits_w, y.n_w, y.fmt.wl, slot_rng(rng, l, 2), net->ws + y.g_off(), &st->shift_w,
-                                         &st->g_sumsq))
+        if (int s = requantize_fit_exp(ctx, accw, bits_w, y.n_w, y.fmt.wl, slot_rng(rng, l, 2), net->ws + y.g_off(), &st->shift_w,
+                                       &st->g_sumsq, e_cur, fin.fl, &ex_l->e_g))
             return s;
-        if (l > 0) {
+        if (y.src >= 0) {
+            NetLayer &t = net->L[y.src];
+            const bool first = ncontrib[y.src] == 0;
             const int bits_x = adapt_acc_bits((int64_t)c.r * c.s * c.k, fdy, y.fmt);
-            if (int s = adapt_requantize_fit(ctx, accx, bits_x, y.n_in, net->L[l - 1].fmt.wl, slot_rng(rng, l, 1),
-                                             net->ws + net->L[l - 1].off_da, &st->shift_a, nullptr))
+            char *dst = first ? net->ws + t.off_da : net->ws + net->P.off_tmp;
+            long long *e_dst = first ? &net->exps(y.src)->e_da : &ex_l->spare;
+            if (int s = requantize_fit_exp(ctx, accx, bits_x, y.n_in, t.fmt.wl, slot_rng(rng, l, 1), dst, &st->shift_a, nullptr, e_cur,
+                                           y.fmt.fl, e_dst))
                 return s;
+            if (int s = contribute(y.src, dst, t.fmt.wl, e_dst, true)) return s;
         }
     }
     net->backward_done = true;
     net->switch_due = net->has_switch;
-    return ADAPT_OK;
+    return hip_status(ctx, hipGetLastError());
 }
 
 extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng rng, adapt_switch_report *report, int *strategy)
@@ -775,13 +936,11 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
         strategy_new = adapt_strategy_next(net->strategy, acc / (double)k, loss);
     }
 
-    // Windows as they will be once this batch's gradients have joined them, and their diversities.  The fitting shifts
-    // of the backward pass give every gradient tensor its exponent,
-    //   e(g_l) = dlogits_fl + sum_{j>l} FL(W^_j) + FL(a_{l-1}) - shift_w(l) - sum_{j>l} shift_a(j);
-    // the shifts are on the device, so the host hands over the other terms and the device finishes the sum.
+    // Windows as they will be once this batch's gradients have joined them, and their diversities.  The exponent of
+    // every gradient tensor of this backward pass lies in device memory (the fitting passes wrote it), so the device
+    // lays the windows out itself.
     std::vector<std::vector<int>> win_new(count);
     size_t n_w[kMaxLayers];
-    long long fl_above = net->dlogits_fl;
     for (int l = count - 1; l >= 0; --l) {
         const NetLayer &y = net->L[l];
         std::vector<int> &w = win_new[l];
@@ -794,13 +953,12 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
             const int s2 = w[w.size() - use + i];
             c.g[i] = net->ws + y.off_ring + (size_t)s2 * y.slot_bytes;
             c.wl[i] = (uint8_t)(i == use - 1 ? y.g_wl : y.slot_wl[s2]);
-            c.exp[i] = i == use - 1 ? fl_above + y.fl_in : y.slot_exp[s2];
+            c.exp[i] = i == use - 1 ? 0 : y.slot_exp[s2];
         }
         n_w[l] = y.n_w;
-        fl_above += y.fl_w;
     }
-    if (int s = gradient_diversity_chain(ctx, net->chain_in, count, n_w, reinterpret_cast<const adapt_net_stats *>(net->ws + net->off_stats),
-                                         reinterpret_cast<GradWindow *>(net->ws + net->off_win), net->chain_out))
+    if (int s = gradient_diversity_chain(ctx, net->chain_in, count, n_w, &net->exps(0)->e_g, kExpBytes / 8,
+                                         reinterpret_cast<GradWindow *>(net->ws + net->P.off_win), net->chain_out))
         return s;
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return hip_status(ctx, e);
@@ -813,7 +971,7 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
     for (int l = 0; l < count; ++l) {
         const NetLayer &y = net->L[l];
         lb_new[l] = adapt_lookback_next(y.lb, out[l].ds, sp.lb_lwr, sp.lb_upr, sp.gamma);
-        res_new[l] = adapt_resolution_next(y.res, lb_new[l], sp.lb_lwr, sp.lb_upr, sp.r_lwr, sp.r_upr);
+        res_new[l] = adapt_resolution_next(y.res_bins, lb_new[l], sp.lb_lwr, sp.lb_upr, sp.r_lwr, sp.r_upr);
         switches[l] = (int)win_new[l].size() >= lb_new[l];
         if (switches[l]) lo_of[l] = std::max(sp.wl_lo, y.fmt.wl - y.fmt.fl);
     }
@@ -835,8 +993,8 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
         }
         if (m == 0) continue;
         // the t-th member of a group writes kld[16 * (group_base + t)...] and sel[2 * (group_base + t)]
-        double *gk = reinterpret_cast<double *>(net->ws + net->off_kld_group);
-        int32_t *gs = reinterpret_cast<int32_t *>(net->ws + net->off_sel_group);
+        double *gk = reinterpret_cast<double *>(net->ws + net->P.off_kld_group);
+        int32_t *gs = reinterpret_cast<int32_t *>(net->ws + net->P.off_sel_group);
         if (int s = adapt_kld_precision_search_batched_ranged(ctx, items, ranges, m, lo, sp.wl_hi, sp.eps, -1.0, rng.mode, rng.seed,
                                                               gk + (size_t)group_base * 16, gs + 2 * (size_t)group_base))
             return s;
@@ -845,7 +1003,7 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
     }
     std::vector<int32_t> sel(2 * (size_t)count, 0);
     if (group_base > 0) {
-        e = hipMemcpyAsync(sel.data(), net->ws + net->off_sel_group, (size_t)group_base * 8, hipMemcpyDeviceToHost, ctx->stream);
+        e = hipMemcpyAsync(sel.data(), net->ws + net->P.off_sel_group, (size_t)group_base * 8, hipMemcpyDeviceToHost, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e != hipSuccess) return hip_status(ctx, e);
     }
@@ -877,7 +1035,7 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
         y.slot_exp[y.g_slot] = out[l].exp_new;
         y.win.swap(win_new[l]);
         y.lb = lb_new[l];
-        y.res = res_new[l];
+        y.res_bins = res_new[l];
         if (switches[l]) {
             y.fmt = fmt_new[l];
             y.win.clear();
@@ -887,7 +1045,7 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
             report[l] = adapt_switch_report{};
             report[l].ds = out[l].ds;
             report[l].lb = y.lb;
-            report[l].res = y.res;
+            report[l].res = y.res_bins;
             report[l].used = out[l].used;
             report[l].switched = switches[l];
             report[l].wl_min = wl_min_of[l];
@@ -906,6 +1064,10 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
     for (int l = 0; l < count; ++l) {
         NetLayer &y = net->L[l];
         y.range_valid = false;
+        if (y.bn)
+            if (int s = adapt_bn_update(net->ctx, y.gamma, y.beta, reinterpret_cast<const double *>(net->ws + y.off_dgam),
+                                        reinterpret_cast<const double *>(net->ws + y.off_dbet), y.d.conv.k, opt.lr))
+                return s;
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
         if (y.g_wl == 0) return ADAPT_EINVAL;                        // no backward pass yet
         const adapt_fmt fg = {y.g_wl, 0};                            // the gradient keeps the word length it was made with

@@ -172,21 +172,18 @@ gd_final_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const ui
 
 size_t ws_need_gradient_diversity(uint64_t n, int count);
 
-// One thread per layer of a chained step: the exponent of this batch's gradient follows from the
-// fitting shifts that the backward pass left in the statistics records, so the window can be laid
-// out without the host reading them first.  The aligned element sum of the diversity kernel is a
-// 32-bit integer: when the scales of the window lie too far apart for that, the oldest entries are
-// left out until the rest fits (at least the newest entry stays).
-__global__ void chain_prep_kernel(const ChainLayerIn *__restrict__ in, int nlayers, const adapt_net_stats *__restrict__ stats,
+// One thread per layer of a chained step: the exponent of this batch's gradient lies in device memory (the fitting
+// pass of the backward pass wrote it), so the window can be laid out without the host reading it first.  The aligned
+// element sum of the diversity kernel is a 32-bit integer: when the scales of the window lie too far apart for that,
+// the oldest entries are left out until the rest fits (at least the newest entry stays).
+__global__ void chain_prep_kernel(const ChainLayerIn *__restrict__ in, int nlayers, const long long *__restrict__ e_g, size_t e_stride,
                                   GradWindow *__restrict__ win, ChainLayerOut *__restrict__ out)
 {
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= nlayers) return;
     const ChainLayerIn &c = in[l];
-    long long shifts = stats[l].shift_w;
-    for (int j = l + 1; j < nlayers; ++j) shifts += stats[j].shift_a;
     const int count = c.count;
-    const long long e_new = c.exp[count - 1] - shifts;
+    const long long e_new = e_g[(size_t)l * e_stride];
     auto exp_of = [&](int k) { return k == count - 1 ? e_new : c.exp[k]; };
     int first = 0;
     long long e_min = 0, e_max = 0;
@@ -219,7 +216,7 @@ __global__ void chain_prep_kernel(const ChainLayerIn *__restrict__ in, int nlaye
     out[l].used = used;
 }
 
-int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers, const size_t *n, const adapt_net_stats *stats,
+int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers, const size_t *n, const long long *e_g, size_t e_stride,
                              GradWindow *win, ChainLayerOut *out)
 {
     if (nlayers < 1) return ADAPT_EINVAL;
@@ -230,7 +227,7 @@ int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers
     }
     if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
-    hipLaunchKernelGGL(chain_prep_kernel, dim3(1), dim3(64), 0, ctx->stream, in, nlayers, stats, win, out);
+    hipLaunchKernelGGL(chain_prep_kernel, dim3(1), dim3(64), 0, ctx->stream, in, nlayers, e_g, e_stride, win, out);
     const size_t per_block = (size_t)kGdThreads * kGdPerThread;
     const GradWindow none = {};
     for (int l = 0; l < nlayers; ++l) {
