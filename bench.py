@@ -482,6 +482,66 @@ def chained_step(ctx, pkg, torch, batch=128):
     return res
 
 
+def chained_resnet18(ctx, pkg, torch, batch=256):
+    """The ResNet-18-CIFAR layers of configs[4] as one chained fixed-point training step: convolutions, fixed-point batch
+    normalisation with the shortcuts fused in, global average pooling, backward pass with merged gradients, update of
+    weights, gamma and beta + re-quantization; formats of configs[4] (word lengths below 6 raised to 6: a chain
+    feeds each layer's output to the next, and 4-bit activations saturate); device time per phase."""
+    import numpy as np
+    import workloads as wk
+    from paper_2107_13490_amd import ConvDesc, NodeDesc
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    nodes, ws, bn, fmts, macs = [], [], [], [], 0
+    graph = wk.resnet18_cifar_graph(batch)
+    for sp, relu, has_bn, src, res, gap in graph:
+        s = sp.shape
+        nodes.append(NodeDesc(ConvDesc(s.n, s.h, s.w, s.c, s.k, s.r, s.s, s.stride, s.pad), int(relu), 0, int(has_bn), src, res, int(gap)))
+        ws.append(torch.randn((s.k, s.r, s.s, s.c), device="cuda", generator=gen) * (1.4 / np.sqrt(s.r * s.s * s.c)))
+        bn.append((torch.ones(s.k, device="cuda"), torch.zeros(s.k, device="cuda")) if has_bn else None)
+        wl = max(sp.wl, 6)
+        fmts.append((wl, wl - 4))
+        macs += s.macs
+    ctx.reserve_for_layers([(d.conv, f, f, f) for d in nodes for f in ((8, 4), (16, 12))], kld_bins=150, wl_lo=4, wl_hi=16)
+    net = pkg.Net(ctx, nodes, ws, bn=bn)
+    for l, (wl, fl) in enumerate(fmts):
+        net.set_format(l, wl, fl)
+    x = torch.randn((batch, 32, 32, 3), device="cuda", generator=gen)
+    dl = torch.randint(-4, 4, (batch, 100), device="cuda", dtype=torch.int32, generator=gen).to(
+        torch.int8 if fmts[-1][0] <= 8 else torch.int16)
+    net.quantize_weights()
+
+    def timed(fn, reps=10):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def fwd():
+        net.forward(x)
+
+    def fwd_bwd():
+        net.forward(x)
+        net.backward(dl, 0)
+
+    def full():
+        net.forward(x)
+        net.backward(dl, 0)
+        net.update(0.01, 1e-5, 1e-4)
+    t_f, t_fb, t_all = timed(fwd), timed(fwd_bwd), timed(full)
+    ops = 2.0 * macs * 3 - 2.0 * graph[0][0].shape.macs               # no data gradient below the first layer
+    net.close()
+    return {"workload": f"ResNet-18-CIFAR chain (batch norm, shortcuts, average pooling), batch {batch}, formats of configs[4] (WL >= 6)",
+            "formats": fmts, "forward_ms": t_f, "forward_backward_ms": t_fb, "step_ms": t_all,
+            "useful_TOPS": ops / (t_all * 1e-3) / 1e12}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -520,7 +580,8 @@ def main():
         return
     ctx = pkg.Context()
     if args.chained_step:
-        print(json.dumps({"chained_step": chained_step(ctx, pkg, torch, batch=128)}))
+        print(json.dumps({"chained_step": chained_step(ctx, pkg, torch, batch=128),
+                          "chained_step_resnet18": chained_resnet18(ctx, pkg, torch, batch=256)}))
         return
     if args.steps_only:
         print(json.dumps(run_config(args.config, args.steps, args.warmup, ctx, pkg, torch, plain=True)))
@@ -563,6 +624,8 @@ def main():
         torch.cuda.empty_cache()
         out["next_rows"] = next_rows(ctx, pkg, torch, 110592)
         out["next_rows"]["chained_step"] = chained_step(ctx, pkg, torch, batch=128)
+        torch.cuda.empty_cache()
+        out["next_rows"]["chained_step_resnet18"] = chained_resnet18(ctx, pkg, torch, batch=256)
         out["next_rows"]["chained_step_elementwise"] = elementwise_rows(ctx, pkg, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)

@@ -412,7 +412,7 @@ int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *
  * gamma, beta: device float[channels] (finite).  state: device, 64-byte aligned,
  * adapt_bn_state_bytes(channels) bytes, written here and read by adapt_bn_backward; layout: a 64-byte
  * header (int32 channels, fl_y, fl_o, FA, FB, 3 reserved; uint64 rows), then mean[K], sig[K], alpha[K]
- * (double), B[K], R[K] (int64), A[K], P[K], Q[K] (int32).  Three launches. */
+ * (double), B[K], R[K] (int64), A[K], P[K], Q[K] (int32).  Four launches. */
 size_t adapt_bn_state_bytes(int channels);
 int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, size_t rows, int channels,
                      const float *gamma, const float *beta, double eps, const void *res,
@@ -426,7 +426,7 @@ int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, size_t rows, i
  *   dy = requantize_fit(P^ dz + Q^ y + R^) in wl_out bits (the rule of adapt_requantize_fit).
  * The gradient with respect to y's values is dy 2^-(e + FB - shift + fo.fl - fy.fl).  shift: device
  * int32 or NULL; e_in / e_out: device int64 or NULL, *e_out = *e_in + FB - shift + fo.fl - fy.fl
- * (e_in = NULL counts as 0).  y, fy, rows, channels as in the forward call.  Four launches. */
+ * (e_in = NULL counts as 0).  y, fy, rows, channels as in the forward call.  Five launches. */
 int adapt_bn_backward(adapt_ctx *ctx, const void *dz, int wl_dz, const void *y, adapt_fmt fy,
                       size_t rows, int channels, void *state, int wl_out, adapt_rng rng, void *dy,
                       double *dgamma, double *dbeta, int32_t *shift, const int64_t *e_in,

@@ -149,9 +149,30 @@ __device__ inline double block_max_f64(double v, double *sm)
     return v;
 }
 
+// Totals of the block partials partial[nparts][width] of a statistics launch: a block takes 8 columns, 32 threads per
+// column each add every 32nd partial (independent loads), LDS combines them.
+__global__ void __launch_bounds__(256)
+bn_total_kernel(const long long *__restrict__ partial, int nparts, int width, long long *__restrict__ totals)
+{
+    __shared__ long long sm[32][8];
+    const int c = threadIdx.x & 7, rl = threadIdx.x >> 3;
+    const int col = blockIdx.x * 8 + c;
+    long long acc = 0;
+    if (col < width)
+        for (int r = rl; r < nparts; r += 32) acc += partial[(size_t)r * width + col];
+    sm[rl][c] = acc;
+    __syncthreads();
+    if (threadIdx.x < 8 && col < width) {
+        long long t = 0;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) t += sm[i][threadIdx.x];
+        totals[col] = t;
+    }
+}
+
 // One block: totals of the block partials, statistics and forward coefficients.
 __global__ void __launch_bounds__(1024)
-bn_coef_fwd_kernel(const long long *__restrict__ partial, int nparts, int channels, unsigned long long rows, int fl_y, int fl_o,
+bn_coef_fwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int channels, unsigned long long rows, int fl_y, int fl_o,
                    const float *__restrict__ gamma, const float *__restrict__ beta, double eps, void *state)
 {
     __shared__ double sm[16];
@@ -159,16 +180,12 @@ bn_coef_fwd_kernel(const long long *__restrict__ partial, int nparts, int channe
     const double m = (double)rows;
     double amax = 0.0;
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
-        long long s1 = 0, s2 = 0;
-        for (int p = 0; p < nparts; ++p) {
-            s1 += partial[(size_t)p * 2 * channels + k];
-            s2 += partial[(size_t)p * 2 * channels + channels + k];
-        }
+        const long long s1 = tot[k], s2 = tot[channels + k];
         const double mean = (double)s1 / m;
         const double ex2 = (double)s2 / m;
         const double var = fmax(ex2 - mean * mean, 0.0);
         const double sig = sqrt(var + ldexp(eps, 2 * fl_y));
-        const double alpha = ((ldexp((double)gamma[k], fl_o)) / (sig));
+        const double alpha = ldexp((double)gamma[k], fl_o) / sig;
         st.mean[k] = mean;
         st.sig[k] = sig;
         st.alpha[k] = alpha;
@@ -178,7 +195,7 @@ bn_coef_fwd_kernel(const long long *__restrict__ partial, int nparts, int channe
     const int fa = coef_exponent(amax);
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
         const double alpha = st.alpha[k];
-        const double off = ((ldexp((double)beta[k], fl_o)) - (((st.mean[k]) * (alpha))));
+        const double off = ldexp((double)beta[k], fl_o) - st.mean[k] * alpha;
         st.A[k] = (int32_t)rint_clamped(alpha, fa, 1073741824.0);
         st.B[k] = rint_clamped(off, fa, 2305843009213693952.0);
     }
@@ -189,7 +206,7 @@ bn_coef_fwd_kernel(const long long *__restrict__ partial, int nparts, int channe
 
 // One block: totals of (sum dz, sum dz*y), the parameter gradients and the backward coefficients.
 __global__ void __launch_bounds__(1024)
-bn_coef_bwd_kernel(const long long *__restrict__ partial, int nparts, int channels, void *state, double *__restrict__ dgamma,
+bn_coef_bwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int channels, void *state, double *__restrict__ dgamma,
                    double *__restrict__ dbeta)
 {
     __shared__ double sm[16];
@@ -197,11 +214,7 @@ bn_coef_bwd_kernel(const long long *__restrict__ partial, int nparts, int channe
     const double m = (double)st.h->rows;
     double pmax = 0.0;
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
-        long long d1 = 0, d2 = 0;
-        for (int p = 0; p < nparts; ++p) {
-            d1 += partial[(size_t)p * 2 * channels + k];
-            d2 += partial[(size_t)p * 2 * channels + channels + k];
-        }
+        const long long d1 = tot[k], d2 = tot[channels + k];
         const double mean = st.mean[k], sig = st.sig[k], alpha = st.alpha[k];
         const double dg = ((double)d2 - mean * (double)d1) / sig;
         const double c1 = (((double)d1) / (m));
@@ -532,7 +545,7 @@ static bool rng_ok(adapt_rng r) { return r.mode == ADAPT_SR || r.mode == ADAPT_R
 
 size_t ws_need_bn(int num_cu, int channels)
 {
-    return (size_t)num_cu * 2 * 2 * (size_t)channels * 8 + (size_t)num_cu * 8 * 8 + 256;
+    return (size_t)num_cu * 2 * 2 * (size_t)channels * 8 + (size_t)2 * channels * 8 + (size_t)num_cu * 8 * 8 + 256;
 }
 
 }  // namespace adapt
@@ -579,7 +592,9 @@ extern "C" int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, siz
     long long *partial = reinterpret_cast<long long *>(scratch(ctx));
     int grid;
     launch_sums<0>(ctx, y, storage_bytes(fy), y, storage_bytes(fy), groups, channels, partial, grid);
-    hipLaunchKernelGGL(bn_coef_fwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, partial, grid, channels, (unsigned long long)rows, fy.fl,
+    long long *totals = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
+    hipLaunchKernelGGL(bn_total_kernel, dim3((2 * channels + 7) / 8), dim3(256), 0, ctx->stream, partial, grid, 2 * channels, totals);
+    hipLaunchKernelGGL(bn_coef_fwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, totals, channels, (unsigned long long)rows, fy.fl,
                        fo.fl, gamma, beta, eps, state);
     BnApplyArgs a;
     a.y = y; a.res = res; a.out = out; a.state = state; a.groups = groups; a.channels = channels; a.wl = fo.wl; a.relu = relu != 0;
@@ -619,13 +634,15 @@ extern "C" int adapt_bn_backward(adapt_ctx *ctx, const void *dz, int wl_dz, cons
     const int es_d = wl_dz <= 8 ? 1 : 2, es_y = storage_bytes(fy), es_o = wl_out <= 8 ? 1 : 2;
     int grid;
     launch_sums<1>(ctx, dz, es_d, y, es_y, groups, channels, partial, grid);
-    hipLaunchKernelGGL(bn_coef_bwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, partial, grid, channels, state, dgamma, dbeta);
+    long long *totals = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
+    hipLaunchKernelGGL(bn_total_kernel, dim3((2 * channels + 7) / 8), dim3(256), 0, ctx->stream, partial, grid, 2 * channels, totals);
+    hipLaunchKernelGGL(bn_coef_bwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, totals, channels, state, dgamma, dbeta);
     BnBwdArgs a;
     a.dz = dz; a.y = y; a.dy = dy; a.state = state; a.groups = groups; a.channels = channels; a.wl = wl_out; a.mode = rng.mode;
     a.seed = rng.seed; a.stream = rng.stream; a.shift_out = shift;
     a.e_in = reinterpret_cast<const long long *>(e_in); a.e_out = reinterpret_cast<long long *>(e_out);
     const int grid1 = (int)std::min<uint64_t>(std::max<uint64_t>((groups + kBnThreads - 1) / kBnThreads, 1), (uint64_t)ctx->num_cu * 4);
-    a.part = reinterpret_cast<uint64_t *>(scratch(ctx) + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels * 8);
+    a.part = reinterpret_cast<uint64_t *>(scratch(ctx) + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels * 8 + (size_t)2 * channels * 8);
     a.nparts = grid1;
     const size_t lds = (size_t)channels * 16;
     const dim3 t(kBnThreads), g2(bn_grid(ctx, groups));

@@ -167,5 +167,31 @@ def resnet18_cifar_layers(batch: int = 256, seed: int = 5) -> list[LayerSpec]:
     return out
 
 
+def resnet18_cifar_graph(batch: int = 256, seed: int = 5):
+    """The same 21 layers as the graph of a residual network: per layer (spec, relu, bn, src, res, gap), src / res the
+    indices of the layer that feeds the convolution and of the shortcut that joins after its batch norm (-1: the layer
+    before / none).  Basic blocks conv-bn-relu-conv-bn(+shortcut)-relu; the first block of stages 1-3 halves the map
+    with stride 2 and a 1x1 projection on the shortcut; global average pooling before the fully connected layer."""
+    specs = {sp.name: (i, sp) for i, sp in enumerate(resnet18_cifar_layers(batch, seed))}
+    out = [None] * len(specs)
+    out[0] = (specs["stem"][1], True, True, -1, -1, False)
+    last = 0
+    for stage in range(4):
+        for block in range(2):
+            i1, s1 = specs[f"s{stage}b{block}c1"]
+            i2, s2 = specs[f"s{stage}b{block}c2"]
+            out[i1] = (s1, True, True, last, -1, False)
+            short = last
+            if f"s{stage}b{block}proj" in specs:
+                ip, sp = specs[f"s{stage}b{block}proj"]
+                out[ip] = (sp, False, True, last, -1, False)
+                short = ip
+            out[i2] = (s2, True, True, i1, short, stage == 3 and block == 1)
+            last = i2
+    ifc, sfc = specs["fc"]
+    out[ifc] = (sfc, False, False, last, -1, False)
+    return out
+
+
 def layer_inputs(spec: LayerSpec, seed: int) -> ConvLayerInputs:
     return conv_layer(spec.shape, spec.wl, spec.fl, seed, spec.zero_frac, spec.name)
