@@ -35,8 +35,14 @@ METRIC = "fxp conv/GEMM TOPS (% int8 MFMA peak) + KLD precision-search GB/s"
 # commands is the file named here, and tests/test_bench_constants.py checks that the numbers agree with it.
 TRAFFIC = {
     "profile": "profiles/bench_config5_hbm_traffic.md",
-    "contractions_read_bytes": None,
-    "contractions_written_bytes": None,
+    "contractions_read_bytes": 1774641185,
+    "contractions_written_bytes": 840245197,
+    # from the kernel trace of the same workload (profiles/bench_config5_kernel_stats.md): device time of the contraction
+    # kernels per step and their launches per step; the HIP-event figure measured live (roofline.avg_launch_ms) also
+    # holds the dispatch gaps between the launches of a call and the channel-padding copies
+    "stats_profile": "profiles/bench_config5_kernel_stats.md",
+    "contractions_us_per_step": 2495.0,
+    "contraction_launches_per_step": 72,
 }
 
 WORKLOADS = {
@@ -606,6 +612,9 @@ def main():
                      "achieved": con["issued_TOPS"], "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": con["frac_int8_peak"],
                      "avg_launch_ms": con["ms_per_step_in_timed_region"], "avg_launch_ms_note": con["note"],
                      "traffic": traffic, "traffic_profile": TRAFFIC["profile"] if traffic else None,
+                     "rocprof_us_per_step": TRAFFIC["contractions_us_per_step"] if args.config == 5 else None,
+                     "rocprof_launches_per_step": TRAFFIC["contraction_launches_per_step"] if args.config == 5 else None,
+                     "rocprof_profile": TRAFFIC["stats_profile"] if args.config == 5 else None,
                      "useful_TOPS": con["useful_TOPS"], "heaviest_layer": head.get("heaviest_layer")},
         "quantize": head["quantize"], "kld": head["kld"], "calls_ms_back_to_back": head["calls_ms_back_to_back"],
         "host_enqueue_ms_per_step": head["host_enqueue_ms_per_step"],
