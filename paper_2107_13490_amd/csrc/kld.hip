@@ -10,9 +10,8 @@
 //            it for the later kernels), then reads its share of the tensor once: reference bin +
 //            one bin per candidate for every element, counted in LDS histograms, and written to the block's own slab with plain stores.
 //   sum      blocks of (256 bins, row): add the slabs of one row.
-//   final    blocks of 256 bins: partial KL sums of every candidate on those bins in fp64; the last
-//            block to finish adds the partial sums in a fixed order and picks the lowest WL with
-//            KL < eps.
+//   final    blocks of (256 bins, candidate): partial KL sums in fp64; the last block to finish adds
+//            the partial sums in a fixed order and picks the lowest WL with KL < eps.
 // All counts are integers, so the result does not depend on the order of accumulation.
 #include <algorithm>
 #include <cstdlib>
@@ -520,9 +519,9 @@ kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict
 // D = n_finite + alpha nb, so bins with cp_b == cq_b contribute nothing and need no logarithm.
 // Two launches (a device-wide fence per block, which a single launch would need, empties the caches the slab
 // loads live on).  Sum: block (x, row) adds bins [x*kChunk, (x+1)*kChunk) of one row over the slabs into
-// sums[row][bins].  Final: block x forms the terms of every candidate on its bins and their sums
-// part[c][x] = (sum of terms), part[ncand][x] = (sum of reference counts); the last block of the search to
-// finish (a ticket) adds them in a fixed order and selects.
+// sums[row][bins].  Final: block (x, c) forms the terms of candidate c on its bins and their sum part[c][x]
+// (block (x, 0) also part[ncand][x], the sum of reference counts); the last block of the search to finish
+// (a ticket) adds them in a fixed order and selects.
 // The region of a search in the scratch: ticket | part | sums.
 struct KlRegion {
     uint32_t *tickets;      // [0]: blocks of the final kernel that have finished
@@ -572,13 +571,16 @@ __device__ __forceinline__ void kld_sum_body(const KldPlan *__restrict__ plan, c
         }
     }
     if (b < bins) {
-        sums[(size_t)row * bins + b] = u;
+        __hip_atomic_store(sums + (size_t)row * bins + b, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (hist_out) hist_out[(size_t)row * bins + b] = u;
     }
 }
 
-// kernel 3b, block x: terms of every candidate on bins [x*kChunk, (x+1)*kChunk), summed over the chunk in a fixed
-// order (lanes, then wavefronts); the last block of the search to finish adds the chunks in a fixed order and selects
+// kernel 3b, block (x, y): terms of the candidates y, y + gy, ... on bins [x*kChunk, (x+1)*kChunk), each summed over
+// the chunk in a fixed order (lanes, then wavefronts); the blocks with y = 0 also sum the chunk's reference counts.
+// gy = number of candidates: one logarithm per thread (small searches, where latency counts); gy = 1: every
+// candidate in turn (batches of large searches, where the device-wide fence of 13 times as many tickets costs more
+// than it saves).  The last block of the search to finish adds the chunks in a fixed order and selects.
 __device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan, int rows, int bins, double alpha_in,
                                                const KlRegion reg, int wl_lo, int il, double eps, double *kld, int32_t *sel,
                                                long long *grid_out, const BlockGeo geo)
@@ -589,40 +591,37 @@ __device__ __forceinline__ void kld_final_body(const KldPlan *__restrict__ plan,
     const int nb = plan->degenerate ? 0 : plan->nb;
     __shared__ double red[kMaxCand + 1][kChunk / kWave];
     const double alpha = alpha_in < 0.0 ? 1.0 / (double)(nb > 0 ? nb : 1) : alpha_in;
-    const uint32_t uq = b < nb ? reg.sums[b] : 0u;
-    uint32_t up[kMaxCand];
-#pragma unroll
-    for (int c = 0; c < kMaxCand; ++c) up[c] = (c < ncand && b < nb) ? reg.sums[(size_t)(c + 1) * bins + b] : uq;
-#pragma unroll
-    for (int c = 0; c < kMaxCand; ++c) {
-        if (c >= ncand) break;
+    const uint32_t uq = b < nb ? __hip_atomic_load(reg.sums + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+    for (int c = geo.by; c < ncand; c += geo.gy) {
+        const uint32_t up = b < nb ? __hip_atomic_load(reg.sums + (size_t)(c + 1) * bins + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : uq;
         double term = 0.0;
-        if (up[c] != uq) {
-            const double pp = (double)up[c] + alpha, qq = (double)uq + alpha;
+        if (up != uq) {
+            const double pp = (double)up + alpha, qq = (double)uq + alpha;
             if (pp > 0.0) term = (qq > 0.0) ? pp * log2(pp / qq) : (double)INFINITY;
         }
         term = wave_sum_f64(term);
         if (lane == 0) red[c][wave] = term;
     }
-    {
+    if (geo.by == 0) {
         const double cnt = wave_sum_f64((double)uq);      // exact
         if (lane == 0) red[ncand][wave] = cnt;
     }
     __syncthreads();
-    if ((int)threadIdx.x <= ncand) {
-        double t = red[threadIdx.x][0];
+    __shared__ bool last_block;
+    if (threadIdx.x == 0) {
+        auto put = [&](int c) {
+            double t = red[c][0];
 #pragma unroll
-        for (int i = 1; i < kChunk / kWave; ++i) t += red[threadIdx.x][i];
-        __hip_atomic_store(reg.part + (size_t)threadIdx.x * nchunks + x, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int i = 1; i < kChunk / kWave; ++i) t += red[c][i];
+            __hip_atomic_store(reg.part + (size_t)c * nchunks + x, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        for (int c = geo.by; c < ncand; c += geo.gy) put(c);
+        if (geo.by == 0) put(ncand);
+        // release this block's partial sums, acquire everyone else's
+        last_block = __hip_atomic_fetch_add(reg.tickets, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == geo.gx * geo.gy - 1;
     }
-    // every wavefront waits for its stores, the barrier orders them before thread 0's ticket
-    __shared__ bool last_chunk;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    if (threadIdx.x == 0)
-        last_chunk = __hip_atomic_fetch_add(reg.tickets, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)nchunks - 1;
-    __syncthreads();
-    if (!last_chunk) return;
+    if (!last_block) return;
 
     __shared__ double kl_s[kMaxCand];
     if ((int)threadIdx.x < ncand) {
@@ -664,7 +663,7 @@ kld_final_kernel(const KldPlan *__restrict__ plan, int rows, int bins, double al
                  double *kld, int32_t *sel, long long *grid_out)
 {
     kld_final_body(plan, rows, bins, alpha_in, kl_region(region, rows - 1, gridDim.x), wl_lo, il, eps, kld, sel, grid_out,
-                   BlockGeo{blockIdx.x, 0, gridDim.x, 1});
+                   BlockGeo{blockIdx.x, blockIdx.y, gridDim.x, gridDim.y});
 }
 
 // ---- batched form: the three phases of up to kKldBatchMax searches, one launch per phase --------------------
@@ -683,6 +682,7 @@ struct KldBatch {
     // first block of each tensor in the four launches (ascending)
     unsigned first_range[kKldBatchMax], first_hist[kKldBatchMax], first_sum[kKldBatchMax], first_final[kKldBatchMax];
     int count, wl_lo, wl_hi, mode;
+    int final_y;              // blocks per chunk of the final launch: the number of candidates, or 1
     unsigned long long seed;
     double eps, alpha;
     char *ws;
@@ -733,7 +733,7 @@ kld_final_batched_kernel(const KldBatch b)
     const int ncand = b.wl_hi - b.wl_lo + 1;
     kld_final_body(reinterpret_cast<const KldPlan *>(b.ws + it.off_plan), ncand + 1, it.bins, b.alpha,
                    kl_region(b.ws + it.off_klpart, ncand, it.nchunks), b.wl_lo, it.il, b.eps, it.kld, it.sel, nullptr,
-                   BlockGeo{l, 0, (unsigned)it.nchunks, 1});
+                   BlockGeo{l % (unsigned)it.nchunks, l / (unsigned)it.nchunks, (unsigned)it.nchunks, (unsigned)b.final_y});
 }
 
 static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int wl_hi, int il, int bins, double eps,
@@ -791,8 +791,8 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
     }
     hipLaunchKernelGGL(kld_sum_kernel, dim3(nchunks, rows), dim3(kChunk), 0, ctx->stream, plan, slabs, hist_grid, rows, bins, klpart,
                        hist);
-    hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks), dim3(kChunk), 0, ctx->stream, plan, rows, bins, alpha, klpart, wl_lo, il, eps,
-                       kld, sel, reinterpret_cast<long long *>(grid));
+    hipLaunchKernelGGL(kld_final_kernel, dim3(nchunks, ncand), dim3(kChunk), 0, ctx->stream, plan, rows, bins, alpha, klpart, wl_lo, il,
+                       eps, kld, sel, reinterpret_cast<long long *>(grid));
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -847,6 +847,8 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, const float
         uint64_t batch_elems = 0, batch_blocks = 0;
         const uint64_t per_block = (uint64_t)threads * 8;
         for (int m = 0; m < kKldBatchMax && t0 + m < count; ++m) batch_elems += items[t0 + m].n;
+        // a chunk's candidates share a block when the batch is large (see kld_final_body)
+        b.final_y = batch_elems >= ((uint64_t)1 << 21) ? 1 : ncand;
         // the launch ends with its most loaded block: no block takes more than `load` elements, and `load` is chosen so
         // that the blocks of all tensors (each rounded up) still number at most one per CU
         int batch_count = 0;
@@ -893,7 +895,7 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, const float
             nr += (unsigned)it.range_blocks;
             nh += (unsigned)(it.hist_x * it.groups);
             nsum += (unsigned)(it.nchunks * rows);
-            nf += (unsigned)it.nchunks;
+            nf += (unsigned)(it.nchunks * b.final_y);
             lds_max = std::max(lds_max, (size_t)rpg * per_row + 16);
             b.item[b.count++] = it;
         }
