@@ -20,7 +20,9 @@
  *   - Return value: ADAPT_OK (0) or a negative adapt_status.  Nothing is printed, no
  *     exceptions cross the boundary.  On error no kernel of that call has been launched.
  *   - Storage of a tensor in format <wl,fl>: int8_t for wl <= 8 (sign-extended codes),
- *     int16_t for 9 <= wl <= 16.  The represented value of code q is q * 2^-fl.
+ *     int16_t for 9 <= wl <= 16, int32_t for 17 <= wl <= 32 (adapt_quantize and the four
+ *     contractions take those; every other entry point stops at 16).  The represented value
+ *     of code q is q * 2^-fl.
  *   - Layouts: activations NHWC, filters KRSC (Cout, R, S, Cin), row-major, dense.
  */
 #ifndef ADAPT_FXP_H
@@ -36,7 +38,7 @@ extern "C" {
 typedef enum {
     ADAPT_OK = 0,
     ADAPT_EINVAL = -1,       /* null / misaligned pointer, size, WL, FL, bins or range out of bounds */
-    ADAPT_EUNSUPPORTED = -2, /* valid request this build does not implement (WL > 16, dilation, groups) */
+    ADAPT_EUNSUPPORTED = -2, /* valid request this build does not implement (WL > 16 where not stated, dilation, groups) */
     ADAPT_EBOUND = -3,       /* the reduction is too long for one block's int32 accumulators and the workspace
                                 cannot hold the partial sums of the splits that would keep them in bounds */
     ADAPT_EHIP = -4,         /* HIP runtime failure (see adapt_error_string / hipGetLastError) */
@@ -46,7 +48,8 @@ typedef enum {
 typedef struct adapt_ctx adapt_ctx; /* opaque: stream, device, workspace */
 
 /* Fixed-point format <WL,FL> (Sec. 2.1, Sec. 3.2): signed, wl total bits, fl fractional bits.
- * 2 <= wl <= 16, 0 <= fl <= 31 (fl need not be smaller than wl). */
+ * 2 <= wl <= 16 (32 where an entry point says so: Sec. 3.3 bounds precision at 32 bits),
+ * 0 <= fl <= 31 (fl need not be smaller than wl). */
 typedef struct { int wl, fl; } adapt_fmt;
 
 /* Rounding.  ADAPT_SR is the paper's stochastic rounding (Sec. 3.2): round down, or up with
@@ -64,7 +67,8 @@ typedef struct { int mode; uint64_t seed, stream; } adapt_rng;
 typedef struct { int n, h, w, c, k, r, s, stride, pad; } adapt_conv_desc;
 
 /* What a contraction writes.
- *  raw != 0 : the exact integer accumulator, int32_t if adapt_acc_bits(...) == 32 else int64_t.
+ *  raw != 0 : the exact integer accumulator: int32_t if adapt_acc_bits(...) == 32, int64_t if 64,
+ *             a 128-bit two's-complement integer (16 bytes, low 8 bytes first) if 128.
  *  raw == 0 : the accumulator converted to `fmt` (storage as for any tensor of that format):
  *             with s = fl_a + fl_b - fmt.fl,
  *               s <= 0      q = acc * 2^-s
@@ -134,7 +138,8 @@ int adapt_version(void);
  * t = floor(y * 2^16), q = min((t + R16) >> 16, 2^(wl-1)-1).  NaN gives 0, +-Inf saturate,
  * denormals are not flushed.
  *   x          device, fp32[n]
- *   q          device, int8_t[n] (wl <= 8) or int16_t[n]
+ *   q          device, int8_t[n] (wl <= 8), int16_t[n] (wl <= 16) or int32_t[n] (wl <= 32: the same rule
+ *              with t held in 64 bits)
  *   nnz        device uint64_t, may be NULL: number of non-zero codes (the paper's sp^l is
  *              nnz / n, Sec. 3.4 "Inducing Sparsity")
  *   saturated  device uint64_t, may be NULL: number of elements with x*2^fl outside the range
@@ -194,7 +199,18 @@ int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantize_item *ite
  * results, output shapes and rounding bits are those of the unpadded operands.  When one operand
  * has wl <= 8 and the other 9..16, the int8 operand is multiplied as a single limb. */
 
-/* 32 if K * 2^(wl_a-1) * 2^(wl_b-1) <= 2^31 - 1 (every possible sum fits int32), else 64. */
+/* Word lengths 17..32 (adapt_fxp_gemm, adapt_conv_fwd, adapt_conv_dgrad, adapt_conv_wgrad; operands
+ * and / or the requantized output): an operand above 16 bits is int32_t codes; the call splits it
+ * into three 11-bit parts a = a2 2^22 + a1 2^11 + a0 (a0, a1 in [0, 2047], a2 = a >> 22), runs the
+ * exact contraction of every pair of parts (nine for two such operands, three for one) on the int8
+ * matrix cores, adds the partial results at their weights 2^(11(i+j)) in 128-bit integers and applies
+ * the epilogue's rule once; the result is the exact contraction of the full codes, requantized as
+ * for any other.  The parts, one partial result (8 bytes per output) and the 128-bit sums (16 bytes
+ * per output) live in the workspace (adapt_workspace_bytes counts them).  adapt_fxp_gemm needs
+ * ldc == N and K > 0 on this path; adapt_conv_backward and the chain stop at 16 bits. */
+
+/* 32 if K * 2^(wl_a-1) * 2^(wl_b-1) <= 2^31 - 1 (every possible sum fits int32), else 64; 128 when
+ * an operand has more than 16 bits. */
 int adapt_acc_bits(int64_t K, adapt_fmt a, adapt_fmt b);
 
 /* C[M,N] = op(A)[M,K] . op(B)[K,N], exact over the integers.  Row-major with leading

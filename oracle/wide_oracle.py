@@ -1,0 +1,97 @@
+"""CPU oracle for contractions with word lengths 17..32 (AdaPT, arXiv 2107.13490: Sec. 3.3 bounds the
+precision that PushUp may ask for at 32 bits).
+
+TEST INFRASTRUCTURE ONLY.  Slow, plain reference; nothing in the product package may import it;
+only tests/, the smoke check and the benchmark's cpu_baseline leg do.  It shares no code with
+the HIP path.
+
+Codes of up to 32 bits multiply to 62 bits and a reduction adds more, so the exact sums do not fit
+64 bits: everything here is Python integers (numpy arrays of dtype object), the contractions written
+out from their definitions, and the accumulator -> <WL,FL> rule of the narrow oracle applied to those
+integers unchanged (shift <= 0: multiply; 1..16: add the top bits of the 16 random bits and shift;
+above 16: drop shift-16 bits, then the 16 guard bits; ReLU; saturation).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import fxp_oracle as orc
+
+
+def _obj(a):
+    return np.asarray(a).astype(object)
+
+
+def gemm(a, b, trans_a: bool = False, trans_b: bool = False):
+    a, b = _obj(a), _obj(b)
+    if trans_a:
+        a = a.T
+    if trans_b:
+        b = b.T
+    return a.dot(b)
+
+
+def conv_fwd(x, w, stride: int, pad: int):
+    """y[n,p,q,k] = sum_{r,s,c} x[n, p*stride - pad + r, q*stride - pad + s, c] * w[k,r,s,c] (zero padding)."""
+    x, w = _obj(x), _obj(w)
+    n, h, wd, c = x.shape
+    k, r, s, _ = w.shape
+    p, q = (h + 2 * pad - r) // stride + 1, (wd + 2 * pad - s) // stride + 1
+    y = np.zeros((n, p, q, k), dtype=object)
+    for i in range(p):
+        for j in range(q):
+            for dr in range(r):
+                for ds in range(s):
+                    hh, ww = i * stride - pad + dr, j * stride - pad + ds
+                    if 0 <= hh < h and 0 <= ww < wd:
+                        y[:, i, j, :] += x[:, hh, ww, :].dot(w[:, dr, ds, :].T)
+    return y
+
+
+def conv_dgrad(dy, w, h: int, wd: int, stride: int, pad: int):
+    """dx[n,hh,ww,c] = sum over the outputs that read it: dy[n,p,q,k] * w[k,r,s,c]."""
+    dy, w = _obj(dy), _obj(w)
+    n, p, q, k = dy.shape
+    _, r, s, c = w.shape
+    dx = np.zeros((n, h, wd, c), dtype=object)
+    for i in range(p):
+        for j in range(q):
+            for dr in range(r):
+                for ds in range(s):
+                    hh, ww = i * stride - pad + dr, j * stride - pad + ds
+                    if 0 <= hh < h and 0 <= ww < wd:
+                        dx[:, hh, ww, :] += dy[:, i, j, :].dot(w[:, dr, ds, :])
+    return dx
+
+
+def conv_wgrad(dy, x, r: int, s: int, stride: int, pad: int):
+    """dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride - pad + r, q*stride - pad + s, c]."""
+    dy, x = _obj(dy), _obj(x)
+    n, p, q, k = dy.shape
+    _, h, wd, c = x.shape
+    dw = np.zeros((k, r, s, c), dtype=object)
+    for i in range(p):
+        for j in range(q):
+            for dr in range(r):
+                for ds in range(s):
+                    hh, ww = i * stride - pad + dr, j * stride - pad + ds
+                    if 0 <= hh < h and 0 <= ww < wd:
+                        dw[:, dr, ds, :] += dy[:, i, j, :].T.dot(x[:, hh, ww, :])
+    return dw
+
+
+def requantize(acc, shift: int, wl_o: int, mode: int = orc.SR, seed: int = 0, stream: int = 0, relu: bool = False):
+    """The accumulator -> <wl_o, FL_o> rule of the narrow oracle on Python integers (wl_o up to 32)."""
+    a = _obj(acc)
+    flat = a.ravel()
+    if shift <= 0:
+        q = flat * (1 << (-shift))
+    else:
+        bits = orc.rounding_bits(flat.size, mode, seed, stream).astype(object)
+        if shift <= 16:
+            q = np.array([(int(v) + (int(r) >> (16 - shift))) >> shift for v, r in zip(flat, bits)], dtype=object)
+        else:
+            q = np.array([((int(v) >> (shift - 16)) + int(r)) >> 16 for v, r in zip(flat, bits)], dtype=object)
+    lo, hi = -(1 << (wl_o - 1)), (1 << (wl_o - 1)) - 1
+    q = np.array([min(max(max(int(v), 0) if relu else int(v), lo), hi) for v in q], dtype=np.int64)
+    return q.reshape(a.shape)

@@ -354,7 +354,7 @@ class Context:
     @staticmethod
     def storage_dtype(wl: int):
         import torch
-        return torch.int8 if wl <= 8 else torch.int16
+        return torch.int8 if wl <= 8 else torch.int16 if wl <= 16 else torch.int32
 
     # -- quantize -----------------------------------------------------------------------------
     def quantize(self, x, wl, fl, mode=SR, seed=0, stream=0, out=None, counters=None):
@@ -408,6 +408,13 @@ class Context:
             return torch.int32 if self._lib.adapt_acc_bits(k_total, fa, fb) == 32 else torch.int64
         return self.storage_dtype(ep.fmt.wl)
 
+    def _out_tensor(self, shape, k_total, fa, fb, ep, device):
+        """Exact sums of operands above 16 bits are 128-bit integers: an int64 tensor with a last axis (low, high)."""
+        torch = self._torch
+        if ep.raw and self._lib.adapt_acc_bits(k_total, fa, fb) == 128:
+            return torch.empty(tuple(shape) + (2,), dtype=torch.int64, device=device)
+        return torch.empty(tuple(shape), dtype=self._out_dtype(k_total, fa, fb, ep), device=device)
+
     def fxp_gemm(self, a, fa, b, fb, ep, trans_a=False, trans_b=False, out=None):
         torch = self._torch
         m, k = (a.shape[1], a.shape[0]) if trans_a else a.shape
@@ -415,18 +422,19 @@ class Context:
         assert k == k2
         fa, fb = Fmt(*fa), Fmt(*fb)
         if out is None:
-            out = torch.empty((m, n), dtype=self._out_dtype(k, fa, fb, ep), device=a.device)
+            out = self._out_tensor((m, n), k, fa, fb, ep, a.device)
         lda = a.stride(0) if a.numel() else max(a.shape[1], 1)      # empty tensors report stride 0
         ldb = b.stride(0) if b.numel() else max(b.shape[1], 1)
+        ldc = n if out.dim() == 3 else out.stride(0)
         _check(self._lib.adapt_fxp_gemm(self._h, int(trans_a), int(trans_b), m, n, k, _ptr(a), fa, lda,
-                                        _ptr(b), fb, ldb, _ptr(out), out.stride(0), ep), "adapt_fxp_gemm")
+                                        _ptr(b), fb, ldb, _ptr(out), ldc, ep), "adapt_fxp_gemm")
         return out
 
     def conv_fwd(self, d: ConvDesc, x, fx, w, fw, ep, out=None):
         torch = self._torch
         fx, fw = Fmt(*fx), Fmt(*fw)
         if out is None:
-            out = torch.empty((d.n, d.p, d.q, d.k), dtype=self._out_dtype(d.r * d.s * d.c, fx, fw, ep), device=x.device)
+            out = self._out_tensor((d.n, d.p, d.q, d.k), d.r * d.s * d.c, fx, fw, ep, x.device)
         _check(self._lib.adapt_conv_fwd(self._h, d, _ptr(x), fx, _ptr(w), fw, _ptr(out), ep), "adapt_conv_fwd")
         return out
 
@@ -434,7 +442,7 @@ class Context:
         torch = self._torch
         fdy, fw = Fmt(*fdy), Fmt(*fw)
         if out is None:
-            out = torch.empty((d.n, d.h, d.w, d.c), dtype=self._out_dtype(d.r * d.s * d.k, fdy, fw, ep), device=dy.device)
+            out = self._out_tensor((d.n, d.h, d.w, d.c), d.r * d.s * d.k, fdy, fw, ep, dy.device)
         _check(self._lib.adapt_conv_dgrad(self._h, d, _ptr(dy), fdy, _ptr(w), fw, _ptr(out), ep), "adapt_conv_dgrad")
         return out
 
@@ -442,7 +450,7 @@ class Context:
         torch = self._torch
         fdy, fx = Fmt(*fdy), Fmt(*fx)
         if out is None:
-            out = torch.empty((d.k, d.r, d.s, d.c), dtype=self._out_dtype(d.n * d.p * d.q, fdy, fx, ep), device=dy.device)
+            out = self._out_tensor((d.k, d.r, d.s, d.c), d.n * d.p * d.q, fdy, fx, ep, dy.device)
         _check(self._lib.adapt_conv_wgrad(self._h, d, _ptr(dy), fdy, _ptr(x), fx, _ptr(out), ep), "adapt_conv_wgrad")
         return out
 

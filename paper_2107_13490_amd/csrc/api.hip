@@ -67,7 +67,8 @@ extern "C" int adapt_set_stream(adapt_ctx *c, void *hip_stream)
 
 extern "C" int adapt_acc_bits(int64_t K, adapt_fmt a, adapt_fmt b)
 {
-    if (K < 0 || !fmt_ok(a) || !fmt_ok(b)) return ADAPT_EINVAL;
+    if (K < 0 || !fmt_ok_wide(a) || !fmt_ok_wide(b)) return ADAPT_EINVAL;
+    if (a.wl > 16 || b.wl > 16) return 128;                  // the composed path for wide operands sums in 128 bits
     // K * 2^(wl_a-1) * 2^(wl_b-1) <= 2^31 - 1, evaluated without overflow (K < 2^63, shift <= 30)
     const int sh = a.wl + b.wl - 2;
     const int64_t lim = ((int64_t)1 << 31) - 1;

@@ -32,6 +32,16 @@ constexpr size_t kStaticScratchBytes = 32 * 1024;      // static scratch of the 
 hipError_t static_scratch_address(void **ptr);         // of the current device's copy
 constexpr size_t kDefaultWorkspace = (size_t)64 << 20;
 
+}  // namespace adapt
+#include <functional>
+namespace adapt {
+// Contraction with operands or an output of 17..32 bits, composed of exact contractions of 11-bit parts (wide.hip).
+// sub(a_part, fa, b_part, fb, c, exact epilogue) runs one of them; elems_*: codes in each operand's allocation.
+typedef std::function<int(const void *, adapt_fmt, const void *, adapt_fmt, void *, adapt_epilogue)> SubContraction;
+int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems_a, const void *b, adapt_fmt fb, uint64_t elems_b,
+                     uint64_t outputs, int64_t k_total, void *out, adapt_epilogue ep, const SubContraction &sub);
+size_t ws_need_wide(uint64_t elems_a, bool wide_a, uint64_t elems_b, bool wide_b, uint64_t outputs, bool raw);
+
 inline char *scratch(adapt_ctx *c) { return c->ws + kCtlBytes; }
 inline size_t scratch_bytes(const adapt_ctx *c) { return c->ws_bytes - kCtlBytes; }
 inline uint32_t *ticket(adapt_ctx *c, int slot) { return reinterpret_cast<uint32_t *>(c->ws) + slot; }
@@ -68,5 +78,9 @@ size_t ws_need_requantize_fit(int num_cu, uint64_t n);
 
 inline bool fmt_ok(adapt_fmt f) { return f.wl >= 2 && f.wl <= 16 && f.fl >= 0 && f.fl <= 31; }
 inline int storage_bytes(adapt_fmt f) { return f.wl <= 8 ? 1 : 2; }
+// word lengths 17..32 (int32 codes): only the entry points that say so take them
+// true when a contraction with these formats takes the composed path for word lengths above 16
+inline bool wants_wide(adapt_fmt fa, adapt_fmt fb, const adapt_epilogue &ep) { return fa.wl > 16 || fb.wl > 16 || (!ep.raw && ep.fmt.wl > 16); }
+inline bool fmt_ok_wide(adapt_fmt f) { return f.wl >= 2 && f.wl <= 32 && f.fl >= 0 && f.fl <= 31; }
 
 }  // namespace adapt

@@ -7,6 +7,17 @@ using namespace adapt;
 extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *w,
                                 adapt_fmt fw, void *dx, adapt_epilogue ep)
 {
+    if (ctx && wants_wide(fdy, fw, ep)) {
+        if (!conv_ok(d)) return ADAPT_EINVAL;
+        if (d.n == 0) return ADAPT_OK;
+        if (!check_ptrs(dy, w, dx)) return ADAPT_EINVAL;
+        const int p = (d.h + 2 * d.pad - d.r) / d.stride + 1, q = (d.w + 2 * d.pad - d.s) / d.stride + 1;
+        const SubContraction sub = [&](const void *pa, adapt_fmt fpa, const void *pb, adapt_fmt fpb, void *c, adapt_epilogue ex) {
+            return adapt_conv_dgrad(ctx, d, pa, fpa, pb, fpb, c, ex);
+        };
+        return wide_contraction(ctx, dy, fdy, (uint64_t)d.n * p * q * d.k, w, fw, (uint64_t)d.k * d.r * d.s * d.c, (uint64_t)d.n * d.h * d.w * d.c,
+                                (int64_t)d.r * d.s * d.k, dx, ep, sub);
+    }
     if (!ctx || !fmt_ok(fdy) || !fmt_ok(fw) || !conv_ok(d)) return ADAPT_EINVAL;
     if (d.n == 0) return ADAPT_OK;
     if (!check_ptrs(dy, w, dx)) return ADAPT_EINVAL;

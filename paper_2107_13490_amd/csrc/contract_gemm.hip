@@ -6,6 +6,18 @@ using namespace adapt;
 extern "C" int adapt_fxp_gemm(adapt_ctx *ctx, int transA, int transB, int M, int N, int K, const void *A, adapt_fmt fa,
                               int lda, const void *B, adapt_fmt fb, int ldb, void *C, int ldc, adapt_epilogue ep)
 {
+    if (ctx && wants_wide(fa, fb, ep)) {
+        if (M < 0 || N < 0 || K < 0) return ADAPT_EINVAL;
+        if (M == 0 || N == 0) return ADAPT_OK;
+        if (!C || !aligned16(C) || (K > 0 && (!A || !B || !aligned16(A) || !aligned16(B)))) return ADAPT_EINVAL;
+        if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return ADAPT_EINVAL;
+        if (ldc != N || K == 0) return ADAPT_EUNSUPPORTED;
+        const SubContraction sub = [&](const void *pa, adapt_fmt fpa, const void *pb, adapt_fmt fpb, void *c, adapt_epilogue ex) {
+            return adapt_fxp_gemm(ctx, transA, transB, M, N, K, pa, fpa, lda, pb, fpb, ldb, c, N, ex);
+        };
+        return wide_contraction(ctx, A, fa, (uint64_t)(transA ? K : M) * lda, B, fb, (uint64_t)(transB ? N : K) * ldb, (uint64_t)M * N, K, C,
+                                ep, sub);
+    }
     if (!ctx || !fmt_ok(fa) || !fmt_ok(fb) || M < 0 || N < 0 || K < 0) return ADAPT_EINVAL;
     if (M == 0 || N == 0) return ADAPT_OK;
     if (!C || !aligned16(C) || ldc < N) return ADAPT_EINVAL;

@@ -7,6 +7,17 @@ using namespace adapt;
 extern "C" int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *x,
                                 adapt_fmt fx, void *dw, adapt_epilogue ep)
 {
+    if (ctx && wants_wide(fdy, fx, ep)) {
+        if (!conv_ok(d)) return ADAPT_EINVAL;
+        if (!dw || !aligned16(dw) || (d.n > 0 && !check_ptrs(dy, x, dw))) return ADAPT_EINVAL;
+        if (d.n == 0) return ADAPT_EUNSUPPORTED;             // (an empty batch would only clear dw)
+        const int p = (d.h + 2 * d.pad - d.r) / d.stride + 1, q = (d.w + 2 * d.pad - d.s) / d.stride + 1;
+        const SubContraction sub = [&](const void *pa, adapt_fmt fpa, const void *pb, adapt_fmt fpb, void *c, adapt_epilogue ex) {
+            return adapt_conv_wgrad(ctx, d, pa, fpa, pb, fpb, c, ex);
+        };
+        return wide_contraction(ctx, dy, fdy, (uint64_t)d.n * p * q * d.k, x, fx, (uint64_t)d.n * d.h * d.w * d.c, (uint64_t)d.k * d.r * d.s * d.c,
+                                (int64_t)d.n * p * q, dw, ep, sub);
+    }
     if (!ctx || !fmt_ok(fdy) || !fmt_ok(fx) || !conv_ok(d)) return ADAPT_EINVAL;
     if (!dw || !aligned16(dw)) return ADAPT_EINVAL;
     if (d.n > 0 && !check_ptrs(dy, x, dw)) return ADAPT_EINVAL;

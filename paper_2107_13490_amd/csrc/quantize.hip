@@ -128,6 +128,67 @@ quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, i
     }
 }
 
+// Word lengths 17..32 (Sec. 3.3 bounds precision at 32 bits): int32 codes.  The scaled value with its 16 guard bits
+// needs up to 48 bits, so the rule of quantize_one is evaluated in fp64 and 64-bit integers (all steps exact).
+__device__ __forceinline__ int quantize_one_wide(float x, uint32_t r16, int wl, int fl, int &sat)
+{
+    const double y = ldexp((double)x, fl);
+    const double qmin = -ldexp(1.0, wl - 1), qmax = ldexp(1.0, wl - 1) - 1.0;
+    sat = (y < qmin) | (y > qmax);                         // false for NaN
+    const double yc = fmin(fmax(y, qmin), qmax);
+    const long long t = (long long)floor(yc * 65536.0);
+    long long q = (t + (long long)r16) >> 16;
+    q = q > (long long)qmax ? (long long)qmax : q;
+    return (x != x) ? 0 : (int)q;
+}
+
+__global__ void __launch_bounds__(kQThreads)
+quantize_wide_kernel(const float *__restrict__ x, int32_t *__restrict__ q, uint64_t n, int wl, int fl, int mode, uint64_t seed,
+                     uint64_t stream, uint32_t *partial /* [2][gridDim.x] or null */)
+{
+    uint32_t nnz = 0, nsat = 0;
+    const uint64_t full_groups = n >> 3;
+    const uint64_t first = (uint64_t)blockIdx.x * kQThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kQThreads;
+    for (uint64_t g = first; g < full_groups; g += stride) {
+        const float4 a = reinterpret_cast<const float4 *>(x)[2 * g], b = reinterpret_cast<const float4 *>(x)[2 * g + 1];
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        uint32_t r[8];
+        if (mode == ADAPT_SR) {
+            const u32x4 blk = rounding_block(seed, stream, g);
+            r[0] = blk.x & 0xffffu; r[1] = blk.x >> 16; r[2] = blk.y & 0xffffu; r[3] = blk.y >> 16;
+            r[4] = blk.z & 0xffffu; r[5] = blk.z >> 16; r[6] = blk.w & 0xffffu; r[7] = blk.w >> 16;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = 0x8000u;
+        }
+        int c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int s;
+            c[e] = quantize_one_wide(v[e], r[e], wl, fl, s);
+            nnz += (c[e] != 0);
+            nsat += s;
+        }
+        reinterpret_cast<int4 *>(q)[2 * g] = make_int4(c[0], c[1], c[2], c[3]);
+        reinterpret_cast<int4 *>(q)[2 * g + 1] = make_int4(c[4], c[5], c[6], c[7]);
+    }
+    if ((n & 7) && first == 0)
+        for (uint64_t i = full_groups << 3; i < n; ++i) {
+            int s;
+            const int c = quantize_one_wide(x[i], rounding_bits_of(seed, stream, i, mode), wl, fl, s);
+            q[i] = c;
+            nnz += (c != 0);
+            nsat += s;
+        }
+    if (partial == nullptr) return;
+    uint64_t bn, bs;
+    block_sum2(nnz, nsat, bn, bs);
+    if (threadIdx.x == 0) {
+        partial[blockIdx.x] = (uint32_t)bn;
+        partial[gridDim.x + blockIdx.x] = (uint32_t)bs;
+    }
+}
+
 // Sums the per-block partial counts (partial[col][block]) into out[col]: one wavefront per column,
 // all loads of a lane in flight at once.  A separate launch: the kernel boundary makes the
 // partials visible without fences that would force the L2 to write back the freshly quantized
@@ -288,7 +349,7 @@ using namespace adapt;
 static int quantize_on(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, adapt_rng rng, void *q, uint64_t *nnz,
                        uint64_t *saturated, char *base, size_t room)
 {
-    if (!ctx || !fmt_ok(fmt) || (rng.mode != ADAPT_SR && rng.mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(fmt) || (rng.mode != ADAPT_SR && rng.mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
     if (n > 0 && (!x || !q || !aligned16(x) || !aligned16(q))) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if ((nnz && ((uintptr_t)nnz & 7)) || (saturated && ((uintptr_t)saturated & 7))) return ADAPT_EINVAL;
@@ -297,7 +358,10 @@ static int quantize_on(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt fmt, 
     const size_t part_bytes = ((size_t)grid * 8 + 255) & ~(size_t)255;
     if (part_bytes + 16 > room) return ADAPT_EWORKSPACE;
     uint32_t *partial = count ? reinterpret_cast<uint32_t *>(base) : nullptr;
-    if (fmt.wl <= 8)
+    if (fmt.wl > 16)
+        hipLaunchKernelGGL(quantize_wide_kernel, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int32_t *)q, (uint64_t)n, fmt.wl,
+                           fmt.fl, rng.mode, rng.seed, rng.stream, partial);
+    else if (fmt.wl <= 8)
         hipLaunchKernelGGL(quantize_kernel<int8_t>, dim3(grid), dim3(kQThreads), 0, ctx->stream, x, (int8_t *)q,
                            (uint64_t)n, fmt.wl, fmt.fl, rng.mode, rng.seed, rng.stream, partial);
     else

@@ -1,0 +1,167 @@
+// Contractions with word lengths 17..32 (Sec. 3.3 bounds the precision that PushUp may ask for at
+// 32 bits).  An operand of up to 32 bits is held as int32 codes and split into three parts of 11 bits,
+//     a = a2 2^22 + a1 2^11 + a0,   a0, a1 in [0, 2047],   a2 = a >> 22 in [-512, 511],
+// each a 12-bit code that the two-limb int8 MFMA kernels of this library take; an operand of at most
+// 16 bits stays as it is.  Every pair of parts is one exact contraction (int32 or int64 sums, by the
+// accumulator bound of that pair); the partial results are added at their weights 2^(11(i+j)) in
+// 128-bit integers, and the requantizing rule of the contraction epilogue (or the exact 128-bit sum)
+// is applied once at the end.  Nine contractions for two wide operands, three when one is narrow:
+// the cost of precision above 16 bits on hardware whose matrix cores multiply bytes.
+//
+// The host code below composes the library's own entry points; the three kernels here are bound by
+// HBM traffic (split: 4 B read, 6 B written per code; accumulate: 4-8 B read, 16 B read and written
+// per output and part pair; finish: 16 B read, 1-4 B written per output).
+#include <algorithm>
+#include <functional>
+
+#include "common.hpp"
+#include "context.hpp"
+
+namespace adapt {
+
+constexpr int kWideThreads = 256;
+constexpr int kPartBits = 11;
+
+typedef __int128 i128;
+
+__global__ void __launch_bounds__(kWideThreads)
+split3_kernel(const int32_t *__restrict__ a, int16_t *__restrict__ p0, int16_t *__restrict__ p1, int16_t *__restrict__ p2, uint64_t n)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWideThreads) {
+        const int32_t v = a[i];
+        p0[i] = (int16_t)(v & 2047);
+        p1[i] = (int16_t)((v >> kPartBits) & 2047);
+        p2[i] = (int16_t)(v >> (2 * kPartBits));
+    }
+}
+
+// acc[i] (+)= c[i] * 2^sh
+template <typename CT>
+__global__ void __launch_bounds__(kWideThreads)
+acc128_kernel(const CT *__restrict__ c, int sh, i128 *__restrict__ acc, uint64_t n, int first)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWideThreads) {
+        const i128 v = (i128)((unsigned __int128)(i128)c[i] << sh);
+        acc[i] = first ? v : acc[i] + v;
+    }
+}
+
+// the contraction epilogue's rule on a 128-bit accumulator, output of up to 32 bits
+__device__ __forceinline__ int requantize_wide_one(i128 acc, int shift, int wl, int relu, uint32_t r16)
+{
+    i128 q;
+    if (shift <= 0) {
+        const i128 lim = (i128)1 << 33;                      // beyond any 32-bit range: saturates below
+        const i128 c = acc > lim ? lim : acc < -lim ? -lim : acc;
+        const int l = -shift > 62 ? 62 : -shift;
+        q = (i128)((unsigned __int128)c << l);
+    } else if (shift <= 16) {
+        q = (acc + (i128)(r16 >> (16 - shift))) >> shift;
+    } else {
+        q = ((acc >> (shift - 16)) + (i128)r16) >> 16;
+    }
+    if (relu && q < 0) q = 0;
+    const i128 qmax = ((i128)1 << (wl - 1)) - 1, qmin = -((i128)1 << (wl - 1));
+    return (int)(q > qmax ? qmax : q < qmin ? qmin : q);
+}
+
+template <typename OutT>
+__global__ void __launch_bounds__(kWideThreads)
+finish128_kernel(const i128 *__restrict__ acc, OutT *__restrict__ out, uint64_t n, int shift, int wl, int relu, int mode, uint64_t seed,
+                 uint64_t stream)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWideThreads)
+        out[i] = (OutT)requantize_wide_one(acc[i], shift, wl, relu, rounding_bits_of(seed, stream, i, mode));
+}
+
+static int wide_grid(const adapt_ctx *ctx, uint64_t n)
+{
+    return (int)std::min<uint64_t>(std::max<uint64_t>((n + kWideThreads - 1) / kWideThreads, 1), (uint64_t)ctx->num_cu * 8);
+}
+
+static size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t ws_need_wide(uint64_t elems_a, bool wide_a, uint64_t elems_b, bool wide_b, uint64_t outputs, bool raw)
+{
+    return (wide_a ? 3 * a256(elems_a * 2) : 0) + (wide_b ? 3 * a256(elems_b * 2) : 0) + a256(outputs * 8) + (raw ? 0 : a256(outputs * 16));
+}
+
+// One operand of a wide contraction: its parts (pointers, formats) after the split
+struct WideOperand {
+    const void *part[3];
+    adapt_fmt fmt[3];
+    int parts;
+};
+
+int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems_a, const void *b, adapt_fmt fb, uint64_t elems_b,
+                     uint64_t outputs, int64_t k_total, void *out, adapt_epilogue ep, const SubContraction &sub)
+{
+    if (!fmt_ok_wide(fa) || !fmt_ok_wide(fb)) return ADAPT_EINVAL;
+    if (!ep.raw && (!fmt_ok_wide(ep.fmt) || (ep.rng.mode != ADAPT_SR && ep.rng.mode != ADAPT_RN_HALF_UP))) return ADAPT_EINVAL;
+    if (outputs == 0) return ADAPT_OK;
+    const bool wide_a = fa.wl > 16, wide_b = fb.wl > 16;
+    // buffers of this call at the end of the workspace; the contractions of the parts see the rest
+    const size_t tail = ws_need_wide(elems_a, wide_a, elems_b, wide_b, outputs, ep.raw != 0);
+    const size_t keep = (size_t)1 << 20;
+    if (tail + keep > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    const size_t saved = ctx->ws_bytes;
+    char *base = ctx->ws + saved - tail;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = base + off; off += a256(bytes); return p; };
+    WideOperand A, B;
+    auto prepare = [&](WideOperand &o, const void *p, adapt_fmt f, uint64_t elems, bool wide) {
+        if (!wide) {
+            o.parts = 1; o.part[0] = p; o.fmt[0] = f;
+            return;
+        }
+        o.parts = 3;
+        int16_t *q[3];
+        for (int i = 0; i < 3; ++i) {
+            q[i] = reinterpret_cast<int16_t *>(take(elems * 2));
+            o.part[i] = q[i];
+            o.fmt[i] = adapt_fmt{12, 0};
+        }
+        hipLaunchKernelGGL(split3_kernel, dim3(wide_grid(ctx, elems)), dim3(kWideThreads), 0, ctx->stream,
+                           static_cast<const int32_t *>(p), q[0], q[1], q[2], elems);
+    };
+    prepare(A, a, fa, elems_a, wide_a);
+    prepare(B, b, fb, elems_b, wide_b);
+    void *c = take(outputs * 8);
+    i128 *acc = ep.raw ? static_cast<i128 *>(out) : reinterpret_cast<i128 *>(take(outputs * 16));
+    adapt_epilogue ex = {};
+    ex.raw = 1;
+    ex.fmt = adapt_fmt{8, 0};
+    ex.rng.mode = ADAPT_RN_HALF_UP;
+    int status = ADAPT_OK;
+    ctx->ws_bytes = saved - tail;                      // what the part contractions may use
+    bool first = true;
+    for (int i = 0; i < A.parts && status == ADAPT_OK; ++i)
+        for (int j = 0; j < B.parts && status == ADAPT_OK; ++j) {
+            status = sub(A.part[i], A.fmt[i], B.part[j], B.fmt[j], c, ex);
+            if (status != ADAPT_OK) break;
+            const int sh = kPartBits * ((wide_a ? i : 0) + (wide_b ? j : 0));
+            const int bits = adapt_acc_bits(k_total, A.fmt[i], B.fmt[j]);
+            const dim3 g(wide_grid(ctx, outputs)), t(kWideThreads);
+            if (bits == 32) hipLaunchKernelGGL(acc128_kernel<int32_t>, g, t, 0, ctx->stream, static_cast<const int32_t *>(c), sh, acc, outputs, first ? 1 : 0);
+            else hipLaunchKernelGGL(acc128_kernel<int64_t>, g, t, 0, ctx->stream, static_cast<const int64_t *>(c), sh, acc, outputs, first ? 1 : 0);
+            first = false;
+        }
+    ctx->ws_bytes = saved;
+    if (status != ADAPT_OK) return status;
+    if (!ep.raw) {
+        const int shift = fa.fl + fb.fl - ep.fmt.fl;
+        const dim3 g(wide_grid(ctx, outputs)), t(kWideThreads);
+        if (ep.fmt.wl <= 8)
+            hipLaunchKernelGGL(finish128_kernel<int8_t>, g, t, 0, ctx->stream, acc, static_cast<int8_t *>(out), outputs, shift, ep.fmt.wl,
+                               ep.relu != 0, ep.rng.mode, ep.rng.seed, ep.rng.stream);
+        else if (ep.fmt.wl <= 16)
+            hipLaunchKernelGGL(finish128_kernel<int16_t>, g, t, 0, ctx->stream, acc, static_cast<int16_t *>(out), outputs, shift, ep.fmt.wl,
+                               ep.relu != 0, ep.rng.mode, ep.rng.seed, ep.rng.stream);
+        else
+            hipLaunchKernelGGL(finish128_kernel<int32_t>, g, t, 0, ctx->stream, acc, static_cast<int32_t *>(out), outputs, shift, ep.fmt.wl,
+                               ep.relu != 0, ep.rng.mode, ep.rng.seed, ep.rng.stream);
+    }
+    return hip_status(ctx, hipGetLastError());
+}
+
+}  // namespace adapt

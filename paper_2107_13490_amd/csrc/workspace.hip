@@ -80,7 +80,20 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
         case ADAPT_CALL_QUANTIZE_BATCHED:
             return q->count < 0 ? kInvalid : ws_need_quantize_batched(num_cu, q->count) + slack;
         case ADAPT_CALL_GEMM: {
-            if (q->M < 0 || q->N < 0 || q->K < 0 || !fmt_ok(q->fa) || !fmt_ok(q->fb)) return kInvalid;
+            if (q->M < 0 || q->N < 0 || q->K < 0 || !fmt_ok_wide(q->fa) || !fmt_ok_wide(q->fb)) return kInvalid;
+            if (q->fa.wl > 16 || q->fb.wl > 16) {
+                // word lengths above 16: the parts, one exact partial result and the 128-bit sums, after the largest
+                // contraction of two 12-bit parts (or of a part and the narrow operand)
+                adapt_workspace_query sub = *q;
+                if (sub.fa.wl > 16) sub.fa = adapt_fmt{12, 0};
+                if (sub.fb.wl > 16) sub.fb = adapt_fmt{12, 0};
+                const size_t inner = adapt_workspace_bytes(ctx, &sub);
+                if (inner == kInvalid) return kInvalid;
+                const int lda = q->lda ? q->lda : (q->transA ? q->M : q->K), ldb = q->ldb ? q->ldb : (q->transB ? q->K : q->N);
+                return std::max<size_t>(inner, (size_t)1 << 20) +
+                       ws_need_wide((uint64_t)(q->transA ? q->K : q->M) * lda, q->fa.wl > 16, (uint64_t)(q->transB ? q->N : q->K) * ldb,
+                                    q->fb.wl > 16, (uint64_t)q->M * q->N, false) + slack;
+            }
             const int lda = q->lda ? q->lda : (q->transA ? q->M : q->K), ldb = q->ldb ? q->ldb : (q->transB ? q->K : q->N);
             ContractArgs a = {};
             fill_gemm(a, q->transA, q->transB, q->M, q->N, q->K, nullptr, q->fa, lda, nullptr, q->fb, ldb, nullptr, q->N);
@@ -93,6 +106,20 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
         case ADAPT_CALL_CONV_DGRAD:
         case ADAPT_CALL_CONV_WGRAD:
         case ADAPT_CALL_CONV_BACKWARD: {
+            if (q->call != ADAPT_CALL_CONV_BACKWARD && fmt_ok_wide(q->fa) && fmt_ok_wide(q->fb) && (q->fa.wl > 16 || q->fb.wl > 16) &&
+                conv_ok(q->conv)) {
+                adapt_workspace_query sub = *q;
+                if (sub.fa.wl > 16) sub.fa = adapt_fmt{12, 0};
+                if (sub.fb.wl > 16) sub.fb = adapt_fmt{12, 0};
+                const size_t inner = adapt_workspace_bytes(ctx, &sub);
+                if (inner == kInvalid) return kInvalid;
+                const adapt_conv_desc &d = q->conv;
+                const uint64_t p = (d.h + 2 * d.pad - d.r) / d.stride + 1, qq = (d.w + 2 * d.pad - d.s) / d.stride + 1;
+                const uint64_t nx = (uint64_t)d.n * d.h * d.w * d.c, nw = (uint64_t)d.k * d.r * d.s * d.c, ny = (uint64_t)d.n * p * qq * d.k;
+                const uint64_t ea = q->call == ADAPT_CALL_CONV_FWD ? nx : ny, eb = q->call == ADAPT_CALL_CONV_WGRAD ? nx : nw;
+                const uint64_t outs = q->call == ADAPT_CALL_CONV_FWD ? ny : q->call == ADAPT_CALL_CONV_DGRAD ? nx : nw;
+                return std::max<size_t>(inner, (size_t)1 << 20) + ws_need_wide(ea, q->fa.wl > 16, eb, q->fb.wl > 16, outs, false) + slack;
+            }
             if (!fmt_ok(q->fa) || !fmt_ok(q->fb) || !conv_ok(q->conv)) return kInvalid;
             if (q->call == ADAPT_CALL_CONV_BACKWARD && !fmt_ok(q->fc)) return kInvalid;
             const size_t need = conv_need(&dry, q->call, q->conv, q->fa, q->fb, q->fc);

@@ -254,9 +254,11 @@ def test_config3_full_size_sampled():
 def test_invalid_arguments():
     a = torch.zeros((16, 16), dtype=torch.int8, device="cuda")
     with pytest.raises(pkg.AdaptError):
-        ctx().fxp_gemm(a, (17, 0), a, (8, 0), Epilogue.exact())
+        ctx().fxp_gemm(a, (33, 0), a, (8, 0), Epilogue.exact())
     with pytest.raises(pkg.AdaptError):
-        ctx().fxp_gemm(a, (8, 0), a, (8, 0), Epilogue.requant(20, 0))
+        ctx().fxp_gemm(a, (8, 0), a, (8, 0), Epilogue.requant(33, 0))
+    with pytest.raises(pkg.AdaptError):
+        ctx().fxp_gemm(a, (8, 32), a, (8, 0), Epilogue.exact())
     d = ConvDesc(1, 2, 2, 16, 16, 5, 5, 1, 0)        # filter larger than the padded input
     with pytest.raises(pkg.AdaptError):
         ctx().conv_fwd(d, a, (8, 0), a, (8, 0), Epilogue.exact(), out=a)

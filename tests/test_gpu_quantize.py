@@ -106,7 +106,7 @@ def test_batched_many_items():
 def test_invalid_arguments_are_rejected():
     x = torch.zeros(64, dtype=torch.float32, device="cuda")
     with pytest.raises(pkg.AdaptError) as e:
-        ctx().quantize(x, 17, 4)
+        ctx().quantize(x, 33, 4)
     assert e.value.status == -1
     with pytest.raises(pkg.AdaptError):
         ctx().quantize(x, 8, 32)

@@ -34,7 +34,7 @@ def test_quantize_noalloc_argument_checks_and_other_contexts_share_the_array():
     out = torch.empty(4096, dtype=torch.int8, device="cuda")
     cnt = torch.zeros(2, dtype=torch.int64, device="cuda")
     with pytest.raises(pkg.AdaptError):
-        c.quantize_noalloc(x, 17, 5, pkg.SR, 0, 0, out, cnt)
+        c.quantize_noalloc(x, 33, 5, pkg.SR, 0, 0, out, cnt)
     with pytest.raises(pkg.AdaptError):
         c.quantize_noalloc(x[1:], 8, 5, pkg.SR, 0, 0, out, cnt)          # misaligned input
     tiny = pkg.Context(workspace_bytes=256)                               # no room for partials in its workspace: not needed
