@@ -261,7 +261,7 @@ int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt
  *   hist     device uint32_t[(wl_hi - wl_lo + 2) * bins] or NULL: row 0 = counts of Q, row
  *            1 + c = counts of P_c; entries nb..bins-1 of every row are zero
  *   grid     device int64_t[3] or NULL: e, floor(min w / 2^e), nb  (0,0,0 in the degenerate case)
- * Limits: 2 <= wl_lo <= wl_hi <= 16, 1 <= il, wl_lo - il >= 0, wl_hi - il <= 31,
+ * Limits: 2 <= wl_lo <= wl_hi <= 32 (above 16 the scaled value is held in 64 bits), 1 <= il, wl_lo - il >= 0, wl_hi - il <= 31,
  * 2 <= bins <= 65536. */
 int adapt_kld_precision_search(adapt_ctx *ctx, const float *w, size_t n, int wl_lo, int wl_hi,
                                int il, int bins, double eps, double alpha, adapt_rng rng,

@@ -22,7 +22,7 @@
 
 namespace adapt {
 
-constexpr int kMaxCand = 15;
+constexpr int kMaxCand = 31;                      // candidate word lengths 2..32
 constexpr int kHistMaxThreads = 1024;
 constexpr int kRangeThreads = 256;
 constexpr size_t kLdsBudget = 156 * 1024;      // dynamic LDS of a block; 160 KB per CU less the static part
@@ -53,6 +53,8 @@ struct KldPlan {
     float base_f;     // floor(lo * 2^-e), exactly representable
     float tscale;     // 2^(FLmax + 16)
     float tmin, tmax; // code range of the widest candidate, times 2^16
+    int wide;         // candidates above 16 bits: the scaled value needs 48 bits (fp64 scaling, 64-bit integer forms)
+    double tscale_d, tmin_d, tmax_d;
     long long base;
     KldCand cand[kMaxCand];
 };
@@ -81,6 +83,10 @@ __device__ void make_grid(KldPlan *plan, float lo, float hi, int wl_hi, int il, 
     plan->tscale = ldexpf(1.0f, flmax + 16);
     plan->tmin = -ldexpf(1.0f, wl_hi - 1 + 16);
     plan->tmax = (ldexpf(1.0f, wl_hi - 1) - 1.0f) * 65536.0f;
+    plan->wide = wl_hi > 16;
+    plan->tscale_d = ldexp(1.0, flmax + 16);
+    plan->tmin_d = -ldexp(1.0, wl_hi - 1 + 16);
+    plan->tmax_d = (ldexp(1.0, wl_hi - 1) - 1.0) * 65536.0;
     plan->degenerate = 0;
 }
 
@@ -100,7 +106,8 @@ __device__ void make_candidate(KldPlan *plan, int c, int wl_lo, int wl_hi, int i
     long long braw;
     if (sh >= 0) {
         k.kind = 0;
-        k.s = 16 + sh > 31 ? 31 : 16 + sh;
+        const int cap = plan->wide ? 63 : 31;               // beyond the width of the scaled value only its sign is left
+        k.s = 16 + sh > cap ? cap : 16 + sh;
         braw = (qmax >> (sh > 62 ? 62 : sh)) - base;
     } else {
         const int L = -sh;
@@ -205,13 +212,22 @@ __device__ __forceinline__ int clamp_i32(int x, int lo, int hi)
 // `park` is a lane-private LDS word that takes the (zero) additions of the elements that are counted elsewhere: zeros
 // and non-finite elements.  An atomic addition of 0 still takes its turn at the counter's address, and the zeros of
 // a pruned tensor would queue up there.
-__device__ __forceinline__ void count_candidate_by_code(const KldCand &k, uint32_t *priv, uint32_t *park, int lane, const int (&T)[8],
+// TT: int for candidates up to 16 bits, long long above (the scaled value has up to 48 bits)
+template <typename TT>
+__device__ __forceinline__ int clamp_tt(TT x, int lo, int hi)
+{
+    if (sizeof(TT) == 4) return clamp_i32((int)x, lo, hi);
+    return (int)(x < (TT)lo ? (TT)lo : x > (TT)hi ? (TT)hi : x);
+}
+
+template <typename TT>
+__device__ __forceinline__ void count_candidate_by_code(const KldCand &k, uint32_t *priv, uint32_t *park, int lane, const TT (&T)[8],
                                                         const int (&r)[8], const uint32_t (&inc)[8])
 {
     const int sub = lane & ((1 << k.rsh) - 1);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const int q = clamp_i32(((T[j] >> k.d) + r[j]) >> 16, k.qmin, k.qmax);
+        const int q = clamp_tt<TT>(((T[j] >> k.d) + (TT)r[j]) >> 16, k.qmin, k.qmax);
         atomicAdd(inc[j] ? &priv[((q - k.qmin) << k.rsh) + sub] : park, inc[j]);
     }
 }
@@ -224,21 +240,22 @@ __device__ __forceinline__ void count_one(uint32_t *row, uint32_t *park, int x, 
     else if (inc) atomicAdd(&row[x], inc);
 }
 
-template <bool USE_LDS>
-__device__ __forceinline__ void count_candidate(const KldCand &k, uint32_t *row, uint32_t *park, const int (&T)[8], const int (&r)[8],
+template <bool USE_LDS, typename TT>
+__device__ __forceinline__ void count_candidate(const KldCand &k, uint32_t *row, uint32_t *park, const TT (&T)[8], const int (&r)[8],
                                                 const uint32_t (&inc)[8])
 {
+    typedef typename std::make_unsigned<TT>::type UT;
     if (k.kind == 0) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int x = ((T[j] >> k.d) + r[j]) >> k.s;
-            count_one<USE_LDS>(row, park, clamp_i32(x, k.lo, k.hi), inc[j]);
+            const TT x = ((T[j] >> k.d) + (TT)r[j]) >> k.s;
+            count_one<USE_LDS>(row, park, clamp_tt<TT>(x, k.lo, k.hi), inc[j]);
         }
     } else if (k.kind == 1) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int x = (int)((unsigned)(((T[j] >> k.d) + r[j]) >> 16) << k.s);
-            count_one<USE_LDS>(row, park, clamp_i32(x, k.lo, k.hi), inc[j]);
+            const TT x = (TT)((UT)(((T[j] >> k.d) + (TT)r[j]) >> 16) << k.s);
+            count_one<USE_LDS>(row, park, clamp_tt<TT>(x, k.lo, k.hi), inc[j]);
         }
     } else {
 #pragma unroll
@@ -260,7 +277,7 @@ __global__ void zero_words_kernel(uint32_t *p, size_t n)
 // slabs[block][row][bins] with plain stores: device-wide atomics on shared counters are far
 // slower than that on this GPU.  USE_LDS = false (bins too large for LDS) counts with atomics
 // straight into the block's slab, which the host has cleared.
-template <bool USE_LDS>
+template <bool USE_LDS, bool WIDE = false>
 __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial,
                                               int range_blocks, int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out,
                                               uint32_t *tickets, uint32_t *slabs, int total_rows, int rows_per_group, int mode,
@@ -353,7 +370,8 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
     auto count_groups = [&](auto gtag, const float (&v)[decltype(gtag)::value][8], const int (&r)[decltype(gtag)::value][8],
                             const int (&cnt)[decltype(gtag)::value]) {
         constexpr int G = decltype(gtag)::value;
-        int T[G][8];
+        typedef typename std::conditional<WIDE, long long, int>::type TT;
+        TT T[G][8];
         uint32_t inc[G][8];
 #pragma unroll
         for (int u = 0; u < G; ++u)
@@ -363,7 +381,8 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
                 const bool fin = j < cnt[u] && fabsf(v[u][j]) < INFINITY;
                 nzero += (fin && zero) ? 1u : 0u;
                 inc[u][j] = (fin && !zero) ? 1u : 0u;
-                T[u][j] = (int)floorf(fminf(fmaxf(v[u][j] * tscale, tmin), tmax));      // NaN -> tmin
+                if (WIDE) T[u][j] = (TT)floor(fmin(fmax((double)v[u][j] * plan.tscale_d, plan.tmin_d), plan.tmax_d));
+                else T[u][j] = (TT)(int)floorf(fminf(fmaxf(v[u][j] * tscale, tmin), tmax));      // NaN -> tmin
                 // (the clamp only acts when a caller-supplied range does not bound the tensor)
             }
         if (do_ref) {
@@ -389,10 +408,10 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
             const int poff = __builtin_amdgcn_readfirstlane(priv_off[c]), roff = __builtin_amdgcn_readfirstlane(row_off[c]);
             if (USE_LDS && poff >= 0) {
 #pragma unroll
-                for (int u = 0; u < G; ++u) count_candidate_by_code(k, lds + poff, park, threadIdx.x & (kWave - 1), T[u], r[u], inc[u]);
+                for (int u = 0; u < G; ++u) count_candidate_by_code<TT>(k, lds + poff, park, threadIdx.x & (kWave - 1), T[u], r[u], inc[u]);
             } else {
 #pragma unroll
-                for (int u = 0; u < G; ++u) count_candidate<USE_LDS>(k, hist + roff, park, T[u], r[u], inc[u]);
+                for (int u = 0; u < G; ++u) count_candidate<USE_LDS, TT>(k, hist + roff, park, T[u], r[u], inc[u]);
             }
         }
     };
@@ -503,13 +522,13 @@ __device__ __forceinline__ void kld_hist_body(const float *__restrict__ w, uint6
     }
 }
 
-template <bool USE_LDS>
+template <bool USE_LDS, bool WIDE = false>
 __global__ void __launch_bounds__(kHistMaxThreads)
 kld_hist_kernel(const float *__restrict__ w, uint64_t n, const float *__restrict__ range_partial, int range_blocks,
                 int wl_lo, int wl_hi, int il, int bins, KldPlan *plan_out, uint32_t *tickets, uint32_t *slabs, int total_rows,
                 int rows_per_group, int mode, uint64_t seed, uint64_t stream)
 {
-    kld_hist_body<USE_LDS>(w, n, range_partial, range_blocks, wl_lo, wl_hi, il, bins, plan_out, tickets, slabs, total_rows,
+    kld_hist_body<USE_LDS, WIDE>(w, n, range_partial, range_blocks, wl_lo, wl_hi, il, bins, plan_out, tickets, slabs, total_rows,
                            rows_per_group, mode, seed, stream, BlockGeo{blockIdx.x, blockIdx.y, gridDim.x, gridDim.y});
 }
 
@@ -703,12 +722,13 @@ kld_range_batched_kernel(const KldBatch b)
     kld_range_body(it.w, it.n, reinterpret_cast<float *>(b.ws + it.off_range), BlockGeo{l, 0, (unsigned)it.range_blocks, 1});
 }
 
+template <bool WIDE>
 __global__ void __launch_bounds__(kHistMaxThreads)
 kld_hist_batched_kernel(const KldBatch b)
 {
     ADAPT_KLD_FIND(first_hist);
     const int rows = b.wl_hi - b.wl_lo + 2;
-    kld_hist_body<true>(it.w, it.n, it.range ? it.range : reinterpret_cast<const float *>(b.ws + it.off_range),
+    kld_hist_body<true, WIDE>(it.w, it.n, it.range ? it.range : reinterpret_cast<const float *>(b.ws + it.off_range),
                         it.range ? 1 : it.range_blocks, b.wl_lo, b.wl_hi,
                         it.il, it.bins, reinterpret_cast<KldPlan *>(b.ws + it.off_plan),
                         reinterpret_cast<uint32_t *>(b.ws + it.off_klpart), reinterpret_cast<uint32_t *>(b.ws + it.off_slabs), rows,
@@ -779,15 +799,24 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
         const int groups = (rows + rows_per_group - 1) / rows_per_group;
         // one set of LDS histograms per block: per-wavefront replicas were measured no faster
         const size_t lds = (size_t)rows_per_group * per_row + 16;
-        hipLaunchKernelGGL(kld_hist_kernel<true>, dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, range_src,
-                           range_count, wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows_per_group, mode, seed,
-                           stream);
+        if (wl_hi > 16)
+            hipLaunchKernelGGL((kld_hist_kernel<true, true>), dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, range_src,
+                               range_count, wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows_per_group,
+                               mode, seed, stream);
+        else
+            hipLaunchKernelGGL((kld_hist_kernel<true, false>), dim3(hist_grid, groups), dim3(threads), lds, ctx->stream, w, n, range_src,
+                               range_count, wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows_per_group,
+                               mode, seed, stream);
     } else {
         const size_t zw = (size_t)hist_grid * hist_words;
         hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)std::min<size_t>((zw + 255) / 256, (size_t)ctx->num_cu * 8)),
                            dim3(256), 0, ctx->stream, slabs, zw);
-        hipLaunchKernelGGL(kld_hist_kernel<false>, dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, range_src, range_count,
-                           wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows, mode, seed, stream);
+        if (wl_hi > 16)
+            hipLaunchKernelGGL((kld_hist_kernel<false, true>), dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, range_src, range_count,
+                               wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows, mode, seed, stream);
+        else
+            hipLaunchKernelGGL((kld_hist_kernel<false, false>), dim3(hist_grid, 1), dim3(threads), 0, ctx->stream, w, n, range_src, range_count,
+                               wl_lo, wl_hi, il, bins, plan, reinterpret_cast<uint32_t *>(klpart), slabs, rows, rows, mode, seed, stream);
     }
     hipLaunchKernelGGL(kld_sum_kernel, dim3(nchunks, rows), dim3(kChunk), 0, ctx->stream, plan, slabs, hist_grid, rows, bins, klpart,
                        hist);
@@ -798,7 +827,7 @@ static int search_one(adapt_ctx *ctx, const float *w, uint64_t n, int wl_lo, int
 
 static int check_search_args(int wl_lo, int wl_hi, int il, int bins, double eps, double alpha, int mode)
 {
-    if (wl_lo < 2 || wl_hi > 16 || wl_lo > wl_hi) return ADAPT_EINVAL;
+    if (wl_lo < 2 || wl_hi > 32 || wl_lo > wl_hi) return ADAPT_EINVAL;
     if (il < 1 || wl_lo - il < 0 || wl_hi - il > 31) return ADAPT_EINVAL;
     if (bins < 2 || bins > 65536) return ADAPT_EINVAL;
     if (mode != ADAPT_SR && mode != ADAPT_RN_HALF_UP) return ADAPT_EINVAL;
@@ -808,8 +837,10 @@ static int check_search_args(int wl_lo, int wl_hi, int il, int bins, double eps,
 
 static hipError_t allow_hist_lds(adapt_ctx *ctx)
 {
-    hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_kernel<true>), kLdsBudget);
-    if (e == hipSuccess) e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_batched_kernel), kLdsBudget);
+    hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_kernel<true, false>), kLdsBudget);
+    if (e == hipSuccess) e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_kernel<true, true>), kLdsBudget);
+    if (e == hipSuccess) e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_batched_kernel<false>), kLdsBudget);
+    if (e == hipSuccess) e = allow_big_lds(ctx, reinterpret_cast<const void *>(&kld_hist_batched_kernel<true>), kLdsBudget);
     return e;
 }
 
@@ -901,7 +932,8 @@ static int search_batch(adapt_ctx *ctx, const adapt_kld_item *items, const float
         }
         for (int i = b.count; i < kKldBatchMax; ++i) { b.first_range[i] = b.first_hist[i] = b.first_sum[i] = b.first_final[i] = 0xffffffffu; }
         if (nr) hipLaunchKernelGGL(kld_range_batched_kernel, dim3(nr), dim3(kRangeThreads), 0, ctx->stream, b);
-        hipLaunchKernelGGL(kld_hist_batched_kernel, dim3(nh), dim3(threads), lds_max, ctx->stream, b);
+        if (wl_hi > 16) hipLaunchKernelGGL(kld_hist_batched_kernel<true>, dim3(nh), dim3(threads), lds_max, ctx->stream, b);
+        else hipLaunchKernelGGL(kld_hist_batched_kernel<false>, dim3(nh), dim3(threads), lds_max, ctx->stream, b);
         hipLaunchKernelGGL(kld_sum_batched_kernel, dim3(nsum), dim3(kChunk), 0, ctx->stream, b);
         hipLaunchKernelGGL(kld_final_batched_kernel, dim3(nf), dim3(kChunk), 0, ctx->stream, b);
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return hip_status(ctx, e);

@@ -126,10 +126,10 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
             return need + slack;
         }
         case ADAPT_CALL_KLD_SEARCH:
-            if (q->wl_lo < 2 || q->wl_hi > 16 || q->wl_lo > q->wl_hi || q->bins < 2 || q->bins > 65536) return kInvalid;
+            if (q->wl_lo < 2 || q->wl_hi > 32 || q->wl_lo > q->wl_hi || q->bins < 2 || q->bins > 65536) return kInvalid;
             return ws_need_kld_search(num_cu, q->n, q->wl_lo, q->wl_hi, q->bins) + slack;
         case ADAPT_CALL_KLD_SEARCH_BATCHED:
-            if (q->wl_lo < 2 || q->wl_hi > 16 || q->wl_lo > q->wl_hi || q->count < 0 || (q->count > 0 && !q->kld_items)) return kInvalid;
+            if (q->wl_lo < 2 || q->wl_hi > 32 || q->wl_lo > q->wl_hi || q->count < 0 || (q->count > 0 && !q->kld_items)) return kInvalid;
             for (int t = 0; t < q->count; ++t)
                 if (q->kld_items[t].bins < 2 || q->kld_items[t].bins > 65536) return kInvalid;
             return ws_need_kld_search_batched(num_cu, q->kld_items, q->count, q->wl_lo, q->wl_hi) + slack;

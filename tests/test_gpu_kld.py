@@ -116,6 +116,34 @@ def test_batched_with_known_ranges():
     assert np.array_equal(host(kld)[0], host(one["kld"])) and host(sel)[0].tolist() == host(one["sel"]).tolist()
 
 
+@pytest.mark.parametrize("lo,hi,il,bins", [(4, 32, 3, 256), (17, 32, 2, 2048), (2, 24, 2, 150), (20, 20, 4, 64), (8, 32, 1, 50000), (30, 32, 1, 7)])
+def test_candidates_up_to_thirty_two_bits(lo, hi, il, bins):
+    g = np.random.default_rng(lo + hi)
+    if bins >= 50000:
+        ctx().reserve_workspace(256 << 20)                  # rows that do not fit LDS are counted in per-block slabs
+    for n, scale in ((30011, 0.3), (9, 1.0), (200003 if bins < 50000 else 5003, 2.0 ** (il - 3))):      # (slabs of wide rows are large)
+        w = (g.standard_normal(n) * scale).astype(np.float32)
+        w[g.random(n) < 0.2] = 0.0
+        _compare(w, lo, hi, il, bins, 1e-3, seed=hi, stream=n)
+    # a tensor on a 2^-20 grid: everything from its own precision up is lossless
+    codes = np.clip(np.round(g.standard_normal(5000) * 2 ** 17), -(2 ** 20 - 1), 2 ** 20 - 1)
+    w = (codes * 2.0 ** -20).astype(np.float32)
+    ref = _compare(w, max(lo, 4), 32, 3, 256, 1e-300)
+    assert (ref["kld"][-9:] == 0).all()
+
+
+def test_batched_with_candidates_up_to_thirty_two_bits():
+    g = np.random.default_rng(23)
+    ws = [(g.standard_normal(n) * s).astype(np.float32) for n, s in ((5000, 0.05), (300000, 0.1), (64, 1.0))]
+    ils, bins, streams = [2, 3, 2], [100, 2048, 64], [1, 2, 3]
+    kld, sel = ctx().kld_precision_search_batched([dev(w) for w in ws], ils, bins, streams, 6, 32, 1e-3, seed=5)
+    kld, sel = host(kld), host(sel)
+    for t, w in enumerate(ws):
+        ref = orc.kld_precision_search(w, 6, 32, ils[t], bins[t], 1e-3, None, pkg.SR, 5, streams[t])
+        assert (np.abs(kld[t] - ref["kld"]) <= 1e-5 * np.abs(ref["kld"]) + 1e-12).all(), t
+        assert sel[t].tolist() == [ref["wl_sel"], ref["fl_sel"]], t
+
+
 def test_degenerate_inputs():
     _compare(np.full(1000, 0.25, dtype=np.float32), 3, 8, 2, 100, 1e-3)
     _compare(np.array([np.nan, np.inf, -np.inf, np.nan], dtype=np.float32), 3, 8, 2, 100, 1e-3)
@@ -194,7 +222,7 @@ def test_batched_many_tensors_mixed_sizes():
 
 def test_invalid_arguments():
     w = torch.zeros(64, dtype=torch.float32, device="cuda")
-    for args in ((1, 8, 2, 100), (4, 17, 2, 100), (8, 4, 2, 100), (4, 8, 5, 100), (4, 8, 2, 1), (4, 8, 2, 70000),
+    for args in ((1, 8, 2, 100), (4, 33, 2, 100), (8, 4, 2, 100), (4, 8, 5, 100), (4, 8, 2, 1), (4, 8, 2, 70000),
                  (4, 8, 0, 100)):
         with pytest.raises(pkg.AdaptError):
             ctx().kld_precision_search(w, args[0], args[1], args[2], args[3], 1e-3)
