@@ -371,13 +371,32 @@ __global__ void __launch_bounds__(kBnThreads) bn_bwd_kernel(const BnBwdArgs a)
 __global__ void __launch_bounds__(1024)
 bn_update_kernel(float *gamma, float *beta, const double *__restrict__ dgamma, const double *__restrict__ dbeta, int channels, float lr)
 {
+    // the squares are formed by all threads, a chunk at a time; the two sums run in channel order (the order fixes
+    // the rounding) on one lane each
+    constexpr int kChunk = 2048;
+    __shared__ double sq[2][kChunk];
     __shared__ double nrm[2];
-    if (threadIdx.x < 2) {                           // the two sums of squares, each in channel order
-        const double *d = threadIdx.x == 0 ? dgamma : dbeta;
-        double t = 0.0;
-        for (int k = 0; k < channels; ++k) t = t + d[k] * d[k];
-        nrm[threadIdx.x] = sqrt(t);
+    const bool summer = (threadIdx.x & 63) == 0 && threadIdx.x < 128;
+    double t = 0.0;
+    for (int base = 0; base < channels; base += kChunk) {
+        const int len = channels - base < kChunk ? channels - base : kChunk;
+        for (int k = threadIdx.x; k < len; k += blockDim.x) {
+            sq[0][k] = dgamma[base + k] * dgamma[base + k];
+            sq[1][k] = dbeta[base + k] * dbeta[base + k];
+        }
+        __syncthreads();
+        if (summer) {
+            const double *d = sq[threadIdx.x >> 6];
+            int k = 0;
+            for (; k + 8 <= len; k += 8) {
+                const double v0 = d[k], v1 = d[k + 1], v2 = d[k + 2], v3 = d[k + 3], v4 = d[k + 4], v5 = d[k + 5], v6 = d[k + 6], v7 = d[k + 7];
+                t = t + v0; t = t + v1; t = t + v2; t = t + v3; t = t + v4; t = t + v5; t = t + v6; t = t + v7;
+            }
+            for (; k < len; ++k) t = t + d[k];
+        }
+        __syncthreads();
     }
+    if (summer) nrm[threadIdx.x >> 6] = sqrt(t);
     __syncthreads();
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
         if (nrm[0] > 0.0 && nrm[0] < (double)INFINITY) gamma[k] = __builtin_fmaf(-lr, (float)((dgamma[k]) / (nrm[0])), gamma[k]);

@@ -103,6 +103,19 @@ def test_batch_norm_special_channels_and_nearest_rounding():
     assert st["FA"] == 30 and np.array_equal(host(out).astype(np.int64), want)
 
 
+@pytest.mark.parametrize("channels", [1, 8, 520, 2048, 2049, 4096])
+def test_batch_norm_update_alone_many_channels(channels):
+    # sums of squares in channel order across the kernel's staging chunks; magnitudes spread over many binades
+    g = np.random.default_rng(channels)
+    gamma, beta = g.standard_normal(channels).astype(np.float32), g.standard_normal(channels).astype(np.float32)
+    dgam = g.standard_normal(channels) * np.exp2(g.integers(-30, 30, channels))
+    dbet = g.standard_normal(channels) * np.exp2(g.integers(-8, 8, channels))
+    gdev, bdev = dev(gamma.copy()), dev(beta.copy())
+    ctx().bn_update(gdev, bdev, dev(dgam), dev(dbet), 0.125)
+    g2, b2 = go.bn_update(gamma, beta, dgam, dbet, 0.125)
+    assert np.array_equal(host(gdev).view(np.uint32), g2.view(np.uint32)) and np.array_equal(host(bdev).view(np.uint32), b2.view(np.uint32))
+
+
 def test_batch_norm_rejects_what_it_does_not_handle():
     y = torch.zeros((2, 2, 2, 12), dtype=torch.int8, device="cuda")
     p = torch.ones(12, dtype=torch.float32, device="cuda")
