@@ -33,6 +33,11 @@ Random streams: the step is given (seed, stream0); layer l uses stream0 + 8 l + 
 0 = forward output, 1 = data gradient it hands down, 2 = weight gradient, 3 = re-quantized weights,
 4 = network input (l = 0 only), 5 = first quantization of the weights.
 
+Word lengths 17..32 (Sec. 3.3 lets PushUp ask for up to 32 bits): a contraction with an operand above 16 bits, and
+the fitting of its accumulators, run on Python integers (the wide oracle); every rule above is unchanged.  The
+element-wise sum of a window that holds codes above 16 bits is kept in 64-bit integers, and the bound below which
+the oldest entries are left out is 2^48 instead of 2^31.
+
 Also here: the residual addition of two fixed-point tensors (exact sum on the finer grid, then the
 requantize rule).
 """
@@ -45,6 +50,7 @@ import numpy as np
 from . import conv_oracle as co
 from . import fxp_oracle as orc
 from . import sgd_oracle as so
+from . import wide_oracle as wo
 
 SLOT_FWD, SLOT_DA, SLOT_DW, SLOT_UPD, SLOT_IN, SLOT_WQ = 0, 1, 2, 3, 4, 5
 
@@ -115,6 +121,40 @@ def residual_add(a, fl_a: int, b, fl_b: int, wl_o: int, fl_o: int, mode: int = o
     return orc.requantize(s, f - fl_o, wl_o, mode, seed, stream, relu)
 
 
+# ---- contractions and fitting by word length -------------------------------------------------------------
+# force_wide: tests run formats of at most 16 bits through the Python-integer path as well, which pins that path
+# to the int64 one.
+force_wide = False
+
+
+def _wide(*wls) -> bool:
+    return force_wide or any(w > 16 for w in wls)
+
+
+def _conv_fwd(x, wl_x, w, wl_w, stride, pad):
+    return wo.conv_fwd(x, w, stride, pad) if _wide(wl_x, wl_w) else co.conv_fwd(x, w, stride, pad)
+
+
+def _conv_dgrad(dy, wl_dy, w, wl_w, h, wd, stride, pad):
+    return wo.conv_dgrad(dy, w, h, wd, stride, pad) if _wide(wl_dy, wl_w) else co.conv_dgrad(dy, w, h, wd, stride, pad)
+
+
+def _conv_wgrad(dy, wl_dy, x, wl_x, r, s, stride, pad):
+    return wo.conv_wgrad(dy, x, r, s, stride, pad) if _wide(wl_dy, wl_x) else co.conv_wgrad(dy, x, r, s, stride, pad)
+
+
+def _requantize(acc, shift, wl, mode, seed, stream, relu):
+    if np.asarray(acc).dtype == object or wl > 16:
+        return wo.requantize(acc, shift, wl, mode, seed, stream, relu)
+    return orc.requantize(acc, shift, wl, mode, seed, stream, relu)
+
+
+def _requantize_fit(acc, wl, mode, seed, stream):
+    if np.asarray(acc).dtype == object or wl > 16:
+        return wo.requantize_fit(acc, wl, mode, seed, stream)
+    return requantize_fit(acc, wl, mode, seed, stream)
+
+
 # ---- the chained step ------------------------------------------------------------------------------------
 
 @dataclass
@@ -157,16 +197,16 @@ def forward(layers, fmts, wq, x, seed: int, stream0: int):
     wl0, fl0 = fmts[0]
     a_in = orc.quantize(np.asarray(x, np.float32), wl0, fl0, orc.SR, seed, stream_of(stream0, 0, SLOT_IN))[0].reshape(x.shape)
     ys, acts = [], []
-    cur, fl_cur = a_in, fl0
+    cur, fl_cur, wl_cur = a_in, fl0, wl0
     for l, (L, (wl, fl)) in enumerate(zip(layers, fmts)):
         cur = cur.reshape(n, L.h, L.w, L.c)                       # flatten / unflatten between conv and FC
-        z = co.conv_fwd(cur, wq[l], L.stride, L.pad)
+        z = _conv_fwd(cur, wl_cur, wq[l], wl, L.stride, L.pad)
         shift = fl_cur + fl - fl                                   # FL of the activations + FL of the weights - FL of the output
-        y = orc.requantize(z, shift, wl, orc.SR, seed, stream_of(stream0, l, SLOT_FWD), L.relu)
+        y = _requantize(z, shift, wl, orc.SR, seed, stream_of(stream0, l, SLOT_FWD), L.relu)
         ys.append(y)
         cur = maxpool2(y) if L.pool else y
         acts.append(cur)
-        fl_cur = fl
+        fl_cur, wl_cur = fl, wl
     return {"a_in": a_in, "y": ys, "a": acts}
 
 
@@ -185,11 +225,12 @@ def backward(layers, fmts, wq, fwd, dlogits, seed: int, stream0: int):
         wl, _ = fmts[l]
         dy[l] = relu_pool_bwd(da[l], fwd["y"][l], L.relu, L.pool)
         a_prev = (fwd["a"][l - 1] if l > 0 else fwd["a_in"]).reshape(n, L.h, L.w, L.c)
-        acc_w = co.conv_wgrad(dy[l], a_prev, L.r, L.s, L.stride, L.pad)
-        g[l], shift_w[l], sumsq[l] = requantize_fit(acc_w, wl, orc.SR, seed, stream_of(stream0, l, SLOT_DW))
+        wl_prev = fmts[l - 1][0] if l > 0 else fmts[0][0]
+        acc_w = _conv_wgrad(dy[l], wl, a_prev, wl_prev, L.r, L.s, L.stride, L.pad)
+        g[l], shift_w[l], sumsq[l] = _requantize_fit(acc_w, wl, orc.SR, seed, stream_of(stream0, l, SLOT_DW))
         if l > 0:
-            acc_a = co.conv_dgrad(dy[l], wq[l], L.h, L.w, L.stride, L.pad)
-            q, shift_a[l], _ = requantize_fit(acc_a, fmts[l - 1][0], orc.SR, seed, stream_of(stream0, l, SLOT_DA))
+            acc_a = _conv_dgrad(dy[l], wl, wq[l], wl, L.h, L.w, L.stride, L.pad)
+            q, shift_a[l], _ = _requantize_fit(acc_a, fmts[l - 1][0], orc.SR, seed, stream_of(stream0, l, SLOT_DA))
             da[l - 1] = q.reshape(fwd["a"][l - 1].shape)
     return {"g": g, "sumsq": sumsq, "shift_w": shift_w, "da": da, "dy": dy, "shift_a": shift_a}
 
@@ -227,9 +268,9 @@ SLOT_KLD = 6
 
 class SwitchState:
     def __init__(self, nl: int, lb_lwr: int, lb_upr: int, lb_init: int, r_lwr: int, r_upr: int, r_init: int, gamma: float,
-                 eps: float, buff: int, wl_lo: int, wl_hi: int, strategy: int = po.ST_MIN):
+                 eps: float, buff: int, wl_lo: int, wl_hi: int, strategy: int = po.ST_MIN, wl_cap: int = 16):
         self.p = dict(lb_lwr=lb_lwr, lb_upr=lb_upr, r_lwr=r_lwr, r_upr=r_upr, gamma=gamma, eps=eps, buff=buff, wl_lo=wl_lo,
-                      wl_hi=wl_hi)
+                      wl_hi=wl_hi, wl_cap=wl_cap)
         self.lb = [lb_init] * nl
         self.res = [r_init] * nl
         self.windows = [[] for _ in range(nl)]            # entries (codes, wl, exponent)
@@ -267,12 +308,16 @@ def precision_switch(st: SwitchState, fmts, weights, bwd, dlogits_fl: int, loss:
         if len(win) > p["lb_upr"]:
             win.pop(0)
         use = win[-min(len(win), st.lb[l]):]
-        # The element-wise sum of the window, aligned to its finest grid, is held in 32-bit integers: while the bound
-        # sum_k 2^(wl_k - 1 + e_max - e_k) reaches 2^31 the oldest entry is left out (the newest always stays).
-        while len(use) > 1 and sum(2 ** (w - 1 + max(e for _, _, e in use) - e) for _, w, e in use) >= 2 ** 31:
+        # The element-wise sum of the window, aligned to its finest grid, is held in 32-bit integers (64-bit ones if
+        # the window holds codes above 16 bits): while the bound sum_k 2^(wl_k - 1 + e_max - e_k) reaches 2^31 (2^48)
+        # the oldest entry is left out (the newest always stays).
+        wide = any(w > 16 for _, w, _ in use)
+        limit = 2 ** 48 if wide else 2 ** 31
+        while len(use) > 1 and sum(2 ** (w - 1 + max(e for _, _, e in use) - e) for _, w, e in use) >= limit:
             use = use[1:]
         e_min = min(e for _, _, e in use)
-        gd = po.gradient_diversity_np([c for c, _, _ in use], [e - e_min for _, _, e in use])
+        gd_fn = wo.gradient_diversity if wide else po.gradient_diversity_np
+        gd = gd_fn([c for c, _, _ in use], [e - e_min for _, _, e in use])
         ds = gd["ds"]
         st.lb[l] = po.adapt_lookback(st.lb[l], ds, p["lb_lwr"], p["lb_upr"], p["gamma"])
         st.res[l] = po.adapt_resolution(st.res[l], st.lb[l], p["lb_lwr"], p["lb_upr"], p["r_lwr"], p["r_upr"])
@@ -286,7 +331,7 @@ def precision_switch(st: SwitchState, fmts, weights, bwd, dlogits_fl: int, loss:
                                              seed=seed, stream=stream_of(stream0, l, SLOT_KLD))
                 wl_min = min(int(r["wl_sel"]), wl)
             fl_min = wl_min - il
-            nw, nf, _, _, _ = po.pushup_suggest(ds, wl_min, fl_min, st.strategy, p["buff"], 16)
+            nw, nf, _, _, _ = po.pushup_suggest(ds, wl_min, fl_min, st.strategy, p["buff"], p["wl_cap"])
             fmts[l] = (nw, nf)
             win.clear()
             row.update(switched=True, wl_min=wl_min, fl_min=fl_min)

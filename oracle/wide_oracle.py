@@ -5,6 +5,10 @@ TEST INFRASTRUCTURE ONLY.  Slow, plain reference; nothing in the product package
 only tests/, the smoke check and the benchmark's cpu_baseline leg do.  It shares no code with
 the HIP path.
 
+Also here, on the same Python integers: the fitting requantization of exact accumulators of any size
+(the narrow oracle's rule, shift = max(0, bit_length(max |acc|) - (WL-1))) and the gradient-diversity sums
+of windows that hold codes above 16 bits.
+
 Codes of up to 32 bits multiply to 62 bits and a reduction adds more, so the exact sums do not fit
 64 bits: everything here is Python integers (numpy arrays of dtype object), the contractions written
 out from their definitions, and the accumulator -> <WL,FL> rule of the narrow oracle applied to those
@@ -95,3 +99,44 @@ def requantize(acc, shift: int, wl_o: int, mode: int = orc.SR, seed: int = 0, st
     lo, hi = -(1 << (wl_o - 1)), (1 << (wl_o - 1)) - 1
     q = np.array([min(max(max(int(v), 0) if relu else int(v), lo), hi) for v in q], dtype=np.int64)
     return q.reshape(a.shape)
+
+
+def fit_shift(acc, wl: int) -> int:
+    """Smallest right shift after which the largest magnitude of acc has at most wl-1 bits."""
+    flat = _obj(acc).ravel()
+    m = max((abs(int(v)) for v in flat), default=0)
+    return max(0, m.bit_length() - (wl - 1))
+
+
+def requantize_fit(acc, wl: int, mode: int = orc.SR, seed: int = 0, stream: int = 0):
+    """Exact accumulators of any size -> wl-bit codes (wl up to 32) with the fitting shift.
+    Returns (codes int64, shift, sum of squared codes as a Python integer)."""
+    sh = fit_shift(acc, wl)
+    q = requantize(acc, sh, wl, mode, seed, stream, False)
+    return q, sh, sum(int(v) * int(v) for v in q.ravel())
+
+
+def gradient_diversity(codes, fls):
+    """The gradient-diversity quantities of the PushUp oracle (Sec. 3.3 "The PushUp Operation") for windows whose
+    codes or aligned sums exceed 32 bits: the same exact integer sums (numpy arrays of Python integers), the same
+    fp64 norms.  codes: list of integer arrays of one shape, oldest first; fls: their FL."""
+    import math
+    fl_max = max(int(f) for f in fls)
+    total = None
+    sumsq = []
+    for c, f in zip(codes, fls):
+        flat = _obj(np.asarray(c).ravel())
+        sumsq.append(int((flat * flat).sum()) if flat.size else 0)
+        scaled = flat * (1 << (fl_max - int(f)))
+        total = scaled if total is None else total + scaled
+    sumsq_sum = int((total * total).sum()) if total.size else 0
+    num = 0.0
+    for q, f in zip(sumsq, fls):
+        num += math.sqrt(q) * 2.0 ** (-int(f))
+    den = math.sqrt(sumsq_sum) * 2.0 ** (-fl_max)
+    if den > 0.0:
+        ds = num / den
+    else:
+        ds = math.inf if num > 0.0 else math.nan
+    log_ds = math.log(ds) if (0.0 < ds < math.inf) else 1.0
+    return {"sumsq": sumsq, "fl_max": fl_max, "sumsq_sum": sumsq_sum, "num": num, "den": den, "ds": ds, "log_ds": log_ds}
