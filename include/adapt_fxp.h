@@ -311,10 +311,12 @@ int adapt_kld_precision_search_batched_ranged(adapt_ctx *ctx, const adapt_kld_it
  *                                      multiply-adds in exactly this order)
  *   q  = quantize(w', fq) as adapt_quantize does, with `rng`
  *   w         device fp32[n], updated in place
- *   g         device codes of the gradient, int8_t[n] (fg.wl <= 8) or int16_t[n]
- *   g_sumsq   device uint64_t or NULL: sum of the squared codes of g (adapt_gradient_diversity
- *             writes it as sums[k])
- *   q         device int8_t[n] (fq.wl <= 8) or int16_t[n]
+ *   g         device codes of the gradient, int8_t[n] (fg.wl <= 8), int16_t[n] (<= 16) or int32_t[n]
+ *             (<= 32; converted to fp32 with round-to-nearest-even)
+ *   g_sumsq   device or NULL: sum of the squared codes of g (adapt_gradient_diversity writes it as
+ *             sums[k], adapt_requantize_fit as sumsq): one uint64_t for fg.wl <= 16, uint64_t[2] (low
+ *             word first) for fg.wl > 16, whose nearest double enters the quotient
+ *   q         device int8_t[n] (fq.wl <= 8), int16_t[n] (<= 16) or int32_t[n] (<= 32)
  *   counters  device uint64_t[2] or NULL: non-zero codes, saturated elements
  *   range     device float[2] or NULL: min and max of the finite w' (+inf, -inf if there is none)
  * Pointers 16-byte aligned; n <= 2^40. */
@@ -377,7 +379,8 @@ int adapt_resolution_next(int r, int lb, int lb_lwr, int lb_upr, int r_lwr, int 
 
 /* 2x2 max-pooling, stride 2, of codes: a[n,i,j,c] = max of y[n,2i..2i+1,2j..2j+1,c] (the code order
  * is the value order).  y: device codes of an n x h x w x c tensor stored as format f (only the
- * storage width of f matters), h and w even; a: device, n x h/2 x w/2 x c, same storage. */
+ * storage width of f matters: int8_t, int16_t, or int32_t for 17 <= f.wl <= 32), h and w even; a:
+ * device, n x h/2 x w/2 x c, same storage. */
 int adapt_maxpool2_fwd(adapt_ctx *ctx, const void *y, adapt_fmt f, int n, int h, int w, int c, void *a);
 
 /* Gradient with respect to a contraction's output from the gradient with respect to the layer's
@@ -386,7 +389,7 @@ int adapt_maxpool2_fwd(adapt_ctx *ctx, const void *y, adapt_fmt f, int n, int h,
  *              in the order (0,0),(0,1),(1,0),(1,1); the other three positions get 0
  *   pool == 0: da is n x h x w x c and dy = da
  *   relu != 0: additionally dy = 0 where y <= 0 (the stored output decides the mask)
- * da, y and dy share the storage width of f.  dy must not overlap da or y. */
+ * da, y and dy share the storage width of f (f.wl up to 32).  dy must not overlap da or y. */
 int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y, adapt_fmt f, int n, int h,
                         int w, int c, int relu, int pool, void *dy);
 
@@ -396,10 +399,14 @@ int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y, adapt_fmt
  * power-of-two factor:
  *   shift = max(0, bit_length(max_i |acc[i]|) - (wl - 1))
  *   q[i]  = the contraction epilogue's rule with this shift (SR on the dropped bits, saturation)
- *   acc       device int32_t[n] (acc_bits = 32) or int64_t[n] (acc_bits = 64)
- *   q         device int8_t[n] (wl <= 8) or int16_t[n]
+ *   acc       device int32_t[n] (acc_bits = 32), int64_t[n] (acc_bits = 64) or 128-bit integers as
+ *             pairs of int64_t, low word first (acc_bits = 128: the exact output of a contraction
+ *             with an operand above 16 bits)
+ *   q         device int8_t[n] (wl <= 8), int16_t[n] (wl <= 16) or int32_t[n] (wl <= 32)
  *   shift     device int32_t or NULL
- *   sumsq     device uint64_t or NULL: sum of q[i]^2 (what adapt_sgd_update_quantize takes)
+ *   sumsq     device or NULL: sum of q[i]^2 (what adapt_sgd_update_quantize takes): one uint64_t for
+ *             wl <= 16; for wl > 16 the sum may pass 64 bits and is written as uint64_t[2], low word
+ *             first
  * Two passes over acc.  n <= 2^40; n = 0 writes shift = 0, sumsq = 0. */
 int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl,
                          adapt_rng rng, void *q, int32_t *shift, uint64_t *sumsq);

@@ -585,15 +585,18 @@ class Context:
                                              _ptr(out)), "adapt_relu_pool_bwd")
         return out
 
-    def requantize_fit(self, acc, wl, mode=SR, seed=0, stream=0, out=None, want_sumsq=True):
-        """acc: int32 / int64 exact accumulators.  Returns (codes, shift int32[1], sumsq int64[1] or None)."""
+    def requantize_fit(self, acc, wl, mode=SR, seed=0, stream=0, out=None, want_sumsq=True, acc_bits=None):
+        """acc: int32 / int64 exact accumulators, or 128-bit ones as int64[..., 2] (low word first) with acc_bits=128.
+        Returns (codes, shift int32[1], sumsq or None); sumsq is int64[1], or for wl > 16 the 128-bit sum as int64[2]."""
         torch = self._torch
+        bits = acc_bits if acc_bits is not None else (32 if acc.dtype == torch.int32 else 64)
+        shape = acc.shape[:-1] if bits == 128 else acc.shape
+        count = acc.numel() // 2 if bits == 128 else acc.numel()
         if out is None:
-            out = torch.empty(acc.shape, dtype=self.storage_dtype(wl), device=acc.device)
+            out = torch.empty(shape, dtype=self.storage_dtype(wl), device=acc.device)
         shift = torch.empty(1, dtype=torch.int32, device=acc.device)
-        sumsq = torch.empty(1, dtype=torch.int64, device=acc.device) if want_sumsq else None
-        bits = 32 if acc.dtype == torch.int32 else 64
-        _check(self._lib.adapt_requantize_fit(self._h, _ptr(acc), bits, acc.numel(), wl, Rng(mode, seed, stream), _ptr(out),
+        sumsq = torch.empty(2 if wl > 16 else 1, dtype=torch.int64, device=acc.device) if want_sumsq else None
+        _check(self._lib.adapt_requantize_fit(self._h, _ptr(acc), bits, count, wl, Rng(mode, seed, stream), _ptr(out),
                                               _ptr(shift), _ptr(sumsq)), "adapt_requantize_fit")
         return out, shift, sumsq
 

@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libadapt_fxp.so")
 SOURCES = ["api.hip", "quantize.hip", "kld.hip", "contract_gemm.hip", "contract_fwd.hip",
            "contract_dgrad.hip", "contract_wgrad.hip", "pushup.hip", "sgd.hip",
            "contract_backward.hip", "contract_pair_d64x64.hip", "contract_pair_d128x64.hip", "contract_pair_d64x128.hip",
-           "contract_pair_d128x128.hip", "perf_model.hip", "net.hip", "workspace.hip", "bn.hip", "wide.hip"]
+           "contract_pair_d128x128.hip", "perf_model.hip", "net.hip", "workspace.hip", "bn.hip", "wide.hip", "wide_ops.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-fno-gpu-flush-denormals-to-zero", "-Wall", "-Wno-unused-function",

@@ -132,6 +132,13 @@ __device__ __forceinline__ void load_codes8<int16_t>(const int16_t *g, uint64_t 
     for (int j = 0; j < 8; ++j) c[j] = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
 }
 
+template <>
+__device__ __forceinline__ void load_codes8<int32_t>(const int32_t *g, uint64_t grp, int (&c)[8])
+{
+    const int4 a = reinterpret_cast<const int4 *>(g)[2 * grp], b = reinterpret_cast<const int4 *>(g)[2 * grp + 1];
+    c[0] = a.x; c[1] = a.y; c[2] = a.z; c[3] = a.w; c[4] = b.x; c[5] = b.y; c[6] = b.z; c[7] = b.w;
+}
+
 template <typename OutT>
 __device__ __forceinline__ void store_codes8(OutT *q, uint64_t grp, const int (&v)[8]);
 template <>
@@ -151,6 +158,27 @@ __device__ __forceinline__ void store_codes8<int16_t>(int16_t *q, uint64_t grp, 
     o.z = (uint32_t)(v[4] & 0xffff) | ((uint32_t)v[5] << 16);
     o.w = (uint32_t)(v[6] & 0xffff) | ((uint32_t)v[7] << 16);
     reinterpret_cast<uint4 *>(q)[grp] = o;
+}
+
+template <>
+__device__ __forceinline__ void store_codes8<int32_t>(int32_t *q, uint64_t grp, const int (&v)[8])
+{
+    reinterpret_cast<int4 *>(q)[2 * grp] = make_int4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<int4 *>(q)[2 * grp + 1] = make_int4(v[4], v[5], v[6], v[7]);
+}
+
+// Word lengths 17..32 (Sec. 3.3 bounds precision at 32 bits): int32 codes.  The scaled value with its 16 guard bits
+// needs up to 48 bits, so the rule of quantize_one is evaluated in fp64 and 64-bit integers (all steps exact).
+__device__ __forceinline__ int quantize_one_wide(float x, uint32_t r16, int wl, int fl, int &sat)
+{
+    const double y = ldexp((double)x, fl);
+    const double qmin = -ldexp(1.0, wl - 1), qmax = ldexp(1.0, wl - 1) - 1.0;
+    sat = (y < qmin) | (y > qmax);                         // false for NaN
+    const double yc = fmin(fmax(y, qmin), qmax);
+    const long long t = (long long)floor(yc * 65536.0);
+    long long q = (t + (long long)r16) >> 16;
+    q = q > (long long)qmax ? (long long)qmax : q;
+    return (x != x) ? 0 : (int)q;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -41,6 +41,10 @@ typedef std::function<int(const void *, adapt_fmt, const void *, adapt_fmt, void
 int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems_a, const void *b, adapt_fmt fb, uint64_t elems_b,
                      uint64_t outputs, int64_t k_total, void *out, adapt_epilogue ep, const SubContraction &sub);
 size_t ws_need_wide(uint64_t elems_a, bool wide_a, uint64_t elems_b, bool wide_b, uint64_t outputs, bool raw);
+// The fitting requantization with 128-bit accumulators or an output above 16 bits (wide_ops.hip); arguments as in
+// adapt_requantize_fit, plus the exponent bookkeeping of the chained step (*e_out = (e_in ? *e_in : 0) + e_add - shift).
+int requantize_fit_wide(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q, int32_t *shift,
+                        uint64_t *sumsq, const long long *e_in, long long e_add, long long *e_out);
 
 inline char *scratch(adapt_ctx *c) { return c->ws + kCtlBytes; }
 inline size_t scratch_bytes(const adapt_ctx *c) { return c->ws_bytes - kCtlBytes; }
@@ -77,7 +81,7 @@ size_t ws_need_gradient_diversity(uint64_t n, int count);
 size_t ws_need_requantize_fit(int num_cu, uint64_t n);
 
 inline bool fmt_ok(adapt_fmt f) { return f.wl >= 2 && f.wl <= 16 && f.fl >= 0 && f.fl <= 31; }
-inline int storage_bytes(adapt_fmt f) { return f.wl <= 8 ? 1 : 2; }
+inline int storage_bytes(adapt_fmt f) { return f.wl <= 8 ? 1 : f.wl <= 16 ? 2 : 4; }      // int8, int16 or int32 codes
 // word lengths 17..32 (int32 codes): only the entry points that say so take them
 // true when a contraction with these formats takes the composed path for word lengths above 16
 inline bool wants_wide(adapt_fmt fa, adapt_fmt fb, const adapt_epilogue &ep) { return fa.wl > 16 || fb.wl > 16 || (!ep.raw && ep.fmt.wl > 16); }

@@ -6,6 +6,22 @@
 
 namespace adapt {
 
+struct FitArgs {
+    const void *acc;
+    void *q;
+    const uint64_t *part;
+    int nparts;
+    uint64_t n;
+    int wl, mode;
+    uint64_t seed, stream;
+    int32_t *shift_out;
+    unsigned long long *sumsq;
+    // exponent of the codes: *e_out = (e_in ? *e_in : 0) + e_add - shift (device memory; e_out may be null)
+    const long long *e_in;
+    long long e_add;
+    long long *e_out;
+};
+
 __device__ __forceinline__ uint64_t magnitude(long long v) { return v < 0 ? 0ull - (uint64_t)v : (uint64_t)v; }
 
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)

@@ -158,22 +158,6 @@ absmax_kernel(const AccT *__restrict__ acc, const uint64_t n, uint64_t *__restri
     }
 }
 
-struct FitArgs {
-    const void *acc;
-    void *q;
-    const uint64_t *part;
-    int nparts;
-    uint64_t n;
-    int wl, mode;
-    uint64_t seed, stream;
-    int32_t *shift_out;
-    unsigned long long *sumsq;
-    // exponent of the codes: *e_out = (e_in ? *e_in : 0) + e_add - shift (device memory; e_out may be null)
-    const long long *e_in;
-    long long e_add;
-    long long *e_out;
-};
-
 // codes = requantize(acc, shift) with shift = max(0, bit_length(max |acc|) - (wl-1)); every block
 // derives the shift from the partial maxima itself
 template <typename AccT, typename OutT>
@@ -323,7 +307,7 @@ using namespace adapt;
 
 extern "C" int adapt_maxpool2_fwd(adapt_ctx *ctx, const void *y, adapt_fmt f, int n, int h, int w, int c, void *a)
 {
-    if (!ctx || !fmt_ok(f)) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(f)) return ADAPT_EINVAL;
     const int es = storage_bytes(f);
     PoolGeo g;
     int vec;
@@ -331,7 +315,9 @@ extern "C" int adapt_maxpool2_fwd(adapt_ctx *ctx, const void *y, adapt_fmt f, in
     if (g.items == 0) return ADAPT_OK;
     if (!y || !a || !aligned16(y) || !aligned16(a)) return ADAPT_EINVAL;
     const dim3 grid(ew_grid(ctx, g.items)), block(kEwThreads);
-    if (es == 1 && vec == 16) hipLaunchKernelGGL((maxpool2_kernel<int8_t, 16>), grid, block, 0, ctx->stream, (const int8_t *)y, (int8_t *)a, g);
+    if (es == 4 && vec == 4) hipLaunchKernelGGL((maxpool2_kernel<int32_t, 4>), grid, block, 0, ctx->stream, (const int32_t *)y, (int32_t *)a, g);
+    else if (es == 4) hipLaunchKernelGGL((maxpool2_kernel<int32_t, 1>), grid, block, 0, ctx->stream, (const int32_t *)y, (int32_t *)a, g);
+    else if (es == 1 && vec == 16) hipLaunchKernelGGL((maxpool2_kernel<int8_t, 16>), grid, block, 0, ctx->stream, (const int8_t *)y, (int8_t *)a, g);
     else if (es == 1) hipLaunchKernelGGL((maxpool2_kernel<int8_t, 1>), grid, block, 0, ctx->stream, (const int8_t *)y, (int8_t *)a, g);
     else if (vec == 8) hipLaunchKernelGGL((maxpool2_kernel<int16_t, 8>), grid, block, 0, ctx->stream, (const int16_t *)y, (int16_t *)a, g);
     else hipLaunchKernelGGL((maxpool2_kernel<int16_t, 1>), grid, block, 0, ctx->stream, (const int16_t *)y, (int16_t *)a, g);
@@ -341,7 +327,7 @@ extern "C" int adapt_maxpool2_fwd(adapt_ctx *ctx, const void *y, adapt_fmt f, in
 extern "C" int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y, adapt_fmt f, int n, int h, int w, int c,
                                    int relu, int pool, void *dy)
 {
-    if (!ctx || !fmt_ok(f)) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(f)) return ADAPT_EINVAL;
     const int es = storage_bytes(f);
     PoolGeo g;
     int vec;
@@ -351,12 +337,16 @@ extern "C" int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y
     const dim3 grid(ew_grid(ctx, g.items)), block(kEwThreads);
 #define ADAPT_BWD(T, V, P) hipLaunchKernelGGL((relu_pool_bwd_kernel<T, V, P>), grid, block, 0, ctx->stream, (const T *)da, (const T *)y, (T *)dy, g, relu)
     if (pool) {
-        if (es == 1 && vec == 16) ADAPT_BWD(int8_t, 16, true);
+        if (es == 4 && vec == 4) ADAPT_BWD(int32_t, 4, true);
+        else if (es == 4) ADAPT_BWD(int32_t, 1, true);
+        else if (es == 1 && vec == 16) ADAPT_BWD(int8_t, 16, true);
         else if (es == 1) ADAPT_BWD(int8_t, 1, true);
         else if (vec == 8) ADAPT_BWD(int16_t, 8, true);
         else ADAPT_BWD(int16_t, 1, true);
     } else {
-        if (es == 1 && vec == 16) ADAPT_BWD(int8_t, 16, false);
+        if (es == 4 && vec == 4) ADAPT_BWD(int32_t, 4, false);
+        else if (es == 4) ADAPT_BWD(int32_t, 1, false);
+        else if (es == 1 && vec == 16) ADAPT_BWD(int8_t, 16, false);
         else if (es == 1) ADAPT_BWD(int8_t, 1, false);
         else if (vec == 8) ADAPT_BWD(int16_t, 8, false);
         else ADAPT_BWD(int16_t, 1, false);
@@ -368,6 +358,8 @@ extern "C" int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y
 static int requantize_fit_exp(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q, int32_t *shift,
                               uint64_t *sumsq, const long long *e_in, long long e_add, long long *e_out)
 {
+    if (ctx && (acc_bits == 128 || (wl > 16 && wl <= 32)))
+        return requantize_fit_wide(ctx, acc, acc_bits, n, wl, rng, q, shift, sumsq, e_in, e_add, e_out);
     if (!ctx || (acc_bits != 32 && acc_bits != 64) || wl < 2 || wl > 16 || !rng_ok(rng)) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if ((shift && ((uintptr_t)shift & 3)) || (sumsq && ((uintptr_t)sumsq & 7))) return ADAPT_EINVAL;

@@ -128,20 +128,6 @@ quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, i
     }
 }
 
-// Word lengths 17..32 (Sec. 3.3 bounds precision at 32 bits): int32 codes.  The scaled value with its 16 guard bits
-// needs up to 48 bits, so the rule of quantize_one is evaluated in fp64 and 64-bit integers (all steps exact).
-__device__ __forceinline__ int quantize_one_wide(float x, uint32_t r16, int wl, int fl, int &sat)
-{
-    const double y = ldexp((double)x, fl);
-    const double qmin = -ldexp(1.0, wl - 1), qmax = ldexp(1.0, wl - 1) - 1.0;
-    sat = (y < qmin) | (y > qmax);                         // false for NaN
-    const double yc = fmin(fmax(y, qmin), qmax);
-    const long long t = (long long)floor(yc * 65536.0);
-    long long q = (t + (long long)r16) >> 16;
-    q = q > (long long)qmax ? (long long)qmax : q;
-    return (x != x) ? 0 : (int)q;
-}
-
 __global__ void __launch_bounds__(kQThreads)
 quantize_wide_kernel(const float *__restrict__ x, int32_t *__restrict__ q, uint64_t n, int wl, int fl, int mode, uint64_t seed,
                      uint64_t stream, uint32_t *partial /* [2][gridDim.x] or null */)

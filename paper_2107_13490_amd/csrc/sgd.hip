@@ -8,8 +8,11 @@
 // quantize it to <WL,FL> with the Sec. 3.2 rule, count non-zero and saturated codes and track the
 // finite range of w' for the next precision search.  10-12 bytes of HBM traffic per element
 // instead of the 18 of separate update, range and quantize passes.
+#include <type_traits>
+
 #include "common.hpp"
 #include "context.hpp"
+#include "wide.hpp"
 
 namespace adapt {
 
@@ -20,7 +23,7 @@ struct SgdArgs {
     float *w;
     const void *g;
     void *q;
-    const uint64_t *g_sumsq;     // device: sum of squared gradient codes, or null (no normalisation)
+    const uint64_t *g_sumsq;     // device: sum of squared gradient codes (two words, low first, for int32 codes), or null
     uint64_t n;
     double lr;
     float l1, l2;
@@ -44,13 +47,14 @@ sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
 {
     float step;
     if (a.g_sumsq != nullptr) {
-        const uint64_t s = *a.g_sumsq;
-        step = s != 0 ? (float)(a.lr / sqrt((double)s)) : 0.0f;
+        // int32 codes: the sum of squares has 128 bits; its nearest double enters the quotient
+        const double s = std::is_same<GT, int32_t>::value ? u128_to_double(a.g_sumsq[0], a.g_sumsq[1]) : (double)a.g_sumsq[0];
+        step = s != 0.0 ? (float)(a.lr / sqrt(s)) : 0.0f;
     } else {
         step = (float)ldexp(a.lr, -a.fl_g);
     }
     const float lr = (float)a.lr;
-    const QuantParams p = make_quant_params(a.wl, a.fl);
+    const QuantParams p = make_quant_params(std::is_same<OutT, int32_t>::value ? 8 : a.wl, a.fl);      // unused for int32 codes
     const GT *g = static_cast<const GT *>(a.g);
     OutT *q = static_cast<OutT *>(a.q);
     float4 *w4 = reinterpret_cast<float4 *>(a.w);
@@ -60,7 +64,8 @@ sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
     auto one = [&](float w, int c, uint32_t r, int &code) {
         const float wn = sgd_one(w, c, step, lr, a.l1, a.l2);
         int s;
-        code = quantize_one(wn, r, p, s);
+        if (std::is_same<OutT, int32_t>::value) code = quantize_one_wide(wn, r, a.wl, a.fl, s);
+        else code = quantize_one(wn, r, p, s);
         nnz += (code != 0);
         nsat += s;
         if (fabsf(wn) < INFINITY) { lo = fminf(lo, wn); hi = fmaxf(hi, wn); }
@@ -172,7 +177,7 @@ extern "C" int adapt_sgd_update_quantize(adapt_ctx *ctx, float *w, size_t n, con
                                          const uint64_t *g_sumsq, adapt_sgd_params opt, adapt_fmt fq, adapt_rng rng,
                                          void *q, uint64_t *counters, float *range)
 {
-    if (!ctx || !fmt_ok(fg) || !fmt_ok(fq) || (rng.mode != ADAPT_SR && rng.mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(fg) || !fmt_ok_wide(fq) || (rng.mode != ADAPT_SR && rng.mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
     if (n > 0 && (!w || !g || !q || !aligned16(w) || !aligned16(g) || !aligned16(q))) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if ((counters && ((uintptr_t)counters & 7)) || (g_sumsq && ((uintptr_t)g_sumsq & 7)) || (range && ((uintptr_t)range & 3)))
@@ -189,11 +194,19 @@ extern "C" int adapt_sgd_update_quantize(adapt_ctx *ctx, float *w, size_t n, con
     SgdArgs a;
     a.w = w; a.g = g; a.q = q; a.g_sumsq = g_sumsq; a.n = n; a.lr = opt.lr; a.l1 = (float)opt.l1; a.l2 = (float)opt.l2;
     a.fl_g = fg.fl; a.wl = fq.wl; a.fl = fq.fl; a.mode = rng.mode; a.seed = rng.seed; a.stream = rng.stream;
-    const bool g8 = fg.wl <= 8, q8 = fq.wl <= 8;
-    if (g8 && q8) hipLaunchKernelGGL((sgd_update_quantize_kernel<int8_t, int8_t>), dim3(grid), dim3(kSgdThreads), 0, ctx->stream, a, counts, rpart);
-    else if (g8) hipLaunchKernelGGL((sgd_update_quantize_kernel<int8_t, int16_t>), dim3(grid), dim3(kSgdThreads), 0, ctx->stream, a, counts, rpart);
-    else if (q8) hipLaunchKernelGGL((sgd_update_quantize_kernel<int16_t, int8_t>), dim3(grid), dim3(kSgdThreads), 0, ctx->stream, a, counts, rpart);
-    else hipLaunchKernelGGL((sgd_update_quantize_kernel<int16_t, int16_t>), dim3(grid), dim3(kSgdThreads), 0, ctx->stream, a, counts, rpart);
+#define ADAPT_SGD(G, Q) hipLaunchKernelGGL((sgd_update_quantize_kernel<G, Q>), dim3(grid), dim3(kSgdThreads), 0, ctx->stream, a, counts, rpart)
+    switch (storage_bytes(fg) * 8 + storage_bytes(fq)) {
+    case 1 * 8 + 1: ADAPT_SGD(int8_t, int8_t); break;
+    case 1 * 8 + 2: ADAPT_SGD(int8_t, int16_t); break;
+    case 1 * 8 + 4: ADAPT_SGD(int8_t, int32_t); break;
+    case 2 * 8 + 1: ADAPT_SGD(int16_t, int8_t); break;
+    case 2 * 8 + 2: ADAPT_SGD(int16_t, int16_t); break;
+    case 2 * 8 + 4: ADAPT_SGD(int16_t, int32_t); break;
+    case 4 * 8 + 1: ADAPT_SGD(int32_t, int8_t); break;
+    case 4 * 8 + 2: ADAPT_SGD(int32_t, int16_t); break;
+    default: ADAPT_SGD(int32_t, int32_t); break;
+    }
+#undef ADAPT_SGD
     if (counters || range)
         hipLaunchKernelGGL(sgd_final_kernel, dim3(1), dim3(kSgdFinalThreads), 0, ctx->stream, counts, rpart, grid, counters, range);
     return hip_status(ctx, hipGetLastError());

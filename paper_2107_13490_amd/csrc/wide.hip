@@ -16,13 +16,13 @@
 
 #include "common.hpp"
 #include "context.hpp"
+#include "wide.hpp"
 
 namespace adapt {
 
 constexpr int kWideThreads = 256;
 constexpr int kPartBits = 11;
 
-typedef __int128 i128;
 
 __global__ void __launch_bounds__(kWideThreads)
 split3_kernel(const int32_t *__restrict__ a, int16_t *__restrict__ p0, int16_t *__restrict__ p1, int16_t *__restrict__ p2, uint64_t n)
@@ -41,28 +41,9 @@ __global__ void __launch_bounds__(kWideThreads)
 acc128_kernel(const CT *__restrict__ c, int sh, i128 *__restrict__ acc, uint64_t n, int first)
 {
     for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWideThreads) {
-        const i128 v = (i128)((unsigned __int128)(i128)c[i] << sh);
+        const i128 v = (i128)((u128)(i128)c[i] << sh);
         acc[i] = first ? v : acc[i] + v;
     }
-}
-
-// the contraction epilogue's rule on a 128-bit accumulator, output of up to 32 bits
-__device__ __forceinline__ int requantize_wide_one(i128 acc, int shift, int wl, int relu, uint32_t r16)
-{
-    i128 q;
-    if (shift <= 0) {
-        const i128 lim = (i128)1 << 33;                      // beyond any 32-bit range: saturates below
-        const i128 c = acc > lim ? lim : acc < -lim ? -lim : acc;
-        const int l = -shift > 62 ? 62 : -shift;
-        q = (i128)((unsigned __int128)c << l);
-    } else if (shift <= 16) {
-        q = (acc + (i128)(r16 >> (16 - shift))) >> shift;
-    } else {
-        q = ((acc >> (shift - 16)) + (i128)r16) >> 16;
-    }
-    if (relu && q < 0) q = 0;
-    const i128 qmax = ((i128)1 << (wl - 1)) - 1, qmin = -((i128)1 << (wl - 1));
-    return (int)(q > qmax ? qmax : q < qmin ? qmin : q);
 }
 
 template <typename OutT>

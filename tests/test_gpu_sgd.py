@@ -112,7 +112,7 @@ def test_invalid_arguments():
     w = dev(np.zeros(64, dtype=np.float32))
     g = dev(np.zeros(64, dtype=np.int8))
     with pytest.raises(pkg.AdaptError):
-        ctx().sgd_update_quantize(w, g, (17, 3), 0.1, 0, 0, 8, 5)
+        ctx().sgd_update_quantize(w, g, (33, 3), 0.1, 0, 0, 8, 5)
     with pytest.raises(pkg.AdaptError):
         ctx().sgd_update_quantize(w, g, (8, 3), float("nan"), 0, 0, 8, 5)
     with pytest.raises(pkg.AdaptError):
