@@ -341,7 +341,11 @@ int adapt_sgd_update_quantize(adapt_ctx *ctx, float *w, size_t n, const void *g,
  *   out    device double[2]: ds (+inf if only the denominator is 0, NaN if both are), and
  *          log ds (natural) when 0 < ds < inf, else 1 (the paper's "otherwise" case)
  * Limits: 1 <= count <= 64, n <= 2^30, and sum_k 2^(wl_k - 1 + fl_max - fl_k) < 2^31 (the element
- * sum is kept in 32 bits); ADAPT_EUNSUPPORTED beyond them.  n = 0 gives NaN and 1. */
+ * sum is kept in 32 bits); ADAPT_EUNSUPPORTED beyond them.  n = 0 gives NaN and 1.
+ * A window with a word length above 16 (int32_t codes for those tensors): the element sum is kept in
+ * 64 bits, the limit is sum_k 2^(wl_k - 1 + fl_max - fl_k) < 2^48, and every sum takes 128 bits:
+ * sums is then uint64_t[2 (count + 1)], pairs of words, low first: sum_i c_k[i]^2 for k < count, then
+ * the sum of the squared aligned element sums. */
 typedef struct { const void *g; int32_t wl, fl; } adapt_grad_item;
 int adapt_gradient_diversity(adapt_ctx *ctx, const adapt_grad_item *items, int count, size_t n,
                              uint64_t *sums, double *out);

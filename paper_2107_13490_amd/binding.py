@@ -529,9 +529,10 @@ class Context:
 
     # -- PushUp ---------------------------------------------------------------------------------
     def gradient_diversity(self, gs, fmts, out=None, sums=None, want_sums=True):
-        """gs: device code tensors of one size (int8 for wl <= 8, else int16), oldest first; fmts: their
-        (wl, fl).  Returns (out, sums): out = float64[2] (ds, log ds or 1), sums = int64 view of the
-        uint64[count + 2] integer sums (None unless asked for)."""
+        """gs: device code tensors of one size (int8 for wl <= 8, int16 for wl <= 16, else int32), oldest first; fmts:
+        their (wl, fl).  Returns (out, sums): out = float64[2] (ds, log ds or 1), sums = int64 view of the
+        uint64[count + 2] integer sums, or of the uint64[2 (count + 1)] 128-bit sums (low word first) when a word
+        length of the window exceeds 16 (None unless asked for)."""
         torch = self._torch
         count = len(gs)
         n = gs[0].numel() if count else 0
@@ -539,7 +540,8 @@ class Context:
         if out is None:
             out = torch.empty(2, dtype=torch.float64, device=dev)
         if sums is None and want_sums:
-            sums = torch.empty(count + 2, dtype=torch.int64, device=dev)
+            wide = any(f[0] > 16 for f in fmts)
+            sums = torch.empty(2 * (count + 1) if wide else count + 2, dtype=torch.int64, device=dev)
         items = (GradItem * max(count, 1))()
         for k in range(count):
             if gs[k].numel() != n:

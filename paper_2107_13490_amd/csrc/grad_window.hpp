@@ -13,7 +13,7 @@ constexpr int kGdMaxTensors = 64;
 // what the kernels read: tensors oldest first, each with its alignment to the finest grid
 struct GradWindow {
     const void *g[kGdMaxTensors];
-    uint8_t es[kGdMaxTensors];            // element bytes: 1 or 2
+    uint8_t es[kGdMaxTensors];            // element bytes: 1, 2 or 4
     uint8_t shift[kGdMaxTensors];         // fl_max - fl_k
     int8_t fl[kGdMaxTensors];
     int count;

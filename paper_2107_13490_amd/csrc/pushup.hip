@@ -16,6 +16,7 @@
 #include "common.hpp"
 #include "context.hpp"
 #include "grad_window.hpp"
+#include "wide.hpp"
 
 namespace adapt {
 
@@ -170,12 +171,119 @@ gd_final_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const ui
     out[1] = (ds > 0.0 && ds < (double)INFINITY) ? log(ds) : 1.0;
 }
 
+// ---- windows that hold int32 codes (word lengths 17..32) --------------------------------------------------------
+// The aligned element sum is kept in 64 bits (its bound is below 2^48), every sum of squares in 128 bits.
+// partial[col][block] as two words, low first: col k < count: sum of squares of tensor k; col count: sum of the
+// squared aligned element sums.
+__device__ __forceinline__ void load16_any(const void *g, int es, uint32_t n, uint32_t e0, int (&c)[16])
+{
+    if (e0 + 16 <= n) {
+        if (es == 4) {
+            const int4 *p = reinterpret_cast<const int4 *>(static_cast<const int32_t *>(g) + e0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int4 v = p[i];
+                c[4 * i] = v.x; c[4 * i + 1] = v.y; c[4 * i + 2] = v.z; c[4 * i + 3] = v.w;
+            }
+        } else {
+            gd_v4u raw[2];
+            const gd_v4u *p = reinterpret_cast<const gd_v4u *>(static_cast<const char *>(g) + (size_t)e0 * es);
+            raw[0] = p[0];
+            raw[1] = es == 2 ? p[1] : gd_v4u{0, 0, 0, 0};
+            unpack16(raw, es, c);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            int v = 0;
+            if (e0 + j < n) v = es == 4 ? static_cast<const int32_t *>(g)[e0 + j] : es == 2 ? (int)static_cast<const int16_t *>(g)[e0 + j]
+                                                                                          : (int)static_cast<const int8_t *>(g)[e0 + j];
+            c[j] = v;
+        }
+    }
+}
+
+template <bool BYPTR>
+__global__ void __launch_bounds__(kGdThreads)
+gd_partial_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, uint32_t n, uint64_t *partial)
+{
+    const GradWindow &w = BYPTR ? *wp : wv;
+    __shared__ unsigned long long wave_part[kGdThreads / kWave][kGdMaxTensors + 1][2];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const uint32_t e0 = (blockIdx.x * kGdThreads + threadIdx.x) * kGdPerThread;
+    long long S[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) S[j] = 0;
+    for (int k = 0; k < w.count; ++k) {
+        int c[16];
+        if (e0 < n) {
+            load16_any(w.g[k], w.es[k], n, e0, c);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) c[j] = 0;
+        }
+        const int sh = w.shift[k];
+        u128 sq = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            S[j] += (long long)((unsigned long long)(long long)c[j] << sh);
+            sq += (u128)(unsigned long long)((long long)c[j] * (long long)c[j]);
+        }
+        sq = wave_sum_u128(sq);
+        if (lane == 0) { wave_part[wave][k][0] = (unsigned long long)sq; wave_part[wave][k][1] = (unsigned long long)(sq >> 64); }
+    }
+    u128 t = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) t += (u128)((i128)S[j] * (i128)S[j]);
+    t = wave_sum_u128(t);
+    if (lane == 0) { wave_part[wave][w.count][0] = (unsigned long long)t; wave_part[wave][w.count][1] = (unsigned long long)(t >> 64); }
+    __syncthreads();
+    for (int col = threadIdx.x; col < w.count + 1; col += kGdThreads) {
+        u128 v = 0;
+#pragma unroll
+        for (int i = 0; i < kGdThreads / kWave; ++i) v += ((u128)wave_part[i][col][1] << 64) | wave_part[i][col][0];
+        uint64_t *dst = partial + 2 * ((size_t)col * gridDim.x + blockIdx.x);
+        dst[0] = (uint64_t)v;
+        dst[1] = (uint64_t)(v >> 64);
+    }
+}
+
+template <bool BYPTR>
+__global__ void __launch_bounds__(kGdFinalThreads)
+gd_final_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const uint64_t *__restrict__ partial, int nblocks,
+                     uint64_t *sums_out, double *out)
+{
+    const GradWindow &w = BYPTR ? *wp : wv;
+    __shared__ unsigned long long col_sum[kGdMaxTensors + 1][2];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (int col = wave; col < w.count + 1; col += kGdFinalThreads / kWave) {
+        const uint64_t *p = partial + 2 * (size_t)col * nblocks;
+        u128 v = 0;
+        for (int b = lane; b < nblocks; b += kWave) v += ((u128)p[2 * b + 1] << 64) | p[2 * b];
+        v = wave_sum_u128(v);
+        if (lane == 0) {
+            col_sum[col][0] = (unsigned long long)v;
+            col_sum[col][1] = (unsigned long long)(v >> 64);
+            if (sums_out) { sums_out[2 * col] = (uint64_t)v; sums_out[2 * col + 1] = (uint64_t)(v >> 64); }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    double num = 0.0;
+    for (int k = 0; k < w.count; ++k) num += ldexp(sqrt(u128_to_double(col_sum[k][0], col_sum[k][1])), -(int)w.fl[k]);
+    const double den = ldexp(sqrt(u128_to_double(col_sum[w.count][0], col_sum[w.count][1])), -w.fl_max);
+    const double ds = den > 0.0 ? num / den : (num > 0.0 ? (double)INFINITY : (double)NAN);
+    out[0] = ds;
+    out[1] = (ds > 0.0 && ds < (double)INFINITY) ? log(ds) : 1.0;
+}
+
 size_t ws_need_gradient_diversity(uint64_t n, int count);
 
 // One thread per layer of a chained step: the exponent of this batch's gradient lies in device memory (the fitting
 // pass of the backward pass wrote it), so the window can be laid out without the host reading it first.  The aligned
-// element sum of the diversity kernel is a 32-bit integer: when the scales of the window lie too far apart for that,
-// the oldest entries are left out until the rest fits (at least the newest entry stays).
+// element sum of the diversity kernel is a 32-bit integer (a 64-bit one with the bound 2^48 when the window holds codes
+// above 16 bits): when the scales of the window lie too far apart for that, the oldest entries are left out until the
+// rest fits (at least the newest entry stays).
 __global__ void chain_prep_kernel(const ChainLayerIn *__restrict__ in, int nlayers, const long long *__restrict__ e_g, size_t e_stride,
                                   GradWindow *__restrict__ win, ChainLayerOut *__restrict__ out)
 {
@@ -185,6 +293,9 @@ __global__ void chain_prep_kernel(const ChainLayerIn *__restrict__ in, int nlaye
     const int count = c.count;
     const long long e_new = e_g[(size_t)l * e_stride];
     auto exp_of = [&](int k) { return k == count - 1 ? e_new : c.exp[k]; };
+    bool wide = false;                              // codes above 16 bits: 64-bit element sums, bound 2^48
+    for (int k = 0; k < count; ++k) wide = wide || c.wl[k] > 16;
+    const int cap = wide ? 48 : 31;
     int first = 0;
     long long e_min = 0, e_max = 0;
     for (;; ++first) {
@@ -197,16 +308,16 @@ __global__ void chain_prep_kernel(const ChainLayerIn *__restrict__ in, int nlaye
         unsigned long long bound = 0;               // sum of 2^(wl - 1 + e_max - e_k), capped
         for (int k = first; k < count; ++k) {
             const long long b = (long long)c.wl[k] - 1 + e_max - exp_of(k);
-            bound += b >= 31 ? (1ull << 31) : (1ull << b);
+            bound += b >= cap ? (1ull << cap) : (1ull << b);
         }
-        if (bound < (1ull << 31) || first == count - 1) break;
+        if (bound < (1ull << cap) || first == count - 1) break;
     }
     GradWindow &w = win[l];
     const int used = count - first;
     for (int i = 0; i < used; ++i) {
         const int k = first + i;
         w.g[i] = c.g[k];
-        w.es[i] = (uint8_t)(c.wl[k] <= 8 ? 1 : 2);
+        w.es[i] = (uint8_t)(c.wl[k] <= 8 ? 1 : c.wl[k] <= 16 ? 2 : 4);
         w.shift[i] = (uint8_t)(e_max - exp_of(k));
         w.fl[i] = (int8_t)(exp_of(k) - e_min);
     }
@@ -232,6 +343,14 @@ int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers
     const GradWindow none = {};
     for (int l = 0; l < nlayers; ++l) {
         const int grid = (int)std::max<size_t>(1, (n[l] + per_block - 1) / per_block);
+        bool wide = false;
+        for (int k = 0; k < in[l].count; ++k) wide = wide || in[l].wl[k] > 16;
+        if (wide) {
+            hipLaunchKernelGGL(gd_partial_wide_kernel<true>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, none, win + l, (uint32_t)n[l], partial);
+            hipLaunchKernelGGL(gd_final_wide_kernel<true>, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, none, win + l, partial, grid,
+                               nullptr, &out[l].ds);
+            continue;
+        }
         hipLaunchKernelGGL(gd_partial_kernel<true>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, none, win + l, (uint32_t)n[l], partial);
         hipLaunchKernelGGL(gd_final_kernel<true>, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, none, win + l, partial, grid,
                            nullptr, &out[l].ds);
@@ -242,7 +361,8 @@ int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers
 size_t ws_need_gradient_diversity(uint64_t n, int count)
 {
     const size_t per_block = (size_t)kGdThreads * kGdPerThread;
-    return std::max<size_t>(1, (n + per_block - 1) / per_block) * (size_t)(count + 2) * sizeof(uint64_t);
+    // (count + 2) words per block, or (count + 1) pairs of words for windows with int32 codes
+    return std::max<size_t>(1, (n + per_block - 1) / per_block) * (size_t)(count + 1) * 2 * sizeof(uint64_t);
 }
 
 }  // namespace adapt
@@ -262,7 +382,7 @@ extern "C" int adapt_gradient_diversity(adapt_ctx *ctx, const adapt_grad_item *i
     int wl_max = 0;
     for (int k = 0; k < count; ++k) {
         const adapt_fmt f = adapt_fmt{items[k].wl, items[k].fl};
-        if (!fmt_ok(f)) return ADAPT_EINVAL;
+        if (!fmt_ok_wide(f)) return ADAPT_EINVAL;
         if (n > 0 && (!items[k].g || !aligned16(items[k].g))) return ADAPT_EINVAL;
         w.fl_max = std::max(w.fl_max, f.fl);
         wl_max = std::max(wl_max, f.wl);
@@ -271,14 +391,22 @@ extern "C" int adapt_gradient_diversity(adapt_ctx *ctx, const adapt_grad_item *i
     double bound = 0.0;
     for (int k = 0; k < count; ++k) {
         w.g[k] = items[k].g;
-        w.es[k] = (uint8_t)(items[k].wl <= 8 ? 1 : 2);
+        w.es[k] = (uint8_t)(items[k].wl <= 8 ? 1 : items[k].wl <= 16 ? 2 : 4);
         w.shift[k] = (uint8_t)(w.fl_max - items[k].fl);
         w.fl[k] = (int8_t)items[k].fl;
         bound += std::ldexp(1.0, items[k].wl - 1 + w.fl_max - items[k].fl);
     }
-    if (bound >= 2147483648.0) return ADAPT_EUNSUPPORTED;
     const size_t per_block = (size_t)kGdThreads * kGdPerThread;
     const int grid = (int)std::max<size_t>(1, (n + per_block - 1) / per_block);
+    if (wl_max > 16) {           // int32 codes in the window: 64-bit element sums (bound 2^48), 128-bit sums of squares
+        if (bound >= 281474976710656.0) return ADAPT_EUNSUPPORTED;
+        if ((size_t)grid * (count + 1) * 2 * sizeof(uint64_t) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+        uint64_t *part = reinterpret_cast<uint64_t *>(scratch(ctx));
+        hipLaunchKernelGGL(gd_partial_wide_kernel<false>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, w, nullptr, (uint32_t)n, part);
+        hipLaunchKernelGGL(gd_final_wide_kernel<false>, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, w, nullptr, part, grid, sums, out);
+        return hip_status(ctx, hipGetLastError());
+    }
+    if (bound >= 2147483648.0) return ADAPT_EUNSUPPORTED;
     if ((size_t)grid * (count + 2) * sizeof(uint64_t) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
     hipLaunchKernelGGL(gd_partial_kernel<false>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, w, nullptr, (uint32_t)n, partial);

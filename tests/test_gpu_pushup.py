@@ -105,7 +105,7 @@ def test_window_of_requantized_weight_gradients():
 def test_invalid_arguments():
     g = dev(np.zeros(64, dtype=np.int8))
     with pytest.raises(pkg.AdaptError):
-        ctx().gradient_diversity([g], [(17, 3)])
+        ctx().gradient_diversity([g], [(33, 3)])
     with pytest.raises(pkg.AdaptError):
         ctx().gradient_diversity([g] * 65, [(8, 3)] * 65)
     with pytest.raises(pkg.AdaptError):                      # 2^15 * 2^16 exceeds the 32-bit element sum

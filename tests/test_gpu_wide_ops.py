@@ -156,3 +156,37 @@ def test_step_from_a_sum_of_squares_that_needs_rounding_to_a_double():
         step = so.sgd_step_size(2.0 ** 60, 0, ss)
         want = so.fma32(-step, c.astype(np.float32), w)
         assert np.array_equal(host(wd).view(np.uint32), want.view(np.uint32)), ss
+
+
+def _pairs(t, count):
+    a = host(t).astype(np.int64)
+    return [(int(a[2 * k + 1]) & ((1 << 64) - 1)) * (1 << 64) + (int(a[2 * k]) & ((1 << 64) - 1)) for k in range(count)]
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 4095, 4096, 4097, 50021])
+@pytest.mark.parametrize("fmts", [[(32, 0)], [(32, 3), (32, 0), (32, 7)], [(24, 5), (8, 2), (16, 9), (17, 0)], [(20, 0)] * 9,
+                                  [(32, 0), (32, 16)], [(18, 20), (4, 0)]])
+def test_gradient_diversity_of_windows_with_int32_codes(n, fmts):
+    g = np.random.default_rng(n + len(fmts))
+    codes = [_codes(g, n, wl) for wl, _ in fmts]
+    out, sums = ctx().gradient_diversity([dev(c.astype(_dt(wl))) for c, (wl, _) in zip(codes, fmts)], fmts)
+    ref = wo.gradient_diversity(codes, [f for _, f in fmts])
+    got = _pairs(sums, len(fmts) + 1)
+    assert got[:-1] == ref["sumsq"] and got[-1] == ref["sumsq_sum"]
+    ds, log_ds = host(out).tolist()
+    assert abs(ds - ref["ds"]) <= 1e-12 * abs(ref["ds"]) and abs(log_ds - ref["log_ds"]) <= 1e-12 * max(1.0, abs(ref["log_ds"]))
+
+
+def test_gradient_diversity_wide_limits_and_degenerate_windows():
+    z = dev(np.zeros(100, np.int32))
+    out, sums = ctx().gradient_diversity([z, z], [(32, 0), (32, 0)])
+    ds, log_ds = host(out).tolist()
+    assert np.isnan(ds) and log_ds == 1.0 and _pairs(sums, 3) == [0, 0, 0]
+    a = dev(np.full(100, 5, np.int32))
+    out, _ = ctx().gradient_diversity([a, dev(np.full(100, -5, np.int32))], [(20, 0), (20, 0)])
+    assert host(out).tolist() == [float("inf"), 1.0]
+    with pytest.raises(pkg.AdaptError):                      # 2^31 * 2^17 reaches the 2^48 bound of the element sum
+        ctx().gradient_diversity([a, a], [(32, 0), (32, 17)])
+    ctx().gradient_diversity([a, a], [(32, 0), (31, 16)])     # 2^31 + 2^46 < 2^48
+    with pytest.raises(pkg.AdaptError):
+        ctx().gradient_diversity([a], [(33, 0)])
