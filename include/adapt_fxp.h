@@ -490,10 +490,11 @@ typedef struct adapt_net adapt_net; /* opaque, host */
 /* Per-layer record the step keeps in the workspace (device memory). */
 typedef struct {
     uint64_t g_sumsq;            /* sum of the squared weight-gradient codes */
+    uint64_t g_sumsq_hi;         /* its bits above 64: written only for gradient codes above 16 bits */
     uint64_t nnz, saturated;     /* of the re-quantized weights (adapt_net_update) */
     float range_lo, range_hi;    /* finite range of the updated master weights */
     int32_t shift_w, shift_a;    /* shifts chosen for the weight gradient / the data gradient handed down */
-    int32_t reserved[6];
+    int32_t reserved[4];
 } adapt_net_stats;
 
 enum { ADAPT_NT_INPUT = 0,   /* quantized network input (layer ignored) */
@@ -561,6 +562,18 @@ size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int 
 int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
                      float *const *weights, const adapt_switch_params *sp, void *workspace,
                      size_t workspace_bytes, adapt_net **net);
+/* The same chain laid out for word lengths up to wl_max (16 or 32; for callers that cannot tell in advance how far
+ * PushUp will go, Sec. 3.3 caps it at 32): with 32 every code buffer holds int32_t storage and the accumulator
+ * buffers 128-bit integers, adapt_net_set_format and the switch parameters' wl_hi may go up to 32, PushUp's cap is
+ * 32, tensors of layers above 16 bits are int32_t (adapt_net_tensor reports 4-byte elements), the loss gradient
+ * handed to adapt_net_backward is int32_t when the last layer has more than 16 bits, and adapt_net_stats holds the
+ * 128-bit sum of squares in g_sumsq / g_sumsq_hi.  A window whose gradients have more than 16 bits follows
+ * adapt_gradient_diversity's rule for such windows (bound 2^48).  Contractions with an operand above 16 bits are
+ * composed of 11-bit parts (see adapt_acc_bits): correct, and many times slower than the native ones. */
+size_t adapt_net_workspace_bytes_wide(const adapt_layer_desc *layers, int count, int lb_upr, int wl_max);
+int adapt_net_create_wide(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
+                          float *const *weights, const adapt_switch_params *sp, int wl_max,
+                          void *workspace, size_t workspace_bytes, adapt_net **out);
 int adapt_net_destroy(adapt_net *net);
 /* <WL,FL> of layer l: its weights, its output activations, and (WL only) its gradients. */
 int adapt_net_set_format(adapt_net *net, int layer, adapt_fmt f);

@@ -103,8 +103,9 @@ class NodeDesc(C.Structure):
 
 
 class NetStats(C.Structure):
-    _fields_ = [("g_sumsq", C.c_uint64), ("nnz", C.c_uint64), ("saturated", C.c_uint64), ("range_lo", C.c_float),
-                ("range_hi", C.c_float), ("shift_w", C.c_int32), ("shift_a", C.c_int32), ("reserved", C.c_int32 * 6)]
+    _fields_ = [("g_sumsq", C.c_uint64), ("g_sumsq_hi", C.c_uint64), ("nnz", C.c_uint64), ("saturated", C.c_uint64),
+                ("range_lo", C.c_float), ("range_hi", C.c_float), ("shift_w", C.c_int32), ("shift_a", C.c_int32),
+                ("reserved", C.c_int32 * 4)]
 
 
 NT_INPUT, NT_Y, NT_A, NT_DY, NT_DA, NT_QW, NT_G, NT_STATS, NT_YC, NT_DYC, NT_BN, NT_EXP, NT_DGAMMA, NT_DBETA = range(14)
@@ -192,6 +193,9 @@ def load_library():
     lib.adapt_net_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i, i]
     lib.adapt_net_workspace_bytes.restype = sz
     lib.adapt_net_create.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), C.POINTER(SwitchParams), vp, sz, C.POINTER(vp)]
+    lib.adapt_net_workspace_bytes_wide.argtypes = [C.POINTER(LayerDesc), i, i, i]
+    lib.adapt_net_workspace_bytes_wide.restype = sz
+    lib.adapt_net_create_wide.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), C.POINTER(SwitchParams), i, vp, sz, C.POINTER(vp)]
     lib.adapt_graph_workspace_bytes.argtypes = [C.POINTER(NodeDesc), i, i]
     lib.adapt_graph_workspace_bytes.restype = sz
     lib.adapt_graph_create.argtypes = [vp, C.POINTER(NodeDesc), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), dbl,
@@ -459,9 +463,9 @@ class Context:
         torch = self._torch
         fdy, fw, fx = Fmt(*fdy), Fmt(*fw), Fmt(*fx)
         if out_dx is None:
-            out_dx = torch.empty((d.n, d.h, d.w, d.c), dtype=self._out_dtype(d.r * d.s * d.k, fdy, fw, ep_dx), device=dy.device)
+            out_dx = self._out_tensor((d.n, d.h, d.w, d.c), d.r * d.s * d.k, fdy, fw, ep_dx, dy.device)
         if out_dw is None:
-            out_dw = torch.empty((d.k, d.r, d.s, d.c), dtype=self._out_dtype(d.n * d.p * d.q, fdy, fx, ep_dw), device=dy.device)
+            out_dw = self._out_tensor((d.k, d.r, d.s, d.c), d.n * d.p * d.q, fdy, fx, ep_dw, dy.device)
         _check(self._lib.adapt_conv_backward(self._h, d, _ptr(dy), fdy, _ptr(w), fw, _ptr(x), fx, _ptr(out_dx), ep_dx,
                                              _ptr(out_dw), ep_dw), "adapt_conv_backward")
         return out_dx, out_dw
@@ -677,9 +681,11 @@ class Net:
     """A chained fixed-point training step (adapt_net_*).  Holds the workspace tensor and the master
     weights (fp32 device tensors, KRSC, updated in place by update())."""
 
-    def __init__(self, ctx: Context, layers, weights, switch: "SwitchParams | None" = None, bn=None, bn_eps: float = 1e-5):
+    def __init__(self, ctx: Context, layers, weights, switch: "SwitchParams | None" = None, bn=None, bn_eps: float = 1e-5,
+                 wl_max: int = 16):
         """layers: LayerDesc entries (a plain chain) or NodeDesc entries (a graph; bn = list with, per layer, a
-        (gamma, beta) pair of device fp32 tensors or None)."""
+        (gamma, beta) pair of device fp32 tensors or None).  wl_max = 32 lays a plain chain out for word lengths up
+        to 32 (int32 codes, 128-bit accumulators)."""
         import torch
         self._ctx, self._lib, self._torch = ctx, ctx._lib, torch
         self.layers = list(layers)
@@ -688,9 +694,14 @@ class Net:
         n = len(self.layers)
         graph = any(isinstance(d, NodeDesc) for d in self.layers)
         lb_upr = switch.lb_upr if switch is not None else 0
+        if graph and wl_max != 16:
+            raise ValueError("graphs with batch normalisation keep word lengths of at most 16")
         if graph:
             descs = (NodeDesc * n)(*self.layers)
             need = self._lib.adapt_graph_workspace_bytes(descs, n, lb_upr)
+        elif wl_max != 16:
+            descs = (LayerDesc * n)(*self.layers)
+            need = self._lib.adapt_net_workspace_bytes_wide(descs, n, lb_upr, wl_max)
         else:
             descs = (LayerDesc * n)(*self.layers)
             need = self._lib.adapt_net_workspace_bytes(descs, n, lb_upr)
@@ -705,6 +716,9 @@ class Net:
             bp = (C.c_void_p * n)(*[(p[1].data_ptr() if p is not None else None) for p in (self.bn or [None] * n)])
             _check(self._lib.adapt_graph_create(ctx.handle, descs, n, wptrs, gp, bp, float(bn_eps), sw, _ptr(self.workspace), need,
                                                 C.byref(h)), "adapt_graph_create")
+        elif wl_max != 16:
+            _check(self._lib.adapt_net_create_wide(ctx.handle, descs, n, wptrs, sw, wl_max, _ptr(self.workspace), need, C.byref(h)),
+                   "adapt_net_create_wide")
         else:
             _check(self._lib.adapt_net_create(ctx.handle, descs, n, wptrs, sw, _ptr(self.workspace), need, C.byref(h)),
                    "adapt_net_create")
@@ -738,7 +752,7 @@ class Net:
             return raw.view(torch.int64)
         if which in (NT_DGAMMA, NT_DBETA):
             return raw.view(torch.float64)
-        return raw.view(torch.int8 if es.value == 1 else torch.int16)
+        return raw.view(torch.int8 if es.value == 1 else torch.int16 if es.value == 2 else torch.int32)
 
     def quantize_weights(self, mode=SR, seed=0, stream=0):
         _check(self._lib.adapt_net_quantize_weights(self._h, Rng(mode, seed, stream)), "adapt_net_quantize_weights")

@@ -23,6 +23,12 @@ extern "C" int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void
                                    adapt_fmt fw, const void *x, adapt_fmt fx, void *dx, adapt_epilogue ep_dx, void *dw,
                                    adapt_epilogue ep_dw)
 {
+    if (ctx && (wants_wide(fdy, fw, ep_dx) || wants_wide(fdy, fx, ep_dw))) {
+        // word lengths above 16: the two contractions one after the other, each composed of its parts
+        if (d.n > 0)
+            if (int s = adapt_conv_dgrad(ctx, d, dy, fdy, w, fw, dx, ep_dx)) return s;
+        return adapt_conv_wgrad(ctx, d, dy, fdy, x, fx, dw, ep_dw);
+    }
     if (!ctx || !fmt_ok(fdy) || !fmt_ok(fw) || !fmt_ok(fx) || !conv_ok(d)) return ADAPT_EINVAL;
     if (!dw || !aligned16(dw)) return ADAPT_EINVAL;
     if (d.n > 0 && (!check_ptrs(dy, w, dx) || !check_ptrs(dy, x, dw))) return ADAPT_EINVAL;

@@ -466,16 +466,20 @@ struct NetLayer {
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
-constexpr size_t kKldStride = 128;      // bytes per layer for the KL values of up to 15 candidates
+constexpr size_t kKldStride = 256;      // bytes per layer for the KL values of up to 31 candidates
 
 struct NetPlan {
     size_t off_in, off_accx, off_accw, off_stats, off_sel_group, off_kld_group, off_win, off_tmp, bytes;
 };
 
 // Lays the workspace out; returns false for an invalid network.
-bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, std::vector<NetLayer> &L, NetPlan &P)
+// wl_max: the largest word length any layer may take (16: int16 storage everywhere; 32: int32 storage and 128-bit
+// accumulators; only for networks without batch normalisation, shortcuts and average pooling)
+bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, int wl_max, std::vector<NetLayer> &L, NetPlan &P)
 {
-    if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64) return false;
+    if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64 || (wl_max != 16 && wl_max != 32)) return false;
+    const size_t cb = wl_max > 16 ? 4 : 2;              // bytes per code
+    const size_t ab = wl_max > 16 ? 16 : 8;             // bytes per exact accumulator
     L.assign(count, NetLayer());
     size_t off = 0, max_in = 0, max_w = 0, max_merge = 0;
     auto take = [&off](size_t bytes) { const size_t o = off; off += align_up(std::max<size_t>(bytes, 16)); return o; };
@@ -502,6 +506,7 @@ bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, std::vector<N
         y.src = descs[l].src >= 0 ? descs[l].src : l - 1;
         y.res = descs[l].res;
         if (y.src >= l || descs[l].src < -1 || y.res >= l || y.res < -1) return false;
+        if (wl_max > 16 && (y.bn || y.gap || y.res >= 0)) return false;
         if (y.res >= 0 && !y.bn) return false;                     // the shortcut is added inside the batch-norm output
         if (y.gap && y.d.pool) return false;
         y.fmt = adapt_fmt{8, 4};
@@ -520,24 +525,24 @@ bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, std::vector<N
         if (y.res >= 0 && L[y.res].n_a != y.n_y) return false;
         if (y.src >= 0) ++consumers[y.src];
         if (y.res >= 0) ++consumers[y.res];
-        // every code buffer holds int16 storage, so a layer may change its word length later
+        // every code buffer holds the widest storage, so a layer may change its word length later
         const bool post = y.d.pool || y.gap;                        // something follows the activation
-        y.off_y = take(2 * y.n_y);
-        y.off_a = post ? take(2 * y.n_a) : y.off_y;
-        y.off_da = take(2 * y.n_a);
-        y.off_dgap = y.gap ? take(2 * y.n_y) : 0;
-        y.off_dy = (y.d.pool || y.d.relu) ? take(2 * y.n_y) : (y.gap ? y.off_dgap : y.off_da);
-        y.off_yc = y.bn ? take(2 * y.n_y) : 0;
-        y.off_dyc = y.bn ? take(2 * y.n_y) : y.off_dy;
+        y.off_y = take(cb * y.n_y);
+        y.off_a = post ? take(cb * y.n_a) : y.off_y;
+        y.off_da = take(cb * y.n_a);
+        y.off_dgap = y.gap ? take(cb * y.n_y) : 0;
+        y.off_dy = (y.d.pool || y.d.relu) ? take(cb * y.n_y) : (y.gap ? y.off_dgap : y.off_da);
+        y.off_yc = y.bn ? take(cb * y.n_y) : 0;
+        y.off_dyc = y.bn ? take(cb * y.n_y) : y.off_dy;
         y.off_bn = y.bn ? take(adapt_bn_state_bytes(c.k)) : 0;
         y.off_dgam = y.bn ? take((size_t)c.k * 8) : 0;
         y.off_dbet = y.bn ? take((size_t)c.k * 8) : 0;
-        y.off_qw = take(2 * y.n_w);
+        y.off_qw = take(cb * y.n_w);
         // The weight gradient is written straight into a slot of the lookback ring (one slot more than the longest
         // window, so a free one always exists); without precision switching it has a buffer of its own.
-        y.off_g = lb_upr ? 0 : take(2 * y.n_w);
+        y.off_g = lb_upr ? 0 : take(cb * y.n_w);
         y.g_slot = -1;
-        y.slot_bytes = align_up(2 * y.n_w);
+        y.slot_bytes = align_up(cb * y.n_w);
         y.off_stat = P.off_stats + (size_t)l * kStatBytes;
         y.off_exp = off_exp + (size_t)l * kExpBytes;
         y.off_ds = off_ds + (size_t)l * 16;
@@ -554,10 +559,10 @@ bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, std::vector<N
         if (consumers[l] > 4) return false;
         if (consumers[l] > 1) max_merge = std::max(max_merge, L[l].n_a);
     }
-    P.off_in = take(2 * L[0].n_in);
-    P.off_accx = take(8 * max_in);
-    P.off_accw = take(8 * max_w);
-    P.off_tmp = max_merge ? take(2 * max_merge) : 0;
+    P.off_in = take(cb * L[0].n_in);
+    P.off_accx = take(ab * max_in);
+    P.off_accw = take(ab * max_w);
+    P.off_tmp = max_merge ? take(cb * max_merge) : 0;
     P.bytes = off;
     return true;
 }
@@ -572,6 +577,7 @@ struct adapt_net {
     char *ws;
     NetPlan P;
     double bn_eps;
+    int wl_max;               // 16, or 32 for a chain laid out for int32 codes
     bool forward_done, backward_done;
     int dlogits_fl;
     // precision switch
@@ -611,12 +617,12 @@ adapt_epilogue exact_ep()
 
 }  // namespace
 
-static bool switch_params_ok(const adapt_switch_params &p)
+static bool switch_params_ok(const adapt_switch_params &p, int wl_max)
 {
     if (p.lb_lwr < 1 || p.lb_upr < p.lb_lwr || p.lb_upr > 64 || p.lb_init < p.lb_lwr || p.lb_init > p.lb_upr) return false;
     if (p.r_lwr < 2 || p.r_upr < p.r_lwr || p.r_upr > 65536 || p.r_init < p.r_lwr || p.r_init > p.r_upr) return false;
     if (!(p.gamma >= 0.0 && p.gamma <= 1.0) || !(p.eps >= 0.0)) return false;
-    if (p.buff < 1 || p.buff > 15 || p.wl_lo < 2 || p.wl_hi < p.wl_lo || p.wl_hi > 16) return false;
+    if (p.buff < 1 || p.buff > wl_max - 1 || p.wl_lo < 2 || p.wl_hi < p.wl_lo || p.wl_hi > wl_max) return false;
     return p.strategy_init >= ADAPT_ST_MIN && p.strategy_init <= ADAPT_ST_MAX;
 }
 
@@ -639,7 +645,7 @@ extern "C" size_t adapt_graph_workspace_bytes(const adapt_node_desc *nodes, int 
 {
     std::vector<NetLayer> L;
     NetPlan P;
-    return plan_net(nodes, count, lb_upr, L, P) ? P.bytes : 0;
+    return plan_net(nodes, count, lb_upr, 16, L, P) ? P.bytes : 0;
 }
 
 extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int lb_upr)
@@ -648,12 +654,21 @@ extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int 
     return nodes.empty() ? 0 : adapt_graph_workspace_bytes(nodes.data(), count, lb_upr);
 }
 
-extern "C" int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights, float *const *gammas,
-                                  float *const *betas, double bn_eps, const adapt_switch_params *sp, void *workspace,
-                                  size_t workspace_bytes, adapt_net **out)
+extern "C" size_t adapt_net_workspace_bytes_wide(const adapt_layer_desc *layers, int count, int lb_upr, int wl_max)
+{
+    const std::vector<adapt_node_desc> nodes = plain_nodes(layers, count);
+    std::vector<NetLayer> L;
+    NetPlan P;
+    return (!nodes.empty() && plan_net(nodes.data(), count, lb_upr, wl_max, L, P)) ? P.bytes : 0;
+}
+
+static int graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights, float *const *gammas,
+                        float *const *betas, double bn_eps, const adapt_switch_params *sp, int wl_max, void *workspace,
+                        size_t workspace_bytes, adapt_net **out)
 {
     if (!ctx || !out || !weights || !workspace || ((uintptr_t)workspace & 255) || !(bn_eps >= 0.0)) return ADAPT_EINVAL;
-    if (sp && !switch_params_ok(*sp)) return ADAPT_EINVAL;
+    if (wl_max != 16 && wl_max != 32) return ADAPT_EINVAL;
+    if (sp && !switch_params_ok(*sp, wl_max)) return ADAPT_EINVAL;
     adapt_net *net = new (std::nothrow) adapt_net();
     if (!net) return ADAPT_EINVAL;
     net->ctx = ctx;
@@ -661,6 +676,7 @@ extern "C" int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, 
     net->forward_done = net->backward_done = false;
     net->dlogits_fl = 0;
     net->bn_eps = bn_eps;
+    net->wl_max = wl_max;
     net->has_switch = sp != nullptr;
     net->switch_due = false;
     if (sp) net->sp = *sp;
@@ -668,7 +684,7 @@ extern "C" int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, 
     net->pinned = nullptr;
     net->chain_in = nullptr;
     net->chain_out = nullptr;
-    const bool planned = plan_net(nodes, count, sp ? sp->lb_upr : 0, net->L, net->P);
+    const bool planned = plan_net(nodes, count, sp ? sp->lb_upr : 0, wl_max, net->L, net->P);
     bool ok = planned && net->P.bytes <= workspace_bytes;
     for (int l = 0; ok && l < count; ++l) {
         NetLayer &y = net->L[l];
@@ -700,12 +716,28 @@ extern "C" int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, 
     return ADAPT_OK;
 }
 
+extern "C" int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights, float *const *gammas,
+                                  float *const *betas, double bn_eps, const adapt_switch_params *sp, void *workspace,
+                                  size_t workspace_bytes, adapt_net **out)
+{
+    return graph_create(ctx, nodes, count, weights, gammas, betas, bn_eps, sp, 16, workspace, workspace_bytes, out);
+}
+
 extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
                                 const adapt_switch_params *sp, void *workspace, size_t workspace_bytes, adapt_net **out)
 {
     const std::vector<adapt_node_desc> nodes = plain_nodes(layers, count);
     if (nodes.empty()) return ADAPT_EINVAL;
-    return adapt_graph_create(ctx, nodes.data(), count, weights, nullptr, nullptr, 0.0, sp, workspace, workspace_bytes, out);
+    return graph_create(ctx, nodes.data(), count, weights, nullptr, nullptr, 0.0, sp, 16, workspace, workspace_bytes, out);
+}
+
+extern "C" int adapt_net_create_wide(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,
+                                     const adapt_switch_params *sp, int wl_max, void *workspace, size_t workspace_bytes,
+                                     adapt_net **out)
+{
+    const std::vector<adapt_node_desc> nodes = plain_nodes(layers, count);
+    if (nodes.empty()) return ADAPT_EINVAL;
+    return graph_create(ctx, nodes.data(), count, weights, nullptr, nullptr, 0.0, sp, wl_max, workspace, workspace_bytes, out);
 }
 
 extern "C" int adapt_net_destroy(adapt_net *net)
@@ -721,7 +753,7 @@ extern "C" int adapt_net_destroy(adapt_net *net)
 
 extern "C" int adapt_net_set_format(adapt_net *net, int layer, adapt_fmt f)
 {
-    if (!net || layer < 0 || layer >= (int)net->L.size() || !fmt_ok(f)) return ADAPT_EINVAL;
+    if (!net || layer < 0 || layer >= (int)net->L.size() || !fmt_ok_wide(f) || f.wl > net->wl_max) return ADAPT_EINVAL;
     net->L[layer].fmt = f;
     net->forward_done = net->backward_done = false;
     return ADAPT_OK;
@@ -741,7 +773,7 @@ extern "C" int adapt_net_tensor(const adapt_net *net, int layer, int which, size
     case ADAPT_NT_DY: *offset = y.off_dy; *count = y.n_y; *elem_bytes = es; break;
     case ADAPT_NT_DA: *offset = y.off_da; *count = y.n_a; *elem_bytes = es; break;
     case ADAPT_NT_QW: *offset = y.off_qw; *count = y.n_w; *elem_bytes = es; break;
-    case ADAPT_NT_G: *offset = y.g_off(); *count = y.n_w; *elem_bytes = y.g_wl ? (y.g_wl <= 8 ? 1 : 2) : es; break;
+    case ADAPT_NT_G: *offset = y.g_off(); *count = y.n_w; *elem_bytes = y.g_wl ? storage_bytes(adapt_fmt{y.g_wl, 0}) : es; break;
     case ADAPT_NT_STATS: *offset = y.off_stat; *count = 1; *elem_bytes = (int)sizeof(adapt_net_stats); break;
     case ADAPT_NT_YC: if (!y.bn) return ADAPT_EINVAL; *offset = y.off_yc; *count = y.n_y; *elem_bytes = es; break;
     case ADAPT_NT_DYC: *offset = y.off_dyc; *count = y.n_y; *elem_bytes = es; break;
@@ -760,16 +792,22 @@ extern "C" int adapt_net_quantize_weights(adapt_net *net, adapt_rng rng)
     const int count = (int)net->L.size();
     for (NetLayer &y : net->L) y.range_valid = false;          // the caller may have written the master weights
     adapt_quantize_item items[kMaxLayers];
+    int m = 0;
     for (int l = 0; l < count; ++l) {
         const NetLayer &y = net->L[l];
-        items[l].x = y.w;
-        items[l].q = net->ws + y.off_qw;
-        items[l].n = y.n_w;
-        items[l].wl = y.fmt.wl;
-        items[l].fl = y.fmt.fl;
-        items[l].stream = rng.stream + (uint64_t)(8 * l + 5);
+        if (y.fmt.wl > 16) {                                   // int32 codes: the batched call stops at 16 bits
+            if (int s = adapt_quantize(net->ctx, y.w, y.n_w, y.fmt, slot_rng(rng, l, 5), net->ws + y.off_qw, nullptr, nullptr)) return s;
+            continue;
+        }
+        items[m].x = y.w;
+        items[m].q = net->ws + y.off_qw;
+        items[m].n = y.n_w;
+        items[m].wl = y.fmt.wl;
+        items[m].fl = y.fmt.fl;
+        items[m].stream = rng.stream + (uint64_t)(8 * l + 5);
+        ++m;
     }
-    return adapt_quantize_batched(net->ctx, items, count, rng.mode, rng.seed, nullptr);
+    return m ? adapt_quantize_batched(net->ctx, items, m, rng.mode, rng.seed, nullptr) : ADAPT_OK;
 }
 
 extern "C" int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng)
@@ -984,11 +1022,11 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
             members[m++] = l;
         }
         if (m == 0) continue;
-        // the t-th member of a group writes kld[16 * (group_base + t)...] and sel[2 * (group_base + t)]
+        // the t-th member of a group writes kld[32 * (group_base + t)...] and sel[2 * (group_base + t)]
         double *gk = reinterpret_cast<double *>(net->ws + net->P.off_kld_group);
         int32_t *gs = reinterpret_cast<int32_t *>(net->ws + net->P.off_sel_group);
         if (int s = adapt_kld_precision_search_batched_ranged(ctx, items, ranges, m, lo, sp.wl_hi, sp.eps, -1.0, rng.mode, rng.seed,
-                                                              gk + (size_t)group_base * 16, gs + 2 * (size_t)group_base))
+                                                              gk + (size_t)group_base * 32, gs + 2 * (size_t)group_base))
             return s;
         for (int t = 0; t < m; ++t) group_slot[members[t]] = group_base + t;
         group_base += m;
@@ -1010,7 +1048,7 @@ extern "C" int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng
         if (lo_of[l] <= sp.wl_hi) wl_min = std::min<int>(sel[2 * (size_t)group_slot[l]], y.fmt.wl);
         const int fl_min = wl_min - il;
         adapt_pushup_result r;
-        if (int s = adapt_pushup_suggest(out[l].ds, wl_min, fl_min, strategy_new, sp.buff, 16, &r)) return s;
+        if (int s = adapt_pushup_suggest(out[l].ds, wl_min, fl_min, strategy_new, sp.buff, net->wl_max, &r)) return s;
         fmt_new[l] = adapt_fmt{r.wl, r.fl};
         wl_min_of[l] = wl_min;
         fl_min_of[l] = fl_min;

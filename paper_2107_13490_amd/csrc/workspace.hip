@@ -120,6 +120,17 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
                 const uint64_t outs = q->call == ADAPT_CALL_CONV_FWD ? ny : q->call == ADAPT_CALL_CONV_DGRAD ? nx : nw;
                 return std::max<size_t>(inner, (size_t)1 << 20) + ws_need_wide(ea, q->fa.wl > 16, eb, q->fb.wl > 16, outs, false) + slack;
             }
+            if (q->call == ADAPT_CALL_CONV_BACKWARD && fmt_ok_wide(q->fa) && fmt_ok_wide(q->fb) && fmt_ok_wide(q->fc) &&
+                (q->fa.wl > 16 || q->fb.wl > 16 || q->fc.wl > 16) && conv_ok(q->conv)) {
+                // above 16 bits the backward call runs the two contractions one after the other
+                adapt_workspace_query sub = *q;
+                sub.call = ADAPT_CALL_CONV_DGRAD;
+                const size_t a = adapt_workspace_bytes(ctx, &sub);
+                sub.call = ADAPT_CALL_CONV_WGRAD;
+                sub.fb = q->fc;
+                const size_t b = adapt_workspace_bytes(ctx, &sub);
+                return (a == kInvalid || b == kInvalid) ? kInvalid : std::max(a, b);
+            }
             if (!fmt_ok(q->fa) || !fmt_ok(q->fb) || !conv_ok(q->conv)) return kInvalid;
             if (q->call == ADAPT_CALL_CONV_BACKWARD && !fmt_ok(q->fc)) return kInvalid;
             const size_t need = conv_need(&dry, q->call, q->conv, q->fa, q->fb, q->fc);

@@ -17,7 +17,11 @@ pytestmark = pytest.mark.gpu
 
 
 def _dt(wl):
-    return np.int8 if wl <= 8 else np.int16
+    return np.int8 if wl <= 8 else np.int16 if wl <= 16 else np.int32
+
+
+def _sumsq(st):
+    return (st.g_sumsq_hi << 64) + st.g_sumsq
 
 
 def _codes(rng, shape, wl, zero_frac=0.0):
@@ -113,14 +117,14 @@ def test_residual_add(n, fa, fb, fo):
 
 # ---- the chained step -----------------------------------------------------------------------------------
 
-def _run_chain(layers, fmts, n, seed, lr=0.05, l1=1e-4, l2=1e-3):
+def _run_chain(layers, fmts, n, seed, lr=0.05, l1=1e-4, l2=1e-3, wl_max=16):
     rng = np.random.default_rng(seed)
     first = layers[0]
     x = rng.standard_normal((n, first.h, first.w, first.c)).astype(np.float32)
     ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * (1.5 / np.sqrt(L.r * L.s * L.c))).astype(np.float32) for L in layers]
     descs = [LayerDesc(ConvDesc(n, L.h, L.w, L.c, L.k, L.r, L.s, L.stride, L.pad), int(L.relu), int(L.pool)) for L in layers]
     wdev = [dev(w.copy()) for w in ws]
-    net = pkg.Net(ctx(), descs, wdev)
+    net = pkg.Net(ctx(), descs, wdev, wl_max=wl_max)
     for l, (wl, fl) in enumerate(fmts):
         net.set_format(l, wl, fl)
     s0 = 1000 + seed
@@ -147,7 +151,7 @@ def _run_chain(layers, fmts, n, seed, lr=0.05, l1=1e-4, l2=1e-3):
     for l in range(len(layers)):
         st = net.tensor(l, pkg.NT_STATS)
         assert np.array_equal(host(net.tensor(l, pkg.NT_G)).astype(np.int64), bwd["g"][l].ravel()), l
-        assert st.shift_w == bwd["shift_w"][l] and st.g_sumsq == bwd["sumsq"][l], l
+        assert st.shift_w == bwd["shift_w"][l] and (_sumsq(st) if fmts[l][0] > 16 else st.g_sumsq) == bwd["sumsq"][l], l
         if layers[l].relu or layers[l].pool:
             assert np.array_equal(host(net.tensor(l, pkg.NT_DY)).astype(np.int64), bwd["dy"][l].ravel()), l
         if l > 0:
@@ -216,7 +220,7 @@ def test_invalid_chains_are_rejected():
 
 # ---- the whole of Alg. 1 with the precision switch of Alg. 2 -----------------------------------------------
 
-def _train_with_switch(layers, fmts, n, steps, seed, sp_kw, fl_jumps=None, cx=None, starved=None, used_seen=None):
+def _train_with_switch(layers, fmts, n, steps, seed, sp_kw, fl_jumps=None, cx=None, starved=None, used_seen=None, wl_max=16):
     """fl_jumps: step -> added to the fractional bits the loss gradient is declared with (its codes stay the same);
     cx: the context to run on; starved: an empty list: the first precision switch that fails for lack of scratch in cx
     is repeated after the scratch has grown, and its step is appended; used_seen: list that collects r.used."""
@@ -228,12 +232,12 @@ def _train_with_switch(layers, fmts, n, steps, seed, sp_kw, fl_jumps=None, cx=No
     wdev = [dev(w.copy()) for w in ws]
     sp = pkg.SwitchParams(sp_kw["lb_lwr"], sp_kw["lb_upr"], sp_kw["lb_init"], sp_kw["r_lwr"], sp_kw["r_upr"], sp_kw["r_init"],
                           sp_kw["gamma"], sp_kw["eps"], sp_kw["buff"], sp_kw["wl_lo"], sp_kw["wl_hi"], po.ST_MIN)
-    net = pkg.Net(cx if cx is not None else ctx(), descs, wdev, switch=sp)
+    net = pkg.Net(cx if cx is not None else ctx(), descs, wdev, switch=sp, wl_max=wl_max)
     fmts = list(fmts)
     for l, (wl, fl) in enumerate(fmts):
         net.set_format(l, wl, fl)
     st = no.SwitchState(len(layers), sp_kw["lb_lwr"], sp_kw["lb_upr"], sp_kw["lb_init"], sp_kw["r_lwr"], sp_kw["r_upr"],
-                        sp_kw["r_init"], sp_kw["gamma"], sp_kw["eps"], sp_kw["buff"], sp_kw["wl_lo"], sp_kw["wl_hi"])
+                        sp_kw["r_init"], sp_kw["gamma"], sp_kw["eps"], sp_kw["buff"], sp_kw["wl_lo"], sp_kw["wl_hi"], wl_cap=wl_max)
     net.quantize_weights(seed=seed, stream=5)
     wq = no.quantize_weights(layers, fmts, ws, seed, 5)
     last = len(layers) - 1
@@ -295,6 +299,44 @@ def test_training_steps_with_precision_switching_follow_the_oracle():
     kw = dict(lb_lwr=2, lb_upr=4, lb_init=2, r_lwr=50, r_upr=60, r_init=55, gamma=0.5, eps=1e-2, buff=2, wl_lo=2, wl_hi=16)
     switches, fmts = _train_with_switch(_small_net(), [(8, 5), (8, 5), (8, 4)], n=6, steps=8, seed=31, sp_kw=kw)
     assert switches >= 3
+
+
+# ---- chains laid out for word lengths up to 32 ---------------------------------------------------------------
+
+def _tiny_net():
+    return [no.Layer(6, 6, 3, 8, relu=True, pool=True),
+            no.Layer(3, 3, 8, 8, relu=True, pool=False),
+            no.Layer(1, 1, 72, 5, 1, 1, 1, 0, relu=False, pool=False)]
+
+
+@pytest.mark.parametrize("fmts", [[(24, 18), (20, 14), (32, 24)], [(8, 5), (24, 16), (12, 8)], [(17, 12), (16, 11), (17, 10)],
+                                  [(32, 26), (32, 26), (32, 26)], [(12, 8), (8, 5), (8, 4)]])
+def test_small_chain_with_layers_above_sixteen_bits(fmts):
+    _run_chain(_tiny_net(), fmts, n=3, seed=sum(w for w, _ in fmts), wl_max=32)
+
+
+@pytest.mark.parametrize("start,buff,eps,crossed", [([(14, 10), (20, 15), (8, 4)], 4, 1e-4, 1), ([(16, 12), (30, 24), (12, 8)], 6, 1e-6, 3)])
+def test_training_steps_with_precision_switching_up_to_thirty_two_bits(start, buff, eps, crossed):
+    # the second case takes a 16-bit and a 12-bit layer above 16 bits by PushUp and a 30-bit layer down to 21
+    kw = dict(lb_lwr=2, lb_upr=3, lb_init=2, r_lwr=50, r_upr=60, r_init=55, gamma=0.5, eps=eps, buff=buff, wl_lo=2, wl_hi=32)
+    switches, fmts = _train_with_switch(_tiny_net(), start, n=3, steps=7, seed=41, sp_kw=kw, wl_max=32)
+    assert switches >= 6 and sum(w > 16 for w, _ in fmts) == crossed
+
+
+def test_wide_chain_limits():
+    descs = [LayerDesc(ConvDesc(2, 8, 8, 4, 8, 3, 3, 1, 1), 1, 1)]
+    w = [dev(np.zeros((8, 3, 3, 4), np.float32))]
+    net = pkg.Net(ctx(), descs, w)
+    with pytest.raises(pkg.AdaptError):                    # a chain laid out for 16 bits takes no wider format
+        net.set_format(0, 17, 12)
+    net.close()
+    net = pkg.Net(ctx(), descs, w, wl_max=32)
+    net.set_format(0, 32, 20)
+    with pytest.raises(pkg.AdaptError):
+        net.set_format(0, 33, 20)
+    net.close()
+    with pytest.raises(pkg.AdaptError):
+        pkg.Net(ctx(), descs, w, wl_max=24)
 
 
 def test_precision_switching_across_the_one_and_two_limb_boundary():

@@ -111,6 +111,24 @@ def test_wide_convolutions(shp, wx, ww):
     assert np.array_equal(host(out).astype(np.int64), wo.requantize(dw, 2 * fx[1], 32, orc.RN_HALF_UP, 0, 0))
 
 
+@pytest.mark.parametrize("wdy,ww,wx", [(24, 20, 12), (12, 28, 8), (8, 8, 32), (32, 32, 32)])
+def test_wide_backward_call_gives_both_gradients(wdy, ww, wx):
+    shp = (2, 6, 5, 8, 16, 3, 3, 1, 1)
+    n, h, w, c, k, r, s, stride, pad = shp
+    d = ConvDesc(*shp)
+    g = np.random.default_rng(wdy + ww + wx)
+    x, wt, dy = _codes(g, (n, h, w, c), wx), _codes(g, (k, r, s, c), ww), _codes(g, (n, d.p, d.q, k), wdy)
+    dx, dw = ctx().conv_backward(d, dev(dy), (wdy, 0), dev(wt), (ww, 3), dev(x), (wx, 2), Epilogue.exact(), Epilogue.exact())
+    want_dx, want_dw = wo.conv_dgrad(dy, wt, h, w, stride, pad), wo.conv_wgrad(dy, x, r, s, stride, pad)
+    as_int = lambda t, wide: _i128(t) if wide else host(t).astype(object)
+    assert np.array_equal(as_int(dx, wdy > 16 or ww > 16), want_dx)
+    assert np.array_equal(as_int(dw, wdy > 16 or wx > 16), want_dw)
+    need = ctx().workspace_bytes(pkg.CALL_CONV_BACKWARD, conv=d, fa=(wdy, 0), fb=(ww, 3), fc=(wx, 2))
+    one = max(ctx().workspace_bytes(pkg.CALL_CONV_DGRAD, conv=d, fa=(wdy, 0), fb=(ww, 3)),
+              ctx().workspace_bytes(pkg.CALL_CONV_WGRAD, conv=d, fa=(wdy, 0), fb=(wx, 2)))
+    assert need == one
+
+
 def test_workspace_query_covers_a_wide_call():
     g = np.random.default_rng(8)
     m, n, k = 96, 80, 512
