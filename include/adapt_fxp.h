@@ -166,7 +166,8 @@ int adapt_quantize_noalloc(adapt_ctx *ctx, const float *x, size_t n, adapt_fmt f
  * pointers); each tensor is quantized exactly as by adapt_quantize with the item's own format
  * and rng stream (mode and seed are shared).  nnz / saturated of item t are written to
  * counters[2t], counters[2t+1] (device, uint64_t[2*count], may be NULL).  Descriptors travel
- * as kernel arguments, 64 per launch. */
+ * as kernel arguments, 64 per launch.  Items with 17 <= wl <= 32 (int32_t codes) are taken out of the
+ * shared launch and run one after the other, each with a launch of its own. */
 typedef struct {
     const float *x; void *q; uint64_t n; int32_t wl, fl; uint64_t stream;
 } adapt_quantize_item;

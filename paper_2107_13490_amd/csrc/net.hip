@@ -792,22 +792,16 @@ extern "C" int adapt_net_quantize_weights(adapt_net *net, adapt_rng rng)
     const int count = (int)net->L.size();
     for (NetLayer &y : net->L) y.range_valid = false;          // the caller may have written the master weights
     adapt_quantize_item items[kMaxLayers];
-    int m = 0;
     for (int l = 0; l < count; ++l) {
         const NetLayer &y = net->L[l];
-        if (y.fmt.wl > 16) {                                   // int32 codes: the batched call stops at 16 bits
-            if (int s = adapt_quantize(net->ctx, y.w, y.n_w, y.fmt, slot_rng(rng, l, 5), net->ws + y.off_qw, nullptr, nullptr)) return s;
-            continue;
-        }
-        items[m].x = y.w;
-        items[m].q = net->ws + y.off_qw;
-        items[m].n = y.n_w;
-        items[m].wl = y.fmt.wl;
-        items[m].fl = y.fmt.fl;
-        items[m].stream = rng.stream + (uint64_t)(8 * l + 5);
-        ++m;
+        items[l].x = y.w;
+        items[l].q = net->ws + y.off_qw;
+        items[l].n = y.n_w;
+        items[l].wl = y.fmt.wl;
+        items[l].fl = y.fmt.fl;
+        items[l].stream = rng.stream + (uint64_t)(8 * l + 5);
     }
-    return m ? adapt_quantize_batched(net->ctx, items, m, rng.mode, rng.seed, nullptr) : ADAPT_OK;
+    return adapt_quantize_batched(net->ctx, items, count, rng.mode, rng.seed, nullptr);
 }
 
 extern "C" int adapt_net_forward(adapt_net *net, const float *x, adapt_rng rng)

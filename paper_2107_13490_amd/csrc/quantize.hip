@@ -130,9 +130,10 @@ quantize_kernel(const float *__restrict__ x, OutT *__restrict__ q, uint64_t n, i
 
 __global__ void __launch_bounds__(kQThreads)
 quantize_wide_kernel(const float *__restrict__ x, int32_t *__restrict__ q, uint64_t n, int wl, int fl, int mode, uint64_t seed,
-                     uint64_t stream, uint32_t *partial /* [2][gridDim.x] or null */)
+                     uint64_t stream, uint32_t *partial /* [2][gridDim.x] or null */, float *range_partial = nullptr /* [2][gridDim.x] */)
 {
     uint32_t nnz = 0, nsat = 0;
+    float lo = INFINITY, hi = -INFINITY;                   // finite range of the input (only stored when asked for)
     const uint64_t full_groups = n >> 3;
     const uint64_t first = (uint64_t)blockIdx.x * kQThreads + threadIdx.x, stride = (uint64_t)gridDim.x * kQThreads;
     for (uint64_t g = first; g < full_groups; g += stride) {
@@ -154,6 +155,7 @@ quantize_wide_kernel(const float *__restrict__ x, int32_t *__restrict__ q, uint6
             c[e] = quantize_one_wide(v[e], r[e], wl, fl, s);
             nnz += (c[e] != 0);
             nsat += s;
+            if (fabsf(v[e]) < INFINITY) { lo = fminf(lo, v[e]); hi = fmaxf(hi, v[e]); }
         }
         reinterpret_cast<int4 *>(q)[2 * g] = make_int4(c[0], c[1], c[2], c[3]);
         reinterpret_cast<int4 *>(q)[2 * g + 1] = make_int4(c[4], c[5], c[6], c[7]);
@@ -165,7 +167,20 @@ quantize_wide_kernel(const float *__restrict__ x, int32_t *__restrict__ q, uint6
             q[i] = c;
             nnz += (c != 0);
             nsat += s;
+            if (fabsf(x[i]) < INFINITY) { lo = fminf(lo, x[i]); hi = fmaxf(hi, x[i]); }
         }
+    if (range_partial != nullptr) {
+        __shared__ float wr[2][kQThreads / kWave];
+        lo = wave_min_f32(lo);
+        hi = wave_max_f32(hi);
+        if ((threadIdx.x & (kWave - 1)) == 0) { wr[0][threadIdx.x / kWave] = lo; wr[1][threadIdx.x / kWave] = hi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < kQThreads / kWave; ++w) { lo = fminf(lo, wr[0][w]); hi = fmaxf(hi, wr[1][w]); }
+            range_partial[blockIdx.x] = lo;
+            range_partial[gridDim.x + blockIdx.x] = hi;
+        }
+    }
     if (partial == nullptr) return;
     uint64_t bn, bs;
     block_sum2(nnz, nsat, bn, bs);
@@ -409,7 +424,7 @@ extern "C" int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantiz
     if ((counters && ((uintptr_t)counters & 7)) || (ranges && ((uintptr_t)ranges & 3))) return ADAPT_EINVAL;
     for (int t = 0; t < count; ++t) {
         const adapt_quantize_item &it = items[t];
-        if (!fmt_ok(adapt_fmt{it.wl, it.fl}) || it.n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
+        if (!fmt_ok_wide(adapt_fmt{it.wl, it.fl}) || it.n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
         if (it.n > 0 && (!it.x || !it.q || !aligned16(it.x) || !aligned16(it.q))) return ADAPT_EINVAL;
     }
     if (count == 0) return ADAPT_OK;
@@ -419,7 +434,11 @@ extern "C" int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantiz
         uint64_t total_blocks = 0;
         for (int t = 0; t < batch.count; ++t) {
             batch.item[t] = items[base + t];
-            total_blocks += (((items[base + t].n + 7) >> 3) + kQThreads - 1) / kQThreads;
+            if (items[base + t].wl > 16) {             // int32 codes: a launch of its own below; an empty placeholder here
+                batch.item[t].n = 0;
+                batch.item[t].wl = 8;
+            }
+            total_blocks += (((batch.item[t].n + 7) >> 3) + kQThreads - 1) / kQThreads;
         }
         uint64_t grid = total_blocks;
         uint64_t cap = (uint64_t)ctx->num_cu * 4;
@@ -435,6 +454,23 @@ extern "C" int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantiz
             hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kSumThreads), 0, ctx->stream, partial, (int)grid,
                                2 * batch.count, counters ? counters + 2 * base : (uint64_t *)nullptr, (uint64_t *)nullptr,
                                range_partial, ranges ? 2 * batch.count : 0, ranges ? ranges + 2 * base : (float *)nullptr);
+    }
+    // tensors above 16 bits, one after the other; their counters and ranges replace the placeholders' zeros
+    for (int t = 0; t < count; ++t) {
+        const adapt_quantize_item &it = items[t];
+        if (it.wl <= 16) continue;
+        const int grid = grid_for(ctx, it.n);
+        const size_t part_bytes = ((size_t)grid * 2 * sizeof(uint32_t) + 255) & ~(size_t)255;
+        if (2 * part_bytes > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+        const bool want_range = ranges && ((range_mask >> t) & 1);
+        uint32_t *partial = counters ? reinterpret_cast<uint32_t *>(scratch(ctx)) : nullptr;
+        float *range_partial = want_range ? reinterpret_cast<float *>(scratch(ctx) + part_bytes) : nullptr;
+        hipLaunchKernelGGL(quantize_wide_kernel, dim3(grid), dim3(kQThreads), 0, ctx->stream, it.x, static_cast<int32_t *>(it.q), it.n,
+                           (int)it.wl, (int)it.fl, mode, seed, it.stream, partial, range_partial);
+        if (counters || want_range)
+            hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kSumThreads), 0, ctx->stream, partial, grid, counters ? 2 : 0,
+                               counters ? counters + 2 * t : (uint64_t *)nullptr, (uint64_t *)nullptr, range_partial,
+                               want_range ? 2 : 0, want_range ? ranges + 2 * t : (float *)nullptr);
     }
     return hip_status(ctx, hipGetLastError());
 }

@@ -190,3 +190,29 @@ def test_gradient_diversity_wide_limits_and_degenerate_windows():
     ctx().gradient_diversity([a, a], [(32, 0), (31, 16)])     # 2^31 + 2^46 < 2^48
     with pytest.raises(pkg.AdaptError):
         ctx().gradient_diversity([a], [(33, 0)])
+
+
+def test_batched_quantize_with_items_above_sixteen_bits():
+    g = np.random.default_rng(77)
+    fmts = [(8, 5), (24, 20), (12, 9), (32, 28), (17, 10), (4, 1), (32, 0)]
+    sizes = [1000, 4099, 7, 70001, 8, 0, 513]
+    xs = [(g.standard_normal(n) * (3.0 if t == 4 else 0.7)).astype(np.float32) for t, n in enumerate(sizes)]
+    xs[3][5] = np.nan
+    xs[3][6] = np.inf
+    streams = [11 * t + 3 for t in range(len(xs))]
+    dx = [dev(x) for x in xs]
+    outs, counters = ctx().quantize_batched(dx, fmts, streams, seed=9)
+    cnt = host(counters).view(np.uint64).reshape(-1, 2)
+    for t, (x, (wl, fl)) in enumerate(zip(xs, fmts)):
+        q, nnz, sat = orc.quantize(x, wl, fl, orc.SR, 9, streams[t])
+        assert outs[t].dtype == (torch.int8 if wl <= 8 else torch.int16 if wl <= 16 else torch.int32)
+        assert np.array_equal(host(outs[t]).astype(np.int64), q), t
+        assert cnt[t].tolist() == [nnz, sat], t
+    ranges = torch.empty(2 * len(xs), dtype=torch.float32, device="cuda")
+    outs, counters = ctx().quantize_batched(dx, fmts, streams, seed=9, ranges=ranges, range_of=[0, 1, 3, 6])
+    r = host(ranges).reshape(-1, 2)
+    for t, x in enumerate(xs):
+        fin = x[np.isfinite(x)]
+        want = (float(fin.min()), float(fin.max())) if t in (0, 1, 3, 6) and fin.size else (np.inf, -np.inf)
+        assert tuple(r[t].tolist()) == want, t
+        assert np.array_equal(host(outs[t]).astype(np.int64), orc.quantize(x, fmts[t][0], fmts[t][1], orc.SR, 9, streams[t])[0]), t
