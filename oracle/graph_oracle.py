@@ -32,6 +32,9 @@ codes.  The rules taken here (every tensor that crosses a layer is codes * 2^-FL
       with the fitting shift; if the exponents differ by more than 40 the contribution with the larger exponent
       (the far smaller values) is left out
 
+Word lengths 17..32: the same rules on Python integers wherever a sum or product can pass 64 bits (S2 and D2 reach
+85 bits, A y + B + shortcut more); an integer total enters the fp64 formulas as its nearest double (ties to even).
+
 Random streams of the new steps: stream0 + 2^20 + 8 l + slot, slot 0 = batch-norm output, 1 = batch-norm data
 gradient, 2 = average pooling, 3.. = the k-th contribution merged into the gradient of layer l's output.
 """
@@ -46,6 +49,7 @@ from . import conv_oracle as co
 from . import fxp_oracle as orc
 from . import net_oracle as no
 from . import sgd_oracle as so
+from . import wide_oracle as wo
 
 X_BN, X_BNB, X_GAP, X_MERGE = 0, 1, 2, 3
 
@@ -64,14 +68,30 @@ def _coef_exponent(vmax: float) -> int:
     return min(max(30 - e, 0), 30)
 
 
+def _big(*arrays) -> bool:
+    """True when some code needs more than 16 bits (or the chain oracle is told to use Python integers throughout)."""
+    return no.force_wide or any(a is not None and np.size(a) and int(np.abs(np.asarray(a, dtype=np.int64)).max()) >= (1 << 15)
+                                for a in arrays)
+
+
+def _ints(a, big: bool):
+    a = np.asarray(a, dtype=np.int64)
+    return a.astype(object) if big else a
+
+
+def _f64(v) -> np.ndarray:
+    """Integer totals (int64 or Python integers) as their nearest doubles."""
+    return np.array([float(int(x)) for x in np.asarray(v).ravel()], dtype=np.float64).reshape(np.shape(v))
+
+
 def bn_coeffs(y, fl_y: int, gamma, beta, eps: float, fl_o: int):
     """Per-channel statistics and fixed-point coefficients.  y: (..., K) codes."""
-    y2 = np.asarray(y, dtype=np.int64).reshape(-1, np.shape(y)[-1])
+    y2 = _ints(y, _big(y)).reshape(-1, np.shape(y)[-1])
     m = y2.shape[0]
     s1 = y2.sum(axis=0)
     s2 = (y2 * y2).sum(axis=0)
-    mean = s1.astype(np.float64) / np.float64(m)
-    ex2 = s2.astype(np.float64) / np.float64(m)
+    mean = _f64(s1) / np.float64(m)
+    ex2 = _f64(s2) / np.float64(m)
     var = np.maximum(ex2 - mean * mean, 0.0)
     sig = np.sqrt(var + math.ldexp(float(eps), 2 * fl_y))
     g64 = np.asarray(gamma, np.float32).astype(np.float64)
@@ -88,13 +108,14 @@ def bn_forward(y, fl_y: int, gamma, beta, eps: float, wl_o: int, fl_o: int, relu
                res=None, fl_res: int = 0, mode: int = orc.SR):
     """Returns (codes of the normalised output [+ shortcut], state)."""
     st = bn_coeffs(y, fl_y, gamma, beta, eps, fl_o)
-    yi = np.asarray(y, dtype=np.int64)
-    acc = yi * st["A"] + st["B"]                           # broadcast over the channel (last) axis
+    big = _big(y, res) or wl_o > 16
+    yi = _ints(y, big)
+    acc = yi * _ints(st["A"], big) + _ints(st["B"], big)   # broadcast over the channel (last) axis
     if res is not None:
         sh = fl_o + st["FA"] - fl_res
-        r = np.asarray(res, dtype=np.int64).reshape(yi.shape)
+        r = _ints(res, big).reshape(yi.shape)
         acc = acc + (r * (1 << sh) if sh >= 0 else r >> (-sh))
-    out = orc.requantize(acc, st["FA"], wl_o, mode, seed, stream, relu)
+    out = no._requantize(acc, st["FA"], wl_o, mode, seed, stream, relu)
     return out, st
 
 
@@ -104,11 +125,12 @@ def bn_backward(dz, y, st, wl_out: int, seed: int, stream: int, mode: int = orc.
     normalised values is dy * 2^-(e + e_add), e_add = FB - shift + FL_o - FL_y (alpha carries 2^FL_o where the chain
     rule has 2^FL_y); dgamma and dbeta are in units of 2^-e."""
     k = np.shape(y)[-1]
-    d2 = np.asarray(dz, dtype=np.int64).reshape(-1, k)
-    y2 = np.asarray(y, dtype=np.int64).reshape(-1, k)
+    big = _big(dz, y) or wl_out > 16
+    d2 = _ints(dz, big).reshape(-1, k)
+    y2 = _ints(y, big).reshape(-1, k)
     m = np.float64(y2.shape[0])
-    dd1 = d2.sum(axis=0).astype(np.float64)
-    dd2 = (d2 * y2).sum(axis=0).astype(np.float64)
+    dd1 = _f64(d2.sum(axis=0))
+    dd2 = _f64((d2 * y2).sum(axis=0))
     mean, sig, alpha = st["mean"], st["sig"], st["alpha"]
     dg = (dd2 - mean * dd1) / sig
     c1 = dd1 / m
@@ -120,8 +142,8 @@ def bn_backward(dz, y, st, wl_out: int, seed: int, stream: int, mode: int = orc.
     pc = np.clip(np.rint(np.ldexp(p, fb)), -float(1 << 30), float(1 << 30)).astype(np.int64)
     qc = np.clip(np.rint(np.ldexp(q, fb)), -float(1 << 30), float(1 << 30)).astype(np.int64)
     rc = np.clip(np.rint(np.ldexp(r, fb)), -float(1 << 61), float(1 << 61)).astype(np.int64)
-    acc = d2 * pc + y2 * qc + rc
-    codes, shift, _ = no.requantize_fit(acc, wl_out, mode, seed, stream)
+    acc = d2 * _ints(pc, big) + y2 * _ints(qc, big) + _ints(rc, big)
+    codes, shift, _ = no._requantize_fit(acc, wl_out, mode, seed, stream)
     return {"dy": codes.reshape(np.shape(y)), "shift": shift, "FB": fb, "e_add": fb - shift + st["fl_o"] - st["fl_y"],
             "dgamma": dg, "dbeta": dd1}
 
@@ -172,11 +194,12 @@ MERGE_MAX_GAP = 40
 
 def grad_add(a, e_a: int, b, e_b, wl: int, seed: int, stream: int, mode: int = orc.SR):
     """a * 2^-e_a [+ b * 2^-e_b] as wl-bit codes with the fitting shift.  Returns (codes, exponent, shift)."""
-    ai = np.asarray(a, dtype=np.int64)
+    big = _big(a, b) or wl > 16
+    ai = _ints(a, big)
     if b is None:
         acc, e = ai, e_a
     else:
-        bi = np.asarray(b, dtype=np.int64).reshape(ai.shape)
+        bi = _ints(b, big).reshape(ai.shape)
         if e_a - e_b > MERGE_MAX_GAP:
             acc, e = bi, e_b
         elif e_b - e_a > MERGE_MAX_GAP:
@@ -184,7 +207,7 @@ def grad_add(a, e_a: int, b, e_b, wl: int, seed: int, stream: int, mode: int = o
         else:
             e = max(e_a, e_b)
             acc = ai * (1 << (e - e_a)) + bi * (1 << (e - e_b))
-    codes, shift, _ = no.requantize_fit(acc, wl, mode, seed, stream)
+    codes, shift, _ = no._requantize_fit(acc, wl, mode, seed, stream)
     return codes, e - shift, shift
 
 
@@ -218,18 +241,18 @@ def forward(nodes, fmts, wq, bn_params, x, eps: float, seed: int, stream0: int):
     yc, ys, acts, states = [], [], [], []
     for l, (L, (wl, fl)) in enumerate(zip(nodes, fmts)):
         s = _src(l, L)
-        cur, fl_cur = (a_in, fl0) if s < 0 else (acts[s], fmts[s][1])
+        cur, fl_cur, wl_cur = (a_in, fl0, wl0) if s < 0 else (acts[s], fmts[s][1], fmts[s][0])
         cur = cur.reshape(n, L.h, L.w, L.c)
-        z = co.conv_fwd(cur, wq[l], L.stride, L.pad)
+        z = no._conv_fwd(cur, wl_cur, wq[l], wl, L.stride, L.pad)
         if L.bn:
-            c = orc.requantize(z, fl_cur, wl, orc.SR, seed, no.stream_of(stream0, l, no.SLOT_FWD), False)
+            c = no._requantize(z, fl_cur, wl, orc.SR, seed, no.stream_of(stream0, l, no.SLOT_FWD), False)
             res, fl_res = (acts[L.res], fmts[L.res][1]) if L.res >= 0 else (None, 0)
             y, st = bn_forward(c, fl, bn_params[l][0], bn_params[l][1], eps, wl, fl, L.relu, seed, stream_x(stream0, l, X_BN),
                                res, fl_res)
         else:
             assert L.res < 0
             c, st = None, None
-            y = orc.requantize(z, fl_cur, wl, orc.SR, seed, no.stream_of(stream0, l, no.SLOT_FWD), L.relu)
+            y = no._requantize(z, fl_cur, wl, orc.SR, seed, no.stream_of(stream0, l, no.SLOT_FWD), L.relu)
         yc.append(c)
         ys.append(y)
         states.append(st)
@@ -282,14 +305,14 @@ def backward(nodes, fmts, wq, fwd, dlogits, dlogits_fl: int, seed: int, stream0:
         else:
             dyc[l] = dz
         s = _src(l, L)
-        a_prev, fl_in = (fwd["a_in"], fmts[0][1]) if s < 0 else (fwd["a"][s], fmts[s][1])
+        a_prev, fl_in, wl_in = (fwd["a_in"], fmts[0][1], fmts[0][0]) if s < 0 else (fwd["a"][s], fmts[s][1], fmts[s][0])
         a_prev = a_prev.reshape(n, L.h, L.w, L.c)
-        acc_w = co.conv_wgrad(dyc[l], a_prev, L.r, L.s, L.stride, L.pad)
-        g[l], sh_w, sumsq[l] = no.requantize_fit(acc_w, wl, orc.SR, seed, no.stream_of(stream0, l, no.SLOT_DW))
+        acc_w = no._conv_wgrad(dyc[l], wl, a_prev, wl_in, L.r, L.s, L.stride, L.pad)
+        g[l], sh_w, sumsq[l] = no._requantize_fit(acc_w, wl, orc.SR, seed, no.stream_of(stream0, l, no.SLOT_DW))
         e_g[l] = e + fl_in - sh_w
         if s >= 0:
-            acc_a = co.conv_dgrad(dyc[l], wq[l], L.h, L.w, L.stride, L.pad)
-            q, sh_a, _ = no.requantize_fit(acc_a, fmts[s][0], orc.SR, seed, no.stream_of(stream0, l, no.SLOT_DA))
+            acc_a = no._conv_dgrad(dyc[l], wl, wq[l], wl, L.h, L.w, L.stride, L.pad)
+            q, sh_a, _ = no._requantize_fit(acc_a, fmts[s][0], orc.SR, seed, no.stream_of(stream0, l, no.SLOT_DA))
             contribute(s, q, e + fl - sh_a)
     return {"g": g, "sumsq": sumsq, "e_g": e_g, "dgamma": dgam, "dbeta": dbet, "da": da, "e_da": e_da, "dyc": dyc}
 

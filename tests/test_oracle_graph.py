@@ -228,3 +228,89 @@ def test_plain_chain_through_the_graph_oracle_is_the_chain_oracle():
     b1, b2 = no.backward(layers, fmts, wq, f1, dl, 2, 0), go.backward(nodes, fmts, wq, f2, dl, 5, 2, 0)
     assert all(np.array_equal(a, b) for a, b in zip(b1["g"], b2["g"]))
     assert b2["e_g"] == no.gradient_exponents(fmts, b1, 5)
+
+
+# ---- word lengths above 16 bits -------------------------------------------------------------------------------
+
+def _wide_bn_case(seed, shape=(3, 4, 4, 8), wl=28):
+    g = np.random.default_rng(seed)
+    lim = 1 << (wl - 1)
+    y = np.clip(np.rint(g.standard_normal(shape) * (lim / 6) + g.standard_normal(shape[-1]) * (lim / 8)), -lim, lim - 1).astype(np.int64)
+    gamma = (1.0 + 0.3 * g.standard_normal(shape[-1])).astype(np.float32)
+    beta = (0.2 * g.standard_normal(shape[-1])).astype(np.float32)
+    return g, y, gamma, beta
+
+
+def test_python_integer_path_of_batch_norm_and_merging_equals_the_int64_path():
+    g, y, gamma, beta = _bn_case(21)
+    res = g.integers(-300, 300, y.shape)
+    dz = g.integers(-(1 << 11), 1 << 11, y.shape)
+    outs = []
+    for flag in (False, True):
+        no.force_wide = flag
+        try:
+            out, st = go.bn_forward(y, 8, gamma, beta, 1e-5, 12, 7, True, 5, 6, res=res, fl_res=5)
+            r = go.bn_backward(dz, y, st, 12, 7, 8)
+            m, e, sh = go.grad_add(dz, 9, res, 3, 10, 1, 2)
+            p = go.gap_forward(y[:, :4, :4, :], 12, 3, 4)
+        finally:
+            no.force_wide = False
+        outs.append((out, st, r, m, e, sh, p))
+    a, b = outs
+    assert np.array_equal(a[0], b[0]) and a[1]["FA"] == b[1]["FA"] and np.array_equal(a[1]["A"], b[1]["A"]) and np.array_equal(a[1]["B"], b[1]["B"])
+    assert np.array_equal(a[1]["mean"], b[1]["mean"]) and np.array_equal(a[1]["sig"], b[1]["sig"])
+    assert np.array_equal(a[2]["dy"], b[2]["dy"]) and a[2]["shift"] == b[2]["shift"] and np.array_equal(a[2]["dgamma"], b[2]["dgamma"])
+    assert np.array_equal(a[3], b[3]) and a[4:6] == b[4:6] and np.array_equal(a[6], b[6])
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_batch_norm_on_twenty_eight_bit_codes_is_the_library_routine(seed):
+    g, y, gamma, beta = _wide_bn_case(30 + seed)
+    fl_y, wl_o, fl_o, eps = 24, 32, 27, 1e-5
+    out, st = go.bn_forward(y, fl_y, gamma, beta, eps, wl_o, fl_o, False, 1, 2, mode=orc.RN_HALF_UP)
+    yt = torch.tensor(y.astype(np.float64) / 2.0 ** fl_y).permute(0, 3, 1, 2)
+    want = F.batch_norm(yt, None, None, torch.tensor(gamma.astype(np.float64)), torch.tensor(beta.astype(np.float64)), True, 0.0, eps)
+    want = want.permute(0, 2, 3, 1).numpy()
+    # half a step of the 27-bit output grid plus the 2^-30 relative error of the coefficients (values up to about 4)
+    assert np.max(np.abs(out / 2.0 ** fl_o - want)) <= 0.5 / 2.0 ** fl_o + 4.0 * 2.0 ** -29
+    res = g.integers(-(1 << 23), 1 << 23, y.shape)
+    out_r, _ = go.bn_forward(y, fl_y, gamma, beta, eps, wl_o, fl_o, True, 1, 2, res=res, fl_res=20, mode=orc.RN_HALF_UP)
+    want_r = np.maximum(want + res / 2.0 ** 20, 0.0)
+    assert np.max(np.abs(out_r / 2.0 ** fl_o - want_r)) <= 0.5 / 2.0 ** fl_o + 4.0 * 2.0 ** -29
+    flat = (y.astype(np.float64) / 2.0 ** fl_y).reshape(-1, y.shape[-1])
+    assert np.allclose(st["mean"] / 2.0 ** fl_y, flat.mean(axis=0), rtol=1e-12, atol=1e-12)
+    assert np.allclose((st["sig"] / 2.0 ** fl_y) ** 2, flat.var(axis=0) + eps, rtol=1e-10)
+    # the integer totals are exact although the squares pass 64 bits
+    assert [int(v) for v in st["s2"]] == [sum(int(v) ** 2 for v in y.reshape(-1, y.shape[-1])[:, k]) for k in range(y.shape[-1])]
+    assert max(int(v) for v in st["s2"]) > 1 << 55
+
+    # backward against automatic differentiation, 32-bit gradient codes
+    e_dz = 30
+    dz = g.integers(-(1 << 30), 1 << 30, y.shape)
+    r = go.bn_backward(dz, y, st, 32, 3, 4)
+    yt = torch.tensor(y.astype(np.float64) / 2.0 ** fl_y, requires_grad=True)
+    gt = torch.tensor(gamma.astype(np.float64), requires_grad=True)
+    bt = torch.tensor(beta.astype(np.float64), requires_grad=True)
+    z = F.batch_norm(yt.permute(0, 3, 1, 2), None, None, gt, bt, True, 0.0, eps).permute(0, 2, 3, 1)
+    (z * torch.tensor(dz.astype(np.float64) / 2.0 ** e_dz)).sum().backward()
+    want = yt.grad.numpy()
+    got = r["dy"].astype(np.float64) * 2.0 ** -(e_dz + r["e_add"])
+    assert np.max(np.abs(got - want)) <= np.max(np.abs(want)) * 2.0 ** -27      # 30-bit coefficients bound the accuracy
+    assert int(np.abs(r["dy"]).max()) >= 1 << 30
+    assert np.allclose(r["dgamma"] * 2.0 ** -e_dz, gt.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert np.allclose(r["dbeta"] * 2.0 ** -e_dz, bt.grad.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_sum_of_two_wide_gradient_tensors_against_exact_rationals():
+    g = np.random.default_rng(40)
+    a = g.integers(-(1 << 31), 1 << 31, 50)
+    b = g.integers(-(1 << 23), 1 << 23, 50)
+    for e_a, e_b in ((10, 50), (50, 10), (7, 7), (0, 40)):
+        codes, e, sh = go.grad_add(a, e_a, b, e_b, 32, 1, 2, mode=orc.RN_HALF_UP)
+        exact = [Fraction(int(x), 1 << e_a) + Fraction(int(y), 1 << e_b) for x, y in zip(a, b)]
+        step = Fraction(1, 1 << e) if e >= 0 else Fraction(1 << -e)
+        assert all(abs(Fraction(int(c)) * step - v) <= step / 2 for c, v in zip(codes, exact))
+        assert int(np.abs(codes).max()) >= 1 << 30 or sh == 0
+    # beyond the gap of 40 the far smaller tensor is left out
+    codes, e, sh = go.grad_add(a, 0, b, 41, 32, 1, 2, mode=orc.RN_HALF_UP)
+    assert np.array_equal(codes, np.asarray(a)) and e == 0 and sh == 0
