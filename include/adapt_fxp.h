@@ -426,7 +426,10 @@ int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *
  * The paper trains residual networks with batch normalisation (Sec. 4.1) and does not say how these
  * steps are carried out on codes; the rules below are this library's.  Tensors are NHWC, so the
  * `channels` codes of one position are contiguous ("a row"); channels % 8 == 0, channels <= 4096,
- * rows <= 2^23.
+ * rows <= 2^23.  Word lengths go up to 32 in all of these calls (int32_t codes above 16 bits): a call
+ * with such a tensor runs the same rules in 128-bit integers (S2 and D2 reach 85 bits, and enter the
+ * fp64 formulas as their nearest doubles), one element per thread; it is exact and far from the speed
+ * of the calls on int8 / int16 codes.
  *
  * adapt_bn_forward (training mode: statistics of the batch).  Per channel k over the `rows` codes of
  * y (format fy): S1 = sum y, S2 = sum y^2 (exact); in fp64, one rounded operation at a time:
@@ -563,7 +566,7 @@ size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int count, int 
 int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
                      float *const *weights, const adapt_switch_params *sp, void *workspace,
                      size_t workspace_bytes, adapt_net **net);
-/* The same chain laid out for word lengths up to wl_max (16 or 32; for callers that cannot tell in advance how far
+/* The same chain or graph laid out for word lengths up to wl_max (16 or 32; for callers that cannot tell in advance how far
  * PushUp will go, Sec. 3.3 caps it at 32): with 32 every code buffer holds int32_t storage and the accumulator
  * buffers 128-bit integers, adapt_net_set_format and the switch parameters' wl_hi may go up to 32, PushUp's cap is
  * 32, tensors of layers above 16 bits are int32_t (adapt_net_tensor reports 4-byte elements), the loss gradient
@@ -572,6 +575,11 @@ int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
  * adapt_gradient_diversity's rule for such windows (bound 2^48).  Contractions with an operand above 16 bits are
  * composed of 11-bit parts (see adapt_acc_bits): correct, and many times slower than the native ones. */
 size_t adapt_net_workspace_bytes_wide(const adapt_layer_desc *layers, int count, int lb_upr, int wl_max);
+size_t adapt_graph_workspace_bytes_wide(const adapt_node_desc *nodes, int count, int lb_upr, int wl_max);
+int adapt_graph_create_wide(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights,
+                            float *const *gammas, float *const *betas, double bn_eps,
+                            const adapt_switch_params *sp, int wl_max, void *workspace,
+                            size_t workspace_bytes, adapt_net **out);
 int adapt_net_create_wide(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
                           float *const *weights, const adapt_switch_params *sp, int wl_max,
                           void *workspace, size_t workspace_bytes, adapt_net **out);

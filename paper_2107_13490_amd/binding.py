@@ -196,6 +196,10 @@ def load_library():
     lib.adapt_net_workspace_bytes_wide.argtypes = [C.POINTER(LayerDesc), i, i, i]
     lib.adapt_net_workspace_bytes_wide.restype = sz
     lib.adapt_net_create_wide.argtypes = [vp, C.POINTER(LayerDesc), i, C.POINTER(vp), C.POINTER(SwitchParams), i, vp, sz, C.POINTER(vp)]
+    lib.adapt_graph_workspace_bytes_wide.argtypes = [C.POINTER(NodeDesc), i, i, i]
+    lib.adapt_graph_workspace_bytes_wide.restype = sz
+    lib.adapt_graph_create_wide.argtypes = [vp, C.POINTER(NodeDesc), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), dbl,
+                                            C.POINTER(SwitchParams), i, vp, sz, C.POINTER(vp)]
     lib.adapt_graph_workspace_bytes.argtypes = [C.POINTER(NodeDesc), i, i]
     lib.adapt_graph_workspace_bytes.restype = sz
     lib.adapt_graph_create.argtypes = [vp, C.POINTER(NodeDesc), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), dbl,
@@ -694,11 +698,10 @@ class Net:
         n = len(self.layers)
         graph = any(isinstance(d, NodeDesc) for d in self.layers)
         lb_upr = switch.lb_upr if switch is not None else 0
-        if graph and wl_max != 16:
-            raise ValueError("graphs with batch normalisation keep word lengths of at most 16")
         if graph:
             descs = (NodeDesc * n)(*self.layers)
-            need = self._lib.adapt_graph_workspace_bytes(descs, n, lb_upr)
+            need = (self._lib.adapt_graph_workspace_bytes(descs, n, lb_upr) if wl_max == 16 else
+                    self._lib.adapt_graph_workspace_bytes_wide(descs, n, lb_upr, wl_max))
         elif wl_max != 16:
             descs = (LayerDesc * n)(*self.layers)
             need = self._lib.adapt_net_workspace_bytes_wide(descs, n, lb_upr, wl_max)
@@ -714,8 +717,12 @@ class Net:
         if graph:
             gp = (C.c_void_p * n)(*[(p[0].data_ptr() if p is not None else None) for p in (self.bn or [None] * n)])
             bp = (C.c_void_p * n)(*[(p[1].data_ptr() if p is not None else None) for p in (self.bn or [None] * n)])
-            _check(self._lib.adapt_graph_create(ctx.handle, descs, n, wptrs, gp, bp, float(bn_eps), sw, _ptr(self.workspace), need,
-                                                C.byref(h)), "adapt_graph_create")
+            if wl_max == 16:
+                _check(self._lib.adapt_graph_create(ctx.handle, descs, n, wptrs, gp, bp, float(bn_eps), sw, _ptr(self.workspace), need,
+                                                    C.byref(h)), "adapt_graph_create")
+            else:
+                _check(self._lib.adapt_graph_create_wide(ctx.handle, descs, n, wptrs, gp, bp, float(bn_eps), sw, wl_max,
+                                                         _ptr(self.workspace), need, C.byref(h)), "adapt_graph_create_wide")
         elif wl_max != 16:
             _check(self._lib.adapt_net_create_wide(ctx.handle, descs, n, wptrs, sw, wl_max, _ptr(self.workspace), need, C.byref(h)),
                    "adapt_net_create_wide")

@@ -28,6 +28,7 @@
 #include "common.hpp"
 #include "context.hpp"
 #include "fit.hpp"
+#include "wide.hpp"
 
 // every fp64 operation of the coefficient kernels is rounded on its own: no fused multiply-adds
 #pragma clang fp contract(off)
@@ -173,16 +174,17 @@ bn_total_kernel(const long long *__restrict__ partial, int nparts, int width, lo
 // One block: totals of the block partials, statistics and forward coefficients.
 __global__ void __launch_bounds__(1024)
 bn_coef_fwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int channels, unsigned long long rows, int fl_y, int fl_o,
-                   const float *__restrict__ gamma, const float *__restrict__ beta, double eps, void *state)
+                   const float *__restrict__ gamma, const float *__restrict__ beta, double eps, void *state,
+                   const double *__restrict__ s2d = nullptr /* sums of squares beyond 64 bits, as their nearest doubles */)
 {
     __shared__ double sm[16];
     const BnState st = bn_state(state, channels);
     const double m = (double)rows;
     double amax = 0.0;
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
-        const long long s1 = tot[k], s2 = tot[channels + k];
+        const long long s1 = tot[k];
         const double mean = (double)s1 / m;
-        const double ex2 = (double)s2 / m;
+        const double ex2 = (s2d ? s2d[k] : (double)tot[channels + k]) / m;
         const double var = fmax(ex2 - mean * mean, 0.0);
         const double sig = sqrt(var + ldexp(eps, 2 * fl_y));
         const double alpha = ldexp((double)gamma[k], fl_o) / sig;
@@ -207,16 +209,17 @@ bn_coef_fwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int c
 // One block: totals of (sum dz, sum dz*y), the parameter gradients and the backward coefficients.
 __global__ void __launch_bounds__(1024)
 bn_coef_bwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int channels, void *state, double *__restrict__ dgamma,
-                   double *__restrict__ dbeta)
+                   double *__restrict__ dbeta, const double *__restrict__ d2d = nullptr /* sums of products beyond 64 bits */)
 {
     __shared__ double sm[16];
     const BnState st = bn_state(state, channels);
     const double m = (double)st.h->rows;
     double pmax = 0.0;
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
-        const long long d1 = tot[k], d2 = tot[channels + k];
+        const long long d1 = tot[k];
+        const double d2 = d2d ? d2d[k] : (double)tot[channels + k];
         const double mean = st.mean[k], sig = st.sig[k], alpha = st.alpha[k];
-        const double dg = ((double)d2 - mean * (double)d1) / sig;
+        const double dg = (d2 - mean * (double)d1) / sig;
         const double c1 = (((double)d1) / (m));
         const double c2 = dg / (m * sig);
         const double q = -((alpha) * (c2));
@@ -364,6 +367,160 @@ __global__ void __launch_bounds__(kBnThreads) bn_bwd_kernel(const BnBwdArgs a)
     if (!FIT) {
         mx = block_max_u64(mx, sm, kBnThreads / kWave);
         if (threadIdx.x == 0) a.part[blockIdx.x] = mx;
+    }
+}
+
+
+// ---- word lengths 17..32 (int32 codes) ------------------------------------------------------------------------
+// The same rules with wider integers: sums of squares and of products reach 85 bits and are kept in 128, their
+// totals enter the fp64 formulas as their nearest doubles; A y + B + shortcut and P dz + Q y + R are formed in 128
+// bits.  One element per thread and iteration, storage width chosen at run time: these paths are for correctness
+// (a layer that PushUp took above 16 bits), not for speed.
+__device__ __forceinline__ long long code_at(const void *p, int es, uint64_t i)
+{
+    return es == 1 ? (long long)static_cast<const int8_t *>(p)[i] : es == 2 ? (long long)static_cast<const int16_t *>(p)[i]
+                                                                            : (long long)static_cast<const int32_t *>(p)[i];
+}
+__device__ __forceinline__ void code_put(void *p, int es, uint64_t i, int v)
+{
+    if (es == 1) static_cast<int8_t *>(p)[i] = (int8_t)v;
+    else if (es == 2) static_cast<int16_t *>(p)[i] = (int16_t)v;
+    else static_cast<int32_t *>(p)[i] = v;
+}
+// nearest double of a signed 128-bit integer given as two words
+__device__ __forceinline__ double i128_to_double(unsigned long long lo, unsigned long long hi)
+{
+    if (!(hi >> 63)) return u128_to_double(lo, hi);
+    const u128 m = (u128)0 - (((u128)hi << 64) | lo);
+    return -u128_to_double((unsigned long long)m, (unsigned long long)(m >> 64));
+}
+
+// partial[block][channel][4]: first sum, unused, second sum (low word, high word).  A block takes a run of rows.
+__global__ void __launch_bounds__(kBnThreads)
+bn_sums_wide_kernel(const void *__restrict__ a, int es_a, const void *__restrict__ b, int es_b, int mode, uint64_t rows, int channels,
+                    unsigned long long *__restrict__ partial)
+{
+    const uint64_t per = (rows + gridDim.x - 1) / gridDim.x;
+    const uint64_t r0 = (uint64_t)blockIdx.x * per, r1 = r0 + per < rows ? r0 + per : rows;
+    for (int c = threadIdx.x; c < channels; c += kBnThreads) {
+        long long s1 = 0;
+        i128 s2 = 0;
+        for (uint64_t r = r0; r < r1; ++r) {
+            const long long x = code_at(a, es_a, r * channels + c);
+            const long long y = mode == 1 ? code_at(b, es_b, r * channels + c) : x;
+            s1 += x;
+            s2 += (i128)(x * y);
+        }
+        unsigned long long *dst = partial + ((size_t)blockIdx.x * channels + c) * 4;
+        dst[0] = (unsigned long long)s1;
+        dst[1] = 0;
+        dst[2] = (unsigned long long)s2;
+        dst[3] = (unsigned long long)((u128)s2 >> 64);
+    }
+}
+
+// totals over the blocks: tot[c] = first sum (64 bits suffice), second[c] = nearest double of the second sum
+__global__ void __launch_bounds__(64)
+bn_total_wide_kernel(const unsigned long long *__restrict__ partial, int nparts, int channels, long long *__restrict__ tot,
+                     double *__restrict__ second)
+{
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    if (c >= channels) return;
+    long long s1 = 0;
+    i128 s2 = 0;
+    for (int p = 0; p < nparts; ++p) {
+        const unsigned long long *src = partial + ((size_t)p * channels + c) * 4;
+        s1 += (long long)src[0];
+        s2 += (i128)(((u128)src[3] << 64) | src[2]);
+    }
+    tot[c] = s1;
+    second[c] = i128_to_double((unsigned long long)s2, (unsigned long long)((u128)s2 >> 64));
+}
+
+struct BnWideArgs {
+    const void *x, *y;            // forward: y codes, shortcut or null; backward: dz codes, y codes
+    void *out;
+    const void *state;
+    uint64_t n;
+    int es_x, es_y, es_o, channels, wl, relu, mode, fl_res;
+    uint64_t seed, stream;
+    uint64_t *part;
+    int nparts;
+    int32_t *shift_out;
+    const long long *e_in;
+    long long *e_out;
+};
+
+__global__ void __launch_bounds__(kBnThreads) bn_apply_wide_kernel(const BnWideArgs a)
+{
+    const BnState st = bn_state(const_cast<void *>(a.state), a.channels);
+    const int fa = st.h->fa;
+    const int rsh = st.h->fl_o + fa - a.fl_res;
+    for (uint64_t i = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x; i < a.n; i += (uint64_t)gridDim.x * kBnThreads) {
+        const int c = (int)(i % (uint64_t)a.channels);
+        i128 acc = (i128)st.A[c] * (i128)code_at(a.x, a.es_x, i) + (i128)st.B[c];
+        if (a.y) {
+            const long long s = code_at(a.y, a.es_y, i);
+            acc += rsh >= 0 ? (i128)((u128)(i128)s << rsh) : (i128)(s >> (-rsh > 63 ? 63 : -rsh));
+        }
+        code_put(a.out, a.es_o, i, requantize_wide_one(acc, fa, a.wl, a.relu, rounding_bits_of(a.seed, a.stream, i, a.mode)));
+    }
+}
+
+// PASS 0: the largest bit length of acc = P dz + Q y + R per block; PASS 1: the fitted codes
+template <int PASS>
+__global__ void __launch_bounds__(kBnThreads) bn_bwd_wide_kernel(const BnWideArgs a)
+{
+    __shared__ uint64_t sm[kBnThreads / kWave];
+    const BnState st = bn_state(const_cast<void *>(a.state), a.channels);
+    int shift = 0;
+    if (PASS == 1) {
+        uint64_t m = 0;
+        for (int i = threadIdx.x; i < a.nparts; i += kBnThreads) m = a.part[i] > m ? a.part[i] : m;
+        m = block_max_u64(m, sm, kBnThreads / kWave);
+        shift = max(0, (int)m - (a.wl - 1));
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            if (a.shift_out) *a.shift_out = shift;
+            if (a.e_out) *a.e_out = (a.e_in ? *a.e_in : 0) + st.h->fb - shift + st.h->fl_o - st.h->fl_y;
+        }
+    }
+    uint64_t mx = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x; i < a.n; i += (uint64_t)gridDim.x * kBnThreads) {
+        const int c = (int)(i % (uint64_t)a.channels);
+        const i128 acc = (i128)st.P[c] * (i128)code_at(a.x, a.es_x, i) + (i128)st.Q[c] * (i128)code_at(a.y, a.es_y, i) + (i128)st.R[c];
+        if (PASS == 0) {
+            const uint64_t bl = (uint64_t)bit_length_128(acc);
+            mx = bl > mx ? bl : mx;
+        } else {
+            code_put(a.out, a.es_o, i, requantize_wide_one(acc, shift, a.wl, 0, rounding_bits_of(a.seed, a.stream, i, a.mode)));
+        }
+    }
+    if (PASS == 0) {
+        mx = block_max_u64(mx, sm, kBnThreads / kWave);
+        if (threadIdx.x == 0) a.part[blockIdx.x] = mx;
+    }
+}
+
+// global average pooling of codes of any width: one thread per (sample, channel)
+__global__ void __launch_bounds__(kBnThreads)
+gap_fwd_wide_kernel(const void *__restrict__ a, int es, void *__restrict__ out, uint32_t n, uint32_t hw, uint32_t c, int sh, int wl, int mode,
+                    uint64_t seed, uint64_t stream)
+{
+    const uint64_t total = (uint64_t)n * c;
+    for (uint64_t i = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x; i < total; i += (uint64_t)gridDim.x * kBnThreads) {
+        const uint64_t s = i / c, ch = i - s * c;
+        i128 acc = 0;
+        for (uint32_t p = 0; p < hw; ++p) acc += (i128)code_at(a, es, (s * hw + p) * c + ch);
+        code_put(out, es, i, requantize_wide_one(acc, sh, wl, 0, rounding_bits_of(seed, stream, i, mode)));
+    }
+}
+
+__global__ void __launch_bounds__(kBnThreads)
+gap_bwd_wide_kernel(const int32_t *__restrict__ dout, int32_t *__restrict__ da, uint64_t total, uint32_t hw, uint32_t c)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x; i < total; i += (uint64_t)gridDim.x * kBnThreads) {
+        const uint64_t pos = i / c;
+        da[i] = dout[(pos / hw) * c + (i - pos * c)];
     }
 }
 
@@ -544,6 +701,44 @@ __global__ void __launch_bounds__(kBnThreads) merge_kernel(const MergeArgs a)
     }
 }
 
+
+// the merge for tensors above 16 bits: the aligned sum in 128 bits (a gap of 40 on 32-bit codes passes 64)
+template <int PASS>
+__global__ void __launch_bounds__(kBnThreads) merge_wide_kernel(const MergeArgs a, int es_a, int es_b, int es_o)
+{
+    __shared__ uint64_t sm[kBnThreads / kWave];
+    int sa, sb;
+    long long e;
+    merge_plan(a, sa, sb, e);
+    int shift = 0;
+    if (PASS == 1) {
+        uint64_t m = 0;
+        for (int i = threadIdx.x; i < a.nparts; i += kBnThreads) m = a.part[i] > m ? a.part[i] : m;
+        m = block_max_u64(m, sm, kBnThreads / kWave);
+        shift = max(0, (int)m - (a.wl - 1));
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            if (a.shift_out) *a.shift_out = shift;
+            if (a.e_out) *a.e_out = e - shift;
+        }
+    }
+    uint64_t mx = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * kBnThreads + threadIdx.x; i < a.n; i += (uint64_t)gridDim.x * kBnThreads) {
+        i128 s = 0;
+        if (sa >= 0) s += (i128)((u128)(i128)code_at(a.a, es_a, i) << sa);
+        if (sb >= 0 && a.b) s += (i128)((u128)(i128)code_at(a.b, es_b, i) << sb);
+        if (PASS == 0) {
+            const uint64_t bl = (uint64_t)bit_length_128(s);
+            mx = bl > mx ? bl : mx;
+        } else {
+            code_put(a.out, es_o, i, requantize_wide_one(s, shift, a.wl, 0, rounding_bits_of(a.seed, a.stream, i, a.mode)));
+        }
+    }
+    if (PASS == 0) {
+        mx = block_max_u64(mx, sm, kBnThreads / kWave);
+        if (threadIdx.x == 0) a.part[blockIdx.x] = mx;
+    }
+}
+
 static int bn_grid(const adapt_ctx *ctx, uint64_t groups)
 {
     const uint64_t blocks = (groups + kBnThreads - 1) / kBnThreads;
@@ -601,7 +796,7 @@ extern "C" int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, siz
                                 const float *beta, double eps, const void *res, adapt_fmt fres, adapt_fmt fo, adapt_rng rng, int relu,
                                 void *out, void *state)
 {
-    if (!ctx || !fmt_ok(fy) || !fmt_ok(fo) || !rng_ok(rng) || !(eps >= 0.0) || (res && !fmt_ok(fres))) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(fy) || !fmt_ok_wide(fo) || !rng_ok(rng) || !(eps >= 0.0) || (res && !fmt_ok_wide(fres))) return ADAPT_EINVAL;
     if (channels < 8 || channels > kBnMaxChannels || (channels & 7)) return ADAPT_EUNSUPPORTED;
     if (rows < 1 || rows > ((size_t)1 << 23)) return ADAPT_EUNSUPPORTED;         // sums of squares stay below 2^53
     if (!y || !out || !state || !gamma || !beta || !aligned16(y) || !aligned16(out) || ((uintptr_t)state & 63) || (res && !aligned16(res)))
@@ -609,6 +804,23 @@ extern "C" int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, siz
     const uint64_t groups = (uint64_t)rows * channels / 8;
     if (ws_need_bn(ctx->num_cu, channels) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     long long *partial = reinterpret_cast<long long *>(scratch(ctx));
+    if (fy.wl > 16 || fo.wl > 16 || (res && fres.wl > 16)) {      // int32 codes somewhere: the 128-bit kernels
+        const int gridw = (int)std::min<uint64_t>(rows, (uint64_t)ctx->num_cu);
+        long long *tot = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
+        double *second = reinterpret_cast<double *>(tot + channels);
+        hipLaunchKernelGGL(bn_sums_wide_kernel, dim3(gridw), dim3(kBnThreads), 0, ctx->stream, y, storage_bytes(fy), y, storage_bytes(fy), 0,
+                           (uint64_t)rows, channels, reinterpret_cast<unsigned long long *>(partial));
+        hipLaunchKernelGGL(bn_total_wide_kernel, dim3((channels + 63) / 64), dim3(64), 0, ctx->stream,
+                           reinterpret_cast<const unsigned long long *>(partial), gridw, channels, tot, second);
+        hipLaunchKernelGGL(bn_coef_fwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, tot, channels, (unsigned long long)rows, fy.fl, fo.fl,
+                           gamma, beta, eps, state, second);
+        BnWideArgs w = {};
+        w.x = y; w.y = res; w.out = out; w.state = state; w.n = (uint64_t)rows * channels; w.es_x = storage_bytes(fy);
+        w.es_y = res ? storage_bytes(fres) : 1; w.es_o = storage_bytes(fo); w.channels = channels; w.wl = fo.wl; w.relu = relu != 0;
+        w.mode = rng.mode; w.fl_res = res ? fres.fl : 0; w.seed = rng.seed; w.stream = rng.stream;
+        hipLaunchKernelGGL(bn_apply_wide_kernel, dim3(bn_grid(ctx, w.n)), dim3(kBnThreads), 0, ctx->stream, w);
+        return hip_status(ctx, hipGetLastError());
+    }
     int grid;
     launch_sums<0>(ctx, y, storage_bytes(fy), y, storage_bytes(fy), groups, channels, partial, grid);
     long long *totals = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
@@ -640,7 +852,7 @@ extern "C" int adapt_bn_backward(adapt_ctx *ctx, const void *dz, int wl_dz, cons
                                  void *state, int wl_out, adapt_rng rng, void *dy, double *dgamma, double *dbeta, int32_t *shift,
                                  const int64_t *e_in, int64_t *e_out)
 {
-    if (!ctx || !fmt_ok(fy) || wl_dz < 2 || wl_dz > 16 || wl_out < 2 || wl_out > 16 || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(fy) || wl_dz < 2 || wl_dz > 32 || wl_out < 2 || wl_out > 32 || !rng_ok(rng)) return ADAPT_EINVAL;
     if (channels < 8 || channels > kBnMaxChannels || (channels & 7)) return ADAPT_EUNSUPPORTED;
     if (rows < 1 || rows > ((size_t)1 << 23)) return ADAPT_EUNSUPPORTED;
     if (!dz || !y || !dy || !state || !dgamma || !dbeta || !aligned16(dz) || !aligned16(y) || !aligned16(dy) || ((uintptr_t)state & 63))
@@ -650,7 +862,27 @@ extern "C" int adapt_bn_backward(adapt_ctx *ctx, const void *dz, int wl_dz, cons
     const uint64_t groups = (uint64_t)rows * channels / 8;
     if (ws_need_bn(ctx->num_cu, channels) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     long long *partial = reinterpret_cast<long long *>(scratch(ctx));
-    const int es_d = wl_dz <= 8 ? 1 : 2, es_y = storage_bytes(fy), es_o = wl_out <= 8 ? 1 : 2;
+    const int es_d = storage_bytes(adapt_fmt{wl_dz, 0}), es_y = storage_bytes(fy), es_o = storage_bytes(adapt_fmt{wl_out, 0});
+    if (es_d == 4 || es_y == 4 || es_o == 4) {                     // int32 codes somewhere: the 128-bit kernels
+        const int gridw = (int)std::min<uint64_t>(rows, (uint64_t)ctx->num_cu);
+        long long *tot = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
+        double *second = reinterpret_cast<double *>(tot + channels);
+        hipLaunchKernelGGL(bn_sums_wide_kernel, dim3(gridw), dim3(kBnThreads), 0, ctx->stream, dz, es_d, y, es_y, 1, (uint64_t)rows, channels,
+                           reinterpret_cast<unsigned long long *>(partial));
+        hipLaunchKernelGGL(bn_total_wide_kernel, dim3((channels + 63) / 64), dim3(64), 0, ctx->stream,
+                           reinterpret_cast<const unsigned long long *>(partial), gridw, channels, tot, second);
+        hipLaunchKernelGGL(bn_coef_bwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, tot, channels, state, dgamma, dbeta, second);
+        BnWideArgs w = {};
+        w.x = dz; w.y = y; w.out = dy; w.state = state; w.n = (uint64_t)rows * channels; w.es_x = es_d; w.es_y = es_y; w.es_o = es_o;
+        w.channels = channels; w.wl = wl_out; w.mode = rng.mode; w.seed = rng.seed; w.stream = rng.stream; w.shift_out = shift;
+        w.e_in = reinterpret_cast<const long long *>(e_in); w.e_out = reinterpret_cast<long long *>(e_out);
+        const int gridp = (int)std::min<uint64_t>(std::max<uint64_t>((w.n + kBnThreads - 1) / kBnThreads, 1), (uint64_t)ctx->num_cu * 4);
+        w.part = reinterpret_cast<uint64_t *>(scratch(ctx) + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels * 8 + (size_t)2 * channels * 8);
+        w.nparts = gridp;
+        hipLaunchKernelGGL(bn_bwd_wide_kernel<0>, dim3(gridp), dim3(kBnThreads), 0, ctx->stream, w);
+        hipLaunchKernelGGL(bn_bwd_wide_kernel<1>, dim3(bn_grid(ctx, w.n)), dim3(kBnThreads), 0, ctx->stream, w);
+        return hip_status(ctx, hipGetLastError());
+    }
     int grid;
     launch_sums<1>(ctx, dz, es_d, y, es_y, groups, channels, partial, grid);
     long long *totals = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
@@ -696,12 +928,17 @@ extern "C" int adapt_bn_update(adapt_ctx *ctx, float *gamma, float *beta, const 
 
 extern "C" int adapt_gap_fwd(adapt_ctx *ctx, const void *a, adapt_fmt f, int n, int hw, int c, adapt_rng rng, void *out)
 {
-    if (!ctx || !fmt_ok(f) || !rng_ok(rng) || n < 0 || hw < 1 || c < 1) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(f) || !rng_ok(rng) || n < 0 || hw < 1 || c < 1) return ADAPT_EINVAL;
     if ((hw & (hw - 1)) || (c & 7) || hw > (1 << 20) || (uint64_t)n * c >= ((uint64_t)1 << 31)) return ADAPT_EUNSUPPORTED;
     if (n == 0) return ADAPT_OK;
     if (!a || !out || !aligned16(a) || !aligned16(out)) return ADAPT_EINVAL;
     int sh = 0;
     while ((1 << sh) < hw) ++sh;
+    if (f.wl > 16) {
+        hipLaunchKernelGGL(gap_fwd_wide_kernel, dim3(bn_grid(ctx, (uint64_t)n * c)), dim3(kBnThreads), 0, ctx->stream, a, 4, out, (uint32_t)n,
+                           (uint32_t)hw, (uint32_t)c, sh, f.wl, rng.mode, rng.seed, rng.stream);
+        return hip_status(ctx, hipGetLastError());
+    }
     const uint32_t cg = (uint32_t)c / 8;
     const dim3 g(bn_grid(ctx, (uint64_t)n * cg)), t(kBnThreads);
     if (storage_bytes(f) == 1)
@@ -715,10 +952,16 @@ extern "C" int adapt_gap_fwd(adapt_ctx *ctx, const void *a, adapt_fmt f, int n, 
 
 extern "C" int adapt_gap_bwd(adapt_ctx *ctx, const void *dout, int wl, int n, int hw, int c, void *da)
 {
-    if (!ctx || wl < 2 || wl > 16 || n < 0 || hw < 1 || c < 1) return ADAPT_EINVAL;
+    if (!ctx || wl < 2 || wl > 32 || n < 0 || hw < 1 || c < 1) return ADAPT_EINVAL;
     if ((hw & (hw - 1)) || (c & 7)) return ADAPT_EUNSUPPORTED;
     if (n == 0) return ADAPT_OK;
     if (!dout || !da || !aligned16(dout) || !aligned16(da)) return ADAPT_EINVAL;
+    if (wl > 16) {
+        const uint64_t total = (uint64_t)n * hw * c;
+        hipLaunchKernelGGL(gap_bwd_wide_kernel, dim3(bn_grid(ctx, total)), dim3(kBnThreads), 0, ctx->stream, (const int32_t *)dout,
+                           (int32_t *)da, total, (uint32_t)hw, (uint32_t)c);
+        return hip_status(ctx, hipGetLastError());
+    }
     const uint32_t cg = (uint32_t)c / 8;
     const uint64_t groups = (uint64_t)n * hw * cg;
     const dim3 g(bn_grid(ctx, groups)), t(kBnThreads);
@@ -730,7 +973,7 @@ extern "C" int adapt_gap_bwd(adapt_ctx *ctx, const void *dout, int wl, int n, in
 extern "C" int adapt_grad_add(adapt_ctx *ctx, const void *a, int wl_a, const int64_t *e_a, const void *b, int wl_b, const int64_t *e_b,
                               size_t n, int wl_out, adapt_rng rng, void *out, int32_t *shift, int64_t *e_out)
 {
-    if (!ctx || wl_a < 2 || wl_a > 16 || wl_out < 2 || wl_out > 16 || (b && (wl_b < 2 || wl_b > 16)) || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (!ctx || wl_a < 2 || wl_a > 32 || wl_out < 2 || wl_out > 32 || (b && (wl_b < 2 || wl_b > 32)) || !rng_ok(rng)) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if (((uintptr_t)e_a & 7) || ((uintptr_t)e_b & 7) || ((uintptr_t)e_out & 7) || ((uintptr_t)shift & 3)) return ADAPT_EINVAL;
     if (n > 0 && (!a || !out || !aligned16(a) || !aligned16(out) || (b && !aligned16(b)))) return ADAPT_EINVAL;
@@ -742,6 +985,12 @@ extern "C" int adapt_grad_add(adapt_ctx *ctx, const void *a, int wl_a, const int
     m.e_out = reinterpret_cast<long long *>(e_out); m.shift_out = shift; m.n = n; m.wl = wl_out; m.mode = rng.mode; m.seed = rng.seed;
     m.stream = rng.stream; m.part = reinterpret_cast<uint64_t *>(scratch(ctx)); m.nparts = grid1;
     const dim3 t(kBnThreads), g2(bn_grid(ctx, groups));
+    if (wl_a > 16 || wl_out > 16 || (b && wl_b > 16)) {             // int32 codes somewhere: sums in 128 bits
+        const int ea = storage_bytes(adapt_fmt{wl_a, 0}), eb = b ? storage_bytes(adapt_fmt{wl_b, 0}) : 1, eo = storage_bytes(adapt_fmt{wl_out, 0});
+        hipLaunchKernelGGL(merge_wide_kernel<0>, dim3(grid1), t, 0, ctx->stream, m, ea, eb, eo);
+        hipLaunchKernelGGL(merge_wide_kernel<1>, dim3(bn_grid(ctx, (uint64_t)n)), t, 0, ctx->stream, m, ea, eb, eo);
+        return hip_status(ctx, hipGetLastError());
+    }
     const int sel = (wl_a > 8) * 4 + ((b ? wl_b : 8) > 8) * 2 + (wl_out > 8);
 #define ADAPT_MERGE(TA, TB, TO)                                                                               \
     do {                                                                                                      \

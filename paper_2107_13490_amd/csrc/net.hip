@@ -474,7 +474,7 @@ struct NetPlan {
 
 // Lays the workspace out; returns false for an invalid network.
 // wl_max: the largest word length any layer may take (16: int16 storage everywhere; 32: int32 storage and 128-bit
-// accumulators; only for networks without batch normalisation, shortcuts and average pooling)
+// accumulators)
 bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, int wl_max, std::vector<NetLayer> &L, NetPlan &P)
 {
     if (!descs || count < 1 || count > kMaxLayers || lb_upr < 0 || lb_upr > 64 || (wl_max != 16 && wl_max != 32)) return false;
@@ -506,7 +506,6 @@ bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, int wl_max, s
         y.src = descs[l].src >= 0 ? descs[l].src : l - 1;
         y.res = descs[l].res;
         if (y.src >= l || descs[l].src < -1 || y.res >= l || y.res < -1) return false;
-        if (wl_max > 16 && (y.bn || y.gap || y.res >= 0)) return false;
         if (y.res >= 0 && !y.bn) return false;                     // the shortcut is added inside the batch-norm output
         if (y.gap && y.d.pool) return false;
         y.fmt = adapt_fmt{8, 4};
@@ -654,6 +653,13 @@ extern "C" size_t adapt_net_workspace_bytes(const adapt_layer_desc *layers, int 
     return nodes.empty() ? 0 : adapt_graph_workspace_bytes(nodes.data(), count, lb_upr);
 }
 
+extern "C" size_t adapt_graph_workspace_bytes_wide(const adapt_node_desc *nodes, int count, int lb_upr, int wl_max)
+{
+    std::vector<NetLayer> L;
+    NetPlan P;
+    return plan_net(nodes, count, lb_upr, wl_max, L, P) ? P.bytes : 0;
+}
+
 extern "C" size_t adapt_net_workspace_bytes_wide(const adapt_layer_desc *layers, int count, int lb_upr, int wl_max)
 {
     const std::vector<adapt_node_desc> nodes = plain_nodes(layers, count);
@@ -721,6 +727,13 @@ extern "C" int adapt_graph_create(adapt_ctx *ctx, const adapt_node_desc *nodes, 
                                   size_t workspace_bytes, adapt_net **out)
 {
     return graph_create(ctx, nodes, count, weights, gammas, betas, bn_eps, sp, 16, workspace, workspace_bytes, out);
+}
+
+extern "C" int adapt_graph_create_wide(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights,
+                                       float *const *gammas, float *const *betas, double bn_eps, const adapt_switch_params *sp, int wl_max,
+                                       void *workspace, size_t workspace_bytes, adapt_net **out)
+{
+    return graph_create(ctx, nodes, count, weights, gammas, betas, bn_eps, sp, wl_max, workspace, workspace_bytes, out);
 }
 
 extern "C" int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count, float *const *weights,

@@ -153,3 +153,82 @@ def test_sum_of_two_gradient_tensors(n, wl_a, wl_b, wl_o, e_a, e_b):
     out, shift, e = ctx().grad_add(dev(a), wl_a, ea, None, 8, None, wl_o, seed=2, stream=n)
     want, we, ws = go.grad_add(a, e_a, None, None, wl_o, 2, n)
     assert (int(host(shift)[0]), int(host(e)[0])) == (ws, we) and np.array_equal(host(out).astype(np.int64), want)
+
+
+# ---- word lengths above 16 bits --------------------------------------------------------------------------------
+
+def _dtw(wl):
+    return np.int8 if wl <= 8 else np.int16 if wl <= 16 else np.int32
+
+
+def _codes_w(g, shape, wl, scale=0.25, offset=True):
+    lim = 1 << (wl - 1)
+    v = g.standard_normal(shape) * (lim * scale)
+    if offset:
+        v = v + g.standard_normal(shape[-1]) * (lim * 0.2)
+    return np.clip(np.rint(v), -lim, lim - 1).astype(np.int64)
+
+
+WIDE_BN_CASES = [((3, 4, 4, 8), (28, 22), (32, 26), None), ((2, 5, 3, 16), (32, 20), (24, 18), (20, 15)), ((4, 2, 2, 24), (12, 8), (20, 15), (32, 28)),
+                 ((2, 3, 3, 8), (24, 20), (8, 4), (8, 5)), ((1, 1, 2, 8), (17, 10), (17, 10), None), ((9, 7, 5, 40), (32, 30), (32, 30), (32, 30))]
+
+
+@pytest.mark.parametrize("shape,fy,fo,fres", WIDE_BN_CASES)
+@pytest.mark.parametrize("relu", [False, True])
+def test_batch_norm_above_sixteen_bits(shape, fy, fo, fres, relu):
+    g = np.random.default_rng(sum(shape) + fy[0] + 7 * relu)
+    k = shape[-1]
+    y = _codes_w(g, shape, fy[0])
+    gamma = (1.0 + 0.3 * g.standard_normal(k)).astype(np.float32)
+    beta = (0.3 * g.standard_normal(k)).astype(np.float32)
+    res = _codes_w(g, shape, fres[0], 0.2, False) if fres else None
+    eps, seed, stream = 1e-5, 13, 900 + k
+    out, state = ctx().bn_forward(dev(y.astype(_dtw(fy[0]))), fy, dev(gamma), dev(beta), eps, fo, relu,
+                                  dev(res.astype(_dtw(fres[0]))) if fres else None, fres, seed=seed, stream=stream)
+    want, st = go.bn_forward(y, fy[1], gamma, beta, eps, fo[0], fo[1], relu, seed, stream, res, fres[1] if fres else 0)
+    got = _state_fields(state, k)
+    assert (got["channels"], got["fl_y"], got["fl_o"], got["FA"]) == (k, fy[1], fo[1], st["FA"])
+    for name in ("mean", "sig", "alpha"):
+        assert np.array_equal(got[name].view(np.uint64), st[name].view(np.uint64)), name
+    assert np.array_equal(got["A"], st["A"]) and np.array_equal(got["B"], st["B"])
+    assert np.array_equal(host(out).astype(np.int64), want)
+
+    wl_dz, wl_out = fo[0], fy[0]
+    dz = _codes_w(g, shape, wl_dz, 0.3, False)
+    e_in = torch.tensor([-5], dtype=torch.int64, device="cuda")
+    r = ctx().bn_backward(dev(dz.astype(_dtw(wl_dz))), wl_dz, dev(y.astype(_dtw(fy[0]))), fy, state, wl_out, seed=seed, stream=stream + 1,
+                          e_in=e_in)
+    wb = go.bn_backward(dz, y, st, wl_out, seed, stream + 1)
+    got = _state_fields(state, k)
+    assert got["FB"] == wb["FB"] and int(host(r["shift"])[0]) == wb["shift"]
+    assert int(host(r["e_out"])[0]) == -5 + wb["e_add"]
+    assert np.array_equal(host(r["dgamma"]).view(np.uint64), wb["dgamma"].view(np.uint64))
+    assert np.array_equal(host(r["dbeta"]).view(np.uint64), wb["dbeta"].view(np.uint64))
+    assert np.array_equal(host(r["dy"]).astype(np.int64), wb["dy"])
+
+
+@pytest.mark.parametrize("wl", [17, 24, 32])
+def test_average_pooling_and_gradient_merge_above_sixteen_bits(wl):
+    g = np.random.default_rng(wl)
+    a = _codes_w(g, (3, 4, 4, 16), wl, 0.4)
+    a.reshape(-1)[:3] = [(1 << (wl - 1)) - 1, -(1 << (wl - 1)), 0]
+    out = ctx().gap_fwd(dev(a.astype(np.int32)), (wl, 3), seed=2, stream=9)
+    assert np.array_equal(host(out).astype(np.int64), go.gap_forward(a, wl, 2, 9))
+    one = ctx().gap_fwd(dev(a[:, :1, :1, :].astype(np.int32).copy()), (wl, 3), seed=2, stream=9)     # a single position: the codes themselves
+    assert np.array_equal(host(one).astype(np.int64), a[:, 0, 0, :])
+    d = _codes_w(g, (3, 16), wl, 0.4, False)
+    da = ctx().gap_bwd(dev(d.astype(np.int32)), wl, 4, 4)
+    assert np.array_equal(host(da).astype(np.int64), go.gap_backward(d, 4, 4)[0])
+    for wl_b, e_a, e_b in ((wl, 3, 3), (12, 0, 30), (wl, 45, 5), (8, 2, 43), (32, 20, 0)):
+        x = _codes_w(g, 5000, wl, 0.3, False)
+        y = _codes_w(g, 5000, wl_b, 0.3, False)
+        ea = torch.tensor([e_a], dtype=torch.int64, device="cuda")
+        eb = torch.tensor([e_b], dtype=torch.int64, device="cuda")
+        for wl_out in (wl, 10):
+            codes, shift, e_out = ctx().grad_add(dev(x.astype(np.int32)), wl, ea, dev(y.astype(_dtw(wl_b))), wl_b, eb, wl_out, seed=4, stream=7)
+            want, e, sh = go.grad_add(x, e_a, y, e_b, wl_out, 4, 7)
+            assert int(host(shift)[0]) == sh and int(host(e_out)[0]) == e, (wl_b, e_a, e_b, wl_out)
+            assert np.array_equal(host(codes).astype(np.int64), want)
+    codes, shift, e_out = ctx().grad_add(dev(x.astype(np.int32)), wl, ea, None, 8, None, 12, seed=4, stream=7)        # refit alone
+    want, e, sh = go.grad_add(x, e_a, None, None, 12, 4, 7)
+    assert np.array_equal(host(codes).astype(np.int64), want) and int(host(e_out)[0]) == e

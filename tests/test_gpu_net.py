@@ -590,6 +590,18 @@ def _small_resnet():
             N(1, 1, 16, 10, 1, 1, 1, 0, relu=False)]                             # 6 fully connected
 
 
+def _tiny_resnet():
+    """The same topology on 4x4 maps (the oracle above 16 bits runs on Python integers)."""
+    N = go.Node
+    return [N(4, 4, 3, 8, bn=True),
+            N(4, 4, 8, 8, bn=True),
+            N(4, 4, 8, 8, bn=True, res=0),
+            N(4, 4, 8, 16, stride=2, bn=True, src=2),
+            N(4, 4, 8, 16, 1, 1, 2, 0, relu=False, bn=True, src=2),
+            N(2, 2, 16, 16, bn=True, src=3, res=4, gap=True),
+            N(1, 1, 16, 10, 1, 1, 1, 0, relu=False)]
+
+
 def _resnet18_cifar(classes=100):
     N = go.Node
     nodes = [N(32, 32, 3, 64, bn=True)]
@@ -652,7 +664,8 @@ def _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, labels_rng, seed, s0, 
         ex = host(net.tensor(l, pkg.NT_EXP))
         assert np.array_equal(host(net.tensor(l, pkg.NT_G)).astype(np.int64), bwd["g"][l].ravel()), l
         assert int(ex[2]) == bwd["e_g"][l], (l, ex, bwd["e_g"][l])
-        assert net.tensor(l, pkg.NT_STATS).g_sumsq == bwd["sumsq"][l], l
+        st_l = net.tensor(l, pkg.NT_STATS)
+        assert (_sumsq(st_l) if fmts[l][0] > 16 else st_l.g_sumsq) == bwd["sumsq"][l], l
         if check_all:
             if l < last or L.bn or L.relu or L.pool:             # (the last layer may use the caller's gradient as it is)
                 assert np.array_equal(host(net.tensor(l, pkg.NT_DYC)).astype(np.int64), bwd["dyc"][l].ravel()), l
@@ -684,7 +697,7 @@ def _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, labels_rng, seed, s0, 
     return ws, bn_new, loss
 
 
-def _run_graph(nodes, fmts, n, steps, seed, switch_kw=None, check_all=True, lr=0.05):
+def _run_graph(nodes, fmts, n, steps, seed, switch_kw=None, check_all=True, lr=0.05, wl_max=16):
     from oracle import pushup_oracle as po
     rng = np.random.default_rng(seed)
     first = nodes[0]
@@ -700,8 +713,8 @@ def _run_graph(nodes, fmts, n, steps, seed, switch_kw=None, check_all=True, lr=0
         sp = pkg.SwitchParams(k["lb_lwr"], k["lb_upr"], k["lb_init"], k["r_lwr"], k["r_upr"], k["r_init"], k["gamma"], k["eps"], k["buff"],
                               k["wl_lo"], k["wl_hi"], po.ST_MIN)
         state = no.SwitchState(len(nodes), k["lb_lwr"], k["lb_upr"], k["lb_init"], k["r_lwr"], k["r_upr"], k["r_init"], k["gamma"], k["eps"],
-                               k["buff"], k["wl_lo"], k["wl_hi"])
-    net = pkg.Net(ctx(), [_node_desc(n, L) for L in nodes], wdev, switch=sp, bn=bndev, bn_eps=1e-5)
+                               k["buff"], k["wl_lo"], k["wl_hi"], wl_cap=wl_max)
+    net = pkg.Net(ctx(), [_node_desc(n, L) for L in nodes], wdev, switch=sp, bn=bndev, bn_eps=1e-5, wl_max=wl_max)
     fmts = list(fmts)
     for l, (wl, fl) in enumerate(fmts):
         net.set_format(l, wl, fl)
@@ -726,6 +739,19 @@ def test_residual_network_training_with_precision_switching():
     kw = dict(lb_lwr=1, lb_upr=3, lb_init=2, r_lwr=50, r_upr=80, r_init=60, gamma=0.4, eps=1e-2, buff=3, wl_lo=4, wl_hi=16)
     switches, fmts = _run_graph(_small_resnet(), [(12, 8)] * 6 + [(12, 7)], n=6, steps=6, seed=42, switch_kw=kw)
     assert switches >= 6
+
+
+@pytest.mark.parametrize("fmts", [[(24, 18), (20, 14), (32, 25), (17, 11), (28, 20), (24, 17), (20, 14)],
+                                  [(12, 8), (24, 18), (16, 11), (8, 4), (32, 24), (8, 4), (12, 8)]])
+def test_small_residual_network_above_sixteen_bits(fmts):
+    _run_graph(_tiny_resnet(), fmts, n=3, steps=2, seed=51, wl_max=32)
+
+
+def test_residual_network_training_with_precision_switching_up_to_thirty_two_bits():
+    kw = dict(lb_lwr=1, lb_upr=3, lb_init=2, r_lwr=50, r_upr=80, r_init=60, gamma=0.4, eps=1e-6, buff=6, wl_lo=4, wl_hi=32)
+    switches, fmts = _run_graph(_tiny_resnet(), [(16, 12), (30, 24), (12, 8), (14, 10), (20, 15), (16, 11), (12, 7)], n=3, steps=5,
+                                seed=52, switch_kw=kw, wl_max=32)
+    assert switches >= 6 and sum(w > 16 for w, _ in fmts) >= 3
 
 
 def test_graph_descriptions_that_are_rejected():
