@@ -117,8 +117,11 @@ def residual_add(a, fl_a: int, b, fl_b: int, wl_o: int, fl_o: int, mode: int = o
                  stream: int = 0, relu: bool = False) -> np.ndarray:
     """codes of a*2^-fl_a + b*2^-fl_b in <wl_o,fl_o>: exact sum with max(fl_a,fl_b) fractional bits, requantized."""
     f = max(fl_a, fl_b)
-    s = np.asarray(a, dtype=np.int64) * (1 << (f - fl_a)) + np.asarray(b, dtype=np.int64) * (1 << (f - fl_b))
-    return orc.requantize(s, f - fl_o, wl_o, mode, seed, stream, relu)
+    a, b = np.asarray(a, dtype=np.int64), np.asarray(b, dtype=np.int64)
+    if force_wide or wl_o > 16 or (a.size and max(int(np.abs(a).max()), int(np.abs(b).max())) >= 1 << 15):
+        a, b = a.astype(object), b.astype(object)            # codes above 16 bits: the aligned sum can pass 64 bits
+    s = a * (1 << (f - fl_a)) + b * (1 << (f - fl_b))
+    return _requantize(s, f - fl_o, wl_o, mode, seed, stream, relu)
 
 
 # ---- contractions and fitting by word length -------------------------------------------------------------

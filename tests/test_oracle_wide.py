@@ -206,3 +206,26 @@ def test_update_with_wide_gradient_codes_and_wide_weights_closed_form():
     assert r["sumsq"] == 8 * ((1 << 31) - 1) ** 2 and r["sumsq"] > 1 << 64
     want = -np.float32(np.float32(1.0 / np.sqrt(float(r["sumsq"]))) * np.float32(2.0 ** 31))     # fp32(code) = 2^31
     assert np.all(r["w"] == want) and abs(float(want) + 1.0 / np.sqrt(8.0)) < 1e-7
+
+
+def test_residual_addition_of_wide_codes_is_the_rounded_exact_sum():
+    from oracle import net_oracle as no
+    g = np.random.default_rng(15)
+    a = g.integers(-(1 << 31), 1 << 31, 200)
+    b = g.integers(-(1 << 23), 1 << 23, 200)
+    for (fl_a, fl_b, wl_o, fl_o) in ((31, 0, 32, 0), (5, 20, 32, 28), (20, 5, 17, 3), (10, 10, 8, 0)):
+        got = no.residual_add(a, fl_a, b, fl_b, wl_o, fl_o, orc.RN_HALF_UP)
+        lo, hi = -(1 << (wl_o - 1)), (1 << (wl_o - 1)) - 1
+        for x, y, c in zip(a, b, got):
+            v = (Fraction(int(x), 1 << fl_a) + Fraction(int(y), 1 << fl_b)) * (1 << fl_o)
+            want = min(max((v + Fraction(1, 2)).__floor__(), lo), hi)
+            # above 16 dropped bits the rule floors once before the 16 guard bits: at most one step below the exact rounding
+            assert int(c) == want or (max(fl_a, fl_b) - fl_o > 16 and int(c) == max(want - 1, lo)), (x, y, c, want)
+    # narrow inputs: identical to the int64 path
+    a8, b8 = g.integers(-128, 128, 300), g.integers(-2000, 2000, 300)
+    no.force_wide = True
+    try:
+        w = no.residual_add(a8, 5, b8, 9, 12, 7, orc.SR, 3, 4, True)
+    finally:
+        no.force_wide = False
+    assert np.array_equal(w, no.residual_add(a8, 5, b8, 9, 12, 7, orc.SR, 3, 4, True))
