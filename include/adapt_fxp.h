@@ -418,7 +418,8 @@ int adapt_requantize_fit(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n
 
 /* Residual addition of two fixed-point tensors: out = a + b in format fo, i.e. the exact sum with
  * max(fa.fl, fb.fl) fractional bits, then the contraction epilogue's rule with
- * s = max(fa.fl, fb.fl) - fo.fl (SR or round-to-nearest, optional ReLU, saturation).  n <= 2^40. */
+ * s = max(fa.fl, fb.fl) - fo.fl (SR or round-to-nearest, optional ReLU, saturation).  n <= 2^40.
+ * Word lengths up to 32 (int32_t codes above 16 bits; the sum is then formed in 128 bits). */
 int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *b, adapt_fmt fb,
                        size_t n, adapt_fmt fo, adapt_rng rng, int relu, void *out);
 

@@ -24,6 +24,7 @@
 #include "context.hpp"
 #include "fit.hpp"
 #include "grad_window.hpp"
+#include "wide.hpp"
 
 namespace adapt {
 
@@ -269,6 +270,22 @@ __global__ void __launch_bounds__(kEwThreads) residual_add_kernel(const AddArgs 
         }
 }
 
+// the same sum for tensors above 16 bits (int32 codes): 128-bit arithmetic, storage widths chosen at run time
+__global__ void __launch_bounds__(kEwThreads) residual_add_wide_kernel(const AddArgs p, int es_a, int es_b, int es_o)
+{
+    auto code_at = [](const void *q, int es, uint64_t i) -> long long {
+        return es == 1 ? (long long)static_cast<const int8_t *>(q)[i] : es == 2 ? (long long)static_cast<const int16_t *>(q)[i]
+                                                                              : (long long)static_cast<const int32_t *>(q)[i];
+    };
+    for (uint64_t i = (uint64_t)blockIdx.x * kEwThreads + threadIdx.x; i < p.n; i += (uint64_t)gridDim.x * kEwThreads) {
+        const i128 s = (i128)((u128)(i128)code_at(p.a, es_a, i) << p.sa) + (i128)((u128)(i128)code_at(p.b, es_b, i) << p.sb);
+        const int c = requantize_wide_one(s, p.shift, p.wl, p.relu, rounding_bits_of(p.seed, p.stream, i, p.mode));
+        if (es_o == 1) static_cast<int8_t *>(p.out)[i] = (int8_t)c;
+        else if (es_o == 2) static_cast<int16_t *>(p.out)[i] = (int16_t)c;
+        else static_cast<int32_t *>(p.out)[i] = c;
+    }
+}
+
 static int ew_grid(const adapt_ctx *ctx, uint64_t items)
 {
     const uint64_t blocks = (items + kEwThreads - 1) / kEwThreads;
@@ -398,7 +415,7 @@ __global__ void exp_set_kernel(long long *dst, const long long *src, long long a
 extern "C" int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, const void *b, adapt_fmt fb, size_t n,
                                   adapt_fmt fo, adapt_rng rng, int relu, void *out)
 {
-    if (!ctx || !fmt_ok(fa) || !fmt_ok(fb) || !fmt_ok(fo) || !rng_ok(rng)) return ADAPT_EINVAL;
+    if (!ctx || !fmt_ok_wide(fa) || !fmt_ok_wide(fb) || !fmt_ok_wide(fo) || !rng_ok(rng)) return ADAPT_EINVAL;
     if (n > ((uint64_t)1 << 40)) return ADAPT_EINVAL;
     if (n == 0) return ADAPT_OK;
     if (!a || !b || !out || !aligned16(a) || !aligned16(b) || !aligned16(out)) return ADAPT_EINVAL;
@@ -406,6 +423,11 @@ extern "C" int adapt_residual_add(adapt_ctx *ctx, const void *a, adapt_fmt fa, c
     AddArgs p;
     p.a = a; p.b = b; p.out = out; p.n = n; p.sa = f - fa.fl; p.sb = f - fb.fl; p.shift = f - fo.fl; p.wl = fo.wl;
     p.relu = relu != 0; p.mode = rng.mode; p.seed = rng.seed; p.stream = rng.stream;
+    if (fa.wl > 16 || fb.wl > 16 || fo.wl > 16) {
+        hipLaunchKernelGGL(residual_add_wide_kernel, dim3(ew_grid(ctx, (uint64_t)n)), dim3(kEwThreads), 0, ctx->stream, p, storage_bytes(fa),
+                           storage_bytes(fb), storage_bytes(fo));
+        return hip_status(ctx, hipGetLastError());
+    }
     const dim3 grid(ew_grid(ctx, ((uint64_t)n + 7) >> 3)), block(kEwThreads);
     const int sel = (storage_bytes(fa) == 2) * 4 + (storage_bytes(fb) == 2) * 2 + (storage_bytes(fo) == 2);
 #define ADAPT_ADD(TA, TB, TO) hipLaunchKernelGGL((residual_add_kernel<TA, TB, TO>), grid, block, 0, ctx->stream, p)

@@ -216,3 +216,16 @@ def test_batched_quantize_with_items_above_sixteen_bits():
         want = (float(fin.min()), float(fin.max())) if t in (0, 1, 3, 6) and fin.size else (np.inf, -np.inf)
         assert tuple(r[t].tolist()) == want, t
         assert np.array_equal(host(outs[t]).astype(np.int64), orc.quantize(x, fmts[t][0], fmts[t][1], orc.SR, 9, streams[t])[0]), t
+
+
+@pytest.mark.parametrize("n", [1, 9, 4099])
+@pytest.mark.parametrize("fa,fb,fo", [((32, 31), (32, 0), (32, 0)), ((24, 5), (12, 9), (32, 28)), ((8, 5), (32, 20), (17, 3)), ((20, 10), (20, 10), (8, 0)),
+                                      ((16, 12), (8, 3), (24, 20))])
+def test_residual_addition_with_int32_codes(n, fa, fb, fo):
+    g = np.random.default_rng(n + fa[0] + fo[0])
+    a, b = _codes(g, n, fa[0]), _codes(g, n, fb[0])
+    for relu in (False, True):
+        got = ctx().residual_add(dev(a.astype(_dt(fa[0]))), fa, dev(b.astype(_dt(fb[0]))), fb, fo, seed=5, stream=n, relu=relu)
+        want = no.residual_add(a, fa[1], b, fb[1], fo[0], fo[1], orc.SR, 5, n, relu)
+        assert got.dtype == (torch.int8 if fo[0] <= 8 else torch.int16 if fo[0] <= 16 else torch.int32)
+        assert np.array_equal(host(got).astype(np.int64), want)
