@@ -412,6 +412,50 @@ def elementwise_rows(ctx, pkg, torch):
     return rows
 
 
+def wide_rows(ctx, pkg, torch):
+    """Word lengths 17..32 (int32 codes, contractions composed of 11-bit parts with 128-bit recombination): device time
+    of quantize on 16 M elements and of the forward / backward calls of configs[2]'s layer shape with <24,20> and
+    <32,28> operands.  TOPS are useful ops (2 M N K); these calls are exact, not fast."""
+    from paper_2107_13490_amd import ConvDesc, Epilogue
+
+    def timed(fn, reps=5):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    rows = {}
+    n = 1 << 24
+    x = torch.randn(n, device="cuda")
+    q = torch.empty(n, dtype=torch.int32, device="cuda")
+    ms = timed(lambda: ctx.quantize(x, 24, 20, pkg.SR, seed=1, stream=2, out=q), 20)
+    rows["quantize_24bit_16M"] = {"ms": ms, "GBps": 8.0 * n / (ms * 1e-3) / 1e9, "frac_hbm": 8.0 * n / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    d = ConvDesc(128, 16, 16, 64, 192, 3, 3, 1, 1)
+    ops = 2.0 * d.n * d.p * d.q * d.k * d.r * d.s * d.c
+    for wl, fl in ((24, 20), (32, 28)):
+        lim = 1 << (wl - 2)
+        xq = torch.randint(-lim, lim, (d.n, d.h, d.w, d.c), dtype=torch.int32, device="cuda")
+        wq = torch.randint(-lim, lim, (d.k, d.r, d.s, d.c), dtype=torch.int32, device="cuda")
+        dy = torch.randint(-lim, lim, (d.n, d.p, d.q, d.k), dtype=torch.int32, device="cuda")
+        need = max(ctx.workspace_bytes(pkg.CALL_CONV_FWD, conv=d, fa=(wl, fl), fb=(wl, fl)),
+                   ctx.workspace_bytes(pkg.CALL_CONV_BACKWARD, conv=d, fa=(wl, 0), fb=(wl, fl), fc=(wl, fl)))
+        ctx.reserve_workspace(need)
+        ep = Epilogue.requant(wl, fl, pkg.SR, 0, 10, relu=True)
+        y = ctx.conv_fwd(d, xq, (wl, fl), wq, (wl, fl), ep)
+        f_ms = timed(lambda: ctx.conv_fwd(d, xq, (wl, fl), wq, (wl, fl), ep, out=y))
+        dx, dw = ctx.conv_backward(d, dy, (wl, 0), wq, (wl, fl), xq, (wl, fl), Epilogue.exact(), Epilogue.exact())
+        b_ms = timed(lambda: ctx.conv_backward(d, dy, (wl, 0), wq, (wl, fl), xq, (wl, fl), Epilogue.exact(), Epilogue.exact(),
+                                               out_dx=dx, out_dw=dw))
+        rows[f"conv_config2_shape_wl{wl}"] = {"forward_ms": f_ms, "forward_useful_TOPS": ops / (f_ms * 1e-3) / 1e12,
+                                              "backward_ms": b_ms, "backward_useful_TOPS": 2 * ops / (b_ms * 1e-3) / 1e12}
+    return rows
+
+
 def chained_step(ctx, pkg, torch, batch=128):
     """The AlexNet-CIFAR layers of configs[3] as one chained fixed-point training step (forward pass, backward
     pass with fitted gradient codes, update + re-quantization), formats of configs[3]; device time per phase."""
@@ -636,6 +680,7 @@ def main():
         torch.cuda.empty_cache()
         out["next_rows"]["chained_step_resnet18"] = chained_resnet18(ctx, pkg, torch, batch=256)
         out["next_rows"]["chained_step_elementwise"] = elementwise_rows(ctx, pkg, torch)
+        out["next_rows"]["wide_17_32_bits"] = wide_rows(ctx, pkg, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

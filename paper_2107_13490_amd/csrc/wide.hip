@@ -1,12 +1,16 @@
 // Contractions with word lengths 17..32 (Sec. 3.3 bounds the precision that PushUp may ask for at
-// 32 bits).  An operand of up to 32 bits is held as int32 codes and split into three parts of 11 bits,
-//     a = a2 2^22 + a1 2^11 + a0,   a0, a1 in [0, 2047],   a2 = a >> 22 in [-512, 511],
-// each a 12-bit code that the two-limb int8 MFMA kernels of this library take; an operand of at most
-// 16 bits stays as it is.  Every pair of parts is one exact contraction (int32 or int64 sums, by the
-// accumulator bound of that pair); the partial results are added at their weights 2^(11(i+j)) in
-// 128-bit integers, and the requantizing rule of the contraction epilogue (or the exact 128-bit sum)
-// is applied once at the end.  Nine contractions for two wide operands, three when one is narrow:
-// the cost of precision above 16 bits on hardware whose matrix cores multiply bytes.
+// 32 bits).  An operand above 16 bits is held as int32 codes and split into parts that the two-limb
+// int8 MFMA kernels of this library take; an operand of at most 16 bits stays as it is.
+//   17..31 bits: two 16-bit parts, a = a1 2^16 + a0 with a0 the signed low half-word (so a1 =
+//                (a + 2^15) >> 16 stays within 16 bits: |a1| <= 2^14);
+//   32 bits:     there a1 could reach 2^15, so three parts of 11 bits, a = a2 2^22 + a1 2^11 + a0,
+//                a0, a1 in [0, 2047], a2 = a >> 22 in [-512, 511], each a 12-bit code.
+// Every pair of parts is one exact contraction (int32 or int64 sums, by the accumulator bound of that
+// pair); the partial results are added at their weights 2^(bits_a i + bits_b j) in 128-bit integers,
+// and the requantizing rule of the contraction epilogue (or the exact 128-bit sum) is applied once at
+// the end.  Four contractions for two operands of up to 31 bits, nine for two of 32, two or three
+// when one operand is narrow: the cost of precision above 16 bits on hardware whose matrix cores
+// multiply bytes.
 //
 // The host code below composes the library's own entry points; the three kernels here are bound by
 // HBM traffic (split: 4 B read, 6 B written per code; accumulate: 4-8 B read, 16 B read and written
@@ -32,6 +36,18 @@ split3_kernel(const int32_t *__restrict__ a, int16_t *__restrict__ p0, int16_t *
         p0[i] = (int16_t)(v & 2047);
         p1[i] = (int16_t)((v >> kPartBits) & 2047);
         p2[i] = (int16_t)(v >> (2 * kPartBits));
+    }
+}
+
+// codes of at most 31 bits: signed low half-word and what is left above it
+__global__ void __launch_bounds__(kWideThreads)
+split2_kernel(const int32_t *__restrict__ a, int16_t *__restrict__ p0, int16_t *__restrict__ p1, uint64_t n)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWideThreads) {
+        const int32_t v = a[i];
+        const int32_t lo = (int32_t)(int16_t)(v & 0xffff);
+        p0[i] = (int16_t)lo;
+        p1[i] = (int16_t)((v - lo) >> 16);
     }
 }
 
@@ -72,6 +88,7 @@ struct WideOperand {
     const void *part[3];
     adapt_fmt fmt[3];
     int parts;
+    int bits;          // weight of part i: 2^(bits * i)
 };
 
 int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems_a, const void *b, adapt_fmt fb, uint64_t elems_b,
@@ -92,18 +109,24 @@ int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems
     WideOperand A, B;
     auto prepare = [&](WideOperand &o, const void *p, adapt_fmt f, uint64_t elems, bool wide) {
         if (!wide) {
-            o.parts = 1; o.part[0] = p; o.fmt[0] = f;
+            o.parts = 1; o.bits = 0; o.part[0] = p; o.fmt[0] = f;
             return;
         }
-        o.parts = 3;
-        int16_t *q[3];
-        for (int i = 0; i < 3; ++i) {
+        const bool two = f.wl <= 31;
+        o.parts = two ? 2 : 3;
+        o.bits = two ? 16 : kPartBits;
+        int16_t *q[3] = {nullptr, nullptr, nullptr};
+        for (int i = 0; i < o.parts; ++i) {
             q[i] = reinterpret_cast<int16_t *>(take(elems * 2));
             o.part[i] = q[i];
-            o.fmt[i] = adapt_fmt{12, 0};
+            o.fmt[i] = two ? adapt_fmt{16, 0} : adapt_fmt{12, 0};
         }
-        hipLaunchKernelGGL(split3_kernel, dim3(wide_grid(ctx, elems)), dim3(kWideThreads), 0, ctx->stream,
-                           static_cast<const int32_t *>(p), q[0], q[1], q[2], elems);
+        if (two)
+            hipLaunchKernelGGL(split2_kernel, dim3(wide_grid(ctx, elems)), dim3(kWideThreads), 0, ctx->stream,
+                               static_cast<const int32_t *>(p), q[0], q[1], elems);
+        else
+            hipLaunchKernelGGL(split3_kernel, dim3(wide_grid(ctx, elems)), dim3(kWideThreads), 0, ctx->stream,
+                               static_cast<const int32_t *>(p), q[0], q[1], q[2], elems);
     };
     prepare(A, a, fa, elems_a, wide_a);
     prepare(B, b, fb, elems_b, wide_b);
@@ -120,7 +143,7 @@ int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems
         for (int j = 0; j < B.parts && status == ADAPT_OK; ++j) {
             status = sub(A.part[i], A.fmt[i], B.part[j], B.fmt[j], c, ex);
             if (status != ADAPT_OK) break;
-            const int sh = kPartBits * ((wide_a ? i : 0) + (wide_b ? j : 0));
+            const int sh = A.bits * i + B.bits * j;
             const int bits = adapt_acc_bits(k_total, A.fmt[i], B.fmt[j]);
             const dim3 g(wide_grid(ctx, outputs)), t(kWideThreads);
             if (bits == 32) hipLaunchKernelGGL(acc128_kernel<int32_t>, g, t, 0, ctx->stream, static_cast<const int32_t *>(c), sh, acc, outputs, first ? 1 : 0);

@@ -85,8 +85,8 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
                 // word lengths above 16: the parts, one exact partial result and the 128-bit sums, after the largest
                 // contraction of two 12-bit parts (or of a part and the narrow operand)
                 adapt_workspace_query sub = *q;
-                if (sub.fa.wl > 16) sub.fa = adapt_fmt{12, 0};
-                if (sub.fb.wl > 16) sub.fb = adapt_fmt{12, 0};
+                if (sub.fa.wl > 16) sub.fa = sub.fa.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};      // the parts' formats (wide.hip)
+                if (sub.fb.wl > 16) sub.fb = sub.fb.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};
                 const size_t inner = adapt_workspace_bytes(ctx, &sub);
                 if (inner == kInvalid) return kInvalid;
                 const int lda = q->lda ? q->lda : (q->transA ? q->M : q->K), ldb = q->ldb ? q->ldb : (q->transB ? q->K : q->N);
@@ -109,8 +109,8 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
             if (q->call != ADAPT_CALL_CONV_BACKWARD && fmt_ok_wide(q->fa) && fmt_ok_wide(q->fb) && (q->fa.wl > 16 || q->fb.wl > 16) &&
                 conv_ok(q->conv)) {
                 adapt_workspace_query sub = *q;
-                if (sub.fa.wl > 16) sub.fa = adapt_fmt{12, 0};
-                if (sub.fb.wl > 16) sub.fb = adapt_fmt{12, 0};
+                if (sub.fa.wl > 16) sub.fa = sub.fa.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};      // the parts' formats (wide.hip)
+                if (sub.fb.wl > 16) sub.fb = sub.fb.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};
                 const size_t inner = adapt_workspace_bytes(ctx, &sub);
                 if (inner == kInvalid) return kInvalid;
                 const adapt_conv_desc &d = q->conv;

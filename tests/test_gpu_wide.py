@@ -51,7 +51,7 @@ def test_quantize_to_int32_codes(wl, fl, n):
 
 
 GEMM_CASES = [((5, 7, 9), 32, 32), ((64, 48, 130), 24, 20), ((33, 17, 64), 17, 8), ((16, 16, 16), 12, 32), ((70, 130, 300), 32, 16),
-              ((128, 64, 1024), 32, 32)]
+              ((128, 64, 1024), 32, 32), ((24, 40, 96), 31, 31), ((17, 9, 200), 31, 32), ((32, 32, 64), 8, 31), ((9, 33, 48), 31, 17)]
 
 
 @pytest.mark.parametrize("shape,wa,wb", GEMM_CASES)
@@ -84,7 +84,8 @@ def test_narrow_operands_with_a_wide_output():
 
 
 CONV_CASES = [((2, 6, 6, 8, 16, 3, 3, 1, 1), 32, 32), ((3, 8, 8, 16, 8, 3, 3, 2, 1), 20, 24), ((2, 5, 7, 3, 8, 3, 3, 1, 1), 32, 8),
-              ((2, 4, 4, 32, 16, 1, 1, 1, 0), 12, 32), ((1, 9, 9, 8, 8, 5, 5, 2, 2), 17, 17)]
+              ((2, 4, 4, 32, 16, 1, 1, 1, 0), 12, 32), ((1, 9, 9, 8, 8, 5, 5, 2, 2), 17, 17), ((2, 6, 6, 8, 16, 3, 3, 1, 1), 31, 31),
+              ((2, 5, 5, 16, 8, 3, 3, 2, 1), 32, 31)]
 
 
 @pytest.mark.parametrize("shp,wx,ww", CONV_CASES)
