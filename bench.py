@@ -444,7 +444,7 @@ def wide_rows(ctx, pkg, torch):
         dy = torch.randint(-lim, lim, (d.n, d.p, d.q, d.k), dtype=torch.int32, device="cuda")
         need = max(ctx.workspace_bytes(pkg.CALL_CONV_FWD, conv=d, fa=(wl, fl), fb=(wl, fl)),
                    ctx.workspace_bytes(pkg.CALL_CONV_BACKWARD, conv=d, fa=(wl, 0), fb=(wl, fl), fc=(wl, fl)))
-        ctx.reserve_workspace(need)
+        ctx.reserve_workspace(need + 2 * 9 * 8 * max(xq.numel(), dy.numel()))      # room for one exact buffer per pair of parts
         ep = Epilogue.requant(wl, fl, pkg.SR, 0, 10, relu=True)
         y = ctx.conv_fwd(d, xq, (wl, fl), wq, (wl, fl), ep)
         f_ms = timed(lambda: ctx.conv_fwd(d, xq, (wl, fl), wq, (wl, fl), ep, out=y))

@@ -71,6 +71,30 @@ finish128_kernel(const i128 *__restrict__ acc, OutT *__restrict__ out, uint64_t 
         out[i] = (OutT)requantize_wide_one(acc[i], shift, wl, relu, rounding_bits_of(seed, stream, i, mode));
 }
 
+// With room for one exact output buffer per pair of parts, the partial results are combined in one pass instead of
+// one accumulation pass per pair: out = requantize(sum_p c_p 2^sh_p) (or the 128-bit sum itself).
+struct PairSet {
+    const void *c[9];
+    int sh[9];
+    int is32[9];
+    int count;
+};
+
+template <typename OutT, bool RAW>
+__global__ void __launch_bounds__(kWideThreads)
+combine_kernel(const PairSet ps, OutT *__restrict__ out, uint64_t n, int shift, int wl, int relu, int mode, uint64_t seed, uint64_t stream)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWideThreads) {
+        i128 s = 0;
+        for (int p = 0; p < ps.count; ++p) {
+            const long long v = ps.is32[p] ? (long long)static_cast<const int32_t *>(ps.c[p])[i] : static_cast<const long long *>(ps.c[p])[i];
+            s += (i128)((u128)(i128)v << ps.sh[p]);
+        }
+        if (RAW) reinterpret_cast<i128 *>(out)[i] = s;
+        else out[i] = (OutT)requantize_wide_one(s, shift, wl, relu, rounding_bits_of(seed, stream, i, mode));
+    }
+}
+
 static int wide_grid(const adapt_ctx *ctx, uint64_t n)
 {
     return (int)std::min<uint64_t>(std::max<uint64_t>((n + kWideThreads - 1) / kWideThreads, 1), (uint64_t)ctx->num_cu * 8);
@@ -99,8 +123,14 @@ int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems
     if (outputs == 0) return ADAPT_OK;
     const bool wide_a = fa.wl > 16, wide_b = fb.wl > 16;
     // buffers of this call at the end of the workspace; the contractions of the parts see the rest
-    const size_t tail = ws_need_wide(elems_a, wide_a, elems_b, wide_b, outputs, ep.raw != 0);
     const size_t keep = (size_t)1 << 20;
+    const int npairs = (wide_a ? (fa.wl <= 31 ? 2 : 3) : 1) * (wide_b ? (fb.wl <= 31 ? 2 : 3) : 1);
+    // one output buffer per pair and a single combining pass, when the workspace has room for that beside what a
+    // part contraction of this size may itself need (taken as twice the minimal tail); else one buffer and a pass per pair
+    const size_t tail_min = ws_need_wide(elems_a, wide_a, elems_b, wide_b, outputs, ep.raw != 0);
+    const size_t tail_all = (wide_a ? 3 * a256(elems_a * 2) : 0) + (wide_b ? 3 * a256(elems_b * 2) : 0) + (size_t)npairs * a256(outputs * 8);
+    const bool all_pairs = tail_all + tail_min + keep <= scratch_bytes(ctx);
+    const size_t tail = all_pairs ? tail_all : tail_min;
     if (tail + keep > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
     const size_t saved = ctx->ws_bytes;
     char *base = ctx->ws + saved - tail;
@@ -130,13 +160,44 @@ int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems
     };
     prepare(A, a, fa, elems_a, wide_a);
     prepare(B, b, fb, elems_b, wide_b);
-    void *c = take(outputs * 8);
-    i128 *acc = ep.raw ? static_cast<i128 *>(out) : reinterpret_cast<i128 *>(take(outputs * 16));
     adapt_epilogue ex = {};
     ex.raw = 1;
     ex.fmt = adapt_fmt{8, 0};
     ex.rng.mode = ADAPT_RN_HALF_UP;
     int status = ADAPT_OK;
+    const size_t off_parts = off;
+    if (all_pairs) {
+        PairSet ps = {};
+        ctx->ws_bytes = saved - tail;                  // what the part contractions may use
+        for (int i = 0; i < A.parts && status == ADAPT_OK; ++i)
+            for (int j = 0; j < B.parts && status == ADAPT_OK; ++j) {
+                void *cp = take(outputs * 8);
+                status = sub(A.part[i], A.fmt[i], B.part[j], B.fmt[j], cp, ex);
+                ps.c[ps.count] = cp;
+                ps.sh[ps.count] = A.bits * i + B.bits * j;
+                ps.is32[ps.count] = adapt_acc_bits(k_total, A.fmt[i], B.fmt[j]) == 32;
+                ++ps.count;
+            }
+        ctx->ws_bytes = saved;
+        if (status == ADAPT_EWORKSPACE && tail_all >= tail_min) {      // a part contraction wanted more scratch: the frugal way
+            status = ADAPT_OK;
+            off = off_parts;
+        } else {
+            if (status != ADAPT_OK) return status;
+            const int shift = ep.raw ? 0 : fa.fl + fb.fl - ep.fmt.fl;
+            const dim3 g(wide_grid(ctx, outputs)), t(kWideThreads);
+#define ADAPT_COMBINE(T, RAW) hipLaunchKernelGGL((combine_kernel<T, RAW>), g, t, 0, ctx->stream, ps, static_cast<T *>(out), outputs, shift, \
+                                                 (int)ep.fmt.wl, ep.relu != 0, (int)ep.rng.mode, ep.rng.seed, ep.rng.stream)
+            if (ep.raw) ADAPT_COMBINE(long long, true);
+            else if (ep.fmt.wl <= 8) ADAPT_COMBINE(int8_t, false);
+            else if (ep.fmt.wl <= 16) ADAPT_COMBINE(int16_t, false);
+            else ADAPT_COMBINE(int32_t, false);
+#undef ADAPT_COMBINE
+            return hip_status(ctx, hipGetLastError());
+        }
+    }
+    void *c = take(outputs * 8);
+    i128 *acc = ep.raw ? static_cast<i128 *>(out) : reinterpret_cast<i128 *>(take(outputs * 16));
     ctx->ws_bytes = saved - tail;                      // what the part contractions may use
     bool first = true;
     for (int i = 0; i < A.parts && status == ADAPT_OK; ++i)
