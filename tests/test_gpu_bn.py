@@ -170,7 +170,8 @@ def _codes_w(g, shape, wl, scale=0.25, offset=True):
 
 
 WIDE_BN_CASES = [((3, 4, 4, 8), (28, 22), (32, 26), None), ((2, 5, 3, 16), (32, 20), (24, 18), (20, 15)), ((4, 2, 2, 24), (12, 8), (20, 15), (32, 28)),
-                 ((2, 3, 3, 8), (24, 20), (8, 4), (8, 5)), ((1, 1, 2, 8), (17, 10), (17, 10), None), ((9, 7, 5, 40), (32, 30), (32, 30), (32, 30))]
+                 ((2, 3, 3, 8), (24, 20), (8, 4), (8, 5)), ((1, 1, 2, 8), (17, 10), (17, 10), None), ((9, 7, 5, 40), (32, 30), (32, 30), (32, 30)),
+                 ((33, 11, 13, 16), (24, 19), (20, 14), (16, 12))]           # 4719 rows: many rows per block of the statistics pass
 
 
 @pytest.mark.parametrize("shape,fy,fo,fres", WIDE_BN_CASES)
