@@ -106,7 +106,8 @@ int adapt_set_stream(adapt_ctx *ctx, void *hip_stream);
  * copies of narrow layers, one batch for up to 24 searches) and returns neither ADAPT_EWORKSPACE nor
  * ADAPT_EBOUND; 0 for a query that is invalid.  With less, contractions use fewer K splits and
  * batched searches smaller batches where they can.  ctx may be NULL: the current device is asked
- * for its number of compute units.  Host pointers; no device work. */
+ * for its number of compute units, and without a device the 256 of an MI355X are assumed (planning
+ * on a host without a GPU).  Host pointers; no device work. */
 typedef enum {
     ADAPT_CALL_QUANTIZE = 0, ADAPT_CALL_QUANTIZE_BATCHED = 1, ADAPT_CALL_GEMM = 2, ADAPT_CALL_CONV_FWD = 3,
     ADAPT_CALL_CONV_DGRAD = 4, ADAPT_CALL_CONV_WGRAD = 5, ADAPT_CALL_CONV_BACKWARD = 6, ADAPT_CALL_KLD_SEARCH = 7,

@@ -66,10 +66,15 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
     if (ctx) {
         num_cu = ctx->num_cu;
     } else {
+        // the current device's size, or (no device: host-side planning) the 256 compute units of an MI355X
         int dev = 0;
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return kInvalid;
-        num_cu = prop.multiProcessorCount;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+            num_cu = prop.multiProcessorCount;
+        } else {
+            (void)hipGetLastError();
+            num_cu = 256;
+        }
     }
     adapt_ctx dry = {};      // plans like a context with unlimited workspace; nothing is launched through it
     dry.num_cu = num_cu;

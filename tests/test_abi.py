@@ -77,3 +77,48 @@ def test_header_is_plain_c(tmp_path):
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_host_side_sizing_needs_no_gpu():
+    """Workspace queries and the chain's layout are host arithmetic: they answer without a device."""
+    import ctypes as C
+    import paper_2107_13490_amd as pkg
+    from paper_2107_13490_amd import ConvDesc, Fmt, LayerDesc, NodeDesc
+    from paper_2107_13490_amd.binding import WorkspaceQuery
+    lib = pkg.load_library()
+    assert pkg.acc_bits(64, Fmt(24, 0), Fmt(8, 0)) == 128 and pkg.acc_bits(64, Fmt(8, 0), Fmt(32, 0)) == 128
+    assert pkg.acc_bits(64, Fmt(33, 0), Fmt(8, 0)) < 0
+
+    def need(call, **kw):
+        q = WorkspaceQuery()
+        q.call = call
+        for k, v in kw.items():
+            setattr(q, k, v)
+        return lib.adapt_workspace_bytes(None, C.byref(q))
+
+    d = ConvDesc(128, 16, 16, 64, 192, 3, 3, 1, 1)
+    narrow = need(pkg.CALL_CONV_FWD, conv=d, fa=Fmt(8, 5), fb=Fmt(8, 5))
+    two = need(pkg.CALL_CONV_FWD, conv=d, fa=Fmt(12, 9), fb=Fmt(12, 9))
+    wide = need(pkg.CALL_CONV_FWD, conv=d, fa=Fmt(24, 20), fb=Fmt(24, 20))
+    assert 0 < narrow <= two < wide
+    # the parts of the operands and the exact sums of the outputs are part of a wide call's need
+    outputs = 128 * 16 * 16 * 192
+    assert wide >= 8 * outputs + 16 * outputs
+    back = need(pkg.CALL_CONV_BACKWARD, conv=d, fa=Fmt(32, 0), fb=Fmt(32, 28), fc=Fmt(32, 28))
+    assert back == max(need(pkg.CALL_CONV_DGRAD, conv=d, fa=Fmt(32, 0), fb=Fmt(32, 28)), need(pkg.CALL_CONV_WGRAD, conv=d, fa=Fmt(32, 0), fb=Fmt(32, 28)))
+    assert need(pkg.CALL_CONV_FWD, conv=d, fa=Fmt(33, 5), fb=Fmt(8, 5)) == 0              # no such format
+    assert need(pkg.CALL_KLD_SEARCH, n=1 << 20, wl_lo=2, wl_hi=32, bins=2048) > need(pkg.CALL_KLD_SEARCH, n=1 << 20, wl_lo=4, wl_hi=16, bins=2048) > 0
+
+    layers = (LayerDesc * 2)(LayerDesc(ConvDesc(4, 8, 8, 4, 8, 3, 3, 1, 1), 1, 1), LayerDesc(ConvDesc(4, 1, 1, 128, 10, 1, 1, 1, 0), 0, 0))
+    w16 = lib.adapt_net_workspace_bytes(layers, 2, 0)
+    w32 = lib.adapt_net_workspace_bytes_wide(layers, 2, 0, 32)
+    assert 0 < w16 < w32 <= 2 * w16 + 4096 and lib.adapt_net_workspace_bytes_wide(layers, 2, 0, 16) == w16
+    assert lib.adapt_net_workspace_bytes_wide(layers, 2, 0, 24) == 0                          # 16 or 32
+    assert lib.adapt_net_workspace_bytes(layers, 2, 4) > w16                                  # the lookback rings
+    bad = (LayerDesc * 2)(layers[0], LayerDesc(ConvDesc(4, 1, 1, 100, 10, 1, 1, 1, 0), 0, 0))  # 128 values do not feed 100 inputs
+    assert lib.adapt_net_workspace_bytes(bad, 2, 0) == 0
+    c = ConvDesc(2, 4, 4, 8, 8, 3, 3, 1, 1)
+    nodes = (NodeDesc * 3)(NodeDesc(c, 1, 0, 1, -1, -1, 0), NodeDesc(c, 1, 0, 1, -1, -1, 0), NodeDesc(c, 1, 0, 1, -1, 0, 1))
+    g16 = lib.adapt_graph_workspace_bytes(nodes, 3, 0)
+    assert 0 < g16 < lib.adapt_graph_workspace_bytes_wide(nodes, 3, 0, 32)
+    assert lib.adapt_bn_state_bytes(64) >= 64 + 64 * 52 and lib.adapt_bn_state_bytes(0) == 0 and lib.adapt_bn_state_bytes(5000) == 0
