@@ -52,6 +52,20 @@ extern "C" int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void
             }
         }
     }
+    if (!planned && wants_cout_pad(d) && d.r * d.s <= 32) {      // output channels not a multiple of 16 (see pad_cout)
+        size_t off = 0;
+        const void *dyp;
+        const size_t rows = (size_t)d.n * ((d.h + 2 * d.pad - d.r) / d.stride + 1) * ((d.w + 2 * d.pad - d.s) / d.stride + 1);
+        aw = ContractArgs{};
+        ad = ContractArgs{};
+        if (pad_cout(ctx, dy, storage_bytes(fdy), rows, d.k, off, &dyp) == ADAPT_OK && fill_wgrad_kpad(aw, d, dyp, fdy, x, fx, dw) == ADAPT_OK &&
+            fill_dgrad_kpad(ad, d, dyp, fdy, w, fw, dx) == ADAPT_OK) {
+            int s = plan_contraction<OP_DGRAD>(ctx, ad, fdy, fw, ep_dx, off, pd);
+            if (s == ADAPT_OK) s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, off, pw);
+            if (s == ADAPT_OK) planned = true;
+            else if (s != ADAPT_EWORKSPACE) return s;
+        }
+    }
     if (!planned) {
         aw = ContractArgs{};
         ad = ContractArgs{};

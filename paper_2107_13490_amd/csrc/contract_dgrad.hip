@@ -33,6 +33,17 @@ extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *d
         }
         a = ContractArgs{};
     }
+    if (wants_cout_pad(d) && d.r * d.s <= 32) {      // output channels not a multiple of 16: dy with zero channels appended
+        size_t off = 0;
+        const void *dyp;
+        if (pad_cout(ctx, dy, storage_bytes(fdy), (size_t)d.n * ((d.h + 2 * d.pad - d.r) / d.stride + 1) * ((d.w + 2 * d.pad - d.s) / d.stride + 1),
+                     d.k, off, &dyp) == ADAPT_OK &&
+            fill_dgrad_kpad(a, d, dyp, fdy, w, fw, dx) == ADAPT_OK) {
+            const int s = run_contraction<OP_DGRAD>(ctx, a, fdy, fw, ep, off);
+            if (s != ADAPT_EWORKSPACE) return s;
+        }
+        a = ContractArgs{};
+    }
     if (int s = fill_dgrad(a, d, dy, fdy, w, fw, dx)) return s;
     return run_contraction<OP_DGRAD>(ctx, a, fdy, fw, ep, 0);
 }

@@ -1613,6 +1613,54 @@ static int pad_channels(adapt_ctx *ctx, const void *src, int es, size_t rows, in
     return ADAPT_OK;
 }
 
+// A classifier has 10 or 100 output channels: the rows of dy are then not a multiple of 16 codes, and both gradient
+// contractions would gather dy element by element.  They run on a copy of dy with zero channels appended up to the
+// next multiple of 16 instead (in the context's workspace): zeros add nothing to the data gradient (the filter rows
+// that would meet them lie beyond the filter tensor and read as zero as well), and the weight gradient keeps its
+// d.k real rows.  Measured on 256 x 512 -> 100, one limb: dgrad 25 -> 9 us, wgrad 30 -> 12 us.
+template <typename T>
+__global__ void __launch_bounds__(256)
+pad_rows_kernel(const T *__restrict__ src, T *__restrict__ dst, const uint64_t chunks, const int c, const int c_to)
+{
+    constexpr int PER = 16 / (int)sizeof(T);                       // codes per 16-byte chunk
+    const int cpr = c_to / PER;                                      // chunks per row
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (uint64_t)gridDim.x * 256) {
+        const uint64_t r = i / (uint64_t)cpr;
+        const int e0 = (int)(i - r * cpr) * PER;
+        T v[PER];
+#pragma unroll
+        for (int e = 0; e < PER; ++e) v[e] = e0 + e < c ? src[r * (uint64_t)c + e0 + e] : (T)0;
+        reinterpret_cast<uint4 *>(dst)[i] = *reinterpret_cast<const uint4 *>(v);
+    }
+}
+
+static inline int round_up16(int k) { return (k + 15) & ~15; }
+
+// Copy of dy [rows][k] with rows of round_up16(k) codes at scratch + off, which is advanced.
+static int pad_cout(adapt_ctx *ctx, const void *dy, int es, size_t rows, int k, size_t &off, const void **out)
+{
+    const int k_to = round_up16(k);
+    const size_t bytes = rows * (size_t)k_to * (size_t)es;
+    off = (off + 255) & ~(size_t)255;
+    if (bytes >= ((size_t)1 << 32) || off + bytes > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    char *dst = scratch(ctx) + off;
+    const uint64_t chunks = bytes / 16;
+    const unsigned grid = (unsigned)std::min<uint64_t>(std::max<uint64_t>((chunks + 255) / 256, 1), (uint64_t)ctx->num_cu * 8);
+    if (es == 1)
+        hipLaunchKernelGGL(pad_rows_kernel<int8_t>, dim3(grid), dim3(256), 0, ctx->stream, static_cast<const int8_t *>(dy),
+                           reinterpret_cast<int8_t *>(dst), chunks, k, k_to);
+    else
+        hipLaunchKernelGGL(pad_rows_kernel<int16_t>, dim3(grid), dim3(256), 0, ctx->stream, static_cast<const int16_t *>(dy),
+                           reinterpret_cast<int16_t *>(dst), chunks, k, k_to);
+    if (hipGetLastError() != hipSuccess) return ADAPT_EHIP;
+    *out = dst;
+    off += bytes;
+    return ADAPT_OK;
+}
+
+// true when the gradient contractions of this layer take the padded copy of dy
+static inline bool wants_cout_pad(const adapt_conv_desc &d) { return d.n > 0 && d.k % 16 != 0 && d.c >= 16 && d.c % 16 == 0; }
+
 static bool epilogue_ok(const adapt_epilogue &ep)
 {
     return ep.raw || (fmt_ok(ep.fmt) && (ep.rng.mode == ADAPT_SR || ep.rng.mode == ADAPT_RN_HALF_UP));
@@ -1728,6 +1776,26 @@ static void unpad_wgrad_finish(ContractPlan &p, const adapt_conv_desc &d)
     p.fin.ldc = p.fin.N;
     p.fin.pad_c = d.c;
     p.fin.pad_to = kPadC;
+}
+
+// The gradient contractions on dy with zero channels appended (see pad_cout): dyp has rows of round_up16(d.k) codes.
+static int fill_dgrad_kpad(ContractArgs &a, const adapt_conv_desc &d, const void *dyp, adapt_fmt fdy, const void *w, adapt_fmt fw, void *dx)
+{
+    adapt_conv_desc d2 = d;
+    d2.k = round_up16(d.k);
+    if (int s = fill_dgrad(a, d2, dyp, fdy, w, fw, dx)) return s;
+    a.wgt_bytes = (uint32_t)((long long)d.k * d.r * d.s * d.c * a.wgt_es);      // the filter rows of the appended channels read as zero
+    a.k_bound = d.r * d.s * d.k;       // the caller's accumulator type follows the logical reduction length
+    return ADAPT_OK;
+}
+
+static int fill_wgrad_kpad(ContractArgs &a, const adapt_conv_desc &d, const void *dyp, adapt_fmt fdy, const void *x, adapt_fmt fx, void *dw)
+{
+    adapt_conv_desc d2 = d;
+    d2.k = round_up16(d.k);
+    if (int s = fill_wgrad(a, d2, dyp, fdy, x, fx, dw)) return s;
+    a.M = d.k;                         // dw keeps its real rows; the appended ones are never written
+    return ADAPT_OK;
 }
 
 static void fill_gemm(ContractArgs &a, int transA, int transB, int M, int N, int K, const void *A, adapt_fmt fa, int lda,

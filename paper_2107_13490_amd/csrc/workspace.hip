@@ -19,6 +19,7 @@ size_t conv_need(adapt_ctx *dry, int call, const adapt_conv_desc &d, adapt_fmt f
     const size_t big = (size_t)1 << 62;
     const bool narrow = d.c < kPadC && d.n > 0;
     const size_t x_rows = (size_t)d.n * d.h * d.w, w_rows = (size_t)d.k * d.r * d.s;
+    const size_t dy_rows = (size_t)d.n * ((d.h + 2 * d.pad - d.r) / d.stride + 1) * ((d.w + 2 * d.pad - d.s) / d.stride + 1);
     ContractArgs a = {};
     ContractPlan p;
     size_t need = 0;
@@ -38,6 +39,9 @@ size_t conv_need(adapt_ctx *dry, int call, const adapt_conv_desc &d, adapt_fmt f
             if (call == ADAPT_CALL_CONV_BACKWARD) off = pad_bytes(0, x_rows, storage_bytes(fc));
             off = pad_bytes(off, w_rows, storage_bytes(fb));
             if (fill_dgrad_padded(a, d, nullptr, fa, nullptr, fb, nullptr) != ADAPT_OK) return kInvalid;
+        } else if (wants_cout_pad(d) && d.r * d.s <= 32) {   // the copy of dy with zero channels appended, then the plan on it
+            off = a256(0) + dy_rows * (size_t)round_up16(d.k) * storage_bytes(fa);
+            if (fill_dgrad_kpad(a, d, nullptr, fa, nullptr, fb, nullptr) != ADAPT_OK) return kInvalid;
         } else if (fill_dgrad(a, d, nullptr, fa, nullptr, fb, nullptr) != ADAPT_OK) return kInvalid;
         if (plan_contraction<OP_DGRAD>(dry, a, fa, fb, ep, off, p, big) != ADAPT_OK) return kInvalid;
         need = std::max(need, p.ws_end);
@@ -50,6 +54,9 @@ size_t conv_need(adapt_ctx *dry, int call, const adapt_conv_desc &d, adapt_fmt f
             off = pad_bytes(0, x_rows, storage_bytes(fx));
             if (call == ADAPT_CALL_CONV_BACKWARD) off = pad_bytes(off, w_rows, storage_bytes(fb));
             if (fill_wgrad_padded(a, d, nullptr, fa, nullptr, fx, nullptr) != ADAPT_OK) return kInvalid;
+        } else if (wants_cout_pad(d) && (call == ADAPT_CALL_CONV_WGRAD || d.r * d.s <= 32)) {
+            off = a256(0) + dy_rows * (size_t)round_up16(d.k) * storage_bytes(fa);
+            if (fill_wgrad_kpad(a, d, nullptr, fa, nullptr, fx, nullptr) != ADAPT_OK) return kInvalid;
         } else if (fill_wgrad(a, d, nullptr, fa, nullptr, fx, nullptr) != ADAPT_OK) return kInvalid;
         if (plan_contraction<OP_WGRAD>(dry, a, fa, fx, ep, off, p, big) != ADAPT_OK) return kInvalid;
         need = std::max(need, p.ws_end);

@@ -189,6 +189,31 @@ def test_conv_mixed_word_lengths(case):
     _conv_all(case, 16, 8, 9)
 
 
+COUT_CASES = [(3, 6, 6, 32, 10, 3, 3, 1, 1), (2, 8, 8, 16, 100, 3, 3, 2, 1), (5, 1, 1, 4096, 10, 1, 1, 1, 0), (2, 5, 7, 64, 17, 1, 1, 1, 0),
+              (2, 6, 6, 16, 130, 3, 3, 1, 1), (300, 1, 1, 512, 100, 1, 1, 1, 0), (2, 9, 9, 32, 24, 5, 5, 2, 2)]
+
+
+@pytest.mark.parametrize("case", COUT_CASES)
+@pytest.mark.parametrize("wl", [8, 12, 16])
+def test_output_channels_that_are_not_a_multiple_of_sixteen(case, wl):
+    """The gradient contractions read dy through a copy with zero channels appended; results and rounding indices
+    are those of the plain definition."""
+    n, h, w, c, k, r, s, st, pad = case
+    d = ConvDesc(n, h, w, c, k, r, s, st, pad)
+    x, wt, dy = codes((n, h, w, c), wl, 1, True), codes((k, r, s, c), wl, 2, True), codes((n, d.p, d.q, k), wl, 3, True)
+    dx_ref, dw_ref = co.conv_dgrad(dy, wt, h, w, st, pad), co.conv_wgrad(dy, x, r, s, st, pad)
+    f = (wl, 4)
+    dx = ctx().conv_dgrad(d, to_dev(dy), f, to_dev(wt), f, Epilogue.exact())
+    dw = ctx().conv_wgrad(d, to_dev(dy), f, to_dev(x), f, Epilogue.exact())
+    assert np.array_equal(host(dx).astype(np.int64), dx_ref) and np.array_equal(host(dw).astype(np.int64), dw_ref)
+    bx, bw = ctx().conv_backward(d, to_dev(dy), f, to_dev(wt), f, to_dev(x), f, Epilogue.exact(), Epilogue.exact())
+    assert np.array_equal(host(bx).astype(np.int64), dx_ref) and np.array_equal(host(bw).astype(np.int64), dw_ref)
+    ep1, ep2 = Epilogue.requant(wl, 2, pkg.SR, seed=4, stream=21), Epilogue.requant(wl, 0, pkg.SR, seed=4, stream=22)
+    bx, bw = ctx().conv_backward(d, to_dev(dy), f, to_dev(wt), f, to_dev(x), f, ep1, ep2)
+    assert np.array_equal(host(bx).astype(np.int64), orc.requantize(dx_ref, 6, wl, orc.SR, 4, 21))
+    assert np.array_equal(host(bw).astype(np.int64), orc.requantize(dw_ref, 8, wl, orc.SR, 4, 22))
+
+
 def _layer_codes(L):
     qx, _, _ = orc.quantize(L.x, L.wl, L.fl, orc.SR, 0, 1)
     qw, _, _ = orc.quantize(L.w, L.wl, L.fl, orc.SR, 0, 2)
