@@ -511,7 +511,7 @@ def chained_step(ctx, pkg, torch, batch=128):
 
     # the precision switch between backward pass and update: wall time of the call, over a few real steps so that
     # windows fill and switches occur
-    sw_ms, switched = [], 0
+    sw_ms, quiet_ms, switched = [], [], 0
     for step in range(8):
         net.forward(x)
         net.backward(dl, 0)
@@ -519,6 +519,8 @@ def chained_step(ctx, pkg, torch, batch=128):
         t0 = time.perf_counter()
         rep, _ = net.precision_switch(2.0 - 0.1 * step, stream=100 * step)
         sw_ms.append((time.perf_counter() - t0) * 1e3)
+        if not any(r.switched for r in rep):
+            quiet_ms.append(sw_ms[-1])             # no layer switched: diversities, lookback and resolution only
         switched += sum(r.switched for r in rep)
         net.update(0.01, 1e-5, 1e-4, stream=100 * step)
     torch.cuda.synchronize()
@@ -526,6 +528,7 @@ def chained_step(ctx, pkg, torch, batch=128):
     res = {"workload": f"AlexNet-CIFAR chain, batch {batch}, formats of configs[3]", "formats": fmts,
            "forward_ms": t_f, "forward_backward_ms": t_fb, "step_ms": t_all, "useful_TOPS": ops / (t_all * 1e-3) / 1e12,
            "precision_switch_ms_median": sorted(sw_ms)[len(sw_ms) // 2], "precision_switch_ms_max": max(sw_ms),
+           "precision_switch_ms_when_no_layer_switches": (sorted(quiet_ms)[len(quiet_ms) // 2] if quiet_ms else None),
            "layers_switched_in_8_steps": int(switched),
            "formats_after": [(r.wl, r.fl) for r in rep]}
     net.close()

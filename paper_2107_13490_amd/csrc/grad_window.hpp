@@ -9,6 +9,7 @@
 namespace adapt {
 
 constexpr int kGdMaxTensors = 64;
+constexpr int kGdMaxLayers = 64;         // layers of a chained step
 
 // what the kernels read: tensors oldest first, each with its alignment to the finest grid
 struct GradWindow {

@@ -60,14 +60,12 @@ __device__ __forceinline__ void unpack16(const gd_v4u (&raw)[2], int es, int (&c
 // low / high 32-bit halves of (aligned element sum)^2
 // BYPTR: the window description lies in device memory (written by chain_prep_kernel) instead of the
 // kernel arguments
-template <bool BYPTR>
-__global__ void __launch_bounds__(kGdThreads)
-gd_partial_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, uint32_t n, uint64_t *partial)
+// blk of nblk: this block's place among the blocks of the tensor (a chained step runs all layers in one launch)
+__device__ __forceinline__ void gd_partial_body(const GradWindow &w, uint32_t n, uint64_t *partial, const uint32_t blk, const uint32_t nblk)
 {
-    const GradWindow &w = BYPTR ? *wp : wv;
     __shared__ uint64_t wave_part[kGdThreads / kWave][kGdMaxTensors + 2];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const uint32_t e0 = (blockIdx.x * kGdThreads + threadIdx.x) * kGdPerThread;
+    const uint32_t e0 = (blk * kGdThreads + threadIdx.x) * kGdPerThread;
     int S[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) S[j] = 0;
@@ -129,17 +127,21 @@ gd_partial_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, uint32
         uint64_t v = 0;
 #pragma unroll
         for (int i = 0; i < kGdThreads / kWave; ++i) v += wave_part[i][col];
-        partial[(size_t)col * gridDim.x + blockIdx.x] = v;
+        partial[(size_t)col * nblk + blk] = v;
     }
 }
 
-// One block: column sums (one wavefront per column at a time), then the norms and the ratio.
 template <bool BYPTR>
-__global__ void __launch_bounds__(kGdFinalThreads)
-gd_final_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const uint64_t *__restrict__ partial, int nblocks,
-                uint64_t *sums_out, double *out)
+__global__ void __launch_bounds__(kGdThreads)
+gd_partial_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, uint32_t n, uint64_t *partial)
 {
-    const GradWindow &w = BYPTR ? *wp : wv;
+    gd_partial_body(BYPTR ? *wp : wv, n, partial, blockIdx.x, gridDim.x);
+}
+
+// One block: column sums (one wavefront per column at a time), then the norms and the ratio.
+__device__ __forceinline__ void gd_final_body(const GradWindow &w, const uint64_t *__restrict__ partial, int nblocks, uint64_t *sums_out,
+                                              double *out)
+{
     __shared__ uint64_t col_sum[kGdMaxTensors + 2];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     for (int col = wave; col < w.count + 2; col += kGdFinalThreads / kWave) {
@@ -169,6 +171,14 @@ gd_final_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const ui
     const double ds = den > 0.0 ? num / den : (num > 0.0 ? (double)INFINITY : (double)NAN);
     out[0] = ds;
     out[1] = (ds > 0.0 && ds < (double)INFINITY) ? log(ds) : 1.0;
+}
+
+template <bool BYPTR>
+__global__ void __launch_bounds__(kGdFinalThreads)
+gd_final_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const uint64_t *__restrict__ partial, int nblocks,
+                uint64_t *sums_out, double *out)
+{
+    gd_final_body(BYPTR ? *wp : wv, partial, nblocks, sums_out, out);
 }
 
 // ---- windows that hold int32 codes (word lengths 17..32) --------------------------------------------------------
@@ -203,14 +213,12 @@ __device__ __forceinline__ void load16_any(const void *g, int es, uint32_t n, ui
     }
 }
 
-template <bool BYPTR>
-__global__ void __launch_bounds__(kGdThreads)
-gd_partial_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, uint32_t n, uint64_t *partial)
+__device__ __forceinline__ void gd_partial_wide_body(const GradWindow &w, uint32_t n, uint64_t *partial, const uint32_t blk,
+                                                     const uint32_t nblk)
 {
-    const GradWindow &w = BYPTR ? *wp : wv;
     __shared__ unsigned long long wave_part[kGdThreads / kWave][kGdMaxTensors + 1][2];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const uint32_t e0 = (blockIdx.x * kGdThreads + threadIdx.x) * kGdPerThread;
+    const uint32_t e0 = (blk * kGdThreads + threadIdx.x) * kGdPerThread;
     long long S[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) S[j] = 0;
@@ -242,18 +250,22 @@ gd_partial_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, u
         u128 v = 0;
 #pragma unroll
         for (int i = 0; i < kGdThreads / kWave; ++i) v += ((u128)wave_part[i][col][1] << 64) | wave_part[i][col][0];
-        uint64_t *dst = partial + 2 * ((size_t)col * gridDim.x + blockIdx.x);
+        uint64_t *dst = partial + 2 * ((size_t)col * nblk + blk);
         dst[0] = (uint64_t)v;
         dst[1] = (uint64_t)(v >> 64);
     }
 }
 
 template <bool BYPTR>
-__global__ void __launch_bounds__(kGdFinalThreads)
-gd_final_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const uint64_t *__restrict__ partial, int nblocks,
-                     uint64_t *sums_out, double *out)
+__global__ void __launch_bounds__(kGdThreads)
+gd_partial_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, uint32_t n, uint64_t *partial)
 {
-    const GradWindow &w = BYPTR ? *wp : wv;
+    gd_partial_wide_body(BYPTR ? *wp : wv, n, partial, blockIdx.x, gridDim.x);
+}
+
+__device__ __forceinline__ void gd_final_wide_body(const GradWindow &w, const uint64_t *__restrict__ partial, int nblocks,
+                                                   uint64_t *sums_out, double *out)
+{
     __shared__ unsigned long long col_sum[kGdMaxTensors + 1][2];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     for (int col = wave; col < w.count + 1; col += kGdFinalThreads / kWave) {
@@ -277,7 +289,46 @@ gd_final_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, con
     out[1] = (ds > 0.0 && ds < (double)INFINITY) ? log(ds) : 1.0;
 }
 
+template <bool BYPTR>
+__global__ void __launch_bounds__(kGdFinalThreads)
+gd_final_wide_kernel(const GradWindow wv, const GradWindow *__restrict__ wp, const uint64_t *__restrict__ partial, int nblocks,
+                     uint64_t *sums_out, double *out)
+{
+    gd_final_wide_body(BYPTR ? *wp : wv, partial, nblocks, sums_out, out);
+}
+
 size_t ws_need_gradient_diversity(uint64_t n, int count);
+
+// All layers of a chained step in one launch per phase: the blocks of layer l are [first[l], first[l + 1]), its
+// partial sums start part_off[l] words into the scratch.
+struct ChainGeo {
+    uint32_t first[kGdMaxLayers + 1];
+    uint32_t n[kGdMaxLayers];
+    uint64_t part_off[kGdMaxLayers];
+    uint8_t wide[kGdMaxLayers];
+    int nlayers;
+};
+
+__global__ void __launch_bounds__(kGdThreads)
+gd_partial_chain_kernel(const ChainGeo geo, const GradWindow *__restrict__ win, uint64_t *partial)
+{
+    // the layer this block belongs to: every lane compares one table entry, the wavefront votes
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t first = lane < geo.nlayers ? geo.first[lane] : 0xffffffffu;
+    const int l = __popcll(__ballot(blockIdx.x >= first)) - 1;
+    const uint32_t blk = blockIdx.x - geo.first[l], nblk = geo.first[l + 1] - geo.first[l];
+    if (geo.wide[l]) gd_partial_wide_body(win[l], geo.n[l], partial + geo.part_off[l], blk, nblk);
+    else gd_partial_body(win[l], geo.n[l], partial + geo.part_off[l], blk, nblk);
+}
+
+__global__ void __launch_bounds__(kGdFinalThreads)
+gd_final_chain_kernel(const ChainGeo geo, const GradWindow *__restrict__ win, const uint64_t *__restrict__ partial, ChainLayerOut *out)
+{
+    const int l = blockIdx.x;
+    const int nblk = (int)(geo.first[l + 1] - geo.first[l]);
+    if (geo.wide[l]) gd_final_wide_body(win[l], partial + geo.part_off[l], nblk, nullptr, &out[l].ds);
+    else gd_final_body(win[l], partial + geo.part_off[l], nblk, nullptr, &out[l].ds);
+}
 
 // One thread per layer of a chained step: the exponent of this batch's gradient lies in device memory (the fitting
 // pass of the backward pass wrote it), so the window can be laid out without the host reading it first.  The aligned
@@ -331,30 +382,31 @@ int gradient_diversity_chain(adapt_ctx *ctx, const ChainLayerIn *in, int nlayers
                              GradWindow *win, ChainLayerOut *out)
 {
     if (nlayers < 1) return ADAPT_EINVAL;
-    size_t need = 0;
+    if (nlayers > kGdMaxLayers) return ADAPT_EUNSUPPORTED;
+    const size_t per_block = (size_t)kGdThreads * kGdPerThread;
+    ChainGeo geo = {};
+    geo.nlayers = nlayers;
+    size_t words = 0;
+    uint64_t blocks = 0;
     for (int l = 0; l < nlayers; ++l) {
         if (in[l].count < 1 || in[l].count > kGdMaxTensors || n[l] > ((size_t)1 << 30)) return ADAPT_EUNSUPPORTED;
-        need = std::max(need, ws_need_gradient_diversity(n[l], in[l].count));
-    }
-    if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
-    uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
-    hipLaunchKernelGGL(chain_prep_kernel, dim3(1), dim3(64), 0, ctx->stream, in, nlayers, e_g, e_stride, win, out);
-    const size_t per_block = (size_t)kGdThreads * kGdPerThread;
-    const GradWindow none = {};
-    for (int l = 0; l < nlayers; ++l) {
-        const int grid = (int)std::max<size_t>(1, (n[l] + per_block - 1) / per_block);
         bool wide = false;
         for (int k = 0; k < in[l].count; ++k) wide = wide || in[l].wl[k] > 16;
-        if (wide) {
-            hipLaunchKernelGGL(gd_partial_wide_kernel<true>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, none, win + l, (uint32_t)n[l], partial);
-            hipLaunchKernelGGL(gd_final_wide_kernel<true>, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, none, win + l, partial, grid,
-                               nullptr, &out[l].ds);
-            continue;
-        }
-        hipLaunchKernelGGL(gd_partial_kernel<true>, dim3(grid), dim3(kGdThreads), 0, ctx->stream, none, win + l, (uint32_t)n[l], partial);
-        hipLaunchKernelGGL(gd_final_kernel<true>, dim3(1), dim3(kGdFinalThreads), 0, ctx->stream, none, win + l, partial, grid,
-                           nullptr, &out[l].ds);
+        const uint64_t grid = std::max<size_t>(1, (n[l] + per_block - 1) / per_block);
+        geo.first[l] = (uint32_t)blocks;
+        geo.n[l] = (uint32_t)n[l];
+        geo.part_off[l] = words;
+        geo.wide[l] = wide;
+        blocks += grid;
+        words += ws_need_gradient_diversity(n[l], in[l].count) / sizeof(uint64_t);
     }
+    geo.first[nlayers] = (uint32_t)blocks;
+    if (blocks >= ((uint64_t)1 << 31)) return ADAPT_EUNSUPPORTED;
+    if (words * sizeof(uint64_t) > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    uint64_t *partial = reinterpret_cast<uint64_t *>(scratch(ctx));
+    hipLaunchKernelGGL(chain_prep_kernel, dim3(1), dim3(64), 0, ctx->stream, in, nlayers, e_g, e_stride, win, out);
+    hipLaunchKernelGGL(gd_partial_chain_kernel, dim3((unsigned)blocks), dim3(kGdThreads), 0, ctx->stream, geo, win, partial);
+    hipLaunchKernelGGL(gd_final_chain_kernel, dim3(nlayers), dim3(kGdFinalThreads), 0, ctx->stream, geo, win, partial, out);
     return hip_status(ctx, hipGetLastError());
 }
 
