@@ -200,9 +200,11 @@ sum_partials_kernel(const uint32_t *__restrict__ partial, int nblocks, int cols,
                     const float *__restrict__ range_partial = nullptr /* [rcols][nblocks]: even columns min, odd max */,
                     int rcols = 0, float *range_out = nullptr)
 {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    // a column per wavefront; several blocks share the columns of a batched call
+    const int lane = threadIdx.x & (kWave - 1), wave = blockIdx.x * (kSumThreads / kWave) + threadIdx.x / kWave;
+    const int nwaves = gridDim.x * (kSumThreads / kWave);
     // range columns are taken by the last wavefronts so that they run beside the counter columns
-    for (int j = kSumThreads / kWave - 1 - wave; j < rcols; j += kSumThreads / kWave) {
+    for (int j = nwaves - 1 - wave; j < rcols; j += nwaves) {
         const float *col = range_partial + (size_t)j * nblocks;
         const bool is_min = (j & 1) == 0;
         float v = is_min ? INFINITY : -INFINITY;
@@ -219,7 +221,7 @@ sum_partials_kernel(const uint32_t *__restrict__ partial, int nblocks, int cols,
         if (lane == 0) range_out[j] = v;
     }
     if (out0 == nullptr) return;
-    for (int j = wave; j < cols; j += kSumThreads / kWave) {
+    for (int j = wave; j < cols; j += nwaves) {
         const uint32_t *col = partial + (size_t)j * nblocks;
         uint64_t sum = 0;
         int b = lane;
@@ -450,8 +452,11 @@ extern "C" int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantiz
         float *range_partial = ranges ? reinterpret_cast<float *>(scratch(ctx) + part_bytes) : nullptr;
         hipLaunchKernelGGL(quantize_batched_kernel, dim3((unsigned)grid), dim3(kQThreads), 0, ctx->stream, batch, mode,
                            seed, partial, range_partial, range_mask >> base);
+        // one wavefront per column: enough blocks for all the columns of the batch to run side by side
+        const int sum_cols = (counters ? 2 * batch.count : 0) + (ranges ? 2 * batch.count : 0);
+        const int sum_blocks = std::min(std::max((sum_cols + kSumThreads / kWave - 1) / (kSumThreads / kWave), 1), 16);
         if (counters || ranges)
-            hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(kSumThreads), 0, ctx->stream, partial, (int)grid,
+            hipLaunchKernelGGL(sum_partials_kernel, dim3(sum_blocks), dim3(kSumThreads), 0, ctx->stream, partial, (int)grid,
                                2 * batch.count, counters ? counters + 2 * base : (uint64_t *)nullptr, (uint64_t *)nullptr,
                                range_partial, ranges ? 2 * batch.count : 0, ranges ? ranges + 2 * base : (float *)nullptr);
     }
