@@ -28,6 +28,7 @@
 #include "common.hpp"
 #include "context.hpp"
 #include "fit.hpp"
+#include "update_batch.hpp"
 #include "wide.hpp"
 
 // every fp64 operation of the coefficient kernels is rounded on its own: no fused multiply-adds
@@ -525,8 +526,8 @@ gap_bwd_wide_kernel(const int32_t *__restrict__ dout, int32_t *__restrict__ da, 
 }
 
 // ---- update of gamma and beta -------------------------------------------------------------------------------
-__global__ void __launch_bounds__(1024)
-bn_update_kernel(float *gamma, float *beta, const double *__restrict__ dgamma, const double *__restrict__ dbeta, int channels, float lr)
+__device__ __forceinline__ void bn_update_body(float *gamma, float *beta, const double *__restrict__ dgamma,
+                                               const double *__restrict__ dbeta, int channels, float lr)
 {
     // the squares are formed by all threads, a chunk at a time; the two sums run in channel order (the order fixes
     // the rounding) on one lane each
@@ -559,6 +560,22 @@ bn_update_kernel(float *gamma, float *beta, const double *__restrict__ dgamma, c
         if (nrm[0] > 0.0 && nrm[0] < (double)INFINITY) gamma[k] = __builtin_fmaf(-lr, (float)((dgamma[k]) / (nrm[0])), gamma[k]);
         if (nrm[1] > 0.0 && nrm[1] < (double)INFINITY) beta[k] = __builtin_fmaf(-lr, (float)((dbeta[k]) / (nrm[1])), beta[k]);
     }
+}
+
+__global__ void __launch_bounds__(1024)
+bn_update_kernel(float *gamma, float *beta, const double *__restrict__ dgamma, const double *__restrict__ dbeta, int channels, float lr)
+{
+    bn_update_body(gamma, beta, dgamma, dbeta, channels, lr);
+}
+
+// block t: layer t of a chained step
+struct BnUpdateBatch {
+    BnUpdateItem item[kUpdateMaxItems];
+};
+__global__ void __launch_bounds__(1024) bn_update_batch_kernel(const BnUpdateBatch b, float lr)
+{
+    const BnUpdateItem &it = b.item[blockIdx.x];
+    bn_update_body(it.gamma, it.beta, it.dgamma, it.dbeta, it.channels, lr);
 }
 
 // ---- global average pooling ----------------------------------------------------------------------------------
@@ -925,6 +942,25 @@ extern "C" int adapt_bn_update(adapt_ctx *ctx, float *gamma, float *beta, const 
     hipLaunchKernelGGL(bn_update_kernel, dim3(1), dim3(1024), 0, ctx->stream, gamma, beta, dgamma, dbeta, channels, (float)lr);
     return hip_status(ctx, hipGetLastError());
 }
+
+namespace adapt {
+int bn_update_batch(adapt_ctx *ctx, const BnUpdateItem *items, int count, double lr)
+{
+    if (!ctx || count < 0 || (count > 0 && !items) || !(lr == lr)) return ADAPT_EINVAL;
+    for (int t = 0; t < count; ++t) {
+        const BnUpdateItem &it = items[t];
+        if (!it.gamma || !it.beta || !it.dgamma || !it.dbeta || it.channels < 1 || it.channels > kBnMaxChannels) return ADAPT_EINVAL;
+        if (((uintptr_t)it.dgamma & 7) || ((uintptr_t)it.dbeta & 7)) return ADAPT_EINVAL;
+    }
+    for (int base = 0; base < count; base += kUpdateMaxItems) {
+        BnUpdateBatch b;
+        const int m = std::min(count - base, kUpdateMaxItems);
+        for (int t = 0; t < m; ++t) b.item[t] = items[base + t];
+        hipLaunchKernelGGL(bn_update_batch_kernel, dim3(m), dim3(1024), 0, ctx->stream, b, (float)lr);
+    }
+    return hip_status(ctx, hipGetLastError());
+}
+}  // namespace adapt
 
 extern "C" int adapt_gap_fwd(adapt_ctx *ctx, const void *a, adapt_fmt f, int n, int hw, int c, adapt_rng rng, void *out)
 {

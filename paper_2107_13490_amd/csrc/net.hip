@@ -24,6 +24,7 @@
 #include "context.hpp"
 #include "fit.hpp"
 #include "grad_window.hpp"
+#include "update_batch.hpp"
 #include "wide.hpp"
 
 namespace adapt {
@@ -1121,20 +1122,55 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
     if (!net || !rng_ok(rng)) return ADAPT_EINVAL;
     const int count = (int)net->L.size();
     for (int l = 0; l < count; ++l) {
+        net->L[l].range_valid = false;
+        if (net->L[l].g_wl == 0) return ADAPT_EINVAL;                // no backward pass yet
+    }
+    // gamma and beta of every normalisation layer in one launch
+    std::vector<BnUpdateItem> bn_items;
+    for (int l = 0; l < count; ++l) {
         NetLayer &y = net->L[l];
-        y.range_valid = false;
         if (y.bn)
-            if (int s = adapt_bn_update(net->ctx, y.gamma, y.beta, reinterpret_cast<const double *>(net->ws + y.off_dgam),
-                                        reinterpret_cast<const double *>(net->ws + y.off_dbet), y.d.conv.k, opt.lr))
-                return s;
+            bn_items.push_back(BnUpdateItem{y.gamma, y.beta, reinterpret_cast<const double *>(net->ws + y.off_dgam),
+                                            reinterpret_cast<const double *>(net->ws + y.off_dbet), y.d.conv.k});
+    }
+    if (int s = bn_update_batch(net->ctx, bn_items.data(), (int)bn_items.size(), opt.lr)) return s;
+    // the weights: every layer whose gradient and weight codes have at most 16 bits in one batched launch pair, the
+    // others (and all of them when the context's scratch is too small for the batch) one call each
+    std::vector<SgdBatchItem> items;
+    std::vector<int> single;
+    for (int l = 0; l < count; ++l) {
+        NetLayer &y = net->L[l];
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
-        if (y.g_wl == 0) return ADAPT_EINVAL;                        // no backward pass yet
+        if (y.g_wl > 16 || y.fmt.wl > 16) {
+            single.push_back(l);
+            continue;
+        }
+        const adapt_rng r = slot_rng(rng, l, 3);
+        SgdBatchItem it = {};
+        it.w = y.w; it.g = net->ws + y.g_off(); it.q = net->ws + y.off_qw; it.g_sumsq = &st->g_sumsq; it.n = y.n_w;
+        it.seed = r.seed; it.stream = r.stream; it.counters = &st->nnz; it.range = &st->range_lo;
+        it.es_g = (int8_t)(y.g_wl <= 8 ? 1 : 2); it.es_q = (int8_t)(y.fmt.wl <= 8 ? 1 : 2); it.fl_g = 0;
+        it.wl = (int8_t)y.fmt.wl; it.fl = (int8_t)y.fmt.fl;
+        items.push_back(it);
+    }
+    if (!items.empty()) {
+        const int s = sgd_update_batch(net->ctx, items.data(), (int)items.size(), opt, rng.mode);
+        if (s == ADAPT_EWORKSPACE) {
+            single.clear();
+            for (int l = 0; l < count; ++l) single.push_back(l);
+        } else if (s) {
+            return s;
+        }
+    }
+    for (int l : single) {
+        NetLayer &y = net->L[l];
+        adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
         const adapt_fmt fg = {y.g_wl, 0};                            // the gradient keeps the word length it was made with
         if (int s = adapt_sgd_update_quantize(net->ctx, y.w, y.n_w, net->ws + y.g_off(), fg, &st->g_sumsq, opt, y.fmt,
                                               slot_rng(rng, l, 3), net->ws + y.off_qw, &st->nnz, &st->range_lo))
             return s;
-        y.range_valid = true;
     }
+    for (int l = 0; l < count; ++l) net->L[l].range_valid = true;
     net->forward_done = net->backward_done = false;
     return ADAPT_OK;
 }

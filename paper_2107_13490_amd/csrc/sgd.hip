@@ -8,10 +8,12 @@
 // quantize it to <WL,FL> with the Sec. 3.2 rule, count non-zero and saturated codes and track the
 // finite range of w' for the next precision search.  10-12 bytes of HBM traffic per element
 // instead of the 18 of separate update, range and quantize passes.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.hpp"
 #include "context.hpp"
+#include "update_batch.hpp"
 #include "wide.hpp"
 
 namespace adapt {
@@ -40,10 +42,11 @@ __device__ __forceinline__ float sgd_one(float w, int c, float step, float lr, f
     return __builtin_fmaf(-lr, d, w1);
 }
 
-// counts[2][grid] (nnz, saturated) and range[grid][2] (min, max of the finite new weights)
+// One tensor's share of a block: groups first, first + stride, ...; the thread with first == 0 also takes the ragged
+// tail.  Adds to the caller's counters and range.
 template <typename GT, typename OutT>
-__global__ void __launch_bounds__(kSgdThreads)
-sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
+__device__ __forceinline__ void sgd_span(const SgdArgs &a, uint64_t first, uint64_t stride, uint32_t &nnz, uint32_t &nsat, float &lo,
+                                         float &hi)
 {
     float step;
     if (a.g_sumsq != nullptr) {
@@ -58,8 +61,6 @@ sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
     const GT *g = static_cast<const GT *>(a.g);
     OutT *q = static_cast<OutT *>(a.q);
     float4 *w4 = reinterpret_cast<float4 *>(a.w);
-    uint32_t nnz = 0, nsat = 0;
-    float lo = INFINITY, hi = -INFINITY;
 
     auto one = [&](float w, int c, uint32_t r, int &code) {
         const float wn = sgd_one(w, c, step, lr, a.l1, a.l2);
@@ -73,8 +74,6 @@ sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
     };
 
     const uint64_t full_groups = a.n >> 3;
-    const uint64_t first = (uint64_t)blockIdx.x * kSgdThreads + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * kSgdThreads;
     for (uint64_t grp = first; grp < full_groups; grp += stride) {
         const float4 x0 = w4[2 * grp], x1 = w4[2 * grp + 1];
         int c[8];
@@ -104,9 +103,14 @@ sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
             q[i] = (OutT)code;
         }
     }
+}
 
-    __shared__ uint32_t sc[2][kSgdThreads / kWave];
-    __shared__ float sr[2][kSgdThreads / kWave];
+// The block's totals of the four per-thread values: counts[block] = nnz, counts[nblocks + block] = saturated,
+// range[2 block] = min, range[2 block + 1] = max (one barrier; the shared arrays may be reused after the next one)
+__device__ __forceinline__ void sgd_block_partials(uint32_t nnz, uint32_t nsat, float lo, float hi, uint32_t *counts, float *range,
+                                                   uint32_t block, uint32_t nblocks, uint32_t (*sc)[kSgdThreads / kWave],
+                                                   float (*sr)[kSgdThreads / kWave])
+{
     nnz = wave_sum_u32(nnz);
     nsat = wave_sum_u32(nsat);
     lo = wave_min_f32(lo);
@@ -120,17 +124,70 @@ sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
             nnz += sc[0][i]; nsat += sc[1][i];
             lo = fminf(lo, sr[0][i]); hi = fmaxf(hi, sr[1][i]);
         }
-        counts[blockIdx.x] = nnz;
-        counts[gridDim.x + blockIdx.x] = nsat;
-        range[2 * blockIdx.x] = lo;
-        range[2 * blockIdx.x + 1] = hi;
+        counts[block] = nnz;
+        counts[nblocks + block] = nsat;
+        range[2 * block] = lo;
+        range[2 * block + 1] = hi;
+    }
+}
+
+// counts[2][grid] (nnz, saturated) and range[grid][2] (min, max of the finite new weights)
+template <typename GT, typename OutT>
+__global__ void __launch_bounds__(kSgdThreads)
+sgd_update_quantize_kernel(const SgdArgs a, uint32_t *counts, float *range)
+{
+    __shared__ uint32_t sc[2][kSgdThreads / kWave];
+    __shared__ float sr[2][kSgdThreads / kWave];
+    uint32_t nnz = 0, nsat = 0;
+    float lo = INFINITY, hi = -INFINITY;
+    sgd_span<GT, OutT>(a, (uint64_t)blockIdx.x * kSgdThreads + threadIdx.x, (uint64_t)gridDim.x * kSgdThreads, nnz, nsat, lo, hi);
+    sgd_block_partials(nnz, nsat, lo, hi, counts, range, blockIdx.x, gridDim.x, sc, sr);
+}
+
+// Several layers per launch.  Blocks are dealt to the tensors round-robin, tensor t starting where tensor t-1 ended,
+// so that small tensors do not all land on block 0; every block writes its partials of every tensor (neutral values
+// where it had no share), tensor t's at counts + 2 t grid and range + 2 t grid, laid out as above.
+struct SgdBatch {
+    SgdBatchItem item[kUpdateMaxItems];
+    int count;
+};
+
+__global__ void __launch_bounds__(kSgdThreads)
+sgd_update_batch_kernel(const SgdBatch batch, double lr, float l1, float l2, int mode, uint32_t *counts, float *range)
+{
+    __shared__ uint32_t sc[2][kSgdThreads / kWave];
+    __shared__ float sr[2][kSgdThreads / kWave];
+    uint32_t rot = 0;
+    for (int t = 0; t < batch.count; ++t) {
+        const SgdBatchItem &it = batch.item[t];
+        const uint64_t groups = (it.n + 7) >> 3;
+        const uint32_t blocks_needed = (uint32_t)min((uint64_t)gridDim.x, max((groups + kSgdThreads - 1) / kSgdThreads, (uint64_t)1));
+        const uint32_t slot = (blockIdx.x + gridDim.x - rot % gridDim.x) % gridDim.x;
+        rot += blocks_needed;
+        uint32_t nnz = 0, nsat = 0;
+        float lo = INFINITY, hi = -INFINITY;
+        if (slot < blocks_needed) {
+            SgdArgs a;
+            a.w = it.w; a.g = it.g; a.q = it.q; a.g_sumsq = it.g_sumsq; a.n = it.n; a.lr = lr; a.l1 = l1; a.l2 = l2;
+            a.fl_g = it.fl_g; a.wl = it.wl; a.fl = it.fl; a.mode = mode; a.seed = it.seed; a.stream = it.stream;
+            const uint64_t first = (uint64_t)slot * kSgdThreads + threadIdx.x, stride = (uint64_t)blocks_needed * kSgdThreads;
+            if (it.es_g == 1) {
+                if (it.es_q == 1) sgd_span<int8_t, int8_t>(a, first, stride, nnz, nsat, lo, hi);
+                else sgd_span<int8_t, int16_t>(a, first, stride, nnz, nsat, lo, hi);
+            } else {
+                if (it.es_q == 1) sgd_span<int16_t, int8_t>(a, first, stride, nnz, nsat, lo, hi);
+                else sgd_span<int16_t, int16_t>(a, first, stride, nnz, nsat, lo, hi);
+            }
+        }
+        sgd_block_partials(nnz, nsat, lo, hi, counts + (size_t)2 * t * gridDim.x, range + (size_t)2 * t * gridDim.x, blockIdx.x,
+                           gridDim.x, sc, sr);
+        __syncthreads();                           // the shared arrays are free again
     }
 }
 
 // one block: totals of the block partials
-__global__ void __launch_bounds__(kSgdFinalThreads)
-sgd_final_kernel(const uint32_t *__restrict__ counts, const float *__restrict__ range, int nblocks, uint64_t *counters,
-                 float *range_out)
+__device__ __forceinline__ void sgd_final_body(const uint32_t *__restrict__ counts, const float *__restrict__ range, int nblocks,
+                                               uint64_t *counters, float *range_out)
 {
     __shared__ uint64_t sc[2][kSgdFinalThreads / kWave];
     __shared__ float sr[2][kSgdFinalThreads / kWave];
@@ -162,11 +219,69 @@ sgd_final_kernel(const uint32_t *__restrict__ counts, const float *__restrict__ 
     }
 }
 
+__global__ void __launch_bounds__(kSgdFinalThreads)
+sgd_final_kernel(const uint32_t *__restrict__ counts, const float *__restrict__ range, int nblocks, uint64_t *counters,
+                 float *range_out)
+{
+    sgd_final_body(counts, range, nblocks, counters, range_out);
+}
+
+// block t: the totals of tensor t of a batched launch
+__global__ void __launch_bounds__(kSgdFinalThreads)
+sgd_final_batch_kernel(const SgdBatch batch, const uint32_t *__restrict__ counts, const float *__restrict__ range, int nblocks)
+{
+    const SgdBatchItem &it = batch.item[blockIdx.x];
+    if (!it.counters && !it.range) return;
+    sgd_final_body(counts + (size_t)2 * blockIdx.x * nblocks, range + (size_t)2 * blockIdx.x * nblocks, nblocks, it.counters, it.range);
+}
+
 size_t ws_need_sgd_update(int num_cu, uint64_t n)
 {
     const uint64_t groups = (n + 7) >> 3;
     const uint64_t blocks = std::min<uint64_t>(std::max<uint64_t>((groups + kSgdThreads - 1) / kSgdThreads, 1), (uint64_t)num_cu * 8);
     return (((size_t)blocks * 8 + 255) & ~(size_t)255) + (size_t)blocks * 8;
+}
+
+int sgd_update_batch(adapt_ctx *ctx, const SgdBatchItem *items, int count, adapt_sgd_params opt, int mode)
+{
+    if (!ctx || count < 0 || (count > 0 && !items) || (mode != ADAPT_SR && mode != ADAPT_RN_HALF_UP)) return ADAPT_EINVAL;
+    if (!(opt.lr == opt.lr) || !(opt.l1 == opt.l1) || !(opt.l2 == opt.l2)) return ADAPT_EINVAL;
+    for (int t = 0; t < count; ++t) {
+        const SgdBatchItem &it = items[t];
+        if ((it.es_g != 1 && it.es_g != 2) || it.wl < 2 || it.wl > 16 || it.es_q != (it.wl <= 8 ? 1 : 2) || it.fl < 0 || it.fl > 31 ||
+            it.n > ((uint64_t)1 << 40))
+            return ADAPT_EINVAL;
+        if (it.n > 0 && (!it.w || !it.g || !it.q || !aligned16(it.w) || !aligned16(it.g) || !aligned16(it.q))) return ADAPT_EINVAL;
+        if (((uintptr_t)it.counters & 7) || ((uintptr_t)it.g_sumsq & 7) || ((uintptr_t)it.range & 3)) return ADAPT_EINVAL;
+    }
+    // the grid of every launch, and the scratch of the largest, before anything is enqueued
+    const uint64_t cap = (uint64_t)ctx->num_cu * 4;
+    size_t need = 0;
+    for (int base = 0; base < count; base += kUpdateMaxItems) {
+        const int m = std::min(count - base, kUpdateMaxItems);
+        uint64_t blocks = 0;
+        for (int t = 0; t < m; ++t) blocks += std::max<uint64_t>((((items[base + t].n + 7) >> 3) + kSgdThreads - 1) / kSgdThreads, 1);
+        const size_t grid = (size_t)std::min(blocks, cap);
+        need = std::max(need, 2 * (((size_t)2 * m * grid * 4 + 255) & ~(size_t)255));
+    }
+    if (need > scratch_bytes(ctx)) return ADAPT_EWORKSPACE;
+    for (int base = 0; base < count; base += kUpdateMaxItems) {
+        SgdBatch batch;
+        batch.count = std::min(count - base, kUpdateMaxItems);
+        uint64_t blocks = 0;
+        for (int t = 0; t < batch.count; ++t) {
+            batch.item[t] = items[base + t];
+            blocks += std::max<uint64_t>((((items[base + t].n + 7) >> 3) + kSgdThreads - 1) / kSgdThreads, 1);
+        }
+        const int grid = (int)std::min(blocks, cap);
+        const size_t part = ((size_t)2 * batch.count * grid * 4 + 255) & ~(size_t)255;
+        uint32_t *counts = reinterpret_cast<uint32_t *>(scratch(ctx));
+        float *range = reinterpret_cast<float *>(scratch(ctx) + part);
+        hipLaunchKernelGGL(sgd_update_batch_kernel, dim3(grid), dim3(kSgdThreads), 0, ctx->stream, batch, opt.lr, (float)opt.l1,
+                           (float)opt.l2, mode, counts, range);
+        hipLaunchKernelGGL(sgd_final_batch_kernel, dim3(batch.count), dim3(kSgdFinalThreads), 0, ctx->stream, batch, counts, range, grid);
+    }
+    return hip_status(ctx, hipGetLastError());
 }
 
 }  // namespace adapt
