@@ -588,11 +588,19 @@ def chained_resnet18(ctx, pkg, torch, batch=256):
         net.backward(dl, 0)
         net.update(0.01, 1e-5, 1e-4)
     t_f, t_fb, t_all = timed(fwd), timed(fwd_bwd), timed(full)
+    # host time to enqueue a step with an idle queue (the device works behind it): below step_ms, the step is bound by the device
+    enq = []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        full()
+        enq.append((time.perf_counter() - t0) * 1e3)
+    torch.cuda.synchronize()
     ops = 2.0 * macs * 3 - 2.0 * graph[0][0].shape.macs               # no data gradient below the first layer
     net.close()
     return {"workload": f"ResNet-18-CIFAR chain (batch norm, shortcuts, average pooling), batch {batch}, formats of configs[4] (WL >= 6)",
             "formats": fmts, "forward_ms": t_f, "forward_backward_ms": t_fb, "step_ms": t_all,
-            "useful_TOPS": ops / (t_all * 1e-3) / 1e12}
+            "host_enqueue_ms": sorted(enq)[len(enq) // 2], "useful_TOPS": ops / (t_all * 1e-3) / 1e12}
 
 
 def main():

@@ -151,41 +151,26 @@ __device__ inline double block_max_f64(double v, double *sm)
     return v;
 }
 
-// Totals of the block partials partial[nparts][width] of a statistics launch: a block takes 8 columns, 32 threads per
-// column each add every 32nd partial (independent loads), LDS combines them.
-__global__ void __launch_bounds__(256)
-bn_total_kernel(const long long *__restrict__ partial, int nparts, int width, long long *__restrict__ totals)
+// The totals may have been written by other blocks of the same launch (the merged totals + coefficients kernels):
+// they are read at device scope, past this compute unit's cache.
+__device__ __forceinline__ long long total_at(const long long *tot, int i)
 {
-    __shared__ long long sm[32][8];
-    const int c = threadIdx.x & 7, rl = threadIdx.x >> 3;
-    const int col = blockIdx.x * 8 + c;
-    long long acc = 0;
-    if (col < width)
-        for (int r = rl; r < nparts; r += 32) acc += partial[(size_t)r * width + col];
-    sm[rl][c] = acc;
-    __syncthreads();
-    if (threadIdx.x < 8 && col < width) {
-        long long t = 0;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) t += sm[i][threadIdx.x];
-        totals[col] = t;
-    }
+    return __hip_atomic_load(tot + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// One block: totals of the block partials, statistics and forward coefficients.
-__global__ void __launch_bounds__(1024)
-bn_coef_fwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int channels, unsigned long long rows, int fl_y, int fl_o,
-                   const float *__restrict__ gamma, const float *__restrict__ beta, double eps, void *state,
-                   const double *__restrict__ s2d = nullptr /* sums of squares beyond 64 bits, as their nearest doubles */)
+// One block: statistics and forward coefficients from the totals.
+__device__ __forceinline__ void bn_coef_fwd_body(const long long *tot /* [2 * channels] */, int channels, unsigned long long rows, int fl_y,
+                                                 int fl_o, const float *__restrict__ gamma, const float *__restrict__ beta, double eps,
+                                                 void *state, const double *__restrict__ s2d)
 {
     __shared__ double sm[16];
     const BnState st = bn_state(state, channels);
     const double m = (double)rows;
     double amax = 0.0;
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
-        const long long s1 = tot[k];
+        const long long s1 = total_at(tot, k);
         const double mean = (double)s1 / m;
-        const double ex2 = (s2d ? s2d[k] : (double)tot[channels + k]) / m;
+        const double ex2 = (s2d ? s2d[k] : (double)total_at(tot, channels + k)) / m;
         const double var = fmax(ex2 - mean * mean, 0.0);
         const double sig = sqrt(var + ldexp(eps, 2 * fl_y));
         const double alpha = ldexp((double)gamma[k], fl_o) / sig;
@@ -207,18 +192,25 @@ bn_coef_fwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int c
     }
 }
 
-// One block: totals of (sum dz, sum dz*y), the parameter gradients and the backward coefficients.
 __global__ void __launch_bounds__(1024)
-bn_coef_bwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int channels, void *state, double *__restrict__ dgamma,
-                   double *__restrict__ dbeta, const double *__restrict__ d2d = nullptr /* sums of products beyond 64 bits */)
+bn_coef_fwd_kernel(const long long *tot, int channels, unsigned long long rows, int fl_y, int fl_o, const float *__restrict__ gamma,
+                   const float *__restrict__ beta, double eps, void *state,
+                   const double *__restrict__ s2d = nullptr /* sums of squares beyond 64 bits, as their nearest doubles */)
+{
+    bn_coef_fwd_body(tot, channels, rows, fl_y, fl_o, gamma, beta, eps, state, s2d);
+}
+
+// One block: from the totals of (sum dz, sum dz*y) the parameter gradients and the backward coefficients.
+__device__ __forceinline__ void bn_coef_bwd_body(const long long *tot /* [2 * channels] */, int channels, void *state,
+                                                 double *__restrict__ dgamma, double *__restrict__ dbeta, const double *__restrict__ d2d)
 {
     __shared__ double sm[16];
     const BnState st = bn_state(state, channels);
     const double m = (double)st.h->rows;
     double pmax = 0.0;
     for (int k = threadIdx.x; k < channels; k += blockDim.x) {
-        const long long d1 = tot[k];
-        const double d2 = d2d ? d2d[k] : (double)tot[channels + k];
+        const long long d1 = total_at(tot, k);
+        const double d2 = d2d ? d2d[k] : (double)total_at(tot, channels + k);
         const double mean = st.mean[k], sig = st.sig[k], alpha = st.alpha[k];
         const double dg = (d2 - mean * (double)d1) / sig;
         const double c1 = (((double)d1) / (m));
@@ -241,6 +233,58 @@ bn_coef_bwd_kernel(const long long *__restrict__ tot /* [2 * channels] */, int c
         st.R[k] = rint_clamped(r, fb, 2305843009213693952.0);
     }
     if (threadIdx.x == 0) st.h->fb = fb;
+}
+
+__global__ void __launch_bounds__(1024)
+bn_coef_bwd_kernel(const long long *tot, int channels, void *state, double *__restrict__ dgamma, double *__restrict__ dbeta,
+                   const double *__restrict__ d2d = nullptr /* sums of products beyond 64 bits */)
+{
+    bn_coef_bwd_body(tot, channels, state, dgamma, dbeta, d2d);
+}
+
+// Totals and coefficients in one launch.  Totals of the block partials partial[nparts][2 * channels] of a statistics
+// launch: a block takes 8 columns, 32 threads per column each add every 32nd partial (independent loads), LDS
+// combines them.  The block that finishes last (a ticket, zero before the launch and zero again after it) goes on
+// with the coefficients.
+struct BnCoefArgs {
+    int channels, fl_y, fl_o;
+    unsigned long long rows;
+    const float *gamma, *beta;
+    double eps;
+    void *state;
+    double *dgamma, *dbeta;
+};
+
+template <bool BWD>
+__global__ void __launch_bounds__(256)
+bn_total_coef_kernel(const long long *__restrict__ partial, int nparts, long long *totals, uint32_t *ticket, const BnCoefArgs c)
+{
+    __shared__ long long sm[32][8];
+    __shared__ bool last;
+    const int width = 2 * c.channels;
+    const int col8 = threadIdx.x & 7, rl = threadIdx.x >> 3;
+    const int col = blockIdx.x * 8 + col8;
+    long long acc = 0;
+    if (col < width)
+        for (int r = rl; r < nparts; r += 32) acc += partial[(size_t)r * width + col];
+    sm[rl][col8] = acc;
+    __syncthreads();
+    if (threadIdx.x < 8 && col < width) {
+        long long t = 0;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) t += sm[i][threadIdx.x];
+        __hip_atomic_store(totals + col, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();                               // the block's totals are issued before its ticket
+    if (threadIdx.x == 0) {
+        // release this block's totals, acquire everyone else's
+        last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1;
+        if (last) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // for the next launch
+    }
+    __syncthreads();
+    if (!last) return;
+    if (BWD) bn_coef_bwd_body(totals, c.channels, c.state, c.dgamma, c.dbeta, nullptr);
+    else bn_coef_fwd_body(totals, c.channels, c.rows, c.fl_y, c.fl_o, c.gamma, c.beta, c.eps, c.state, nullptr);
 }
 
 // ---- forward: out = requantize(A y + B [+ shortcut], FA) ---------------------------------------------------
@@ -841,9 +885,11 @@ extern "C" int adapt_bn_forward(adapt_ctx *ctx, const void *y, adapt_fmt fy, siz
     int grid;
     launch_sums<0>(ctx, y, storage_bytes(fy), y, storage_bytes(fy), groups, channels, partial, grid);
     long long *totals = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
-    hipLaunchKernelGGL(bn_total_kernel, dim3((2 * channels + 7) / 8), dim3(256), 0, ctx->stream, partial, grid, 2 * channels, totals);
-    hipLaunchKernelGGL(bn_coef_fwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, totals, channels, (unsigned long long)rows, fy.fl,
-                       fo.fl, gamma, beta, eps, state);
+    BnCoefArgs ca = {};
+    ca.channels = channels; ca.fl_y = fy.fl; ca.fl_o = fo.fl; ca.rows = (unsigned long long)rows; ca.gamma = gamma; ca.beta = beta;
+    ca.eps = eps; ca.state = state;
+    hipLaunchKernelGGL(bn_total_coef_kernel<false>, dim3((2 * channels + 7) / 8), dim3(256), 0, ctx->stream, partial, grid, totals,
+                       ticket(ctx, 0), ca);
     BnApplyArgs a;
     a.y = y; a.res = res; a.out = out; a.state = state; a.groups = groups; a.channels = channels; a.wl = fo.wl; a.relu = relu != 0;
     a.mode = rng.mode; a.has_res = res != nullptr; a.fl_res = res ? fres.fl : 0; a.seed = rng.seed; a.stream = rng.stream;
@@ -903,8 +949,10 @@ extern "C" int adapt_bn_backward(adapt_ctx *ctx, const void *dz, int wl_dz, cons
     int grid;
     launch_sums<1>(ctx, dz, es_d, y, es_y, groups, channels, partial, grid);
     long long *totals = partial + (size_t)ctx->num_cu * 2 * 2 * (size_t)channels;
-    hipLaunchKernelGGL(bn_total_kernel, dim3((2 * channels + 7) / 8), dim3(256), 0, ctx->stream, partial, grid, 2 * channels, totals);
-    hipLaunchKernelGGL(bn_coef_bwd_kernel, dim3(1), dim3(1024), 0, ctx->stream, totals, channels, state, dgamma, dbeta);
+    BnCoefArgs ca = {};
+    ca.channels = channels; ca.state = state; ca.dgamma = dgamma; ca.dbeta = dbeta;
+    hipLaunchKernelGGL(bn_total_coef_kernel<true>, dim3((2 * channels + 7) / 8), dim3(256), 0, ctx->stream, partial, grid, totals,
+                       ticket(ctx, 0), ca);
     BnBwdArgs a;
     a.dz = dz; a.y = y; a.dy = dy; a.state = state; a.groups = groups; a.channels = channels; a.wl = wl_out; a.mode = rng.mode;
     a.seed = rng.seed; a.stream = rng.stream; a.shift_out = shift;
