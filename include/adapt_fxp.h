@@ -644,7 +644,12 @@ typedef struct {
 int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng rng,
                                adapt_switch_report *report, int *strategy);
 /* Per layer adapt_sgd_update_quantize with the gradient codes and their sum of squares (the step
- * has length lr per layer); writes the new weight codes and the stats record. */
+ * has length lr per layer) and rng stream rng.stream + 8 l + 3; writes the new weight codes and the
+ * stats record; gamma and beta of the layers with batch normalisation as adapt_bn_update does.
+ * The results are those of the per-layer calls bit for bit, enqueued as one launch for all gamma /
+ * beta and one launch pair for the weights of all layers with codes of at most 16 bits (per-layer
+ * launches for the others, and for all when the context's workspace cannot hold the batch's
+ * per-block partials).  ADAPT_EINVAL, with nothing enqueued, before the first backward pass. */
 int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng rng);
 
 /* ---- the paper's performance model (Sec. 4.1 "Performance Model") --------------------------- */

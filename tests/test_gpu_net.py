@@ -194,6 +194,22 @@ def test_vgg_like_chain_with_wide_channels():
     _run_chain(layers, [(8, 5), (8, 5), (6, 4), (12, 8), (8, 4)], n=8, seed=21)
 
 
+def test_deep_chain_updates_more_layers_than_one_batched_launch_holds():
+    # 40 layers: the batched update takes 32 tensors per launch, the 33rd starts a second one; ragged weight counts
+    # (24 x 24 and 24 x 10 elements) put the tails of several tensors into one launch
+    layers = [no.Layer(1, 1, 24, 24, 1, 1, 1, 0, relu=(l % 3 != 2), pool=False) for l in range(39)]
+    layers.append(no.Layer(1, 1, 24, 10, 1, 1, 1, 0, relu=False, pool=False))
+    fmts = [((8, 4), (12, 8), (16, 11), (6, 3))[l % 4] for l in range(40)]
+    _run_chain(layers, fmts, n=6, seed=77)
+
+
+def test_deep_chain_with_some_layers_above_sixteen_bits_updates_them_one_by_one():
+    layers = [no.Layer(1, 1, 16, 16, 1, 1, 1, 0, relu=True, pool=False) for _ in range(34)]
+    layers.append(no.Layer(1, 1, 16, 10, 1, 1, 1, 0, relu=False, pool=False))
+    fmts = [((8, 4), (20, 14), (12, 8))[l % 3] for l in range(35)]
+    _run_chain(layers, fmts, n=4, seed=78, wl_max=32)
+
+
 def test_alexnet_cifar_chain_reduced_batch():
     layers, fmts = [], []
     for sp, relu, pool in wk.alexnet_cifar_chain(batch=2):
