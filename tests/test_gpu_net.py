@@ -649,7 +649,7 @@ def _bn_state(net, l, k):
             "B": body[24 * k:32 * k].view(np.int64)}
 
 
-def _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, labels_rng, seed, s0, lr, check_all, sw=None):
+def _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, labels_rng, seed, s0, lr, check_all, sw=None, forward_only=False):
     """One training step on both sides, compared tensor by tensor.  Returns (new ws, new wq, new bn, loss)."""
     n = x.shape[0]
     last = len(nodes) - 1
@@ -664,6 +664,8 @@ def _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, labels_rng, seed, s0, 
                 assert st["FA"] == fwd["bn"][l]["FA"] and np.array_equal(st["A"], fwd["bn"][l]["A"]) and np.array_equal(st["B"], fwd["bn"][l]["B"]), l
             assert np.array_equal(host(net.tensor(l, pkg.NT_Y)).astype(np.int64), fwd["y"][l].ravel()), l
             assert np.array_equal(host(net.tensor(l, pkg.NT_A)).astype(np.int64), fwd["a"][l].ravel()), l
+    if forward_only:
+        return ws, bn, 0.0
     wl_last, fl_last = fmts[last]
     logits = fwd["a"][last].reshape(n, -1) / 2.0 ** fl_last
     e = np.exp(logits - logits.max(axis=1, keepdims=True))
@@ -713,7 +715,7 @@ def _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, labels_rng, seed, s0, 
     return ws, bn_new, loss
 
 
-def _run_graph(nodes, fmts, n, steps, seed, switch_kw=None, check_all=True, lr=0.05, wl_max=16):
+def _run_graph(nodes, fmts, n, steps, seed, switch_kw=None, check_all=True, lr=0.05, wl_max=16, forward_only=False):
     from oracle import pushup_oracle as po
     rng = np.random.default_rng(seed)
     first = nodes[0]
@@ -740,7 +742,7 @@ def _run_graph(nodes, fmts, n, steps, seed, switch_kw=None, check_all=True, lr=0
         x = rng.standard_normal((n, first.h, first.w, first.c)).astype(np.float32)
         for l, (wl, fl) in enumerate(fmts):                      # formats may have switched
             pass
-        ws, bn, _ = _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, rng, seed, 1000 * (step + 1), lr, check_all, sw)
+        ws, bn, _ = _graph_step(net, nodes, fmts, ws, wdev, bn, bndev, x, rng, seed, 1000 * (step + 1), lr, check_all, sw, forward_only)
     net.close()
     return sw["switches"], fmts
 
@@ -783,6 +785,23 @@ def test_graph_descriptions_that_are_rejected():
             pkg.Net(ctx(), nodes, w[:len(nodes)], bn=p[:len(nodes)])
     with pytest.raises(pkg.AdaptError):                                                   # batch norm without its parameters
         pkg.Net(ctx(), [NodeDesc(c, 1, 0, 1, -1, -1, 0)], w[:1], bn=[None])
+
+
+def _resnet18_formats(seed):
+    g = np.random.default_rng(seed)
+    fmts = [(int(wl), int(wl) - 4) for wl in g.integers(6, 17, 21)]
+    fmts[0] = (12, 8)
+    return fmts
+
+
+def test_resnet18_cifar_chain_batch_64_every_tensor_of_a_step():
+    # 4.2 M-element activations: every element-wise kernel runs several grid-stride rounds
+    _run_graph(_resnet18_cifar(), _resnet18_formats(43), n=64, steps=1, seed=44, check_all=True, lr=0.02)
+
+
+def test_resnet18_cifar_chain_full_batch_forward_every_tensor():
+    # the batch the benchmark times (the whole step at this batch was compared once by hand: the oracle needs two minutes)
+    _run_graph(_resnet18_cifar(), _resnet18_formats(43), n=256, steps=1, seed=45, check_all=True, forward_only=True)
 
 
 def test_resnet18_cifar_chain_reduced_batch():
