@@ -9,6 +9,16 @@
 
 #include "adapt_fxp.h"
 
+// Where a contraction with an exact output leaves the largest magnitude of each of its blocks' outputs, for the
+// fitting requantization that follows it in the chained step (which then needs no pass of its own over the
+// accumulators).  Armed by the chained step around a contraction call (part != null), filled in by the launch.
+struct adapt_amax_sink {
+    unsigned long long *part;      // device: room for `capacity` maxima
+    unsigned long long *zero;      // device word the producing launch clears (the sum the fitting pass adds to), or null
+    int capacity;
+    int count;                     // maxima the last launch stored; 0: none (not armed, nothing launched), -1: more than fit
+};
+
 struct adapt_ctx {
     hipStream_t stream;
     int device;
@@ -23,6 +33,8 @@ struct adapt_ctx {
     std::vector<const void *> big_lds_kernels;
     // this device's copy of the static scratch array of adapt_quantize_noalloc (null if its address could not be taken)
     void *static_scratch;
+    // [0]: forward / data-gradient / GEMM contractions, [1]: weight gradients
+    adapt_amax_sink amax[2];
 };
 
 namespace adapt {

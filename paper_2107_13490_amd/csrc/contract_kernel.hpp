@@ -105,6 +105,12 @@ struct ContractArgs {
     int out_mode;
     int shift, wl_o, relu, rmode;
     uint64_t seed, stream;
+    // Exact output modes, optional (the fitting requantization that follows needs the tensor's largest magnitude):
+    // block b of the launch that writes the final output stores the largest magnitude of its outputs at amax_part[b]
+    // (b < amax_cap), and its first block clears *amax_zero (the sum the fitting pass adds to) when that is not null.
+    unsigned long long *amax_part;
+    unsigned long long *amax_zero;
+    unsigned amax_cap;
 };
 
 // stride-2 data gradient in class order: visited row v -> row of dx (v < M)
@@ -586,14 +592,26 @@ __device__ __forceinline__ uint32_t pack4_i8(int q0, int q1, int q2, int q3)
 //              `shift` rounding bits, floor((256 u + lo8 + r) / 2^shift) = (u + ((lo8 + r) >> 8)) >> (shift - 8):
 //              everything stays in 32-bit arithmetic.  Only requantized outputs take this form.
 enum { FORM_I64 = 0, FORM_I32 = 1, FORM_PAIR = 2 };
-template <int RUN, int FORM>
-__device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m, int n0, const long long (&v)[RUN])
+template <int RUN, int FORM, bool AMAX = false>
+__device__ __forceinline__ void emit_run(const ContractArgs &a, void *out, int m, int n0, const long long (&v)[RUN],
+                                         unsigned long long &vmax)
 {
     constexpr bool FITS32 = FORM == FORM_I32;
     static_assert(RUN == 16, "a lane holds runs of 16 outputs");
     if (m >= a.M || n0 >= a.N) return;
     const int cnt = min(RUN, a.N - n0);
     const long long row = (long long)m * a.ldc + n0;
+    if constexpr (AMAX) {
+        // the exact modes hold the true sums in v (the 32-bit forms belong to the requantizing epilogue)
+        if (a.out_mode == OUT_RAW32 || a.out_mode == OUT_RAW64) {
+#pragma unroll
+            for (int i = 0; i < RUN; ++i)
+                if (i < cnt) {
+                    const unsigned long long mag = v[i] < 0 ? 0ull - (unsigned long long)v[i] : (unsigned long long)v[i];
+                    vmax = mag > vmax ? mag : vmax;
+                }
+        }
+    }
     if (a.out_mode == OUT_RAW32) {
         int32_t *o = static_cast<int32_t *>(out) + row;
         if (cnt == RUN && ((a.ldc | n0) & 3) == 0) {
@@ -725,7 +743,9 @@ __device__ __forceinline__ int dot4_ones(uint32_t v) { return __builtin_amdgcn_s
 // loads of stage kt+2 are issued; MFMA fragments are read one 32-deep sub-step ahead into a second set of
 // registers, and the barrier sits before the last sub-step, so that the fragment reads of the next stage's
 // first sub-step are in flight behind the MFMAs of this stage's last one.
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0>
+// AMAX: an instance that also stores the largest magnitude of each block's outputs (ContractArgs::amax_part); the
+// plain instances carry none of that code
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0, bool AMAX = false>
 __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsigned lin, const unsigned nwg,
                                               const unsigned ntiles, char *const smem)
 {
@@ -1031,6 +1051,7 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
     }
     const long long kpad = (long long)ksteps * BKT;
     void *out = static_cast<char *>(a.out) + (long long)split * a.slab_bytes;
+    unsigned long long vmax = 0;                      // largest magnitude of this lane's outputs (exact modes, when asked for)
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -1060,10 +1081,10 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                 }
             }
             auto emit = [&](const long long (&vals)[16]) {
-                if (LIMBS == 1) emit_run<16, FORM_I32>(a, out, m_of, nb_of + 16 * g, vals);
-                else if (pair_form) emit_run<16, FORM_PAIR>(a, out, m_of, nb_of + 16 * g, vals);
-                else if (i32_form) emit_run<16, FORM_I32>(a, out, m_of, nb_of + 16 * g, vals);
-                else emit_run<16, FORM_I64>(a, out, m_of, nb_of + 16 * g, vals);
+                if (LIMBS == 1) emit_run<16, FORM_I32, AMAX>(a, out, m_of, nb_of + 16 * g, vals, vmax);
+                else if (pair_form) emit_run<16, FORM_PAIR, AMAX>(a, out, m_of, nb_of + 16 * g, vals, vmax);
+                else if (i32_form) emit_run<16, FORM_I32, AMAX>(a, out, m_of, nb_of + 16 * g, vals, vmax);
+                else emit_run<16, FORM_I64, AMAX>(a, out, m_of, nb_of + 16 * g, vals, vmax);
             };
             int m = m0 + wm * WM + j * 32 + l32;
             const int nb0 = n0 + wn * WN + i * 32;
@@ -1093,6 +1114,24 @@ __device__ __forceinline__ void contract_body(const ContractArgs &a, const unsig
                 emit(v);
             }
         }
+    if constexpr (AMAX) {
+        unsigned long long *sm = reinterpret_cast<unsigned long long *>(smem);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const unsigned long long o = __shfl_xor(vmax, off, 64);
+            vmax = o > vmax ? o : vmax;
+        }
+        __syncthreads();                              // every wavefront has left the main loop: the tiles are free
+        if (lane == 0) sm[wave] = vmax;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned long long m = sm[0];
+#pragma unroll
+            for (int i = 1; i < 4; ++i) m = sm[i] > m ? sm[i] : m;
+            if (a.amax_part != nullptr && lin < a.amax_cap) a.amax_part[lin] = m;
+            if (lin == 0 && a.amax_zero != nullptr) *a.amax_zero = 0;
+        }
+    }
 }
 
 // Two-limb 64x64 tiles: three accumulator sets and the staging registers land a few registers above what three
@@ -1112,30 +1151,30 @@ constexpr int min_waves_per_simd(int op, int limbs, int amode, int wmode, int ae
     return (op != OP_WGRAD && limbs == 2 && aes >= 2 && wes >= 2 && bm == 64 && bn == 64) ? 3 : 1;
 }
 
-template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0>
+template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0, bool AMAX = false>
 __global__ void __launch_bounds__(kThreads, min_waves_per_simd(OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, PIPE))
 contract_kernel(const ContractArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    contract_body<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PIPE>(a, blockIdx.y * gridDim.x + blockIdx.x,
-                                                                               gridDim.x * gridDim.y, gridDim.x, smem);
+    contract_body<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PIPE, AMAX>(a, blockIdx.y * gridDim.x + blockIdx.x,
+                                                                                     gridDim.x * gridDim.y, gridDim.x, smem);
 }
 
 // Two independent contractions in one launch (the two gradients of a layer): blocks [0, n_first)
 // run the first, the rest the second, so that each fills the CUs the other leaves idle and one
 // launch floor is paid instead of two.  Both have the same limb mode and stage depth.
 // LM: the limb mode of all four operands (1, or 2 / 3 for int16 operands).
-template <int LM, int BKT, int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB>
+template <int LM, int BKT, int OPA, int AMA, int WMA, int BMA, int BNA, int OPB, int AMB, int WMB, int BMB, int BNB, bool AMAX = false>
 __global__ void __launch_bounds__(kThreads, (LM >= 2 && BMA == 64 && BNA == 64 && BMB == 64 && BNB == 64) ? 3 : 1)      // as above; measured faster for the pair
 contract_pair_kernel(const ContractArgs a, const ContractArgs b, const unsigned n_first, const unsigned tiles_a,
                      const unsigned tiles_b)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     if (blockIdx.x < n_first)
-        contract_body<OPA, limbs_of(LM), AMA, WMA, LM, LM, BMA, BNA, 2, 2, BKT>(a, blockIdx.x, n_first, tiles_a, smem);
+        contract_body<OPA, limbs_of(LM), AMA, WMA, LM, LM, BMA, BNA, 2, 2, BKT, 0, AMAX>(a, blockIdx.x, n_first, tiles_a, smem);
     else
-        contract_body<OPB, limbs_of(LM), AMB, WMB, LM, LM, BMB, BNB, 2, 2, BKT>(b, blockIdx.x - n_first, gridDim.x - n_first,
-                                                                                 tiles_b, smem);
+        contract_body<OPB, limbs_of(LM), AMB, WMB, LM, LM, BMB, BNB, 2, 2, BKT, 0, AMAX>(b, blockIdx.x - n_first, gridDim.x - n_first,
+                                                                                          tiles_b, smem);
 }
 
 // ---- helper: split-K finish ---------------------------------------------------------------------------
@@ -1146,6 +1185,7 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
 {
     const size_t total = (size_t)a.M * a.N;
     const size_t slab = (size_t)a.slab_bytes / sizeof(AccT);        // elements per slab (more than total with appended channels)
+    unsigned long long vmax = 0;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const size_t m = i / a.N, n = i % a.N;
         size_t j = i;                                               // position inside a slab
@@ -1164,6 +1204,10 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
         }
         for (; y < splits; ++y) v += (long long)ws[(size_t)y * slab + j];
         const size_t o = m * (size_t)a.ldc + n;
+        if (a.out_mode == OUT_RAW32 || a.out_mode == OUT_RAW64) {
+            const unsigned long long mag = v < 0 ? 0ull - (unsigned long long)v : (unsigned long long)v;
+            vmax = mag > vmax ? mag : vmax;
+        }
         switch (a.out_mode) {
             case OUT_RAW32: static_cast<int32_t *>(a.out)[o] = (int32_t)v; break;
             case OUT_RAW64: static_cast<long long *>(a.out)[o] = v; break;
@@ -1174,10 +1218,35 @@ finish_kernel(const AccT *__restrict__ ws, int splits, ContractArgs a)
             }
         }
     }
+    if (a.amax_part != nullptr) {                     // uniform over the launch
+        __shared__ unsigned long long sm[4];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const unsigned long long o = __shfl_xor(vmax, off, 64);
+            vmax = o > vmax ? o : vmax;
+        }
+        if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = vmax;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned long long m = sm[0];
+#pragma unroll
+            for (int i = 1; i < 4; ++i) m = sm[i] > m ? sm[i] : m;
+            if (blockIdx.x < a.amax_cap) a.amax_part[blockIdx.x] = m;
+            if (blockIdx.x == 0 && a.amax_zero != nullptr) *a.amax_zero = 0;
+        }
+    }
 }
 
 // ---- host side ---------------------------------------------------------------------------------
 struct TileShape { int bm, bn, bkt, pipe; };      // pipe: the double-buffered pipeline of the large tiles
+
+// A launch that stores per-block maxima (ContractArgs::amax_part) tells the sink it fills how many there are
+static inline void note_amax_blocks(adapt_ctx *ctx, const ContractArgs &a, long long blocks)
+{
+    if (a.amax_part == nullptr) return;
+    for (adapt_amax_sink &s : ctx->amax)
+        if (s.part == a.amax_part) s.count = blocks <= (long long)s.capacity ? (int)blocks : -1;
+}
 
 template <int OP, int LIMBS, int AMODE, int WMODE, int AES, int WES, int BM, int BN, int WGM, int WGN, int BKT, int PIPE = 0>
 static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
@@ -1187,9 +1256,12 @@ static hipError_t launch_es(adapt_ctx *ctx, const ContractArgs &a, int splits)
     typedef typename LoaderSelect<OP, false, WMODE, BN, WES, BKT>::type LB;
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const size_t lds = std::max<size_t>(((size_t)LA::TILE_BYTES * LAL + (size_t)LB::TILE_BYTES * LBL) * (PIPE ? 2 : 1), 4 * 4 * 32 * sizeof(int) * 4);
-    auto kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PIPE>;
+    void (*kern)(const ContractArgs) = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PIPE>;
+    if constexpr (is_dgrad(OP) || OP == OP_WGRAD)      // the gradient contractions of a chained step (see plan_contraction)
+        if (a.amax_part != nullptr) kern = contract_kernel<OP, LIMBS, AMODE, WMODE, AES, WES, BM, BN, WGM, WGN, BKT, PIPE, true>;
     if (hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(kern), lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(tiles, splits), dim3(kThreads), lds, ctx->stream, a);
+    note_amax_blocks(ctx, a, (long long)tiles * splits);
     return hipGetLastError();
 }
 
@@ -1486,8 +1558,17 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     p.tile = t;
     p.splits = splits;
     p.ws_end = ws_offset;
+    // exact output with a sink armed: the launch that writes the final output also stores its blocks' largest magnitudes
+    const adapt_amax_sink &sink = ctx->amax[OP == OP_WGRAD ? 1 : 0];
+    auto arm = [&](ContractArgs &dst) {
+        if (!(OP == OP_DGRAD || OP == OP_WGRAD) || !ep.raw || sink.part == nullptr) return;
+        dst.amax_part = sink.part;
+        dst.amax_zero = sink.zero;
+        dst.amax_cap = (unsigned)sink.capacity;
+    };
     if (splits == 1 && !a.force_finish) {
         a.out_mode = final_mode;
+        arm(a);
         p.kern = a;
         return ADAPT_OK;
     }
@@ -1514,6 +1595,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
         p.splits = splits;
         if (splits == 1 && !a.force_finish) {
             a.out_mode = final_mode;
+            arm(a);
             p.kern = a;
             return ADAPT_OK;
         }
@@ -1530,6 +1612,7 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     p.fin = a;
     p.fin.out_mode = final_mode;
     p.fin.slab_bytes = (long long)slab;
+    arm(p.fin);
     return ADAPT_OK;
 }
 
@@ -1553,6 +1636,7 @@ static hipError_t finish_planned(adapt_ctx *ctx, const ContractPlan &p)
         hipLaunchKernelGGL(finish_kernel<int32_t>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const int32_t *>(p.acc), p.splits, p.fin);
     else
         hipLaunchKernelGGL(finish_kernel<long long>, dim3(fgrid), dim3(256), 0, ctx->stream, reinterpret_cast<const long long *>(p.acc), p.splits, p.fin);
+    note_amax_blocks(ctx, p.fin, fgrid);
     return hipGetLastError();
 }
 

@@ -13,12 +13,17 @@ static hipError_t launch_pair(adapt_ctx *ctx, const ContractPlan &d, const Contr
     typedef typename LoaderSelect<OP_WGRAD, true, LOAD_ROWS, WBM, LM, BKT>::type WA;
     typedef typename LoaderSelect<OP_WGRAD, false, LOAD_ROWS, WBN, LM, BKT>::type WB;
     const size_t lds = std::max<size_t>(DA::TILE_BYTES + DB::TILE_BYTES, WA::TILE_BYTES + WB::TILE_BYTES) * limbs_of(LM);
-    auto kern = contract_pair_kernel<LM, BKT, OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
+    void (*kern)(const ContractArgs, const ContractArgs, const unsigned, const unsigned, const unsigned) =
+        contract_pair_kernel<LM, BKT, OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN>;
+    if (d.kern.amax_part != nullptr || w.kern.amax_part != nullptr)
+        kern = contract_pair_kernel<LM, BKT, OP_DGRAD, LOAD_VEC, LOAD_ROWS, DBM, DBN, OP_WGRAD, LOAD_ROWS, LOAD_ROWS, WBM, WBN, true>;
     if (hipError_t e = allow_big_lds(ctx, reinterpret_cast<const void *>(kern), lds); e != hipSuccess) return e;
     const unsigned tiles_d = (unsigned)(((d.kern.M + DBM - 1) / DBM) * ((d.kern.N + DBN - 1) / DBN));
     const unsigned tiles_w = (unsigned)(((w.kern.M + WBM - 1) / WBM) * ((w.kern.N + WBN - 1) / WBN));
     const unsigned n_d = tiles_d * (unsigned)d.splits, n_w = tiles_w * (unsigned)w.splits;
     hipLaunchKernelGGL(kern, dim3(n_d + n_w), dim3(kThreads), lds, ctx->stream, d.kern, w.kern, n_d, tiles_d, tiles_w);
+    note_amax_blocks(ctx, d.kern, n_d);
+    note_amax_blocks(ctx, w.kern, n_w);
     return hipGetLastError();
 }
 

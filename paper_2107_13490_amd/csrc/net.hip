@@ -373,8 +373,11 @@ extern "C" int adapt_relu_pool_bwd(adapt_ctx *ctx, const void *da, const void *y
     return hip_status(ctx, hipGetLastError());
 }
 
+// ext_part / ext_n: per-block maxima that the kernel which produced `acc` has already stored (and, with sumsq, a cleared
+// *sumsq): the pass over the accumulators that finds them is skipped
 static int requantize_fit_exp(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q, int32_t *shift,
-                              uint64_t *sumsq, const long long *e_in, long long e_add, long long *e_out)
+                              uint64_t *sumsq, const long long *e_in, long long e_add, long long *e_out,
+                              const unsigned long long *ext_part = nullptr, int ext_n = 0)
 {
     if (ctx && (acc_bits == 128 || (wl > 16 && wl <= 32)))
         return requantize_fit_wide(ctx, acc, acc_bits, n, wl, rng, q, shift, sumsq, e_in, e_add, e_out);
@@ -394,8 +397,14 @@ static int requantize_fit_exp(adapt_ctx *ctx, const void *acc, int acc_bits, siz
     a.acc = acc; a.q = q; a.part = part; a.nparts = grid1; a.n = n; a.wl = wl; a.mode = rng.mode; a.seed = rng.seed;
     a.stream = rng.stream; a.shift_out = shift; a.sumsq = ss; a.e_in = e_in; a.e_add = e_add; a.e_out = e_out;
     const dim3 block(kEwThreads);
-    if (acc_bits == 32) hipLaunchKernelGGL(absmax_kernel<int32_t>, dim3(grid1), block, 0, ctx->stream, (const int32_t *)acc, (uint64_t)n, part, ss);
-    else hipLaunchKernelGGL(absmax_kernel<int64_t>, dim3(grid1), block, 0, ctx->stream, (const int64_t *)acc, (uint64_t)n, part, ss);
+    if (ext_part != nullptr && ext_n > 0) {
+        a.part = reinterpret_cast<const uint64_t *>(ext_part);
+        a.nparts = ext_n;
+    } else if (acc_bits == 32) {
+        hipLaunchKernelGGL(absmax_kernel<int32_t>, dim3(grid1), block, 0, ctx->stream, (const int32_t *)acc, (uint64_t)n, part, ss);
+    } else {
+        hipLaunchKernelGGL(absmax_kernel<int64_t>, dim3(grid1), block, 0, ctx->stream, (const int64_t *)acc, (uint64_t)n, part, ss);
+    }
     const bool o8 = wl <= 8;
     if (acc_bits == 32 && o8) hipLaunchKernelGGL((requant_fit_kernel<int32_t, int8_t>), dim3(grid2), block, 0, ctx->stream, a);
     else if (acc_bits == 32) hipLaunchKernelGGL((requant_fit_kernel<int32_t, int16_t>), dim3(grid2), block, 0, ctx->stream, a);
@@ -455,6 +464,7 @@ namespace {
 constexpr int kMaxLayers = 64;
 constexpr int kRingMax = 65;           // ring slots per layer: the longest window and the gradient being made
 constexpr size_t kStatBytes = 64;      // per layer: the adapt_net_stats record
+constexpr int kAmaxCap = 8192;         // per-block maxima a gradient contraction may leave for the fitting pass (more: a pass of its own)
 constexpr size_t kExpBytes = 32;       // per layer: exponents of da, of the gradient at the convolution output, of dW
 
 // random streams of the steps that only residual / batch-norm networks have
@@ -492,7 +502,7 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 constexpr size_t kKldStride = 256;      // bytes per layer for the KL values of up to 31 candidates
 
 struct NetPlan {
-    size_t off_in, off_accx, off_accw, off_stats, off_sel_group, off_kld_group, off_win, off_tmp, bytes;
+    size_t off_in, off_accx, off_accw, off_amax, off_stats, off_sel_group, off_kld_group, off_win, off_tmp, bytes;
 };
 
 // Lays the workspace out; returns false for an invalid network.
@@ -585,6 +595,7 @@ bool plan_net(const adapt_node_desc *descs, int count, int lb_upr, int wl_max, s
     P.off_accx = take(ab * max_in);
     P.off_accw = take(ab * max_w);
     P.off_tmp = max_merge ? take(cb * max_merge) : 0;
+    P.off_amax = take((size_t)2 * kAmaxCap * 8);                 // per-block maxima of the two gradient contractions of a layer
     P.bytes = off;
     return true;
 }
@@ -948,14 +959,21 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
             while (used[y.g_slot]) ++y.g_slot;
         }
         char *accw = net->ws + net->P.off_accw, *accx = net->ws + net->P.off_accx;
-        if (y.src >= 0) {
-            if (int s = adapt_conv_backward(ctx, c, dyc, fdy, net->ws + y.off_qw, y.fmt, a_prev, fin, accx, ex, accw, ex)) return s;
-        } else {
-            if (int s = adapt_conv_wgrad(ctx, c, dyc, fdy, a_prev, fin, accw, ex)) return s;
-        }
+        // The launches that write the exact gradients also leave their blocks' largest magnitudes (and clear the sum of
+        // squares the fitting pass adds to), so that the fitting passes need no pass of their own to find them.  The
+        // composed contractions above 16 bits do not: their counts stay 0.
+        unsigned long long *amax_x = reinterpret_cast<unsigned long long *>(net->ws + net->P.off_amax), *amax_w = amax_x + kAmaxCap;
+        ctx->amax[0] = adapt_amax_sink{amax_x, nullptr, kAmaxCap, 0};
+        ctx->amax[1] = adapt_amax_sink{amax_w, reinterpret_cast<unsigned long long *>(&st->g_sumsq), kAmaxCap, 0};
+        int s_bwd;
+        if (y.src >= 0) s_bwd = adapt_conv_backward(ctx, c, dyc, fdy, net->ws + y.off_qw, y.fmt, a_prev, fin, accx, ex, accw, ex);
+        else s_bwd = adapt_conv_wgrad(ctx, c, dyc, fdy, a_prev, fin, accw, ex);
+        const int n_amax_x = ctx->amax[0].count, n_amax_w = ctx->amax[1].count;
+        ctx->amax[0] = ctx->amax[1] = adapt_amax_sink{};
+        if (s_bwd) return s_bwd;
         const int bits_w = adapt_acc_bits((int64_t)c.n * y.p * y.q, fdy, fin);
         if (int s = requantize_fit_exp(ctx, accw, bits_w, y.n_w, y.fmt.wl, slot_rng(rng, l, 2), net->ws + y.g_off(), &st->shift_w,
-                                       &st->g_sumsq, e_cur, fin.fl, &ex_l->e_g))
+                                       &st->g_sumsq, e_cur, fin.fl, &ex_l->e_g, amax_w, n_amax_w))
             return s;
         if (y.src >= 0) {
             NetLayer &t = net->L[y.src];
@@ -964,7 +982,7 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
             char *dst = first ? net->ws + t.off_da : net->ws + net->P.off_tmp;
             long long *e_dst = first ? &net->exps(y.src)->e_da : &ex_l->spare;
             if (int s = requantize_fit_exp(ctx, accx, bits_x, y.n_in, t.fmt.wl, slot_rng(rng, l, 1), dst, &st->shift_a, nullptr, e_cur,
-                                           y.fmt.fl, e_dst))
+                                           y.fmt.fl, e_dst, amax_x, n_amax_x))
                 return s;
             if (int s = contribute(y.src, dst, t.fmt.wl, e_dst, true)) return s;
         }
