@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadapt_fxp.so")
 SOURCES = ["api.hip", "quantize.hip", "kld.hip", "contract_gemm.hip", "contract_fwd.hip",
-           "contract_dgrad.hip", "contract_wgrad.hip", "pushup.hip", "sgd.hip",
+           "contract_dgrad.hip", "contract_dgrad_s2.hip", "contract_wgrad.hip", "pushup.hip", "sgd.hip",
            "contract_backward.hip", "contract_pair_d64x64.hip", "contract_pair_d128x64.hip", "contract_pair_d64x128.hip",
            "contract_pair_d128x128.hip", "perf_model.hip", "net.hip", "workspace.hip", "bn.hip", "wide.hip", "wide_ops.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -70,7 +70,12 @@ extern "C" int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void
         aw = ContractArgs{};
         ad = ContractArgs{};
         if (int s = fill_wgrad(aw, d, dy, fdy, x, fx, dw)) return s;
-        if (d.n == 0) return run_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0);      // dw = 0, no dx
+        if (d.n == 0) {                                                                    // dw = 0, no dx
+            if (int s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0, pw)) return s;
+            hipError_t e0 = launch_planned_wgrad(ctx, pw);
+            if (e0 == hipSuccess) e0 = finish_planned(ctx, pw);
+            return hip_status(ctx, e0);
+        }
         if (int s = fill_dgrad(ad, d, dy, fdy, w, fw, dx)) return s;
         if (int s = plan_contraction<OP_DGRAD>(ctx, ad, fdy, fw, ep_dx, 0, pd)) return s;
         if (int s = plan_contraction<OP_WGRAD>(ctx, aw, fdy, fx, ep_dw, 0, pw)) return s;
@@ -86,9 +91,9 @@ extern "C" int adapt_conv_backward(adapt_ctx *ctx, adapt_conv_desc d, const void
     }
     if (!paired) {
         // one after the other; both may use the scratch from its start because the stream orders them
-        e = launch_planned<OP_DGRAD>(ctx, pd);
+        e = launch_planned_dgrad(ctx, pd);
         if (e == hipSuccess) e = finish_planned(ctx, pd);
-        if (e == hipSuccess) e = launch_planned<OP_WGRAD>(ctx, pw);
+        if (e == hipSuccess) e = launch_planned_wgrad(ctx, pw);
         if (e == hipSuccess) e = finish_planned(ctx, pw);
     }
     return hip_status(ctx, e);

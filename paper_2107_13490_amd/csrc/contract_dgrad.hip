@@ -3,6 +3,9 @@
 
 using namespace adapt;
 
+namespace adapt {
+hipError_t launch_planned_dgrad(adapt_ctx *ctx, const ContractPlan &p) { return launch_planned<OP_DGRAD>(ctx, p); }
+}  // namespace adapt
 
 extern "C" int adapt_conv_dgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *w,
                                 adapt_fmt fw, void *dx, adapt_epilogue ep)

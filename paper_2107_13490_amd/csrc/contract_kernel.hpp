@@ -1616,16 +1616,22 @@ static int plan_contraction(adapt_ctx *ctx, ContractArgs a, adapt_fmt fa, adapt_
     return ADAPT_OK;
 }
 
+// the stride-2 data gradient in class order: its kernel instances are compiled in a file of their own (contract_dgrad_s2.hip)
+hipError_t launch_planned_dgrad_s2(adapt_ctx *ctx, const ContractPlan &p);
+
 template <int OP>
 static hipError_t launch_planned(adapt_ctx *ctx, const ContractPlan &p)
 {
     if (p.empty) return hipSuccess;
     if constexpr (OP == OP_DGRAD)
-        if (p.kern.dg_classes)
-            return p.limbs == 1 ? launch_modes<OP_DGRAD_S2, 1>(ctx, p.kern, p.splits, p.tile)
-                                : launch_modes<OP_DGRAD_S2, 2>(ctx, p.kern, p.splits, p.tile);
+        if (p.kern.dg_classes) return launch_planned_dgrad_s2(ctx, p);
     return p.limbs == 1 ? launch_modes<OP, 1>(ctx, p.kern, p.splits, p.tile) : launch_modes<OP, 2>(ctx, p.kern, p.splits, p.tile);
 }
+
+// The planned gradient contractions as plain functions (contract_dgrad.hip, contract_wgrad.hip), so that the combined
+// backward call does not compile a second copy of every kernel instance
+hipError_t launch_planned_dgrad(adapt_ctx *ctx, const ContractPlan &p);
+hipError_t launch_planned_wgrad(adapt_ctx *ctx, const ContractPlan &p);
 
 // the slab sum + epilogue of a split contraction
 static hipError_t finish_planned(adapt_ctx *ctx, const ContractPlan &p)

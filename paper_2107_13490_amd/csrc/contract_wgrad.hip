@@ -3,6 +3,10 @@
 
 using namespace adapt;
 
+namespace adapt {
+hipError_t launch_planned_wgrad(adapt_ctx *ctx, const ContractPlan &p) { return launch_planned<OP_WGRAD>(ctx, p); }
+}  // namespace adapt
+
 
 extern "C" int adapt_conv_wgrad(adapt_ctx *ctx, adapt_conv_desc d, const void *dy, adapt_fmt fdy, const void *x,
                                 adapt_fmt fx, void *dw, adapt_epilogue ep)
