@@ -961,10 +961,12 @@ extern "C" int adapt_net_backward(adapt_net *net, const void *dlogits, int dlogi
         char *accw = net->ws + net->P.off_accw, *accx = net->ws + net->P.off_accx;
         // The launches that write the exact gradients also leave their blocks' largest magnitudes (and clear the sum of
         // squares the fitting pass adds to), so that the fitting passes need no pass of their own to find them.  The
-        // composed contractions above 16 bits do not: their counts stay 0.
+        // composed contractions above 16 bits do not (the sinks stay unarmed for them): their counts stay 0.
         unsigned long long *amax_x = reinterpret_cast<unsigned long long *>(net->ws + net->P.off_amax), *amax_w = amax_x + kAmaxCap;
-        ctx->amax[0] = adapt_amax_sink{amax_x, nullptr, kAmaxCap, 0};
-        ctx->amax[1] = adapt_amax_sink{amax_w, reinterpret_cast<unsigned long long *>(&st->g_sumsq), kAmaxCap, 0};
+        if (fdy.wl <= 16 && y.fmt.wl <= 16 && fin.wl <= 16) {
+            ctx->amax[0] = adapt_amax_sink{amax_x, nullptr, kAmaxCap, 0};
+            ctx->amax[1] = adapt_amax_sink{amax_w, reinterpret_cast<unsigned long long *>(&st->g_sumsq), kAmaxCap, 0};
+        }
         int s_bwd;
         if (y.src >= 0) s_bwd = adapt_conv_backward(ctx, c, dyc, fdy, net->ws + y.off_qw, y.fmt, a_prev, fin, accx, ex, accw, ex);
         else s_bwd = adapt_conv_wgrad(ctx, c, dyc, fdy, a_prev, fin, accw, ex);
