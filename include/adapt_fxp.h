@@ -648,8 +648,9 @@ int adapt_net_precision_switch(adapt_net *net, double loss, adapt_rng rng,
  * stats record; gamma and beta of the layers with batch normalisation as adapt_bn_update does.
  * The results are those of the per-layer calls bit for bit, enqueued as one launch for all gamma /
  * beta and one launch pair for the weights of all layers with codes of at most 16 bits (per-layer
- * launches for the others, and for all when the context's workspace cannot hold the batch's
- * per-block partials).  ADAPT_EINVAL, with nothing enqueued, before the first backward pass. */
+ * launches for the others).  ADAPT_EINVAL, with nothing enqueued, before the first backward pass;
+ * ADAPT_EWORKSPACE when the context's workspace cannot hold the batch's per-block partials (the
+ * same 16 KiB per layer on a 256-CU device that adapt_net_quantize_weights takes). */
 int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng rng);
 
 /* ---- the paper's performance model (Sec. 4.1 "Performance Model") --------------------------- */

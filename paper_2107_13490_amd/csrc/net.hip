@@ -1155,7 +1155,7 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
     }
     if (int s = bn_update_batch(net->ctx, bn_items.data(), (int)bn_items.size(), opt.lr)) return s;
     // the weights: every layer whose gradient and weight codes have at most 16 bits in one batched launch pair, the
-    // others (and all of them when the context's scratch is too small for the batch) one call each
+    // others one call each
     std::vector<SgdBatchItem> items;
     std::vector<int> single;
     for (int l = 0; l < count; ++l) {
@@ -1173,15 +1173,10 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
         it.wl = (int8_t)y.fmt.wl; it.fl = (int8_t)y.fmt.fl;
         items.push_back(it);
     }
-    if (!items.empty()) {
-        const int s = sgd_update_batch(net->ctx, items.data(), (int)items.size(), opt, rng.mode);
-        if (s == ADAPT_EWORKSPACE) {
-            single.clear();
-            for (int l = 0; l < count; ++l) single.push_back(l);
-        } else if (s) {
-            return s;
-        }
-    }
+    // (the scratch it needs is what adapt_net_quantize_weights needs for the same layers: a context that could quantize
+    // the weights can update them)
+    if (!items.empty())
+        if (int s = sgd_update_batch(net->ctx, items.data(), (int)items.size(), opt, rng.mode)) return s;
     for (int l : single) {
         NetLayer &y = net->L[l];
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);

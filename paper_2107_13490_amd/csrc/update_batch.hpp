@@ -30,7 +30,7 @@ struct SgdBatchItem {
 
 // Enqueues the fused update of `count` layers: one launch for the element work and one for the totals per
 // kUpdateMaxItems layers.  ADAPT_EWORKSPACE when the context's scratch cannot hold the per-block partials (nothing is
-// enqueued then and the caller takes the per-layer calls).
+// enqueued then).
 int sgd_update_batch(adapt_ctx *ctx, const SgdBatchItem *items, int count, adapt_sgd_params opt, int mode);
 
 // One layer of adapt_bn_update

@@ -117,14 +117,14 @@ def test_residual_add(n, fa, fb, fo):
 
 # ---- the chained step -----------------------------------------------------------------------------------
 
-def _run_chain(layers, fmts, n, seed, lr=0.05, l1=1e-4, l2=1e-3, wl_max=16):
+def _run_chain(layers, fmts, n, seed, lr=0.05, l1=1e-4, l2=1e-3, wl_max=16, context=None):
     rng = np.random.default_rng(seed)
     first = layers[0]
     x = rng.standard_normal((n, first.h, first.w, first.c)).astype(np.float32)
     ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * (1.5 / np.sqrt(L.r * L.s * L.c))).astype(np.float32) for L in layers]
     descs = [LayerDesc(ConvDesc(n, L.h, L.w, L.c, L.k, L.r, L.s, L.stride, L.pad), int(L.relu), int(L.pool)) for L in layers]
     wdev = [dev(w.copy()) for w in ws]
-    net = pkg.Net(ctx(), descs, wdev, wl_max=wl_max)
+    net = pkg.Net(context if context is not None else ctx(), descs, wdev, wl_max=wl_max)
     for l, (wl, fl) in enumerate(fmts):
         net.set_format(l, wl, fl)
     s0 = 1000 + seed
@@ -201,6 +201,21 @@ def test_deep_chain_updates_more_layers_than_one_batched_launch_holds():
     layers.append(no.Layer(1, 1, 24, 10, 1, 1, 1, 0, relu=False, pool=False))
     fmts = [((8, 4), (12, 8), (16, 11), (6, 3))[l % 4] for l in range(40)]
     _run_chain(layers, fmts, n=6, seed=77)
+
+
+def test_a_context_too_small_for_the_batched_calls_reports_it():
+    # six layers with 3.4 M weights: the batched quantize and the batched update want 6 x 16 KiB of per-block partials
+    # each (1024 blocks), more than this context's 64 KiB of scratch
+    small = pkg.Context(workspace_bytes=64 << 10)
+    shapes = [(256, 1024), (1024, 1024), (1024, 1024), (1024, 1024), (1024, 64), (64, 10)]
+    descs = [LayerDesc(ConvDesc(4, 1, 1, c, k, 1, 1, 1, 0), int(k != 10), 0) for c, k in shapes]
+    w = [dev(np.zeros((k, 1, 1, c), np.float32)) for c, k in shapes]
+    net = pkg.Net(small, descs, w)
+    with pytest.raises(pkg.AdaptError) as e:
+        net.quantize_weights()
+    assert e.value.status == -5                          # ADAPT_EWORKSPACE
+    net.close()
+    small.close()
 
 
 def test_deep_chain_with_some_layers_above_sixteen_bits_updates_them_one_by_one():
