@@ -203,6 +203,14 @@ def test_deep_chain_updates_more_layers_than_one_batched_launch_holds():
     _run_chain(layers, fmts, n=6, seed=77)
 
 
+def test_more_gradient_blocks_than_the_maxima_buffer_of_the_step_holds():
+    # 1.1 M output rows: the data gradient of the second layer runs 8800 blocks of 128 rows, more than the 8192 maxima the
+    # step has room for, so the fitting pass finds the largest magnitude in a pass of its own
+    layers = [no.Layer(32, 32, 16, 16, relu=True, pool=False), no.Layer(32, 32, 16, 16, relu=True, pool=True),
+              no.Layer(1, 1, 16 * 16 * 16, 10, 1, 1, 1, 0, relu=False, pool=False)]
+    _run_chain(layers, [(8, 5), (8, 5), (8, 4)], n=1100, seed=5)
+
+
 def test_a_context_too_small_for_the_batched_calls_reports_it():
     # six layers with 3.4 M weights: the batched quantize and the batched update want 6 x 16 KiB of per-block partials
     # each (1024 blocks), more than this context's 64 KiB of scratch
