@@ -1153,7 +1153,6 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
             bn_items.push_back(BnUpdateItem{y.gamma, y.beta, reinterpret_cast<const double *>(net->ws + y.off_dgam),
                                             reinterpret_cast<const double *>(net->ws + y.off_dbet), y.d.conv.k});
     }
-    if (int s = bn_update_batch(net->ctx, bn_items.data(), (int)bn_items.size(), opt.lr)) return s;
     // the weights: every layer whose gradient and weight codes have at most 16 bits in one batched launch pair, the
     // others one call each
     std::vector<SgdBatchItem> items;
@@ -1162,6 +1161,7 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
         NetLayer &y = net->L[l];
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
         if (y.g_wl > 16 || y.fmt.wl > 16) {
+            if (ws_need_sgd_update(net->ctx->num_cu, y.n_w) > scratch_bytes(net->ctx)) return ADAPT_EWORKSPACE;
             single.push_back(l);
             continue;
         }
@@ -1173,10 +1173,12 @@ extern "C" int adapt_net_update(adapt_net *net, adapt_sgd_params opt, adapt_rng 
         it.wl = (int8_t)y.fmt.wl; it.fl = (int8_t)y.fmt.fl;
         items.push_back(it);
     }
-    // (the scratch it needs is what adapt_net_quantize_weights needs for the same layers: a context that could quantize
-    // the weights can update them)
+    // The batched launch checks its arguments and its scratch before it enqueues anything, and it comes first: a call
+    // that fails has changed nothing.  (The scratch it needs is what adapt_net_quantize_weights needs for the same layers:
+    // a context that could quantize the weights can update them.)
     if (!items.empty())
         if (int s = sgd_update_batch(net->ctx, items.data(), (int)items.size(), opt, rng.mode)) return s;
+    if (int s = bn_update_batch(net->ctx, bn_items.data(), (int)bn_items.size(), opt.lr)) return s;
     for (int l : single) {
         NetLayer &y = net->L[l];
         adapt_net_stats *st = reinterpret_cast<adapt_net_stats *>(net->ws + y.off_stat);
