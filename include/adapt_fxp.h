@@ -203,11 +203,13 @@ int adapt_quantize_batched_ranges(adapt_ctx *ctx, const adapt_quantize_item *ite
 
 /* Word lengths 17..32 (adapt_fxp_gemm, adapt_conv_fwd, adapt_conv_dgrad, adapt_conv_wgrad; operands
  * and / or the requantized output): an operand above 16 bits is int32_t codes; the call splits it
- * into three 11-bit parts a = a2 2^22 + a1 2^11 + a0 (a0, a1 in [0, 2047], a2 = a >> 22), runs the
- * exact contraction of every pair of parts (nine for two such operands, three for one) on the int8
- * matrix cores, adds the partial results at their weights 2^(11(i+j)) in 128-bit integers and applies
- * the epilogue's rule once; the result is the exact contraction of the full codes, requantized as
- * for any other.  The parts, one partial result (8 bytes per output) and the 128-bit sums (16 bytes
+ * into parts the narrow kernels take (17..23 bits: the signed low byte and the rest, a = a1 2^8 +
+ * a0; 24..31 bits: the signed low half-word and the rest, a = a1 2^16 + a0; 32 bits: three 11-bit
+ * parts a = a2 2^22 + a1 2^11 + a0 with a0, a1 in [0, 2047], a2 = a >> 22), runs the exact
+ * contraction of every pair of parts (four for two operands of up to 31 bits, nine for two of 32,
+ * two or three with one narrow operand) on the int8 matrix cores, adds the partial results at their
+ * power-of-two weights in 128-bit integers and applies the epilogue's rule once; the result is the
+ * exact contraction of the full codes, requantized as for any other.  The parts, one partial result (8 bytes per output) and the 128-bit sums (16 bytes
  * per output) live in the workspace (adapt_workspace_bytes counts them).  adapt_fxp_gemm needs
  * ldc == N and K > 0 on this path; adapt_conv_backward and the chain stop at 16 bits. */
 
@@ -575,7 +577,7 @@ int adapt_net_create(adapt_ctx *ctx, const adapt_layer_desc *layers, int count,
  * handed to adapt_net_backward is int32_t when the last layer has more than 16 bits, and adapt_net_stats holds the
  * 128-bit sum of squares in g_sumsq / g_sumsq_hi.  A window whose gradients have more than 16 bits follows
  * adapt_gradient_diversity's rule for such windows (bound 2^48).  Contractions with an operand above 16 bits are
- * composed of 11-bit parts (see adapt_acc_bits): correct, and many times slower than the native ones. */
+ * composed of narrower parts (see adapt_acc_bits): correct, and several times slower than the native ones. */
 size_t adapt_net_workspace_bytes_wide(const adapt_layer_desc *layers, int count, int lb_upr, int wl_max);
 size_t adapt_graph_workspace_bytes_wide(const adapt_node_desc *nodes, int count, int lb_upr, int wl_max);
 int adapt_graph_create_wide(adapt_ctx *ctx, const adapt_node_desc *nodes, int count, float *const *weights,

@@ -53,6 +53,8 @@ typedef std::function<int(const void *, adapt_fmt, const void *, adapt_fmt, void
 int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems_a, const void *b, adapt_fmt fb, uint64_t elems_b,
                      uint64_t outputs, int64_t k_total, void *out, adapt_epilogue ep, const SubContraction &sub);
 size_t ws_need_wide(uint64_t elems_a, bool wide_a, uint64_t elems_b, bool wide_b, uint64_t outputs, bool raw);
+// formats of the parts an operand is split into (lowest first), their weight step in bits; returns their number
+int wide_parts(adapt_fmt f, adapt_fmt fmt[3], int *step);
 // The fitting requantization with 128-bit accumulators or an output above 16 bits (wide_ops.hip); arguments as in
 // adapt_requantize_fit, plus the exponent bookkeeping of the chained step (*e_out = (e_in ? *e_in : 0) + e_add - shift).
 int requantize_fit_wide(adapt_ctx *ctx, const void *acc, int acc_bits, size_t n, int wl, adapt_rng rng, void *q, int32_t *shift,

@@ -1,7 +1,10 @@
 // Contractions with word lengths 17..32 (Sec. 3.3 bounds the precision that PushUp may ask for at
 // 32 bits).  An operand above 16 bits is held as int32 codes and split into parts that the two-limb
 // int8 MFMA kernels of this library take; an operand of at most 16 bits stays as it is.
-//   17..31 bits: two 16-bit parts, a = a1 2^16 + a0 with a0 the signed low half-word (so a1 =
+//   17..23 bits: the signed low byte and what is left above it, a = a1 2^8 + a0 with |a1| <= 2^(wl-9), a code of
+//                wl - 7 <= 16 bits: the byte stays one limb in the kernels, so a pair of such operands costs nine
+//                int8 products (4 + 2 + 2 + 1) instead of the sixteen of two 16-bit parts each;
+//   24..31 bits: two 16-bit parts, a = a1 2^16 + a0 with a0 the signed low half-word (so a1 =
 //                (a + 2^15) >> 16 stays within 16 bits: |a1| <= 2^14);
 //   32 bits:     there a1 could reach 2^15, so three parts of 11 bits, a = a2 2^22 + a1 2^11 + a0,
 //                a0, a1 in [0, 2047], a2 = a >> 22 in [-512, 511], each a 12-bit code.
@@ -48,6 +51,18 @@ split2_kernel(const int32_t *__restrict__ a, int16_t *__restrict__ p0, int16_t *
         const int32_t lo = (int32_t)(int16_t)(v & 0xffff);
         p0[i] = (int16_t)lo;
         p1[i] = (int16_t)((v - lo) >> 16);
+    }
+}
+
+// codes of at most 23 bits: signed low byte (an int8 tensor) and what is left above it
+__global__ void __launch_bounds__(kWideThreads)
+split_byte_kernel(const int32_t *__restrict__ a, int8_t *__restrict__ p0, int16_t *__restrict__ p1, uint64_t n)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWideThreads) {
+        const int32_t v = a[i];
+        const int32_t lo = (int32_t)(int8_t)(v & 0xff);
+        p0[i] = (int8_t)lo;
+        p1[i] = (int16_t)((v - lo) >> 8);
     }
 }
 
@@ -107,6 +122,18 @@ size_t ws_need_wide(uint64_t elems_a, bool wide_a, uint64_t elems_b, bool wide_b
     return (wide_a ? 3 * a256(elems_a * 2) : 0) + (wide_b ? 3 * a256(elems_b * 2) : 0) + a256(outputs * 8) + (raw ? 0 : a256(outputs * 16));
 }
 
+// The parts an operand of format f is split into: their formats (lowest first) and the weight step in bits; returns
+// the number of parts (1: the operand as it is)
+int wide_parts(adapt_fmt f, adapt_fmt fmt[3], int *step)
+{
+    if (f.wl <= 16) { fmt[0] = f; *step = 0; return 1; }
+    if (f.wl <= 23) { fmt[0] = adapt_fmt{8, 0}; fmt[1] = adapt_fmt{f.wl - 7, 0}; *step = 8; return 2; }
+    if (f.wl <= 31) { fmt[0] = fmt[1] = adapt_fmt{16, 0}; *step = 16; return 2; }
+    fmt[0] = fmt[1] = fmt[2] = adapt_fmt{12, 0};
+    *step = kPartBits;
+    return 3;
+}
+
 // One operand of a wide contraction: its parts (pointers, formats) after the split
 struct WideOperand {
     const void *part[3];
@@ -124,7 +151,9 @@ int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems
     const bool wide_a = fa.wl > 16, wide_b = fb.wl > 16;
     // buffers of this call at the end of the workspace; the contractions of the parts see the rest
     const size_t keep = (size_t)1 << 20;
-    const int npairs = (wide_a ? (fa.wl <= 31 ? 2 : 3) : 1) * (wide_b ? (fb.wl <= 31 ? 2 : 3) : 1);
+    adapt_fmt pf[3];
+    int step;
+    const int npairs = wide_parts(fa, pf, &step) * wide_parts(fb, pf, &step);
     // one output buffer per pair and a single combining pass, when the workspace has room for that beside what a
     // part contraction of this size may itself need (taken as twice the minimal tail); else one buffer and a pass per pair
     const size_t tail_min = ws_need_wide(elems_a, wide_a, elems_b, wide_b, outputs, ep.raw != 0);
@@ -142,16 +171,16 @@ int wide_contraction(adapt_ctx *ctx, const void *a, adapt_fmt fa, uint64_t elems
             o.parts = 1; o.bits = 0; o.part[0] = p; o.fmt[0] = f;
             return;
         }
-        const bool two = f.wl <= 31;
-        o.parts = two ? 2 : 3;
-        o.bits = two ? 16 : kPartBits;
+        o.parts = wide_parts(f, o.fmt, &o.bits);
         int16_t *q[3] = {nullptr, nullptr, nullptr};
         for (int i = 0; i < o.parts; ++i) {
-            q[i] = reinterpret_cast<int16_t *>(take(elems * 2));
+            q[i] = reinterpret_cast<int16_t *>(take(elems * 2));      // (the byte part of the 8-bit split uses half of its room)
             o.part[i] = q[i];
-            o.fmt[i] = two ? adapt_fmt{16, 0} : adapt_fmt{12, 0};
         }
-        if (two)
+        if (o.bits == 8)
+            hipLaunchKernelGGL(split_byte_kernel, dim3(wide_grid(ctx, elems)), dim3(kWideThreads), 0, ctx->stream,
+                               static_cast<const int32_t *>(p), reinterpret_cast<int8_t *>(q[0]), q[1], elems);
+        else if (o.parts == 2)
             hipLaunchKernelGGL(split2_kernel, dim3(wide_grid(ctx, elems)), dim3(kWideThreads), 0, ctx->stream,
                                static_cast<const int32_t *>(p), q[0], q[1], elems);
         else

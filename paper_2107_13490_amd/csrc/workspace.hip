@@ -66,6 +66,26 @@ size_t conv_need(adapt_ctx *dry, int call, const adapt_conv_desc &d, adapt_fmt f
 
 }  // namespace
 
+// A contraction with an operand above 16 bits runs one narrow contraction per pair of parts (wide.hip): the largest
+// need among them, with the query's own call and shapes
+static size_t wide_inner_need(const adapt_ctx *ctx, const adapt_workspace_query &q)
+{
+    adapt_fmt pa[3], pb[3];
+    int step;
+    const int na = wide_parts(q.fa, pa, &step), nb = wide_parts(q.fb, pb, &step);
+    size_t inner = 0;
+    for (int i = 0; i < na; ++i)
+        for (int j = 0; j < nb; ++j) {
+            adapt_workspace_query sub = q;
+            sub.fa = pa[i];
+            sub.fb = pb[j];
+            const size_t need = adapt_workspace_bytes(ctx, &sub);
+            if (need == kInvalid) return kInvalid;
+            inner = std::max(inner, need);
+        }
+    return inner;
+}
+
 extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_workspace_query *q)
 {
     if (!q) return kInvalid;
@@ -96,10 +116,7 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
             if (q->fa.wl > 16 || q->fb.wl > 16) {
                 // word lengths above 16: the parts, one exact partial result and the 128-bit sums, after the largest
                 // contraction of two 12-bit parts (or of a part and the narrow operand)
-                adapt_workspace_query sub = *q;
-                if (sub.fa.wl > 16) sub.fa = sub.fa.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};      // the parts' formats (wide.hip)
-                if (sub.fb.wl > 16) sub.fb = sub.fb.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};
-                const size_t inner = adapt_workspace_bytes(ctx, &sub);
+                const size_t inner = wide_inner_need(ctx, *q);
                 if (inner == kInvalid) return kInvalid;
                 const int lda = q->lda ? q->lda : (q->transA ? q->M : q->K), ldb = q->ldb ? q->ldb : (q->transB ? q->K : q->N);
                 return std::max<size_t>(inner, (size_t)1 << 20) +
@@ -120,10 +137,7 @@ extern "C" size_t adapt_workspace_bytes(const adapt_ctx *ctx, const adapt_worksp
         case ADAPT_CALL_CONV_BACKWARD: {
             if (q->call != ADAPT_CALL_CONV_BACKWARD && fmt_ok_wide(q->fa) && fmt_ok_wide(q->fb) && (q->fa.wl > 16 || q->fb.wl > 16) &&
                 conv_ok(q->conv)) {
-                adapt_workspace_query sub = *q;
-                if (sub.fa.wl > 16) sub.fa = sub.fa.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};      // the parts' formats (wide.hip)
-                if (sub.fb.wl > 16) sub.fb = sub.fb.wl <= 31 ? adapt_fmt{16, 0} : adapt_fmt{12, 0};
-                const size_t inner = adapt_workspace_bytes(ctx, &sub);
+                const size_t inner = wide_inner_need(ctx, *q);
                 if (inner == kInvalid) return kInvalid;
                 const adapt_conv_desc &d = q->conv;
                 const uint64_t p = (d.h + 2 * d.pad - d.r) / d.stride + 1, qq = (d.w + 2 * d.pad - d.s) / d.stride + 1;
