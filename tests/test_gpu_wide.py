@@ -142,6 +142,21 @@ def test_workspace_query_covers_a_wide_call():
         assert np.array_equal(host(out).astype(np.int64), wo.requantize(wo.gemm(a, b), 20, 32, orc.SR, 1, 1))
     finally:
         cx.close()
+    # operands of 17..23 bits split into a byte and a part of up to 16 bits: the query covers every pair of parts
+    d2 = ConvDesc(16, 16, 16, 64, 64, 3, 3, 1, 1)
+    x, wt = _codes(g, (16, 16, 16, 64), 20), _codes(g, (64, 3, 3, 64), 23)
+    dy = _codes(g, (16, 16, 16, 64), 20)
+    calls = [(pkg.CALL_CONV_FWD, lambda c: c.conv_fwd(d2, dev(x), (20, 12), dev(wt), (23, 15), Epilogue.exact()), wo.conv_fwd(x, wt, 1, 1)),
+             (pkg.CALL_CONV_DGRAD, lambda c: c.conv_dgrad(d2, dev(dy), (20, 12), dev(wt), (23, 15), Epilogue.exact()), wo.conv_dgrad(dy, wt, 16, 16, 1, 1)),
+             (pkg.CALL_CONV_WGRAD, lambda c: c.conv_wgrad(d2, dev(dy), (20, 12), dev(x), (20, 12), Epilogue.exact()), wo.conv_wgrad(dy, x, 3, 3, 1, 1))]
+    for call, run, want in calls:
+        fb = (20, 12) if call == pkg.CALL_CONV_WGRAD else (23, 15)
+        need = ctx().workspace_bytes(call, conv=d2, fa=(20, 12), fb=fb)
+        cx = pkg.Context(workspace_bytes=need)
+        try:
+            assert np.array_equal(_i128(run(cx)), want), call
+        finally:
+            cx.close()
     d = ConvDesc(2, 8, 8, 16, 16, 3, 3, 1, 1)
     for call in (pkg.CALL_CONV_FWD, pkg.CALL_CONV_DGRAD, pkg.CALL_CONV_WGRAD):
         assert ctx().workspace_bytes(call, conv=d, fa=(20, 10), fb=(8, 4)) > ctx().workspace_bytes(call, conv=d, fa=(12, 10), fb=(8, 4))
