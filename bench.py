@@ -413,9 +413,10 @@ def elementwise_rows(ctx, pkg, torch):
 
 
 def wide_rows(ctx, pkg, torch):
-    """Word lengths 17..32 (int32 codes, contractions composed of 11-bit parts with 128-bit recombination): device time
-    of quantize on 16 M elements and of the forward / backward calls of configs[2]'s layer shape with <24,20> and
-    <32,28> operands.  TOPS are useful ops (2 M N K); these calls are exact, not fast."""
+    """Word lengths 17..32 (int32 codes, contractions composed of narrower parts with 128-bit recombination): device time
+    of quantize on 16 M elements and of the forward / backward calls of configs[2]'s layer shape with <20,16>, <24,20>
+    and <32,28> operands (the three ways an operand is split).  TOPS are useful ops (2 M N K); these calls are exact,
+    not fast."""
     from paper_2107_13490_amd import ConvDesc, Epilogue
 
     def timed(fn, reps=5):
@@ -437,7 +438,7 @@ def wide_rows(ctx, pkg, torch):
     rows["quantize_24bit_16M"] = {"ms": ms, "GBps": 8.0 * n / (ms * 1e-3) / 1e9, "frac_hbm": 8.0 * n / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
     d = ConvDesc(128, 16, 16, 64, 192, 3, 3, 1, 1)
     ops = 2.0 * d.n * d.p * d.q * d.k * d.r * d.s * d.c
-    for wl, fl in ((24, 20), (32, 28)):
+    for wl, fl in ((20, 16), (24, 20), (32, 28)):
         lim = 1 << (wl - 2)
         xq = torch.randint(-lim, lim, (d.n, d.h, d.w, d.c), dtype=torch.int32, device="cuda")
         wq = torch.randint(-lim, lim, (d.k, d.r, d.s, d.c), dtype=torch.int32, device="cuda")
