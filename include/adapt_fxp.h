@@ -540,8 +540,9 @@ typedef struct {
  * adds the output of layer `res` inside it: adapt_bn_forward), then ReLU, then 2x2 max-pooling (pool)
  * or global average pooling (gap: adapt_gap_fwd).  src, res < l; every layer but the last needs a
  * consumer, at most four.  Backward, a layer's output gradient is the sum of what its consumers hand
- * back: the first contribution is stored (refitted with adapt_grad_add when it comes from a layer of
- * another word length), later ones are added with adapt_grad_add; exponents stay in device memory
+ * back: the first contribution is stored (a convolution's data gradient as the fitting pass wrote
+ * it; a shortcut's gradient refitted with adapt_grad_add alone), later ones are added with
+ * adapt_grad_add; exponents stay in device memory
  * (ADAPT_NT_EXP).  Random streams of the additional steps: rng.stream + 2^20 + 8 l + slot with slot
  * 0 = batch-norm output, 1 = batch-norm data gradient, 2 = average pooling, 3 + k = the k-th contribution
  * to the gradient of layer l's output. */

@@ -276,12 +276,17 @@ def backward(nodes, fmts, wq, fwd, dlogits, dlogits_fl: int, seed: int, stream0:
     da[nl - 1] = np.asarray(dlogits).astype(np.int64).reshape(fwd["a"][nl - 1].shape)
     e_da[nl - 1] = dlogits_fl
 
-    def contribute(j: int, codes, e: int):
-        """Adds codes * 2^-e to the gradient of layer j's output (stored in layer j's word length)."""
+    def contribute(j: int, codes, e: int, fitted: bool = False):
+        """Adds codes * 2^-e to the gradient of layer j's output (stored in layer j's word length).  fitted: the codes
+        are a data gradient that the fitting rule has just stored in layer j's word length; as the first contribution
+        they are kept as they are (a second fitting pass would not be the identity when a code is -2^(wl-1), whose
+        magnitude has wl bits).  Codes of another tensor (a shortcut's gradient) pass through grad_add alone."""
         k = ncontrib[j]
         wl_j = fmts[j][0]
         st = stream_x(stream0, j, X_MERGE + k)
-        if k == 0:
+        if k == 0 and fitted:
+            da[j], e_da[j] = codes.reshape(fwd["a"][j].shape), e
+        elif k == 0:
             da[j], e_da[j], _ = grad_add(codes.reshape(fwd["a"][j].shape), e, None, None, wl_j, seed, st)
         else:
             da[j], e_da[j], _ = grad_add(da[j], e_da[j], codes.reshape(fwd["a"][j].shape), e, wl_j, seed, st)
@@ -313,7 +318,7 @@ def backward(nodes, fmts, wq, fwd, dlogits, dlogits_fl: int, seed: int, stream0:
         if s >= 0:
             acc_a = no._conv_dgrad(dyc[l], wl, wq[l], wl, L.h, L.w, L.stride, L.pad)
             q, sh_a, _ = no._requantize_fit(acc_a, fmts[s][0], orc.SR, seed, no.stream_of(stream0, l, no.SLOT_DA))
-            contribute(s, q, e + fl - sh_a)
+            contribute(s, q, e + fl - sh_a, fitted=True)
     return {"g": g, "sumsq": sumsq, "e_g": e_g, "dgamma": dgam, "dbeta": dbet, "da": da, "e_da": e_da, "dyc": dyc}
 
 

@@ -776,6 +776,12 @@ def test_small_residual_network_all_tensors(fmts):
     _run_graph(_small_resnet(), fmts, n=6, steps=2, seed=41)
 
 
+def test_residual_network_whose_fitted_gradient_holds_the_most_negative_code():
+    # in the second step the data gradient handed to layer 3 (7 bits) contains -64: stored as the fitting pass wrote it
+    fmts = [(9, 5), (5, 2), (14, 9), (7, 4), (5, 0), (10, 7), (13, 9)]
+    _run_graph(_small_resnet(), fmts, n=4, steps=2, seed=1711)
+
+
 def test_residual_network_training_with_precision_switching():
     kw = dict(lb_lwr=1, lb_upr=3, lb_init=2, r_lwr=50, r_upr=80, r_init=60, gamma=0.4, eps=1e-2, buff=3, wl_lo=4, wl_hi=16)
     switches, fmts = _run_graph(_small_resnet(), [(12, 8)] * 6 + [(12, 7)], n=6, steps=6, seed=42, switch_kw=kw)

@@ -230,6 +230,32 @@ def test_plain_chain_through_the_graph_oracle_is_the_chain_oracle():
     assert b2["e_g"] == no.gradient_exponents(fmts, b1, 5)
 
 
+def test_a_fitted_gradient_that_holds_the_most_negative_code_is_stored_as_it_is():
+    """The data gradient of a layer's only consumer is fitted straight into the layer's word length and stored; a
+    second fitting pass over it would shift by one bit when a code equals -2^(wl-1) (its magnitude has wl bits).  On a
+    plain chain the graph oracle must therefore agree with the chain oracle also in that case."""
+    layers = [no.Layer(4, 4, 4, 8, relu=True, pool=False), no.Layer(4, 4, 8, 8, relu=True, pool=False),
+              no.Layer(1, 1, 128, 10, 1, 1, 1, 0, relu=False, pool=False)]
+    nodes = [go.Node(L.h, L.w, L.c, L.k, L.r, L.s, L.stride, L.pad, L.relu, L.pool) for L in layers]
+    fmts = [(4, 1), (4, 2), (6, 3)]
+    found = 0
+    for seed in range(150):
+        rng = np.random.default_rng(seed)
+        x = rng.standard_normal((3, 4, 4, 4)).astype(np.float32)
+        ws = [(rng.standard_normal((L.k, L.r, L.s, L.c)) * 0.4).astype(np.float32) for L in layers]
+        wq = no.quantize_weights(layers, fmts, ws, seed, 0)
+        f1, f2 = no.forward(layers, fmts, wq, x, seed, 0), go.forward(nodes, fmts, wq, [None] * 3, x, 1e-5, seed, 0)
+        dl = rng.integers(-32, 32, (3, 1, 1, 10))
+        b1, b2 = no.backward(layers, fmts, wq, f1, dl, seed, 0), go.backward(nodes, fmts, wq, f2, dl, 5, seed, 0)
+        lowest = [int(b1["da"][l].min()) == -(1 << (fmts[l][0] - 1)) for l in range(2)]
+        if any(lowest):
+            found += 1
+            assert all(np.array_equal(a, b) for a, b in zip(b1["g"], b2["g"])), seed
+            assert all(np.array_equal(b1["da"][l].ravel(), b2["da"][l].ravel()) for l in range(2)), seed
+            assert b2["e_g"] == no.gradient_exponents(fmts, b1, 5), seed
+    assert found >= 3                                  # (the case needs the largest magnitude to be negative and in the top eighth of its binade)
+
+
 # ---- word lengths above 16 bits -------------------------------------------------------------------------------
 
 def _wide_bn_case(seed, shape=(3, 4, 4, 8), wl=28):
