@@ -135,3 +135,26 @@ def test_random_searches_and_quantizations(chunk):
         q, cnt = ctx().quantize(dev(w), wl, fl, mode, seed=case, stream=5)
         rq, rn, rs = orc.quantize(w, wl, fl, mode, case, 5)
         assert np.array_equal(_i64(q), rq.astype(np.int64)) and host(cnt).tolist() == [int(rn), int(rs)], (chunk, case, wl, fl)
+
+
+@pytest.mark.parametrize("chunk", range(3))
+def test_random_chains_and_residual_graphs(chunk):
+    """Whole training steps (every tensor against the oracle) on drawn word lengths: feed-forward chains of drawn
+    shapes, the small residual network with and without the precision switch, and formats above 16 bits."""
+    import test_gpu_net as tn
+    g = np.random.default_rng(6_000_000 + chunk)
+    for case in range(6):
+        rng = np.random.default_rng(6_100_000 + 100 * chunk + case)
+        layers, fmts = tn._random_net(rng)
+        tn._run_chain(layers, fmts, n=int(rng.choice([2, 3, 5, 9])), seed=3000 + 100 * chunk + case)
+    for case in range(6):
+        fm = [(wl, wl - int(g.integers(3, 6))) for wl in (int(v) for v in g.integers(5, 17, 7))]
+        tn._run_graph(tn._small_resnet(), fm, n=int(g.choice([2, 4, 6])), steps=2, seed=3200 + 100 * chunk + case)
+    for case in range(3):
+        fm = [(wl, wl - int(g.integers(3, 6))) for wl in (int(v) for v in g.integers(6, 17, 7))]
+        kw = dict(lb_lwr=1, lb_upr=int(g.integers(2, 5)), lb_init=2, r_lwr=50, r_upr=80, r_init=60, gamma=float(g.choice([0.3, 0.5])),
+                  eps=float(g.choice([1e-2, 1e-3])), buff=int(g.integers(1, 5)), wl_lo=4, wl_hi=16)
+        tn._run_graph(tn._small_resnet(), fm, n=int(g.choice([2, 4])), steps=5, seed=3400 + 100 * chunk + case, switch_kw=kw)
+    for case in range(3):
+        fm = [(wl, wl - int(g.integers(4, 8))) for wl in (int(v) for v in g.choice([8, 12, 16, 17, 20, 23, 24, 28, 32], 7))]
+        tn._run_graph(tn._tiny_resnet(), fm, n=2, steps=2, seed=3600 + 100 * chunk + case, wl_max=32)
