@@ -226,3 +226,27 @@ def test_invalid_arguments():
                  (4, 8, 0, 100)):
         with pytest.raises(pkg.AdaptError):
             ctx().kld_precision_search(w, args[0], args[1], args[2], args[3], 1e-3)
+
+
+def test_workspace_query_covers_batched_searches():
+    """A context of exactly the queried size runs the batch (more tensors than one batch holds, tables too wide for LDS)."""
+    g = np.random.default_rng(5)
+    for case in range(4):
+        count = int(g.choice([5, 24, 25, 40]))
+        sizes = [int(g.choice([0, 7, 300, 4097, 36864, 150000, 600000])) for _ in range(count)]
+        bins = [int(g.choice([16, 150, 2048, 4096, 50000, 65536])) for _ in range(count)]
+        lo = int(g.integers(2, 17))
+        hi = int(g.integers(lo, 17))
+        ws = [(g.standard_normal(n) * 0.1).astype(np.float32) for n in sizes]
+        need = ctx().workspace_bytes(pkg.CALL_KLD_SEARCH_BATCHED, kld_items=list(zip(sizes, bins)), wl_lo=lo, wl_hi=hi)
+        cx = pkg.Context(workspace_bytes=need)
+        try:
+            devs = [dev(w) if w.size else torch.empty(0, device="cuda") for w in ws]
+            ils, streams = [min(2, lo)] * count, list(range(count))
+            kld, sel = cx.kld_precision_search_batched(devs, ils, bins, streams, lo, hi, 1e-3, seed=case)
+            sel = host(sel)
+            for t, w in enumerate(ws):
+                ref = orc.kld_precision_search(w, lo, hi, ils[t], bins[t], 1e-3, None, pkg.SR, case, streams[t])
+                assert sel[t].tolist() == [ref["wl_sel"], ref["fl_sel"]], (case, t)
+        finally:
+            cx.close()
